@@ -1,0 +1,550 @@
+/*
+ * lasp_oracle.c -- fp64 CPU oracle for causal linear attention with decay
+ * (LASP, arxiv 2404.02882).
+ *
+ * THIS IS TEST INFRASTRUCTURE. It is plain, slow and meant to be checked
+ * against the paper by eye. Only the tests, the smoke check and the
+ * cpu_baseline leg of the benchmark may call it; the GPU library shares no
+ * code with it and never routes through it.
+ *
+ * Conventions (all host pointers, all double):
+ *   q,k,v,out,dout,dq,dk,dv : [B][H][N][D] row-major, one token row = D values
+ *   kv_in,kv_out,dkv_out,dkv_in : [B][H][D][D], state[a][c] = sum k[a]*v[c]
+ *   decay : [H], lambda_h, shared over the batch, 0 < lambda <= 1
+ *   tokens are 1-based (s = 1..N) in the formulas, as in the paper.
+ *
+ * Three independent forms of the same result:
+ *   *_brute     : the definition (Sec. 3.2, per-token causal form with decay;
+ *                 equivalently O = (Q K^T (.) M) V with M_ij = lambda^(i-j),
+ *                 i >= j), extended by the carried state: a non-zero kv_in
+ *                 stands for the tokens before this block (inter-chunk term of
+ *                 Alg. 2), a non-zero dkv_out for the tokens after it (Alg. 3).
+ *                 This form is the authority.
+ *   *_recurrent : the token recurrence kv_s = lambda kv_{s-1} + k_s v_s^T and
+ *                 the reverse recurrence for dkv (Sec. 3.2, recurrence forms).
+ *   *_chunked   : Alg. 2 / Alg. 3 taken step by step in the paper's order and
+ *                 notation (mask M, diagonal Lambda, intra + inter, state
+ *                 update) for an arbitrary chunk length C | N.
+ * Every power of lambda is a direct pow() call: nothing is factored as
+ * lambda^i * lambda^-j and Lambda^-1 is never formed.
+ *
+ * Pins (tests/test_oracle_pins.py): textbook tril(QK^T)V at lambda = 1,
+ * geometric-series and impulse closed forms, a hand-computed N=3 example,
+ * exact finite differences (the loss is multilinear), backward == three
+ * forwards, superposition in kv_in, and agreement of the three forms and of
+ * T-way splitting with state passing.
+ */
+#include <math.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+typedef long long i64;
+
+static const double *rowp(const double *x, int H, i64 N, int D, int b, int h, i64 s0)
+{
+    return x + ((((i64)b * H + h) * N) + s0) * D;
+}
+static double *rowpw(double *x, int H, i64 N, int D, int b, int h, i64 s0)
+{
+    return x + ((((i64)b * H + h) * N) + s0) * D;
+}
+static const double *statep(const double *x, int H, int D, int b, int h)
+{
+    return x ? x + ((i64)b * H + h) * D * D : NULL;
+}
+
+static double dot(const double *a, const double *b, int D)
+{
+    double acc = 0.0;
+    for (int c = 0; c < D; ++c) acc += a[c] * b[c];
+    return acc;
+}
+
+/* ------------------------------------------------------------------ */
+/* Brute force: the definition, one output row at a time.              */
+/* ------------------------------------------------------------------ */
+
+/* o_s = sum_{i<=s} lambda^(s-i) (q_s . k_i) v_i  +  lambda^s K0^T q_s
+ * (Sec. 3.2 per-token causal form; second term: inter-chunk output of Alg. 2
+ * with all earlier tokens folded into K0).  s is 1-based. */
+static void fwd_row(const double *q, const double *k, const double *v, const double *K0,
+                    double lam, i64 s, int D, double *o)
+{
+    const double *qs = q + (s - 1) * D;
+    for (int c = 0; c < D; ++c) o[c] = 0.0;
+    for (i64 i = 1; i <= s; ++i) {
+        double w = pow(lam, (double)(s - i)) * dot(qs, k + (i - 1) * D, D);
+        const double *vi = v + (i - 1) * D;
+        for (int c = 0; c < D; ++c) o[c] += w * vi[c];
+    }
+    if (K0) {
+        double ls = pow(lam, (double)s);
+        for (int a = 0; a < D; ++a) {
+            double w = ls * qs[a];
+            for (int c = 0; c < D; ++c) o[c] += w * K0[a * D + c];
+        }
+    }
+}
+
+/* dq_s = kv_s do_s with kv_s = lambda^s K0 + sum_{i<=s} lambda^(s-i) k_i v_i^T
+ * dk_s = dkv_s v_s, dv_s = dkv_s^T k_s with
+ * dkv_s = sum_{i>=s} lambda^(i-s) q_i do_i^T + lambda^(N-s) G
+ * (Sec. 3.2 backward equations, extended by the two boundary states). */
+static void bwd_row(const double *q, const double *k, const double *v, const double *dO,
+                    const double *K0, const double *G, double lam, i64 s, i64 N, int D,
+                    double *dq, double *dk, double *dv)
+{
+    const double *dos = dO + (s - 1) * D;
+    const double *ks = k + (s - 1) * D;
+    const double *vs = v + (s - 1) * D;
+    if (dq) {
+        for (int a = 0; a < D; ++a) dq[a] = 0.0;
+        for (i64 i = 1; i <= s; ++i) {
+            double w = pow(lam, (double)(s - i)) * dot(v + (i - 1) * D, dos, D);
+            const double *ki = k + (i - 1) * D;
+            for (int a = 0; a < D; ++a) dq[a] += w * ki[a];
+        }
+        if (K0) {
+            double ls = pow(lam, (double)s);
+            for (int a = 0; a < D; ++a) dq[a] += ls * dot(K0 + a * D, dos, D);
+        }
+    }
+    if (dk) {
+        for (int a = 0; a < D; ++a) dk[a] = 0.0;
+        for (i64 i = s; i <= N; ++i) {
+            double w = pow(lam, (double)(i - s)) * dot(dO + (i - 1) * D, vs, D);
+            const double *qi = q + (i - 1) * D;
+            for (int a = 0; a < D; ++a) dk[a] += w * qi[a];
+        }
+        if (G) {
+            double ls = pow(lam, (double)(N - s));
+            for (int a = 0; a < D; ++a) dk[a] += ls * dot(G + a * D, vs, D);
+        }
+    }
+    if (dv) {
+        for (int c = 0; c < D; ++c) dv[c] = 0.0;
+        for (i64 i = s; i <= N; ++i) {
+            double w = pow(lam, (double)(i - s)) * dot(q + (i - 1) * D, ks, D);
+            const double *doi = dO + (i - 1) * D;
+            for (int c = 0; c < D; ++c) dv[c] += w * doi[c];
+        }
+        if (G) {
+            double ls = pow(lam, (double)(N - s));
+            for (int a = 0; a < D; ++a) {
+                double w = ls * ks[a];
+                for (int c = 0; c < D; ++c) dv[c] += w * G[a * D + c];
+            }
+        }
+    }
+}
+
+/* kv_out = lambda^N K0 + sum_i lambda^(N-i) k_i v_i^T   (state update equation
+ * of Sec. 3.2 taken over the whole block). */
+static void kv_out_brute(const double *k, const double *v, const double *K0, double lam,
+                         i64 N, int D, double *kv_out)
+{
+    double lN = pow(lam, (double)N);
+    for (int e = 0; e < D * D; ++e) kv_out[e] = K0 ? lN * K0[e] : 0.0;
+    for (i64 i = 1; i <= N; ++i) {
+        double w = pow(lam, (double)(N - i));
+        const double *ki = k + (i - 1) * D, *vi = v + (i - 1) * D;
+        for (int a = 0; a < D; ++a)
+            for (int c = 0; c < D; ++c) kv_out[a * D + c] += w * ki[a] * vi[c];
+    }
+}
+
+/* dkv_in = lambda^N G + sum_s lambda^s q_s do_s^T  (dKV update of Alg. 3 taken
+ * over the whole block; note the exponent s, not s-1: Lambda is 1-based). */
+static void dkv_in_brute(const double *q, const double *dO, const double *G, double lam,
+                         i64 N, int D, double *dkv_in)
+{
+    double lN = pow(lam, (double)N);
+    for (int e = 0; e < D * D; ++e) dkv_in[e] = G ? lN * G[e] : 0.0;
+    for (i64 s = 1; s <= N; ++s) {
+        double w = pow(lam, (double)s);
+        const double *qs = q + (s - 1) * D, *ds = dO + (s - 1) * D;
+        for (int a = 0; a < D; ++a)
+            for (int c = 0; c < D; ++c) dkv_in[a * D + c] += w * qs[a] * ds[c];
+    }
+}
+
+int lasp_oracle_fwd_brute(int B, int H, i64 N, int D, const double *q, const double *k,
+                          const double *v, const double *kv_in, const double *decay,
+                          double *out, double *kv_out)
+{
+    if (!q || !k || !v || !decay || !out || !kv_out || B <= 0 || H <= 0 || N <= 0 || D <= 0) return 1;
+    i64 total = (i64)B * H * N;
+#pragma omp parallel for schedule(dynamic, 8)
+    for (i64 r = 0; r < total; ++r) {
+        int bh = (int)(r / N), b = bh / H, h = bh % H;
+        i64 s = r % N + 1;
+        fwd_row(rowp(q, H, N, D, b, h, 0), rowp(k, H, N, D, b, h, 0), rowp(v, H, N, D, b, h, 0),
+                statep(kv_in, H, D, b, h), decay[h], s, D, rowpw(out, H, N, D, b, h, s - 1));
+    }
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int bh = 0; bh < B * H; ++bh) {
+        int b = bh / H, h = bh % H;
+        kv_out_brute(rowp(k, H, N, D, b, h, 0), rowp(v, H, N, D, b, h, 0), statep(kv_in, H, D, b, h),
+                     decay[h], N, D, kv_out + (i64)bh * D * D);
+    }
+    return 0;
+}
+
+/* rows: nrows triples (b, h, s0) with s0 0-based; out_rows: [nrows][D]. */
+int lasp_oracle_fwd_brute_rows(int B, int H, i64 N, int D, const double *q, const double *k,
+                               const double *v, const double *kv_in, const double *decay,
+                               i64 nrows, const i64 *rows, double *out_rows)
+{
+    if (!q || !k || !v || !decay || !rows || !out_rows) return 1;
+    for (i64 r = 0; r < nrows; ++r)
+        if (rows[3 * r] < 0 || rows[3 * r] >= B || rows[3 * r + 1] < 0 || rows[3 * r + 1] >= H ||
+            rows[3 * r + 2] < 0 || rows[3 * r + 2] >= N)
+            return 2;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (i64 r = 0; r < nrows; ++r) {
+        int b = (int)rows[3 * r], h = (int)rows[3 * r + 1];
+        i64 s = rows[3 * r + 2] + 1;
+        fwd_row(rowp(q, H, N, D, b, h, 0), rowp(k, H, N, D, b, h, 0), rowp(v, H, N, D, b, h, 0),
+                statep(kv_in, H, D, b, h), decay[h], s, D, out_rows + r * D);
+    }
+    return 0;
+}
+
+int lasp_oracle_bwd_brute(int B, int H, i64 N, int D, const double *q, const double *k,
+                          const double *v, const double *dout, const double *kv_in,
+                          const double *dkv_out, const double *decay, double *dq, double *dk,
+                          double *dv, double *dkv_in)
+{
+    if (!q || !k || !v || !dout || !decay || !dq || !dk || !dv || !dkv_in) return 1;
+    i64 total = (i64)B * H * N;
+#pragma omp parallel for schedule(dynamic, 8)
+    for (i64 r = 0; r < total; ++r) {
+        int bh = (int)(r / N), b = bh / H, h = bh % H;
+        i64 s = r % N + 1;
+        bwd_row(rowp(q, H, N, D, b, h, 0), rowp(k, H, N, D, b, h, 0), rowp(v, H, N, D, b, h, 0),
+                rowp(dout, H, N, D, b, h, 0), statep(kv_in, H, D, b, h), statep(dkv_out, H, D, b, h),
+                decay[h], s, N, D, rowpw(dq, H, N, D, b, h, s - 1), rowpw(dk, H, N, D, b, h, s - 1),
+                rowpw(dv, H, N, D, b, h, s - 1));
+    }
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int bh = 0; bh < B * H; ++bh) {
+        int b = bh / H, h = bh % H;
+        dkv_in_brute(rowp(q, H, N, D, b, h, 0), rowp(dout, H, N, D, b, h, 0),
+                     statep(dkv_out, H, D, b, h), decay[h], N, D, dkv_in + (i64)bh * D * D);
+    }
+    return 0;
+}
+
+int lasp_oracle_bwd_brute_rows(int B, int H, i64 N, int D, const double *q, const double *k,
+                               const double *v, const double *dout, const double *kv_in,
+                               const double *dkv_out, const double *decay, i64 nrows,
+                               const i64 *rows, double *dq_rows, double *dk_rows, double *dv_rows)
+{
+    if (!q || !k || !v || !dout || !decay || !rows || !dq_rows || !dk_rows || !dv_rows) return 1;
+    for (i64 r = 0; r < nrows; ++r)
+        if (rows[3 * r] < 0 || rows[3 * r] >= B || rows[3 * r + 1] < 0 || rows[3 * r + 1] >= H ||
+            rows[3 * r + 2] < 0 || rows[3 * r + 2] >= N)
+            return 2;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (i64 r = 0; r < nrows; ++r) {
+        int b = (int)rows[3 * r], h = (int)rows[3 * r + 1];
+        i64 s = rows[3 * r + 2] + 1;
+        bwd_row(rowp(q, H, N, D, b, h, 0), rowp(k, H, N, D, b, h, 0), rowp(v, H, N, D, b, h, 0),
+                rowp(dout, H, N, D, b, h, 0), statep(kv_in, H, D, b, h), statep(dkv_out, H, D, b, h),
+                decay[h], s, N, D, dq_rows + r * D, dk_rows + r * D, dv_rows + r * D);
+    }
+    return 0;
+}
+
+/* ------------------------------------------------------------------ */
+/* Token recurrence (Sec. 3.2 recurrence forms).                        */
+/* ------------------------------------------------------------------ */
+
+int lasp_oracle_fwd_recurrent(int B, int H, i64 N, int D, const double *q, const double *k,
+                              const double *v, const double *kv_in, const double *decay,
+                              double *out, double *kv_out)
+{
+    if (!q || !k || !v || !decay || !out || !kv_out) return 1;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int bh = 0; bh < B * H; ++bh) {
+        int b = bh / H, h = bh % H;
+        double lam = decay[h];
+        double *kv = kv_out + (i64)bh * D * D; /* running state, ends as kv_N */
+        const double *K0 = statep(kv_in, H, D, b, h);
+        for (int e = 0; e < D * D; ++e) kv[e] = K0 ? K0[e] : 0.0; /* kv_0 */
+        for (i64 s = 1; s <= N; ++s) {
+            const double *qs = rowp(q, H, N, D, b, h, s - 1), *ks = rowp(k, H, N, D, b, h, s - 1),
+                         *vs = rowp(v, H, N, D, b, h, s - 1);
+            double *os = rowpw(out, H, N, D, b, h, s - 1);
+            /* kv_s = lambda kv_{s-1} + k_s v_s^T */
+            for (int a = 0; a < D; ++a)
+                for (int c = 0; c < D; ++c) kv[a * D + c] = lam * kv[a * D + c] + ks[a] * vs[c];
+            /* o_s^T = q_s^T kv_s */
+            for (int c = 0; c < D; ++c) os[c] = 0.0;
+            for (int a = 0; a < D; ++a)
+                for (int c = 0; c < D; ++c) os[c] += qs[a] * kv[a * D + c];
+        }
+    }
+    return 0;
+}
+
+int lasp_oracle_bwd_recurrent(int B, int H, i64 N, int D, const double *q, const double *k,
+                              const double *v, const double *dout, const double *kv_in,
+                              const double *dkv_out, const double *decay, double *dq, double *dk,
+                              double *dv, double *dkv_in)
+{
+    if (!q || !k || !v || !dout || !decay || !dq || !dk || !dv || !dkv_in) return 1;
+    int fail = 0;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int bh = 0; bh < B * H; ++bh) {
+        int b = bh / H, h = bh % H;
+        double lam = decay[h];
+        double *kv = (double *)malloc(sizeof(double) * D * D);
+        double *dkv = (double *)malloc(sizeof(double) * D * D);
+        if (!kv || !dkv) {
+            fail = 1;
+            free(kv);
+            free(dkv);
+            continue;
+        }
+        const double *K0 = statep(kv_in, H, D, b, h), *G = statep(dkv_out, H, D, b, h);
+        /* forward sweep: dq_s = kv_s do_s */
+        for (int e = 0; e < D * D; ++e) kv[e] = K0 ? K0[e] : 0.0;
+        for (i64 s = 1; s <= N; ++s) {
+            const double *ks = rowp(k, H, N, D, b, h, s - 1), *vs = rowp(v, H, N, D, b, h, s - 1),
+                         *ds = rowp(dout, H, N, D, b, h, s - 1);
+            double *dqs = rowpw(dq, H, N, D, b, h, s - 1);
+            for (int a = 0; a < D; ++a)
+                for (int c = 0; c < D; ++c) kv[a * D + c] = lam * kv[a * D + c] + ks[a] * vs[c];
+            for (int a = 0; a < D; ++a) dqs[a] = dot(kv + a * D, ds, D);
+        }
+        /* reverse sweep: dkv_{N+1} = G/lambda formally; written so that no
+         * division is needed: D_s = q_s do_s^T + lambda D_{s+1}, with the
+         * gradient arriving at kv_N being G. */
+        for (int e = 0; e < D * D; ++e) dkv[e] = 0.0;
+        for (i64 s = N; s >= 1; --s) {
+            const double *qs = rowp(q, H, N, D, b, h, s - 1), *ks = rowp(k, H, N, D, b, h, s - 1),
+                         *vs = rowp(v, H, N, D, b, h, s - 1), *ds = rowp(dout, H, N, D, b, h, s - 1);
+            double *dks = rowpw(dk, H, N, D, b, h, s - 1), *dvs = rowpw(dv, H, N, D, b, h, s - 1);
+            for (int a = 0; a < D; ++a)
+                for (int c = 0; c < D; ++c) {
+                    double carried = (s == N) ? (G ? G[a * D + c] : 0.0) : lam * dkv[a * D + c];
+                    dkv[a * D + c] = carried + qs[a] * ds[c];
+                }
+            for (int a = 0; a < D; ++a) dks[a] = dot(dkv + a * D, vs, D);
+            for (int c = 0; c < D; ++c) dvs[c] = 0.0;
+            for (int a = 0; a < D; ++a)
+                for (int c = 0; c < D; ++c) dvs[c] += dkv[a * D + c] * ks[a];
+        }
+        /* gradient w.r.t. kv_0: kv_1 = lambda kv_0 + ... */
+        double *gin = dkv_in + (i64)bh * D * D;
+        for (int e = 0; e < D * D; ++e) gin[e] = lam * dkv[e];
+        free(kv);
+        free(dkv);
+    }
+    return fail;
+}
+
+/* ------------------------------------------------------------------ */
+/* Chunked form: Alg. 2 and Alg. 3 step by step, chunk length C | N.    */
+/* ------------------------------------------------------------------ */
+
+/* C = A(m x n, row stride n) times B(n x p), plain triple loop. */
+static void matmul(const double *A, const double *Bm, double *Cm, int m, int n, int p)
+{
+    for (int i = 0; i < m; ++i) {
+        for (int j = 0; j < p; ++j) Cm[i * p + j] = 0.0;
+        for (int l = 0; l < n; ++l) {
+            double a = A[i * n + l];
+            for (int j = 0; j < p; ++j) Cm[i * p + j] += a * Bm[l * p + j];
+        }
+    }
+}
+/* C = A^T B with A (n x m), B (n x p). */
+static void matmul_tn(const double *A, const double *Bm, double *Cm, int n, int m, int p)
+{
+    for (int e = 0; e < m * p; ++e) Cm[e] = 0.0;
+    for (int l = 0; l < n; ++l)
+        for (int i = 0; i < m; ++i) {
+            double a = A[l * m + i];
+            for (int j = 0; j < p; ++j) Cm[i * p + j] += a * Bm[l * p + j];
+        }
+}
+/* C = A B^T with A (m x n), B (p x n). */
+static void matmul_nt(const double *A, const double *Bm, double *Cm, int m, int n, int p)
+{
+    for (int i = 0; i < m; ++i)
+        for (int j = 0; j < p; ++j) Cm[i * p + j] = dot(A + i * n, Bm + j * n, n);
+}
+
+typedef struct {
+    double *M;      /* C x C, M_ij = lambda^(i-j) for i >= j else 0 (Alg. 2 init) */
+    double *Lam;    /* Lambda diagonal: lambda^1 .. lambda^C (1-based) */
+    double *LamInv; /* diagonal of lambda^C Lambda^-1 = lambda^(C-1) .. lambda^0 */
+    double lamC;
+} chunk_consts;
+
+static int make_consts(chunk_consts *cc, double lam, int C)
+{
+    cc->M = (double *)malloc(sizeof(double) * C * C);
+    cc->Lam = (double *)malloc(sizeof(double) * C);
+    cc->LamInv = (double *)malloc(sizeof(double) * C);
+    if (!cc->M || !cc->Lam || !cc->LamInv) return 1;
+    for (int i = 0; i < C; ++i)
+        for (int j = 0; j < C; ++j) cc->M[i * C + j] = (i >= j) ? pow(lam, (double)(i - j)) : 0.0;
+    for (int r = 1; r <= C; ++r) {
+        cc->Lam[r - 1] = pow(lam, (double)r);
+        cc->LamInv[r - 1] = pow(lam, (double)(C - r));
+    }
+    cc->lamC = pow(lam, (double)C);
+    return 0;
+}
+static void free_consts(chunk_consts *cc)
+{
+    free(cc->M);
+    free(cc->Lam);
+    free(cc->LamInv);
+}
+
+/* One chunk of Alg. 2: O_t = [(Q K^T) (.) M] V + Lambda Q KV_{t-1};
+ * KV_t = lambda^C KV_{t-1} + (lambda^C Lambda^-1 K)^T V.  KV is updated in place. */
+static void fwd_chunk(const chunk_consts *cc, const double *Q, const double *K, const double *V,
+                      double *KV, double *O, int C, int D, double *S, double *tmp, double *Kd)
+{
+    matmul_nt(Q, K, S, C, D, C);
+    for (int e = 0; e < C * C; ++e) S[e] *= cc->M[e];
+    matmul(S, V, O, C, C, D);   /* O_intra */
+    matmul(Q, KV, tmp, C, D, D); /* Q KV_{t-1} */
+    for (int r = 0; r < C; ++r)
+        for (int c = 0; c < D; ++c) O[r * D + c] += cc->Lam[r] * tmp[r * D + c];
+    for (int r = 0; r < C; ++r)
+        for (int a = 0; a < D; ++a) Kd[r * D + a] = cc->LamInv[r] * K[r * D + a];
+    matmul_tn(Kd, V, tmp, C, D, D); /* (lambda^C Lambda^-1 K)^T V, D x D (tmp holds >= D*D) */
+    for (int e = 0; e < D * D; ++e) KV[e] = cc->lamC * KV[e] + tmp[e];
+}
+
+int lasp_oracle_fwd_chunked(int B, int H, i64 N, int D, int C, const double *q, const double *k,
+                            const double *v, const double *kv_in, const double *decay,
+                            double *out, double *kv_out)
+{
+    if (!q || !k || !v || !decay || !out || !kv_out || C <= 0 || N % C != 0) return 1;
+    int fail = 0;
+    int big = (C > D ? C : D);
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int bh = 0; bh < B * H; ++bh) {
+        int b = bh / H, h = bh % H;
+        chunk_consts cc;
+        double *S = (double *)malloc(sizeof(double) * C * C);
+        double *tmp = (double *)malloc(sizeof(double) * big * D);
+        double *Kd = (double *)malloc(sizeof(double) * C * D);
+        if (make_consts(&cc, decay[h], C) || !S || !tmp || !Kd) {
+            fail = 1;
+        } else {
+            double *KV = kv_out + (i64)bh * D * D;
+            const double *K0 = statep(kv_in, H, D, b, h);
+            for (int e = 0; e < D * D; ++e) KV[e] = K0 ? K0[e] : 0.0;
+            for (i64 t = 0; t < N / C; ++t)
+                fwd_chunk(&cc, rowp(q, H, N, D, b, h, t * C), rowp(k, H, N, D, b, h, t * C),
+                          rowp(v, H, N, D, b, h, t * C), KV, rowpw(out, H, N, D, b, h, t * C), C, D,
+                          S, tmp, Kd);
+        }
+        free_consts(&cc);
+        free(S);
+        free(tmp);
+        free(Kd);
+    }
+    return fail;
+}
+
+int lasp_oracle_bwd_chunked(int B, int H, i64 N, int D, int C, const double *q, const double *k,
+                            const double *v, const double *dout, const double *kv_in,
+                            const double *dkv_out, const double *decay, double *dq, double *dk,
+                            double *dv, double *dkv_in)
+{
+    if (!q || !k || !v || !dout || !decay || !dq || !dk || !dv || !dkv_in || C <= 0 || N % C != 0)
+        return 1;
+    int fail = 0;
+    i64 T = N / C;
+    int big = (C > D ? C : D);
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int bh = 0; bh < B * H; ++bh) {
+        int b = bh / H, h = bh % H;
+        chunk_consts cc;
+        double *S = (double *)malloc(sizeof(double) * C * C);
+        double *dS = (double *)malloc(sizeof(double) * C * C);
+        double *tmp = (double *)malloc(sizeof(double) * big * D);
+        double *sc = (double *)malloc(sizeof(double) * C * D);
+        double *Otmp = (double *)malloc(sizeof(double) * C * D);
+        double *cache = (double *)malloc(sizeof(double) * (T + 1) * D * D); /* KV_0 .. KV_T */
+        if (make_consts(&cc, decay[h], C) || !S || !dS || !tmp || !sc || !Otmp || !cache) {
+            fail = 1;
+        } else {
+            const double *K0 = statep(kv_in, H, D, b, h), *G = statep(dkv_out, H, D, b, h);
+            /* forward sweep only to rebuild the cached states KV_{t-1} (Alg. 2, "save KV_{t-1}") */
+            for (int e = 0; e < D * D; ++e) cache[e] = K0 ? K0[e] : 0.0;
+            for (i64 t = 0; t < T; ++t) {
+                memcpy(cache + (t + 1) * D * D, cache + t * D * D, sizeof(double) * D * D);
+                fwd_chunk(&cc, rowp(q, H, N, D, b, h, t * C), rowp(k, H, N, D, b, h, t * C),
+                          rowp(v, H, N, D, b, h, t * C), cache + (t + 1) * D * D, Otmp, C, D, S, tmp, sc);
+            }
+            /* dKV: what chunk t receives from the right (gradient w.r.t. KV_t). */
+            double *dKV = dkv_in + (i64)bh * D * D;
+            for (int e = 0; e < D * D; ++e) dKV[e] = G ? G[e] : 0.0;
+            for (i64 t = T - 1; t >= 0; --t) {
+                const double *Q = rowp(q, H, N, D, b, h, t * C), *K = rowp(k, H, N, D, b, h, t * C),
+                             *V = rowp(v, H, N, D, b, h, t * C), *dO = rowp(dout, H, N, D, b, h, t * C);
+                double *dQ = rowpw(dq, H, N, D, b, h, t * C), *dK = rowpw(dk, H, N, D, b, h, t * C),
+                       *dV = rowpw(dv, H, N, D, b, h, t * C);
+                const double *KVprev = cache + t * D * D;
+                /* dQ_intra = [(dO V^T) (.) M] K ; dK_intra = [(dO V^T) (.) M]^T Q */
+                matmul_nt(dO, V, dS, C, D, C);
+                for (int e = 0; e < C * C; ++e) dS[e] *= cc.M[e];
+                matmul(dS, K, dQ, C, C, D);
+                matmul_tn(dS, Q, dK, C, C, D);
+                /* dV_intra = [(Q K^T) (.) M]^T dO */
+                matmul_nt(Q, K, S, C, D, C);
+                for (int e = 0; e < C * C; ++e) S[e] *= cc.M[e];
+                matmul_tn(S, dO, dV, C, C, D);
+                /* dQ_inter = Lambda dO KV_{t-1}^T */
+                matmul_nt(dO, KVprev, tmp, C, D, D);
+                for (int r = 0; r < C; ++r)
+                    for (int a = 0; a < D; ++a) dQ[r * D + a] += cc.Lam[r] * tmp[r * D + a];
+                /* dK_inter = (lambda^C Lambda^-1 V) dKV^T */
+                for (int r = 0; r < C; ++r)
+                    for (int c = 0; c < D; ++c) sc[r * D + c] = cc.LamInv[r] * V[r * D + c];
+                matmul_nt(sc, dKV, tmp, C, D, D);
+                for (int e = 0; e < C * D; ++e) dK[e] += tmp[e];
+                /* dV_inter = (lambda^C Lambda^-1 K) dKV */
+                for (int r = 0; r < C; ++r)
+                    for (int a = 0; a < D; ++a) sc[r * D + a] = cc.LamInv[r] * K[r * D + a];
+                matmul(sc, dKV, tmp, C, D, D);
+                for (int e = 0; e < C * D; ++e) dV[e] += tmp[e];
+                /* dKV <- lambda^C dKV + (Lambda Q)^T dO */
+                for (int r = 0; r < C; ++r)
+                    for (int a = 0; a < D; ++a) sc[r * D + a] = cc.Lam[r] * Q[r * D + a];
+                matmul_tn(sc, dO, tmp, C, D, D);
+                for (int e = 0; e < D * D; ++e) dKV[e] = cc.lamC * dKV[e] + tmp[e];
+            }
+        }
+        free_consts(&cc);
+        free(S);
+        free(dS);
+        free(tmp);
+        free(sc);
+        free(Otmp);
+        free(cache);
+    }
+    return fail;
+}
+
+int lasp_oracle_num_threads(void)
+{
+    int n = 1;
+#ifdef _OPENMP
+    n = omp_get_max_threads();
+#endif
+    return n;
+}

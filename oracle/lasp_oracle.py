@@ -1,0 +1,210 @@
+"""ctypes front end of the fp64 CPU oracle (oracle/lasp_oracle.c).
+
+TEST INFRASTRUCTURE ONLY: imported by tests/, by the smoke check and by the
+cpu_baseline leg of bench.py. It imports nothing from the GPU package.
+
+All functions take numpy arrays of any float dtype (converted exactly to
+float64) in the layouts of the C file: q/k/v/dout [B,H,N,D], states [B,H,D,D],
+decay [H]; they return float64 arrays.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "lasp_oracle.c")
+_LIB = os.path.join(_HERE, "liblasp_oracle.so")
+
+_dp = ctypes.POINTER(ctypes.c_double)
+_ip = ctypes.POINTER(ctypes.c_longlong)
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc (plain -O2, OpenMP over heads/rows)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        subprocess.check_call(
+            ["gcc", "-O2", "-fopenmp", "-fPIC", "-shared", "-Wall", "-Wextra", "-o", _LIB, _SRC, "-lm"]
+        )
+    return _LIB
+
+
+_lib = None
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        _lib = ctypes.CDLL(_LIB)
+    return _lib
+
+
+def _d(x):
+    return np.ascontiguousarray(np.asarray(x, dtype=np.float64))
+
+
+def _p(x):
+    return x.ctypes.data_as(_dp) if x is not None else None
+
+
+def _shape(q):
+    if q.ndim != 4:
+        raise ValueError("expected [B,H,N,D]")
+    return tuple(int(x) for x in q.shape)
+
+
+def _opt_state(x, B, H, D):
+    if x is None:
+        return None
+    x = _d(x)
+    if x.shape != (B, H, D, D):
+        raise ValueError("state must be [B,H,D,D]")
+    return x
+
+
+def num_threads() -> int:
+    return int(_load().lasp_oracle_num_threads())
+
+
+def _fwd(name, q, k, v, decay, kv_in, chunk=None):
+    lib = _load()
+    q, k, v, decay = _d(q), _d(k), _d(v), _d(decay)
+    B, H, N, D = _shape(q)
+    assert k.shape == q.shape and v.shape == q.shape and decay.shape == (H,)
+    kv_in = _opt_state(kv_in, B, H, D)
+    out = np.empty_like(q)
+    kv_out = np.empty((B, H, D, D), dtype=np.float64)
+    fn = getattr(lib, name)
+    args = [ctypes.c_int(B), ctypes.c_int(H), ctypes.c_longlong(N), ctypes.c_int(D)]
+    if chunk is not None:
+        args.append(ctypes.c_int(int(chunk)))
+    args += [_p(q), _p(k), _p(v), _p(kv_in), _p(decay), _p(out), _p(kv_out)]
+    rc = fn(*args)
+    if rc != 0:
+        raise RuntimeError(f"{name} failed with code {rc}")
+    return out, kv_out
+
+
+def _bwd(name, q, k, v, dout, decay, kv_in, dkv_out, chunk=None):
+    lib = _load()
+    q, k, v, dout, decay = _d(q), _d(k), _d(v), _d(dout), _d(decay)
+    B, H, N, D = _shape(q)
+    assert k.shape == q.shape and v.shape == q.shape and dout.shape == q.shape and decay.shape == (H,)
+    kv_in = _opt_state(kv_in, B, H, D)
+    dkv_out = _opt_state(dkv_out, B, H, D)
+    dq, dk, dv = np.empty_like(q), np.empty_like(q), np.empty_like(q)
+    dkv_in = np.empty((B, H, D, D), dtype=np.float64)
+    fn = getattr(lib, name)
+    args = [ctypes.c_int(B), ctypes.c_int(H), ctypes.c_longlong(N), ctypes.c_int(D)]
+    if chunk is not None:
+        args.append(ctypes.c_int(int(chunk)))
+    args += [_p(q), _p(k), _p(v), _p(dout), _p(kv_in), _p(dkv_out), _p(decay), _p(dq), _p(dk), _p(dv), _p(dkv_in)]
+    rc = fn(*args)
+    if rc != 0:
+        raise RuntimeError(f"{name} failed with code {rc}")
+    return dq, dk, dv, dkv_in
+
+
+def fwd_brute(q, k, v, decay, kv_in=None):
+    """Definition: o_s = sum_{i<=s} lam^(s-i) (q_s.k_i) v_i + lam^s K0^T q_s; returns (out, kv_out)."""
+    return _fwd("lasp_oracle_fwd_brute", q, k, v, decay, kv_in)
+
+
+def fwd_recurrent(q, k, v, decay, kv_in=None):
+    return _fwd("lasp_oracle_fwd_recurrent", q, k, v, decay, kv_in)
+
+
+def fwd_chunked(q, k, v, decay, chunk, kv_in=None):
+    return _fwd("lasp_oracle_fwd_chunked", q, k, v, decay, kv_in, chunk=chunk)
+
+
+def bwd_brute(q, k, v, dout, decay, kv_in=None, dkv_out=None):
+    """Returns (dq, dk, dv, dkv_in) for the loss sum(out*dout) + sum(kv_out*dkv_out)."""
+    return _bwd("lasp_oracle_bwd_brute", q, k, v, dout, decay, kv_in, dkv_out)
+
+
+def bwd_recurrent(q, k, v, dout, decay, kv_in=None, dkv_out=None):
+    return _bwd("lasp_oracle_bwd_recurrent", q, k, v, dout, decay, kv_in, dkv_out)
+
+
+def bwd_chunked(q, k, v, dout, decay, chunk, kv_in=None, dkv_out=None):
+    return _bwd("lasp_oracle_bwd_chunked", q, k, v, dout, decay, kv_in, dkv_out, chunk=chunk)
+
+
+def _rows(rows, B, H, N):
+    rows = np.ascontiguousarray(np.asarray(rows, dtype=np.int64))
+    if rows.ndim != 2 or rows.shape[1] != 3:
+        raise ValueError("rows must be [n,3] of (b,h,s0)")
+    return rows
+
+
+def fwd_brute_rows(q, k, v, decay, rows, kv_in=None):
+    """Brute-force outputs for selected (b, h, s0) rows only; returns [n, D]."""
+    lib = _load()
+    q, k, v, decay = _d(q), _d(k), _d(v), _d(decay)
+    B, H, N, D = _shape(q)
+    kv_in = _opt_state(kv_in, B, H, D)
+    rows = _rows(rows, B, H, N)
+    out = np.empty((rows.shape[0], D), dtype=np.float64)
+    rc = lib.lasp_oracle_fwd_brute_rows(
+        ctypes.c_int(B), ctypes.c_int(H), ctypes.c_longlong(N), ctypes.c_int(D), _p(q), _p(k), _p(v),
+        _p(kv_in), _p(decay), ctypes.c_longlong(rows.shape[0]), rows.ctypes.data_as(_ip), _p(out))
+    if rc != 0:
+        raise RuntimeError(f"fwd_brute_rows failed with code {rc}")
+    return out
+
+
+def bwd_brute_rows(q, k, v, dout, decay, rows, kv_in=None, dkv_out=None):
+    """Brute-force (dq, dk, dv) for selected (b, h, s0) rows only; each [n, D]."""
+    lib = _load()
+    q, k, v, dout, decay = _d(q), _d(k), _d(v), _d(dout), _d(decay)
+    B, H, N, D = _shape(q)
+    kv_in = _opt_state(kv_in, B, H, D)
+    dkv_out = _opt_state(dkv_out, B, H, D)
+    rows = _rows(rows, B, H, N)
+    n = rows.shape[0]
+    dq, dk, dv = (np.empty((n, D), dtype=np.float64) for _ in range(3))
+    rc = lib.lasp_oracle_bwd_brute_rows(
+        ctypes.c_int(B), ctypes.c_int(H), ctypes.c_longlong(N), ctypes.c_int(D), _p(q), _p(k), _p(v),
+        _p(dout), _p(kv_in), _p(dkv_out), _p(decay), ctypes.c_longlong(n), rows.ctypes.data_as(_ip),
+        _p(dq), _p(dk), _p(dv))
+    if rc != 0:
+        raise RuntimeError(f"bwd_brute_rows failed with code {rc}")
+    return dq, dk, dv
+
+
+def fwd_split(fwd_fn, q, k, v, decay, T, kv_in=None, **kw):
+    """T sub-sequences processed in order, kv_out of one handed to the next as
+    kv_in (the ring of Alg. 2 folded into a loop). Returns (out, kv_out, kv_ins)
+    where kv_ins[t] is the state sub-sequence t received (kept for backward)."""
+    q, k, v = _d(q), _d(k), _d(v)
+    N = q.shape[2]
+    assert N % T == 0
+    n = N // T
+    outs, kv_ins = [], []
+    state = kv_in
+    for t in range(T):
+        sl = slice(t * n, (t + 1) * n)
+        kv_ins.append(state)
+        o, state = fwd_fn(q[:, :, sl], k[:, :, sl], v[:, :, sl], decay, kv_in=state, **kw)
+        outs.append(o)
+    return np.concatenate(outs, axis=2), state, kv_ins
+
+
+def bwd_split(bwd_fn, q, k, v, dout, decay, T, kv_ins, dkv_out=None, **kw):
+    """Reverse loop of Alg. 3: sub-sequence t receives dkv from t+1 and hands
+    its dkv_in to t-1. Returns (dq, dk, dv, dkv_in)."""
+    q, k, v, dout = _d(q), _d(k), _d(v), _d(dout)
+    N = q.shape[2]
+    n = N // T
+    dqs, dks, dvs = [None] * T, [None] * T, [None] * T
+    g = dkv_out
+    for t in reversed(range(T)):
+        sl = slice(t * n, (t + 1) * n)
+        dqs[t], dks[t], dvs[t], g = bwd_fn(q[:, :, sl], k[:, :, sl], v[:, :, sl], dout[:, :, sl], decay,
+                                           kv_in=kv_ins[t], dkv_out=g, **kw)
+    return np.concatenate(dqs, axis=2), np.concatenate(dks, axis=2), np.concatenate(dvs, axis=2), g
