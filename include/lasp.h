@@ -1,0 +1,139 @@
+/*
+ * lasp.h -- C ABI of the MI355X (gfx950) hot path of LASP, arxiv 2404.02882:
+ * causal linear attention with per-head decay, computed chunk by chunk with a
+ * carried d x d KV state (forward) and a carried dKV state (backward).
+ *
+ * One call processes one sub-sequence of N tokens for all B*H heads. A longer
+ * sequence is processed as successive calls: forward in order, handing kv_out
+ * of one call to the next as kv_in; backward in reverse order, handing dkv_in
+ * of one call to the previous as dkv_out. This loop is the paper's ring of
+ * ranks (Alg. 2 Recv/Send of KV, Alg. 3 Recv/Send of dKV) folded onto one GPU:
+ * the messages are these state buffers.
+ *
+ * Common conventions
+ *   - Every pointer is a DEVICE pointer owned by the caller. The library never
+ *     allocates, frees or synchronises: work is enqueued on `hip_stream`
+ *     (a hipStream_t; NULL = the default stream) and the call returns at once.
+ *   - q, k, v, out, dout, dq, dk, dv: [B][H][N][D], row-major, one token row is
+ *     D contiguous elements of `dtype` (LASP_F32: float, LASP_BF16: bfloat16).
+ *   - kv_in, kv_out, dkv_out, dkv_in: [B][H][D][D] float, state[a][c] with a the
+ *     key/query feature and c the value feature (KV = sum k[a] v[c]).
+ *   - decay: [H] float on the device, lambda_h in (0, 1], shared over the
+ *     batch; lambda = 1 is ordinary linear attention (Sec. 3.2). It is not
+ *     learnable, so no gradient is produced for it.
+ *   - Every function returns a lasp_status; nothing throws or aborts. All
+ *     argument checks run on the host before anything is launched.
+ *   - Outputs must not alias inputs or each other. Calls that share a scratch
+ *     or state_cache buffer must be ordered on one stream.
+ */
+#ifndef LASP_H
+#define LASP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    LASP_OK = 0,
+    LASP_ERR_NULL = 1,      /* a required pointer is NULL */
+    LASP_ERR_SHAPE = 2,     /* B,H,N <= 0; D not 64/128; chunk not 64/128/256; N % chunk != 0; bad segments */
+    LASP_ERR_DTYPE = 3,     /* dtype is neither LASP_F32 nor LASP_BF16 */
+    LASP_ERR_DECAY = 4,     /* lasp_check_decay: a value outside (0, 1] or not finite */
+    LASP_ERR_WORKSPACE = 5, /* scratch missing or smaller than lasp_scratch_bytes() */
+    LASP_ERR_ALIAS = 6,     /* an output buffer overlaps an input or another output */
+    LASP_ERR_HIP = 7        /* the HIP runtime refused a launch */
+} lasp_status;
+
+typedef enum { LASP_F32 = 0, LASP_BF16 = 1 } lasp_dtype;
+
+/*
+ * Problem shape of one call.
+ *   N        tokens in this sub-sequence (the paper's per-rank length N/T).
+ *   chunk    the chunk length C of Alg. 2 / Alg. 3. The kernels walk the
+ *            sub-sequence in tiles of lasp_tile_tokens() tokens; the tile
+ *            divides the chunk, which is exact because the state update of
+ *            Sec. 3.2 composes over consecutive tiles.
+ *   segments 0 = chosen by the library. Otherwise the number of independent
+ *            segments each head's sub-sequence is cut into so that B*H*segments
+ *            workgroups fill the chip (1 <= segments <= N / tile).
+ */
+typedef struct {
+    int32_t B, H, N, D, chunk;
+    int32_t dtype;    /* lasp_dtype */
+    int32_t segments; /* 0 = auto */
+} lasp_shape;
+
+int lasp_version(void);
+const char *lasp_status_str(int status);
+
+/* Validates a shape exactly as lasp_fwd / lasp_bwd do. Host only. */
+int lasp_check_shape(const lasp_shape *shape);
+
+/* Validates a HOST copy of the decay vector: every value finite and in (0, 1]. */
+int lasp_check_decay(const float *decay_host, int32_t H);
+
+/* Tokens per kernel tile for this shape (divides chunk); 0 on an invalid shape. */
+int32_t lasp_tile_tokens(const lasp_shape *shape);
+
+/* Segments per head the library will use for this shape; 0 on an invalid shape. */
+int32_t lasp_num_segments(const lasp_shape *shape);
+
+/*
+ * Bytes of the per-tile state cache: the state KV_{t-1} every tile starts
+ * from, written by lasp_fwd and read by lasp_bwd for dQ_inter (the paper caches
+ * the state a rank receives, Alg. 2 "save KV_{t-1}", Sec. 3.4; this build
+ * caches it per tile so that the backward pass needs no forward recurrence).
+ * Stored in `dtype`. 0 on an invalid shape.
+ */
+size_t lasp_state_cache_bytes(const lasp_shape *shape);
+
+/*
+ * Bytes of scratch both lasp_fwd and lasp_bwd need: one float [D][D] state per
+ * head per segment. Contents are overwritten by every call. 0 on an invalid shape.
+ */
+size_t lasp_scratch_bytes(const lasp_shape *shape);
+
+/*
+ * Forward (Alg. 2 without the projections and with Recv/Send replaced by
+ * kv_in/kv_out). For every head and token s = 1..N of this sub-sequence:
+ *     out_s  = sum_{i<=s} lambda^(s-i) (q_s . k_i) v_i  +  lambda^s kv_in^T q_s
+ *     kv_out = lambda^N kv_in + sum_i lambda^(N-i) k_i v_i^T
+ * computed per tile as O = [(Q K^T) (.) M] V + Lambda Q KV_{t-1} and
+ * KV_t = lambda^C KV_{t-1} + (lambda^C Lambda^-1 K)^T V.
+ *
+ *   kv_in        NULL = zeros (first sub-sequence, Alg. 2 "KV = 0").
+ *   out, kv_out  required.
+ *   state_cache  NULL = forward only, nothing cached; else at least
+ *                lasp_state_cache_bytes() bytes, to be passed to lasp_bwd.
+ *   scratch      at least lasp_scratch_bytes() bytes (scratch_bytes = its size).
+ */
+int lasp_fwd(const lasp_shape *shape, const void *q, const void *k, const void *v,
+             const float *kv_in, const float *decay, void *out, float *kv_out,
+             void *state_cache, void *scratch, size_t scratch_bytes, void *hip_stream);
+
+/*
+ * Backward (Alg. 3 with Recv/Send replaced by dkv_out/dkv_in). Gradients of
+ *     L = sum(out * dout) + sum(kv_out * dkv_out):
+ *     dq_s = kv_s do_s,  dk_s = dkv_s v_s,  dv_s = dkv_s^T k_s,
+ *     dkv_s = sum_{i>=s} lambda^(i-s) q_i do_i^T + lambda^(N-s) dkv_out,
+ *     dkv_in = lambda^N dkv_out + sum_s lambda^s q_s do_s^T   (gradient w.r.t. kv_in)
+ * computed per tile as in Alg. 3 (intra parts from the masked S and dS, inter
+ * parts from the cached KV_{t-1} and the carried dKV).
+ *
+ *   dkv_out      NULL = zeros (last sub-sequence, Alg. 3 "dKV = 0").
+ *   state_cache  required: the buffer the matching lasp_fwd call filled (same
+ *                shape, same inputs, same kv_in).
+ *   dq, dk, dv, dkv_in  required.
+ */
+int lasp_bwd(const lasp_shape *shape, const void *q, const void *k, const void *v,
+             const void *dout, const float *dkv_out, const float *decay,
+             const void *state_cache, void *dq, void *dk, void *dv, float *dkv_in,
+             void *scratch, size_t scratch_bytes, void *hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LASP_H */

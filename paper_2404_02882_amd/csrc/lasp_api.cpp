@@ -1,0 +1,169 @@
+// C-ABI host layer: argument validation, launch planning, dispatch. No device
+// memory is allocated or freed here and nothing synchronises; see include/lasp.h.
+#include "../../include/lasp.h"
+
+#include <cmath>
+#include <cstdint>
+
+#include "lasp_internal.h"
+
+namespace {
+
+// Segments per head when the caller leaves the choice to the library: enough
+// workgroups (B*H*segments) for two per compute unit of a 256-CU device, never
+// more than one segment per tile.
+constexpr int kTargetWorkgroups = 512;
+
+bool valid_dims(const lasp_shape *s) {
+    if (!s) return false;
+    if (s->B <= 0 || s->H <= 0 || s->N <= 0) return false;
+    if (s->D != 64 && s->D != 128) return false;
+    if (s->chunk != 64 && s->chunk != 128 && s->chunk != 256) return false;
+    if (s->N % s->chunk != 0) return false;
+    if ((int64_t)s->B * s->H > 65535) return false;  // grid.y limit
+    return true;
+}
+
+int make_plan(const lasp_shape *s, lasp::Plan *p) {
+    if (!s) return LASP_ERR_NULL;
+    if (s->dtype != LASP_F32 && s->dtype != LASP_BF16) return LASP_ERR_DTYPE;
+    if (!valid_dims(s)) return LASP_ERR_SHAPE;
+    p->B = s->B;
+    p->H = s->H;
+    p->N = s->N;
+    p->D = s->D;
+    p->dtype = s->dtype;
+    p->tile = lasp::tile_tokens(s->dtype, s->chunk, s->D);
+    p->ntiles = s->N / p->tile;
+    int want = s->segments;
+    if (want < 0 || want > p->ntiles) return LASP_ERR_SHAPE;
+    if (want == 0) {
+        int64_t chains = (int64_t)s->B * s->H;
+        want = (int)((kTargetWorkgroups + chains - 1) / chains);
+        if (want > p->ntiles) want = p->ntiles;
+        if (want < 1) want = 1;
+    }
+    p->tiles_per_seg = (p->ntiles + want - 1) / want;
+    p->nseg = (p->ntiles + p->tiles_per_seg - 1) / p->tiles_per_seg;  // every segment non-empty
+    return LASP_OK;
+}
+
+size_t elem_bytes(int dtype) { return dtype == LASP_F32 ? 4 : 2; }
+
+struct Span {
+    const char *p;
+    size_t n;
+};
+bool overlap(Span a, Span b) { return a.p && b.p && a.p < b.p + b.n && b.p < a.p + a.n; }
+
+}  // namespace
+
+extern "C" {
+
+int lasp_version(void) { return 1; }
+
+const char *lasp_status_str(int status) {
+    switch (status) {
+        case LASP_OK: return "ok";
+        case LASP_ERR_NULL: return "a required pointer is NULL";
+        case LASP_ERR_SHAPE: return "unsupported shape (need B,H,N > 0, D in {64,128}, chunk in {64,128,256}, N % chunk == 0, 0 <= segments <= N/tile)";
+        case LASP_ERR_DTYPE: return "unsupported dtype (LASP_F32 or LASP_BF16)";
+        case LASP_ERR_DECAY: return "decay must be finite and in (0, 1]";
+        case LASP_ERR_WORKSPACE: return "scratch buffer missing or too small (see lasp_scratch_bytes)";
+        case LASP_ERR_ALIAS: return "an output buffer overlaps an input or another output";
+        case LASP_ERR_HIP: return "HIP runtime error at launch";
+        default: return "unknown status";
+    }
+}
+
+int lasp_check_shape(const lasp_shape *shape) {
+    lasp::Plan p;
+    return make_plan(shape, &p);
+}
+
+int lasp_check_decay(const float *decay_host, int32_t H) {
+    if (!decay_host) return LASP_ERR_NULL;
+    if (H <= 0) return LASP_ERR_SHAPE;
+    for (int32_t h = 0; h < H; ++h) {
+        float x = decay_host[h];
+        if (!std::isfinite(x) || !(x > 0.0f) || x > 1.0f) return LASP_ERR_DECAY;
+    }
+    return LASP_OK;
+}
+
+int32_t lasp_tile_tokens(const lasp_shape *shape) {
+    lasp::Plan p;
+    return make_plan(shape, &p) == LASP_OK ? p.tile : 0;
+}
+
+int32_t lasp_num_segments(const lasp_shape *shape) {
+    lasp::Plan p;
+    return make_plan(shape, &p) == LASP_OK ? p.nseg : 0;
+}
+
+size_t lasp_state_cache_bytes(const lasp_shape *shape) {
+    lasp::Plan p;
+    if (make_plan(shape, &p) != LASP_OK) return 0;
+    return (size_t)p.B * p.H * p.ntiles * p.D * p.D * elem_bytes(p.dtype);
+}
+
+size_t lasp_scratch_bytes(const lasp_shape *shape) {
+    lasp::Plan p;
+    if (make_plan(shape, &p) != LASP_OK) return 0;
+    return (size_t)p.B * p.H * p.nseg * p.D * p.D * sizeof(float);
+}
+
+int lasp_fwd(const lasp_shape *shape, const void *q, const void *k, const void *v, const float *kv_in,
+             const float *decay, void *out, float *kv_out, void *state_cache, void *scratch,
+             size_t scratch_bytes, void *hip_stream) {
+    lasp::Plan p;
+    int rc = make_plan(shape, &p);
+    if (rc != LASP_OK) return rc;
+    if (!q || !k || !v || !decay || !out || !kv_out) return LASP_ERR_NULL;
+    if (!scratch || scratch_bytes < lasp_scratch_bytes(shape)) return LASP_ERR_WORKSPACE;
+
+    const size_t tb = (size_t)p.B * p.H * p.N * p.D * elem_bytes(p.dtype);
+    const size_t sb = (size_t)p.B * p.H * p.D * p.D * sizeof(float);
+    const Span ins[] = {{(const char *)q, tb}, {(const char *)k, tb}, {(const char *)v, tb},
+                        {(const char *)kv_in, sb}, {(const char *)decay, p.H * sizeof(float)}};
+    const Span outs[] = {{(const char *)out, tb}, {(const char *)kv_out, sb},
+                         {(const char *)state_cache, lasp_state_cache_bytes(shape)},
+                         {(const char *)scratch, lasp_scratch_bytes(shape)}};
+    for (const Span &o : outs) {
+        for (const Span &i : ins)
+            if (overlap(o, i)) return LASP_ERR_ALIAS;
+        for (const Span &o2 : outs)
+            if (&o != &o2 && overlap(o, o2)) return LASP_ERR_ALIAS;
+    }
+    lasp::FwdArgs a{q, k, v, kv_in, decay, out, kv_out, state_cache, (float *)scratch};
+    return lasp::launch_fwd(p, a, (hipStream_t)hip_stream) == hipSuccess ? LASP_OK : LASP_ERR_HIP;
+}
+
+int lasp_bwd(const lasp_shape *shape, const void *q, const void *k, const void *v, const void *dout,
+             const float *dkv_out, const float *decay, const void *state_cache, void *dq, void *dk,
+             void *dv, float *dkv_in, void *scratch, size_t scratch_bytes, void *hip_stream) {
+    lasp::Plan p;
+    int rc = make_plan(shape, &p);
+    if (rc != LASP_OK) return rc;
+    if (!q || !k || !v || !dout || !decay || !state_cache || !dq || !dk || !dv || !dkv_in) return LASP_ERR_NULL;
+    if (!scratch || scratch_bytes < lasp_scratch_bytes(shape)) return LASP_ERR_WORKSPACE;
+
+    const size_t tb = (size_t)p.B * p.H * p.N * p.D * elem_bytes(p.dtype);
+    const size_t sb = (size_t)p.B * p.H * p.D * p.D * sizeof(float);
+    const Span ins[] = {{(const char *)q, tb}, {(const char *)k, tb}, {(const char *)v, tb},
+                        {(const char *)dout, tb}, {(const char *)dkv_out, sb},
+                        {(const char *)decay, p.H * sizeof(float)},
+                        {(const char *)state_cache, lasp_state_cache_bytes(shape)}};
+    const Span outs[] = {{(const char *)dq, tb}, {(const char *)dk, tb}, {(const char *)dv, tb},
+                         {(const char *)dkv_in, sb}, {(const char *)scratch, lasp_scratch_bytes(shape)}};
+    for (const Span &o : outs) {
+        for (const Span &i : ins)
+            if (overlap(o, i)) return LASP_ERR_ALIAS;
+        for (const Span &o2 : outs)
+            if (&o != &o2 && overlap(o, o2)) return LASP_ERR_ALIAS;
+    }
+    lasp::BwdArgs a{q, k, v, dout, dkv_out, decay, state_cache, dq, dk, dv, dkv_in, (float *)scratch};
+    return lasp::launch_bwd(p, a, (hipStream_t)hip_stream) == hipSuccess ? LASP_OK : LASP_ERR_HIP;
+}
+
+}  // extern "C"

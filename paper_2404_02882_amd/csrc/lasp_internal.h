@@ -1,0 +1,49 @@
+// Internal interface between the C-ABI host layer (lasp_api.cpp) and the HIP
+// kernels (lasp_kernels.hip). Not installed; the public boundary is include/lasp.h.
+#ifndef LASP_INTERNAL_H
+#define LASP_INTERNAL_H
+
+#include <hip/hip_runtime_api.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace lasp {
+
+// Everything a launch needs, already validated by the host layer.
+struct Plan {
+    int B, H, N, D;
+    int dtype;          // 0 = float, 1 = bfloat16
+    int tile;           // tokens per kernel tile (CT)
+    int ntiles;         // N / tile
+    int nseg;           // segments per head (S)
+    int tiles_per_seg;  // ceil(ntiles / nseg); the last segment may be shorter
+};
+
+struct FwdArgs {
+    const void *q, *k, *v;
+    const float *kv_in;   // may be null (zeros)
+    const float *decay;
+    void *out;
+    float *kv_out;
+    void *cache;          // may be null
+    float *scratch;       // [B*H][nseg][D][D]
+};
+
+struct BwdArgs {
+    const void *q, *k, *v, *dout;
+    const float *dkv_out; // may be null (zeros)
+    const float *decay;
+    const void *cache;
+    void *dq, *dk, *dv;
+    float *dkv_in;
+    float *scratch;
+};
+
+// Tile length used for a (dtype, chunk, D) combination.
+int tile_tokens(int dtype, int chunk, int D);
+
+hipError_t launch_fwd(const Plan &p, const FwdArgs &a, hipStream_t stream);
+hipError_t launch_bwd(const Plan &p, const BwdArgs &a, hipStream_t stream);
+
+}  // namespace lasp
+#endif

@@ -1,0 +1,704 @@
+// HIP kernels (gfx950 / CDNA4) for chunked causal linear attention with decay:
+// the per-device hot path of LASP (arxiv 2404.02882, Alg. 2 forward, Alg. 3
+// backward).
+//
+// Parallel structure. One head's sub-sequence is a serial recurrence over
+// tiles, and there can be as few as 16 heads, so every head is cut into
+// `nseg` segments of consecutive tiles that run as independent workgroups:
+//   1. k_local : each segment accumulates its local state from zero
+//                (forward: sum lambda^(len-s) k_s v_s^T; backward: sum
+//                lambda^s q_s do_s^T), reading only K,V (or Q,dO).
+//   2. k_scan  : an elementwise scan over the segments of a head turns the
+//                local states into the state each segment starts from
+//                (KV_t = lambda^len KV_{t-1} + local, the state update of
+//                Sec. 3.2 taken over a whole segment).
+//   3. k_fwd / k_bwd : each segment walks its tiles with the d x d state held
+//                in registers: intra-chunk left product, inter-chunk right
+//                product, state update (Alg. 2 / Alg. 3 per tile).
+// This is the paper's "intra parts in parallel, inter parts in sequence"
+// (Alg. 2) folded onto one GPU; there are no atomics, so results are
+// bit-reproducible.
+//
+// Wave tiling. A workgroup has D/32 waves; wave w owns the 32-wide column block
+// w of every [.][D] output tile and of the state, so the state tile it holds in
+// MFMA accumulator layout can be fed back as the B operand of the next product
+// without leaving registers (the contraction index is permuted identically on
+// the A side). All products use 32x32 MFMA tiles: v_mfma_f32_32x32x16_bf16 for
+// bfloat16 data, v_mfma_f32_32x32x2_f32 for float data; accumulation and the
+// state are always fp32.
+#include <hip/hip_runtime.h>
+
+#include "lasp_internal.h"
+
+namespace lasp {
+
+typedef unsigned short bf16_t;  // storage type of bfloat16 data
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+typedef __attribute__((ext_vector_type(8))) float f32x8;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) short s16x4;
+
+#define DEVI __device__ __forceinline__
+
+DEVI int lane_id() { return threadIdx.x & 63; }
+DEVI int lane_r() { return threadIdx.x & 31; }         // row / column inside a 32-wide tile
+DEVI int lane_h() { return (threadIdx.x >> 5) & 1; }   // which half of the contraction step
+
+// Row of accumulator register i (0..15) inside a 32x32 MFMA tile; the column is lane_r().
+DEVI int acc_row(int i) { return 8 * (i >> 2) + 4 * lane_h() + (i & 3); }
+
+// ---------------------------------------------------------------------------
+// Element traits: how MFMA operand fragments are fetched for each data type.
+// A fragment is what one lane feeds to one MFMA: for a 32-row (or 32-column)
+// operand block, lane (r, h) supplies row/column r and the h-th half of the
+// KSTEP contraction indices of that MFMA.
+//   ld_kc : contraction index contiguous in memory  X[(row0 + r) * ld + k]
+//   ld_ks : contraction index strided in memory     X[k * ld + col0 + r]
+//   ld_kp : contraction index contiguous, but taken in the permuted order in
+//           which an accumulator tile enumerates its rows (sub-step m of the
+//           32-wide block starting at kb), so that accumulator registers can be
+//           the other operand.
+// ---------------------------------------------------------------------------
+template <typename T>
+struct Elem;
+
+template <>
+struct Elem<float> {
+    typedef float frag;
+    static constexpr int KSTEP = 2;   // contraction extent of one MFMA
+    static constexpr int NSUB = 16;   // MFMAs per 32-wide contraction block
+    static constexpr int PAD = 4;     // elements of row padding in LDS tiles
+    static DEVI f32x16 mfma(frag a, frag b, f32x16 c) { return __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, c, 0, 0, 0); }
+    static DEVI frag ld_kc(const float *X, int ld, int row0, int k0) { return X[(row0 + lane_r()) * ld + k0 + lane_h()]; }
+    static DEVI frag ld_ks(const float *X, int ld, int k0, int col0) { return X[(k0 + lane_h()) * ld + col0 + lane_r()]; }
+    static DEVI frag ld_kp(const float *X, int ld, int row0, int kb, int m) {
+        return X[(row0 + lane_r()) * ld + kb + acc_row(m)];
+    }
+    // accumulator tile -> fragment for sub-step m
+    static DEVI frag from_acc(const f32x16 &t, int m) { return t[m]; }
+    // multiply each contraction element k of the fragment by w[k]
+    template <typename W>
+    static DEVI frag scale(frag f, int k0, W w) { return f * w(k0 + lane_h()); }
+    // store 4 values of consecutive columns
+    static DEVI void st4(float *p, float a, float b, float c, float d) { *(f32x4 *)p = f32x4{a, b, c, d}; }
+    static DEVI void st1(float *p, float a) { *p = a; }
+    static DEVI float ld1(const float *p) { return *p; }
+};
+
+template <>
+struct Elem<bf16_t> {
+    typedef bf16x8 frag;
+    static constexpr int KSTEP = 16;
+    static constexpr int NSUB = 2;
+    static constexpr int PAD = 8;
+    static DEVI f32x16 mfma(frag a, frag b, f32x16 c) { return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0); }
+    static DEVI frag ld_kc(const bf16_t *X, int ld, int row0, int k0) {
+        return *(const bf16x8 *)(X + (row0 + lane_r()) * ld + k0 + 8 * lane_h());
+    }
+    // LDS only: two transposing reads (ds_read_b64_tr_b16). Within each group of
+    // 16 lanes, lane i ends up with element (row e, column i) of the 4 x 16 block
+    // whose rows the lanes addressed in 4-element pieces.
+    static DEVI frag ld_ks(const bf16_t *X, int ld, int k0, int col0) {
+        const int l = lane_id();
+        const int l16 = l & 15;
+        const bf16_t *p = X + (k0 + 8 * lane_h() + (l16 >> 2)) * ld + col0 + 16 * ((l >> 4) & 1) + 4 * (l16 & 3);
+        typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+        s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)p);
+        s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(p + 4 * ld));
+        union { struct { s16x4 a, b; } s; bf16x8 v; } u;
+        u.s.a = lo;
+        u.s.b = hi;
+        return u.v;
+    }
+    static DEVI frag ld_kp(const bf16_t *X, int ld, int row0, int kb, int m) {
+        const bf16_t *p = X + (row0 + lane_r()) * ld + kb + 16 * m + 4 * lane_h();
+        union { struct { bf16x4 a, b; } s; bf16x8 v; } u;
+        u.s.a = *(const bf16x4 *)p;
+        u.s.b = *(const bf16x4 *)(p + 8);
+        return u.v;
+    }
+    static DEVI frag from_acc(const f32x16 &t, int m) {
+        f32x8 x;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) x[e] = t[8 * m + e];
+        return __builtin_convertvector(x, bf16x8);
+    }
+    template <typename W>
+    static DEVI frag scale(frag f, int k0, W w) {
+        f32x8 x = __builtin_convertvector(f, f32x8);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) x[e] *= w(k0 + 8 * lane_h() + e);
+        return __builtin_convertvector(x, bf16x8);
+    }
+    static DEVI void st4(bf16_t *p, float a, float b, float c, float d) {
+        *(bf16x4 *)p = __builtin_convertvector(f32x4{a, b, c, d}, bf16x4);
+    }
+    static DEVI void st1(bf16_t *p, float a) {
+        union { __bf16 b; bf16_t u; } c;
+        c.b = (__bf16)a;
+        *p = c.u;
+    }
+    static DEVI float ld1(const bf16_t *p) { return __uint_as_float(((unsigned)*p) << 16); }
+};
+
+// ---------------------------------------------------------------------------
+// Tile movement: global -> registers -> LDS in 16-byte pieces. Splitting the
+// two halves lets the next tile's loads fly while the current one is computed.
+// ---------------------------------------------------------------------------
+template <typename T, int ROWS, int COLS, int NT>
+struct TileMover {
+    static constexpr int EPV = 16 / sizeof(T);          // elements per 16-byte piece
+    static constexpr int VPR = COLS / EPV;              // pieces per row
+    static constexpr int NV = ROWS * VPR / NT;          // pieces per thread
+    static_assert(ROWS * VPR % NT == 0, "tile must divide evenly over the workgroup");
+    uint4 r[NV];
+    DEVI void load(const T *g) {  // g: first element of the tile, row stride COLS
+#pragma unroll
+        for (int i = 0; i < NV; ++i) {
+            int v = threadIdx.x + i * NT;
+            r[i] = *(const uint4 *)(g + (size_t)(v / VPR) * COLS + (v % VPR) * EPV);
+        }
+    }
+    DEVI void store(T *s, int ld) const {
+#pragma unroll
+        for (int i = 0; i < NV; ++i) {
+            int v = threadIdx.x + i * NT;
+            *(uint4 *)(s + (v / VPR) * ld + (v % VPR) * EPV) = r[i];
+        }
+    }
+};
+
+// lambda^n for n = 0..CT into LDS, evaluated in double so that the table adds
+// no error of its own.
+template <int CT>
+DEVI void fill_pow_table(float *pw, float lam) {
+    for (int i = threadIdx.x; i <= CT; i += blockDim.x) pw[i] = (float)exp2((double)i * log2((double)lam));
+}
+
+// Load / store a wave's column block of a [D][D] float state (row-major [a][c])
+// into accumulator layout: st[ab][i] = S[32 ab + acc_row(i)][32 w + lane_r()].
+template <int D>
+DEVI void state_load(f32x16 (&st)[D / 32], const float *g, int w) {
+#pragma unroll
+    for (int ab = 0; ab < D / 32; ++ab)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) st[ab][i] = g[(32 * ab + acc_row(i)) * D + 32 * w + lane_r()];
+}
+template <int D>
+DEVI void state_store(const f32x16 (&st)[D / 32], float *g, int w) {
+#pragma unroll
+    for (int ab = 0; ab < D / 32; ++ab)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) g[(32 * ab + acc_row(i)) * D + 32 * w + lane_r()] = st[ab][i];
+}
+
+// Masked score tile (Alg. 2 / Alg. 3 mask M): the wave holds the transposed
+// 32x32 block ST[j][i] = sum_d A[j][d] B[i][d] in accumulator layout (row = key j,
+// column = query i), multiplies by lambda^(i-j) for i >= j (zero above the
+// diagonal) and writes it as P[i][j] so that four consecutive keys land in one
+// store.
+template <typename T, int LDP>
+DEVI void store_masked_scores(T *sP, const f32x16 &acc, int jb, int ib, const float *pw) {
+    const int iq = 32 * ib + lane_r();
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+        const int j0 = 32 * jb + 8 * g + 4 * lane_h();
+        float x[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const int d = iq - (j0 + e);
+            x[e] = d >= 0 ? acc[4 * g + e] * pw[d] : 0.0f;
+        }
+        Elem<T>::st4(sP + iq * LDP + j0, x[0], x[1], x[2], x[3]);
+    }
+}
+
+// ST[jb][ib] = A[jb] B[ib]^T over the feature dimension (both operands have the
+// contraction index contiguous), for every lower-triangular block assigned to
+// this wave; result masked and stored to sP.
+template <typename T, int CT, int D, int LDD, int LDP>
+DEVI void masked_scores(T *sP, const T *sA, const T *sB, const float *pw, int w) {
+    using E = Elem<T>;
+    constexpr int NB = CT / 32, NW = D / 32;
+    int idx = 0;
+#pragma unroll
+    for (int ib = 0; ib < NB; ++ib)
+#pragma unroll
+        for (int jb = 0; jb <= ib; ++jb, ++idx) {
+            if (idx % NW != w) continue;
+            f32x16 acc = {0};
+#pragma unroll
+            for (int k0 = 0; k0 < D; k0 += E::KSTEP)
+                acc = E::mfma(E::ld_kc(sA, LDD, 32 * jb, k0), E::ld_kc(sB, LDD, 32 * ib, k0), acc);
+            store_masked_scores<T, LDP>(sP, acc, jb, ib, pw);
+        }
+}
+
+// Write one 32x32 accumulator tile to a [.][D] global tensor (rows row0.., column block w).
+template <typename T, int D>
+DEVI void store_out_tile(T *g, const f32x16 &acc, int row0, int w) {
+#pragma unroll
+    for (int i = 0; i < 16; ++i) Elem<T>::st1(g + (size_t)(row0 + acc_row(i)) * D + 32 * w + lane_r(), acc[i]);
+}
+
+// ---------------------------------------------------------------------------
+// k_local: local state of a segment, from zero.
+//   forward : local = sum_s lambda^(len - s) k_s v_s^T            (X = K, Y = V)
+//   backward: local = sum_s lambda^s q_s do_s^T                    (X = Q, Y = dO)
+// per tile (state update of Alg. 2 / dKV update of Alg. 3):
+//   forward : S <- lambda^CT S + (diag{lambda^(CT-1)..1} X)^T Y, tiles ascending
+//   backward: S <- lambda^CT S + (diag{lambda^1..lambda^CT} X)^T Y, tiles descending
+// The row weight is applied to the Y fragments (shared by all row blocks).
+// ---------------------------------------------------------------------------
+template <typename T, int CT, int D, bool BWD>
+__global__ __launch_bounds__(D * 2) void k_local(const T *__restrict__ X, const T *__restrict__ Y,
+                                                  const float *__restrict__ decay, float *__restrict__ scratch,
+                                                  int H, int ntiles, int nseg, int tiles_per_seg) {
+    using E = Elem<T>;
+    constexpr int NT = D * 2, LDD = D + E::PAD, DB = D / 32, NKS = CT / E::KSTEP;
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    T *sX = (T *)smem;
+    T *sY = sX + CT * LDD;
+    float *pw = (float *)(sY + CT * LDD);
+
+    const int chain = blockIdx.y;
+    const int seg = BWD ? blockIdx.x + 1 : blockIdx.x;
+    const int t0 = seg * tiles_per_seg;
+    const int t1 = min(t0 + tiles_per_seg, ntiles);
+    const int w = threadIdx.x >> 6;
+    const float lam = decay[chain % H];
+    fill_pow_table<CT>(pw, lam);
+
+    const size_t base = (size_t)chain * ntiles * CT * D;
+    f32x16 st[DB];
+#pragma unroll
+    for (int ab = 0; ab < DB; ++ab) st[ab] = f32x16{0};
+
+    TileMover<T, CT, D, NT> mx, my;
+    {
+        const int t = BWD ? t1 - 1 : t0;
+        mx.load(X + base + (size_t)t * CT * D);
+        my.load(Y + base + (size_t)t * CT * D);
+    }
+    for (int n = 0; n < t1 - t0; ++n) {
+        __syncthreads();  // previous tile fully consumed (and pw visible on the first pass)
+        mx.store(sX, LDD);
+        my.store(sY, LDD);
+        __syncthreads();
+        if (n + 1 < t1 - t0) {
+            const int t = BWD ? t1 - 2 - n : t0 + n + 1;
+            mx.load(X + base + (size_t)t * CT * D);
+            my.load(Y + base + (size_t)t * CT * D);
+        }
+        const float lamC = pw[CT];
+        typename E::frag yf[NKS];
+#pragma unroll
+        for (int ks = 0; ks < NKS; ++ks) {
+            yf[ks] = E::ld_ks(sY, LDD, ks * E::KSTEP, 32 * w);
+            yf[ks] = E::scale(yf[ks], ks * E::KSTEP, [&](int k) { return BWD ? pw[k + 1] : pw[CT - 1 - k]; });
+        }
+#pragma unroll
+        for (int ab = 0; ab < DB; ++ab) {
+            f32x16 acc = st[ab] * lamC;
+#pragma unroll
+            for (int ks = 0; ks < NKS; ++ks) acc = E::mfma(E::ld_ks(sX, LDD, ks * E::KSTEP, 32 * ab), yf[ks], acc);
+            st[ab] = acc;
+        }
+    }
+    state_store<D>(st, scratch + ((size_t)chain * nseg + seg) * D * D, w);
+}
+
+// ---------------------------------------------------------------------------
+// k_scan: per state element, scan over the segments of a head.
+//   forward : start_0 = kv_in (or 0); start_{j+1} = lambda^(len_j) start_j + local_j
+//   backward: recv_{S-1} = dkv_out (or 0); recv_{j-1} = lambda^(len_j) recv_j + local_j
+// scratch[chain][j] holds local_j on entry and start_j / recv_j on exit.
+// ---------------------------------------------------------------------------
+template <bool BWD>
+__global__ void k_scan(float *__restrict__ scratch, const float *__restrict__ boundary,
+                       const float *__restrict__ decay, int H, int DD, int nseg, int tiles_per_seg,
+                       int ntiles, int tile) {
+    const int chain = blockIdx.y;
+    const int e = blockIdx.x * blockDim.x + threadIdx.x;
+    if (e >= DD) return;
+    const double l2 = log2((double)decay[chain % H]);
+    float carry = boundary ? boundary[(size_t)chain * DD + e] : 0.0f;
+    float *s = scratch + (size_t)chain * nseg * DD + e;
+    for (int n = 0; n < nseg; ++n) {
+        const int j = BWD ? nseg - 1 - n : n;
+        const int len = (min((j + 1) * tiles_per_seg, ntiles) - j * tiles_per_seg) * tile;
+        const bool has_local = BWD ? (j > 0) : (j < nseg - 1);
+        const float local = has_local ? s[(size_t)j * DD] : 0.0f;
+        s[(size_t)j * DD] = carry;
+        carry = (float)exp2((double)len * l2) * carry + local;
+    }
+}
+
+// ---------------------------------------------------------------------------
+// k_fwd: one segment of one head, tiles ascending (Alg. 2 per tile):
+//   P      = (Q K^T) (.) M                       masked scores, via LDS
+//   O      = P V + Lambda (Q KV_{t-1})           intra + inter
+//   KV_t   = lambda^CT KV_{t-1} + (lambda^CT Lambda^-1 K)^T V
+// The state KV_{t-1} each tile starts from is optionally written to the cache.
+// ---------------------------------------------------------------------------
+template <typename T, int CT, int D>
+__global__ __launch_bounds__(D * 2) void k_fwd(const T *__restrict__ Q, const T *__restrict__ K,
+                                                const T *__restrict__ V, const float *__restrict__ decay,
+                                                T *__restrict__ O, float *__restrict__ kv_out,
+                                                T *__restrict__ cache, const float *__restrict__ scratch,
+                                                int H, int ntiles, int nseg, int tiles_per_seg) {
+    using E = Elem<T>;
+    constexpr int NT = D * 2, LDD = D + E::PAD, LDP = CT + E::PAD, DB = D / 32, NB = CT / 32, NKS = CT / E::KSTEP;
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    T *sQ = (T *)smem;
+    T *sK = sQ + CT * LDD;
+    T *sV = sK + CT * LDD;
+    T *sP = sV + CT * LDD;
+    float *pw = (float *)(sP + CT * LDP);
+
+    const int chain = blockIdx.y, seg = blockIdx.x;
+    const int t0 = seg * tiles_per_seg;
+    const int t1 = min(t0 + tiles_per_seg, ntiles);
+    const int w = threadIdx.x >> 6;
+    const float lam = decay[chain % H];
+    fill_pow_table<CT>(pw, lam);
+
+    const size_t base = (size_t)chain * ntiles * CT * D;
+    f32x16 st[DB];
+    state_load<D>(st, scratch + ((size_t)chain * nseg + seg) * D * D, w);
+
+    TileMover<T, CT, D, NT> mq, mk, mv;
+    mq.load(Q + base + (size_t)t0 * CT * D);
+    mk.load(K + base + (size_t)t0 * CT * D);
+    mv.load(V + base + (size_t)t0 * CT * D);
+
+    for (int t = t0; t < t1; ++t) {
+        __syncthreads();
+        mq.store(sQ, LDD);
+        mk.store(sK, LDD);
+        mv.store(sV, LDD);
+        __syncthreads();
+        if (t + 1 < t1) {
+            mq.load(Q + base + (size_t)(t + 1) * CT * D);
+            mk.load(K + base + (size_t)(t + 1) * CT * D);
+            mv.load(V + base + (size_t)(t + 1) * CT * D);
+        }
+        // masked scores P (all waves share the lower-triangular blocks)
+        masked_scores<T, CT, D, LDD, LDP>(sP, sK, sQ, pw, w);
+
+        // state as MFMA operand, and into the cache as KV_{t-1}
+        typename E::frag sf[DB][E::NSUB];
+#pragma unroll
+        for (int ab = 0; ab < DB; ++ab)
+#pragma unroll
+            for (int m = 0; m < E::NSUB; ++m) sf[ab][m] = E::from_acc(st[ab], m);
+        if (cache) {
+            T *c = cache + ((size_t)chain * ntiles + t) * D * D;
+#pragma unroll
+            for (int ab = 0; ab < DB; ++ab)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) E::st1(c + (32 * ab + acc_row(i)) * D + 32 * w + lane_r(), st[ab][i]);
+        }
+        typename E::frag vf[NKS];
+#pragma unroll
+        for (int ks = 0; ks < NKS; ++ks) vf[ks] = E::ld_ks(sV, LDD, ks * E::KSTEP, 32 * w);
+        __syncthreads();  // P visible
+
+        T *o = O + base + (size_t)t * CT * D;
+#pragma unroll
+        for (int ib = 0; ib < NB; ++ib) {
+            f32x16 acc = {0};
+            // inter: Q KV_{t-1}, contraction over the key feature a in accumulator order
+#pragma unroll
+            for (int ab = 0; ab < DB; ++ab)
+#pragma unroll
+                for (int m = 0; m < E::NSUB; ++m) acc = E::mfma(E::ld_kp(sQ, LDD, 32 * ib, 32 * ab, m), sf[ab][m], acc);
+            // Lambda: row r (1-based) carries lambda^r
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[i] *= pw[32 * ib + acc_row(i) + 1];
+            // intra: P V over the keys j <= i
+#pragma unroll
+            for (int ks = 0; ks < (ib + 1) * (32 / E::KSTEP); ++ks)
+                acc = E::mfma(E::ld_kc(sP, LDP, 32 * ib, ks * E::KSTEP), vf[ks], acc);
+            store_out_tile<T, D>(o, acc, 32 * ib, w);
+        }
+        // state update with K rows weighted lambda^(CT-1-j) (applied to the V fragments)
+        const float lamC = pw[CT];
+#pragma unroll
+        for (int ks = 0; ks < NKS; ++ks)
+            vf[ks] = E::scale(vf[ks], ks * E::KSTEP, [&](int k) { return pw[CT - 1 - k]; });
+#pragma unroll
+        for (int ab = 0; ab < DB; ++ab) {
+            f32x16 acc = st[ab] * lamC;
+#pragma unroll
+            for (int ks = 0; ks < NKS; ++ks) acc = E::mfma(E::ld_ks(sK, LDD, ks * E::KSTEP, 32 * ab), vf[ks], acc);
+            st[ab] = acc;
+        }
+    }
+    if (seg == nseg - 1) state_store<D>(st, kv_out + (size_t)chain * D * D, w);
+}
+
+// ---------------------------------------------------------------------------
+// k_bwd: one segment of one head, tiles descending (Alg. 3 per tile):
+//   dSm = (dO V^T) (.) M,  Sm = (Q K^T) (.) M
+//   dQ  = dSm K + Lambda (dO KV_{t-1}^T)
+//   dK  = dSm^T Q + (lambda^CT Lambda^-1) (V dKV^T)
+//   dV  = Sm^T dO + (lambda^CT Lambda^-1) (K dKV)
+//   dKV <- lambda^CT dKV + (Lambda Q)^T dO
+// dKV is the state received from the right (gradient w.r.t. KV_t). The wave
+// keeps its column block dKV[:, c in w] in registers, which serves dV directly;
+// dK needs the transposed block, fetched once per tile through an LDS exchange.
+// LDS is time-shared: first {V, dO}, then {K, Q}.
+// ---------------------------------------------------------------------------
+template <typename T, int CT, int D>
+struct BwdSmem {
+    using E = Elem<T>;
+    static constexpr int LDD = D + E::PAD, LDP = CT + E::PAD;
+    static constexpr size_t IN_BYTES = 2 * (size_t)CT * LDD * sizeof(T);   // two input tiles
+    static constexpr size_t X_BYTES = (size_t)D * LDD * sizeof(T);         // exchange buffer
+    static constexpr bool OVERLAY = X_BYTES <= IN_BYTES;                    // exchange reuses the input tiles
+    static constexpr size_t P_OFF = IN_BYTES + (OVERLAY ? 0 : X_BYTES);
+    static constexpr size_t PW_OFF = P_OFF + 2 * (size_t)CT * LDP * sizeof(T);
+    static constexpr size_t TOTAL = PW_OFF + (CT + 1) * sizeof(float);
+};
+
+template <typename T, int CT, int D>
+__global__ __launch_bounds__(D * 2) void k_bwd(const T *__restrict__ Q, const T *__restrict__ K,
+                                                const T *__restrict__ V, const T *__restrict__ dO,
+                                                const float *__restrict__ decay, const T *__restrict__ cache,
+                                                T *__restrict__ dQ, T *__restrict__ dK, T *__restrict__ dV,
+                                                float *__restrict__ dkv_in, const float *__restrict__ scratch,
+                                                int H, int ntiles, int nseg, int tiles_per_seg) {
+    using E = Elem<T>;
+    using SM = BwdSmem<T, CT, D>;
+    constexpr int NT = D * 2, LDD = SM::LDD, LDP = SM::LDP, DB = D / 32, NB = CT / 32, NKS = CT / E::KSTEP,
+                  NKD = D / E::KSTEP, SPB = 32 / E::KSTEP;
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    T *bufA = (T *)smem;
+    T *bufB = bufA + CT * LDD;
+    T *sX = SM::OVERLAY ? bufA : (T *)(smem + SM::IN_BYTES);
+    T *sS = (T *)(smem + SM::P_OFF);
+    T *sDS = sS + CT * LDP;
+    float *pw = (float *)(smem + SM::PW_OFF);
+
+    const int chain = blockIdx.y, seg = blockIdx.x;
+    const int t0 = seg * tiles_per_seg;
+    const int t1 = min(t0 + tiles_per_seg, ntiles);
+    const int w = threadIdx.x >> 6;
+    const float lam = decay[chain % H];
+    fill_pow_table<CT>(pw, lam);
+
+    const size_t base = (size_t)chain * ntiles * CT * D;
+    f32x16 dkv[DB];
+    state_load<D>(dkv, scratch + ((size_t)chain * nseg + seg) * D * D, w);
+
+    TileMover<T, CT, D, NT> ma, mb;
+    ma.load(V + base + (size_t)(t1 - 1) * CT * D);
+    mb.load(dO + base + (size_t)(t1 - 1) * CT * D);
+
+    for (int t = t1 - 1; t >= t0; --t) {
+        const size_t off = base + (size_t)t * CT * D;
+        // ---- exchange: dKV^T fragments for dK_inter (B[k = c][n = a in w]) ----
+        __syncthreads();
+#pragma unroll
+        for (int ab = 0; ab < DB; ++ab)
+#pragma unroll
+            for (int g = 0; g < 4; ++g)
+                E::st4(sX + (32 * w + lane_r()) * LDD + 32 * ab + 8 * g + 4 * lane_h(), dkv[ab][4 * g], dkv[ab][4 * g + 1],
+                       dkv[ab][4 * g + 2], dkv[ab][4 * g + 3]);
+        __syncthreads();
+        typename E::frag xf[NKD];
+#pragma unroll
+        for (int ks = 0; ks < NKD; ++ks) xf[ks] = E::ld_ks(sX, LDD, ks * E::KSTEP, 32 * w);
+        __syncthreads();
+
+        // ---- step 1: V (bufA), dO (bufB) ----
+        ma.store(bufA, LDD);
+        mb.store(bufB, LDD);
+        __syncthreads();
+        ma.load(K + off);
+        mb.load(Q + off);
+
+        masked_scores<T, CT, D, LDD, LDP>(sDS, bufA, bufB, pw, w);  // dS^T = V dO^T
+
+        f32x16 accQ[NB], accK[NB];
+#pragma unroll
+        for (int b = 0; b < NB; ++b) accQ[b] = accK[b] = f32x16{0};
+        // dQ_inter = Lambda (dO KV_{t-1}^T): B[k = c][n = a] = KV[a][c], read from the cache in place
+        {
+            const T *c = cache + ((size_t)chain * ntiles + t) * D * D;
+#pragma unroll
+            for (int ks = 0; ks < NKD; ++ks) {
+                typename E::frag b = E::ld_kc(c, D, 32 * w, ks * E::KSTEP);
+#pragma unroll
+                for (int ib = 0; ib < NB; ++ib) accQ[ib] = E::mfma(E::ld_kc(bufB, LDD, 32 * ib, ks * E::KSTEP), b, accQ[ib]);
+            }
+#pragma unroll
+            for (int ib = 0; ib < NB; ++ib)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) accQ[ib][i] *= pw[32 * ib + acc_row(i) + 1];
+        }
+        // dK_inter = (lambda^CT Lambda^-1) (V dKV^T)
+#pragma unroll
+        for (int ks = 0; ks < NKD; ++ks)
+#pragma unroll
+            for (int jb = 0; jb < NB; ++jb) accK[jb] = E::mfma(E::ld_kc(bufA, LDD, 32 * jb, ks * E::KSTEP), xf[ks], accK[jb]);
+#pragma unroll
+        for (int jb = 0; jb < NB; ++jb)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) accK[jb][i] *= pw[CT - 1 - (32 * jb + acc_row(i))];
+        // dO fragments of this wave's column block: B[k = i][n = c in w]
+        typename E::frag dof[NKS];
+#pragma unroll
+        for (int ks = 0; ks < NKS; ++ks) dof[ks] = E::ld_ks(bufB, LDD, ks * E::KSTEP, 32 * w);
+
+        // ---- step 2: K (bufA), Q (bufB) ----
+        __syncthreads();
+        ma.store(bufA, LDD);
+        mb.store(bufB, LDD);
+        __syncthreads();
+        if (t > t0) {
+            ma.load(V + off - (size_t)CT * D);
+            mb.load(dO + off - (size_t)CT * D);
+        }
+        masked_scores<T, CT, D, LDD, LDP>(sS, bufA, bufB, pw, w);  // S^T = K Q^T
+        __syncthreads();
+
+        // dQ = dQ_inter + dSm K
+#pragma unroll
+        for (int ks = 0; ks < NKS; ++ks) {
+            typename E::frag b = E::ld_ks(bufA, LDD, ks * E::KSTEP, 32 * w);
+#pragma unroll
+            for (int ib = ks / SPB; ib < NB; ++ib) accQ[ib] = E::mfma(E::ld_kc(sDS, LDP, 32 * ib, ks * E::KSTEP), b, accQ[ib]);
+        }
+#pragma unroll
+        for (int ib = 0; ib < NB; ++ib) store_out_tile<T, D>(dQ + off, accQ[ib], 32 * ib, w);
+        // dK = dK_inter + dSm^T Q
+#pragma unroll
+        for (int ks = 0; ks < NKS; ++ks) {
+            typename E::frag b = E::ld_ks(bufB, LDD, ks * E::KSTEP, 32 * w);
+#pragma unroll
+            for (int jb = 0; jb <= ks / SPB; ++jb) accK[jb] = E::mfma(E::ld_ks(sDS, LDP, ks * E::KSTEP, 32 * jb), b, accK[jb]);
+        }
+#pragma unroll
+        for (int jb = 0; jb < NB; ++jb) store_out_tile<T, D>(dK + off, accK[jb], 32 * jb, w);
+        // dV = (lambda^CT Lambda^-1) (K dKV) + Sm^T dO
+        {
+            typename E::frag df[DB][E::NSUB];
+#pragma unroll
+            for (int ab = 0; ab < DB; ++ab)
+#pragma unroll
+                for (int m = 0; m < E::NSUB; ++m) df[ab][m] = E::from_acc(dkv[ab], m);
+#pragma unroll
+            for (int jb = 0; jb < NB; ++jb) {
+                f32x16 acc = {0};
+#pragma unroll
+                for (int ab = 0; ab < DB; ++ab)
+#pragma unroll
+                    for (int m = 0; m < E::NSUB; ++m) acc = E::mfma(E::ld_kp(bufA, LDD, 32 * jb, 32 * ab, m), df[ab][m], acc);
+#pragma unroll
+                for (int i = 0; i < 16; ++i) acc[i] *= pw[CT - 1 - (32 * jb + acc_row(i))];
+#pragma unroll
+                for (int ks = jb * SPB; ks < NKS; ++ks) acc = E::mfma(E::ld_ks(sS, LDP, ks * E::KSTEP, 32 * jb), dof[ks], acc);
+                store_out_tile<T, D>(dV + off, acc, 32 * jb, w);
+            }
+        }
+        // dKV <- lambda^CT dKV + (Lambda Q)^T dO  (row weight lambda^(i+1) applied to the dO fragments)
+        const float lamC = pw[CT];
+#pragma unroll
+        for (int ks = 0; ks < NKS; ++ks) dof[ks] = E::scale(dof[ks], ks * E::KSTEP, [&](int k) { return pw[k + 1]; });
+#pragma unroll
+        for (int ab = 0; ab < DB; ++ab) {
+            f32x16 acc = dkv[ab] * lamC;
+#pragma unroll
+            for (int ks = 0; ks < NKS; ++ks) acc = E::mfma(E::ld_ks(bufB, LDD, ks * E::KSTEP, 32 * ab), dof[ks], acc);
+            dkv[ab] = acc;
+        }
+    }
+    if (seg == 0) state_store<D>(dkv, dkv_in + (size_t)chain * D * D, w);
+}
+
+// ---------------------------------------------------------------------------
+// Host-side launchers
+// ---------------------------------------------------------------------------
+template <typename T, int CT, int D>
+struct Smem {
+    using E = Elem<T>;
+    static constexpr size_t local = 2 * (size_t)CT * (D + E::PAD) * sizeof(T) + (CT + 1) * sizeof(float);
+    static constexpr size_t fwd = (3 * (size_t)CT * (D + E::PAD) + (size_t)CT * (CT + E::PAD)) * sizeof(T) + (CT + 1) * sizeof(float);
+    static constexpr size_t bwd = BwdSmem<T, CT, D>::TOTAL;
+    static_assert(fwd <= 163840 && bwd <= 163840, "LDS budget of one gfx950 CU exceeded");
+};
+
+template <typename F>
+static hipError_t allow_lds(F kernel, size_t bytes) {
+    return hipFuncSetAttribute((const void *)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+}
+
+template <typename T, int CT, int D>
+static hipError_t run_fwd(const Plan &p, const FwdArgs &a, hipStream_t s) {
+    const int chains = p.B * p.H, DD = D * D;
+    constexpr size_t lds_local = Smem<T, CT, D>::local, lds_fwd = Smem<T, CT, D>::fwd;
+    hipError_t e;
+    if (p.nseg > 1) {
+        auto kl = k_local<T, CT, D, false>;
+        if ((e = allow_lds(kl, lds_local)) != hipSuccess) return e;
+        kl<<<dim3(p.nseg - 1, chains), dim3(D * 2), lds_local, s>>>((const T *)a.k, (const T *)a.v, a.decay, a.scratch,
+                                                                   p.H, p.ntiles, p.nseg, p.tiles_per_seg);
+    }
+    k_scan<false><<<dim3((DD + 255) / 256, chains), dim3(256), 0, s>>>(a.scratch, a.kv_in, a.decay, p.H, DD, p.nseg,
+                                                                       p.tiles_per_seg, p.ntiles, p.tile);
+    auto kf = k_fwd<T, CT, D>;
+    if ((e = allow_lds(kf, lds_fwd)) != hipSuccess) return e;
+    kf<<<dim3(p.nseg, chains), dim3(D * 2), lds_fwd, s>>>((const T *)a.q, (const T *)a.k, (const T *)a.v, a.decay,
+                                                         (T *)a.out, a.kv_out, (T *)a.cache, (const float *)a.scratch,
+                                                         p.H, p.ntiles, p.nseg, p.tiles_per_seg);
+    return hipGetLastError();
+}
+
+template <typename T, int CT, int D>
+static hipError_t run_bwd(const Plan &p, const BwdArgs &a, hipStream_t s) {
+    const int chains = p.B * p.H, DD = D * D;
+    constexpr size_t lds_local = Smem<T, CT, D>::local, lds_bwd = Smem<T, CT, D>::bwd;
+    hipError_t e;
+    if (p.nseg > 1) {
+        auto kl = k_local<T, CT, D, true>;
+        if ((e = allow_lds(kl, lds_local)) != hipSuccess) return e;
+        kl<<<dim3(p.nseg - 1, chains), dim3(D * 2), lds_local, s>>>((const T *)a.q, (const T *)a.dout, a.decay,
+                                                                   a.scratch, p.H, p.ntiles, p.nseg, p.tiles_per_seg);
+    }
+    k_scan<true><<<dim3((DD + 255) / 256, chains), dim3(256), 0, s>>>(a.scratch, a.dkv_out, a.decay, p.H, DD, p.nseg,
+                                                                      p.tiles_per_seg, p.ntiles, p.tile);
+    auto kb = k_bwd<T, CT, D>;
+    if ((e = allow_lds(kb, lds_bwd)) != hipSuccess) return e;
+    kb<<<dim3(p.nseg, chains), dim3(D * 2), lds_bwd, s>>>((const T *)a.q, (const T *)a.k, (const T *)a.v,
+                                                         (const T *)a.dout, a.decay, (const T *)a.cache, (T *)a.dq,
+                                                         (T *)a.dk, (T *)a.dv, a.dkv_in, (const float *)a.scratch, p.H,
+                                                         p.ntiles, p.nseg, p.tiles_per_seg);
+    return hipGetLastError();
+}
+
+int tile_tokens(int dtype, int chunk, int D) {
+    (void)D;
+    if (dtype == 0) return 32;          // float tiles: 32 tokens
+    return chunk >= 128 ? 128 : 64;     // bfloat16 tiles: 128 tokens (64 when the chunk is 64)
+}
+
+#define LASP_DISPATCH(FN, ARGS)                                                        \
+    if (p.dtype == 0) {                                                                \
+        if (p.D == 64) return FN<float, 32, 64>(p, ARGS, stream);                      \
+        return FN<float, 32, 128>(p, ARGS, stream);                                    \
+    }                                                                                  \
+    if (p.tile == 64) {                                                                \
+        if (p.D == 64) return FN<bf16_t, 64, 64>(p, ARGS, stream);                     \
+        return FN<bf16_t, 64, 128>(p, ARGS, stream);                                   \
+    }                                                                                  \
+    if (p.D == 64) return FN<bf16_t, 128, 64>(p, ARGS, stream);                        \
+    return FN<bf16_t, 128, 128>(p, ARGS, stream);
+
+hipError_t launch_fwd(const Plan &p, const FwdArgs &a, hipStream_t stream) { LASP_DISPATCH(run_fwd, a) }
+hipError_t launch_bwd(const Plan &p, const BwdArgs &a, hipStream_t stream) { LASP_DISPATCH(run_bwd, a) }
+
+}  // namespace lasp

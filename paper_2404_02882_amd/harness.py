@@ -1,0 +1,65 @@
+"""Host-side helpers shared by the GPU tests, the smoke check and bench.py:
+upload seeded inputs, run the T-loop through the C-ABI, fetch results.
+No attention arithmetic happens here."""
+from __future__ import annotations
+
+from typing import Dict, Optional
+
+import numpy as np
+import torch
+
+from . import lasp
+from .sequence import LaspSequence
+from .synth_inputs import Inputs, bf16_bits
+
+TORCH_DTYPE = {"f32": torch.float32, "bf16": torch.bfloat16}
+
+
+def to_device(x: np.ndarray, dtype: str, device="cuda") -> torch.Tensor:
+    """Upload values already representable in `dtype` without any further rounding."""
+    if dtype == "f32":
+        return torch.from_numpy(np.ascontiguousarray(x, dtype=np.float32)).to(device)
+    bits = bf16_bits(x)  # exact: x is already a bf16 value
+    return torch.from_numpy(bits.view(np.int16)).to(device).view(torch.bfloat16)
+
+
+def shards(x: np.ndarray, T: int, dtype: str, device="cuda"):
+    n = x.shape[2] // T
+    return [to_device(x[:, :, t * n:(t + 1) * n], dtype, device) for t in range(T)]
+
+
+def to_host(ts) -> np.ndarray:
+    return np.concatenate([t.float().cpu().numpy().astype(np.float64) for t in ts], axis=2)
+
+
+def rel_errors(x: np.ndarray, ref: np.ndarray):
+    """(max|x-ref| / max|ref|, ||x-ref||_F / ||ref||_F)."""
+    x = np.asarray(x, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    d = x - ref
+    return (float(np.max(np.abs(d)) / max(np.max(np.abs(ref)), 1e-300)),
+            float(np.linalg.norm(d.ravel()) / max(np.linalg.norm(ref.ravel()), 1e-300)))
+
+
+def run_gpu(inp: Inputs, T: int = 1, segments: int = 0, backward: bool = True, chunk: Optional[int] = None,
+            device="cuda") -> Dict[str, np.ndarray]:
+    """Forward (and backward) of the whole sequence as T sub-sequences; returns float64 host arrays."""
+    cfg = inp.cfg
+    B, H, N, D = inp.q.shape
+    dt = TORCH_DTYPE[cfg.dtype]
+    seq = LaspSequence(B, H, N, D, chunk or cfg.chunk, dt, T=T, segments=segments, device=device,
+                       need_backward=backward)
+    q, k, v = (shards(x, T, cfg.dtype, device) for x in (inp.q, inp.k, inp.v))
+    decay = torch.from_numpy(inp.decay).to(device)
+    kv_in = torch.from_numpy(inp.kv_in).to(device) if inp.kv_in is not None else None
+    out = [torch.full_like(x, float("nan")) for x in q]
+    kv_out = seq.forward(q, k, v, decay, out, kv_in)
+    res = {"out": to_host(out), "kv_out": kv_out.cpu().numpy().astype(np.float64)}
+    if backward:
+        do = shards(inp.dout, T, cfg.dtype, device)
+        g = torch.from_numpy(inp.dkv_out).to(device) if inp.dkv_out is not None else None
+        dq, dk, dv = ([torch.full_like(x, float("nan")) for x in q] for _ in range(3))
+        dkv_in = seq.backward(q, k, v, do, decay, dq, dk, dv, g)
+        res.update(dq=to_host(dq), dk=to_host(dk), dv=to_host(dv), dkv_in=dkv_in.cpu().numpy().astype(np.float64))
+    torch.cuda.synchronize()
+    return res

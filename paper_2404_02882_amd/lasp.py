@@ -1,0 +1,143 @@
+"""Thin ctypes binding over the C-ABI library (include/lasp.h).
+
+Argument marshalling only: every step of the path runs in the HIP kernels.
+PyTorch supplies device memory and the current stream. If the shared library
+has not been built, importing this module raises: there is no CPU fallback.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "liblasp.so")
+
+LASP_F32, LASP_BF16 = 0, 1
+STATUS_NAMES = {0: "LASP_OK", 1: "LASP_ERR_NULL", 2: "LASP_ERR_SHAPE", 3: "LASP_ERR_DTYPE", 4: "LASP_ERR_DECAY",
+                5: "LASP_ERR_WORKSPACE", 6: "LASP_ERR_ALIAS", 7: "LASP_ERR_HIP"}
+
+
+class Shape(ctypes.Structure):
+    _fields_ = [("B", ctypes.c_int32), ("H", ctypes.c_int32), ("N", ctypes.c_int32), ("D", ctypes.c_int32),
+                ("chunk", ctypes.c_int32), ("dtype", ctypes.c_int32), ("segments", ctypes.c_int32)]
+
+
+class LaspError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {STATUS_NAMES.get(status, status)} ({status_str(status)})")
+
+
+if not os.path.exists(LIB_PATH):
+    raise ImportError(f"{LIB_PATH} is missing: build it first (python -c 'import __graft_entry__ as g; g.build()'). "
+                      "There is no fallback path.")
+
+lib = ctypes.CDLL(LIB_PATH)
+_vp, _sz = ctypes.c_void_p, ctypes.c_size_t
+_sp = ctypes.POINTER(Shape)
+lib.lasp_version.restype = ctypes.c_int
+lib.lasp_status_str.restype = ctypes.c_char_p
+lib.lasp_status_str.argtypes = [ctypes.c_int]
+lib.lasp_check_shape.argtypes = [_sp]
+lib.lasp_check_decay.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_int32]
+lib.lasp_tile_tokens.argtypes = [_sp]
+lib.lasp_tile_tokens.restype = ctypes.c_int32
+lib.lasp_num_segments.argtypes = [_sp]
+lib.lasp_num_segments.restype = ctypes.c_int32
+lib.lasp_state_cache_bytes.argtypes = [_sp]
+lib.lasp_state_cache_bytes.restype = _sz
+lib.lasp_scratch_bytes.argtypes = [_sp]
+lib.lasp_scratch_bytes.restype = _sz
+lib.lasp_fwd.argtypes = [_sp] + [_vp] * 9 + [_sz, _vp]
+lib.lasp_fwd.restype = ctypes.c_int
+lib.lasp_bwd.argtypes = [_sp] + [_vp] * 12 + [_sz, _vp]
+lib.lasp_bwd.restype = ctypes.c_int
+
+
+def status_str(status: int) -> str:
+    return lib.lasp_status_str(int(status)).decode()
+
+
+def version() -> int:
+    return int(lib.lasp_version())
+
+
+def make_shape(B, H, N, D, chunk, dtype, segments=0) -> Shape:
+    if isinstance(dtype, torch.dtype):
+        dtype = {torch.float32: LASP_F32, torch.bfloat16: LASP_BF16}.get(dtype, -1)
+    elif isinstance(dtype, str):
+        dtype = {"f32": LASP_F32, "bf16": LASP_BF16}.get(dtype, -1)
+    return Shape(int(B), int(H), int(N), int(D), int(chunk), int(dtype), int(segments))
+
+
+def check_shape(shape: Shape) -> int:
+    return int(lib.lasp_check_shape(ctypes.byref(shape)))
+
+
+def check_decay(decay_host) -> int:
+    arr = (ctypes.c_float * len(decay_host))(*[float(x) for x in decay_host])
+    return int(lib.lasp_check_decay(arr, len(decay_host)))
+
+
+def tile_tokens(shape: Shape) -> int:
+    return int(lib.lasp_tile_tokens(ctypes.byref(shape)))
+
+
+def num_segments(shape: Shape) -> int:
+    return int(lib.lasp_num_segments(ctypes.byref(shape)))
+
+
+def state_cache_bytes(shape: Shape) -> int:
+    return int(lib.lasp_state_cache_bytes(ctypes.byref(shape)))
+
+
+def scratch_bytes(shape: Shape) -> int:
+    return int(lib.lasp_scratch_bytes(ctypes.byref(shape)))
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    if t is None:
+        return None
+    if not t.is_contiguous():
+        raise ValueError("tensors handed to the library must be contiguous")
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _stream(stream):
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return ctypes.c_void_p(stream.cuda_stream)
+
+
+def lasp_fwd(shape: Shape, q, k, v, kv_in, decay, out, kv_out, state_cache, scratch, stream=None) -> None:
+    """Enqueue the forward pass; raises LaspError on a non-zero status."""
+    nbytes = scratch.numel() * scratch.element_size() if scratch is not None else 0
+    rc = lib.lasp_fwd(ctypes.byref(shape), _ptr(q), _ptr(k), _ptr(v), _ptr(kv_in), _ptr(decay), _ptr(out),
+                      _ptr(kv_out), _ptr(state_cache), _ptr(scratch), nbytes, _stream(stream))
+    if rc != 0:
+        raise LaspError(rc, "lasp_fwd")
+
+
+def lasp_bwd(shape: Shape, q, k, v, dout, dkv_out, decay, state_cache, dq, dk, dv, dkv_in, scratch,
+             stream=None) -> None:
+    """Enqueue the backward pass; raises LaspError on a non-zero status."""
+    nbytes = scratch.numel() * scratch.element_size() if scratch is not None else 0
+    rc = lib.lasp_bwd(ctypes.byref(shape), _ptr(q), _ptr(k), _ptr(v), _ptr(dout), _ptr(dkv_out), _ptr(decay),
+                      _ptr(state_cache), _ptr(dq), _ptr(dk), _ptr(dv), _ptr(dkv_in), _ptr(scratch), nbytes,
+                      _stream(stream))
+    if rc != 0:
+        raise LaspError(rc, "lasp_bwd")
+
+
+class Workspace:
+    """Device buffers one (shape) needs besides the tensors: per-tile state cache and scratch."""
+
+    def __init__(self, shape: Shape, device="cuda", with_cache=True):
+        self.shape = shape
+        if check_shape(shape) != 0:
+            raise LaspError(check_shape(shape), "Workspace")
+        self.cache = torch.empty(state_cache_bytes(shape), dtype=torch.uint8, device=device) if with_cache else None
+        self.scratch = torch.empty(scratch_bytes(shape), dtype=torch.uint8, device=device)

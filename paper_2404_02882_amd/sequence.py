@@ -1,0 +1,63 @@
+"""Outer loop over sub-sequences: the paper's ring of ranks on one GPU.
+
+A sequence of N tokens is held as T shards of N/T tokens, each a contiguous
+[B,H,N/T,D] tensor (what one rank of the paper holds). Forward runs the shards
+in order and hands kv_out of one to the next as kv_in (Alg. 2: Recv KV from
+rank i-1, Send KV to rank i+1); backward runs them in reverse and hands dkv_in
+of one to the previous as dkv_out (Alg. 3). Every shard keeps the per-tile
+state cache its forward call filled until its backward call has used it.
+All buffers are allocated once, up front; the calls only enqueue kernels.
+"""
+from __future__ import annotations
+
+from typing import List, Optional
+
+import torch
+
+from . import lasp
+
+
+class LaspSequence:
+    def __init__(self, B, H, N, D, chunk, dtype: torch.dtype, T=1, segments=0, device="cuda", need_backward=True):
+        if N % T != 0:
+            raise ValueError("N must be a multiple of T")
+        self.B, self.H, self.N, self.D, self.T = B, H, N, D, T
+        self.n_sub = N // T
+        self.dtype = dtype
+        self.shape = lasp.make_shape(B, H, self.n_sub, D, chunk, dtype, segments)
+        rc = lasp.check_shape(self.shape)
+        if rc != 0:
+            raise lasp.LaspError(rc, "LaspSequence")
+        self.scratch = torch.empty(lasp.scratch_bytes(self.shape), dtype=torch.uint8, device=device)
+        self.caches = [torch.empty(lasp.state_cache_bytes(self.shape), dtype=torch.uint8, device=device)
+                       for _ in range(T)] if need_backward else [None] * T
+        st = dict(dtype=torch.float32, device=device)
+        # kv[t] = state entering shard t (kv[T] = final); dkv[t] = gradient w.r.t. kv[t]
+        self.kv = [torch.zeros(B, H, D, D, **st) for _ in range(T + 1)]
+        self.dkv = [torch.zeros(B, H, D, D, **st) for _ in range(T + 1)] if need_backward else None
+        self.has_kv_in = False
+        self.has_dkv_out = False
+
+    def cache_bytes(self) -> int:
+        return sum(c.numel() for c in self.caches if c is not None)
+
+    def forward(self, q: List[torch.Tensor], k, v, decay, out: List[torch.Tensor],
+                kv_in: Optional[torch.Tensor] = None) -> torch.Tensor:
+        self.has_kv_in = kv_in is not None
+        if kv_in is not None:
+            self.kv[0].copy_(kv_in)
+        for t in range(self.T):
+            first = None if (t == 0 and not self.has_kv_in) else self.kv[t]
+            lasp.lasp_fwd(self.shape, q[t], k[t], v[t], first, decay, out[t], self.kv[t + 1], self.caches[t],
+                          self.scratch)
+        return self.kv[self.T]
+
+    def backward(self, q, k, v, dout, decay, dq, dk, dv, dkv_out: Optional[torch.Tensor] = None) -> torch.Tensor:
+        self.has_dkv_out = dkv_out is not None
+        if dkv_out is not None:
+            self.dkv[self.T].copy_(dkv_out)
+        for t in reversed(range(self.T)):
+            last = None if (t == self.T - 1 and not self.has_dkv_out) else self.dkv[t + 1]
+            lasp.lasp_bwd(self.shape, q[t], k[t], v[t], dout[t], last, decay, self.caches[t], dq[t], dk[t], dv[t],
+                          self.dkv[t], self.scratch)
+        return self.dkv[0]

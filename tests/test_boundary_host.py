@@ -1,0 +1,119 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports
+every symbol include/lasp.h declares, and rejects bad arguments before any
+launch (no compute call is made here)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def L():
+    from paper_2404_02882_amd import lasp
+    return lasp
+
+
+def test_exports_every_declared_symbol(L):
+    text = open(os.path.join(ROOT, "include", "lasp.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    names = set(re.findall(r"\b(lasp_[a-z_]+)\s*\(", text))
+    assert {"lasp_fwd", "lasp_bwd", "lasp_scratch_bytes", "lasp_state_cache_bytes"} <= names
+    for n in names:
+        assert hasattr(L.lib, n), n
+    assert L.version() >= 1
+
+
+def test_status_strings(L):
+    for s in range(8):
+        assert L.status_str(s) and "unknown" not in L.status_str(s)
+    assert "unknown" in L.status_str(99)
+
+
+@pytest.mark.parametrize("kw,expect", [
+    (dict(), 0),
+    (dict(D=96), 2), (dict(D=256), 2), (dict(chunk=32), 2), (dict(chunk=512), 2),
+    (dict(N=1000), 2), (dict(N=0), 2), (dict(B=0), 2), (dict(H=-1), 2),
+    (dict(dtype=2), 3), (dict(dtype=-1), 3),
+    (dict(segments=-1), 2), (dict(segments=9), 2), (dict(segments=8), 0),
+])
+def test_check_shape(L, kw, expect):
+    base = dict(B=2, H=4, N=1024, D=128, chunk=128, dtype=1, segments=0)
+    base.update(kw)
+    assert L.check_shape(L.make_shape(**base)) == expect
+
+
+def test_sizes_and_plan(L):
+    s = L.make_shape(1, 16, 32768, 128, 128, "bf16")
+    assert L.tile_tokens(s) == 128
+    assert L.num_segments(s) == 32
+    assert L.state_cache_bytes(s) == 16 * 256 * 128 * 128 * 2
+    assert L.scratch_bytes(s) == 16 * 32 * 128 * 128 * 4
+    f = L.make_shape(1, 2, 256, 64, 64, "f32")
+    assert L.tile_tokens(f) == 32 and 64 % L.tile_tokens(f) == 0
+    assert L.state_cache_bytes(f) == 2 * 8 * 64 * 64 * 4
+    # a segment count that does not divide the tiles still covers them all
+    r = L.make_shape(1, 1, 64 * 7, 64, 64, "bf16", segments=3)
+    assert L.num_segments(r) == 3
+    bad = L.make_shape(1, 1, 100, 64, 64, "bf16")
+    assert L.tile_tokens(bad) == 0 and L.scratch_bytes(bad) == 0 and L.state_cache_bytes(bad) == 0
+
+
+def test_check_decay(L):
+    assert L.check_decay([1.0, 0.5, 0.999]) == 0
+    assert L.check_decay([0.0]) == 4
+    assert L.check_decay([1.0001]) == 4
+    assert L.check_decay([float("nan")]) == 4
+    assert L.check_decay([-0.5]) == 4
+
+
+def _fake(n):
+    """Distinct non-null addresses that are never dereferenced (validation fails first)."""
+    return ctypes.c_void_p(0x10000000 + n * 0x10000000)
+
+
+def test_fwd_rejects_before_launch(L):
+    s = L.make_shape(1, 1, 64, 64, 64, "bf16")
+    sb = L.scratch_bytes(s)
+    P = [_fake(i) for i in range(1, 10)]
+    q, k, v, kvin, dec, out, kvout, cache, scr = P
+    call = lambda *a: L.lib.lasp_fwd(*a)
+    assert call(None, q, k, v, kvin, dec, out, kvout, cache, scr, sb, None) == 1
+    assert call(ctypes.byref(s), None, k, v, kvin, dec, out, kvout, cache, scr, sb, None) == 1
+    assert call(ctypes.byref(s), q, k, v, kvin, None, out, kvout, cache, scr, sb, None) == 1
+    assert call(ctypes.byref(s), q, k, v, kvin, dec, None, kvout, cache, scr, sb, None) == 1
+    assert call(ctypes.byref(s), q, k, v, kvin, dec, out, None, cache, scr, sb, None) == 1
+    assert call(ctypes.byref(s), q, k, v, kvin, dec, out, kvout, cache, None, sb, None) == 5
+    assert call(ctypes.byref(s), q, k, v, kvin, dec, out, kvout, cache, scr, sb - 1, None) == 5
+    assert call(ctypes.byref(s), q, k, v, kvin, dec, q, kvout, cache, scr, sb, None) == 6      # out aliases q
+    assert call(ctypes.byref(s), q, k, v, kvin, dec, out, kvin, cache, scr, sb, None) == 6     # kv_out aliases kv_in
+    assert call(ctypes.byref(s), q, k, v, kvin, dec, out, kvout, out, scr, sb, None) == 6      # cache aliases out
+    bad = L.make_shape(1, 1, 65, 64, 64, "bf16")
+    assert call(ctypes.byref(bad), q, k, v, kvin, dec, out, kvout, cache, scr, sb, None) == 2
+    bad = L.make_shape(1, 1, 64, 64, 64, 7)
+    assert call(ctypes.byref(bad), q, k, v, kvin, dec, out, kvout, cache, scr, sb, None) == 3
+
+
+def test_bwd_rejects_before_launch(L):
+    s = L.make_shape(1, 1, 64, 64, 64, "f32")
+    sb = L.scratch_bytes(s)
+    P = [_fake(i) for i in range(1, 14)]
+    q, k, v, do, g, dec, cache, dq, dk, dv, gin, scr, _ = P
+    call = lambda *a: L.lib.lasp_bwd(*a)
+    ok_args = [ctypes.byref(s), q, k, v, do, g, dec, cache, dq, dk, dv, gin, scr, sb, None]
+    for idx in (1, 2, 3, 4, 6, 7, 8, 9, 10, 11):   # every required pointer
+        a = list(ok_args)
+        a[idx] = None
+        assert call(*a) == 1, idx
+    a = list(ok_args); a[12] = None
+    assert call(*a) == 5
+    a = list(ok_args); a[13] = 0
+    assert call(*a) == 5
+    a = list(ok_args); a[8] = q
+    assert call(*a) == 6
+    a = list(ok_args); a[9] = dq
+    assert call(*a) == 6
+    a = list(ok_args); a[11] = g
+    assert call(*a) == 6
