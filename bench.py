@@ -1,0 +1,138 @@
+#!/usr/bin/env python3
+"""Benchmark of the LASP hot path on one MI355X.
+
+One step = one forward + one backward pass of chunked causal linear attention
+over one batch of synthetic input already resident in HBM (config c3:
+bf16, B=1, H=16, N=32768, d=128, chunk=128). Prints ONE JSON line:
+tokens/s of the whole step, the roofline of the dominant kernel measured with
+HIP events inside the timed region, and the CPU oracle timed on a bounded
+sample of the same workload.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X published dense bf16 MFMA rate
+
+# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE /
+# WRITE_SIZE runs (profiles/), or None while not measured for this build.
+MEASURED_TRAFFIC_BYTES = {"fwd_walk": None, "bwd_walk": None}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--config", default="c3", help="named workload (c3 is the headline)")
+    ap.add_argument("--segments", type=int, default=0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample-tokens", type=int, default=8192)
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on one GPU only (the ring of ranks is a loop over sub-sequences on one "
+              "device); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2404_02882_amd import harness, lasp, synth_inputs as si
+    from paper_2404_02882_amd.sequence import LaspSequence
+
+    cfg = si.CONFIGS[args.config]
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    inp = si.make_inputs(cfg)
+    B, H, N, D, T = cfg.B, cfg.H, cfg.N, cfg.D, cfg.T
+    dt = harness.TORCH_DTYPE[cfg.dtype]
+    seq = LaspSequence(B, H, N, D, cfg.chunk, dt, T=T, segments=args.segments, device=dev)
+    q, k, v, do = (harness.shards(x, T, cfg.dtype, dev) for x in (inp.q, inp.k, inp.v, inp.dout))
+    decay = torch.from_numpy(inp.decay).to(dev)
+    out, dq, dk, dv = ([torch.empty_like(x) for x in q] for _ in range(4))
+    tile = lasp.tile_tokens(seq.shape)
+    nseg = lasp.num_segments(seq.shape)
+
+    def step():
+        seq.forward(q, k, v, decay, out)
+        seq.backward(q, k, v, do, decay, dq, dk, dv)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    lasp.profile_begin(args.steps * T)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    kernel_ms, nf, nb = lasp.profile_end()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    tokens_per_s = B * N / (ms_per_step * 1e-3)
+
+    # ---- roofline of the dominant kernel (largest share of the step) ----
+    tok_heads_per_launch = B * H * (N // T)
+    esz = 2 if cfg.dtype == "bf16" else 4
+    per_launch_ms = {"fwd_local": kernel_ms["fwd"][0] / nf, "fwd_scan": kernel_ms["fwd"][1] / nf,
+                     "fwd_walk": kernel_ms["fwd"][2] / nf, "bwd_local": kernel_ms["bwd"][0] / nb,
+                     "bwd_scan": kernel_ms["bwd"][1] / nb, "bwd_walk": kernel_ms["bwd"][2] / nb}
+    # algorithmic (compulsory) HBM bytes per token-head: forward walk reads q,k,v and
+    # writes o; backward walk reads q,k,v,do and writes dq,dk,dv; local passes read two tensors.
+    alg_bytes = {"fwd_walk": 4 * D * esz, "bwd_walk": 7 * D * esz, "fwd_local": 2 * D * esz, "bwd_local": 2 * D * esz}
+    dominant = max(("fwd_walk", "bwd_walk", "fwd_local", "bwd_local"), key=lambda n: per_launch_ms[n])
+    dom_bytes = alg_bytes[dominant] * tok_heads_per_launch
+    achieved = dom_bytes / (per_launch_ms[dominant] * 1e-3) / 1e9
+    roofline = {"kernel": dominant, "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
+                "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
+                "traffic": MEASURED_TRAFFIC_BYTES.get(dominant),
+                "algorithmic_bytes_per_launch": dom_bytes,
+                "avg_launch_ms": round(per_launch_ms[dominant], 4),
+                "kernel_ms_per_launch": {n: round(x, 4) for n, x in per_launch_ms.items()}}
+
+    # whole-step figures against both roofs (algorithmic numbers, not issued flops)
+    flops_step = (14 * tile * D + 12 * D * D) * B * H * N
+    min_bytes_step = 11 * D * esz * B * H * N
+    step_s = ms_per_step * 1e-3
+    extra = {"algorithmic_tflops": round(flops_step / step_s / 1e12, 2),
+             "mfma_bf16_peak_frac": round(flops_step / step_s / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
+             "min_hbm_bytes_per_step": min_bytes_step,
+             "step_hbm_frac_at_min_bytes": round(min_bytes_step / step_s / 1e9 / HBM_PEAK_GBS, 4)}
+
+    # ---- CPU oracle on a bounded sample of the same workload ----
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import lasp_oracle
+        n_s = min(args.cpu_sample_tokens, N)
+        n_s -= n_s % cfg.chunk
+        sl = slice(0, n_s)
+        a = [np.ascontiguousarray(x[:, :, sl], dtype=np.float64) for x in (inp.q, inp.k, inp.v, inp.dout)]
+        c0 = time.perf_counter()
+        lasp_oracle.fwd_chunked(a[0], a[1], a[2], inp.decay, cfg.chunk)
+        lasp_oracle.bwd_chunked(a[0], a[1], a[2], a[3], inp.decay, cfg.chunk)
+        c1 = time.perf_counter()
+        cpu = {"value": round(B * n_s / (c1 - c0), 1), "unit": "tokens/s", "cores": lasp_oracle.num_threads(),
+               "kind": "oracle",
+               "sample": f"chunked fp64 oracle (Alg. 2 + Alg. 3), fwd+bwd, first {n_s} of {N} tokens of all "
+                         f"{B * H} heads, {c1 - c0:.1f} s"}
+
+    line = {"metric": "fwd+bwd tokens/sec, chunked causal linear attention with decay (LASP per-device hot path)",
+            "value": round(tokens_per_s, 1), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
+            "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
+            "scaling": "weak", "vs_baseline": None, "dtype": cfg.dtype, "data": "synthetic",
+            "config": {"workload": f"{cfg.name}: B={B} H={H} N={N} d={D} chunk={cfg.chunk} {cfg.dtype}, "
+                                   f"T={T} sub-sequence(s), fwd+bwd",
+                       "tile_tokens": tile, "segments_per_head": nseg,
+                       "state_cache_bytes": seq.cache_bytes()},
+            "roofline": roofline, "whole_step": extra, "cpu_baseline": cpu}
+    print(json.dumps(line), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -4,6 +4,7 @@
 
 #include <cmath>
 #include <cstdint>
+#include <vector>
 
 #include "lasp_internal.h"
 
@@ -49,6 +50,19 @@ int make_plan(const lasp_shape *s, lasp::Plan *p) {
 }
 
 size_t elem_bytes(int dtype) { return dtype == LASP_F32 ? 4 : 2; }
+
+// Event pool of the diagnostic profiler (lasp_profile_begin / lasp_profile_end).
+struct Profiler {
+    bool on = false;
+    int cap = 0;
+    int used[2] = {0, 0};                       // recorded forward / backward calls
+    std::vector<lasp::KernelEvents> slots[2];
+} g_prof;
+
+const lasp::KernelEvents *next_slot(int kind) {
+    if (!g_prof.on || g_prof.used[kind] >= g_prof.cap) return nullptr;
+    return &g_prof.slots[kind][g_prof.used[kind]++];
+}
 
 struct Span {
     const char *p;
@@ -136,7 +150,7 @@ int lasp_fwd(const lasp_shape *shape, const void *q, const void *k, const void *
             if (&o != &o2 && overlap(o, o2)) return LASP_ERR_ALIAS;
     }
     lasp::FwdArgs a{q, k, v, kv_in, decay, out, kv_out, state_cache, (float *)scratch};
-    return lasp::launch_fwd(p, a, (hipStream_t)hip_stream) == hipSuccess ? LASP_OK : LASP_ERR_HIP;
+    return lasp::launch_fwd(p, a, (hipStream_t)hip_stream, next_slot(0)) == hipSuccess ? LASP_OK : LASP_ERR_HIP;
 }
 
 int lasp_bwd(const lasp_shape *shape, const void *q, const void *k, const void *v, const void *dout,
@@ -163,7 +177,47 @@ int lasp_bwd(const lasp_shape *shape, const void *q, const void *k, const void *
             if (&o != &o2 && overlap(o, o2)) return LASP_ERR_ALIAS;
     }
     lasp::BwdArgs a{q, k, v, dout, dkv_out, decay, state_cache, dq, dk, dv, dkv_in, (float *)scratch};
-    return lasp::launch_bwd(p, a, (hipStream_t)hip_stream) == hipSuccess ? LASP_OK : LASP_ERR_HIP;
+    return lasp::launch_bwd(p, a, (hipStream_t)hip_stream, next_slot(1)) == hipSuccess ? LASP_OK : LASP_ERR_HIP;
+}
+
+int lasp_profile_begin(int32_t max_calls) {
+    if (max_calls <= 0 || g_prof.on) return LASP_ERR_SHAPE;
+    for (int kind = 0; kind < 2; ++kind) {
+        g_prof.slots[kind].assign(max_calls, lasp::KernelEvents{});
+        for (auto &slot : g_prof.slots[kind])
+            for (auto &ev : slot.ev)
+                if (hipEventCreate(&ev) != hipSuccess) return LASP_ERR_HIP;
+        g_prof.used[kind] = 0;
+    }
+    g_prof.cap = max_calls;
+    g_prof.on = true;
+    return LASP_OK;
+}
+
+int lasp_profile_end(double ms_sum[6], int32_t *fwd_calls, int32_t *bwd_calls) {
+    if (!ms_sum || !fwd_calls || !bwd_calls) return LASP_ERR_NULL;
+    if (!g_prof.on) return LASP_ERR_SHAPE;
+    int rc = LASP_OK;
+    for (int i = 0; i < 6; ++i) ms_sum[i] = 0.0;
+    for (int kind = 0; kind < 2; ++kind) {
+        for (int c = 0; c < g_prof.used[kind]; ++c) {
+            const auto &slot = g_prof.slots[kind][c];
+            if (hipEventSynchronize(slot.ev[3]) != hipSuccess) rc = LASP_ERR_HIP;
+            for (int j = 0; j < 3; ++j) {
+                float ms = 0.0f;
+                if (hipEventElapsedTime(&ms, slot.ev[j], slot.ev[j + 1]) != hipSuccess) rc = LASP_ERR_HIP;
+                ms_sum[3 * kind + j] += ms;
+            }
+        }
+        for (auto &slot : g_prof.slots[kind])
+            for (auto &ev : slot.ev) (void)hipEventDestroy(ev);
+        g_prof.slots[kind].clear();
+    }
+    *fwd_calls = g_prof.used[0];
+    *bwd_calls = g_prof.used[1];
+    g_prof.on = false;
+    g_prof.cap = 0;
+    return rc;
 }
 
 }  // extern "C"

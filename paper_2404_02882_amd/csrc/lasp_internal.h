@@ -39,11 +39,17 @@ struct BwdArgs {
     float *scratch;
 };
 
+// Optional event recorder: when non-null, launch_* records ev[0] before the
+// local pass, ev[1] after it, ev[2] after the scan and ev[3] after the walk.
+struct KernelEvents {
+    hipEvent_t ev[4];
+};
+
 // Tile length used for a (dtype, chunk, D) combination.
 int tile_tokens(int dtype, int chunk, int D);
 
-hipError_t launch_fwd(const Plan &p, const FwdArgs &a, hipStream_t stream);
-hipError_t launch_bwd(const Plan &p, const BwdArgs &a, hipStream_t stream);
+hipError_t launch_fwd(const Plan &p, const FwdArgs &a, hipStream_t stream, const KernelEvents *ke);
+hipError_t launch_bwd(const Plan &p, const BwdArgs &a, hipStream_t stream, const KernelEvents *ke);
 
 }  // namespace lasp
 #endif

@@ -632,51 +632,68 @@ struct Smem {
     static_assert(fwd <= 163840 && bwd <= 163840, "LDS budget of one gfx950 CU exceeded");
 };
 
+// Raise the dynamic LDS limit of a kernel above the 64 KB default, once per
+// kernel and device (the attribute lives in the loaded module of each device).
 template <typename F>
 static hipError_t allow_lds(F kernel, size_t bytes) {
-    return hipFuncSetAttribute((const void *)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+    static bool done[64] = {};
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev >= 0 && dev < 64 && done[dev]) return hipSuccess;
+    e = hipFuncSetAttribute((const void *)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+    if (e == hipSuccess && dev >= 0 && dev < 64) done[dev] = true;
+    return e;
 }
 
 template <typename T, int CT, int D>
-static hipError_t run_fwd(const Plan &p, const FwdArgs &a, hipStream_t s) {
+static hipError_t run_fwd(const Plan &p, const FwdArgs &a, hipStream_t s, const KernelEvents *ke) {
     const int chains = p.B * p.H, DD = D * D;
     constexpr size_t lds_local = Smem<T, CT, D>::local, lds_fwd = Smem<T, CT, D>::fwd;
     hipError_t e;
+    if (ke) (void)hipEventRecord(ke->ev[0], s);
     if (p.nseg > 1) {
         auto kl = k_local<T, CT, D, false>;
         if ((e = allow_lds(kl, lds_local)) != hipSuccess) return e;
         kl<<<dim3(p.nseg - 1, chains), dim3(D * 2), lds_local, s>>>((const T *)a.k, (const T *)a.v, a.decay, a.scratch,
                                                                    p.H, p.ntiles, p.nseg, p.tiles_per_seg);
     }
+    if (ke) (void)hipEventRecord(ke->ev[1], s);
     k_scan<false><<<dim3((DD + 255) / 256, chains), dim3(256), 0, s>>>(a.scratch, a.kv_in, a.decay, p.H, DD, p.nseg,
                                                                        p.tiles_per_seg, p.ntiles, p.tile);
+    if (ke) (void)hipEventRecord(ke->ev[2], s);
     auto kf = k_fwd<T, CT, D>;
     if ((e = allow_lds(kf, lds_fwd)) != hipSuccess) return e;
     kf<<<dim3(p.nseg, chains), dim3(D * 2), lds_fwd, s>>>((const T *)a.q, (const T *)a.k, (const T *)a.v, a.decay,
                                                          (T *)a.out, a.kv_out, (T *)a.cache, (const float *)a.scratch,
                                                          p.H, p.ntiles, p.nseg, p.tiles_per_seg);
+    if (ke) (void)hipEventRecord(ke->ev[3], s);
     return hipGetLastError();
 }
 
 template <typename T, int CT, int D>
-static hipError_t run_bwd(const Plan &p, const BwdArgs &a, hipStream_t s) {
+static hipError_t run_bwd(const Plan &p, const BwdArgs &a, hipStream_t s, const KernelEvents *ke) {
     const int chains = p.B * p.H, DD = D * D;
     constexpr size_t lds_local = Smem<T, CT, D>::local, lds_bwd = Smem<T, CT, D>::bwd;
     hipError_t e;
+    if (ke) (void)hipEventRecord(ke->ev[0], s);
     if (p.nseg > 1) {
         auto kl = k_local<T, CT, D, true>;
         if ((e = allow_lds(kl, lds_local)) != hipSuccess) return e;
         kl<<<dim3(p.nseg - 1, chains), dim3(D * 2), lds_local, s>>>((const T *)a.q, (const T *)a.dout, a.decay,
                                                                    a.scratch, p.H, p.ntiles, p.nseg, p.tiles_per_seg);
     }
+    if (ke) (void)hipEventRecord(ke->ev[1], s);
     k_scan<true><<<dim3((DD + 255) / 256, chains), dim3(256), 0, s>>>(a.scratch, a.dkv_out, a.decay, p.H, DD, p.nseg,
                                                                       p.tiles_per_seg, p.ntiles, p.tile);
+    if (ke) (void)hipEventRecord(ke->ev[2], s);
     auto kb = k_bwd<T, CT, D>;
     if ((e = allow_lds(kb, lds_bwd)) != hipSuccess) return e;
     kb<<<dim3(p.nseg, chains), dim3(D * 2), lds_bwd, s>>>((const T *)a.q, (const T *)a.k, (const T *)a.v,
                                                          (const T *)a.dout, a.decay, (const T *)a.cache, (T *)a.dq,
                                                          (T *)a.dk, (T *)a.dv, a.dkv_in, (const float *)a.scratch, p.H,
                                                          p.ntiles, p.nseg, p.tiles_per_seg);
+    if (ke) (void)hipEventRecord(ke->ev[3], s);
     return hipGetLastError();
 }
 
@@ -688,17 +705,17 @@ int tile_tokens(int dtype, int chunk, int D) {
 
 #define LASP_DISPATCH(FN, ARGS)                                                        \
     if (p.dtype == 0) {                                                                \
-        if (p.D == 64) return FN<float, 32, 64>(p, ARGS, stream);                      \
-        return FN<float, 32, 128>(p, ARGS, stream);                                    \
+        if (p.D == 64) return FN<float, 32, 64>(p, ARGS, stream, ke);                     \
+        return FN<float, 32, 128>(p, ARGS, stream, ke);                                    \
     }                                                                                  \
     if (p.tile == 64) {                                                                \
-        if (p.D == 64) return FN<bf16_t, 64, 64>(p, ARGS, stream);                     \
-        return FN<bf16_t, 64, 128>(p, ARGS, stream);                                   \
+        if (p.D == 64) return FN<bf16_t, 64, 64>(p, ARGS, stream, ke);                     \
+        return FN<bf16_t, 64, 128>(p, ARGS, stream, ke);                                   \
     }                                                                                  \
-    if (p.D == 64) return FN<bf16_t, 128, 64>(p, ARGS, stream);                        \
-    return FN<bf16_t, 128, 128>(p, ARGS, stream);
+    if (p.D == 64) return FN<bf16_t, 128, 64>(p, ARGS, stream, ke);                        \
+    return FN<bf16_t, 128, 128>(p, ARGS, stream, ke);
 
-hipError_t launch_fwd(const Plan &p, const FwdArgs &a, hipStream_t stream) { LASP_DISPATCH(run_fwd, a) }
-hipError_t launch_bwd(const Plan &p, const BwdArgs &a, hipStream_t stream) { LASP_DISPATCH(run_bwd, a) }
+hipError_t launch_fwd(const Plan &p, const FwdArgs &a, hipStream_t stream, const KernelEvents *ke) { LASP_DISPATCH(run_fwd, a) }
+hipError_t launch_bwd(const Plan &p, const BwdArgs &a, hipStream_t stream, const KernelEvents *ke) { LASP_DISPATCH(run_bwd, a) }
 
 }  // namespace lasp

@@ -57,6 +57,27 @@ lib.lasp_bwd.argtypes = [_sp] + [_vp] * 12 + [_sz, _vp]
 lib.lasp_bwd.restype = ctypes.c_int
 
 
+lib.lasp_profile_begin.argtypes = [ctypes.c_int32]
+lib.lasp_profile_end.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int32),
+                                 ctypes.POINTER(ctypes.c_int32)]
+
+
+def profile_begin(max_calls: int) -> None:
+    rc = lib.lasp_profile_begin(int(max_calls))
+    if rc != 0:
+        raise LaspError(rc, "lasp_profile_begin")
+
+
+def profile_end():
+    """Returns ({'fwd': (local, scan, walk), 'bwd': (...)} summed milliseconds, fwd_calls, bwd_calls)."""
+    ms = (ctypes.c_double * 6)()
+    nf, nb = ctypes.c_int32(0), ctypes.c_int32(0)
+    rc = lib.lasp_profile_end(ms, ctypes.byref(nf), ctypes.byref(nb))
+    if rc != 0:
+        raise LaspError(rc, "lasp_profile_end")
+    return {"fwd": tuple(ms[0:3]), "bwd": tuple(ms[3:6])}, nf.value, nb.value
+
+
 def status_str(status: int) -> str:
     return lib.lasp_status_str(int(status)).decode()
 
