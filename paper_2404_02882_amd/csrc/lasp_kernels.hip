@@ -39,6 +39,7 @@ typedef __attribute__((ext_vector_type(8))) float f32x8;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(4))) short s16x4;
+typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
 
 #define DEVI __device__ __forceinline__
 
@@ -153,19 +154,19 @@ struct TileMover {
     static constexpr int VPR = COLS / EPV;              // pieces per row
     static constexpr int NV = ROWS * VPR / NT;          // pieces per thread
     static_assert(ROWS * VPR % NT == 0, "tile must divide evenly over the workgroup");
-    uint4 r[NV];
+    u32x4 r[NV];
     DEVI void load(const T *g) {  // g: first element of the tile, row stride COLS
 #pragma unroll
         for (int i = 0; i < NV; ++i) {
             int v = threadIdx.x + i * NT;
-            r[i] = *(const uint4 *)(g + (size_t)(v / VPR) * COLS + (v % VPR) * EPV);
+            r[i] = *(const u32x4 *)(g + (size_t)(v / VPR) * COLS + (v % VPR) * EPV);
         }
     }
     DEVI void store(T *s, int ld) const {
 #pragma unroll
         for (int i = 0; i < NV; ++i) {
             int v = threadIdx.x + i * NT;
-            *(uint4 *)(s + (v / VPR) * ld + (v % VPR) * EPV) = r[i];
+            *(u32x4 *)(s + (v / VPR) * ld + (v % VPR) * EPV) = r[i];
         }
     }
 };
@@ -236,11 +237,15 @@ DEVI void masked_scores(T *sP, const T *sA, const T *sB, const float *pw, int w)
         }
 }
 
-// Write one 32x32 accumulator tile to a [.][D] global tensor (rows row0.., column block w).
+// Write one 32x32 accumulator tile holding the TRANSPOSE of an output block:
+// accumulator row = feature column 32 w + acc_row(i), accumulator column
+// (lane_r) = token row0 + lane_r. Each lane owns four consecutive features of
+// its token per register group, so it stores them as one 8- or 16-byte piece.
 template <typename T, int D>
-DEVI void store_out_tile(T *g, const f32x16 &acc, int row0, int w) {
+DEVI void store_out_tile_t(T *g, const f32x16 &acc, int row0, int w) {
+    T *p = g + (size_t)(row0 + lane_r()) * D + 32 * w + 4 * lane_h();
 #pragma unroll
-    for (int i = 0; i < 16; ++i) Elem<T>::st1(g + (size_t)(row0 + acc_row(i)) * D + 32 * w + lane_r(), acc[i]);
+    for (int q = 0; q < 4; ++q) Elem<T>::st4(p + 8 * q, acc[4 * q], acc[4 * q + 1], acc[4 * q + 2], acc[4 * q + 3]);
 }
 
 // ---------------------------------------------------------------------------
@@ -350,7 +355,8 @@ __global__ __launch_bounds__(D * 2) void k_fwd(const T *__restrict__ Q, const T 
                                                 T *__restrict__ cache, const float *__restrict__ scratch,
                                                 int H, int ntiles, int nseg, int tiles_per_seg) {
     using E = Elem<T>;
-    constexpr int NT = D * 2, LDD = D + E::PAD, LDP = CT + E::PAD, DB = D / 32, NB = CT / 32, NKS = CT / E::KSTEP;
+    constexpr int NT = D * 2, LDD = D + E::PAD, LDP = CT + E::PAD, DB = D / 32, NB = CT / 32, NKS = CT / E::KSTEP,
+                  SPB = 32 / E::KSTEP;
     extern __shared__ __attribute__((aligned(16))) char smem[];
     T *sQ = (T *)smem;
     T *sK = sQ + CT * LDD;
@@ -388,12 +394,7 @@ __global__ __launch_bounds__(D * 2) void k_fwd(const T *__restrict__ Q, const T 
         // masked scores P (all waves share the lower-triangular blocks)
         masked_scores<T, CT, D, LDD, LDP>(sP, sK, sQ, pw, w);
 
-        // state as MFMA operand, and into the cache as KV_{t-1}
-        typename E::frag sf[DB][E::NSUB];
-#pragma unroll
-        for (int ab = 0; ab < DB; ++ab)
-#pragma unroll
-            for (int m = 0; m < E::NSUB; ++m) sf[ab][m] = E::from_acc(st[ab], m);
+        // the state this tile starts from goes to the cache as KV_{t-1}
         if (cache) {
             T *c = cache + ((size_t)chain * ntiles + t) * D * D;
 #pragma unroll
@@ -401,40 +402,45 @@ __global__ __launch_bounds__(D * 2) void k_fwd(const T *__restrict__ Q, const T 
 #pragma unroll
                 for (int i = 0; i < 16; ++i) E::st1(c + (32 * ab + acc_row(i)) * D + 32 * w + lane_r(), st[ab][i]);
         }
-        typename E::frag vf[NKS];
-#pragma unroll
-        for (int ks = 0; ks < NKS; ++ks) vf[ks] = E::ld_ks(sV, LDD, ks * E::KSTEP, 32 * w);
         __syncthreads();  // P visible
 
+        // Output tiles are accumulated transposed: OT[c][i], c in this wave's column block.
+        f32x16 acc[NB];
+#pragma unroll
+        for (int ib = 0; ib < NB; ++ib) acc[ib] = f32x16{0};
+        // inter: OT[c][i] = sum_a KV_{t-1}[a][c] Q[i][a], a taken in accumulator order
+#pragma unroll
+        for (int ab = 0; ab < DB; ++ab)
+#pragma unroll
+            for (int m = 0; m < E::NSUB; ++m) {
+                const typename E::frag sf = E::from_acc(st[ab], m);
+#pragma unroll
+                for (int ib = 0; ib < NB; ++ib) acc[ib] = E::mfma(sf, E::ld_kp(sQ, LDD, 32 * ib, 32 * ab, m), acc[ib]);
+            }
+        // Lambda: token r (1-based) carries lambda^r; the token is this lane's column
+#pragma unroll
+        for (int ib = 0; ib < NB; ++ib) acc[ib] *= pw[32 * ib + lane_r() + 1];
+        // intra: OT[c][i] += sum_{j<=i} V[j][c] P[i][j]
+#pragma unroll
+        for (int ks = 0; ks < NKS; ++ks) {
+            const typename E::frag vf = E::ld_ks(sV, LDD, ks * E::KSTEP, 32 * w);
+#pragma unroll
+            for (int ib = ks / SPB; ib < NB; ++ib) acc[ib] = E::mfma(vf, E::ld_kc(sP, LDP, 32 * ib, ks * E::KSTEP), acc[ib]);
+        }
         T *o = O + base + (size_t)t * CT * D;
 #pragma unroll
-        for (int ib = 0; ib < NB; ++ib) {
-            f32x16 acc = {0};
-            // inter: Q KV_{t-1}, contraction over the key feature a in accumulator order
-#pragma unroll
-            for (int ab = 0; ab < DB; ++ab)
-#pragma unroll
-                for (int m = 0; m < E::NSUB; ++m) acc = E::mfma(E::ld_kp(sQ, LDD, 32 * ib, 32 * ab, m), sf[ab][m], acc);
-            // Lambda: row r (1-based) carries lambda^r
-#pragma unroll
-            for (int i = 0; i < 16; ++i) acc[i] *= pw[32 * ib + acc_row(i) + 1];
-            // intra: P V over the keys j <= i
-#pragma unroll
-            for (int ks = 0; ks < (ib + 1) * (32 / E::KSTEP); ++ks)
-                acc = E::mfma(E::ld_kc(sP, LDP, 32 * ib, ks * E::KSTEP), vf[ks], acc);
-            store_out_tile<T, D>(o, acc, 32 * ib, w);
-        }
-        // state update with K rows weighted lambda^(CT-1-j) (applied to the V fragments)
+        for (int ib = 0; ib < NB; ++ib) store_out_tile_t<T, D>(o, acc[ib], 32 * ib, w);
+
+        // state update: KV <- lambda^CT KV + (diag{lambda^(CT-1-j)} K)^T V, weight applied to the V fragments
         const float lamC = pw[CT];
 #pragma unroll
-        for (int ks = 0; ks < NKS; ++ks)
-            vf[ks] = E::scale(vf[ks], ks * E::KSTEP, [&](int k) { return pw[CT - 1 - k]; });
+        for (int ab = 0; ab < DB; ++ab) st[ab] *= lamC;
 #pragma unroll
-        for (int ab = 0; ab < DB; ++ab) {
-            f32x16 acc = st[ab] * lamC;
+        for (int ks = 0; ks < NKS; ++ks) {
+            const typename E::frag vd = E::scale(E::ld_ks(sV, LDD, ks * E::KSTEP, 32 * w), ks * E::KSTEP,
+                                                 [&](int k) { return pw[CT - 1 - k]; });
 #pragma unroll
-            for (int ks = 0; ks < NKS; ++ks) acc = E::mfma(E::ld_ks(sK, LDD, ks * E::KSTEP, 32 * ab), vf[ks], acc);
-            st[ab] = acc;
+            for (int ab = 0; ab < DB; ++ab) st[ab] = E::mfma(E::ld_ks(sK, LDD, ks * E::KSTEP, 32 * ab), vd, st[ab]);
         }
     }
     if (seg == nseg - 1) state_store<D>(st, kv_out + (size_t)chain * D * D, w);
@@ -523,33 +529,30 @@ __global__ __launch_bounds__(D * 2) void k_bwd(const T *__restrict__ Q, const T 
 
         masked_scores<T, CT, D, LDD, LDP>(sDS, bufA, bufB, pw, w);  // dS^T = V dO^T
 
+        // All output tiles are accumulated transposed (feature x token), this wave's feature block.
         f32x16 accQ[NB], accK[NB];
 #pragma unroll
         for (int b = 0; b < NB; ++b) accQ[b] = accK[b] = f32x16{0};
-        // dQ_inter = Lambda (dO KV_{t-1}^T): B[k = c][n = a] = KV[a][c], read from the cache in place
+        // dQ_inter^T[a][i] = lambda^i sum_c KV_{t-1}[a][c] dO[i][c]; KV rows are read from the cache in place
         {
             const T *c = cache + ((size_t)chain * ntiles + t) * D * D;
 #pragma unroll
             for (int ks = 0; ks < NKD; ++ks) {
-                typename E::frag b = E::ld_kc(c, D, 32 * w, ks * E::KSTEP);
+                const typename E::frag kvf = E::ld_kc(c, D, 32 * w, ks * E::KSTEP);
 #pragma unroll
-                for (int ib = 0; ib < NB; ++ib) accQ[ib] = E::mfma(E::ld_kc(bufB, LDD, 32 * ib, ks * E::KSTEP), b, accQ[ib]);
+                for (int ib = 0; ib < NB; ++ib) accQ[ib] = E::mfma(kvf, E::ld_kc(bufB, LDD, 32 * ib, ks * E::KSTEP), accQ[ib]);
             }
 #pragma unroll
-            for (int ib = 0; ib < NB; ++ib)
-#pragma unroll
-                for (int i = 0; i < 16; ++i) accQ[ib][i] *= pw[32 * ib + acc_row(i) + 1];
+            for (int ib = 0; ib < NB; ++ib) accQ[ib] *= pw[32 * ib + lane_r() + 1];
         }
-        // dK_inter = (lambda^CT Lambda^-1) (V dKV^T)
+        // dK_inter^T[a][j] = lambda^(CT-j) sum_c dKV[a][c] V[j][c]
 #pragma unroll
         for (int ks = 0; ks < NKD; ++ks)
 #pragma unroll
-            for (int jb = 0; jb < NB; ++jb) accK[jb] = E::mfma(E::ld_kc(bufA, LDD, 32 * jb, ks * E::KSTEP), xf[ks], accK[jb]);
+            for (int jb = 0; jb < NB; ++jb) accK[jb] = E::mfma(xf[ks], E::ld_kc(bufA, LDD, 32 * jb, ks * E::KSTEP), accK[jb]);
 #pragma unroll
-        for (int jb = 0; jb < NB; ++jb)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) accK[jb][i] *= pw[CT - 1 - (32 * jb + acc_row(i))];
-        // dO fragments of this wave's column block: B[k = i][n = c in w]
+        for (int jb = 0; jb < NB; ++jb) accK[jb] *= pw[CT - 1 - (32 * jb + lane_r())];
+        // dO fragments of this wave's column block: [k = i][n = c in w]
         typename E::frag dof[NKS];
 #pragma unroll
         for (int ks = 0; ks < NKS; ++ks) dof[ks] = E::ld_ks(bufB, LDD, ks * E::KSTEP, 32 * w);
@@ -566,55 +569,56 @@ __global__ __launch_bounds__(D * 2) void k_bwd(const T *__restrict__ Q, const T 
         masked_scores<T, CT, D, LDD, LDP>(sS, bufA, bufB, pw, w);  // S^T = K Q^T
         __syncthreads();
 
-        // dQ = dQ_inter + dSm K
+        // dQ^T[a][i] += sum_{j<=i} K[j][a] dSm[i][j]
 #pragma unroll
         for (int ks = 0; ks < NKS; ++ks) {
-            typename E::frag b = E::ld_ks(bufA, LDD, ks * E::KSTEP, 32 * w);
+            const typename E::frag kf = E::ld_ks(bufA, LDD, ks * E::KSTEP, 32 * w);
 #pragma unroll
-            for (int ib = ks / SPB; ib < NB; ++ib) accQ[ib] = E::mfma(E::ld_kc(sDS, LDP, 32 * ib, ks * E::KSTEP), b, accQ[ib]);
+            for (int ib = ks / SPB; ib < NB; ++ib) accQ[ib] = E::mfma(kf, E::ld_kc(sDS, LDP, 32 * ib, ks * E::KSTEP), accQ[ib]);
         }
 #pragma unroll
-        for (int ib = 0; ib < NB; ++ib) store_out_tile<T, D>(dQ + off, accQ[ib], 32 * ib, w);
-        // dK = dK_inter + dSm^T Q
+        for (int ib = 0; ib < NB; ++ib) store_out_tile_t<T, D>(dQ + off, accQ[ib], 32 * ib, w);
+        // dK^T[a][j] += sum_{i>=j} Q[i][a] dSm[i][j]
 #pragma unroll
         for (int ks = 0; ks < NKS; ++ks) {
-            typename E::frag b = E::ld_ks(bufB, LDD, ks * E::KSTEP, 32 * w);
+            const typename E::frag qf = E::ld_ks(bufB, LDD, ks * E::KSTEP, 32 * w);
 #pragma unroll
-            for (int jb = 0; jb <= ks / SPB; ++jb) accK[jb] = E::mfma(E::ld_ks(sDS, LDP, ks * E::KSTEP, 32 * jb), b, accK[jb]);
+            for (int jb = 0; jb <= ks / SPB; ++jb) accK[jb] = E::mfma(qf, E::ld_ks(sDS, LDP, ks * E::KSTEP, 32 * jb), accK[jb]);
         }
 #pragma unroll
-        for (int jb = 0; jb < NB; ++jb) store_out_tile<T, D>(dK + off, accK[jb], 32 * jb, w);
-        // dV = (lambda^CT Lambda^-1) (K dKV) + Sm^T dO
+        for (int jb = 0; jb < NB; ++jb) store_out_tile_t<T, D>(dK + off, accK[jb], 32 * jb, w);
+        // dV^T[c][j] = lambda^(CT-j) sum_a dKV[a][c] K[j][a] + sum_{i>=j} dO[i][c] Sm[i][j]
         {
-            typename E::frag df[DB][E::NSUB];
+            f32x16 accV[NB];
+#pragma unroll
+            for (int jb = 0; jb < NB; ++jb) accV[jb] = f32x16{0};
 #pragma unroll
             for (int ab = 0; ab < DB; ++ab)
 #pragma unroll
-                for (int m = 0; m < E::NSUB; ++m) df[ab][m] = E::from_acc(dkv[ab], m);
+                for (int m = 0; m < E::NSUB; ++m) {
+                    const typename E::frag df = E::from_acc(dkv[ab], m);
 #pragma unroll
-            for (int jb = 0; jb < NB; ++jb) {
-                f32x16 acc = {0};
+                    for (int jb = 0; jb < NB; ++jb) accV[jb] = E::mfma(df, E::ld_kp(bufA, LDD, 32 * jb, 32 * ab, m), accV[jb]);
+                }
 #pragma unroll
-                for (int ab = 0; ab < DB; ++ab)
+            for (int jb = 0; jb < NB; ++jb) accV[jb] *= pw[CT - 1 - (32 * jb + lane_r())];
 #pragma unroll
-                    for (int m = 0; m < E::NSUB; ++m) acc = E::mfma(E::ld_kp(bufA, LDD, 32 * jb, 32 * ab, m), df[ab][m], acc);
+            for (int ks = 0; ks < NKS; ++ks)
 #pragma unroll
-                for (int i = 0; i < 16; ++i) acc[i] *= pw[CT - 1 - (32 * jb + acc_row(i))];
+                for (int jb = 0; jb <= ks / SPB; ++jb)
+                    accV[jb] = E::mfma(dof[ks], E::ld_ks(sS, LDP, ks * E::KSTEP, 32 * jb), accV[jb]);
 #pragma unroll
-                for (int ks = jb * SPB; ks < NKS; ++ks) acc = E::mfma(E::ld_ks(sS, LDP, ks * E::KSTEP, 32 * jb), dof[ks], acc);
-                store_out_tile<T, D>(dV + off, acc, 32 * jb, w);
-            }
+            for (int jb = 0; jb < NB; ++jb) store_out_tile_t<T, D>(dV + off, accV[jb], 32 * jb, w);
         }
         // dKV <- lambda^CT dKV + (Lambda Q)^T dO  (row weight lambda^(i+1) applied to the dO fragments)
         const float lamC = pw[CT];
 #pragma unroll
-        for (int ks = 0; ks < NKS; ++ks) dof[ks] = E::scale(dof[ks], ks * E::KSTEP, [&](int k) { return pw[k + 1]; });
+        for (int ab = 0; ab < DB; ++ab) dkv[ab] *= lamC;
 #pragma unroll
-        for (int ab = 0; ab < DB; ++ab) {
-            f32x16 acc = dkv[ab] * lamC;
+        for (int ks = 0; ks < NKS; ++ks) {
+            const typename E::frag dos = E::scale(dof[ks], ks * E::KSTEP, [&](int k) { return pw[k + 1]; });
 #pragma unroll
-            for (int ks = 0; ks < NKS; ++ks) acc = E::mfma(E::ld_ks(bufB, LDD, ks * E::KSTEP, 32 * ab), dof[ks], acc);
-            dkv[ab] = acc;
+            for (int ab = 0; ab < DB; ++ab) dkv[ab] = E::mfma(E::ld_ks(bufB, LDD, ks * E::KSTEP, 32 * ab), dos, dkv[ab]);
         }
     }
     if (seg == 0) state_store<D>(dkv, dkv_in + (size_t)chain * D * D, w);
