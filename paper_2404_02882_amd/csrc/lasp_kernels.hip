@@ -42,6 +42,17 @@ typedef __attribute__((ext_vector_type(4))) short s16x4;
 typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
 
 #define DEVI __device__ __forceinline__
+// Compiler scheduling fence: keeps the loads of one product step from being
+// hoisted across earlier steps (which would blow up register live ranges).
+#define SCHED_FENCE() __builtin_amdgcn_sched_barrier(0)
+
+// Global access as (uniform base + compile-time bytes) + 32-bit per-lane byte
+// offset: the form the hardware addresses with a scalar base register pair and
+// one vector offset register, instead of a 64-bit address pair per access.
+template <typename V>
+DEVI V gload(const void *base, unsigned lane_bytes) { return *(const V *)((const char *)base + lane_bytes); }
+template <typename V>
+DEVI void gstore(void *base, unsigned lane_bytes, V v) { *(V *)((char *)base + lane_bytes) = v; }
 
 DEVI int lane_id() { return threadIdx.x & 63; }
 DEVI int lane_r() { return threadIdx.x & 31; }         // row / column inside a 32-wide tile
@@ -74,6 +85,10 @@ struct Elem<float> {
     static DEVI f32x16 mfma(frag a, frag b, f32x16 c) { return __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, c, 0, 0, 0); }
     static DEVI frag ld_kc(const float *X, int ld, int row0, int k0) { return X[(row0 + lane_r()) * ld + k0 + lane_h()]; }
     static DEVI frag ld_ks(const float *X, int ld, int k0, int col0) { return X[(k0 + lane_h()) * ld + col0 + lane_r()]; }
+    // ld_kc from global memory: uniform tile pointer, row block row0, contraction step k0
+    static DEVI frag ld_kc_g(const float *X, int ld, int row0, int k0) {
+        return gload<float>(X + k0, ((row0 + lane_r()) * ld + lane_h()) * sizeof(float));
+    }
     static DEVI frag ld_kp(const float *X, int ld, int row0, int kb, int m) {
         return X[(row0 + lane_r()) * ld + kb + acc_row(m)];
     }
@@ -85,6 +100,10 @@ struct Elem<float> {
     // store 4 values of consecutive columns
     static DEVI void st4(float *p, float a, float b, float c, float d) { *(f32x4 *)p = f32x4{a, b, c, d}; }
     static DEVI void st1(float *p, float a) { *p = a; }
+    static DEVI void gst4(float *base, unsigned lane_bytes, float a, float b, float c, float d) {
+        gstore<f32x4>(base, lane_bytes, f32x4{a, b, c, d});
+    }
+    static DEVI void gst1(float *base, unsigned lane_bytes, float a) { gstore<float>(base, lane_bytes, a); }
     static DEVI float ld1(const float *p) { return *p; }
 };
 
@@ -97,6 +116,9 @@ struct Elem<bf16_t> {
     static DEVI f32x16 mfma(frag a, frag b, f32x16 c) { return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0); }
     static DEVI frag ld_kc(const bf16_t *X, int ld, int row0, int k0) {
         return *(const bf16x8 *)(X + (row0 + lane_r()) * ld + k0 + 8 * lane_h());
+    }
+    static DEVI frag ld_kc_g(const bf16_t *X, int ld, int row0, int k0) {
+        return gload<bf16x8>(X + k0, ((row0 + lane_r()) * ld + 8 * lane_h()) * sizeof(bf16_t));
     }
     // LDS only: two transposing reads (ds_read_b64_tr_b16). Within each group of
     // 16 lanes, lane i ends up with element (row e, column i) of the 4 x 16 block
@@ -142,6 +164,10 @@ struct Elem<bf16_t> {
         *p = c.u;
     }
     static DEVI float ld1(const bf16_t *p) { return __uint_as_float(((unsigned)*p) << 16); }
+    static DEVI void gst4(bf16_t *base, unsigned lane_bytes, float a, float b, float c, float d) {
+        gstore<bf16x4>(base, lane_bytes, __builtin_convertvector(f32x4{a, b, c, d}, bf16x4));
+    }
+    static DEVI void gst1(bf16_t *base, unsigned lane_bytes, float a) { gstore<__bf16>(base, lane_bytes, (__bf16)a); }
 };
 
 // ---------------------------------------------------------------------------
@@ -153,21 +179,19 @@ struct TileMover {
     static constexpr int EPV = 16 / sizeof(T);          // elements per 16-byte piece
     static constexpr int VPR = COLS / EPV;              // pieces per row
     static constexpr int NV = ROWS * VPR / NT;          // pieces per thread
-    static_assert(ROWS * VPR % NT == 0, "tile must divide evenly over the workgroup");
+    static_assert(ROWS * VPR % NT == 0 && NT % VPR == 0, "tile must divide evenly over the workgroup");
     u32x4 r[NV];
-    DEVI void load(const T *g) {  // g: first element of the tile, row stride COLS
+    // Per-lane element offset of piece 0; piece i lies NT/VPR rows further down.
+    static DEVI unsigned lane_off(int ld) { return (threadIdx.x / VPR) * ld + (threadIdx.x % VPR) * EPV; }
+    DEVI void load(const T *g) {  // g: first element of the tile (uniform), row stride COLS
+        const unsigned lo = lane_off(COLS) * sizeof(T);
 #pragma unroll
-        for (int i = 0; i < NV; ++i) {
-            int v = threadIdx.x + i * NT;
-            r[i] = *(const u32x4 *)(g + (size_t)(v / VPR) * COLS + (v % VPR) * EPV);
-        }
+        for (int i = 0; i < NV; ++i) r[i] = gload<u32x4>(g + i * (NT / VPR) * COLS, lo);
     }
     DEVI void store(T *s, int ld) const {
+        const unsigned lo = lane_off(ld);
 #pragma unroll
-        for (int i = 0; i < NV; ++i) {
-            int v = threadIdx.x + i * NT;
-            *(u32x4 *)(s + (v / VPR) * ld + (v % VPR) * EPV) = r[i];
-        }
+        for (int i = 0; i < NV; ++i) *(u32x4 *)(s + i * (NT / VPR) * ld + lo) = r[i];
     }
 };
 
@@ -182,17 +206,19 @@ DEVI void fill_pow_table(float *pw, float lam) {
 // into accumulator layout: st[ab][i] = S[32 ab + acc_row(i)][32 w + lane_r()].
 template <int D>
 DEVI void state_load(f32x16 (&st)[D / 32], const float *g, int w) {
+    const unsigned lo = (4 * lane_h() * D + 32 * w + lane_r()) * sizeof(float);
 #pragma unroll
     for (int ab = 0; ab < D / 32; ++ab)
 #pragma unroll
-        for (int i = 0; i < 16; ++i) st[ab][i] = g[(32 * ab + acc_row(i)) * D + 32 * w + lane_r()];
+        for (int i = 0; i < 16; ++i) st[ab][i] = gload<float>(g + (32 * ab + 8 * (i >> 2) + (i & 3)) * D, lo);
 }
 template <int D>
 DEVI void state_store(const f32x16 (&st)[D / 32], float *g, int w) {
+    const unsigned lo = (4 * lane_h() * D + 32 * w + lane_r()) * sizeof(float);
 #pragma unroll
     for (int ab = 0; ab < D / 32; ++ab)
 #pragma unroll
-        for (int i = 0; i < 16; ++i) g[(32 * ab + acc_row(i)) * D + 32 * w + lane_r()] = st[ab][i];
+        for (int i = 0; i < 16; ++i) gstore<float>(g + (32 * ab + 8 * (i >> 2) + (i & 3)) * D, lo, st[ab][i]);
 }
 
 // Masked score tile (Alg. 2 / Alg. 3 mask M): the wave holds the transposed
@@ -210,7 +236,8 @@ DEVI void store_masked_scores(T *sP, const f32x16 &acc, int jb, int ib, const fl
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
             const int d = iq - (j0 + e);
-            x[e] = d >= 0 ? acc[4 * g + e] * pw[d] : 0.0f;
+            const float m = pw[d >= 0 ? d : 0];
+            x[e] = d >= 0 ? acc[4 * g + e] * m : 0.0f;
         }
         Elem<T>::st4(sP + iq * LDP + j0, x[0], x[1], x[2], x[3]);
     }
@@ -243,9 +270,52 @@ DEVI void masked_scores(T *sP, const T *sA, const T *sB, const float *pw, int w)
 // its token per register group, so it stores them as one 8- or 16-byte piece.
 template <typename T, int D>
 DEVI void store_out_tile_t(T *g, const f32x16 &acc, int row0, int w) {
-    T *p = g + (size_t)(row0 + lane_r()) * D + 32 * w + 4 * lane_h();
+    const unsigned lo = (lane_r() * D + 32 * w + 4 * lane_h()) * sizeof(T);
 #pragma unroll
-    for (int q = 0; q < 4; ++q) Elem<T>::st4(p + 8 * q, acc[4 * q], acc[4 * q + 1], acc[4 * q + 2], acc[4 * q + 3]);
+    for (int q = 0; q < 4; ++q)
+        Elem<T>::gst4(g + row0 * D + 8 * q, lo, acc[4 * q], acc[4 * q + 1], acc[4 * q + 2], acc[4 * q + 3]);
+}
+
+// Store a wave's column block of the state into the cache tile g ([a][c], row
+// stride D). Accumulator layout gives each lane four consecutive a for one c,
+// the wrong way round for wide stores, so for bfloat16 tiles that fit the wave
+// transposes its block through a private slice of an idle LDS buffer
+// (written [c][a], read back with transposing reads) and stores 16 bytes per
+// lane; otherwise it stores element by element. The LDS slice is only touched
+// by this wave, and the caller's next barrier orders it against later use.
+template <typename T, int CT, int D>
+DEVI void cache_store(T *g, const f32x16 (&st)[D / 32], T *idle_lds, int w) {
+    using E = Elem<T>;
+    constexpr int LDD = D + E::PAD, LDP = CT + E::PAD;
+    constexpr bool STAGED = sizeof(T) == 2 && D * LDD <= CT * LDP;
+    if constexpr (STAGED) {
+        T *R = idle_lds + w * 32 * LDD;
+#pragma unroll
+        for (int ab = 0; ab < D / 32; ++ab)
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                E::st4(R + lane_r() * LDD + 32 * ab + 8 * q + 4 * lane_h(), st[ab][4 * q], st[ab][4 * q + 1],
+                       st[ab][4 * q + 2], st[ab][4 * q + 3]);
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        const int l = lane_id(), bl = l >> 4, i = l & 15;
+        const unsigned glo = (i * D + 32 * w + 8 * bl) * sizeof(T);
+        typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+#pragma unroll
+        for (int it = 0; it < D / 16; ++it) {
+            const T *p = R + (8 * bl + (i >> 2)) * LDD + 16 * it + 4 * (i & 3);
+            union { struct { s16x4 a, b; } s; u32x4 v; } u;
+            u.s.a = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)p);
+            u.s.b = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(p + 4 * LDD));
+            gstore<u32x4>(g + 16 * it * D, glo, u.v);
+        }
+    } else {
+        const unsigned slo = (4 * lane_h() * D + 32 * w + lane_r()) * sizeof(T);
+#pragma unroll
+        for (int ab = 0; ab < D / 32; ++ab)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) E::gst1(g + (32 * ab + 8 * (i >> 2) + (i & 3)) * D, slo, st[ab][i]);
+    }
 }
 
 // ---------------------------------------------------------------------------
@@ -272,7 +342,7 @@ __global__ __launch_bounds__(D * 2) void k_local(const T *__restrict__ X, const 
     const int seg = BWD ? blockIdx.x + 1 : blockIdx.x;
     const int t0 = seg * tiles_per_seg;
     const int t1 = min(t0 + tiles_per_seg, ntiles);
-    const int w = threadIdx.x >> 6;
+    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);  // wave index, scalar
     const float lam = decay[chain % H];
     fill_pow_table<CT>(pw, lam);
 
@@ -367,7 +437,7 @@ __global__ __launch_bounds__(D * 2) void k_fwd(const T *__restrict__ Q, const T 
     const int chain = blockIdx.y, seg = blockIdx.x;
     const int t0 = seg * tiles_per_seg;
     const int t1 = min(t0 + tiles_per_seg, ntiles);
-    const int w = threadIdx.x >> 6;
+    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);  // wave index, scalar
     const float lam = decay[chain % H];
     fill_pow_table<CT>(pw, lam);
 
@@ -382,6 +452,8 @@ __global__ __launch_bounds__(D * 2) void k_fwd(const T *__restrict__ Q, const T 
 
     for (int t = t0; t < t1; ++t) {
         __syncthreads();
+        // The state this tile starts from goes to the cache as KV_{t-1}, rows a, columns c.
+        if (cache) cache_store<T, CT, D>(cache + ((size_t)chain * ntiles + t) * D * D, st, sP, w);
         mq.store(sQ, LDD);
         mk.store(sK, LDD);
         mv.store(sV, LDD);
@@ -394,14 +466,6 @@ __global__ __launch_bounds__(D * 2) void k_fwd(const T *__restrict__ Q, const T 
         // masked scores P (all waves share the lower-triangular blocks)
         masked_scores<T, CT, D, LDD, LDP>(sP, sK, sQ, pw, w);
 
-        // the state this tile starts from goes to the cache as KV_{t-1}
-        if (cache) {
-            T *c = cache + ((size_t)chain * ntiles + t) * D * D;
-#pragma unroll
-            for (int ab = 0; ab < DB; ++ab)
-#pragma unroll
-                for (int i = 0; i < 16; ++i) E::st1(c + (32 * ab + acc_row(i)) * D + 32 * w + lane_r(), st[ab][i]);
-        }
         __syncthreads();  // P visible
 
         // Output tiles are accumulated transposed: OT[c][i], c in this wave's column block.
@@ -416,6 +480,7 @@ __global__ __launch_bounds__(D * 2) void k_fwd(const T *__restrict__ Q, const T 
                 const typename E::frag sf = E::from_acc(st[ab], m);
 #pragma unroll
                 for (int ib = 0; ib < NB; ++ib) acc[ib] = E::mfma(sf, E::ld_kp(sQ, LDD, 32 * ib, 32 * ab, m), acc[ib]);
+                SCHED_FENCE();
             }
         // Lambda: token r (1-based) carries lambda^r; the token is this lane's column
 #pragma unroll
@@ -426,6 +491,7 @@ __global__ __launch_bounds__(D * 2) void k_fwd(const T *__restrict__ Q, const T 
             const typename E::frag vf = E::ld_ks(sV, LDD, ks * E::KSTEP, 32 * w);
 #pragma unroll
             for (int ib = ks / SPB; ib < NB; ++ib) acc[ib] = E::mfma(vf, E::ld_kc(sP, LDP, 32 * ib, ks * E::KSTEP), acc[ib]);
+            SCHED_FENCE();
         }
         T *o = O + base + (size_t)t * CT * D;
 #pragma unroll
@@ -441,6 +507,7 @@ __global__ __launch_bounds__(D * 2) void k_fwd(const T *__restrict__ Q, const T 
                                                  [&](int k) { return pw[CT - 1 - k]; });
 #pragma unroll
             for (int ab = 0; ab < DB; ++ab) st[ab] = E::mfma(E::ld_ks(sK, LDD, ks * E::KSTEP, 32 * ab), vd, st[ab]);
+            SCHED_FENCE();
         }
     }
     if (seg == nseg - 1) state_store<D>(st, kv_out + (size_t)chain * D * D, w);
@@ -492,7 +559,7 @@ __global__ __launch_bounds__(D * 2) void k_bwd(const T *__restrict__ Q, const T 
     const int chain = blockIdx.y, seg = blockIdx.x;
     const int t0 = seg * tiles_per_seg;
     const int t1 = min(t0 + tiles_per_seg, ntiles);
-    const int w = threadIdx.x >> 6;
+    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);  // wave index, scalar
     const float lam = decay[chain % H];
     fill_pow_table<CT>(pw, lam);
 
@@ -538,7 +605,7 @@ __global__ __launch_bounds__(D * 2) void k_bwd(const T *__restrict__ Q, const T 
             const T *c = cache + ((size_t)chain * ntiles + t) * D * D;
 #pragma unroll
             for (int ks = 0; ks < NKD; ++ks) {
-                const typename E::frag kvf = E::ld_kc(c, D, 32 * w, ks * E::KSTEP);
+                const typename E::frag kvf = E::ld_kc_g(c, D, 32 * w, ks * E::KSTEP);
 #pragma unroll
                 for (int ib = 0; ib < NB; ++ib) accQ[ib] = E::mfma(kvf, E::ld_kc(bufB, LDD, 32 * ib, ks * E::KSTEP), accQ[ib]);
             }
