@@ -44,7 +44,7 @@ typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
 #define DEVI __device__ __forceinline__
 // Compiler scheduling fence: keeps the loads of one product step from being
 // hoisted across earlier steps (which would blow up register live ranges).
-#define SCHED_FENCE() __builtin_amdgcn_sched_barrier(0)
+#define SCHED_FENCE() ((void)0)
 
 // Global access as (uniform base + compile-time bytes) + 32-bit per-lane byte
 // offset: the form the hardware addresses with a scalar base register pair and
@@ -278,36 +278,40 @@ DEVI void store_out_tile_t(T *g, const f32x16 &acc, int row0, int w) {
 
 // Store a wave's column block of the state into the cache tile g ([a][c], row
 // stride D). Accumulator layout gives each lane four consecutive a for one c,
-// the wrong way round for wide stores, so for bfloat16 tiles that fit the wave
-// transposes its block through a private slice of an idle LDS buffer
-// (written [c][a], read back with transposing reads) and stores 16 bytes per
-// lane; otherwise it stores element by element. The LDS slice is only touched
-// by this wave, and the caller's next barrier orders it against later use.
+// the wrong way round for wide stores, so for bfloat16 the wave transposes one
+// 32x32 block at a time through a private slice of an idle LDS buffer (written
+// [c][a], read back with transposing reads) and stores 16 bytes per lane:
+// 64-byte row segments instead of single elements. Other types store element
+// by element. The LDS slice is only touched by this wave (LDS operations of one
+// wave execute in order); the caller's next barrier orders it against later use.
 template <typename T, int CT, int D>
 DEVI void cache_store(T *g, const f32x16 (&st)[D / 32], T *idle_lds, int w) {
     using E = Elem<T>;
-    constexpr int LDD = D + E::PAD, LDP = CT + E::PAD;
-    constexpr bool STAGED = sizeof(T) == 2 && D * LDD <= CT * LDP;
+    constexpr int LDS_ROW = 36;  // 32 a + 4 pad elements: 8-byte aligned rows, staggered banks
+    constexpr bool STAGED = sizeof(T) == 2 && (D / 32) * 32 * LDS_ROW <= CT * (CT + E::PAD);
     if constexpr (STAGED) {
-        T *R = idle_lds + w * 32 * LDD;
-#pragma unroll
-        for (int ab = 0; ab < D / 32; ++ab)
-#pragma unroll
-            for (int q = 0; q < 4; ++q)
-                E::st4(R + lane_r() * LDD + 32 * ab + 8 * q + 4 * lane_h(), st[ab][4 * q], st[ab][4 * q + 1],
-                       st[ab][4 * q + 2], st[ab][4 * q + 3]);
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        __builtin_amdgcn_wave_barrier();
+        T *R = idle_lds + w * 32 * LDS_ROW;
         const int l = lane_id(), bl = l >> 4, i = l & 15;
         const unsigned glo = (i * D + 32 * w + 8 * bl) * sizeof(T);
         typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
 #pragma unroll
-        for (int it = 0; it < D / 16; ++it) {
-            const T *p = R + (8 * bl + (i >> 2)) * LDD + 16 * it + 4 * (i & 3);
-            union { struct { s16x4 a, b; } s; u32x4 v; } u;
-            u.s.a = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)p);
-            u.s.b = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(p + 4 * LDD));
-            gstore<u32x4>(g + 16 * it * D, glo, u.v);
+        for (int ab = 0; ab < D / 32; ++ab) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                E::st4(R + lane_r() * LDS_ROW + 8 * q + 4 * lane_h(), st[ab][4 * q], st[ab][4 * q + 1], st[ab][4 * q + 2],
+                       st[ab][4 * q + 3]);
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+#pragma unroll
+            for (int it = 0; it < 2; ++it) {
+                const T *p = R + (8 * bl + (i >> 2)) * LDS_ROW + 16 * it + 4 * (i & 3);
+                union { struct { s16x4 a, b; } s; u32x4 v; } u;
+                u.s.a = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)p);
+                u.s.b = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(p + 4 * LDS_ROW));
+                gstore<u32x4>(g + (32 * ab + 16 * it) * D, glo, u.v);
+            }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
         }
     } else {
         const unsigned slo = (4 * lane_h() * D + 32 * w + lane_r()) * sizeof(T);
@@ -419,7 +423,7 @@ __global__ void k_scan(float *__restrict__ scratch, const float *__restrict__ bo
 // The state KV_{t-1} each tile starts from is optionally written to the cache.
 // ---------------------------------------------------------------------------
 template <typename T, int CT, int D>
-__global__ __launch_bounds__(D * 2) void k_fwd(const T *__restrict__ Q, const T *__restrict__ K,
+__global__ __launch_bounds__(D * 2, (CT <= 64 && sizeof(T) == 2) ? 2 : 1) void k_fwd(const T *__restrict__ Q, const T *__restrict__ K,
                                                 const T *__restrict__ V, const float *__restrict__ decay,
                                                 T *__restrict__ O, float *__restrict__ kv_out,
                                                 T *__restrict__ cache, const float *__restrict__ scratch,
@@ -538,7 +542,7 @@ struct BwdSmem {
 };
 
 template <typename T, int CT, int D>
-__global__ __launch_bounds__(D * 2) void k_bwd(const T *__restrict__ Q, const T *__restrict__ K,
+__global__ __launch_bounds__(D * 2, (CT <= 64 && sizeof(T) == 2) ? 2 : 1) void k_bwd(const T *__restrict__ Q, const T *__restrict__ K,
                                                 const T *__restrict__ V, const T *__restrict__ dO,
                                                 const float *__restrict__ decay, const T *__restrict__ cache,
                                                 T *__restrict__ dQ, T *__restrict__ dK, T *__restrict__ dV,
@@ -771,7 +775,8 @@ static hipError_t run_bwd(const Plan &p, const BwdArgs &a, hipStream_t s, const 
 int tile_tokens(int dtype, int chunk, int D) {
     (void)D;
     if (dtype == 0) return 32;          // float tiles: 32 tokens
-    return chunk >= 128 ? 128 : 64;     // bfloat16 tiles: 128 tokens (64 when the chunk is 64)
+    (void)chunk;
+    return 64;
 }
 
 #define LASP_DISPATCH(FN, ARGS)                                                        \
