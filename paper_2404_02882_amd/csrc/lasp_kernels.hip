@@ -46,6 +46,52 @@ typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
 // hoisted across earlier steps (which would blow up register live ranges).
 #define SCHED_FENCE() ((void)0)
 
+// Optional per-phase cycle accounting (diagnostic builds only, -DLASP_PHASE_TIMING):
+// thread 0 of every workgroup accumulates shader-clock cycles between PHASE marks
+// and adds them to a device-global table that lasp_debug_phases() reads back.
+#ifdef LASP_PHASE_TIMING
+__device__ unsigned long long g_phase_cycles[32];
+#define PHASE_DECL()                                   \
+    __shared__ unsigned long long ph_acc[32];          \
+    if (threadIdx.x < 32) ph_acc[threadIdx.x] = 0;     \
+    unsigned long long ph_last = clock64()
+#define PHASE(n)                                               \
+    do {                                                       \
+        unsigned long long now_ = clock64();                   \
+        if (threadIdx.x == 0) ph_acc[n] += now_ - ph_last;     \
+        ph_last = now_;                                        \
+    } while (0)
+#define PHASE_FLUSH()                                                                            \
+    do {                                                                                         \
+        __syncthreads();                                                                         \
+        if (threadIdx.x < 32) atomicAdd(&g_phase_cycles[threadIdx.x], ph_acc[threadIdx.x]);      \
+    } while (0)
+#else
+#define PHASE_DECL() ((void)0)
+#define PHASE(n) ((void)0)
+#define PHASE_FLUSH() ((void)0)
+#endif
+
+// Software pipelining of a product loop: the operand fragments of step s+1 are
+// requested before the MFMAs of step s are issued, so that LDS latency is
+// covered by matrix work of the same wave. `load(s)` returns the fragments of
+// step s, `use(s, frags)` consumes them.
+template <int N, typename Load, typename Use>
+DEVI void pipelined(Load load, Use use) {
+    auto cur = load(0);
+#pragma unroll
+    for (int s = 0; s < N; ++s) {
+        decltype(cur) nxt;
+        if (s + 1 < N) nxt = load(s + 1);
+        use(s, cur);
+        if (s + 1 < N) cur = nxt;
+    }
+}
+template <typename F>
+struct FragPair {
+    F a, b;
+};
+
 // Global access as (uniform base + compile-time bytes) + 32-bit per-lane byte
 // offset: the form the hardware addresses with a scalar base register pair and
 // one vector offset register, instead of a 64-bit address pair per access.
@@ -696,6 +742,224 @@ __global__ __launch_bounds__(D * 2, (CT <= 64 && sizeof(T) == 2) ? 2 : 1) void k
 }
 
 // ---------------------------------------------------------------------------
+// k_bwd8: the backward walk for bfloat16 tiles of 64 tokens, one workgroup of
+// 2 * D/32 waves per CU. Same mathematics as k_bwd, different residency:
+//   - all four input tiles (V, dO, K, Q), both masked score tiles and the
+//     transposed-dKV exchange buffer live in LDS at once (about 120 KB), so a
+//     tile needs three barriers instead of seven;
+//   - the waves form two row groups; wave (w, rg) owns feature block w of the
+//     outputs for the 32 tokens of block rg, so accumulators are one tile each;
+//   - both row groups keep a copy of the dKV column block w and apply the
+//     same update to it (redundant matrix work, no extra traffic), which keeps
+//     the state in registers as the operand of dV_inter.
+// ---------------------------------------------------------------------------
+template <typename T, int CT, int D>
+struct Bwd8Smem {
+    using E = Elem<T>;
+    static constexpr int LDD = D + E::PAD, LDP = CT + E::PAD;
+    static constexpr size_t TILE = (size_t)CT * LDD * sizeof(T);
+    static constexpr size_t P_OFF = 4 * TILE;
+    static constexpr size_t X_OFF = P_OFF + 2 * (size_t)CT * LDP * sizeof(T);
+    static constexpr size_t PW_OFF = X_OFF + (size_t)D * LDD * sizeof(T);
+    static constexpr size_t TOTAL = PW_OFF + (CT + 1) * sizeof(float);
+};
+
+template <typename T, int CT, int D>
+__global__ __launch_bounds__(D * 4) void k_bwd8(const T *__restrict__ Q, const T *__restrict__ K,
+                                                 const T *__restrict__ V, const T *__restrict__ dO,
+                                                 const float *__restrict__ decay, const T *__restrict__ cache,
+                                                 T *__restrict__ dQ, T *__restrict__ dK, T *__restrict__ dV,
+                                                 float *__restrict__ dkv_in, const float *__restrict__ scratch,
+                                                 int H, int ntiles, int nseg, int tiles_per_seg) {
+    using E = Elem<T>;
+    using F = typename E::frag;
+    using SM = Bwd8Smem<T, CT, D>;
+    static_assert(CT == 64, "two row groups of one 32-token block each");
+    constexpr int NT = D * 4, NW = D / 32, LDD = SM::LDD, LDP = SM::LDP, DB = D / 32, NKS = CT / E::KSTEP,
+                  NKD = D / E::KSTEP, SPB = 32 / E::KSTEP;
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    T *sV = (T *)smem;
+    T *sdO = sV + CT * LDD;
+    T *sK = sdO + CT * LDD;
+    T *sQ = sK + CT * LDD;
+    T *sS = (T *)(smem + SM::P_OFF);
+    T *sDS = sS + CT * LDP;
+    T *sX = (T *)(smem + SM::X_OFF);
+    float *pw = (float *)(smem + SM::PW_OFF);
+
+    const int chain = blockIdx.y, seg = blockIdx.x;
+    const int t0 = seg * tiles_per_seg;
+    const int t1 = min(t0 + tiles_per_seg, ntiles);
+    const int w8 = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int w = w8 % NW;    // feature block
+    const int rg = w8 / NW;   // token block
+    const float lam = decay[chain % H];
+    fill_pow_table<CT>(pw, lam);
+    PHASE_DECL();
+
+    const size_t base = (size_t)chain * ntiles * CT * D;
+    f32x16 dkv[DB];
+    state_load<D>(dkv, scratch + ((size_t)chain * nseg + seg) * D * D, w);
+
+    TileMover<T, CT, D, NT> mv, mo, mk, mq;
+    {
+        const size_t off = base + (size_t)(t1 - 1) * CT * D;
+        mv.load(V + off);
+        mo.load(dO + off);
+        mk.load(K + off);
+        mq.load(Q + off);
+    }
+
+    for (int t = t1 - 1; t >= t0; --t) {
+        const size_t off = base + (size_t)t * CT * D;
+        // rows a in w of the cached KV_{t-1}: fragments [a][c], c contiguous, straight from global
+        F kvf[NKD];
+        {
+            const T *c = cache + ((size_t)chain * ntiles + t) * D * D;
+#pragma unroll
+            for (int ks = 0; ks < NKD; ++ks) kvf[ks] = E::ld_kc_g(c, D, 32 * w, ks * E::KSTEP);
+        }
+        __syncthreads();  // previous tile fully consumed
+        PHASE(0);
+        mv.store(sV, LDD);
+        mo.store(sdO, LDD);
+        mk.store(sK, LDD);
+        mq.store(sQ, LDD);
+        if (rg == 0) {  // dKV^T into the exchange buffer: sX[c][a]
+#pragma unroll
+            for (int ab = 0; ab < DB; ++ab)
+#pragma unroll
+                for (int g = 0; g < 4; ++g)
+                    E::st4(sX + (32 * w + lane_r()) * LDD + 32 * ab + 8 * g + 4 * lane_h(), dkv[ab][4 * g],
+                           dkv[ab][4 * g + 1], dkv[ab][4 * g + 2], dkv[ab][4 * g + 3]);
+        }
+        __syncthreads();
+        PHASE(1);
+        if (t > t0) {
+            mv.load(V + off - (size_t)CT * D);
+            mo.load(dO + off - (size_t)CT * D);
+            mk.load(K + off - (size_t)CT * D);
+            mq.load(Q + off - (size_t)CT * D);
+        }
+        // masked score tiles: dS^T = V dO^T (tiles 0..2) and S^T = K Q^T (tiles 3..5), one per wave
+        {
+            constexpr int NTRI = 3;  // lower-triangular 32x32 blocks of a 64x64 tile
+            if (w8 < 2 * NTRI || NW * 2 < 2 * NTRI) {
+#pragma unroll
+                for (int idx = 0; idx < 2 * NTRI; ++idx) {
+                    if (idx % (2 * NW) != w8) continue;
+                    const int tri = idx % NTRI, ib = tri == 0 ? 0 : 1, jb = tri == 2 ? 1 : 0;
+                    const T *sA = idx < NTRI ? sV : sK, *sB = idx < NTRI ? sdO : sQ;
+                    f32x16 acc = {0}, acc2 = {0};
+                    pipelined<NKD / 2>(
+                        [&](int s2) {
+                            FragPair<FragPair<F>> f;
+                            f.a.a = E::ld_kc(sA, LDD, 32 * jb, 2 * s2 * E::KSTEP);
+                            f.a.b = E::ld_kc(sB, LDD, 32 * ib, 2 * s2 * E::KSTEP);
+                            f.b.a = E::ld_kc(sA, LDD, 32 * jb, (2 * s2 + 1) * E::KSTEP);
+                            f.b.b = E::ld_kc(sB, LDD, 32 * ib, (2 * s2 + 1) * E::KSTEP);
+                            return f;
+                        },
+                        [&](int, const FragPair<FragPair<F>> &f) {
+                            acc = E::mfma(f.a.a, f.a.b, acc);
+                            acc2 = E::mfma(f.b.a, f.b.b, acc2);
+                        });
+                    acc += acc2;
+                    store_masked_scores<T, LDP>(idx < NTRI ? sDS : sS, acc, jb, ib, pw);
+                }
+            }
+        }
+        __syncthreads();
+        PHASE(2);
+
+        const int r0 = 32 * rg;  // first token of this wave's block
+        // ---- dQ^T[a in w][i] = lambda^i sum_c KV[a][c] dO[i][c] + sum_{j<=i} K[j][a] dSm[i][j] ----
+        {
+            f32x16 acc = {0};
+            pipelined<NKD>([&](int ks) { return E::ld_kc(sdO, LDD, r0, ks * E::KSTEP); },
+                           [&](int ks, const F &b) { acc = E::mfma(kvf[ks], b, acc); });
+            acc *= pw[r0 + lane_r() + 1];
+            // keys j of blocks 0..rg
+            if (rg == 0) {
+                pipelined<SPB>(
+                    [&](int ks) { return FragPair<F>{E::ld_ks(sK, LDD, ks * E::KSTEP, 32 * w), E::ld_kc(sDS, LDP, r0, ks * E::KSTEP)}; },
+                    [&](int, const FragPair<F> &f) { acc = E::mfma(f.a, f.b, acc); });
+            } else {
+                pipelined<2 * SPB>(
+                    [&](int ks) { return FragPair<F>{E::ld_ks(sK, LDD, ks * E::KSTEP, 32 * w), E::ld_kc(sDS, LDP, r0, ks * E::KSTEP)}; },
+                    [&](int, const FragPair<F> &f) { acc = E::mfma(f.a, f.b, acc); });
+            }
+            store_out_tile_t<T, D>(dQ + off, acc, r0, w);
+        }
+        PHASE(3);
+        // ---- dK^T[a in w][j] = lambda^(CT-j) sum_c dKV[a][c] V[j][c] + sum_{i>=j} Q[i][a] dSm[i][j] ----
+        {
+            f32x16 acc = {0};
+            pipelined<NKD>(
+                [&](int ks) { return FragPair<F>{E::ld_ks(sX, LDD, ks * E::KSTEP, 32 * w), E::ld_kc(sV, LDD, r0, ks * E::KSTEP)}; },
+                [&](int, const FragPair<F> &f) { acc = E::mfma(f.a, f.b, acc); });
+            acc *= pw[CT - 1 - (r0 + lane_r())];
+            // queries i of blocks rg..1
+            if (rg == 0) {
+                pipelined<2 * SPB>(
+                    [&](int ks) { return FragPair<F>{E::ld_ks(sQ, LDD, ks * E::KSTEP, 32 * w), E::ld_ks(sDS, LDP, ks * E::KSTEP, r0)}; },
+                    [&](int, const FragPair<F> &f) { acc = E::mfma(f.a, f.b, acc); });
+            } else {
+                pipelined<SPB>(
+                    [&](int ks) { return FragPair<F>{E::ld_ks(sQ, LDD, (ks + SPB) * E::KSTEP, 32 * w), E::ld_ks(sDS, LDP, (ks + SPB) * E::KSTEP, r0)}; },
+                    [&](int, const FragPair<F> &f) { acc = E::mfma(f.a, f.b, acc); });
+            }
+            store_out_tile_t<T, D>(dK + off, acc, r0, w);
+        }
+        PHASE(4);
+        // ---- dV^T[c in w][j] = lambda^(CT-j) sum_a dKV[a][c] K[j][a] + sum_{i>=j} dO[i][c] Sm[i][j] ----
+        {
+            f32x16 acc = {0};
+            pipelined<DB * E::NSUB>([&](int s2) { return E::ld_kp(sK, LDD, r0, 32 * (s2 / E::NSUB), s2 % E::NSUB); },
+                                    [&](int s2, const F &b) { acc = E::mfma(E::from_acc(dkv[s2 / E::NSUB], s2 % E::NSUB), b, acc); });
+            acc *= pw[CT - 1 - (r0 + lane_r())];
+            if (rg == 0) {
+                pipelined<2 * SPB>(
+                    [&](int ks) { return FragPair<F>{E::ld_ks(sdO, LDD, ks * E::KSTEP, 32 * w), E::ld_ks(sS, LDP, ks * E::KSTEP, r0)}; },
+                    [&](int, const FragPair<F> &f) { acc = E::mfma(f.a, f.b, acc); });
+            } else {
+                pipelined<SPB>(
+                    [&](int ks) { return FragPair<F>{E::ld_ks(sdO, LDD, (ks + SPB) * E::KSTEP, 32 * w), E::ld_ks(sS, LDP, (ks + SPB) * E::KSTEP, r0)}; },
+                    [&](int, const FragPair<F> &f) { acc = E::mfma(f.a, f.b, acc); });
+            }
+            store_out_tile_t<T, D>(dV + off, acc, r0, w);
+        }
+        PHASE(5);
+        // ---- dKV <- lambda^CT dKV + (Lambda Q)^T dO, identically in both row groups ----
+        {
+            const float lamC = pw[CT];
+#pragma unroll
+            for (int ab = 0; ab < DB; ++ab) dkv[ab] *= lamC;
+            struct Step {
+                F dos;
+                F q[DB];
+            };
+            pipelined<NKS>(
+                [&](int ks) {
+                    Step f;
+                    f.dos = E::ld_ks(sdO, LDD, ks * E::KSTEP, 32 * w);
+#pragma unroll
+                    for (int ab = 0; ab < DB; ++ab) f.q[ab] = E::ld_ks(sQ, LDD, ks * E::KSTEP, 32 * ab);
+                    return f;
+                },
+                [&](int ks, const Step &f) {
+                    const F dos = E::scale(f.dos, ks * E::KSTEP, [&](int k) { return pw[k + 1]; });
+#pragma unroll
+                    for (int ab = 0; ab < DB; ++ab) dkv[ab] = E::mfma(f.q[ab], dos, dkv[ab]);
+                });
+        }
+        PHASE(6);
+    }
+    if (seg == 0 && rg == 0) state_store<D>(dkv, dkv_in + (size_t)chain * D * D, w);
+    PHASE_FLUSH();
+}
+
+// ---------------------------------------------------------------------------
 // Host-side launchers
 // ---------------------------------------------------------------------------
 template <typename T, int CT, int D>
@@ -762,15 +1026,37 @@ static hipError_t run_bwd(const Plan &p, const BwdArgs &a, hipStream_t s, const 
     k_scan<true><<<dim3((DD + 255) / 256, chains), dim3(256), 0, s>>>(a.scratch, a.dkv_out, a.decay, p.H, DD, p.nseg,
                                                                       p.tiles_per_seg, p.ntiles, p.tile);
     if (ke) (void)hipEventRecord(ke->ev[2], s);
-    auto kb = k_bwd<T, CT, D>;
-    if ((e = allow_lds(kb, lds_bwd)) != hipSuccess) return e;
-    kb<<<dim3(p.nseg, chains), dim3(D * 2), lds_bwd, s>>>((const T *)a.q, (const T *)a.k, (const T *)a.v,
-                                                         (const T *)a.dout, a.decay, (const T *)a.cache, (T *)a.dq,
-                                                         (T *)a.dk, (T *)a.dv, a.dkv_in, (const float *)a.scratch, p.H,
-                                                         p.ntiles, p.nseg, p.tiles_per_seg);
+    if constexpr (sizeof(T) == 2 && CT == 64) {
+        constexpr size_t lds_bwd8 = Bwd8Smem<T, CT, D>::TOTAL;
+        static_assert(lds_bwd8 <= 163840, "LDS budget of one gfx950 CU exceeded");
+        auto kb = k_bwd8<T, CT, D>;
+        if ((e = allow_lds(kb, lds_bwd8)) != hipSuccess) return e;
+        kb<<<dim3(p.nseg, chains), dim3(D * 4), lds_bwd8, s>>>((const T *)a.q, (const T *)a.k, (const T *)a.v,
+                                                               (const T *)a.dout, a.decay, (const T *)a.cache, (T *)a.dq,
+                                                               (T *)a.dk, (T *)a.dv, a.dkv_in, (const float *)a.scratch,
+                                                               p.H, p.ntiles, p.nseg, p.tiles_per_seg);
+    } else {
+        auto kb = k_bwd<T, CT, D>;
+        if ((e = allow_lds(kb, lds_bwd)) != hipSuccess) return e;
+        kb<<<dim3(p.nseg, chains), dim3(D * 2), lds_bwd, s>>>((const T *)a.q, (const T *)a.k, (const T *)a.v,
+                                                             (const T *)a.dout, a.decay, (const T *)a.cache, (T *)a.dq,
+                                                             (T *)a.dk, (T *)a.dv, a.dkv_in, (const float *)a.scratch, p.H,
+                                                             p.ntiles, p.nseg, p.tiles_per_seg);
+    }
     if (ke) (void)hipEventRecord(ke->ev[3], s);
     return hipGetLastError();
 }
+
+#ifdef LASP_PHASE_TIMING
+extern "C" int lasp_debug_phases(unsigned long long *out32, int reset) {
+    if (out32 && hipMemcpyFromSymbol(out32, HIP_SYMBOL(g_phase_cycles), sizeof(g_phase_cycles)) != hipSuccess) return 1;
+    if (reset) {
+        unsigned long long z[32] = {};
+        if (hipMemcpyToSymbol(HIP_SYMBOL(g_phase_cycles), z, sizeof(z)) != hipSuccess) return 1;
+    }
+    return 0;
+}
+#endif
 
 int tile_tokens(int dtype, int chunk, int D) {
     (void)D;

@@ -35,31 +35,36 @@ if not os.path.exists(LIB_PATH):
     raise ImportError(f"{LIB_PATH} is missing: build it first (python -c 'import __graft_entry__ as g; g.build()'). "
                       "There is no fallback path.")
 
-lib = ctypes.CDLL(LIB_PATH)
 _vp, _sz = ctypes.c_void_p, ctypes.c_size_t
 _sp = ctypes.POINTER(Shape)
-lib.lasp_version.restype = ctypes.c_int
-lib.lasp_status_str.restype = ctypes.c_char_p
-lib.lasp_status_str.argtypes = [ctypes.c_int]
-lib.lasp_check_shape.argtypes = [_sp]
-lib.lasp_check_decay.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_int32]
-lib.lasp_tile_tokens.argtypes = [_sp]
-lib.lasp_tile_tokens.restype = ctypes.c_int32
-lib.lasp_num_segments.argtypes = [_sp]
-lib.lasp_num_segments.restype = ctypes.c_int32
-lib.lasp_state_cache_bytes.argtypes = [_sp]
-lib.lasp_state_cache_bytes.restype = _sz
-lib.lasp_scratch_bytes.argtypes = [_sp]
-lib.lasp_scratch_bytes.restype = _sz
-lib.lasp_fwd.argtypes = [_sp] + [_vp] * 9 + [_sz, _vp]
-lib.lasp_fwd.restype = ctypes.c_int
-lib.lasp_bwd.argtypes = [_sp] + [_vp] * 12 + [_sz, _vp]
-lib.lasp_bwd.restype = ctypes.c_int
 
 
-lib.lasp_profile_begin.argtypes = [ctypes.c_int32]
-lib.lasp_profile_end.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int32),
-                                 ctypes.POINTER(ctypes.c_int32)]
+def _bind(handle):
+    """Declare the C signatures of include/lasp.h on a loaded library."""
+    handle.lasp_version.restype = ctypes.c_int
+    handle.lasp_status_str.restype = ctypes.c_char_p
+    handle.lasp_status_str.argtypes = [ctypes.c_int]
+    handle.lasp_check_shape.argtypes = [_sp]
+    handle.lasp_check_decay.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_int32]
+    handle.lasp_tile_tokens.argtypes = [_sp]
+    handle.lasp_tile_tokens.restype = ctypes.c_int32
+    handle.lasp_num_segments.argtypes = [_sp]
+    handle.lasp_num_segments.restype = ctypes.c_int32
+    handle.lasp_state_cache_bytes.argtypes = [_sp]
+    handle.lasp_state_cache_bytes.restype = _sz
+    handle.lasp_scratch_bytes.argtypes = [_sp]
+    handle.lasp_scratch_bytes.restype = _sz
+    handle.lasp_fwd.argtypes = [_sp] + [_vp] * 9 + [_sz, _vp]
+    handle.lasp_fwd.restype = ctypes.c_int
+    handle.lasp_bwd.argtypes = [_sp] + [_vp] * 12 + [_sz, _vp]
+    handle.lasp_bwd.restype = ctypes.c_int
+    handle.lasp_profile_begin.argtypes = [ctypes.c_int32]
+    handle.lasp_profile_end.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int32),
+                                        ctypes.POINTER(ctypes.c_int32)]
+    return handle
+
+
+lib = _bind(ctypes.CDLL(LIB_PATH))
 
 
 def profile_begin(max_calls: int) -> None:
