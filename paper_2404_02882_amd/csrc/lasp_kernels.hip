@@ -100,12 +100,23 @@ DEVI V gload(const void *base, unsigned lane_bytes) { return *(const V *)((const
 template <typename V>
 DEVI void gstore(void *base, unsigned lane_bytes, V v) { *(V *)((char *)base + lane_bytes) = v; }
 
-DEVI int lane_id() { return threadIdx.x & 63; }
-DEVI int lane_r() { return threadIdx.x & 31; }         // row / column inside a 32-wide tile
-DEVI int lane_h() { return (threadIdx.x >> 5) & 1; }   // which half of the contraction step
-
-// Row of accumulator register i (0..15) inside a 32x32 MFMA tile; the column is lane_r().
-DEVI int acc_row(int i) { return 8 * (i >> 2) + 4 * lane_h() + (i & 3); }
+// Lane coordinates inside a wave: id 0..63, r = row / column inside a 32-wide
+// tile, h = which half of an MFMA's contraction step. A Lane is rebuilt from an
+// opaque copy of the thread index at every phase of a kernel (fresh_lane), so
+// the compiler derives the LDS/global lane offsets again where they are used
+// instead of keeping dozens of loop-invariant address registers alive, which
+// would spill; a spill reload queues behind the outstanding HBM prefetch.
+struct Lane {
+    int id, r, h;
+    DEVI explicit Lane(int tid) : id(tid & 63), r(tid & 31), h((tid >> 5) & 1) {}
+    // Row of accumulator register i (0..15) inside a 32x32 MFMA tile; the column is r.
+    DEVI int acc_row(int i) const { return 8 * (i >> 2) + 4 * h + (i & 3); }
+};
+DEVI Lane fresh_lane() {
+    int t = threadIdx.x;
+    asm volatile("" : "+v"(t));
+    return Lane(t);
+}
 
 // ---------------------------------------------------------------------------
 // Element traits: how MFMA operand fragments are fetched for each data type.
@@ -129,20 +140,20 @@ struct Elem<float> {
     static constexpr int NSUB = 16;   // MFMAs per 32-wide contraction block
     static constexpr int PAD = 4;     // elements of row padding in LDS tiles
     static DEVI f32x16 mfma(frag a, frag b, f32x16 c) { return __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, c, 0, 0, 0); }
-    static DEVI frag ld_kc(const float *X, int ld, int row0, int k0) { return X[(row0 + lane_r()) * ld + k0 + lane_h()]; }
-    static DEVI frag ld_ks(const float *X, int ld, int k0, int col0) { return X[(k0 + lane_h()) * ld + col0 + lane_r()]; }
+    static DEVI frag ld_kc(const Lane &ln, const float *X, int ld, int row0, int k0) { return X[(row0 + ln.r) * ld + k0 + ln.h]; }
+    static DEVI frag ld_ks(const Lane &ln, const float *X, int ld, int k0, int col0) { return X[(k0 + ln.h) * ld + col0 + ln.r]; }
     // ld_kc from global memory: uniform tile pointer, row block row0, contraction step k0
-    static DEVI frag ld_kc_g(const float *X, int ld, int row0, int k0) {
-        return gload<float>(X + k0, ((row0 + lane_r()) * ld + lane_h()) * sizeof(float));
+    static DEVI frag ld_kc_g(const Lane &ln, const float *X, int ld, int row0, int k0) {
+        return gload<float>(X + k0, ((row0 + ln.r) * ld + ln.h) * sizeof(float));
     }
-    static DEVI frag ld_kp(const float *X, int ld, int row0, int kb, int m) {
-        return X[(row0 + lane_r()) * ld + kb + acc_row(m)];
+    static DEVI frag ld_kp(const Lane &ln, const float *X, int ld, int row0, int kb, int m) {
+        return X[(row0 + ln.r) * ld + kb + ln.acc_row(m)];
     }
     // accumulator tile -> fragment for sub-step m
     static DEVI frag from_acc(const f32x16 &t, int m) { return t[m]; }
     // multiply each contraction element k of the fragment by w[k]
     template <typename W>
-    static DEVI frag scale(frag f, int k0, W w) { return f * w(k0 + lane_h()); }
+    static DEVI frag scale(const Lane &ln, frag f, int k0, W w) { return f * w(k0 + ln.h); }
     // store 4 values of consecutive columns
     static DEVI void st4(float *p, float a, float b, float c, float d) { *(f32x4 *)p = f32x4{a, b, c, d}; }
     static DEVI void st1(float *p, float a) { *p = a; }
@@ -160,19 +171,19 @@ struct Elem<bf16_t> {
     static constexpr int NSUB = 2;
     static constexpr int PAD = 8;
     static DEVI f32x16 mfma(frag a, frag b, f32x16 c) { return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0); }
-    static DEVI frag ld_kc(const bf16_t *X, int ld, int row0, int k0) {
-        return *(const bf16x8 *)(X + (row0 + lane_r()) * ld + k0 + 8 * lane_h());
+    static DEVI frag ld_kc(const Lane &ln, const bf16_t *X, int ld, int row0, int k0) {
+        return *(const bf16x8 *)(X + (row0 + ln.r) * ld + k0 + 8 * ln.h);
     }
-    static DEVI frag ld_kc_g(const bf16_t *X, int ld, int row0, int k0) {
-        return gload<bf16x8>(X + k0, ((row0 + lane_r()) * ld + 8 * lane_h()) * sizeof(bf16_t));
+    static DEVI frag ld_kc_g(const Lane &ln, const bf16_t *X, int ld, int row0, int k0) {
+        return gload<bf16x8>(X + k0, ((row0 + ln.r) * ld + 8 * ln.h) * sizeof(bf16_t));
     }
     // LDS only: two transposing reads (ds_read_b64_tr_b16). Within each group of
     // 16 lanes, lane i ends up with element (row e, column i) of the 4 x 16 block
     // whose rows the lanes addressed in 4-element pieces.
-    static DEVI frag ld_ks(const bf16_t *X, int ld, int k0, int col0) {
-        const int l = lane_id();
+    static DEVI frag ld_ks(const Lane &ln, const bf16_t *X, int ld, int k0, int col0) {
+        const int l = ln.id;
         const int l16 = l & 15;
-        const bf16_t *p = X + (k0 + 8 * lane_h() + (l16 >> 2)) * ld + col0 + 16 * ((l >> 4) & 1) + 4 * (l16 & 3);
+        const bf16_t *p = X + (k0 + 8 * ln.h + (l16 >> 2)) * ld + col0 + 16 * ((l >> 4) & 1) + 4 * (l16 & 3);
         typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
         s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)p);
         s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(p + 4 * ld));
@@ -181,8 +192,8 @@ struct Elem<bf16_t> {
         u.s.b = hi;
         return u.v;
     }
-    static DEVI frag ld_kp(const bf16_t *X, int ld, int row0, int kb, int m) {
-        const bf16_t *p = X + (row0 + lane_r()) * ld + kb + 16 * m + 4 * lane_h();
+    static DEVI frag ld_kp(const Lane &ln, const bf16_t *X, int ld, int row0, int kb, int m) {
+        const bf16_t *p = X + (row0 + ln.r) * ld + kb + 16 * m + 4 * ln.h;
         union { struct { bf16x4 a, b; } s; bf16x8 v; } u;
         u.s.a = *(const bf16x4 *)p;
         u.s.b = *(const bf16x4 *)(p + 8);
@@ -195,10 +206,10 @@ struct Elem<bf16_t> {
         return __builtin_convertvector(x, bf16x8);
     }
     template <typename W>
-    static DEVI frag scale(frag f, int k0, W w) {
+    static DEVI frag scale(const Lane &ln, frag f, int k0, W w) {
         f32x8 x = __builtin_convertvector(f, f32x8);
 #pragma unroll
-        for (int e = 0; e < 8; ++e) x[e] *= w(k0 + 8 * lane_h() + e);
+        for (int e = 0; e < 8; ++e) x[e] *= w(k0 + 8 * ln.h + e);
         return __builtin_convertvector(x, bf16x8);
     }
     static DEVI void st4(bf16_t *p, float a, float b, float c, float d) {
@@ -249,18 +260,18 @@ DEVI void fill_pow_table(float *pw, float lam) {
 }
 
 // Load / store a wave's column block of a [D][D] float state (row-major [a][c])
-// into accumulator layout: st[ab][i] = S[32 ab + acc_row(i)][32 w + lane_r()].
+// into accumulator layout: st[ab][i] = S[32 ab + ln.acc_row(i)][32 w + ln.r].
 template <int D>
-DEVI void state_load(f32x16 (&st)[D / 32], const float *g, int w) {
-    const unsigned lo = (4 * lane_h() * D + 32 * w + lane_r()) * sizeof(float);
+DEVI void state_load(const Lane &ln, f32x16 (&st)[D / 32], const float *g, int w) {
+    const unsigned lo = (4 * ln.h * D + 32 * w + ln.r) * sizeof(float);
 #pragma unroll
     for (int ab = 0; ab < D / 32; ++ab)
 #pragma unroll
         for (int i = 0; i < 16; ++i) st[ab][i] = gload<float>(g + (32 * ab + 8 * (i >> 2) + (i & 3)) * D, lo);
 }
 template <int D>
-DEVI void state_store(const f32x16 (&st)[D / 32], float *g, int w) {
-    const unsigned lo = (4 * lane_h() * D + 32 * w + lane_r()) * sizeof(float);
+DEVI void state_store(const Lane &ln, const f32x16 (&st)[D / 32], float *g, int w) {
+    const unsigned lo = (4 * ln.h * D + 32 * w + ln.r) * sizeof(float);
 #pragma unroll
     for (int ab = 0; ab < D / 32; ++ab)
 #pragma unroll
@@ -273,11 +284,11 @@ DEVI void state_store(const f32x16 (&st)[D / 32], float *g, int w) {
 // diagonal) and writes it as P[i][j] so that four consecutive keys land in one
 // store.
 template <typename T, int LDP>
-DEVI void store_masked_scores(T *sP, const f32x16 &acc, int jb, int ib, const float *pw) {
-    const int iq = 32 * ib + lane_r();
+DEVI void store_masked_scores(const Lane &ln, T *sP, const f32x16 &acc, int jb, int ib, const float *pw) {
+    const int iq = 32 * ib + ln.r;
 #pragma unroll
     for (int g = 0; g < 4; ++g) {
-        const int j0 = 32 * jb + 8 * g + 4 * lane_h();
+        const int j0 = 32 * jb + 8 * g + 4 * ln.h;
         float x[4];
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
@@ -293,7 +304,7 @@ DEVI void store_masked_scores(T *sP, const f32x16 &acc, int jb, int ib, const fl
 // contraction index contiguous), for every lower-triangular block assigned to
 // this wave; result masked and stored to sP.
 template <typename T, int CT, int D, int LDD, int LDP>
-DEVI void masked_scores(T *sP, const T *sA, const T *sB, const float *pw, int w) {
+DEVI void masked_scores(const Lane &ln, T *sP, const T *sA, const T *sB, const float *pw, int w) {
     using E = Elem<T>;
     constexpr int NB = CT / 32, NW = D / 32;
     int idx = 0;
@@ -305,18 +316,18 @@ DEVI void masked_scores(T *sP, const T *sA, const T *sB, const float *pw, int w)
             f32x16 acc = {0};
 #pragma unroll
             for (int k0 = 0; k0 < D; k0 += E::KSTEP)
-                acc = E::mfma(E::ld_kc(sA, LDD, 32 * jb, k0), E::ld_kc(sB, LDD, 32 * ib, k0), acc);
-            store_masked_scores<T, LDP>(sP, acc, jb, ib, pw);
+                acc = E::mfma(E::ld_kc(ln, sA, LDD, 32 * jb, k0), E::ld_kc(ln, sB, LDD, 32 * ib, k0), acc);
+            store_masked_scores<T, LDP>(ln, sP, acc, jb, ib, pw);
         }
 }
 
 // Write one 32x32 accumulator tile holding the TRANSPOSE of an output block:
-// accumulator row = feature column 32 w + acc_row(i), accumulator column
+// accumulator row = feature column 32 w + ln.acc_row(i), accumulator column
 // (lane_r) = token row0 + lane_r. Each lane owns four consecutive features of
 // its token per register group, so it stores them as one 8- or 16-byte piece.
 template <typename T, int D>
-DEVI void store_out_tile_t(T *g, const f32x16 &acc, int row0, int w) {
-    const unsigned lo = (lane_r() * D + 32 * w + 4 * lane_h()) * sizeof(T);
+DEVI void store_out_tile_t(const Lane &ln, T *g, const f32x16 &acc, int row0, int w) {
+    const unsigned lo = (ln.r * D + 32 * w + 4 * ln.h) * sizeof(T);
 #pragma unroll
     for (int q = 0; q < 4; ++q)
         Elem<T>::gst4(g + row0 * D + 8 * q, lo, acc[4 * q], acc[4 * q + 1], acc[4 * q + 2], acc[4 * q + 3]);
@@ -331,20 +342,20 @@ DEVI void store_out_tile_t(T *g, const f32x16 &acc, int row0, int w) {
 // by element. The LDS slice is only touched by this wave (LDS operations of one
 // wave execute in order); the caller's next barrier orders it against later use.
 template <typename T, int CT, int D>
-DEVI void cache_store(T *g, const f32x16 (&st)[D / 32], T *idle_lds, int w) {
+DEVI void cache_store(const Lane &ln, T *g, const f32x16 (&st)[D / 32], T *idle_lds, int w) {
     using E = Elem<T>;
     constexpr int LDS_ROW = 36;  // 32 a + 4 pad elements: 8-byte aligned rows, staggered banks
     constexpr bool STAGED = sizeof(T) == 2 && (D / 32) * 32 * LDS_ROW <= CT * (CT + E::PAD);
     if constexpr (STAGED) {
         T *R = idle_lds + w * 32 * LDS_ROW;
-        const int l = lane_id(), bl = l >> 4, i = l & 15;
+        const int l = ln.id, bl = l >> 4, i = l & 15;
         const unsigned glo = (i * D + 32 * w + 8 * bl) * sizeof(T);
         typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
 #pragma unroll
         for (int ab = 0; ab < D / 32; ++ab) {
 #pragma unroll
             for (int q = 0; q < 4; ++q)
-                E::st4(R + lane_r() * LDS_ROW + 8 * q + 4 * lane_h(), st[ab][4 * q], st[ab][4 * q + 1], st[ab][4 * q + 2],
+                E::st4(R + ln.r * LDS_ROW + 8 * q + 4 * ln.h, st[ab][4 * q], st[ab][4 * q + 1], st[ab][4 * q + 2],
                        st[ab][4 * q + 3]);
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
             __builtin_amdgcn_wave_barrier();
@@ -360,7 +371,7 @@ DEVI void cache_store(T *g, const f32x16 (&st)[D / 32], T *idle_lds, int w) {
             __builtin_amdgcn_wave_barrier();
         }
     } else {
-        const unsigned slo = (4 * lane_h() * D + 32 * w + lane_r()) * sizeof(T);
+        const unsigned slo = (4 * ln.h * D + 32 * w + ln.r) * sizeof(T);
 #pragma unroll
         for (int ab = 0; ab < D / 32; ++ab)
 #pragma unroll
@@ -393,6 +404,7 @@ __global__ __launch_bounds__(D * 2) void k_local(const T *__restrict__ X, const 
     const int t0 = seg * tiles_per_seg;
     const int t1 = min(t0 + tiles_per_seg, ntiles);
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);  // wave index, scalar
+    Lane ln = fresh_lane();
     const float lam = decay[chain % H];
     fill_pow_table<CT>(pw, lam);
 
@@ -409,6 +421,7 @@ __global__ __launch_bounds__(D * 2) void k_local(const T *__restrict__ X, const 
     }
     for (int n = 0; n < t1 - t0; ++n) {
         __syncthreads();  // previous tile fully consumed (and pw visible on the first pass)
+        ln = fresh_lane();
         mx.store(sX, LDD);
         my.store(sY, LDD);
         __syncthreads();
@@ -421,18 +434,18 @@ __global__ __launch_bounds__(D * 2) void k_local(const T *__restrict__ X, const 
         typename E::frag yf[NKS];
 #pragma unroll
         for (int ks = 0; ks < NKS; ++ks) {
-            yf[ks] = E::ld_ks(sY, LDD, ks * E::KSTEP, 32 * w);
-            yf[ks] = E::scale(yf[ks], ks * E::KSTEP, [&](int k) { return BWD ? pw[k + 1] : pw[CT - 1 - k]; });
+            yf[ks] = E::ld_ks(ln, sY, LDD, ks * E::KSTEP, 32 * w);
+            yf[ks] = E::scale(ln, yf[ks], ks * E::KSTEP, [&](int k) { return BWD ? pw[k + 1] : pw[CT - 1 - k]; });
         }
 #pragma unroll
         for (int ab = 0; ab < DB; ++ab) {
             f32x16 acc = st[ab] * lamC;
 #pragma unroll
-            for (int ks = 0; ks < NKS; ++ks) acc = E::mfma(E::ld_ks(sX, LDD, ks * E::KSTEP, 32 * ab), yf[ks], acc);
+            for (int ks = 0; ks < NKS; ++ks) acc = E::mfma(E::ld_ks(ln, sX, LDD, ks * E::KSTEP, 32 * ab), yf[ks], acc);
             st[ab] = acc;
         }
     }
-    state_store<D>(st, scratch + ((size_t)chain * nseg + seg) * D * D, w);
+    state_store<D>(ln, st, scratch + ((size_t)chain * nseg + seg) * D * D, w);
 }
 
 // ---------------------------------------------------------------------------
@@ -488,12 +501,13 @@ __global__ __launch_bounds__(D * 2, (CT <= 64 && sizeof(T) == 2) ? 2 : 1) void k
     const int t0 = seg * tiles_per_seg;
     const int t1 = min(t0 + tiles_per_seg, ntiles);
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);  // wave index, scalar
+    Lane ln = fresh_lane();
     const float lam = decay[chain % H];
     fill_pow_table<CT>(pw, lam);
 
     const size_t base = (size_t)chain * ntiles * CT * D;
     f32x16 st[DB];
-    state_load<D>(st, scratch + ((size_t)chain * nseg + seg) * D * D, w);
+    state_load<D>(ln, st, scratch + ((size_t)chain * nseg + seg) * D * D, w);
 
     TileMover<T, CT, D, NT> mq, mk, mv;
     mq.load(Q + base + (size_t)t0 * CT * D);
@@ -502,8 +516,9 @@ __global__ __launch_bounds__(D * 2, (CT <= 64 && sizeof(T) == 2) ? 2 : 1) void k
 
     for (int t = t0; t < t1; ++t) {
         __syncthreads();
+        ln = fresh_lane();
         // The state this tile starts from goes to the cache as KV_{t-1}, rows a, columns c.
-        if (cache) cache_store<T, CT, D>(cache + ((size_t)chain * ntiles + t) * D * D, st, sP, w);
+        if (cache) cache_store<T, CT, D>(ln, cache + ((size_t)chain * ntiles + t) * D * D, st, sP, w);
         mq.store(sQ, LDD);
         mk.store(sK, LDD);
         mv.store(sV, LDD);
@@ -514,9 +529,10 @@ __global__ __launch_bounds__(D * 2, (CT <= 64 && sizeof(T) == 2) ? 2 : 1) void k
             mv.load(V + base + (size_t)(t + 1) * CT * D);
         }
         // masked scores P (all waves share the lower-triangular blocks)
-        masked_scores<T, CT, D, LDD, LDP>(sP, sK, sQ, pw, w);
+        masked_scores<T, CT, D, LDD, LDP>(ln, sP, sK, sQ, pw, w);
 
         __syncthreads();  // P visible
+        ln = fresh_lane();
 
         // Output tiles are accumulated transposed: OT[c][i], c in this wave's column block.
         f32x16 acc[NB];
@@ -529,38 +545,39 @@ __global__ __launch_bounds__(D * 2, (CT <= 64 && sizeof(T) == 2) ? 2 : 1) void k
             for (int m = 0; m < E::NSUB; ++m) {
                 const typename E::frag sf = E::from_acc(st[ab], m);
 #pragma unroll
-                for (int ib = 0; ib < NB; ++ib) acc[ib] = E::mfma(sf, E::ld_kp(sQ, LDD, 32 * ib, 32 * ab, m), acc[ib]);
+                for (int ib = 0; ib < NB; ++ib) acc[ib] = E::mfma(sf, E::ld_kp(ln, sQ, LDD, 32 * ib, 32 * ab, m), acc[ib]);
                 SCHED_FENCE();
             }
         // Lambda: token r (1-based) carries lambda^r; the token is this lane's column
 #pragma unroll
-        for (int ib = 0; ib < NB; ++ib) acc[ib] *= pw[32 * ib + lane_r() + 1];
+        for (int ib = 0; ib < NB; ++ib) acc[ib] *= pw[32 * ib + ln.r + 1];
         // intra: OT[c][i] += sum_{j<=i} V[j][c] P[i][j]
 #pragma unroll
         for (int ks = 0; ks < NKS; ++ks) {
-            const typename E::frag vf = E::ld_ks(sV, LDD, ks * E::KSTEP, 32 * w);
+            const typename E::frag vf = E::ld_ks(ln, sV, LDD, ks * E::KSTEP, 32 * w);
 #pragma unroll
-            for (int ib = ks / SPB; ib < NB; ++ib) acc[ib] = E::mfma(vf, E::ld_kc(sP, LDP, 32 * ib, ks * E::KSTEP), acc[ib]);
+            for (int ib = ks / SPB; ib < NB; ++ib) acc[ib] = E::mfma(vf, E::ld_kc(ln, sP, LDP, 32 * ib, ks * E::KSTEP), acc[ib]);
             SCHED_FENCE();
         }
         T *o = O + base + (size_t)t * CT * D;
 #pragma unroll
-        for (int ib = 0; ib < NB; ++ib) store_out_tile_t<T, D>(o, acc[ib], 32 * ib, w);
+        for (int ib = 0; ib < NB; ++ib) store_out_tile_t<T, D>(ln, o, acc[ib], 32 * ib, w);
 
+        ln = fresh_lane();
         // state update: KV <- lambda^CT KV + (diag{lambda^(CT-1-j)} K)^T V, weight applied to the V fragments
         const float lamC = pw[CT];
 #pragma unroll
         for (int ab = 0; ab < DB; ++ab) st[ab] *= lamC;
 #pragma unroll
         for (int ks = 0; ks < NKS; ++ks) {
-            const typename E::frag vd = E::scale(E::ld_ks(sV, LDD, ks * E::KSTEP, 32 * w), ks * E::KSTEP,
+            const typename E::frag vd = E::scale(ln, E::ld_ks(ln, sV, LDD, ks * E::KSTEP, 32 * w), ks * E::KSTEP,
                                                  [&](int k) { return pw[CT - 1 - k]; });
 #pragma unroll
-            for (int ab = 0; ab < DB; ++ab) st[ab] = E::mfma(E::ld_ks(sK, LDD, ks * E::KSTEP, 32 * ab), vd, st[ab]);
+            for (int ab = 0; ab < DB; ++ab) st[ab] = E::mfma(E::ld_ks(ln, sK, LDD, ks * E::KSTEP, 32 * ab), vd, st[ab]);
             SCHED_FENCE();
         }
     }
-    if (seg == nseg - 1) state_store<D>(st, kv_out + (size_t)chain * D * D, w);
+    if (seg == nseg - 1) state_store<D>(ln, st, kv_out + (size_t)chain * D * D, w);
 }
 
 // ---------------------------------------------------------------------------
@@ -610,12 +627,13 @@ __global__ __launch_bounds__(D * 2, (CT <= 64 && sizeof(T) == 2) ? 2 : 1) void k
     const int t0 = seg * tiles_per_seg;
     const int t1 = min(t0 + tiles_per_seg, ntiles);
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);  // wave index, scalar
+    Lane ln = fresh_lane();
     const float lam = decay[chain % H];
     fill_pow_table<CT>(pw, lam);
 
     const size_t base = (size_t)chain * ntiles * CT * D;
     f32x16 dkv[DB];
-    state_load<D>(dkv, scratch + ((size_t)chain * nseg + seg) * D * D, w);
+    state_load<D>(ln, dkv, scratch + ((size_t)chain * nseg + seg) * D * D, w);
 
     TileMover<T, CT, D, NT> ma, mb;
     ma.load(V + base + (size_t)(t1 - 1) * CT * D);
@@ -625,16 +643,17 @@ __global__ __launch_bounds__(D * 2, (CT <= 64 && sizeof(T) == 2) ? 2 : 1) void k
         const size_t off = base + (size_t)t * CT * D;
         // ---- exchange: dKV^T fragments for dK_inter (B[k = c][n = a in w]) ----
         __syncthreads();
+        ln = fresh_lane();
 #pragma unroll
         for (int ab = 0; ab < DB; ++ab)
 #pragma unroll
             for (int g = 0; g < 4; ++g)
-                E::st4(sX + (32 * w + lane_r()) * LDD + 32 * ab + 8 * g + 4 * lane_h(), dkv[ab][4 * g], dkv[ab][4 * g + 1],
+                E::st4(sX + (32 * w + ln.r) * LDD + 32 * ab + 8 * g + 4 * ln.h, dkv[ab][4 * g], dkv[ab][4 * g + 1],
                        dkv[ab][4 * g + 2], dkv[ab][4 * g + 3]);
         __syncthreads();
         typename E::frag xf[NKD];
 #pragma unroll
-        for (int ks = 0; ks < NKD; ++ks) xf[ks] = E::ld_ks(sX, LDD, ks * E::KSTEP, 32 * w);
+        for (int ks = 0; ks < NKD; ++ks) xf[ks] = E::ld_ks(ln, sX, LDD, ks * E::KSTEP, 32 * w);
         __syncthreads();
 
         // ---- step 1: V (bufA), dO (bufB) ----
@@ -644,7 +663,7 @@ __global__ __launch_bounds__(D * 2, (CT <= 64 && sizeof(T) == 2) ? 2 : 1) void k
         ma.load(K + off);
         mb.load(Q + off);
 
-        masked_scores<T, CT, D, LDD, LDP>(sDS, bufA, bufB, pw, w);  // dS^T = V dO^T
+        masked_scores<T, CT, D, LDD, LDP>(ln, sDS, bufA, bufB, pw, w);  // dS^T = V dO^T
 
         // All output tiles are accumulated transposed (feature x token), this wave's feature block.
         f32x16 accQ[NB], accK[NB];
@@ -655,27 +674,28 @@ __global__ __launch_bounds__(D * 2, (CT <= 64 && sizeof(T) == 2) ? 2 : 1) void k
             const T *c = cache + ((size_t)chain * ntiles + t) * D * D;
 #pragma unroll
             for (int ks = 0; ks < NKD; ++ks) {
-                const typename E::frag kvf = E::ld_kc_g(c, D, 32 * w, ks * E::KSTEP);
+                const typename E::frag kvf = E::ld_kc_g(ln, c, D, 32 * w, ks * E::KSTEP);
 #pragma unroll
-                for (int ib = 0; ib < NB; ++ib) accQ[ib] = E::mfma(kvf, E::ld_kc(bufB, LDD, 32 * ib, ks * E::KSTEP), accQ[ib]);
+                for (int ib = 0; ib < NB; ++ib) accQ[ib] = E::mfma(kvf, E::ld_kc(ln, bufB, LDD, 32 * ib, ks * E::KSTEP), accQ[ib]);
             }
 #pragma unroll
-            for (int ib = 0; ib < NB; ++ib) accQ[ib] *= pw[32 * ib + lane_r() + 1];
+            for (int ib = 0; ib < NB; ++ib) accQ[ib] *= pw[32 * ib + ln.r + 1];
         }
         // dK_inter^T[a][j] = lambda^(CT-j) sum_c dKV[a][c] V[j][c]
 #pragma unroll
         for (int ks = 0; ks < NKD; ++ks)
 #pragma unroll
-            for (int jb = 0; jb < NB; ++jb) accK[jb] = E::mfma(xf[ks], E::ld_kc(bufA, LDD, 32 * jb, ks * E::KSTEP), accK[jb]);
+            for (int jb = 0; jb < NB; ++jb) accK[jb] = E::mfma(xf[ks], E::ld_kc(ln, bufA, LDD, 32 * jb, ks * E::KSTEP), accK[jb]);
 #pragma unroll
-        for (int jb = 0; jb < NB; ++jb) accK[jb] *= pw[CT - 1 - (32 * jb + lane_r())];
+        for (int jb = 0; jb < NB; ++jb) accK[jb] *= pw[CT - 1 - (32 * jb + ln.r)];
         // dO fragments of this wave's column block: [k = i][n = c in w]
         typename E::frag dof[NKS];
 #pragma unroll
-        for (int ks = 0; ks < NKS; ++ks) dof[ks] = E::ld_ks(bufB, LDD, ks * E::KSTEP, 32 * w);
+        for (int ks = 0; ks < NKS; ++ks) dof[ks] = E::ld_ks(ln, bufB, LDD, ks * E::KSTEP, 32 * w);
 
         // ---- step 2: K (bufA), Q (bufB) ----
         __syncthreads();
+        ln = fresh_lane();
         ma.store(bufA, LDD);
         mb.store(bufB, LDD);
         __syncthreads();
@@ -683,27 +703,27 @@ __global__ __launch_bounds__(D * 2, (CT <= 64 && sizeof(T) == 2) ? 2 : 1) void k
             ma.load(V + off - (size_t)CT * D);
             mb.load(dO + off - (size_t)CT * D);
         }
-        masked_scores<T, CT, D, LDD, LDP>(sS, bufA, bufB, pw, w);  // S^T = K Q^T
+        masked_scores<T, CT, D, LDD, LDP>(ln, sS, bufA, bufB, pw, w);  // S^T = K Q^T
         __syncthreads();
 
         // dQ^T[a][i] += sum_{j<=i} K[j][a] dSm[i][j]
 #pragma unroll
         for (int ks = 0; ks < NKS; ++ks) {
-            const typename E::frag kf = E::ld_ks(bufA, LDD, ks * E::KSTEP, 32 * w);
+            const typename E::frag kf = E::ld_ks(ln, bufA, LDD, ks * E::KSTEP, 32 * w);
 #pragma unroll
-            for (int ib = ks / SPB; ib < NB; ++ib) accQ[ib] = E::mfma(kf, E::ld_kc(sDS, LDP, 32 * ib, ks * E::KSTEP), accQ[ib]);
+            for (int ib = ks / SPB; ib < NB; ++ib) accQ[ib] = E::mfma(kf, E::ld_kc(ln, sDS, LDP, 32 * ib, ks * E::KSTEP), accQ[ib]);
         }
 #pragma unroll
-        for (int ib = 0; ib < NB; ++ib) store_out_tile_t<T, D>(dQ + off, accQ[ib], 32 * ib, w);
+        for (int ib = 0; ib < NB; ++ib) store_out_tile_t<T, D>(ln, dQ + off, accQ[ib], 32 * ib, w);
         // dK^T[a][j] += sum_{i>=j} Q[i][a] dSm[i][j]
 #pragma unroll
         for (int ks = 0; ks < NKS; ++ks) {
-            const typename E::frag qf = E::ld_ks(bufB, LDD, ks * E::KSTEP, 32 * w);
+            const typename E::frag qf = E::ld_ks(ln, bufB, LDD, ks * E::KSTEP, 32 * w);
 #pragma unroll
-            for (int jb = 0; jb <= ks / SPB; ++jb) accK[jb] = E::mfma(qf, E::ld_ks(sDS, LDP, ks * E::KSTEP, 32 * jb), accK[jb]);
+            for (int jb = 0; jb <= ks / SPB; ++jb) accK[jb] = E::mfma(qf, E::ld_ks(ln, sDS, LDP, ks * E::KSTEP, 32 * jb), accK[jb]);
         }
 #pragma unroll
-        for (int jb = 0; jb < NB; ++jb) store_out_tile_t<T, D>(dK + off, accK[jb], 32 * jb, w);
+        for (int jb = 0; jb < NB; ++jb) store_out_tile_t<T, D>(ln, dK + off, accK[jb], 32 * jb, w);
         // dV^T[c][j] = lambda^(CT-j) sum_a dKV[a][c] K[j][a] + sum_{i>=j} dO[i][c] Sm[i][j]
         {
             f32x16 accV[NB];
@@ -715,17 +735,17 @@ __global__ __launch_bounds__(D * 2, (CT <= 64 && sizeof(T) == 2) ? 2 : 1) void k
                 for (int m = 0; m < E::NSUB; ++m) {
                     const typename E::frag df = E::from_acc(dkv[ab], m);
 #pragma unroll
-                    for (int jb = 0; jb < NB; ++jb) accV[jb] = E::mfma(df, E::ld_kp(bufA, LDD, 32 * jb, 32 * ab, m), accV[jb]);
+                    for (int jb = 0; jb < NB; ++jb) accV[jb] = E::mfma(df, E::ld_kp(ln, bufA, LDD, 32 * jb, 32 * ab, m), accV[jb]);
                 }
 #pragma unroll
-            for (int jb = 0; jb < NB; ++jb) accV[jb] *= pw[CT - 1 - (32 * jb + lane_r())];
+            for (int jb = 0; jb < NB; ++jb) accV[jb] *= pw[CT - 1 - (32 * jb + ln.r)];
 #pragma unroll
             for (int ks = 0; ks < NKS; ++ks)
 #pragma unroll
                 for (int jb = 0; jb <= ks / SPB; ++jb)
-                    accV[jb] = E::mfma(dof[ks], E::ld_ks(sS, LDP, ks * E::KSTEP, 32 * jb), accV[jb]);
+                    accV[jb] = E::mfma(dof[ks], E::ld_ks(ln, sS, LDP, ks * E::KSTEP, 32 * jb), accV[jb]);
 #pragma unroll
-            for (int jb = 0; jb < NB; ++jb) store_out_tile_t<T, D>(dV + off, accV[jb], 32 * jb, w);
+            for (int jb = 0; jb < NB; ++jb) store_out_tile_t<T, D>(ln, dV + off, accV[jb], 32 * jb, w);
         }
         // dKV <- lambda^CT dKV + (Lambda Q)^T dO  (row weight lambda^(i+1) applied to the dO fragments)
         const float lamC = pw[CT];
@@ -733,12 +753,12 @@ __global__ __launch_bounds__(D * 2, (CT <= 64 && sizeof(T) == 2) ? 2 : 1) void k
         for (int ab = 0; ab < DB; ++ab) dkv[ab] *= lamC;
 #pragma unroll
         for (int ks = 0; ks < NKS; ++ks) {
-            const typename E::frag dos = E::scale(dof[ks], ks * E::KSTEP, [&](int k) { return pw[k + 1]; });
+            const typename E::frag dos = E::scale(ln, dof[ks], ks * E::KSTEP, [&](int k) { return pw[k + 1]; });
 #pragma unroll
-            for (int ab = 0; ab < DB; ++ab) dkv[ab] = E::mfma(E::ld_ks(bufB, LDD, ks * E::KSTEP, 32 * ab), dos, dkv[ab]);
+            for (int ab = 0; ab < DB; ++ab) dkv[ab] = E::mfma(E::ld_ks(ln, bufB, LDD, ks * E::KSTEP, 32 * ab), dos, dkv[ab]);
         }
     }
-    if (seg == 0) state_store<D>(dkv, dkv_in + (size_t)chain * D * D, w);
+    if (seg == 0) state_store<D>(ln, dkv, dkv_in + (size_t)chain * D * D, w);
 }
 
 // ---------------------------------------------------------------------------
@@ -760,7 +780,8 @@ struct Bwd8Smem {
     static constexpr size_t TILE = (size_t)CT * LDD * sizeof(T);
     static constexpr size_t P_OFF = 4 * TILE;
     static constexpr size_t X_OFF = P_OFF + 2 * (size_t)CT * LDP * sizeof(T);
-    static constexpr size_t PW_OFF = X_OFF + (size_t)D * LDD * sizeof(T);
+    static constexpr size_t C_OFF = X_OFF + (size_t)D * LDD * sizeof(T);   // cached KV_{t-1} tile
+    static constexpr size_t PW_OFF = C_OFF + (size_t)D * LDD * sizeof(T);
     static constexpr size_t TOTAL = PW_OFF + (CT + 1) * sizeof(float);
 };
 
@@ -785,6 +806,7 @@ __global__ __launch_bounds__(D * 4) void k_bwd8(const T *__restrict__ Q, const T
     T *sS = (T *)(smem + SM::P_OFF);
     T *sDS = sS + CT * LDP;
     T *sX = (T *)(smem + SM::X_OFF);
+    T *sC = (T *)(smem + SM::C_OFF);
     float *pw = (float *)(smem + SM::PW_OFF);
 
     const int chain = blockIdx.y, seg = blockIdx.x;
@@ -793,21 +815,25 @@ __global__ __launch_bounds__(D * 4) void k_bwd8(const T *__restrict__ Q, const T
     const int w8 = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int w = w8 % NW;    // feature block
     const int rg = w8 / NW;   // token block
+    Lane ln = fresh_lane();
     const float lam = decay[chain % H];
     fill_pow_table<CT>(pw, lam);
     PHASE_DECL();
 
     const size_t base = (size_t)chain * ntiles * CT * D;
     f32x16 dkv[DB];
-    state_load<D>(dkv, scratch + ((size_t)chain * nseg + seg) * D * D, w);
+    state_load<D>(ln, dkv, scratch + ((size_t)chain * nseg + seg) * D * D, w);
 
     TileMover<T, CT, D, NT> mv, mo, mk, mq;
+    TileMover<T, D, D, NT> mc;  // cached state tile KV_{t-1}, [a][c]
+    const T *ctile = cache + (size_t)chain * ntiles * D * D;
     {
         const size_t off = base + (size_t)(t1 - 1) * CT * D;
         mv.load(V + off);
         mo.load(dO + off);
         mk.load(K + off);
         mq.load(Q + off);
+        mc.load(ctile + (size_t)(t1 - 1) * D * D);
     }
 
     for (int t = t1 - 1; t >= t0; --t) {
@@ -817,29 +843,33 @@ __global__ __launch_bounds__(D * 4) void k_bwd8(const T *__restrict__ Q, const T
         {
             const T *c = cache + ((size_t)chain * ntiles + t) * D * D;
 #pragma unroll
-            for (int ks = 0; ks < NKD; ++ks) kvf[ks] = E::ld_kc_g(c, D, 32 * w, ks * E::KSTEP);
+            for (int ks = 0; ks < NKD; ++ks) kvf[ks] = E::ld_kc_g(ln, c, D, 32 * w, ks * E::KSTEP);
         }
         __syncthreads();  // previous tile fully consumed
+        ln = fresh_lane();
         PHASE(0);
         mv.store(sV, LDD);
         mo.store(sdO, LDD);
         mk.store(sK, LDD);
         mq.store(sQ, LDD);
+        mc.store(sC, LDD);
         if (rg == 0) {  // dKV^T into the exchange buffer: sX[c][a]
 #pragma unroll
             for (int ab = 0; ab < DB; ++ab)
 #pragma unroll
                 for (int g = 0; g < 4; ++g)
-                    E::st4(sX + (32 * w + lane_r()) * LDD + 32 * ab + 8 * g + 4 * lane_h(), dkv[ab][4 * g],
+                    E::st4(sX + (32 * w + ln.r) * LDD + 32 * ab + 8 * g + 4 * ln.h, dkv[ab][4 * g],
                            dkv[ab][4 * g + 1], dkv[ab][4 * g + 2], dkv[ab][4 * g + 3]);
         }
         __syncthreads();
+        ln = fresh_lane();
         PHASE(1);
         if (t > t0) {
             mv.load(V + off - (size_t)CT * D);
             mo.load(dO + off - (size_t)CT * D);
             mk.load(K + off - (size_t)CT * D);
             mq.load(Q + off - (size_t)CT * D);
+            mc.load(ctile + (size_t)(t - 1) * D * D);
         }
         // masked score tiles: dS^T = V dO^T (tiles 0..2) and S^T = K Q^T (tiles 3..5), one per wave
         {
@@ -854,10 +884,10 @@ __global__ __launch_bounds__(D * 4) void k_bwd8(const T *__restrict__ Q, const T
                     pipelined<NKD / 2>(
                         [&](int s2) {
                             FragPair<FragPair<F>> f;
-                            f.a.a = E::ld_kc(sA, LDD, 32 * jb, 2 * s2 * E::KSTEP);
-                            f.a.b = E::ld_kc(sB, LDD, 32 * ib, 2 * s2 * E::KSTEP);
-                            f.b.a = E::ld_kc(sA, LDD, 32 * jb, (2 * s2 + 1) * E::KSTEP);
-                            f.b.b = E::ld_kc(sB, LDD, 32 * ib, (2 * s2 + 1) * E::KSTEP);
+                            f.a.a = E::ld_kc(ln, sA, LDD, 32 * jb, 2 * s2 * E::KSTEP);
+                            f.a.b = E::ld_kc(ln, sB, LDD, 32 * ib, 2 * s2 * E::KSTEP);
+                            f.b.a = E::ld_kc(ln, sA, LDD, 32 * jb, (2 * s2 + 1) * E::KSTEP);
+                            f.b.b = E::ld_kc(ln, sB, LDD, 32 * ib, (2 * s2 + 1) * E::KSTEP);
                             return f;
                         },
                         [&](int, const FragPair<FragPair<F>> &f) {
@@ -865,71 +895,76 @@ __global__ __launch_bounds__(D * 4) void k_bwd8(const T *__restrict__ Q, const T
                             acc2 = E::mfma(f.b.a, f.b.b, acc2);
                         });
                     acc += acc2;
-                    store_masked_scores<T, LDP>(idx < NTRI ? sDS : sS, acc, jb, ib, pw);
+                    store_masked_scores<T, LDP>(ln, idx < NTRI ? sDS : sS, acc, jb, ib, pw);
                 }
             }
         }
         __syncthreads();
+        ln = fresh_lane();
         PHASE(2);
 
         const int r0 = 32 * rg;  // first token of this wave's block
         // ---- dQ^T[a in w][i] = lambda^i sum_c KV[a][c] dO[i][c] + sum_{j<=i} K[j][a] dSm[i][j] ----
         {
             f32x16 acc = {0};
-            pipelined<NKD>([&](int ks) { return E::ld_kc(sdO, LDD, r0, ks * E::KSTEP); },
-                           [&](int ks, const F &b) { acc = E::mfma(kvf[ks], b, acc); });
-            acc *= pw[r0 + lane_r() + 1];
+            pipelined<NKD>(
+                [&](int ks) { return FragPair<F>{E::ld_kc(ln, sC, LDD, 32 * w, ks * E::KSTEP), E::ld_kc(ln, sdO, LDD, r0, ks * E::KSTEP)}; },
+                [&](int, const FragPair<F> &f) { acc = E::mfma(f.a, f.b, acc); });
+            acc *= pw[r0 + ln.r + 1];
             // keys j of blocks 0..rg
             if (rg == 0) {
                 pipelined<SPB>(
-                    [&](int ks) { return FragPair<F>{E::ld_ks(sK, LDD, ks * E::KSTEP, 32 * w), E::ld_kc(sDS, LDP, r0, ks * E::KSTEP)}; },
+                    [&](int ks) { return FragPair<F>{E::ld_ks(ln, sK, LDD, ks * E::KSTEP, 32 * w), E::ld_kc(ln, sDS, LDP, r0, ks * E::KSTEP)}; },
                     [&](int, const FragPair<F> &f) { acc = E::mfma(f.a, f.b, acc); });
             } else {
                 pipelined<2 * SPB>(
-                    [&](int ks) { return FragPair<F>{E::ld_ks(sK, LDD, ks * E::KSTEP, 32 * w), E::ld_kc(sDS, LDP, r0, ks * E::KSTEP)}; },
+                    [&](int ks) { return FragPair<F>{E::ld_ks(ln, sK, LDD, ks * E::KSTEP, 32 * w), E::ld_kc(ln, sDS, LDP, r0, ks * E::KSTEP)}; },
                     [&](int, const FragPair<F> &f) { acc = E::mfma(f.a, f.b, acc); });
             }
-            store_out_tile_t<T, D>(dQ + off, acc, r0, w);
+            store_out_tile_t<T, D>(ln, dQ + off, acc, r0, w);
         }
         PHASE(3);
+        ln = fresh_lane();
         // ---- dK^T[a in w][j] = lambda^(CT-j) sum_c dKV[a][c] V[j][c] + sum_{i>=j} Q[i][a] dSm[i][j] ----
         {
             f32x16 acc = {0};
             pipelined<NKD>(
-                [&](int ks) { return FragPair<F>{E::ld_ks(sX, LDD, ks * E::KSTEP, 32 * w), E::ld_kc(sV, LDD, r0, ks * E::KSTEP)}; },
+                [&](int ks) { return FragPair<F>{E::ld_ks(ln, sX, LDD, ks * E::KSTEP, 32 * w), E::ld_kc(ln, sV, LDD, r0, ks * E::KSTEP)}; },
                 [&](int, const FragPair<F> &f) { acc = E::mfma(f.a, f.b, acc); });
-            acc *= pw[CT - 1 - (r0 + lane_r())];
+            acc *= pw[CT - 1 - (r0 + ln.r)];
             // queries i of blocks rg..1
             if (rg == 0) {
                 pipelined<2 * SPB>(
-                    [&](int ks) { return FragPair<F>{E::ld_ks(sQ, LDD, ks * E::KSTEP, 32 * w), E::ld_ks(sDS, LDP, ks * E::KSTEP, r0)}; },
+                    [&](int ks) { return FragPair<F>{E::ld_ks(ln, sQ, LDD, ks * E::KSTEP, 32 * w), E::ld_ks(ln, sDS, LDP, ks * E::KSTEP, r0)}; },
                     [&](int, const FragPair<F> &f) { acc = E::mfma(f.a, f.b, acc); });
             } else {
                 pipelined<SPB>(
-                    [&](int ks) { return FragPair<F>{E::ld_ks(sQ, LDD, (ks + SPB) * E::KSTEP, 32 * w), E::ld_ks(sDS, LDP, (ks + SPB) * E::KSTEP, r0)}; },
+                    [&](int ks) { return FragPair<F>{E::ld_ks(ln, sQ, LDD, (ks + SPB) * E::KSTEP, 32 * w), E::ld_ks(ln, sDS, LDP, (ks + SPB) * E::KSTEP, r0)}; },
                     [&](int, const FragPair<F> &f) { acc = E::mfma(f.a, f.b, acc); });
             }
-            store_out_tile_t<T, D>(dK + off, acc, r0, w);
+            store_out_tile_t<T, D>(ln, dK + off, acc, r0, w);
         }
         PHASE(4);
+        ln = fresh_lane();
         // ---- dV^T[c in w][j] = lambda^(CT-j) sum_a dKV[a][c] K[j][a] + sum_{i>=j} dO[i][c] Sm[i][j] ----
         {
             f32x16 acc = {0};
-            pipelined<DB * E::NSUB>([&](int s2) { return E::ld_kp(sK, LDD, r0, 32 * (s2 / E::NSUB), s2 % E::NSUB); },
+            pipelined<DB * E::NSUB>([&](int s2) { return E::ld_kp(ln, sK, LDD, r0, 32 * (s2 / E::NSUB), s2 % E::NSUB); },
                                     [&](int s2, const F &b) { acc = E::mfma(E::from_acc(dkv[s2 / E::NSUB], s2 % E::NSUB), b, acc); });
-            acc *= pw[CT - 1 - (r0 + lane_r())];
+            acc *= pw[CT - 1 - (r0 + ln.r)];
             if (rg == 0) {
                 pipelined<2 * SPB>(
-                    [&](int ks) { return FragPair<F>{E::ld_ks(sdO, LDD, ks * E::KSTEP, 32 * w), E::ld_ks(sS, LDP, ks * E::KSTEP, r0)}; },
+                    [&](int ks) { return FragPair<F>{E::ld_ks(ln, sdO, LDD, ks * E::KSTEP, 32 * w), E::ld_ks(ln, sS, LDP, ks * E::KSTEP, r0)}; },
                     [&](int, const FragPair<F> &f) { acc = E::mfma(f.a, f.b, acc); });
             } else {
                 pipelined<SPB>(
-                    [&](int ks) { return FragPair<F>{E::ld_ks(sdO, LDD, (ks + SPB) * E::KSTEP, 32 * w), E::ld_ks(sS, LDP, (ks + SPB) * E::KSTEP, r0)}; },
+                    [&](int ks) { return FragPair<F>{E::ld_ks(ln, sdO, LDD, (ks + SPB) * E::KSTEP, 32 * w), E::ld_ks(ln, sS, LDP, (ks + SPB) * E::KSTEP, r0)}; },
                     [&](int, const FragPair<F> &f) { acc = E::mfma(f.a, f.b, acc); });
             }
-            store_out_tile_t<T, D>(dV + off, acc, r0, w);
+            store_out_tile_t<T, D>(ln, dV + off, acc, r0, w);
         }
         PHASE(5);
+        ln = fresh_lane();
         // ---- dKV <- lambda^CT dKV + (Lambda Q)^T dO, identically in both row groups ----
         {
             const float lamC = pw[CT];
@@ -942,20 +977,20 @@ __global__ __launch_bounds__(D * 4) void k_bwd8(const T *__restrict__ Q, const T
             pipelined<NKS>(
                 [&](int ks) {
                     Step f;
-                    f.dos = E::ld_ks(sdO, LDD, ks * E::KSTEP, 32 * w);
+                    f.dos = E::ld_ks(ln, sdO, LDD, ks * E::KSTEP, 32 * w);
 #pragma unroll
-                    for (int ab = 0; ab < DB; ++ab) f.q[ab] = E::ld_ks(sQ, LDD, ks * E::KSTEP, 32 * ab);
+                    for (int ab = 0; ab < DB; ++ab) f.q[ab] = E::ld_ks(ln, sQ, LDD, ks * E::KSTEP, 32 * ab);
                     return f;
                 },
                 [&](int ks, const Step &f) {
-                    const F dos = E::scale(f.dos, ks * E::KSTEP, [&](int k) { return pw[k + 1]; });
+                    const F dos = E::scale(ln, f.dos, ks * E::KSTEP, [&](int k) { return pw[k + 1]; });
 #pragma unroll
                     for (int ab = 0; ab < DB; ++ab) dkv[ab] = E::mfma(f.q[ab], dos, dkv[ab]);
                 });
         }
         PHASE(6);
     }
-    if (seg == 0 && rg == 0) state_store<D>(dkv, dkv_in + (size_t)chain * D * D, w);
+    if (seg == 0 && rg == 0) state_store<D>(ln, dkv, dkv_in + (size_t)chain * D * D, w);
     PHASE_FLUSH();
 }
 
