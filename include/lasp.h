@@ -78,7 +78,8 @@ int lasp_check_decay(const float *decay_host, int32_t H);
 /* Tokens per kernel tile for this shape (divides chunk); 0 on an invalid shape. */
 int32_t lasp_tile_tokens(const lasp_shape *shape);
 
-/* Segments per head the library will use for this shape; 0 on an invalid shape. */
+/* Segments per head the forward pass will use for this shape (the backward pass
+ * may choose fewer when `segments` is 0); 0 on an invalid shape. */
 int32_t lasp_num_segments(const lasp_shape *shape);
 
 /*

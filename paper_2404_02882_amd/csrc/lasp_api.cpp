@@ -11,9 +11,12 @@
 namespace {
 
 // Segments per head when the caller leaves the choice to the library: enough
-// workgroups (B*H*segments) for two per compute unit of a 256-CU device, never
-// more than one segment per tile.
-constexpr int kTargetWorkgroups = 512;
+// workgroups (B*H*segments) to fill a 256-CU device at the residency of the
+// walking kernel of each pass (forward: two 4-wave workgroups per CU; backward
+// on bfloat16: one 8-wave workgroup per CU), never more than one per tile.
+constexpr int kTargetWorkgroupsFwd = 512;
+constexpr int kTargetWorkgroupsBwd = 256;
+enum Pass { kForward = 0, kBackward = 1 };
 
 bool valid_dims(const lasp_shape *s) {
     if (!s) return false;
@@ -25,7 +28,7 @@ bool valid_dims(const lasp_shape *s) {
     return true;
 }
 
-int make_plan(const lasp_shape *s, lasp::Plan *p) {
+int make_plan(const lasp_shape *s, Pass pass, lasp::Plan *p) {
     if (!s) return LASP_ERR_NULL;
     if (s->dtype != LASP_F32 && s->dtype != LASP_BF16) return LASP_ERR_DTYPE;
     if (!valid_dims(s)) return LASP_ERR_SHAPE;
@@ -40,7 +43,8 @@ int make_plan(const lasp_shape *s, lasp::Plan *p) {
     if (want < 0 || want > p->ntiles) return LASP_ERR_SHAPE;
     if (want == 0) {
         int64_t chains = (int64_t)s->B * s->H;
-        want = (int)((kTargetWorkgroups + chains - 1) / chains);
+        const int target = (pass == kBackward && s->dtype == LASP_BF16) ? kTargetWorkgroupsBwd : kTargetWorkgroupsFwd;
+        want = (int)((target + chains - 1) / chains);
         if (want > p->ntiles) want = p->ntiles;
         if (want < 1) want = 1;
     }
@@ -92,7 +96,7 @@ const char *lasp_status_str(int status) {
 
 int lasp_check_shape(const lasp_shape *shape) {
     lasp::Plan p;
-    return make_plan(shape, &p);
+    return make_plan(shape, kForward, &p);
 }
 
 int lasp_check_decay(const float *decay_host, int32_t H) {
@@ -107,31 +111,32 @@ int lasp_check_decay(const float *decay_host, int32_t H) {
 
 int32_t lasp_tile_tokens(const lasp_shape *shape) {
     lasp::Plan p;
-    return make_plan(shape, &p) == LASP_OK ? p.tile : 0;
+    return make_plan(shape, kForward, &p) == LASP_OK ? p.tile : 0;
 }
 
 int32_t lasp_num_segments(const lasp_shape *shape) {
     lasp::Plan p;
-    return make_plan(shape, &p) == LASP_OK ? p.nseg : 0;
+    return make_plan(shape, kForward, &p) == LASP_OK ? p.nseg : 0;
 }
 
 size_t lasp_state_cache_bytes(const lasp_shape *shape) {
     lasp::Plan p;
-    if (make_plan(shape, &p) != LASP_OK) return 0;
+    if (make_plan(shape, kForward, &p) != LASP_OK) return 0;
     return (size_t)p.B * p.H * p.ntiles * p.D * p.D * elem_bytes(p.dtype);
 }
 
 size_t lasp_scratch_bytes(const lasp_shape *shape) {
-    lasp::Plan p;
-    if (make_plan(shape, &p) != LASP_OK) return 0;
-    return (size_t)p.B * p.H * p.nseg * p.D * p.D * sizeof(float);
+    lasp::Plan f, b;
+    if (make_plan(shape, kForward, &f) != LASP_OK || make_plan(shape, kBackward, &b) != LASP_OK) return 0;
+    const int nseg = f.nseg > b.nseg ? f.nseg : b.nseg;  // one buffer serves both passes
+    return (size_t)f.B * f.H * nseg * f.D * f.D * sizeof(float);
 }
 
 int lasp_fwd(const lasp_shape *shape, const void *q, const void *k, const void *v, const float *kv_in,
              const float *decay, void *out, float *kv_out, void *state_cache, void *scratch,
              size_t scratch_bytes, void *hip_stream) {
     lasp::Plan p;
-    int rc = make_plan(shape, &p);
+    int rc = make_plan(shape, kForward, &p);
     if (rc != LASP_OK) return rc;
     if (!q || !k || !v || !decay || !out || !kv_out) return LASP_ERR_NULL;
     if (!scratch || scratch_bytes < lasp_scratch_bytes(shape)) return LASP_ERR_WORKSPACE;
@@ -157,7 +162,7 @@ int lasp_bwd(const lasp_shape *shape, const void *q, const void *k, const void *
              const float *dkv_out, const float *decay, const void *state_cache, void *dq, void *dk,
              void *dv, float *dkv_in, void *scratch, size_t scratch_bytes, void *hip_stream) {
     lasp::Plan p;
-    int rc = make_plan(shape, &p);
+    int rc = make_plan(shape, kBackward, &p);
     if (rc != LASP_OK) return rc;
     if (!q || !k || !v || !dout || !decay || !state_cache || !dq || !dk || !dv || !dkv_in) return LASP_ERR_NULL;
     if (!scratch || scratch_bytes < lasp_scratch_bytes(shape)) return LASP_ERR_WORKSPACE;

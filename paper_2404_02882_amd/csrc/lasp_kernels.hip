@@ -455,22 +455,34 @@ __global__ __launch_bounds__(D * 2) void k_local(const T *__restrict__ X, const 
 // scratch[chain][j] holds local_j on entry and start_j / recv_j on exit.
 // ---------------------------------------------------------------------------
 template <bool BWD>
-__global__ void k_scan(float *__restrict__ scratch, const float *__restrict__ boundary,
-                       const float *__restrict__ decay, int H, int DD, int nseg, int tiles_per_seg,
-                       int ntiles, int tile) {
+__global__ __launch_bounds__(256) void k_scan(float *__restrict__ scratch, const float *__restrict__ boundary,
+                                              const float *__restrict__ decay, int H, int DD, int nseg,
+                                              int tiles_per_seg, int ntiles, int tile) {
     const int chain = blockIdx.y;
-    const int e = blockIdx.x * blockDim.x + threadIdx.x;
+    const int e = (blockIdx.x * blockDim.x + threadIdx.x) * 4;  // four consecutive state elements per thread
     if (e >= DD) return;
     const double l2 = log2((double)decay[chain % H]);
-    float carry = boundary ? boundary[(size_t)chain * DD + e] : 0.0f;
+    const float p_full = (float)exp2((double)(tiles_per_seg * tile) * l2);
+    const float p_last = (float)exp2((double)((ntiles - (nseg - 1) * tiles_per_seg) * tile) * l2);
+    f32x4 carry = boundary ? *(const f32x4 *)(boundary + (size_t)chain * DD + e) : f32x4{0, 0, 0, 0};
     float *s = scratch + (size_t)chain * nseg * DD + e;
-    for (int n = 0; n < nseg; ++n) {
-        const int j = BWD ? nseg - 1 - n : n;
-        const int len = (min((j + 1) * tiles_per_seg, ntiles) - j * tiles_per_seg) * tile;
-        const bool has_local = BWD ? (j > 0) : (j < nseg - 1);
-        const float local = has_local ? s[(size_t)j * DD] : 0.0f;
-        s[(size_t)j * DD] = carry;
-        carry = (float)exp2((double)len * l2) * carry + local;
+    constexpr int U = 8;  // segments whose local states are fetched together (independent loads)
+    for (int n0 = 0; n0 < nseg; n0 += U) {
+        f32x4 local[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int n = n0 + u, j = BWD ? nseg - 1 - n : n;
+            const bool has_local = n < nseg && (BWD ? (j > 0) : (j < nseg - 1));
+            local[u] = has_local ? *(const f32x4 *)(s + (size_t)j * DD) : f32x4{0, 0, 0, 0};
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int n = n0 + u, j = BWD ? nseg - 1 - n : n;
+            if (n < nseg) {
+                *(f32x4 *)(s + (size_t)j * DD) = carry;
+                carry = (j == nseg - 1 ? p_last : p_full) * carry + local[u];
+            }
+        }
     }
 }
 
@@ -1033,7 +1045,7 @@ static hipError_t run_fwd(const Plan &p, const FwdArgs &a, hipStream_t s, const 
                                                                    p.H, p.ntiles, p.nseg, p.tiles_per_seg);
     }
     if (ke) (void)hipEventRecord(ke->ev[1], s);
-    k_scan<false><<<dim3((DD + 255) / 256, chains), dim3(256), 0, s>>>(a.scratch, a.kv_in, a.decay, p.H, DD, p.nseg,
+    k_scan<false><<<dim3((DD / 4 + 255) / 256, chains), dim3(256), 0, s>>>(a.scratch, a.kv_in, a.decay, p.H, DD, p.nseg,
                                                                        p.tiles_per_seg, p.ntiles, p.tile);
     if (ke) (void)hipEventRecord(ke->ev[2], s);
     auto kf = k_fwd<T, CT, D>;
@@ -1058,7 +1070,7 @@ static hipError_t run_bwd(const Plan &p, const BwdArgs &a, hipStream_t s, const 
                                                                    a.scratch, p.H, p.ntiles, p.nseg, p.tiles_per_seg);
     }
     if (ke) (void)hipEventRecord(ke->ev[1], s);
-    k_scan<true><<<dim3((DD + 255) / 256, chains), dim3(256), 0, s>>>(a.scratch, a.dkv_out, a.decay, p.H, DD, p.nseg,
+    k_scan<true><<<dim3((DD / 4 + 255) / 256, chains), dim3(256), 0, s>>>(a.scratch, a.dkv_out, a.decay, p.H, DD, p.nseg,
                                                                       p.tiles_per_seg, p.ntiles, p.tile);
     if (ke) (void)hipEventRecord(ke->ev[2], s);
     if constexpr (sizeof(T) == 2 && CT == 64) {
