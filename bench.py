@@ -21,9 +21,11 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X published dense bf16 MFMA rate
 
-# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE /
-# WRITE_SIZE runs (profiles/), or None while not measured for this build.
-MEASURED_TRAFFIC_BYTES = {"fwd_walk": None, "bwd_walk": None}
+# HBM bytes per launch on config c3 from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
+# runs summarised in profiles/c3_fwd_bwd_kernels.md (read + written, scaled by the
+# plain-copy calibration: FETCH_SIZE x 2.000, WRITE_SIZE x 1.000). Other configs: None.
+MEASURED_TRAFFIC_BYTES_C3 = {"fwd_walk": int((416.1 + 386.5) * 2**20), "bwd_walk": int((790.3 + 385.0) * 2**20),
+                             "fwd_local": int((248.1 + 31.0) * 2**20), "bwd_local": int((240.1 + 15.0) * 2**20)}
 
 
 def main():
@@ -34,7 +36,10 @@ def main():
     ap.add_argument("--config", default="c3", help="named workload (c3 is the headline)")
     ap.add_argument("--segments", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-sample-tokens", type=int, default=8192)
+    ap.add_argument("--cpu-sample-tokens", type=int, default=32768)
+    ap.add_argument("--copy-mib", type=int, default=1024,
+                    help="size of the plain device-to-device copy timed for reference (0 = skip); under "
+                         "rocprofv3 --pmc its known size calibrates FETCH_SIZE / WRITE_SIZE")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on one GPU only (the ring of ranks is a loop over sub-sequences on one "
@@ -91,7 +96,7 @@ def main():
     achieved = dom_bytes / (per_launch_ms[dominant] * 1e-3) / 1e9
     roofline = {"kernel": dominant, "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
                 "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-                "traffic": MEASURED_TRAFFIC_BYTES.get(dominant),
+                "traffic": MEASURED_TRAFFIC_BYTES_C3.get(dominant) if (args.config == "c3" and args.segments == 0) else None,
                 "algorithmic_bytes_per_launch": dom_bytes,
                 "avg_launch_ms": round(per_launch_ms[dominant], 4),
                 "kernel_ms_per_launch": {n: round(x, 4) for n, x in per_launch_ms.items()}}
@@ -104,6 +109,26 @@ def main():
              "mfma_bf16_peak_frac": round(flops_step / step_s / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
              "min_hbm_bytes_per_step": min_bytes_step,
              "step_hbm_frac_at_min_bytes": round(min_bytes_step / step_s / 1e9 / HBM_PEAK_GBS, 4)}
+
+    # ---- plain copy of known size: measured HBM copy bandwidth (and counter calibration) ----
+    copy = None
+    if args.copy_mib > 0:
+        n = args.copy_mib * (1 << 20)
+        src = torch.empty(n, dtype=torch.uint8, device=dev).fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(10):
+            dst.copy_(src)
+        e1.record()
+        torch.cuda.synchronize()
+        copy_ms = e0.elapsed_time(e1) / 10
+        copy = {"bytes_read": n, "bytes_written": n, "ms": round(copy_ms, 4),
+                "gbs_read_plus_write": round(2 * n / (copy_ms * 1e-3) / 1e9, 1)}
+        del src, dst
 
     # ---- CPU oracle on a bounded sample of the same workload ----
     cpu = None
@@ -130,7 +155,7 @@ def main():
                                    f"T={T} sub-sequence(s), fwd+bwd",
                        "tile_tokens": tile, "segments_per_head": nseg,
                        "state_cache_bytes": seq.cache_bytes()},
-            "roofline": roofline, "whole_step": extra, "cpu_baseline": cpu}
+            "roofline": roofline, "whole_step": extra, "copy_reference": copy, "cpu_baseline": cpu}
     print(json.dumps(line), flush=True)
 
 
