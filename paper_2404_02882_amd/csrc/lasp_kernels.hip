@@ -777,13 +777,14 @@ __global__ __launch_bounds__(D * 2, (CT <= 64 && sizeof(T) == 2) ? 2 : 1) void k
 // k_bwd8: the backward walk for bfloat16 tiles of 64 tokens, one workgroup of
 // 2 * D/32 waves per CU. Same mathematics as k_bwd, different residency:
 //   - all four input tiles (V, dO, K, Q), both masked score tiles and the
-//     transposed-dKV exchange buffer live in LDS at once (about 120 KB), so a
-//     tile needs three barriers instead of seven;
-//   - the waves form two row groups; wave (w, rg) owns feature block w of the
-//     outputs for the 32 tokens of block rg, so accumulators are one tile each;
-//   - both row groups keep a copy of the dKV column block w and apply the
-//     same update to it (redundant matrix work, no extra traffic), which keeps
-//     the state in registers as the operand of dV_inter.
+//     cached KV_{t-1} tile live in LDS at once, so a tile needs three barriers;
+//   - the waves form two groups that each keep dKV in registers in the
+//     orientation their product needs, so nothing is exchanged:
+//       group 0 holds dKV[a][c in w] (rows a) and produces dV (dV_inter contracts a),
+//       group 1 holds dKV[a in w][c] (rows c) and produces dK (dK_inter contracts c);
+//     under the exchange K<->V, Q<->dO, S<->dS the two products are the same
+//     code, including the dKV update, so the groups differ only in pointers;
+//   - dQ needs only the cached state and is split by token block between them.
 // ---------------------------------------------------------------------------
 template <typename T, int CT, int D>
 struct Bwd8Smem {
@@ -791,8 +792,7 @@ struct Bwd8Smem {
     static constexpr int LDD = D + E::PAD, LDP = CT + E::PAD;
     static constexpr size_t TILE = (size_t)CT * LDD * sizeof(T);
     static constexpr size_t P_OFF = 4 * TILE;
-    static constexpr size_t X_OFF = P_OFF + 2 * (size_t)CT * LDP * sizeof(T);
-    static constexpr size_t C_OFF = X_OFF + (size_t)D * LDD * sizeof(T);   // cached KV_{t-1} tile
+    static constexpr size_t C_OFF = P_OFF + 2 * (size_t)CT * LDP * sizeof(T);   // cached KV_{t-1} tile
     static constexpr size_t PW_OFF = C_OFF + (size_t)D * LDD * sizeof(T);
     static constexpr size_t TOTAL = PW_OFF + (CT + 1) * sizeof(float);
 };
@@ -807,8 +807,8 @@ __global__ __launch_bounds__(D * 4) void k_bwd8(const T *__restrict__ Q, const T
     using E = Elem<T>;
     using F = typename E::frag;
     using SM = Bwd8Smem<T, CT, D>;
-    static_assert(CT == 64, "two row groups of one 32-token block each");
-    constexpr int NT = D * 4, NW = D / 32, LDD = SM::LDD, LDP = SM::LDP, DB = D / 32, NKS = CT / E::KSTEP,
+    static_assert(CT == 64, "two 32-token blocks per tile");
+    constexpr int NT = D * 4, NW = D / 32, LDD = SM::LDD, LDP = SM::LDP, DB = D / 32, NB = CT / 32, NKS = CT / E::KSTEP,
                   NKD = D / E::KSTEP, SPB = 32 / E::KSTEP;
     extern __shared__ __attribute__((aligned(16))) char smem[];
     T *sV = (T *)smem;
@@ -817,7 +817,6 @@ __global__ __launch_bounds__(D * 4) void k_bwd8(const T *__restrict__ Q, const T
     T *sQ = sK + CT * LDD;
     T *sS = (T *)(smem + SM::P_OFF);
     T *sDS = sS + CT * LDP;
-    T *sX = (T *)(smem + SM::X_OFF);
     T *sC = (T *)(smem + SM::C_OFF);
     float *pw = (float *)(smem + SM::PW_OFF);
 
@@ -825,16 +824,39 @@ __global__ __launch_bounds__(D * 4) void k_bwd8(const T *__restrict__ Q, const T
     const int t0 = seg * tiles_per_seg;
     const int t1 = min(t0 + tiles_per_seg, ntiles);
     const int w8 = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int w = w8 % NW;    // feature block
-    const int rg = w8 / NW;   // token block
+    const int w = w8 % NW;    // feature block of this wave's outputs
+    const int rg = w8 / NW;   // group: 0 produces dV, 1 produces dK
     Lane ln = fresh_lane();
     const float lam = decay[chain % H];
     fill_pow_table<CT>(pw, lam);
     PHASE_DECL();
 
+    // Group-dependent operands (wave-uniform selects).
+    const T *sX1 = rg ? sV : sK;     // inter operand: token rows, features contracted with the state
+    const T *sX2 = rg ? sQ : sdO;    // intra operand and state-update B operand: [token][feature in w]
+    const T *sUA = rg ? sdO : sQ;    // state-update A operand: [token][feature of the state rows]
+    const T *sPm = rg ? sDS : sS;    // masked score tile P[i][j] of this product
+    T *gOut = rg ? dK : dV;
+
     const size_t base = (size_t)chain * ntiles * CT * D;
-    f32x16 dkv[DB];
-    state_load<D>(ln, dkv, scratch + ((size_t)chain * nseg + seg) * D * D, w);
+    // st[blk][i]: group 0: dKV[32 blk + acc_row(i)][32 w + r]; group 1: dKV[32 w + r][32 blk + acc_row(i)]
+    f32x16 st[DB];
+    {
+        const float *g = scratch + ((size_t)chain * nseg + seg) * D * D;
+        if (rg == 0) {
+            state_load<D>(ln, st, g, w);
+        } else {
+            const unsigned lo = ((32 * w + ln.r) * D + 4 * ln.h) * sizeof(float);
+#pragma unroll
+            for (int cb = 0; cb < DB; ++cb)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const f32x4 x = gload<f32x4>(g + 32 * cb + 8 * q, lo);
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) st[cb][4 * q + e] = x[e];
+                }
+        }
+    }
 
     TileMover<T, CT, D, NT> mv, mo, mk, mq;
     TileMover<T, D, D, NT> mc;  // cached state tile KV_{t-1}, [a][c]
@@ -850,13 +872,6 @@ __global__ __launch_bounds__(D * 4) void k_bwd8(const T *__restrict__ Q, const T
 
     for (int t = t1 - 1; t >= t0; --t) {
         const size_t off = base + (size_t)t * CT * D;
-        // rows a in w of the cached KV_{t-1}: fragments [a][c], c contiguous, straight from global
-        F kvf[NKD];
-        {
-            const T *c = cache + ((size_t)chain * ntiles + t) * D * D;
-#pragma unroll
-            for (int ks = 0; ks < NKD; ++ks) kvf[ks] = E::ld_kc_g(ln, c, D, 32 * w, ks * E::KSTEP);
-        }
         __syncthreads();  // previous tile fully consumed
         ln = fresh_lane();
         PHASE(0);
@@ -865,14 +880,6 @@ __global__ __launch_bounds__(D * 4) void k_bwd8(const T *__restrict__ Q, const T
         mk.store(sK, LDD);
         mq.store(sQ, LDD);
         mc.store(sC, LDD);
-        if (rg == 0) {  // dKV^T into the exchange buffer: sX[c][a]
-#pragma unroll
-            for (int ab = 0; ab < DB; ++ab)
-#pragma unroll
-                for (int g = 0; g < 4; ++g)
-                    E::st4(sX + (32 * w + ln.r) * LDD + 32 * ab + 8 * g + 4 * ln.h, dkv[ab][4 * g],
-                           dkv[ab][4 * g + 1], dkv[ab][4 * g + 2], dkv[ab][4 * g + 3]);
-        }
         __syncthreads();
         ln = fresh_lane();
         PHASE(1);
@@ -886,123 +893,117 @@ __global__ __launch_bounds__(D * 4) void k_bwd8(const T *__restrict__ Q, const T
         // masked score tiles: dS^T = V dO^T (tiles 0..2) and S^T = K Q^T (tiles 3..5), one per wave
         {
             constexpr int NTRI = 3;  // lower-triangular 32x32 blocks of a 64x64 tile
-            if (w8 < 2 * NTRI || NW * 2 < 2 * NTRI) {
 #pragma unroll
-                for (int idx = 0; idx < 2 * NTRI; ++idx) {
-                    if (idx % (2 * NW) != w8) continue;
-                    const int tri = idx % NTRI, ib = tri == 0 ? 0 : 1, jb = tri == 2 ? 1 : 0;
-                    const T *sA = idx < NTRI ? sV : sK, *sB = idx < NTRI ? sdO : sQ;
-                    f32x16 acc = {0}, acc2 = {0};
-                    pipelined<NKD / 2>(
-                        [&](int s2) {
-                            FragPair<FragPair<F>> f;
-                            f.a.a = E::ld_kc(ln, sA, LDD, 32 * jb, 2 * s2 * E::KSTEP);
-                            f.a.b = E::ld_kc(ln, sB, LDD, 32 * ib, 2 * s2 * E::KSTEP);
-                            f.b.a = E::ld_kc(ln, sA, LDD, 32 * jb, (2 * s2 + 1) * E::KSTEP);
-                            f.b.b = E::ld_kc(ln, sB, LDD, 32 * ib, (2 * s2 + 1) * E::KSTEP);
-                            return f;
-                        },
-                        [&](int, const FragPair<FragPair<F>> &f) {
-                            acc = E::mfma(f.a.a, f.a.b, acc);
-                            acc2 = E::mfma(f.b.a, f.b.b, acc2);
-                        });
-                    acc += acc2;
-                    store_masked_scores<T, LDP>(ln, idx < NTRI ? sDS : sS, acc, jb, ib, pw);
-                }
+            for (int idx = 0; idx < 2 * NTRI; ++idx) {
+                if (idx % (2 * NW) != w8) continue;
+                const int tri = idx % NTRI, ib = tri == 0 ? 0 : 1, jb = tri == 2 ? 1 : 0;
+                const T *sA = idx < NTRI ? sV : sK, *sB = idx < NTRI ? sdO : sQ;
+                f32x16 acc = {0}, acc2 = {0};
+                pipelined<NKD / 2>(
+                    [&](int s2) {
+                        FragPair<FragPair<F>> f;
+                        f.a.a = E::ld_kc(ln, sA, LDD, 32 * jb, 2 * s2 * E::KSTEP);
+                        f.a.b = E::ld_kc(ln, sB, LDD, 32 * ib, 2 * s2 * E::KSTEP);
+                        f.b.a = E::ld_kc(ln, sA, LDD, 32 * jb, (2 * s2 + 1) * E::KSTEP);
+                        f.b.b = E::ld_kc(ln, sB, LDD, 32 * ib, (2 * s2 + 1) * E::KSTEP);
+                        return f;
+                    },
+                    [&](int, const FragPair<FragPair<F>> &f) {
+                        acc = E::mfma(f.a.a, f.a.b, acc);
+                        acc2 = E::mfma(f.b.a, f.b.b, acc2);
+                    });
+                acc += acc2;
+                store_masked_scores<T, LDP>(ln, idx < NTRI ? sDS : sS, acc, jb, ib, pw);
             }
         }
         __syncthreads();
         ln = fresh_lane();
         PHASE(2);
 
-        const int r0 = 32 * rg;  // first token of this wave's block
-        // ---- dQ^T[a in w][i] = lambda^i sum_c KV[a][c] dO[i][c] + sum_{j<=i} K[j][a] dSm[i][j] ----
+        // ---- dQ^T[a in w][i], tokens i of block rg:
+        //      lambda^i sum_c KV_{t-1}[a][c] dO[i][c] + sum_{j<=i} K[j][a] dSm[i][j] ----
         {
+            const int r0 = 32 * rg;
             f32x16 acc = {0};
             pipelined<NKD>(
                 [&](int ks) { return FragPair<F>{E::ld_kc(ln, sC, LDD, 32 * w, ks * E::KSTEP), E::ld_kc(ln, sdO, LDD, r0, ks * E::KSTEP)}; },
                 [&](int, const FragPair<F> &f) { acc = E::mfma(f.a, f.b, acc); });
             acc *= pw[r0 + ln.r + 1];
-            // keys j of blocks 0..rg
-            if (rg == 0) {
-                pipelined<SPB>(
-                    [&](int ks) { return FragPair<F>{E::ld_ks(ln, sK, LDD, ks * E::KSTEP, 32 * w), E::ld_kc(ln, sDS, LDP, r0, ks * E::KSTEP)}; },
-                    [&](int, const FragPair<F> &f) { acc = E::mfma(f.a, f.b, acc); });
-            } else {
-                pipelined<2 * SPB>(
-                    [&](int ks) { return FragPair<F>{E::ld_ks(ln, sK, LDD, ks * E::KSTEP, 32 * w), E::ld_kc(ln, sDS, LDP, r0, ks * E::KSTEP)}; },
-                    [&](int, const FragPair<F> &f) { acc = E::mfma(f.a, f.b, acc); });
-            }
+            auto intra = [&](int ks) { return FragPair<F>{E::ld_ks(ln, sK, LDD, ks * E::KSTEP, 32 * w), E::ld_kc(ln, sDS, LDP, r0, ks * E::KSTEP)}; };
+            auto fma = [&](int, const FragPair<F> &f) { acc = E::mfma(f.a, f.b, acc); };
+            if (rg == 0) pipelined<SPB>(intra, fma);        // keys of block 0
+            else pipelined<2 * SPB>(intra, fma);            // keys of blocks 0 and 1
             store_out_tile_t<T, D>(ln, dQ + off, acc, r0, w);
         }
         PHASE(3);
         ln = fresh_lane();
-        // ---- dK^T[a in w][j] = lambda^(CT-j) sum_c dKV[a][c] V[j][c] + sum_{i>=j} Q[i][a] dSm[i][j] ----
+        // ---- this group's product, both token blocks j (written for dV; dK is the same under K<->V, Q<->dO, S<->dS):
+        //      dV^T[c in w][j] = lambda^(CT-j) sum_a dKV[a][c] K[j][a] + sum_{i>=j} dO[i][c] Sm[i][j] ----
         {
-            f32x16 acc = {0};
-            pipelined<NKD>(
-                [&](int ks) { return FragPair<F>{E::ld_ks(ln, sX, LDD, ks * E::KSTEP, 32 * w), E::ld_kc(ln, sV, LDD, r0, ks * E::KSTEP)}; },
-                [&](int, const FragPair<F> &f) { acc = E::mfma(f.a, f.b, acc); });
-            acc *= pw[CT - 1 - (r0 + ln.r)];
-            // queries i of blocks rg..1
-            if (rg == 0) {
-                pipelined<2 * SPB>(
-                    [&](int ks) { return FragPair<F>{E::ld_ks(ln, sQ, LDD, ks * E::KSTEP, 32 * w), E::ld_ks(ln, sDS, LDP, ks * E::KSTEP, r0)}; },
-                    [&](int, const FragPair<F> &f) { acc = E::mfma(f.a, f.b, acc); });
-            } else {
-                pipelined<SPB>(
-                    [&](int ks) { return FragPair<F>{E::ld_ks(ln, sQ, LDD, (ks + SPB) * E::KSTEP, 32 * w), E::ld_ks(ln, sDS, LDP, (ks + SPB) * E::KSTEP, r0)}; },
-                    [&](int, const FragPair<F> &f) { acc = E::mfma(f.a, f.b, acc); });
-            }
-            store_out_tile_t<T, D>(ln, dK + off, acc, r0, w);
+            f32x16 acc[NB];
+#pragma unroll
+            for (int jb = 0; jb < NB; ++jb) acc[jb] = f32x16{0};
+            struct Two { F b[NB]; };
+            pipelined<DB * E::NSUB>(
+                [&](int s2) {
+                    Two f;
+#pragma unroll
+                    for (int jb = 0; jb < NB; ++jb) f.b[jb] = E::ld_kp(ln, sX1, LDD, 32 * jb, 32 * (s2 / E::NSUB), s2 % E::NSUB);
+                    return f;
+                },
+                [&](int s2, const Two &f) {
+                    const F sf = E::from_acc(st[s2 / E::NSUB], s2 % E::NSUB);
+#pragma unroll
+                    for (int jb = 0; jb < NB; ++jb) acc[jb] = E::mfma(sf, f.b[jb], acc[jb]);
+                });
+#pragma unroll
+            for (int jb = 0; jb < NB; ++jb) acc[jb] *= pw[CT - 1 - (32 * jb + ln.r)];
+            struct Three { F a; F b[NB]; };
+            pipelined<NKS>(
+                [&](int ks) {
+                    Three f;
+                    f.a = E::ld_ks(ln, sX2, LDD, ks * E::KSTEP, 32 * w);
+#pragma unroll
+                    for (int jb = 0; jb < NB; ++jb)
+                        if (jb <= ks / SPB) f.b[jb] = E::ld_ks(ln, sPm, LDP, ks * E::KSTEP, 32 * jb);
+                    return f;
+                },
+                [&](int ks, const Three &f) {
+#pragma unroll
+                    for (int jb = 0; jb < NB; ++jb)
+                        if (jb <= ks / SPB) acc[jb] = E::mfma(f.a, f.b[jb], acc[jb]);
+                });
+#pragma unroll
+            for (int jb = 0; jb < NB; ++jb) store_out_tile_t<T, D>(ln, gOut + off, acc[jb], 32 * jb, w);
         }
         PHASE(4);
         ln = fresh_lane();
-        // ---- dV^T[c in w][j] = lambda^(CT-j) sum_a dKV[a][c] K[j][a] + sum_{i>=j} dO[i][c] Sm[i][j] ----
-        {
-            f32x16 acc = {0};
-            pipelined<DB * E::NSUB>([&](int s2) { return E::ld_kp(ln, sK, LDD, r0, 32 * (s2 / E::NSUB), s2 % E::NSUB); },
-                                    [&](int s2, const F &b) { acc = E::mfma(E::from_acc(dkv[s2 / E::NSUB], s2 % E::NSUB), b, acc); });
-            acc *= pw[CT - 1 - (r0 + ln.r)];
-            if (rg == 0) {
-                pipelined<2 * SPB>(
-                    [&](int ks) { return FragPair<F>{E::ld_ks(ln, sdO, LDD, ks * E::KSTEP, 32 * w), E::ld_ks(ln, sS, LDP, ks * E::KSTEP, r0)}; },
-                    [&](int, const FragPair<F> &f) { acc = E::mfma(f.a, f.b, acc); });
-            } else {
-                pipelined<SPB>(
-                    [&](int ks) { return FragPair<F>{E::ld_ks(ln, sdO, LDD, (ks + SPB) * E::KSTEP, 32 * w), E::ld_ks(ln, sS, LDP, (ks + SPB) * E::KSTEP, r0)}; },
-                    [&](int, const FragPair<F> &f) { acc = E::mfma(f.a, f.b, acc); });
-            }
-            store_out_tile_t<T, D>(ln, dV + off, acc, r0, w);
-        }
-        PHASE(5);
-        ln = fresh_lane();
-        // ---- dKV <- lambda^CT dKV + (Lambda Q)^T dO, identically in both row groups ----
+        // ---- state update in this group's orientation (group 0: dKV <- lambda^CT dKV + (Lambda Q)^T dO) ----
         {
             const float lamC = pw[CT];
 #pragma unroll
-            for (int ab = 0; ab < DB; ++ab) dkv[ab] *= lamC;
+            for (int blk = 0; blk < DB; ++blk) st[blk] *= lamC;
             struct Step {
-                F dos;
-                F q[DB];
+                F b;
+                F a[DB];
             };
             pipelined<NKS>(
                 [&](int ks) {
                     Step f;
-                    f.dos = E::ld_ks(ln, sdO, LDD, ks * E::KSTEP, 32 * w);
+                    f.b = E::ld_ks(ln, sX2, LDD, ks * E::KSTEP, 32 * w);
 #pragma unroll
-                    for (int ab = 0; ab < DB; ++ab) f.q[ab] = E::ld_ks(ln, sQ, LDD, ks * E::KSTEP, 32 * ab);
+                    for (int blk = 0; blk < DB; ++blk) f.a[blk] = E::ld_ks(ln, sUA, LDD, ks * E::KSTEP, 32 * blk);
                     return f;
                 },
                 [&](int ks, const Step &f) {
-                    const F dos = E::scale(ln, f.dos, ks * E::KSTEP, [&](int k) { return pw[k + 1]; });
+                    const F bs = E::scale(ln, f.b, ks * E::KSTEP, [&](int k) { return pw[k + 1]; });
 #pragma unroll
-                    for (int ab = 0; ab < DB; ++ab) dkv[ab] = E::mfma(f.q[ab], dos, dkv[ab]);
+                    for (int blk = 0; blk < DB; ++blk) st[blk] = E::mfma(f.a[blk], bs, st[blk]);
                 });
         }
-        PHASE(6);
+        PHASE(5);
     }
-    if (seg == 0 && rg == 0) state_store<D>(ln, dkv, dkv_in + (size_t)chain * D * D, w);
+    if (seg == 0 && rg == 0) state_store<D>(ln, st, dkv_in + (size_t)chain * D * D, w);
     PHASE_FLUSH();
 }
 
