@@ -154,6 +154,10 @@ struct Elem<float> {
     // multiply each contraction element k of the fragment by w[k]
     template <typename W>
     static DEVI frag scale(const Lane &ln, frag f, int k0, W w) { return f * w(k0 + ln.h); }
+    // Elements per lane of one fragment, and the geometric form of a row weight:
+    // every contraction element e of the fragment is multiplied by a * g[e].
+    static constexpr int KH = 1;
+    static DEVI frag scale_geo(frag f, float a, const float (&g)[8]) { return f * (a * g[0]); }
     // store 4 values of consecutive columns
     static DEVI void st4(float *p, float a, float b, float c, float d) { *(f32x4 *)p = f32x4{a, b, c, d}; }
     static DEVI void st1(float *p, float a) { *p = a; }
@@ -169,7 +173,7 @@ struct Elem<bf16_t> {
     typedef bf16x8 frag;
     static constexpr int KSTEP = 16;
     static constexpr int NSUB = 2;
-    static constexpr int PAD = 8;
+    static constexpr int PAD = 24;  // row stride = 12 banks mod 64: conflict-free 16-byte row reads, disjoint 4-row transposing reads
     static DEVI f32x16 mfma(frag a, frag b, f32x16 c) { return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0); }
     static DEVI frag ld_kc(const Lane &ln, const bf16_t *X, int ld, int row0, int k0) {
         return *(const bf16x8 *)(X + (row0 + ln.r) * ld + k0 + 8 * ln.h);
@@ -210,6 +214,13 @@ struct Elem<bf16_t> {
         f32x8 x = __builtin_convertvector(f, f32x8);
 #pragma unroll
         for (int e = 0; e < 8; ++e) x[e] *= w(k0 + 8 * ln.h + e);
+        return __builtin_convertvector(x, bf16x8);
+    }
+    static constexpr int KH = 8;
+    static DEVI frag scale_geo(frag f, float a, const float (&g)[8]) {
+        f32x8 x = __builtin_convertvector(f, f32x8);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) x[e] *= a * g[e];
         return __builtin_convertvector(x, bf16x8);
     }
     static DEVI void st4(bf16_t *p, float a, float b, float c, float d) {
@@ -405,47 +416,87 @@ __global__ __launch_bounds__(D * 2) void k_local(const T *__restrict__ X, const 
     const int t1 = min(t0 + tiles_per_seg, ntiles);
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);  // wave index, scalar
     Lane ln = fresh_lane();
+    PHASE_DECL();
+    const size_t base = (size_t)chain * ntiles * CT * D;
+    const int ntl = t1 - t0;
+    auto tile_of = [&](int n) { return BWD ? t1 - 1 - n : t0 + n; };
+    // the first tile is requested before anything else so that its latency covers the set-up
+    TileMover<T, CT, D, NT> mx, my;
+    mx.load(X + base + (size_t)tile_of(0) * CT * D);
+    my.load(Y + base + (size_t)tile_of(0) * CT * D);
+    PHASE(22);
     const float lam = decay[chain % H];
     fill_pow_table<CT>(pw, lam);
-
-    const size_t base = (size_t)chain * ntiles * CT * D;
     f32x16 st[DB];
 #pragma unroll
     for (int ab = 0; ab < DB; ++ab) st[ab] = f32x16{0};
-
-    TileMover<T, CT, D, NT> mx, my;
-    {
-        const int t = BWD ? t1 - 1 : t0;
-        mx.load(X + base + (size_t)t * CT * D);
-        my.load(Y + base + (size_t)t * CT * D);
-    }
-    for (int n = 0; n < t1 - t0; ++n) {
+    const float l2f = (float)log2((double)lam);
+    float geo[8];  // uniform: lambda^(KH-1-e) forward, lambda^e backward
+#pragma unroll
+    for (int e = 0; e < 8; ++e) geo[e] = e < E::KH ? exp2f((float)(BWD ? e : E::KH - 1 - e) * l2f) : 1.0f;
+    PHASE(23);
+    for (int n = 0; n < ntl; ++n) {
         __syncthreads();  // previous tile fully consumed (and pw visible on the first pass)
         ln = fresh_lane();
+        PHASE(24);
         mx.store(sX, LDD);
         my.store(sY, LDD);
+        PHASE(25);
         __syncthreads();
-        if (n + 1 < t1 - t0) {
-            const int t = BWD ? t1 - 2 - n : t0 + n + 1;
-            mx.load(X + base + (size_t)t * CT * D);
-            my.load(Y + base + (size_t)t * CT * D);
+        PHASE(26);
+        if (n + 1 < ntl) {
+            mx.load(X + base + (size_t)tile_of(n + 1) * CT * D);
+            my.load(Y + base + (size_t)tile_of(n + 1) * CT * D);
         }
-        const float lamC = pw[CT];
-        typename E::frag yf[NKS];
+        PHASE(27);
+        // Token weight relative to the whole segment, so the accumulators are never rescaled:
+        // forward lambda^(tokens after it in the segment), backward lambda^(its 1-based position).
+        // It factors as (tile factor) * (table entry of the lane's first element) * g[e].
+        const float tile_factor = exp2f((float)((ntl - 1 - n) * CT) * l2f);  // tiles between this one and the segment edge
+        auto weight_of = [&](int ks) {
+            const int k_first = ks * E::KSTEP + E::KH * ln.h;  // lane's first token of this fragment
+            return tile_factor * (BWD ? pw[k_first + 1] : pw[CT - E::KH - k_first]);
+        };
+        if constexpr (NKS * (1 + DB) * sizeof(typename E::frag) <= 80 * 4) {
+            // small tiles: request every operand fragment at once (one exposed LDS latency per tile)
+            typename E::frag yf[NKS], xf[NKS][DB];
 #pragma unroll
-        for (int ks = 0; ks < NKS; ++ks) {
-            yf[ks] = E::ld_ks(ln, sY, LDD, ks * E::KSTEP, 32 * w);
-            yf[ks] = E::scale(ln, yf[ks], ks * E::KSTEP, [&](int k) { return BWD ? pw[k + 1] : pw[CT - 1 - k]; });
+            for (int ks = 0; ks < NKS; ++ks) {
+                yf[ks] = E::ld_ks(ln, sY, LDD, ks * E::KSTEP, 32 * w);
+#pragma unroll
+                for (int ab = 0; ab < DB; ++ab) xf[ks][ab] = E::ld_ks(ln, sX, LDD, ks * E::KSTEP, 32 * ab);
+            }
+#pragma unroll
+            for (int ks = 0; ks < NKS; ++ks) {
+                const typename E::frag yd = E::scale_geo(yf[ks], weight_of(ks), geo);
+#pragma unroll
+                for (int ab = 0; ab < DB; ++ab) st[ab] = E::mfma(xf[ks][ab], yd, st[ab]);
+            }
+        } else {
+            struct Step {
+                typename E::frag y;
+                typename E::frag x[DB];
+            };
+            pipelined<NKS>(
+                [&](int ks) {
+                    Step f;
+                    f.y = E::ld_ks(ln, sY, LDD, ks * E::KSTEP, 32 * w);
+#pragma unroll
+                    for (int ab = 0; ab < DB; ++ab) f.x[ab] = E::ld_ks(ln, sX, LDD, ks * E::KSTEP, 32 * ab);
+                    return f;
+                },
+                [&](int ks, const Step &f) {
+                    const typename E::frag yd = E::scale_geo(f.y, weight_of(ks), geo);
+#pragma unroll
+                    for (int ab = 0; ab < DB; ++ab) st[ab] = E::mfma(f.x[ab], yd, st[ab]);
+                });
         }
-#pragma unroll
-        for (int ab = 0; ab < DB; ++ab) {
-            f32x16 acc = st[ab] * lamC;
-#pragma unroll
-            for (int ks = 0; ks < NKS; ++ks) acc = E::mfma(E::ld_ks(ln, sX, LDD, ks * E::KSTEP, 32 * ab), yf[ks], acc);
-            st[ab] = acc;
-        }
+        PHASE(28);
     }
+    PHASE(29);
     state_store<D>(ln, st, scratch + ((size_t)chain * nseg + seg) * D * D, w);
+    PHASE(30);
+    PHASE_FLUSH();
 }
 
 // ---------------------------------------------------------------------------
@@ -514,17 +565,16 @@ __global__ __launch_bounds__(D * 2, (CT <= 64 && sizeof(T) == 2) ? 2 : 1) void k
     const int t1 = min(t0 + tiles_per_seg, ntiles);
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);  // wave index, scalar
     Lane ln = fresh_lane();
-    const float lam = decay[chain % H];
-    fill_pow_table<CT>(pw, lam);
-
+    // requests first (tile, then start state), table arithmetic while they fly
     const size_t base = (size_t)chain * ntiles * CT * D;
-    f32x16 st[DB];
-    state_load<D>(ln, st, scratch + ((size_t)chain * nseg + seg) * D * D, w);
-
     TileMover<T, CT, D, NT> mq, mk, mv;
     mq.load(Q + base + (size_t)t0 * CT * D);
     mk.load(K + base + (size_t)t0 * CT * D);
     mv.load(V + base + (size_t)t0 * CT * D);
+    f32x16 st[DB];
+    state_load<D>(ln, st, scratch + ((size_t)chain * nseg + seg) * D * D, w);
+    const float lam = decay[chain % H];
+    fill_pow_table<CT>(pw, lam);
 
     for (int t = t0; t < t1; ++t) {
         __syncthreads();
@@ -827,9 +877,23 @@ __global__ __launch_bounds__(D * 4) void k_bwd8(const T *__restrict__ Q, const T
     const int w = w8 % NW;    // feature block of this wave's outputs
     const int rg = w8 / NW;   // group: 0 produces dV, 1 produces dK
     Lane ln = fresh_lane();
+    PHASE_DECL();
+
+    // requests first (last tile of the segment, its cached state), set-up arithmetic while they fly
+    const size_t base = (size_t)chain * ntiles * CT * D;
+    TileMover<T, CT, D, NT> mv, mo, mk, mq;
+    TileMover<T, D, D, NT> mc;  // cached state tile KV_{t-1}, [a][c]
+    const T *ctile = cache + (size_t)chain * ntiles * D * D;
+    {
+        const size_t off = base + (size_t)(t1 - 1) * CT * D;
+        mv.load(V + off);
+        mo.load(dO + off);
+        mk.load(K + off);
+        mq.load(Q + off);
+        mc.load(ctile + (size_t)(t1 - 1) * D * D);
+    }
     const float lam = decay[chain % H];
     fill_pow_table<CT>(pw, lam);
-    PHASE_DECL();
 
     // Group-dependent operands (wave-uniform selects).
     const T *sX1 = rg ? sV : sK;     // inter operand: token rows, features contracted with the state
@@ -838,7 +902,6 @@ __global__ __launch_bounds__(D * 4) void k_bwd8(const T *__restrict__ Q, const T
     const T *sPm = rg ? sDS : sS;    // masked score tile P[i][j] of this product
     T *gOut = rg ? dK : dV;
 
-    const size_t base = (size_t)chain * ntiles * CT * D;
     // st[blk][i]: group 0: dKV[32 blk + acc_row(i)][32 w + r]; group 1: dKV[32 w + r][32 blk + acc_row(i)]
     f32x16 st[DB];
     {
@@ -856,18 +919,6 @@ __global__ __launch_bounds__(D * 4) void k_bwd8(const T *__restrict__ Q, const T
                     for (int e = 0; e < 4; ++e) st[cb][4 * q + e] = x[e];
                 }
         }
-    }
-
-    TileMover<T, CT, D, NT> mv, mo, mk, mq;
-    TileMover<T, D, D, NT> mc;  // cached state tile KV_{t-1}, [a][c]
-    const T *ctile = cache + (size_t)chain * ntiles * D * D;
-    {
-        const size_t off = base + (size_t)(t1 - 1) * CT * D;
-        mv.load(V + off);
-        mo.load(dO + off);
-        mk.load(K + off);
-        mq.load(Q + off);
-        mc.load(ctile + (size_t)(t1 - 1) * D * D);
     }
 
     for (int t = t1 - 1; t >= t0; --t) {
@@ -1033,6 +1084,30 @@ static hipError_t allow_lds(F kernel, size_t bytes) {
     return e;
 }
 
+// The local pass only sums over its segment, so its tile need not be the walk's:
+// bfloat16 segments made of an even number of 64-token tiles are read 128 tokens
+// at a time (half the barriers, twice the bytes in flight per workgroup).
+template <typename T, int CT, int D, bool BWD>
+static hipError_t run_local(const Plan &p, const T *x, const T *y, const float *decay, float *scratch, hipStream_t s) {
+    const int chains = p.B * p.H;
+    hipError_t e;
+    if constexpr (sizeof(T) == 2 && CT == 64) {
+        if (p.tiles_per_seg % 2 == 0 && p.ntiles % 2 == 0) {
+            constexpr size_t lds = Smem<T, 128, D>::local;
+            auto kl = k_local<T, 128, D, BWD>;
+            if ((e = allow_lds(kl, lds)) != hipSuccess) return e;
+            kl<<<dim3(p.nseg - 1, chains), dim3(D * 2), lds, s>>>(x, y, decay, scratch, p.H, p.ntiles / 2, p.nseg,
+                                                                p.tiles_per_seg / 2);
+            return hipSuccess;
+        }
+    }
+    constexpr size_t lds = Smem<T, CT, D>::local;
+    auto kl = k_local<T, CT, D, BWD>;
+    if ((e = allow_lds(kl, lds)) != hipSuccess) return e;
+    kl<<<dim3(p.nseg - 1, chains), dim3(D * 2), lds, s>>>(x, y, decay, scratch, p.H, p.ntiles, p.nseg, p.tiles_per_seg);
+    return hipSuccess;
+}
+
 template <typename T, int CT, int D>
 static hipError_t run_fwd(const Plan &p, const FwdArgs &a, hipStream_t s, const KernelEvents *ke) {
     const int chains = p.B * p.H, DD = D * D;
@@ -1040,10 +1115,7 @@ static hipError_t run_fwd(const Plan &p, const FwdArgs &a, hipStream_t s, const 
     hipError_t e;
     if (ke) (void)hipEventRecord(ke->ev[0], s);
     if (p.nseg > 1) {
-        auto kl = k_local<T, CT, D, false>;
-        if ((e = allow_lds(kl, lds_local)) != hipSuccess) return e;
-        kl<<<dim3(p.nseg - 1, chains), dim3(D * 2), lds_local, s>>>((const T *)a.k, (const T *)a.v, a.decay, a.scratch,
-                                                                   p.H, p.ntiles, p.nseg, p.tiles_per_seg);
+        if (e = run_local<T, CT, D, false>(p, (const T *)a.k, (const T *)a.v, a.decay, a.scratch, s); e != hipSuccess) return e;
     }
     if (ke) (void)hipEventRecord(ke->ev[1], s);
     k_scan<false><<<dim3((DD / 4 + 255) / 256, chains), dim3(256), 0, s>>>(a.scratch, a.kv_in, a.decay, p.H, DD, p.nseg,
@@ -1065,10 +1137,7 @@ static hipError_t run_bwd(const Plan &p, const BwdArgs &a, hipStream_t s, const 
     hipError_t e;
     if (ke) (void)hipEventRecord(ke->ev[0], s);
     if (p.nseg > 1) {
-        auto kl = k_local<T, CT, D, true>;
-        if ((e = allow_lds(kl, lds_local)) != hipSuccess) return e;
-        kl<<<dim3(p.nseg - 1, chains), dim3(D * 2), lds_local, s>>>((const T *)a.q, (const T *)a.dout, a.decay,
-                                                                   a.scratch, p.H, p.ntiles, p.nseg, p.tiles_per_seg);
+        if (e = run_local<T, CT, D, true>(p, (const T *)a.q, (const T *)a.dout, a.decay, a.scratch, s); e != hipSuccess) return e;
     }
     if (ke) (void)hipEventRecord(ke->ev[1], s);
     k_scan<true><<<dim3((DD / 4 + 255) / 256, chains), dim3(256), 0, s>>>(a.scratch, a.dkv_out, a.decay, p.H, DD, p.nseg,
