@@ -48,7 +48,9 @@ int make_plan(const lasp_shape *s, Pass pass, lasp::Plan *p) {
         if (want > p->ntiles) want = p->ntiles;
         if (want < 1) want = 1;
     }
+    p->cache_stride = lasp::cache_stride_for(p->dtype, p->tile, p->ntiles);
     p->tiles_per_seg = (p->ntiles + want - 1) / want;
+    if (p->cache_stride == 2) p->tiles_per_seg += p->tiles_per_seg & 1;   // segments start on cached tiles
     p->nseg = (p->ntiles + p->tiles_per_seg - 1) / p->tiles_per_seg;  // every segment non-empty
     return LASP_OK;
 }
@@ -122,7 +124,7 @@ int32_t lasp_num_segments(const lasp_shape *shape) {
 size_t lasp_state_cache_bytes(const lasp_shape *shape) {
     lasp::Plan p;
     if (make_plan(shape, kForward, &p) != LASP_OK) return 0;
-    return (size_t)p.B * p.H * p.ntiles * p.D * p.D * elem_bytes(p.dtype);
+    return (size_t)p.B * p.H * (p.ntiles / p.cache_stride) * p.D * p.D * elem_bytes(p.dtype);
 }
 
 size_t lasp_scratch_bytes(const lasp_shape *shape) {

@@ -17,6 +17,7 @@ struct Plan {
     int ntiles;         // N / tile
     int nseg;           // segments per head (S)
     int tiles_per_seg;  // ceil(ntiles / nseg); the last segment may be shorter
+    int cache_stride;   // the state cache holds the start state of every cache_stride-th tile (1 or 2)
 };
 
 struct FwdArgs {
@@ -47,6 +48,9 @@ struct KernelEvents {
 
 // Tile length used for a (dtype, chunk, D) combination.
 int tile_tokens(int dtype, int chunk, int D);
+// Cache stride for a shape: 2 (one cached state per pair of tiles, the backward
+// walk rebuilds the other) when the kernels support it, else 1.
+int cache_stride_for(int dtype, int tile, int ntiles);
 
 hipError_t launch_fwd(const Plan &p, const FwdArgs &a, hipStream_t stream, const KernelEvents *ke);
 hipError_t launch_bwd(const Plan &p, const BwdArgs &a, hipStream_t stream, const KernelEvents *ke);

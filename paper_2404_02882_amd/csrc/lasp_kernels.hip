@@ -263,6 +263,33 @@ struct TileMover {
     }
 };
 
+// Row weights lambda^(CT-1-k) ("after": tokens after k in the tile) and lambda^(k+1)
+// ("upto": 1-based position) for the KH consecutive tokens k_first .. k_first+KH-1 a
+// lane holds in one fragment, as one table entry times a wave-uniform factor per element:
+//   after: pw[CT-KH-k_first] * lambda^(KH-1-e)      upto: pw[k_first+1] * lambda^e
+template <typename T>
+struct GeoWeights {
+    float after[8], upto[8];
+    DEVI explicit GeoWeights(float lam) {
+        const float l2f = (float)log2((double)lam);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            after[e] = e < Elem<T>::KH ? exp2f((float)(Elem<T>::KH - 1 - e) * l2f) : 1.0f;
+            upto[e] = e < Elem<T>::KH ? exp2f((float)e * l2f) : 1.0f;
+        }
+    }
+};
+template <typename T, int CT>
+DEVI typename Elem<T>::frag weigh_after(const Lane &ln, typename Elem<T>::frag f, int ks, const float *pw, const GeoWeights<T> &g) {
+    const int k_first = ks * Elem<T>::KSTEP + Elem<T>::KH * ln.h;
+    return Elem<T>::scale_geo(f, pw[CT - Elem<T>::KH - k_first], g.after);
+}
+template <typename T, int CT>
+DEVI typename Elem<T>::frag weigh_upto(const Lane &ln, typename Elem<T>::frag f, int ks, const float *pw, const GeoWeights<T> &g) {
+    const int k_first = ks * Elem<T>::KSTEP + Elem<T>::KH * ln.h;
+    return Elem<T>::scale_geo(f, pw[k_first + 1], g.upto);
+}
+
 // lambda^n for n = 0..CT into LDS, evaluated in double so that the table adds
 // no error of its own.
 template <int CT>
@@ -427,13 +454,11 @@ __global__ __launch_bounds__(D * 2) void k_local(const T *__restrict__ X, const 
     PHASE(22);
     const float lam = decay[chain % H];
     fill_pow_table<CT>(pw, lam);
+    const GeoWeights<T> geo(lam);
     f32x16 st[DB];
 #pragma unroll
     for (int ab = 0; ab < DB; ++ab) st[ab] = f32x16{0};
     const float l2f = (float)log2((double)lam);
-    float geo[8];  // uniform: lambda^(KH-1-e) forward, lambda^e backward
-#pragma unroll
-    for (int e = 0; e < 8; ++e) geo[e] = e < E::KH ? exp2f((float)(BWD ? e : E::KH - 1 - e) * l2f) : 1.0f;
     PHASE(23);
     for (int n = 0; n < ntl; ++n) {
         __syncthreads();  // previous tile fully consumed (and pw visible on the first pass)
@@ -468,7 +493,7 @@ __global__ __launch_bounds__(D * 2) void k_local(const T *__restrict__ X, const 
             }
 #pragma unroll
             for (int ks = 0; ks < NKS; ++ks) {
-                const typename E::frag yd = E::scale_geo(yf[ks], weight_of(ks), geo);
+                const typename E::frag yd = E::scale_geo(yf[ks], weight_of(ks), BWD ? geo.upto : geo.after);
 #pragma unroll
                 for (int ab = 0; ab < DB; ++ab) st[ab] = E::mfma(xf[ks][ab], yd, st[ab]);
             }
@@ -486,7 +511,7 @@ __global__ __launch_bounds__(D * 2) void k_local(const T *__restrict__ X, const 
                     return f;
                 },
                 [&](int ks, const Step &f) {
-                    const typename E::frag yd = E::scale_geo(f.y, weight_of(ks), geo);
+                    const typename E::frag yd = E::scale_geo(f.y, weight_of(ks), BWD ? geo.upto : geo.after);
 #pragma unroll
                     for (int ab = 0; ab < DB; ++ab) st[ab] = E::mfma(f.x[ab], yd, st[ab]);
                 });
@@ -549,7 +574,7 @@ __global__ __launch_bounds__(D * 2, (CT <= 64 && sizeof(T) == 2) ? 2 : 1) void k
                                                 const T *__restrict__ V, const float *__restrict__ decay,
                                                 T *__restrict__ O, float *__restrict__ kv_out,
                                                 T *__restrict__ cache, const float *__restrict__ scratch,
-                                                int H, int ntiles, int nseg, int tiles_per_seg) {
+                                                int H, int ntiles, int nseg, int tiles_per_seg, int cache_stride) {
     using E = Elem<T>;
     constexpr int NT = D * 2, LDD = D + E::PAD, LDP = CT + E::PAD, DB = D / 32, NB = CT / 32, NKS = CT / E::KSTEP,
                   SPB = 32 / E::KSTEP;
@@ -575,12 +600,14 @@ __global__ __launch_bounds__(D * 2, (CT <= 64 && sizeof(T) == 2) ? 2 : 1) void k
     state_load<D>(ln, st, scratch + ((size_t)chain * nseg + seg) * D * D, w);
     const float lam = decay[chain % H];
     fill_pow_table<CT>(pw, lam);
+    const GeoWeights<T> geo(lam);
 
     for (int t = t0; t < t1; ++t) {
         __syncthreads();
         ln = fresh_lane();
         // The state this tile starts from goes to the cache as KV_{t-1}, rows a, columns c.
-        if (cache) cache_store<T, CT, D>(ln, cache + ((size_t)chain * ntiles + t) * D * D, st, sP, w);
+        if (cache && t % cache_stride == 0)
+            cache_store<T, CT, D>(ln, cache + ((size_t)chain * (ntiles / cache_stride) + t / cache_stride) * D * D, st, sP, w);
         mq.store(sQ, LDD);
         mk.store(sK, LDD);
         mv.store(sV, LDD);
@@ -632,8 +659,7 @@ __global__ __launch_bounds__(D * 2, (CT <= 64 && sizeof(T) == 2) ? 2 : 1) void k
         for (int ab = 0; ab < DB; ++ab) st[ab] *= lamC;
 #pragma unroll
         for (int ks = 0; ks < NKS; ++ks) {
-            const typename E::frag vd = E::scale(ln, E::ld_ks(ln, sV, LDD, ks * E::KSTEP, 32 * w), ks * E::KSTEP,
-                                                 [&](int k) { return pw[CT - 1 - k]; });
+            const typename E::frag vd = weigh_after<T, CT>(ln, E::ld_ks(ln, sV, LDD, ks * E::KSTEP, 32 * w), ks, pw, geo);
 #pragma unroll
             for (int ab = 0; ab < DB; ++ab) st[ab] = E::mfma(E::ld_ks(ln, sK, LDD, ks * E::KSTEP, 32 * ab), vd, st[ab]);
             SCHED_FENCE();
@@ -692,6 +718,7 @@ __global__ __launch_bounds__(D * 2, (CT <= 64 && sizeof(T) == 2) ? 2 : 1) void k
     Lane ln = fresh_lane();
     const float lam = decay[chain % H];
     fill_pow_table<CT>(pw, lam);
+    const GeoWeights<T> geo(lam);
 
     const size_t base = (size_t)chain * ntiles * CT * D;
     f32x16 dkv[DB];
@@ -815,7 +842,7 @@ __global__ __launch_bounds__(D * 2, (CT <= 64 && sizeof(T) == 2) ? 2 : 1) void k
         for (int ab = 0; ab < DB; ++ab) dkv[ab] *= lamC;
 #pragma unroll
         for (int ks = 0; ks < NKS; ++ks) {
-            const typename E::frag dos = E::scale(ln, dof[ks], ks * E::KSTEP, [&](int k) { return pw[k + 1]; });
+            const typename E::frag dos = weigh_upto<T, CT>(ln, dof[ks], ks, pw, geo);
 #pragma unroll
             for (int ab = 0; ab < DB; ++ab) dkv[ab] = E::mfma(E::ld_ks(ln, bufB, LDD, ks * E::KSTEP, 32 * ab), dos, dkv[ab]);
         }
@@ -894,6 +921,7 @@ __global__ __launch_bounds__(D * 4) void k_bwd8(const T *__restrict__ Q, const T
     }
     const float lam = decay[chain % H];
     fill_pow_table<CT>(pw, lam);
+    const GeoWeights<T> geo(lam);
 
     // Group-dependent operands (wave-uniform selects).
     const T *sX1 = rg ? sV : sK;     // inter operand: token rows, features contracted with the state
@@ -1047,7 +1075,7 @@ __global__ __launch_bounds__(D * 4) void k_bwd8(const T *__restrict__ Q, const T
                     return f;
                 },
                 [&](int ks, const Step &f) {
-                    const F bs = E::scale(ln, f.b, ks * E::KSTEP, [&](int k) { return pw[k + 1]; });
+                    const F bs = weigh_upto<T, CT>(ln, f.b, ks, pw, geo);
 #pragma unroll
                     for (int blk = 0; blk < DB; ++blk) st[blk] = E::mfma(f.a[blk], bs, st[blk]);
                 });
@@ -1056,6 +1084,285 @@ __global__ __launch_bounds__(D * 4) void k_bwd8(const T *__restrict__ Q, const T
     }
     if (seg == 0 && rg == 0) state_store<D>(ln, st, dkv_in + (size_t)chain * D * D, w);
     PHASE_FLUSH();
+}
+
+// ---------------------------------------------------------------------------
+// k_bwd8p: k_bwd8 for a state cache that holds one state per PAIR of tiles
+// (half the cache traffic of both passes). Tiles are walked in reverse as pairs
+// (E = even tile, O = the odd tile after it). The cache gives KV at the start
+// of E. The O tile needs the state one tile later,
+//     KV_mid = lambda^CT KV + (diag{lambda^(CT-1-j)} K_E)^T V_E   (state update of Sec. 3.2),
+// which the workgroup rebuilds in place in LDS from K_E, V_E; these are needed for
+// the E tile anyway and are simply fetched one tile early. After the O tile the
+// cached state is written to LDS again (it is still in registers) for the E tile.
+// Per pair: six barriers, 9 tile loads, one cache-tile load.
+// ---------------------------------------------------------------------------
+template <typename T, int CT, int D>
+struct Bwd8pSmem {
+    static constexpr int PAD = 8;  // six resident tiles leave no room for wider padding
+    static constexpr int LDD = D + PAD, LDP = CT + PAD;
+    static constexpr size_t TILE = (size_t)CT * LDD * sizeof(T);
+    static constexpr size_t P_OFF = 6 * TILE;
+    static constexpr size_t C_OFF = P_OFF + 2 * (size_t)CT * LDP * sizeof(T);
+    static constexpr size_t PW_OFF = C_OFF + (size_t)D * LDD * sizeof(T);
+    static constexpr size_t TOTAL = PW_OFF + (CT + 1) * sizeof(float);
+};
+
+template <typename T, int CT, int D>
+__global__ __launch_bounds__(D * 4) void k_bwd8p(const T *__restrict__ Q, const T *__restrict__ K,
+                                                  const T *__restrict__ V, const T *__restrict__ dO,
+                                                  const float *__restrict__ decay, const T *__restrict__ cache,
+                                                  T *__restrict__ dQ, T *__restrict__ dK, T *__restrict__ dV,
+                                                  float *__restrict__ dkv_in, const float *__restrict__ scratch,
+                                                  int H, int ntiles, int nseg, int tiles_per_seg) {
+    using E = Elem<T>;
+    using F = typename E::frag;
+    using SM = Bwd8pSmem<T, CT, D>;
+    static_assert(CT == 64, "two 32-token blocks per tile");
+    constexpr int NT = D * 4, NW = D / 32, LDD = SM::LDD, LDP = SM::LDP, DB = D / 32, NB = CT / 32, NKS = CT / E::KSTEP,
+                  NKD = D / E::KSTEP, SPB = 32 / E::KSTEP;
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    T *sVO = (T *)smem;            // V of the O tile
+    T *sdO = sVO + CT * LDD;       // dO of the tile being processed
+    T *sKO = sdO + CT * LDD;       // K of the O tile
+    T *sQ = sKO + CT * LDD;        // Q of the tile being processed
+    T *sVE = sQ + CT * LDD;        // V of the E tile
+    T *sKE = sVE + CT * LDD;       // K of the E tile
+    T *sS = (T *)(smem + SM::P_OFF);
+    T *sDS = sS + CT * LDP;
+    T *sC = (T *)(smem + SM::C_OFF);
+    float *pw = (float *)(smem + SM::PW_OFF);
+
+    const int chain = blockIdx.y, seg = blockIdx.x;
+    const int t0 = seg * tiles_per_seg;                 // even
+    const int t1 = min(t0 + tiles_per_seg, ntiles);     // even
+    const int w8 = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int w = w8 % NW;    // feature block of this wave's outputs
+    const int rg = w8 / NW;   // group: 0 produces dV, 1 produces dK
+    Lane ln = fresh_lane();
+    PHASE_DECL();
+
+    const size_t base = (size_t)chain * ntiles * CT * D;
+    const size_t TS = (size_t)CT * D;  // elements per tile
+    TileMover<T, CT, D, NT> mvO, moX, mkO, mqX, mvE, mkE;   // moX / mqX carry dO, Q of the O tile, then of the E tile
+    TileMover<T, D, D, NT> mc;                               // cached state at the start of the E tile
+    const T *ctile = cache + (size_t)chain * (ntiles / 2) * D * D;
+    auto load_pair = [&](int tE) {
+        const size_t oE = base + (size_t)tE * TS, oO = oE + TS;
+        mvO.load(V + oO);
+        moX.load(dO + oO);
+        mkO.load(K + oO);
+        mqX.load(Q + oO);
+        mvE.load(V + oE);
+        mkE.load(K + oE);
+        mc.load(ctile + (size_t)(tE / 2) * D * D);
+    };
+    load_pair(t1 - 2);
+    const float lam = decay[chain % H];
+    fill_pow_table<CT>(pw, lam);
+    const GeoWeights<T> geo(lam);
+
+    const T *sX2 = rg ? sQ : sdO;    // intra operand and state-update B operand: [token][feature in w]
+    const T *sUA = rg ? sdO : sQ;    // state-update A operand: [token][feature of the state rows]
+    const T *sPm = rg ? sDS : sS;    // masked score tile of this group's product
+    T *gOut = rg ? dK : dV;
+
+    // st[blk][i]: group 0: dKV[32 blk + acc_row(i)][32 w + r]; group 1: dKV[32 w + r][32 blk + acc_row(i)]
+    f32x16 st[DB];
+    {
+        const float *g = scratch + ((size_t)chain * nseg + seg) * D * D;
+        if (rg == 0) {
+            state_load<D>(ln, st, g, w);
+        } else {
+            const unsigned lo = ((32 * w + ln.r) * D + 4 * ln.h) * sizeof(float);
+#pragma unroll
+            for (int cb = 0; cb < DB; ++cb)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const f32x4 x = gload<f32x4>(g + 32 * cb + 8 * q, lo);
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) st[cb][4 * q + e] = x[e];
+                }
+        }
+    }
+
+    // masked score tiles of the tile whose V, K are at pV, pK (dO, Q in sdO, sQ): one 32x32 block per wave
+    auto scores = [&](const T *pV, const T *pK) {
+        constexpr int NTRI = 3;
+#pragma unroll
+        for (int idx = 0; idx < 2 * NTRI; ++idx) {
+            if (idx % (2 * NW) != w8) continue;
+            const int tri = idx % NTRI, ib = tri == 0 ? 0 : 1, jb = tri == 2 ? 1 : 0;
+            const T *sA = idx < NTRI ? pV : pK, *sB = idx < NTRI ? sdO : sQ;
+            f32x16 acc = {0}, acc2 = {0};
+            pipelined<NKD / 2>(
+                [&](int s2) {
+                    FragPair<FragPair<F>> f;
+                    f.a.a = E::ld_kc(ln, sA, LDD, 32 * jb, 2 * s2 * E::KSTEP);
+                    f.a.b = E::ld_kc(ln, sB, LDD, 32 * ib, 2 * s2 * E::KSTEP);
+                    f.b.a = E::ld_kc(ln, sA, LDD, 32 * jb, (2 * s2 + 1) * E::KSTEP);
+                    f.b.b = E::ld_kc(ln, sB, LDD, 32 * ib, (2 * s2 + 1) * E::KSTEP);
+                    return f;
+                },
+                [&](int, const FragPair<FragPair<F>> &f) {
+                    acc = E::mfma(f.a.a, f.a.b, acc);
+                    acc2 = E::mfma(f.b.a, f.b.b, acc2);
+                });
+            acc += acc2;
+            store_masked_scores<T, LDP>(ln, idx < NTRI ? sDS : sS, acc, jb, ib, pw);
+        }
+    };
+
+    // dQ, this group's dV or dK, and the dKV update for the tile at element offset `off`
+    auto products = [&](const T *pV, const T *pK, size_t off) {
+        const T *sX1 = rg ? pV : pK;  // inter operand: token rows, features contracted with the state
+        {   // dQ^T[a in w][i], tokens i of block rg
+            const int r0 = 32 * rg;
+            f32x16 acc = {0};
+            pipelined<NKD>(
+                [&](int ks) { return FragPair<F>{E::ld_kc(ln, sC, LDD, 32 * w, ks * E::KSTEP), E::ld_kc(ln, sdO, LDD, r0, ks * E::KSTEP)}; },
+                [&](int, const FragPair<F> &f) { acc = E::mfma(f.a, f.b, acc); });
+            acc *= pw[r0 + ln.r + 1];
+            auto intra = [&](int ks) { return FragPair<F>{E::ld_ks(ln, pK, LDD, ks * E::KSTEP, 32 * w), E::ld_kc(ln, sDS, LDP, r0, ks * E::KSTEP)}; };
+            auto fma = [&](int, const FragPair<F> &f) { acc = E::mfma(f.a, f.b, acc); };
+            if (rg == 0) pipelined<SPB>(intra, fma);
+            else pipelined<2 * SPB>(intra, fma);
+            store_out_tile_t<T, D>(ln, dQ + off, acc, r0, w);
+        }
+        ln = fresh_lane();
+        {   // dV^T[c in w][j] (group 0) or dK^T[a in w][j] (group 1), both token blocks
+            f32x16 acc[NB];
+#pragma unroll
+            for (int jb = 0; jb < NB; ++jb) acc[jb] = f32x16{0};
+            struct Two { F b[NB]; };
+            pipelined<DB * E::NSUB>(
+                [&](int s2) {
+                    Two f;
+#pragma unroll
+                    for (int jb = 0; jb < NB; ++jb) f.b[jb] = E::ld_kp(ln, sX1, LDD, 32 * jb, 32 * (s2 / E::NSUB), s2 % E::NSUB);
+                    return f;
+                },
+                [&](int s2, const Two &f) {
+                    const F sf = E::from_acc(st[s2 / E::NSUB], s2 % E::NSUB);
+#pragma unroll
+                    for (int jb = 0; jb < NB; ++jb) acc[jb] = E::mfma(sf, f.b[jb], acc[jb]);
+                });
+#pragma unroll
+            for (int jb = 0; jb < NB; ++jb) acc[jb] *= pw[CT - 1 - (32 * jb + ln.r)];
+            struct Three { F a; F b[NB]; };
+            pipelined<NKS>(
+                [&](int ks) {
+                    Three f;
+                    f.a = E::ld_ks(ln, sX2, LDD, ks * E::KSTEP, 32 * w);
+#pragma unroll
+                    for (int jb = 0; jb < NB; ++jb)
+                        if (jb <= ks / SPB) f.b[jb] = E::ld_ks(ln, sPm, LDP, ks * E::KSTEP, 32 * jb);
+                    return f;
+                },
+                [&](int ks, const Three &f) {
+#pragma unroll
+                    for (int jb = 0; jb < NB; ++jb)
+                        if (jb <= ks / SPB) acc[jb] = E::mfma(f.a, f.b[jb], acc[jb]);
+                });
+#pragma unroll
+            for (int jb = 0; jb < NB; ++jb) store_out_tile_t<T, D>(ln, gOut + off, acc[jb], 32 * jb, w);
+        }
+        ln = fresh_lane();
+        {   // state update in this group's orientation
+            const float lamC = pw[CT];
+#pragma unroll
+            for (int blk = 0; blk < DB; ++blk) st[blk] *= lamC;
+            struct Step { F b; F a[DB]; };
+            pipelined<NKS>(
+                [&](int ks) {
+                    Step f;
+                    f.b = E::ld_ks(ln, sX2, LDD, ks * E::KSTEP, 32 * w);
+#pragma unroll
+                    for (int blk = 0; blk < DB; ++blk) f.a[blk] = E::ld_ks(ln, sUA, LDD, ks * E::KSTEP, 32 * blk);
+                    return f;
+                },
+                [&](int ks, const Step &f) {
+                    const F bs = weigh_upto<T, CT>(ln, f.b, ks, pw, geo);
+#pragma unroll
+                    for (int blk = 0; blk < DB; ++blk) st[blk] = E::mfma(f.a[blk], bs, st[blk]);
+                });
+        }
+    };
+
+    for (int tE = t1 - 2; tE >= t0; tE -= 2) {
+        const size_t offE = base + (size_t)tE * TS, offO = offE + TS;
+        __syncthreads();  // previous pair fully consumed
+        ln = fresh_lane();
+        PHASE(0);
+        mvO.store(sVO, LDD);
+        moX.store(sdO, LDD);
+        mkO.store(sKO, LDD);
+        mqX.store(sQ, LDD);
+        mvE.store(sVE, LDD);
+        mkE.store(sKE, LDD);
+        mc.store(sC, LDD);   // mc keeps the cached state in registers for the E tile
+        __syncthreads();
+        ln = fresh_lane();
+        PHASE(1);
+        moX.load(dO + offE);
+        mqX.load(Q + offE);
+        PHASE(2);
+        // ---- O tile ----
+        scores(sVO, sKO);
+        PHASE(3);
+        {   // sC <- KV_mid, in place: block (cb, ab) of KV_mid^T[c][a] = lambda^CT KV^T + sum_j V_E[j][c] (w_j K_E[j][a])
+            constexpr int NBLK = DB * DB, PER = (NBLK + 2 * NW - 1) / (2 * NW);
+            const float lamC = pw[CT];
+#pragma unroll
+            for (int u = 0; u < PER; ++u) {
+                const int blk = w8 * PER + u;
+                if (blk >= NBLK) continue;
+                const int cb = blk / DB, ab = blk % DB;
+                f32x16 acc = {0};
+                pipelined<NKS>(
+                    [&](int ks) { return FragPair<F>{E::ld_ks(ln, sVE, LDD, ks * E::KSTEP, 32 * cb), E::ld_ks(ln, sKE, LDD, ks * E::KSTEP, 32 * ab)}; },
+                    [&](int ks, const FragPair<F> &f) {
+                        acc = E::mfma(f.a, weigh_after<T, CT>(ln, f.b, ks, pw, geo), acc);
+                    });
+                // lane r holds a = 32 ab + r and, per register group q, c = 32 cb + 8 q + 4 h + (0..3)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    T *pc = sC + (32 * ab + ln.r) * LDD + 32 * cb + 8 * q + 4 * ln.h;
+                    float o[4];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) o[e] = lamC * E::ld1(pc + e) + acc[4 * q + e];
+                    E::st4(pc, o[0], o[1], o[2], o[3]);
+                }
+            }
+        }
+        PHASE(4);
+        __syncthreads();
+        ln = fresh_lane();
+        PHASE(5);
+        products(sVO, sKO, offO);
+        PHASE(6);
+        __syncthreads();  // O tile consumed: sdO, sQ, sC are free
+        ln = fresh_lane();
+        PHASE(7);
+        moX.store(sdO, LDD);
+        mqX.store(sQ, LDD);
+        mc.store(sC, LDD);
+        __syncthreads();
+        ln = fresh_lane();
+        PHASE(8);
+        if (tE > t0) load_pair(tE - 2);
+        PHASE(9);
+        // ---- E tile ----
+        scores(sVE, sKE);
+        PHASE(10);
+        __syncthreads();
+        ln = fresh_lane();
+        PHASE(11);
+        products(sVE, sKE, offE);
+        PHASE(12);
+    }
+    PHASE_FLUSH();
+    if (seg == 0 && rg == 0) state_store<D>(ln, st, dkv_in + (size_t)chain * D * D, w);
 }
 
 // ---------------------------------------------------------------------------
@@ -1125,7 +1432,7 @@ static hipError_t run_fwd(const Plan &p, const FwdArgs &a, hipStream_t s, const 
     if ((e = allow_lds(kf, lds_fwd)) != hipSuccess) return e;
     kf<<<dim3(p.nseg, chains), dim3(D * 2), lds_fwd, s>>>((const T *)a.q, (const T *)a.k, (const T *)a.v, a.decay,
                                                          (T *)a.out, a.kv_out, (T *)a.cache, (const float *)a.scratch,
-                                                         p.H, p.ntiles, p.nseg, p.tiles_per_seg);
+                                                         p.H, p.ntiles, p.nseg, p.tiles_per_seg, p.cache_stride);
     if (ke) (void)hipEventRecord(ke->ev[3], s);
     return hipGetLastError();
 }
@@ -1144,6 +1451,16 @@ static hipError_t run_bwd(const Plan &p, const BwdArgs &a, hipStream_t s, const 
                                                                       p.tiles_per_seg, p.ntiles, p.tile);
     if (ke) (void)hipEventRecord(ke->ev[2], s);
     if constexpr (sizeof(T) == 2 && CT == 64) {
+      if (p.cache_stride == 2) {
+        constexpr size_t lds_bwd8p = Bwd8pSmem<T, CT, D>::TOTAL;
+        static_assert(lds_bwd8p <= 163840, "LDS budget of one gfx950 CU exceeded");
+        auto kb = k_bwd8p<T, CT, D>;
+        if ((e = allow_lds(kb, lds_bwd8p)) != hipSuccess) return e;
+        kb<<<dim3(p.nseg, chains), dim3(D * 4), lds_bwd8p, s>>>((const T *)a.q, (const T *)a.k, (const T *)a.v,
+                                                                (const T *)a.dout, a.decay, (const T *)a.cache, (T *)a.dq,
+                                                                (T *)a.dk, (T *)a.dv, a.dkv_in, (const float *)a.scratch,
+                                                                p.H, p.ntiles, p.nseg, p.tiles_per_seg);
+      } else {
         constexpr size_t lds_bwd8 = Bwd8Smem<T, CT, D>::TOTAL;
         static_assert(lds_bwd8 <= 163840, "LDS budget of one gfx950 CU exceeded");
         auto kb = k_bwd8<T, CT, D>;
@@ -1152,6 +1469,7 @@ static hipError_t run_bwd(const Plan &p, const BwdArgs &a, hipStream_t s, const 
                                                                (const T *)a.dout, a.decay, (const T *)a.cache, (T *)a.dq,
                                                                (T *)a.dk, (T *)a.dv, a.dkv_in, (const float *)a.scratch,
                                                                p.H, p.ntiles, p.nseg, p.tiles_per_seg);
+      }
     } else {
         auto kb = k_bwd<T, CT, D>;
         if ((e = allow_lds(kb, lds_bwd)) != hipSuccess) return e;
@@ -1174,6 +1492,10 @@ extern "C" int lasp_debug_phases(unsigned long long *out32, int reset) {
     return 0;
 }
 #endif
+
+int cache_stride_for(int dtype, int tile, int ntiles) {
+    return (dtype == 1 && tile == 64 && ntiles % 2 == 0) ? 2 : 1;
+}
 
 int tile_tokens(int dtype, int chunk, int D) {
     (void)D;

@@ -54,7 +54,8 @@ def test_sizes_and_plan(L):
     assert tile in (32, 64, 128) and 128 % tile == 0          # the tile divides the chunk
     nseg = L.num_segments(s)
     assert 1 <= nseg <= 32768 // tile and 16 * nseg >= 256     # enough workgroups to fill 256 CUs
-    assert L.state_cache_bytes(s) == 16 * (32768 // tile) * 128 * 128 * 2
+    per_tile = 16 * (32768 // tile) * 128 * 128 * 2
+    assert L.state_cache_bytes(s) in (per_tile, per_tile // 2)   # one cached state per tile, or per pair of tiles
     assert L.scratch_bytes(s) == 16 * nseg * 128 * 128 * 4
     f = L.make_shape(1, 2, 256, 64, 64, "f32")
     ft = L.tile_tokens(f)

@@ -107,6 +107,21 @@ def test_ragged_segments_and_determinism(gpu, oracle):
         first = first or got
 
 
+def test_even_tile_counts_pair_cache(gpu, oracle):
+    """Even tile counts use the paired state cache (one cached state per two tiles);
+    segment requests that are odd or do not divide the tiles are rounded to whole pairs."""
+    harness, lasp, si = gpu
+    for D in (64, 128):
+        cfg = si.Config("pairs", B=1, H=2, N=64 * 12, D=D, chunk=64, dtype="bf16", seed=6 + D)
+        inp = si.make_inputs(cfg, with_states=True)
+        inp.decay = np.array([0.95, 1.0 - 2.0 ** -9], dtype=np.float32)
+        ref = oracle_all(oracle, inp)
+        for segments in (1, 2, 3, 5, 6, 12):
+            say(f"case pairs D={D} segments={segments}")
+            got = harness.run_gpu(inp, segments=segments)
+            compare(harness, got, ref, TOL["bf16"], f"D{D}/seg{segments}")
+
+
 def test_lambda_one_chunk1_limit(gpu, oracle):
     """lambda = 1 (ordinary linear attention) in float: textbook tril(QK^T)V."""
     harness, lasp, si = gpu
