@@ -78,13 +78,18 @@ __device__ unsigned long long g_phase_cycles[32];
 // step s, `use(s, frags)` consumes them.
 template <int N, typename Load, typename Use>
 DEVI void pipelined(Load load, Use use) {
+    // two steps ahead: with one or two waves per SIMD the LDS round trip is longer
+    // than the matrix work of a single step
     auto cur = load(0);
+    decltype(cur) nxt;
+    if (N > 1) nxt = load(1);
 #pragma unroll
     for (int s = 0; s < N; ++s) {
-        decltype(cur) nxt;
-        if (s + 1 < N) nxt = load(s + 1);
+        decltype(cur) nn;
+        if (s + 2 < N) nn = load(s + 2);
         use(s, cur);
         if (s + 1 < N) cur = nxt;
+        if (s + 2 < N) nxt = nn;
     }
 }
 template <typename F>
@@ -117,6 +122,20 @@ DEVI Lane fresh_lane() {
     asm volatile("" : "+v"(t));
     return Lane(t);
 }
+
+// LDS layout of bfloat16 tiles with 128-element rows (256 bytes = all 64 banks):
+// no padding; the 16-byte chunk c of row `row` is stored at chunk c ^ swz16(row).
+// A row stride of exactly 128 elements selects this layout in the loaders below.
+// It is conflict-free for 16 lanes reading one chunk of 16 consecutive rows, for
+// the four-row by two-chunk blocks of a transposing read, and for whole-row stores.
+constexpr int kSwzLd = 128;
+DEVI int swz16(int row) { return ((row & 7) << 1) | ((row >> 3) & 1); }
+// element offset of (row, col) in a tile with row stride ld
+DEVI int lds_off(int ld, int row, int col) {
+    return ld == kSwzLd ? row * kSwzLd + ((((col >> 3) ^ swz16(row))) << 3) + (col & 7) : row * ld + col;
+}
+template <typename T, int D>
+constexpr int tile_ld() { return (sizeof(T) == 2 && D == 128) ? kSwzLd : D + (sizeof(T) == 2 ? 24 : 4); }
 
 // ---------------------------------------------------------------------------
 // Element traits: how MFMA operand fragments are fetched for each data type.
@@ -175,7 +194,12 @@ struct Elem<bf16_t> {
     static constexpr int NSUB = 2;
     static constexpr int PAD = 24;  // row stride = 12 banks mod 64: conflict-free 16-byte row reads, disjoint 4-row transposing reads
     static DEVI f32x16 mfma(frag a, frag b, f32x16 c) { return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0); }
+    // row0 is a multiple of 16 and k0 a multiple of 16 wherever these are called.
     static DEVI frag ld_kc(const Lane &ln, const bf16_t *X, int ld, int row0, int k0) {
+        if (ld == kSwzLd) {
+            const int t = ln.h ^ swz16(ln.r);  // lane constant; chunk (k0/8 + h) ^ swz = (k0/8) ^ t since k0/8 is even
+            return *(const bf16x8 *)(X + (row0 + ln.r) * kSwzLd + (((k0 >> 3) ^ t) << 3));
+        }
         return *(const bf16x8 *)(X + (row0 + ln.r) * ld + k0 + 8 * ln.h);
     }
     static DEVI frag ld_kc_g(const Lane &ln, const bf16_t *X, int ld, int row0, int k0) {
@@ -187,20 +211,37 @@ struct Elem<bf16_t> {
     static DEVI frag ld_ks(const Lane &ln, const bf16_t *X, int ld, int k0, int col0) {
         const int l = ln.id;
         const int l16 = l & 15;
-        const bf16_t *p = X + (k0 + 8 * ln.h + (l16 >> 2)) * ld + col0 + 16 * ((l >> 4) & 1) + 4 * (l16 & 3);
         typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
-        s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)p);
-        s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(p + 4 * ld));
+        const bf16_t *plo, *phi;
+        if (ld == kSwzLd) {
+            const int rowl = 8 * ln.h + (l16 >> 2);                    // row inside the 16-row group (k0 % 16 == 0)
+            const int c = (col0 >> 3) + 2 * ((l >> 4) & 1) + ((l16 & 3) >> 1);  // chunk of this lane's 8-byte piece
+            const int e = 4 * (l16 & 1);                                // element inside the chunk
+            plo = X + (k0 + rowl) * kSwzLd + ((c ^ swz16(rowl)) << 3) + e;
+            phi = X + (k0 + rowl + 4) * kSwzLd + ((c ^ swz16(rowl + 4)) << 3) + e;
+        } else {
+            plo = X + (k0 + 8 * ln.h + (l16 >> 2)) * ld + col0 + 16 * ((l >> 4) & 1) + 4 * (l16 & 3);
+            phi = plo + 4 * ld;
+        }
+        s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)plo);
+        s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)phi);
         union { struct { s16x4 a, b; } s; bf16x8 v; } u;
         u.s.a = lo;
         u.s.b = hi;
         return u.v;
     }
     static DEVI frag ld_kp(const Lane &ln, const bf16_t *X, int ld, int row0, int kb, int m) {
-        const bf16_t *p = X + (row0 + ln.r) * ld + kb + 16 * m + 4 * ln.h;
         union { struct { bf16x4 a, b; } s; bf16x8 v; } u;
-        u.s.a = *(const bf16x4 *)p;
-        u.s.b = *(const bf16x4 *)(p + 8);
+        if (ld == kSwzLd) {
+            const int sw = swz16(ln.r), c = (kb >> 3) + 2 * m;
+            const bf16_t *p = X + (row0 + ln.r) * kSwzLd + 4 * ln.h;
+            u.s.a = *(const bf16x4 *)(p + ((c ^ sw) << 3));
+            u.s.b = *(const bf16x4 *)(p + (((c + 1) ^ sw) << 3));
+        } else {
+            const bf16_t *p = X + (row0 + ln.r) * ld + kb + 16 * m + 4 * ln.h;
+            u.s.a = *(const bf16x4 *)p;
+            u.s.b = *(const bf16x4 *)(p + 8);
+        }
         return u.v;
     }
     static DEVI frag from_acc(const f32x16 &t, int m) {
@@ -257,6 +298,14 @@ struct TileMover {
         for (int i = 0; i < NV; ++i) r[i] = gload<u32x4>(g + i * (NT / VPR) * COLS, lo);
     }
     DEVI void store(T *s, int ld) const {
+        if (sizeof(T) == 2 && ld == kSwzLd) {
+            static_assert(sizeof(T) != 2 || COLS != 128 || (NT / VPR) % 16 == 0, "row step must keep row % 16");
+            const int row = threadIdx.x / VPR, chunk = threadIdx.x % VPR;
+            const unsigned lo = row * kSwzLd + ((chunk ^ swz16(row)) << 3);
+#pragma unroll
+            for (int i = 0; i < NV; ++i) *(u32x4 *)(s + i * (NT / VPR) * kSwzLd + lo) = r[i];
+            return;
+        }
         const unsigned lo = lane_off(ld);
 #pragma unroll
         for (int i = 0; i < NV; ++i) *(u32x4 *)(s + i * (NT / VPR) * ld + lo) = r[i];
@@ -431,7 +480,7 @@ __global__ __launch_bounds__(D * 2) void k_local(const T *__restrict__ X, const 
                                                   const float *__restrict__ decay, float *__restrict__ scratch,
                                                   int H, int ntiles, int nseg, int tiles_per_seg) {
     using E = Elem<T>;
-    constexpr int NT = D * 2, LDD = D + E::PAD, DB = D / 32, NKS = CT / E::KSTEP;
+    constexpr int NT = D * 2, LDD = tile_ld<T, D>(), DB = D / 32, NKS = CT / E::KSTEP;
     extern __shared__ __attribute__((aligned(16))) char smem[];
     T *sX = (T *)smem;
     T *sY = sX + CT * LDD;
@@ -576,7 +625,7 @@ __global__ __launch_bounds__(D * 2, (CT <= 64 && sizeof(T) == 2) ? 2 : 1) void k
                                                 T *__restrict__ cache, const float *__restrict__ scratch,
                                                 int H, int ntiles, int nseg, int tiles_per_seg, int cache_stride) {
     using E = Elem<T>;
-    constexpr int NT = D * 2, LDD = D + E::PAD, LDP = CT + E::PAD, DB = D / 32, NB = CT / 32, NKS = CT / E::KSTEP,
+    constexpr int NT = D * 2, LDD = tile_ld<T, D>(), LDP = CT + E::PAD, DB = D / 32, NB = CT / 32, NKS = CT / E::KSTEP,
                   SPB = 32 / E::KSTEP;
     extern __shared__ __attribute__((aligned(16))) char smem[];
     T *sQ = (T *)smem;
@@ -683,7 +732,7 @@ __global__ __launch_bounds__(D * 2, (CT <= 64 && sizeof(T) == 2) ? 2 : 1) void k
 template <typename T, int CT, int D>
 struct BwdSmem {
     using E = Elem<T>;
-    static constexpr int LDD = D + E::PAD, LDP = CT + E::PAD;
+    static constexpr int LDD = tile_ld<T, D>(), LDP = CT + E::PAD;
     static constexpr size_t IN_BYTES = 2 * (size_t)CT * LDD * sizeof(T);   // two input tiles
     static constexpr size_t X_BYTES = (size_t)D * LDD * sizeof(T);         // exchange buffer
     static constexpr bool OVERLAY = X_BYTES <= IN_BYTES;                    // exchange reuses the input tiles
@@ -737,7 +786,7 @@ __global__ __launch_bounds__(D * 2, (CT <= 64 && sizeof(T) == 2) ? 2 : 1) void k
         for (int ab = 0; ab < DB; ++ab)
 #pragma unroll
             for (int g = 0; g < 4; ++g)
-                E::st4(sX + (32 * w + ln.r) * LDD + 32 * ab + 8 * g + 4 * ln.h, dkv[ab][4 * g], dkv[ab][4 * g + 1],
+                E::st4(sX + lds_off(LDD, 32 * w + ln.r, 32 * ab + 8 * g + 4 * ln.h), dkv[ab][4 * g], dkv[ab][4 * g + 1],
                        dkv[ab][4 * g + 2], dkv[ab][4 * g + 3]);
         __syncthreads();
         typename E::frag xf[NKD];
@@ -866,7 +915,7 @@ __global__ __launch_bounds__(D * 2, (CT <= 64 && sizeof(T) == 2) ? 2 : 1) void k
 template <typename T, int CT, int D>
 struct Bwd8Smem {
     using E = Elem<T>;
-    static constexpr int LDD = D + E::PAD, LDP = CT + E::PAD;
+    static constexpr int LDD = tile_ld<T, D>(), LDP = CT + E::PAD;
     static constexpr size_t TILE = (size_t)CT * LDD * sizeof(T);
     static constexpr size_t P_OFF = 4 * TILE;
     static constexpr size_t C_OFF = P_OFF + 2 * (size_t)CT * LDP * sizeof(T);   // cached KV_{t-1} tile
@@ -1099,8 +1148,7 @@ __global__ __launch_bounds__(D * 4) void k_bwd8(const T *__restrict__ Q, const T
 // ---------------------------------------------------------------------------
 template <typename T, int CT, int D>
 struct Bwd8pSmem {
-    static constexpr int PAD = 8;  // six resident tiles leave no room for wider padding
-    static constexpr int LDD = D + PAD, LDP = CT + PAD;
+    static constexpr int LDD = tile_ld<T, D>(), LDP = CT + Elem<T>::PAD;
     static constexpr size_t TILE = (size_t)CT * LDD * sizeof(T);
     static constexpr size_t P_OFF = 6 * TILE;
     static constexpr size_t C_OFF = P_OFF + 2 * (size_t)CT * LDP * sizeof(T);
@@ -1327,7 +1375,7 @@ __global__ __launch_bounds__(D * 4) void k_bwd8p(const T *__restrict__ Q, const 
                 // lane r holds a = 32 ab + r and, per register group q, c = 32 cb + 8 q + 4 h + (0..3)
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
-                    T *pc = sC + (32 * ab + ln.r) * LDD + 32 * cb + 8 * q + 4 * ln.h;
+                    T *pc = sC + lds_off(LDD, 32 * ab + ln.r, 32 * cb + 8 * q + 4 * ln.h);
                     float o[4];
 #pragma unroll
                     for (int e = 0; e < 4; ++e) o[e] = lamC * E::ld1(pc + e) + acc[4 * q + e];
@@ -1371,8 +1419,8 @@ __global__ __launch_bounds__(D * 4) void k_bwd8p(const T *__restrict__ Q, const 
 template <typename T, int CT, int D>
 struct Smem {
     using E = Elem<T>;
-    static constexpr size_t local = 2 * (size_t)CT * (D + E::PAD) * sizeof(T) + (CT + 1) * sizeof(float);
-    static constexpr size_t fwd = (3 * (size_t)CT * (D + E::PAD) + (size_t)CT * (CT + E::PAD)) * sizeof(T) + (CT + 1) * sizeof(float);
+    static constexpr size_t local = 2 * (size_t)CT * tile_ld<T, D>() * sizeof(T) + (CT + 1) * sizeof(float);
+    static constexpr size_t fwd = (3 * (size_t)CT * tile_ld<T, D>() + (size_t)CT * (CT + E::PAD)) * sizeof(T) + (CT + 1) * sizeof(float);
     static constexpr size_t bwd = BwdSmem<T, CT, D>::TOTAL;
     static_assert(fwd <= 163840 && bwd <= 163840, "LDS budget of one gfx950 CU exceeded");
 };
