@@ -24,7 +24,7 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X published dense bf16 MFMA rate
 # HBM bytes per launch on config c3 from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
 # runs summarised in profiles/c3_fwd_bwd_kernels.md (read + written, scaled by the
 # plain-copy calibration: FETCH_SIZE x 2.000, WRITE_SIZE x 1.000). Other configs: None.
-MEASURED_TRAFFIC_BYTES_C3 = {"fwd_walk": int((416.1 + 386.5) * 2**20), "bwd_walk": int((790.3 + 385.0) * 2**20),
+MEASURED_TRAFFIC_BYTES_C3 = {"fwd_walk": int((416.2 + 258.7) * 2**20), "bwd_walk": int((660.4 + 385.0) * 2**20),
                              "fwd_local": int((248.1 + 31.0) * 2**20), "bwd_local": int((240.1 + 15.0) * 2**20)}
 
 
@@ -101,8 +101,10 @@ def main():
                 "avg_launch_ms": round(per_launch_ms[dominant], 4),
                 "kernel_ms_per_launch": {n: round(x, 4) for n, x in per_launch_ms.items()}}
 
-    # whole-step figures against both roofs (algorithmic numbers, not issued flops)
-    flops_step = (14 * tile * D + 12 * D * D) * B * H * N
+    # whole-step figures against both roofs: the chunked algorithm's flops per token-head at the
+    # configured chunk length C (intra-chunk 14*C*d, inter-chunk and state updates 12*d*d), not issued
+    # flops (the kernels run shorter tiles than C and rebuild half of the cached states)
+    flops_step = (14 * cfg.chunk * D + 12 * D * D) * B * H * N
     min_bytes_step = 11 * D * esz * B * H * N
     step_s = ms_per_step * 1e-3
     extra = {"algorithmic_tflops": round(flops_step / step_s / 1e12, 2),

@@ -1545,11 +1545,13 @@ int cache_stride_for(int dtype, int tile, int ntiles) {
     return (dtype == 1 && tile == 64 && ntiles % 2 == 0) ? 2 : 1;
 }
 
+// Tokens per kernel tile: 32 for float data, 64 for bfloat16 data, whatever the
+// chunk (both divide every supported chunk length). 64-token bfloat16 tiles let two
+// forward workgroups, or one backward workgroup with every tile it needs, live on a CU.
 int tile_tokens(int dtype, int chunk, int D) {
-    (void)D;
-    if (dtype == 0) return 32;          // float tiles: 32 tokens
     (void)chunk;
-    return 64;
+    (void)D;
+    return dtype == 0 ? 32 : 64;
 }
 
 #define LASP_DISPATCH(FN, ARGS)                                                        \
@@ -1557,12 +1559,8 @@ int tile_tokens(int dtype, int chunk, int D) {
         if (p.D == 64) return FN<float, 32, 64>(p, ARGS, stream, ke);                     \
         return FN<float, 32, 128>(p, ARGS, stream, ke);                                    \
     }                                                                                  \
-    if (p.tile == 64) {                                                                \
-        if (p.D == 64) return FN<bf16_t, 64, 64>(p, ARGS, stream, ke);                     \
-        return FN<bf16_t, 64, 128>(p, ARGS, stream, ke);                                   \
-    }                                                                                  \
-    if (p.D == 64) return FN<bf16_t, 128, 64>(p, ARGS, stream, ke);                        \
-    return FN<bf16_t, 128, 128>(p, ARGS, stream, ke);
+    if (p.D == 64) return FN<bf16_t, 64, 64>(p, ARGS, stream, ke);                         \
+    return FN<bf16_t, 64, 128>(p, ARGS, stream, ke);
 
 hipError_t launch_fwd(const Plan &p, const FwdArgs &a, hipStream_t stream, const KernelEvents *ke) { LASP_DISPATCH(run_fwd, a) }
 hipError_t launch_bwd(const Plan &p, const BwdArgs &a, hipStream_t stream, const KernelEvents *ke) { LASP_DISPATCH(run_bwd, a) }

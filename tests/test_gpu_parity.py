@@ -122,6 +122,34 @@ def test_even_tile_counts_pair_cache(gpu, oracle):
             compare(harness, got, ref, TOL["bf16"], f"D{D}/seg{segments}")
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_extreme_decays(gpu, oracle, dtype):
+    """Degenerate decays in one launch: lambda = 1 (no decay), lambda close to 1, and
+    decays so strong that lambda^tile underflows to zero. Nothing may overflow or go NaN."""
+    harness, lasp, si = gpu
+    cfg = si.Config("decays", B=1, H=4, N=512, D=64, chunk=128, dtype=dtype, seed=21)
+    inp = si.make_inputs(cfg, with_states=True)
+    inp.decay = np.array([1.0, 1.0 - 2.0 ** -20, 0.05, 1e-4], dtype=np.float32)
+    got = harness.run_gpu(inp, segments=4)
+    ref = oracle_all(oracle, inp)
+    for name in NAMES:
+        assert np.all(np.isfinite(got[name])), name
+    compare(harness, got, ref, TOL[dtype], f"decays/{dtype}")
+
+
+def test_single_head_single_tile_and_reuse(gpu, oracle):
+    """Smallest launches (one head, one tile) and a second call on the same workspace
+    with different data: stale scratch or cache contents must not leak into results."""
+    harness, lasp, si = gpu
+    for dtype, n in (("bf16", 64), ("f32", 64), ("bf16", 128)):
+        cfg = si.Config("tiny", B=1, H=1, N=n, D=128, chunk=64, dtype=dtype, seed=31)
+        a = si.make_inputs(cfg, with_states=True)
+        b = si.make_inputs(cfg, with_states=False, seed=32)
+        for inp in (a, b):
+            got = harness.run_gpu(inp)
+            compare(harness, got, oracle_all(oracle, inp), TOL[dtype], f"tiny/{dtype}/{n}")
+
+
 def test_lambda_one_chunk1_limit(gpu, oracle):
     """lambda = 1 (ordinary linear attention) in float: textbook tril(QK^T)V."""
     harness, lasp, si = gpu
