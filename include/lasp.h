@@ -83,11 +83,13 @@ int32_t lasp_tile_tokens(const lasp_shape *shape);
 int32_t lasp_num_segments(const lasp_shape *shape);
 
 /*
- * Bytes of the per-tile state cache: the state KV_{t-1} every tile starts
- * from, written by lasp_fwd and read by lasp_bwd for dQ_inter (the paper caches
- * the state a rank receives, Alg. 2 "save KV_{t-1}", Sec. 3.4; this build
- * caches it per tile so that the backward pass needs no forward recurrence).
- * Stored in `dtype`. 0 on an invalid shape.
+ * Bytes of the state cache: the states KV_{t-1} that tiles start from, written
+ * by lasp_fwd and read by lasp_bwd for dQ_inter (the paper caches the state a
+ * rank receives, Alg. 2 "save KV_{t-1}", Sec. 3.4; this build caches one state
+ * per tile, or one per two tiles where the backward kernel rebuilds the other
+ * on chip, so that the backward pass never reruns the forward recurrence).
+ * The layout is private to the library; slot 0 is kv_in. Stored in `dtype`.
+ * 0 on an invalid shape.
  */
 size_t lasp_state_cache_bytes(const lasp_shape *shape);
 
