@@ -28,6 +28,10 @@
  * Every power of lambda is a direct pow() call: nothing is factored as
  * lambda^i * lambda^-j and Lambda^-1 is never formed.
  *
+ * The second half of the file holds the same three forms for a per-token
+ * decay g_s (the general recurrent form of App. A.4 with a scalar oscillation
+ * state), pinned in tests/test_oracle_gated_pins.py.
+ *
  * Pins (tests/test_oracle_pins.py): textbook tril(QK^T)V at lambda = 1,
  * geometric-series and impulse closed forms, a hand-computed N=3 example,
  * exact finite differences (the loss is multilinear), backward == three
@@ -527,6 +531,494 @@ int lasp_oracle_bwd_chunked(int B, int H, i64 N, int D, int C, const double *q, 
                     for (int a = 0; a < D; ++a) sc[r * D + a] = cc.Lam[r] * Q[r * D + a];
                 matmul_tn(sc, dO, tmp, C, D, D);
                 for (int e = 0; e < D * D; ++e) dKV[e] = cc.lamC * dKV[e] + tmp[e];
+            }
+        }
+        free_consts(&cc);
+        free(S);
+        free(dS);
+        free(tmp);
+        free(sc);
+        free(Otmp);
+        free(cache);
+    }
+    return fail;
+}
+
+/* ================================================================== */
+/* Per-token decay: the general recurrent form of App. A.4,            */
+/*     m_t = o_t m_{t-1} + e_t i_t^T,                                  */
+/* with a scalar oscillation state o_t = g_t per head and token        */
+/* (the TNL/RetNet row of Table 6 has the constant g_t = lambda):      */
+/*     kv_s = g_s kv_{s-1} + k_s v_s^T,   o_s = kv_s^T q_s.            */
+/* Input log_g : [B][H][N], natural logarithm of g (<= 0).             */
+/* W(i,s) = prod_{l=i+1..s} g_l is the weight token i carries at s.    */
+/* Backward also returns dlog_g [B][H][N] = dL/d(log g_s).             */
+/* Every W is a running product of the g themselves: nothing is        */
+/* formed as a quotient of cumulative products.                        */
+/* ================================================================== */
+
+static const double *lgp(const double *log_g, int H, i64 N, int b, int h)
+{
+    return log_g + ((i64)b * H + h) * N;
+}
+
+/* o_s = sum_{i<=s} W(i,s) (q_s . k_i) v_i + W(0,s) K0^T q_s */
+static void gated_fwd_row(const double *q, const double *k, const double *v, const double *lg,
+                          const double *K0, i64 s, int D, double *o)
+{
+    const double *qs = q + (s - 1) * D;
+    for (int c = 0; c < D; ++c) o[c] = 0.0;
+    double w = 1.0; /* W(i,s), i descending from s */
+    for (i64 i = s; i >= 1; --i) {
+        double x = w * dot(qs, k + (i - 1) * D, D);
+        const double *vi = v + (i - 1) * D;
+        for (int c = 0; c < D; ++c) o[c] += x * vi[c];
+        w *= exp(lg[i - 1]); /* now W(i-1,s) */
+    }
+    if (K0)
+        for (int a = 0; a < D; ++a) {
+            double x = w * qs[a];
+            for (int c = 0; c < D; ++c) o[c] += x * K0[a * D + c];
+        }
+}
+
+/* dq_s = sum_{i<=s} W(i,s) (v_i . do_s) k_i + W(0,s) K0 do_s
+ * dk_s = sum_{i>=s} W(s,i) (do_i . v_s) q_i + W(s,N) G v_s
+ * dv_s = sum_{i>=s} W(s,i) (q_i . k_s) do_i + W(s,N) G^T k_s */
+static void gated_bwd_row(const double *q, const double *k, const double *v, const double *dO,
+                          const double *lg, const double *K0, const double *G, i64 s, i64 N, int D,
+                          double *dq, double *dk, double *dv)
+{
+    const double *dos = dO + (s - 1) * D, *ks = k + (s - 1) * D, *vs = v + (s - 1) * D;
+    for (int a = 0; a < D; ++a) dq[a] = dk[a] = dv[a] = 0.0;
+    double w = 1.0;
+    for (i64 i = s; i >= 1; --i) {
+        double x = w * dot(v + (i - 1) * D, dos, D);
+        const double *ki = k + (i - 1) * D;
+        for (int a = 0; a < D; ++a) dq[a] += x * ki[a];
+        w *= exp(lg[i - 1]);
+    }
+    if (K0)
+        for (int a = 0; a < D; ++a) dq[a] += w * dot(K0 + a * D, dos, D);
+    w = 1.0; /* W(s,i), i ascending from s */
+    for (i64 i = s; i <= N; ++i) {
+        double xk = w * dot(dO + (i - 1) * D, vs, D), xv = w * dot(q + (i - 1) * D, ks, D);
+        const double *qi = q + (i - 1) * D, *doi = dO + (i - 1) * D;
+        for (int a = 0; a < D; ++a) dk[a] += xk * qi[a];
+        for (int c = 0; c < D; ++c) dv[c] += xv * doi[c];
+        if (i < N) w *= exp(lg[i]); /* g_{i+1}: now W(s,i+1) */
+    }
+    if (G) /* w = W(s,N) */
+        for (int a = 0; a < D; ++a) {
+            dk[a] += w * dot(G + a * D, vs, D);
+            for (int c = 0; c < D; ++c) dv[c] += w * ks[a] * G[a * D + c];
+        }
+}
+
+int lasp_oracle_gated_fwd_brute(int B, int H, i64 N, int D, const double *q, const double *k,
+                                const double *v, const double *log_g, const double *kv_in,
+                                double *out, double *kv_out)
+{
+    if (!q || !k || !v || !log_g || !out || !kv_out || B <= 0 || H <= 0 || N <= 0 || D <= 0) return 1;
+    i64 total = (i64)B * H * N;
+#pragma omp parallel for schedule(dynamic, 8)
+    for (i64 r = 0; r < total; ++r) {
+        int bh = (int)(r / N), b = bh / H, h = bh % H;
+        i64 s = r % N + 1;
+        gated_fwd_row(rowp(q, H, N, D, b, h, 0), rowp(k, H, N, D, b, h, 0), rowp(v, H, N, D, b, h, 0),
+                      lgp(log_g, H, N, b, h), statep(kv_in, H, D, b, h), s, D,
+                      rowpw(out, H, N, D, b, h, s - 1));
+    }
+    /* kv_out = W(0,N) K0 + sum_i W(i,N) k_i v_i^T */
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int bh = 0; bh < B * H; ++bh) {
+        int b = bh / H, h = bh % H;
+        const double *kk = rowp(k, H, N, D, b, h, 0), *vv = rowp(v, H, N, D, b, h, 0);
+        const double *lg = lgp(log_g, H, N, b, h), *K0 = statep(kv_in, H, D, b, h);
+        double *kvo = kv_out + (i64)bh * D * D;
+        for (int e = 0; e < D * D; ++e) kvo[e] = 0.0;
+        double w = 1.0; /* W(i,N), i descending */
+        for (i64 i = N; i >= 1; --i) {
+            for (int a = 0; a < D; ++a)
+                for (int c = 0; c < D; ++c) kvo[a * D + c] += w * kk[(i - 1) * D + a] * vv[(i - 1) * D + c];
+            w *= exp(lg[i - 1]);
+        }
+        if (K0)
+            for (int e = 0; e < D * D; ++e) kvo[e] += w * K0[e];
+    }
+    return 0;
+}
+
+int lasp_oracle_gated_fwd_brute_rows(int B, int H, i64 N, int D, const double *q, const double *k,
+                                     const double *v, const double *log_g, const double *kv_in,
+                                     i64 nrows, const i64 *rows, double *out_rows)
+{
+    if (!q || !k || !v || !log_g || !rows || !out_rows) return 1;
+    for (i64 r = 0; r < nrows; ++r)
+        if (rows[3 * r] < 0 || rows[3 * r] >= B || rows[3 * r + 1] < 0 || rows[3 * r + 1] >= H ||
+            rows[3 * r + 2] < 0 || rows[3 * r + 2] >= N)
+            return 2;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (i64 r = 0; r < nrows; ++r) {
+        int b = (int)rows[3 * r], h = (int)rows[3 * r + 1];
+        gated_fwd_row(rowp(q, H, N, D, b, h, 0), rowp(k, H, N, D, b, h, 0), rowp(v, H, N, D, b, h, 0),
+                      lgp(log_g, H, N, b, h), statep(kv_in, H, D, b, h), rows[3 * r + 2] + 1, D,
+                      out_rows + r * D);
+    }
+    return 0;
+}
+
+int lasp_oracle_gated_bwd_brute_rows(int B, int H, i64 N, int D, const double *q, const double *k,
+                                     const double *v, const double *dout, const double *log_g,
+                                     const double *kv_in, const double *dkv_out, i64 nrows,
+                                     const i64 *rows, double *dq_rows, double *dk_rows, double *dv_rows)
+{
+    if (!q || !k || !v || !dout || !log_g || !rows || !dq_rows || !dk_rows || !dv_rows) return 1;
+    for (i64 r = 0; r < nrows; ++r)
+        if (rows[3 * r] < 0 || rows[3 * r] >= B || rows[3 * r + 1] < 0 || rows[3 * r + 1] >= H ||
+            rows[3 * r + 2] < 0 || rows[3 * r + 2] >= N)
+            return 2;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (i64 r = 0; r < nrows; ++r) {
+        int b = (int)rows[3 * r], h = (int)rows[3 * r + 1];
+        gated_bwd_row(rowp(q, H, N, D, b, h, 0), rowp(k, H, N, D, b, h, 0), rowp(v, H, N, D, b, h, 0),
+                      rowp(dout, H, N, D, b, h, 0), lgp(log_g, H, N, b, h), statep(kv_in, H, D, b, h),
+                      statep(dkv_out, H, D, b, h), rows[3 * r + 2] + 1, N, D, dq_rows + r * D,
+                      dk_rows + r * D, dv_rows + r * D);
+    }
+    return 0;
+}
+
+/* Brute-force backward. dlog_g by the definition of a derivative of the
+ * expanded loss: L is a sum over (source i, sink t) pairs, i < t, each weighted
+ * by W(i, t); sources are tokens 1..N and the incoming state (i = 0), sinks are
+ * tokens 1..N and the outgoing state (t = N+1, weight W(i,N)). g_s appears
+ * once, as a factor, in exactly the pairs with i < s <= min(t, N), so
+ *     dL/dlog g_s = sum over those pairs of (weight * pair value).
+ * Pair values: (q_t.k_i)(v_i.do_t); q_t^T K0 do_t; k_i^T G v_i; <K0, G>. */
+int lasp_oracle_gated_bwd_brute(int B, int H, i64 N, int D, const double *q, const double *k,
+                                const double *v, const double *dout, const double *log_g,
+                                const double *kv_in, const double *dkv_out, double *dq, double *dk,
+                                double *dv, double *dlog_g, double *dkv_in)
+{
+    if (!q || !k || !v || !dout || !log_g || !dq || !dk || !dv || !dlog_g || !dkv_in) return 1;
+    i64 total = (i64)B * H * N;
+#pragma omp parallel for schedule(dynamic, 8)
+    for (i64 r = 0; r < total; ++r) {
+        int bh = (int)(r / N), b = bh / H, h = bh % H;
+        i64 s = r % N + 1;
+        gated_bwd_row(rowp(q, H, N, D, b, h, 0), rowp(k, H, N, D, b, h, 0), rowp(v, H, N, D, b, h, 0),
+                      rowp(dout, H, N, D, b, h, 0), lgp(log_g, H, N, b, h), statep(kv_in, H, D, b, h),
+                      statep(dkv_out, H, D, b, h), s, N, D, rowpw(dq, H, N, D, b, h, s - 1),
+                      rowpw(dk, H, N, D, b, h, s - 1), rowpw(dv, H, N, D, b, h, s - 1));
+    }
+    int fail = 0;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int bh = 0; bh < B * H; ++bh) {
+        int b = bh / H, h = bh % H;
+        const double *qq = rowp(q, H, N, D, b, h, 0), *kk = rowp(k, H, N, D, b, h, 0),
+                     *vv = rowp(v, H, N, D, b, h, 0), *dd = rowp(dout, H, N, D, b, h, 0);
+        const double *lg = lgp(log_g, H, N, b, h);
+        const double *K0 = statep(kv_in, H, D, b, h), *G = statep(dkv_out, H, D, b, h);
+        /* dkv_in = W(0,N) G + sum_s W(0,s) q_s do_s^T */
+        double *gin = dkv_in + (i64)bh * D * D;
+        for (int e = 0; e < D * D; ++e) gin[e] = 0.0;
+        double w = 1.0;
+        for (i64 s = 1; s <= N; ++s) {
+            w *= exp(lg[s - 1]); /* W(0,s) */
+            for (int a = 0; a < D; ++a)
+                for (int c = 0; c < D; ++c) gin[a * D + c] += w * qq[(s - 1) * D + a] * dd[(s - 1) * D + c];
+        }
+        if (G)
+            for (int e = 0; e < D * D; ++e) gin[e] += w * G[e];
+        /* weighted pair values A[i][t], i = 0..N, t = 1..N+1 (index t-1) */
+        i64 M = N + 1;
+        double *A = (double *)calloc((size_t)(M * M), sizeof(double));
+        if (!A) {
+            fail = 1;
+            continue;
+        }
+        for (i64 i = 0; i <= N; ++i) {
+            if (i == 0 && !K0) continue;
+            double wt = 1.0; /* W(i,t), t ascending from i */
+            for (i64 t = i + 1; t <= N; ++t) {
+                wt *= exp(lg[t - 1]);
+                double val;
+                if (i == 0) { /* q_t^T K0 do_t */
+                    val = 0.0;
+                    for (int a = 0; a < D; ++a) val += qq[(t - 1) * D + a] * dot(K0 + a * D, dd + (t - 1) * D, D);
+                } else {
+                    val = dot(qq + (t - 1) * D, kk + (i - 1) * D, D) * dot(vv + (i - 1) * D, dd + (t - 1) * D, D);
+                }
+                A[i * M + (t - 1)] = wt * val;
+            }
+            if (G) { /* sink N+1 with weight W(i,N) = wt */
+                double val = 0.0;
+                if (i == 0) {
+                    for (int e = 0; e < D * D; ++e) val += K0[e] * G[e];
+                } else {
+                    for (int a = 0; a < D; ++a) val += kk[(i - 1) * D + a] * dot(G + a * D, vv + (i - 1) * D, D);
+                }
+                A[i * M + N] = wt * val;
+            }
+        }
+        double *dl = dlog_g + (i64)bh * N;
+        for (i64 s = 1; s <= N; ++s) {
+            double acc = 0.0;
+            for (i64 i = 0; i < s; ++i)
+                for (i64 t = s; t <= N + 1; ++t) acc += A[i * M + (t - 1)];
+            dl[s - 1] = acc;
+        }
+        free(A);
+    }
+    return fail;
+}
+
+int lasp_oracle_gated_fwd_recurrent(int B, int H, i64 N, int D, const double *q, const double *k,
+                                    const double *v, const double *log_g, const double *kv_in,
+                                    double *out, double *kv_out)
+{
+    if (!q || !k || !v || !log_g || !out || !kv_out) return 1;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int bh = 0; bh < B * H; ++bh) {
+        int b = bh / H, h = bh % H;
+        const double *lg = lgp(log_g, H, N, b, h);
+        double *kv = kv_out + (i64)bh * D * D;
+        const double *K0 = statep(kv_in, H, D, b, h);
+        for (int e = 0; e < D * D; ++e) kv[e] = K0 ? K0[e] : 0.0;
+        for (i64 s = 1; s <= N; ++s) {
+            const double *qs = rowp(q, H, N, D, b, h, s - 1), *ks = rowp(k, H, N, D, b, h, s - 1),
+                         *vs = rowp(v, H, N, D, b, h, s - 1);
+            double *os = rowpw(out, H, N, D, b, h, s - 1);
+            double g = exp(lg[s - 1]);
+            for (int a = 0; a < D; ++a)
+                for (int c = 0; c < D; ++c) kv[a * D + c] = g * kv[a * D + c] + ks[a] * vs[c];
+            for (int c = 0; c < D; ++c) os[c] = 0.0;
+            for (int a = 0; a < D; ++a)
+                for (int c = 0; c < D; ++c) os[c] += qs[a] * kv[a * D + c];
+        }
+    }
+    return 0;
+}
+
+/* Reverse-mode differentiation of the recurrence, step by step:
+ *   D_s = q_s do_s^T + g_{s+1} D_{s+1}  (D_N = q_N do_N^T + G),
+ *   dk_s = D_s v_s, dv_s = D_s^T k_s, dlog g_s = g_s <D_s, kv_{s-1}>, dkv_in = g_1 D_1.
+ * The states kv_{s-1} are rebuilt block by block from checkpoints taken every
+ * P tokens in the forward sweep. */
+int lasp_oracle_gated_bwd_recurrent(int B, int H, i64 N, int D, const double *q, const double *k,
+                                    const double *v, const double *dout, const double *log_g,
+                                    const double *kv_in, const double *dkv_out, double *dq, double *dk,
+                                    double *dv, double *dlog_g, double *dkv_in)
+{
+    if (!q || !k || !v || !dout || !log_g || !dq || !dk || !dv || !dlog_g || !dkv_in) return 1;
+    int fail = 0;
+    const i64 P = 64;
+    const i64 nblk = (N + P - 1) / P;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int bh = 0; bh < B * H; ++bh) {
+        int b = bh / H, h = bh % H;
+        const double *lg = lgp(log_g, H, N, b, h);
+        const double *K0 = statep(kv_in, H, D, b, h), *G = statep(dkv_out, H, D, b, h);
+        size_t DD = (size_t)D * D;
+        double *ckpt = (double *)malloc(sizeof(double) * DD * (size_t)nblk); /* kv at s = 0, P, 2P, .. */
+        double *blk = (double *)malloc(sizeof(double) * DD * (size_t)(P + 1)); /* kv_{s0} .. kv_{s0+P} */
+        double *dkv = (double *)malloc(sizeof(double) * DD);
+        if (!ckpt || !blk || !dkv) {
+            fail = 1;
+            free(ckpt);
+            free(blk);
+            free(dkv);
+            continue;
+        }
+        double *kv = blk; /* running state for the forward sweep */
+        for (size_t e = 0; e < DD; ++e) kv[e] = K0 ? K0[e] : 0.0;
+        for (i64 s = 1; s <= N; ++s) {
+            if ((s - 1) % P == 0) memcpy(ckpt + ((s - 1) / P) * DD, kv, sizeof(double) * DD);
+            const double *ks = rowp(k, H, N, D, b, h, s - 1), *vs = rowp(v, H, N, D, b, h, s - 1),
+                         *ds = rowp(dout, H, N, D, b, h, s - 1);
+            double *dqs = rowpw(dq, H, N, D, b, h, s - 1);
+            double g = exp(lg[s - 1]);
+            for (int a = 0; a < D; ++a)
+                for (int c = 0; c < D; ++c) kv[a * D + c] = g * kv[a * D + c] + ks[a] * vs[c];
+            for (int a = 0; a < D; ++a) dqs[a] = dot(kv + a * D, ds, D); /* dq_s = kv_s do_s */
+        }
+        for (size_t e = 0; e < DD; ++e) dkv[e] = 0.0;
+        double *dl = dlog_g + (i64)bh * N;
+        for (i64 bi = nblk - 1; bi >= 0; --bi) {
+            i64 s0 = bi * P, s1 = (s0 + P < N) ? s0 + P : N; /* tokens s0+1 .. s1 */
+            memcpy(blk, ckpt + bi * DD, sizeof(double) * DD); /* kv_{s0} */
+            for (i64 s = s0 + 1; s < s1; ++s) {             /* kv_s into slot s - s0 */
+                const double *ks = rowp(k, H, N, D, b, h, s - 1), *vs = rowp(v, H, N, D, b, h, s - 1);
+                const double *prev = blk + (size_t)(s - 1 - s0) * DD;
+                double *cur = blk + (size_t)(s - s0) * DD;
+                double g = exp(lg[s - 1]);
+                for (int a = 0; a < D; ++a)
+                    for (int c = 0; c < D; ++c) cur[a * D + c] = g * prev[a * D + c] + ks[a] * vs[c];
+            }
+            for (i64 s = s1; s > s0; --s) {
+                const double *qs = rowp(q, H, N, D, b, h, s - 1), *ks = rowp(k, H, N, D, b, h, s - 1),
+                             *vs = rowp(v, H, N, D, b, h, s - 1), *ds = rowp(dout, H, N, D, b, h, s - 1);
+                double *dks = rowpw(dk, H, N, D, b, h, s - 1), *dvs = rowpw(dv, H, N, D, b, h, s - 1);
+                for (int a = 0; a < D; ++a)
+                    for (int c = 0; c < D; ++c) {
+                        double carried = (s == N) ? (G ? G[a * D + c] : 0.0) : exp(lg[s]) * dkv[a * D + c];
+                        dkv[a * D + c] = carried + qs[a] * ds[c];
+                    }
+                for (int a = 0; a < D; ++a) dks[a] = dot(dkv + a * D, vs, D);
+                for (int c = 0; c < D; ++c) dvs[c] = 0.0;
+                for (int a = 0; a < D; ++a)
+                    for (int c = 0; c < D; ++c) dvs[c] += dkv[a * D + c] * ks[a];
+                const double *kvprev = blk + (size_t)(s - 1 - s0) * DD; /* kv_{s-1} */
+                double ip = 0.0;
+                for (size_t e = 0; e < DD; ++e) ip += dkv[e] * kvprev[e];
+                dl[s - 1] = exp(lg[s - 1]) * ip;
+            }
+        }
+        double *gin = dkv_in + (i64)bh * D * D;
+        double g1 = exp(lg[0]);
+        for (size_t e = 0; e < DD; ++e) gin[e] = g1 * dkv[e];
+        free(ckpt);
+        free(blk);
+        free(dkv);
+    }
+    return fail;
+}
+
+/* Chunk constants of Alg. 2 with per-token decay, for the chunk whose log
+ * decays are lg[0..C-1]: M_ij = W(j,i) for i >= j, Lambda_i = W(0,i),
+ * "lambda^C Lambda^-1"_j = W(j,C), "lambda^C" = W(0,C) (tokens 1-based in the chunk). */
+static void gated_consts(chunk_consts *cc, const double *lg, int C)
+{
+    for (int i = 1; i <= C; ++i) {
+        for (int j = 1; j <= C; ++j) cc->M[(i - 1) * C + (j - 1)] = 0.0;
+        double w = 1.0;
+        for (int j = i; j >= 1; --j) {
+            cc->M[(i - 1) * C + (j - 1)] = w;
+            w *= exp(lg[j - 1]);
+        }
+        cc->Lam[i - 1] = w; /* W(0,i) */
+    }
+    double w = 1.0;
+    for (int j = C; j >= 1; --j) {
+        cc->LamInv[j - 1] = w; /* W(j,C) */
+        w *= exp(lg[j - 1]);
+    }
+    cc->lamC = w;
+}
+
+int lasp_oracle_gated_fwd_chunked(int B, int H, i64 N, int D, int C, const double *q, const double *k,
+                                  const double *v, const double *log_g, const double *kv_in,
+                                  double *out, double *kv_out)
+{
+    if (!q || !k || !v || !log_g || !out || !kv_out || C <= 0 || N % C != 0) return 1;
+    int fail = 0;
+    int big = (C > D ? C : D);
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int bh = 0; bh < B * H; ++bh) {
+        int b = bh / H, h = bh % H;
+        chunk_consts cc;
+        double *S = (double *)malloc(sizeof(double) * C * C);
+        double *tmp = (double *)malloc(sizeof(double) * big * D);
+        double *Kd = (double *)malloc(sizeof(double) * C * D);
+        if (make_consts(&cc, 1.0, C) || !S || !tmp || !Kd) {
+            fail = 1;
+        } else {
+            double *KV = kv_out + (i64)bh * D * D;
+            const double *K0 = statep(kv_in, H, D, b, h);
+            for (int e = 0; e < D * D; ++e) KV[e] = K0 ? K0[e] : 0.0;
+            for (i64 t = 0; t < N / C; ++t) {
+                gated_consts(&cc, lgp(log_g, H, N, b, h) + t * C, C);
+                fwd_chunk(&cc, rowp(q, H, N, D, b, h, t * C), rowp(k, H, N, D, b, h, t * C),
+                          rowp(v, H, N, D, b, h, t * C), KV, rowpw(out, H, N, D, b, h, t * C), C, D,
+                          S, tmp, Kd);
+            }
+        }
+        free_consts(&cc);
+        free(S);
+        free(tmp);
+        free(Kd);
+    }
+    return fail;
+}
+
+/* Alg. 3 per chunk with the chunk constants above. dlog_g follows from the
+ * other gradients: with r_t = q_t.dq_t - k_t.dk_t,
+ *     dlog g_s = <G, kv_out> + sum_{t>=s} r_t
+ * (from <D_s, kv_s> = dlog g_s + k_s.dk_s = q_s.dq_s + dlog g_{s+1}, the two
+ * ways of expanding kv_s and D_s by their recurrences). */
+int lasp_oracle_gated_bwd_chunked(int B, int H, i64 N, int D, int C, const double *q, const double *k,
+                                  const double *v, const double *dout, const double *log_g,
+                                  const double *kv_in, const double *dkv_out, double *dq, double *dk,
+                                  double *dv, double *dlog_g, double *dkv_in)
+{
+    if (!q || !k || !v || !dout || !log_g || !dq || !dk || !dv || !dlog_g || !dkv_in || C <= 0 || N % C != 0)
+        return 1;
+    int fail = 0;
+    i64 T = N / C;
+    int big = (C > D ? C : D);
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int bh = 0; bh < B * H; ++bh) {
+        int b = bh / H, h = bh % H;
+        chunk_consts cc;
+        double *S = (double *)malloc(sizeof(double) * C * C);
+        double *dS = (double *)malloc(sizeof(double) * C * C);
+        double *tmp = (double *)malloc(sizeof(double) * big * D);
+        double *sc = (double *)malloc(sizeof(double) * C * D);
+        double *Otmp = (double *)malloc(sizeof(double) * C * D);
+        double *cache = (double *)malloc(sizeof(double) * (T + 1) * D * D);
+        if (make_consts(&cc, 1.0, C) || !S || !dS || !tmp || !sc || !Otmp || !cache) {
+            fail = 1;
+        } else {
+            const double *lg = lgp(log_g, H, N, b, h);
+            const double *K0 = statep(kv_in, H, D, b, h), *G = statep(dkv_out, H, D, b, h);
+            for (int e = 0; e < D * D; ++e) cache[e] = K0 ? K0[e] : 0.0;
+            for (i64 t = 0; t < T; ++t) {
+                memcpy(cache + (t + 1) * D * D, cache + t * D * D, sizeof(double) * D * D);
+                gated_consts(&cc, lg + t * C, C);
+                fwd_chunk(&cc, rowp(q, H, N, D, b, h, t * C), rowp(k, H, N, D, b, h, t * C),
+                          rowp(v, H, N, D, b, h, t * C), cache + (t + 1) * D * D, Otmp, C, D, S, tmp, sc);
+            }
+            double tail = 0.0; /* <G, kv_out> */
+            if (G)
+                for (int e = 0; e < D * D; ++e) tail += G[e] * cache[T * D * D + e];
+            double *dKV = dkv_in + (i64)bh * D * D;
+            for (int e = 0; e < D * D; ++e) dKV[e] = G ? G[e] : 0.0;
+            double *dl = dlog_g + (i64)bh * N;
+            for (i64 t = T - 1; t >= 0; --t) {
+                const double *Q = rowp(q, H, N, D, b, h, t * C), *K = rowp(k, H, N, D, b, h, t * C),
+                             *V = rowp(v, H, N, D, b, h, t * C), *dO = rowp(dout, H, N, D, b, h, t * C);
+                double *dQ = rowpw(dq, H, N, D, b, h, t * C), *dK = rowpw(dk, H, N, D, b, h, t * C),
+                       *dV = rowpw(dv, H, N, D, b, h, t * C);
+                const double *KVprev = cache + t * D * D;
+                gated_consts(&cc, lg + t * C, C);
+                matmul_nt(dO, V, dS, C, D, C);
+                for (int e = 0; e < C * C; ++e) dS[e] *= cc.M[e];
+                matmul(dS, K, dQ, C, C, D);
+                matmul_tn(dS, Q, dK, C, C, D);
+                matmul_nt(Q, K, S, C, D, C);
+                for (int e = 0; e < C * C; ++e) S[e] *= cc.M[e];
+                matmul_tn(S, dO, dV, C, C, D);
+                matmul_nt(dO, KVprev, tmp, C, D, D);
+                for (int r = 0; r < C; ++r)
+                    for (int a = 0; a < D; ++a) dQ[r * D + a] += cc.Lam[r] * tmp[r * D + a];
+                for (int r = 0; r < C; ++r)
+                    for (int c = 0; c < D; ++c) sc[r * D + c] = cc.LamInv[r] * V[r * D + c];
+                matmul_nt(sc, dKV, tmp, C, D, D);
+                for (int e = 0; e < C * D; ++e) dK[e] += tmp[e];
+                for (int r = 0; r < C; ++r)
+                    for (int a = 0; a < D; ++a) sc[r * D + a] = cc.LamInv[r] * K[r * D + a];
+                matmul(sc, dKV, tmp, C, D, D);
+                for (int e = 0; e < C * D; ++e) dV[e] += tmp[e];
+                for (int r = 0; r < C; ++r)
+                    for (int a = 0; a < D; ++a) sc[r * D + a] = cc.Lam[r] * Q[r * D + a];
+                matmul_tn(sc, dO, tmp, C, D, D);
+                for (int e = 0; e < D * D; ++e) dKV[e] = cc.lamC * dKV[e] + tmp[e];
+                /* tokens of this chunk, last to first: running sum of r_t */
+                for (int r = C - 1; r >= 0; --r) {
+                    tail += dot(Q + r * D, dQ + r * D, D) - dot(K + r * D, dK + r * D, D);
+                    dl[t * C + r] = tail;
+                }
             }
         }
         free_consts(&cc);

@@ -208,3 +208,146 @@ def bwd_split(bwd_fn, q, k, v, dout, decay, T, kv_ins, dkv_out=None, **kw):
         dqs[t], dks[t], dvs[t], g = bwd_fn(q[:, :, sl], k[:, :, sl], v[:, :, sl], dout[:, :, sl], decay,
                                            kv_in=kv_ins[t], dkv_out=g, **kw)
     return np.concatenate(dqs, axis=2), np.concatenate(dks, axis=2), np.concatenate(dvs, axis=2), g
+
+
+# ---------------------------------------------------------------------------
+# Per-token decay g_s (general recurrent form of App. A.4 with a scalar
+# oscillation state): kv_s = g_s kv_{s-1} + k_s v_s^T. log_g is [B,H,N], the
+# natural logarithm of g. Backward returns (dq, dk, dv, dlog_g, dkv_in).
+# ---------------------------------------------------------------------------
+def _lg(log_g, B, H, N):
+    log_g = _d(log_g)
+    if log_g.shape != (B, H, N):
+        raise ValueError("log_g must be [B,H,N]")
+    return log_g
+
+
+def _gated_fwd(name, q, k, v, log_g, kv_in, chunk=None):
+    lib = _load()
+    q, k, v = _d(q), _d(k), _d(v)
+    B, H, N, D = _shape(q)
+    log_g = _lg(log_g, B, H, N)
+    kv_in = _opt_state(kv_in, B, H, D)
+    out = np.empty_like(q)
+    kv_out = np.empty((B, H, D, D), dtype=np.float64)
+    args = [ctypes.c_int(B), ctypes.c_int(H), ctypes.c_longlong(N), ctypes.c_int(D)]
+    if chunk is not None:
+        args.append(ctypes.c_int(int(chunk)))
+    args += [_p(q), _p(k), _p(v), _p(log_g), _p(kv_in), _p(out), _p(kv_out)]
+    rc = getattr(lib, name)(*args)
+    if rc != 0:
+        raise RuntimeError(f"{name} failed with code {rc}")
+    return out, kv_out
+
+
+def _gated_bwd(name, q, k, v, dout, log_g, kv_in, dkv_out, chunk=None):
+    lib = _load()
+    q, k, v, dout = _d(q), _d(k), _d(v), _d(dout)
+    B, H, N, D = _shape(q)
+    log_g = _lg(log_g, B, H, N)
+    kv_in = _opt_state(kv_in, B, H, D)
+    dkv_out = _opt_state(dkv_out, B, H, D)
+    dq, dk, dv = np.empty_like(q), np.empty_like(q), np.empty_like(q)
+    dlg = np.empty((B, H, N), dtype=np.float64)
+    dkv_in = np.empty((B, H, D, D), dtype=np.float64)
+    args = [ctypes.c_int(B), ctypes.c_int(H), ctypes.c_longlong(N), ctypes.c_int(D)]
+    if chunk is not None:
+        args.append(ctypes.c_int(int(chunk)))
+    args += [_p(q), _p(k), _p(v), _p(dout), _p(log_g), _p(kv_in), _p(dkv_out), _p(dq), _p(dk), _p(dv), _p(dlg),
+             _p(dkv_in)]
+    rc = getattr(lib, name)(*args)
+    if rc != 0:
+        raise RuntimeError(f"{name} failed with code {rc}")
+    return dq, dk, dv, dlg, dkv_in
+
+
+def gated_fwd_brute(q, k, v, log_g, kv_in=None):
+    """Definition: o_s = sum_{i<=s} (prod_{l=i+1..s} g_l)(q_s.k_i) v_i + (prod_{l<=s} g_l) K0^T q_s."""
+    return _gated_fwd("lasp_oracle_gated_fwd_brute", q, k, v, log_g, kv_in)
+
+
+def gated_fwd_recurrent(q, k, v, log_g, kv_in=None):
+    return _gated_fwd("lasp_oracle_gated_fwd_recurrent", q, k, v, log_g, kv_in)
+
+
+def gated_fwd_chunked(q, k, v, log_g, chunk, kv_in=None):
+    return _gated_fwd("lasp_oracle_gated_fwd_chunked", q, k, v, log_g, kv_in, chunk=chunk)
+
+
+def gated_bwd_brute(q, k, v, dout, log_g, kv_in=None, dkv_out=None):
+    return _gated_bwd("lasp_oracle_gated_bwd_brute", q, k, v, dout, log_g, kv_in, dkv_out)
+
+
+def gated_bwd_recurrent(q, k, v, dout, log_g, kv_in=None, dkv_out=None):
+    return _gated_bwd("lasp_oracle_gated_bwd_recurrent", q, k, v, dout, log_g, kv_in, dkv_out)
+
+
+def gated_bwd_chunked(q, k, v, dout, log_g, chunk, kv_in=None, dkv_out=None):
+    return _gated_bwd("lasp_oracle_gated_bwd_chunked", q, k, v, dout, log_g, kv_in, dkv_out, chunk=chunk)
+
+
+def gated_fwd_brute_rows(q, k, v, log_g, rows, kv_in=None):
+    lib = _load()
+    q, k, v = _d(q), _d(k), _d(v)
+    B, H, N, D = _shape(q)
+    log_g = _lg(log_g, B, H, N)
+    kv_in = _opt_state(kv_in, B, H, D)
+    rows = _rows(rows, B, H, N)
+    out = np.empty((rows.shape[0], D), dtype=np.float64)
+    rc = lib.lasp_oracle_gated_fwd_brute_rows(
+        ctypes.c_int(B), ctypes.c_int(H), ctypes.c_longlong(N), ctypes.c_int(D), _p(q), _p(k), _p(v),
+        _p(log_g), _p(kv_in), ctypes.c_longlong(rows.shape[0]), rows.ctypes.data_as(_ip), _p(out))
+    if rc != 0:
+        raise RuntimeError(f"gated_fwd_brute_rows failed with code {rc}")
+    return out
+
+
+def gated_bwd_brute_rows(q, k, v, dout, log_g, rows, kv_in=None, dkv_out=None):
+    lib = _load()
+    q, k, v, dout = _d(q), _d(k), _d(v), _d(dout)
+    B, H, N, D = _shape(q)
+    log_g = _lg(log_g, B, H, N)
+    kv_in = _opt_state(kv_in, B, H, D)
+    dkv_out = _opt_state(dkv_out, B, H, D)
+    rows = _rows(rows, B, H, N)
+    n = rows.shape[0]
+    dq, dk, dv = (np.empty((n, D), dtype=np.float64) for _ in range(3))
+    rc = lib.lasp_oracle_gated_bwd_brute_rows(
+        ctypes.c_int(B), ctypes.c_int(H), ctypes.c_longlong(N), ctypes.c_int(D), _p(q), _p(k), _p(v),
+        _p(dout), _p(log_g), _p(kv_in), _p(dkv_out), ctypes.c_longlong(n), rows.ctypes.data_as(_ip),
+        _p(dq), _p(dk), _p(dv))
+    if rc != 0:
+        raise RuntimeError(f"gated_bwd_brute_rows failed with code {rc}")
+    return dq, dk, dv
+
+
+def gated_fwd_split(fwd_fn, q, k, v, log_g, T, kv_in=None, **kw):
+    """T sub-sequences in order, the state handed on; returns (out, kv_out, kv_ins, kv_outs)."""
+    q, k, v, log_g = _d(q), _d(k), _d(v), _d(log_g)
+    N = q.shape[2]
+    assert N % T == 0
+    n = N // T
+    outs, kv_ins, kv_outs = [], [], []
+    state = kv_in
+    for t in range(T):
+        sl = slice(t * n, (t + 1) * n)
+        kv_ins.append(state)
+        o, state = fwd_fn(q[:, :, sl], k[:, :, sl], v[:, :, sl], log_g[:, :, sl], kv_in=state, **kw)
+        kv_outs.append(state)
+        outs.append(o)
+    return np.concatenate(outs, axis=2), state, kv_ins, kv_outs
+
+
+def gated_bwd_split(bwd_fn, q, k, v, dout, log_g, T, kv_ins, dkv_out=None, **kw):
+    """Reverse loop: sub-sequence t receives dkv from t+1; returns (dq, dk, dv, dlog_g, dkv_in)."""
+    q, k, v, dout, log_g = _d(q), _d(k), _d(v), _d(dout), _d(log_g)
+    N = q.shape[2]
+    n = N // T
+    dqs, dks, dvs, dls = [None] * T, [None] * T, [None] * T, [None] * T
+    g = dkv_out
+    for t in reversed(range(T)):
+        sl = slice(t * n, (t + 1) * n)
+        dqs[t], dks[t], dvs[t], dls[t], g = bwd_fn(q[:, :, sl], k[:, :, sl], v[:, :, sl], dout[:, :, sl],
+                                                   log_g[:, :, sl], kv_in=kv_ins[t], dkv_out=g, **kw)
+    cat = lambda xs: np.concatenate(xs, axis=2)
+    return cat(dqs), cat(dks), cat(dvs), cat(dls), g
