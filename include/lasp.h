@@ -137,6 +137,43 @@ int lasp_bwd(const lasp_shape *shape, const void *q, const void *k, const void *
              void *scratch, size_t scratch_bytes, void *hip_stream);
 
 /*
+ * ---- Per-token decay -------------------------------------------------------
+ * The same path for the general recurrent form of App. A.4, m_t = o_t m_{t-1} +
+ * e_t i_t^T, with a scalar oscillation state o_t = g_t per head and token (Table 6:
+ * the TNL/RetNet row is the constant g_t = lambda; a decay that depends on the
+ * token is the scalar case of the GLA/GateLoop and Mamba rows):
+ *     kv_s = g_s kv_{s-1} + k_s v_s^T,     out_s = kv_s^T q_s,
+ * i.e. with W(i,s) = g_{i+1} ... g_s (empty product = 1)
+ *     out_s  = sum_{i<=s} W(i,s) (q_s . k_i) v_i + W(0,s) kv_in^T q_s
+ *     kv_out = W(0,N) kv_in + sum_i W(i,N) k_i v_i^T.
+ * Per tile this is Alg. 2 / Alg. 3 with M_ij = W(j,i), Lambda = diag{W(0,i)},
+ * lambda^C Lambda^-1 = diag{W(j,C)}, lambda^C = W(0,C).
+ *
+ *   log_g   DEVICE float [B][H][N]: natural logarithm of g, finite and <= 0. The
+ *           library cannot inspect device memory; lasp_check_log_decay validates a
+ *           host copy. Values > 0 or non-finite give undefined numbers (never a
+ *           fault).
+ *   dlog_g  DEVICE float [B][H][N]: gradient of the loss w.r.t. log g_s,
+ *               dlog_g_s = <dkv_out, kv_out> + sum_{t>=s} (q_t . dq_t - k_t . dk_t).
+ *   kv_out  (backward) the state the matching lasp_gated_fwd returned; required
+ *           when dkv_out is given, ignored otherwise.
+ * Everything else (layouts, states, state_cache, scratch, stream, status codes,
+ * aliasing rules) is as for lasp_fwd / lasp_bwd, with the sizes from the
+ * lasp_gated_* size functions.
+ */
+int lasp_check_log_decay(const float *log_g_host, int64_t n);
+size_t lasp_gated_state_cache_bytes(const lasp_shape *shape);
+size_t lasp_gated_scratch_bytes(const lasp_shape *shape);
+int lasp_gated_fwd(const lasp_shape *shape, const void *q, const void *k, const void *v,
+                   const float *log_g, const float *kv_in, void *out, float *kv_out,
+                   void *state_cache, void *scratch, size_t scratch_bytes, void *hip_stream);
+int lasp_gated_bwd(const lasp_shape *shape, const void *q, const void *k, const void *v,
+                   const void *dout, const float *log_g, const float *kv_out,
+                   const float *dkv_out, const void *state_cache, void *dq, void *dk, void *dv,
+                   float *dlog_g, float *dkv_in, void *scratch, size_t scratch_bytes,
+                   void *hip_stream);
+
+/*
  * Per-kernel timing, for benchmarks (diagnostic; not on the hot path, not
  * thread-safe). Between lasp_profile_begin and lasp_profile_end every
  * lasp_fwd / lasp_bwd call records HIP events around its three kernels on the

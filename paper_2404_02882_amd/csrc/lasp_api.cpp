@@ -28,7 +28,7 @@ bool valid_dims(const lasp_shape *s) {
     return true;
 }
 
-int make_plan(const lasp_shape *s, Pass pass, lasp::Plan *p) {
+int make_plan(const lasp_shape *s, Pass pass, lasp::Plan *p, bool token = false) {
     if (!s) return LASP_ERR_NULL;
     if (s->dtype != LASP_F32 && s->dtype != LASP_BF16) return LASP_ERR_DTYPE;
     if (!valid_dims(s)) return LASP_ERR_SHAPE;
@@ -48,7 +48,8 @@ int make_plan(const lasp_shape *s, Pass pass, lasp::Plan *p) {
         if (want > p->ntiles) want = p->ntiles;
         if (want < 1) want = 1;
     }
-    p->cache_stride = lasp::cache_stride_for(p->dtype, p->tile, p->ntiles);
+    p->token = token;
+    p->cache_stride = lasp::cache_stride_for(p->dtype, p->tile, p->ntiles, token);
     p->tiles_per_seg = (p->ntiles + want - 1) / want;
     if (p->cache_stride == 2) p->tiles_per_seg += p->tiles_per_seg & 1;   // segments start on cached tiles
     p->nseg = (p->ntiles + p->tiles_per_seg - 1) / p->tiles_per_seg;  // every segment non-empty
@@ -56,6 +57,32 @@ int make_plan(const lasp_shape *s, Pass pass, lasp::Plan *p) {
 }
 
 size_t elem_bytes(int dtype) { return dtype == LASP_F32 ? 4 : 2; }
+
+size_t cache_bytes(const lasp_shape *shape, bool token) {
+    lasp::Plan p;
+    if (make_plan(shape, kForward, &p, token) != LASP_OK) return 0;
+    return (size_t)p.B * p.H * (p.ntiles / p.cache_stride) * p.D * p.D * elem_bytes(p.dtype);
+}
+
+// Scratch layout: [segment states][per-token decay only: segment log-decays][.. : per-token r_t].
+struct ScratchLayout {
+    size_t states, seglog, rtok, total;  // byte offsets of the three regions (states = 0) and the total size
+};
+bool scratch_layout(const lasp_shape *shape, bool token, ScratchLayout *l) {
+    lasp::Plan f, b;
+    if (make_plan(shape, kForward, &f, token) != LASP_OK || make_plan(shape, kBackward, &b, token) != LASP_OK) return false;
+    const size_t nseg = f.nseg > b.nseg ? f.nseg : b.nseg;  // one buffer serves both passes
+    const size_t chains = (size_t)f.B * f.H;
+    l->states = 0;
+    l->seglog = chains * nseg * f.D * f.D * sizeof(float);
+    l->rtok = l->seglog;
+    l->total = l->seglog;
+    if (token) {
+        l->rtok = l->seglog + ((chains * nseg * sizeof(float) + 255) / 256) * 256;
+        l->total = l->rtok + chains * (size_t)f.N * sizeof(float);
+    }
+    return true;
+}
 
 // Event pool of the diagnostic profiler (lasp_profile_begin / lasp_profile_end).
 struct Profiler {
@@ -88,7 +115,7 @@ const char *lasp_status_str(int status) {
         case LASP_ERR_NULL: return "a required pointer is NULL";
         case LASP_ERR_SHAPE: return "unsupported shape (need B,H,N > 0, D in {64,128}, chunk in {64,128,256}, N % chunk == 0, 0 <= segments <= N/tile)";
         case LASP_ERR_DTYPE: return "unsupported dtype (LASP_F32 or LASP_BF16)";
-        case LASP_ERR_DECAY: return "decay must be finite and in (0, 1]";
+        case LASP_ERR_DECAY: return "decay must be finite and in (0, 1] (log decay: finite and <= 0)";
         case LASP_ERR_WORKSPACE: return "scratch buffer missing or too small (see lasp_scratch_bytes)";
         case LASP_ERR_ALIAS: return "an output buffer overlaps an input or another output";
         case LASP_ERR_HIP: return "HIP runtime error at launch";
@@ -121,17 +148,28 @@ int32_t lasp_num_segments(const lasp_shape *shape) {
     return make_plan(shape, kForward, &p) == LASP_OK ? p.nseg : 0;
 }
 
-size_t lasp_state_cache_bytes(const lasp_shape *shape) {
-    lasp::Plan p;
-    if (make_plan(shape, kForward, &p) != LASP_OK) return 0;
-    return (size_t)p.B * p.H * (p.ntiles / p.cache_stride) * p.D * p.D * elem_bytes(p.dtype);
-}
+size_t lasp_state_cache_bytes(const lasp_shape *shape) { return cache_bytes(shape, false); }
 
 size_t lasp_scratch_bytes(const lasp_shape *shape) {
-    lasp::Plan f, b;
-    if (make_plan(shape, kForward, &f) != LASP_OK || make_plan(shape, kBackward, &b) != LASP_OK) return 0;
-    const int nseg = f.nseg > b.nseg ? f.nseg : b.nseg;  // one buffer serves both passes
-    return (size_t)f.B * f.H * nseg * f.D * f.D * sizeof(float);
+    ScratchLayout l;
+    return scratch_layout(shape, false, &l) ? l.total : 0;
+}
+
+size_t lasp_gated_state_cache_bytes(const lasp_shape *shape) { return cache_bytes(shape, true); }
+
+size_t lasp_gated_scratch_bytes(const lasp_shape *shape) {
+    ScratchLayout l;
+    return scratch_layout(shape, true, &l) ? l.total : 0;
+}
+
+int lasp_check_log_decay(const float *log_g_host, int64_t n) {
+    if (!log_g_host) return LASP_ERR_NULL;
+    if (n <= 0) return LASP_ERR_SHAPE;
+    for (int64_t i = 0; i < n; ++i) {
+        float x = log_g_host[i];
+        if (!std::isfinite(x) || x > 0.0f) return LASP_ERR_DECAY;
+    }
+    return LASP_OK;
 }
 
 int lasp_fwd(const lasp_shape *shape, const void *q, const void *k, const void *v, const float *kv_in,
@@ -156,7 +194,7 @@ int lasp_fwd(const lasp_shape *shape, const void *q, const void *k, const void *
         for (const Span &o2 : outs)
             if (&o != &o2 && overlap(o, o2)) return LASP_ERR_ALIAS;
     }
-    lasp::FwdArgs a{q, k, v, kv_in, decay, out, kv_out, state_cache, (float *)scratch};
+    lasp::FwdArgs a{q, k, v, kv_in, decay, out, kv_out, state_cache, (float *)scratch, nullptr};
     return lasp::launch_fwd(p, a, (hipStream_t)hip_stream, next_slot(0)) == hipSuccess ? LASP_OK : LASP_ERR_HIP;
 }
 
@@ -183,7 +221,69 @@ int lasp_bwd(const lasp_shape *shape, const void *q, const void *k, const void *
         for (const Span &o2 : outs)
             if (&o != &o2 && overlap(o, o2)) return LASP_ERR_ALIAS;
     }
-    lasp::BwdArgs a{q, k, v, dout, dkv_out, decay, state_cache, dq, dk, dv, dkv_in, (float *)scratch};
+    lasp::BwdArgs a{q, k, v, dout, dkv_out, decay, state_cache, dq, dk, dv, dkv_in, (float *)scratch,
+                    nullptr, nullptr, nullptr, nullptr};
+    return lasp::launch_bwd(p, a, (hipStream_t)hip_stream, next_slot(1)) == hipSuccess ? LASP_OK : LASP_ERR_HIP;
+}
+
+int lasp_gated_fwd(const lasp_shape *shape, const void *q, const void *k, const void *v, const float *log_g,
+                   const float *kv_in, void *out, float *kv_out, void *state_cache, void *scratch,
+                   size_t scratch_bytes, void *hip_stream) {
+    lasp::Plan p;
+    int rc = make_plan(shape, kForward, &p, true);
+    if (rc != LASP_OK) return rc;
+    if (!q || !k || !v || !log_g || !out || !kv_out) return LASP_ERR_NULL;
+    ScratchLayout l;
+    scratch_layout(shape, true, &l);
+    if (!scratch || scratch_bytes < l.total) return LASP_ERR_WORKSPACE;
+
+    const size_t tb = (size_t)p.B * p.H * p.N * p.D * elem_bytes(p.dtype);
+    const size_t sb = (size_t)p.B * p.H * p.D * p.D * sizeof(float);
+    const size_t gb = (size_t)p.B * p.H * p.N * sizeof(float);
+    const Span ins[] = {{(const char *)q, tb}, {(const char *)k, tb}, {(const char *)v, tb},
+                        {(const char *)kv_in, sb}, {(const char *)log_g, gb}};
+    const Span outs[] = {{(const char *)out, tb}, {(const char *)kv_out, sb},
+                         {(const char *)state_cache, cache_bytes(shape, true)}, {(const char *)scratch, l.total}};
+    for (const Span &o : outs) {
+        for (const Span &i : ins)
+            if (overlap(o, i)) return LASP_ERR_ALIAS;
+        for (const Span &o2 : outs)
+            if (&o != &o2 && overlap(o, o2)) return LASP_ERR_ALIAS;
+    }
+    lasp::FwdArgs a{q, k, v, kv_in, log_g, out, kv_out, state_cache, (float *)scratch,
+                    (float *)((char *)scratch + l.seglog)};
+    return lasp::launch_fwd(p, a, (hipStream_t)hip_stream, next_slot(0)) == hipSuccess ? LASP_OK : LASP_ERR_HIP;
+}
+
+int lasp_gated_bwd(const lasp_shape *shape, const void *q, const void *k, const void *v, const void *dout,
+                   const float *log_g, const float *kv_out, const float *dkv_out, const void *state_cache,
+                   void *dq, void *dk, void *dv, float *dlog_g, float *dkv_in, void *scratch,
+                   size_t scratch_bytes, void *hip_stream) {
+    lasp::Plan p;
+    int rc = make_plan(shape, kBackward, &p, true);
+    if (rc != LASP_OK) return rc;
+    if (!q || !k || !v || !dout || !log_g || !state_cache || !dq || !dk || !dv || !dlog_g || !dkv_in) return LASP_ERR_NULL;
+    if (dkv_out && !kv_out) return LASP_ERR_NULL;
+    ScratchLayout l;
+    scratch_layout(shape, true, &l);
+    if (!scratch || scratch_bytes < l.total) return LASP_ERR_WORKSPACE;
+
+    const size_t tb = (size_t)p.B * p.H * p.N * p.D * elem_bytes(p.dtype);
+    const size_t sb = (size_t)p.B * p.H * p.D * p.D * sizeof(float);
+    const size_t gb = (size_t)p.B * p.H * p.N * sizeof(float);
+    const Span ins[] = {{(const char *)q, tb}, {(const char *)k, tb}, {(const char *)v, tb},
+                        {(const char *)dout, tb}, {(const char *)dkv_out, sb}, {(const char *)kv_out, sb},
+                        {(const char *)log_g, gb}, {(const char *)state_cache, cache_bytes(shape, true)}};
+    const Span outs[] = {{(const char *)dq, tb}, {(const char *)dk, tb}, {(const char *)dv, tb},
+                         {(const char *)dlog_g, gb}, {(const char *)dkv_in, sb}, {(const char *)scratch, l.total}};
+    for (const Span &o : outs) {
+        for (const Span &i : ins)
+            if (overlap(o, i)) return LASP_ERR_ALIAS;
+        for (const Span &o2 : outs)
+            if (&o != &o2 && overlap(o, o2)) return LASP_ERR_ALIAS;
+    }
+    lasp::BwdArgs a{q, k, v, dout, dkv_out, log_g, state_cache, dq, dk, dv, dkv_in, (float *)scratch,
+                    kv_out, dlog_g, (float *)((char *)scratch + l.seglog), (float *)((char *)scratch + l.rtok)};
     return lasp::launch_bwd(p, a, (hipStream_t)hip_stream, next_slot(1)) == hipSuccess ? LASP_OK : LASP_ERR_HIP;
 }
 

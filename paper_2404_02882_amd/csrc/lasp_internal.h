@@ -18,16 +18,18 @@ struct Plan {
     int nseg;           // segments per head (S)
     int tiles_per_seg;  // ceil(ntiles / nseg); the last segment may be shorter
     int cache_stride;   // the state cache holds the start state of every cache_stride-th tile (1 or 2)
+    bool token;         // per-token decay: `decay` of the argument structs is log g, [B][H][N]
 };
 
 struct FwdArgs {
     const void *q, *k, *v;
     const float *kv_in;   // may be null (zeros)
-    const float *decay;
+    const float *decay;   // lambda [H], or log g [B][H][N] with per-token decay
     void *out;
     float *kv_out;
     void *cache;          // may be null
     float *scratch;       // [B*H][nseg][D][D]
+    float *seglog;        // per-token decay only: [B*H][nseg], log2 of the decay over each segment
 };
 
 struct BwdArgs {
@@ -38,6 +40,11 @@ struct BwdArgs {
     void *dq, *dk, *dv;
     float *dkv_in;
     float *scratch;
+    // per-token decay only
+    const float *kv_out;  // state the forward pass returned (needed when dkv_out is given)
+    float *dlog_g;        // [B][H][N]
+    float *seglog;        // [B*H][nseg]
+    float *rtok;          // [B*H][N] scratch: q_t.dq_t - k_t.dk_t
 };
 
 // Optional event recorder: when non-null, launch_* records ev[0] before the
@@ -50,7 +57,7 @@ struct KernelEvents {
 int tile_tokens(int dtype, int chunk, int D);
 // Cache stride for a shape: 2 (one cached state per pair of tiles, the backward
 // walk rebuilds the other) when the kernels support it, else 1.
-int cache_stride_for(int dtype, int tile, int ntiles);
+int cache_stride_for(int dtype, int tile, int ntiles, bool token);
 
 hipError_t launch_fwd(const Plan &p, const FwdArgs &a, hipStream_t stream, const KernelEvents *ke);
 hipError_t launch_bwd(const Plan &p, const BwdArgs &a, hipStream_t stream, const KernelEvents *ke);

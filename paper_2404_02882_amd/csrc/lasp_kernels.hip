@@ -177,6 +177,8 @@ struct Elem<float> {
     // every contraction element e of the fragment is multiplied by a * g[e].
     static constexpr int KH = 1;
     static DEVI frag scale_geo(frag f, float a, const float (&g)[8]) { return f * (a * g[0]); }
+    // multiply contraction element k of the fragment of step k0 by tab[k] (tab in LDS)
+    static DEVI frag scale_tab(const Lane &ln, frag f, const float *tab, int k0) { return f * tab[k0 + ln.h]; }
     // store 4 values of consecutive columns
     static DEVI void st4(float *p, float a, float b, float c, float d) { *(f32x4 *)p = f32x4{a, b, c, d}; }
     static DEVI void st1(float *p, float a) { *p = a; }
@@ -264,6 +266,17 @@ struct Elem<bf16_t> {
         for (int e = 0; e < 8; ++e) x[e] *= a * g[e];
         return __builtin_convertvector(x, bf16x8);
     }
+    static DEVI frag scale_tab(const Lane &ln, frag f, const float *tab, int k0) {
+        const f32x4 *t = (const f32x4 *)(tab + k0 + 8 * ln.h);  // 16-byte aligned: tab is, k0 % 16 == 0
+        const f32x4 lo = t[0], hi = t[1];
+        f32x8 x = __builtin_convertvector(f, f32x8);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            x[e] *= lo[e];
+            x[4 + e] *= hi[e];
+        }
+        return __builtin_convertvector(x, bf16x8);
+    }
     static DEVI void st4(bf16_t *p, float a, float b, float c, float d) {
         *(bf16x4 *)p = __builtin_convertvector(f32x4{a, b, c, d}, bf16x4);
     }
@@ -346,6 +359,112 @@ DEVI void fill_pow_table(float *pw, float lam) {
     for (int i = threadIdx.x; i <= CT; i += blockDim.x) pw[i] = (float)exp2((double)i * log2((double)lam));
 }
 
+// ---------------------------------------------------------------------------
+// Decay model of a tile of CT tokens (token indices 0-based inside the tile):
+//   upto(i)      weight the state entering the tile carries at token i   (Lambda of Alg. 2)
+//   after(j)     weight token j carries at the end of the tile           (lambda^C Lambda^-1)
+//   whole()      weight the entering state carries at the end of the tile (lambda^C)
+//   masked(x,i,j) x times the weight key j carries at query i, zero for j > i (mask M)
+// FixedDecay: one lambda per head (Alg. 2 / Alg. 3 as printed); every weight is a
+// power of lambda read from one table that serves all tiles.
+// TokenDecay: a decay g_s per token (general recurrent form of App. A.4 with a
+// scalar oscillation state); the weights are products of the g inside the tile,
+// held as cumulative base-2 logarithms and rebuilt for every tile by fill().
+// ---------------------------------------------------------------------------
+template <typename T, int CT>
+struct FixedDecay {
+    static constexpr bool kToken = false;
+    const float *pw;
+    GeoWeights<T> geo;
+    DEVI FixedDecay(float *tab, float lam) : pw(tab), geo(lam) { fill_pow_table<CT>(tab, lam); }
+    DEVI float upto(int i) const { return pw[i + 1]; }
+    DEVI float after(int j) const { return pw[CT - 1 - j]; }
+    DEVI float whole() const { return pw[CT]; }
+    DEVI float masked(float x, int i, int j) const {
+        const int d = i - j;
+        const float m = pw[d >= 0 ? d : 0];
+        return d >= 0 ? x * m : 0.0f;
+    }
+    DEVI typename Elem<T>::frag weigh_after(const Lane &ln, typename Elem<T>::frag f, int ks) const {
+        return lasp::weigh_after<T, CT>(ln, f, ks, pw, geo);
+    }
+    DEVI typename Elem<T>::frag weigh_upto(const Lane &ln, typename Elem<T>::frag f, int ks) const {
+        return lasp::weigh_upto<T, CT>(ln, f, ks, pw, geo);
+    }
+};
+
+constexpr float kLog2e = 1.44269504088896340736f;
+
+template <typename T, int CT>
+struct TokenDecay {
+    static constexpr bool kToken = true;
+    static_assert(CT <= 64, "one wave scans a tile");
+    float *cum, *wu, *wa;  // LDS: cumulative log2 decay up to and including token i; 2^cum[i]; 2^(cum[CT-1]-cum[j])
+    DEVI explicit TokenDecay(float *tab) : cum(tab), wu(tab + CT), wa(tab + 2 * CT) {}
+    // log2 g of token threadIdx.x of the tile starting at `lg` (threads >= CT: unused)
+    static DEVI float fetch(const float *lg) { return threadIdx.x < CT ? lg[threadIdx.x] * kLog2e : 0.0f; }
+    // Rebuilds the tables from the values fetch() returned. Every thread calls it between
+    // the barrier that retires the previous tile and the one that publishes the next.
+    DEVI void fill(float x) const {
+        if (threadIdx.x < 64) {
+            const int l = threadIdx.x;
+            float c = l < CT ? x : 0.0f;
+#pragma unroll
+            for (int d = 1; d < 64; d <<= 1) {
+                const float y = __shfl_up(c, d, 64);
+                if (l >= d) c += y;
+            }
+            const float total = __shfl(c, CT - 1, 64);
+            if (l < CT) {
+                cum[l] = c;
+                wu[l] = exp2f(c);
+                wa[l] = exp2f(total - c);
+            }
+        }
+    }
+    DEVI float upto(int i) const { return wu[i]; }
+    DEVI float after(int j) const { return wa[j]; }
+    DEVI float whole() const { return wu[CT - 1]; }
+    DEVI float masked(float x, int i, int j) const { return i >= j ? x * exp2f(cum[i] - cum[j]) : 0.0f; }
+    DEVI typename Elem<T>::frag weigh_after(const Lane &ln, typename Elem<T>::frag f, int ks) const {
+        return Elem<T>::scale_tab(ln, f, wa, ks * Elem<T>::KSTEP);
+    }
+    DEVI typename Elem<T>::frag weigh_upto(const Lane &ln, typename Elem<T>::frag f, int ks) const {
+        return Elem<T>::scale_tab(ln, f, wu, ks * Elem<T>::KSTEP);
+    }
+};
+template <bool TOKEN, typename T, int CT>
+struct DecaySel {
+    typedef FixedDecay<T, CT> type;
+    // `decay` is lambda per head
+    static DEVI type make(float *tab, const float *decay, int chain, int H) { return type(tab, decay[chain % H]); }
+};
+template <typename T, int CT>
+struct DecaySel<true, T, CT> {
+    typedef TokenDecay<T, CT> type;
+    static DEVI type make(float *tab, const float *, int, int) { return type(tab); }
+};
+
+// floats of LDS behind the tiles of every kernel: decay tables, and one row of
+// per-token partial sums per wave (backward walk with per-token decay)
+template <int CT>
+constexpr int table_floats() { return 3 * CT + 4 + 8 * CT; }
+
+// Sum over this wave's 32 features of accT[feature][token] * X[token][feature] for the
+// lane's token (accT: a transposed output tile in accumulator layout, X: the LDS tile
+// with token rows starting at row0). Both half-waves end up with the full sum.
+template <typename T>
+DEVI float rowdot(const Lane &ln, const f32x16 &acc, const T *sX, int ld, int row0, int w) {
+    float s = 0.0f;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const T *p = sX + lds_off(ld, row0 + ln.r, 32 * w + 8 * q + 4 * ln.h);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) s += acc[4 * q + e] * Elem<T>::ld1(p + e);
+    }
+    return s + __shfl_xor(s, 32, 64);
+}
+
 // Load / store a wave's column block of a [D][D] float state (row-major [a][c])
 // into accumulator layout: st[ab][i] = S[32 ab + ln.acc_row(i)][32 w + ln.r].
 template <int D>
@@ -370,19 +489,15 @@ DEVI void state_store(const Lane &ln, const f32x16 (&st)[D / 32], float *g, int 
 // column = query i), multiplies by lambda^(i-j) for i >= j (zero above the
 // diagonal) and writes it as P[i][j] so that four consecutive keys land in one
 // store.
-template <typename T, int LDP>
-DEVI void store_masked_scores(const Lane &ln, T *sP, const f32x16 &acc, int jb, int ib, const float *pw) {
+template <typename T, int LDP, typename DK>
+DEVI void store_masked_scores(const Lane &ln, T *sP, const f32x16 &acc, int jb, int ib, const DK &dec) {
     const int iq = 32 * ib + ln.r;
 #pragma unroll
     for (int g = 0; g < 4; ++g) {
         const int j0 = 32 * jb + 8 * g + 4 * ln.h;
         float x[4];
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            const int d = iq - (j0 + e);
-            const float m = pw[d >= 0 ? d : 0];
-            x[e] = d >= 0 ? acc[4 * g + e] * m : 0.0f;
-        }
+        for (int e = 0; e < 4; ++e) x[e] = dec.masked(acc[4 * g + e], iq, j0 + e);
         Elem<T>::st4(sP + iq * LDP + j0, x[0], x[1], x[2], x[3]);
     }
 }
@@ -390,8 +505,8 @@ DEVI void store_masked_scores(const Lane &ln, T *sP, const f32x16 &acc, int jb, 
 // ST[jb][ib] = A[jb] B[ib]^T over the feature dimension (both operands have the
 // contraction index contiguous), for every lower-triangular block assigned to
 // this wave; result masked and stored to sP.
-template <typename T, int CT, int D, int LDD, int LDP>
-DEVI void masked_scores(const Lane &ln, T *sP, const T *sA, const T *sB, const float *pw, int w) {
+template <typename T, int CT, int D, int LDD, int LDP, typename DK>
+DEVI void masked_scores(const Lane &ln, T *sP, const T *sA, const T *sB, const DK &dec, int w) {
     using E = Elem<T>;
     constexpr int NB = CT / 32, NW = D / 32;
     int idx = 0;
@@ -404,7 +519,7 @@ DEVI void masked_scores(const Lane &ln, T *sP, const T *sA, const T *sB, const f
 #pragma unroll
             for (int k0 = 0; k0 < D; k0 += E::KSTEP)
                 acc = E::mfma(E::ld_kc(ln, sA, LDD, 32 * jb, k0), E::ld_kc(ln, sB, LDD, 32 * ib, k0), acc);
-            store_masked_scores<T, LDP>(ln, sP, acc, jb, ib, pw);
+            store_masked_scores<T, LDP>(ln, sP, acc, jb, ib, dec);
         }
 }
 
@@ -475,10 +590,11 @@ DEVI void cache_store(const Lane &ln, T *g, const f32x16 (&st)[D / 32], T *idle_
 //   backward: S <- lambda^CT S + (diag{lambda^1..lambda^CT} X)^T Y, tiles descending
 // The row weight is applied to the Y fragments (shared by all row blocks).
 // ---------------------------------------------------------------------------
-template <typename T, int CT, int D, bool BWD>
+template <typename T, int CT, int D, bool BWD, bool TOKEN>
 __global__ __launch_bounds__(D * 2) void k_local(const T *__restrict__ X, const T *__restrict__ Y,
                                                   const float *__restrict__ decay, float *__restrict__ scratch,
-                                                  int H, int ntiles, int nseg, int tiles_per_seg) {
+                                                  float *__restrict__ seglog, int H, int ntiles, int nseg,
+                                                  int tiles_per_seg) {
     using E = Elem<T>;
     constexpr int NT = D * 2, LDD = tile_ld<T, D>(), DB = D / 32, NKS = CT / E::KSTEP;
     extern __shared__ __attribute__((aligned(16))) char smem[];
@@ -501,12 +617,60 @@ __global__ __launch_bounds__(D * 2) void k_local(const T *__restrict__ X, const 
     mx.load(X + base + (size_t)tile_of(0) * CT * D);
     my.load(Y + base + (size_t)tile_of(0) * CT * D);
     PHASE(22);
-    const float lam = decay[chain % H];
-    fill_pow_table<CT>(pw, lam);
-    const GeoWeights<T> geo(lam);
     f32x16 st[DB];
 #pragma unroll
     for (int ab = 0; ab < DB; ++ab) st[ab] = f32x16{0};
+
+    if constexpr (TOKEN) {
+        // `decay` is log g, [chain][token]. Per tile (state update of Alg. 2 / dKV update of Alg. 3
+        // with the tile's own weights): S <- whole S + (after (.) X)^T Y forward, (upto (.) X)^T Y backward.
+        const TokenDecay<T, CT> dec(pw);
+        const float *lg = decay + (size_t)chain * ntiles * CT;
+        float lgreg = TokenDecay<T, CT>::fetch(lg + (size_t)tile_of(0) * CT), lgsum = 0.0f;
+        for (int n = 0; n < ntl; ++n) {
+            __syncthreads();
+            ln = fresh_lane();
+            mx.store(sX, LDD);
+            my.store(sY, LDD);
+            dec.fill(lgreg);
+            lgsum += lgreg;
+            __syncthreads();
+            if (n + 1 < ntl) {
+                mx.load(X + base + (size_t)tile_of(n + 1) * CT * D);
+                my.load(Y + base + (size_t)tile_of(n + 1) * CT * D);
+                lgreg = TokenDecay<T, CT>::fetch(lg + (size_t)tile_of(n + 1) * CT);
+            }
+            const float whole = dec.whole();
+#pragma unroll
+            for (int ab = 0; ab < DB; ++ab) st[ab] *= whole;
+            struct Step {
+                typename E::frag y;
+                typename E::frag x[DB];
+            };
+            pipelined<NKS>(
+                [&](int ks) {
+                    Step f;
+                    f.y = E::ld_ks(ln, sY, LDD, ks * E::KSTEP, 32 * w);
+#pragma unroll
+                    for (int ab = 0; ab < DB; ++ab) f.x[ab] = E::ld_ks(ln, sX, LDD, ks * E::KSTEP, 32 * ab);
+                    return f;
+                },
+                [&](int ks, const Step &f) {
+                    const typename E::frag yd = BWD ? dec.weigh_upto(ln, f.y, ks) : dec.weigh_after(ln, f.y, ks);
+#pragma unroll
+                    for (int ab = 0; ab < DB; ++ab) st[ab] = E::mfma(f.x[ab], yd, st[ab]);
+                });
+        }
+        // log2 of the product of g over the segment, for the scan
+        if (threadIdx.x < 64) {
+#pragma unroll
+            for (int d = 32; d >= 1; d >>= 1) lgsum += __shfl_xor(lgsum, d, 64);
+            if (threadIdx.x == 0) seglog[(size_t)chain * nseg + seg] = lgsum;
+        }
+    } else {
+    const float lam = decay[chain % H];
+    fill_pow_table<CT>(pw, lam);
+    const GeoWeights<T> geo(lam);
     const float l2f = (float)log2((double)lam);
     PHASE(23);
     for (int n = 0; n < ntl; ++n) {
@@ -567,6 +731,7 @@ __global__ __launch_bounds__(D * 2) void k_local(const T *__restrict__ X, const 
         }
         PHASE(28);
     }
+    }
     PHASE(29);
     state_store<D>(ln, st, scratch + ((size_t)chain * nseg + seg) * D * D, w);
     PHASE(30);
@@ -579,33 +744,40 @@ __global__ __launch_bounds__(D * 2) void k_local(const T *__restrict__ X, const 
 //   backward: recv_{S-1} = dkv_out (or 0); recv_{j-1} = lambda^(len_j) recv_j + local_j
 // scratch[chain][j] holds local_j on entry and start_j / recv_j on exit.
 // ---------------------------------------------------------------------------
-template <bool BWD>
+// With per-token decay the factor of segment j is 2^seglog[chain][j] (written by k_local).
+template <bool BWD, bool TOKEN>
 __global__ __launch_bounds__(256) void k_scan(float *__restrict__ scratch, const float *__restrict__ boundary,
-                                              const float *__restrict__ decay, int H, int DD, int nseg,
-                                              int tiles_per_seg, int ntiles, int tile) {
+                                              const float *__restrict__ decay, const float *__restrict__ seglog,
+                                              int H, int DD, int nseg, int tiles_per_seg, int ntiles, int tile) {
     const int chain = blockIdx.y;
     const int e = (blockIdx.x * blockDim.x + threadIdx.x) * 4;  // four consecutive state elements per thread
     if (e >= DD) return;
-    const double l2 = log2((double)decay[chain % H]);
-    const float p_full = (float)exp2((double)(tiles_per_seg * tile) * l2);
-    const float p_last = (float)exp2((double)((ntiles - (nseg - 1) * tiles_per_seg) * tile) * l2);
+    float p_full = 0.0f, p_last = 0.0f;
+    if constexpr (!TOKEN) {
+        const double l2 = log2((double)decay[chain % H]);
+        p_full = (float)exp2((double)(tiles_per_seg * tile) * l2);
+        p_last = (float)exp2((double)((ntiles - (nseg - 1) * tiles_per_seg) * tile) * l2);
+    }
     f32x4 carry = boundary ? *(const f32x4 *)(boundary + (size_t)chain * DD + e) : f32x4{0, 0, 0, 0};
     float *s = scratch + (size_t)chain * nseg * DD + e;
     constexpr int U = 8;  // segments whose local states are fetched together (independent loads)
     for (int n0 = 0; n0 < nseg; n0 += U) {
         f32x4 local[U];
+        float factor[U];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int n = n0 + u, j = BWD ? nseg - 1 - n : n;
             const bool has_local = n < nseg && (BWD ? (j > 0) : (j < nseg - 1));
             local[u] = has_local ? *(const f32x4 *)(s + (size_t)j * DD) : f32x4{0, 0, 0, 0};
+            if constexpr (TOKEN) factor[u] = has_local ? exp2f(seglog[(size_t)chain * nseg + j]) : 0.0f;
+            else factor[u] = j == nseg - 1 ? p_last : p_full;
         }
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int n = n0 + u, j = BWD ? nseg - 1 - n : n;
             if (n < nseg) {
                 *(f32x4 *)(s + (size_t)j * DD) = carry;
-                carry = (j == nseg - 1 ? p_last : p_full) * carry + local[u];
+                carry = factor[u] * carry + local[u];
             }
         }
     }
@@ -618,7 +790,7 @@ __global__ __launch_bounds__(256) void k_scan(float *__restrict__ scratch, const
 //   KV_t   = lambda^CT KV_{t-1} + (lambda^CT Lambda^-1 K)^T V
 // The state KV_{t-1} each tile starts from is optionally written to the cache.
 // ---------------------------------------------------------------------------
-template <typename T, int CT, int D>
+template <typename T, int CT, int D, bool TOKEN>
 __global__ __launch_bounds__(D * 2, (CT <= 64 && sizeof(T) == 2) ? 2 : 1) void k_fwd(const T *__restrict__ Q, const T *__restrict__ K,
                                                 const T *__restrict__ V, const float *__restrict__ decay,
                                                 T *__restrict__ O, float *__restrict__ kv_out,
@@ -647,9 +819,10 @@ __global__ __launch_bounds__(D * 2, (CT <= 64 && sizeof(T) == 2) ? 2 : 1) void k
     mv.load(V + base + (size_t)t0 * CT * D);
     f32x16 st[DB];
     state_load<D>(ln, st, scratch + ((size_t)chain * nseg + seg) * D * D, w);
-    const float lam = decay[chain % H];
-    fill_pow_table<CT>(pw, lam);
-    const GeoWeights<T> geo(lam);
+    const auto dec = DecaySel<TOKEN, T, CT>::make(pw, decay, chain, H);
+    const float *lg = decay + (size_t)chain * ntiles * CT;  // per-token decay: `decay` is log g, [chain][token]
+    float lgreg = 0.0f;
+    if constexpr (TOKEN) lgreg = TokenDecay<T, CT>::fetch(lg + (size_t)t0 * CT);
 
     for (int t = t0; t < t1; ++t) {
         __syncthreads();
@@ -660,14 +833,16 @@ __global__ __launch_bounds__(D * 2, (CT <= 64 && sizeof(T) == 2) ? 2 : 1) void k
         mq.store(sQ, LDD);
         mk.store(sK, LDD);
         mv.store(sV, LDD);
+        if constexpr (TOKEN) dec.fill(lgreg);
         __syncthreads();
         if (t + 1 < t1) {
             mq.load(Q + base + (size_t)(t + 1) * CT * D);
             mk.load(K + base + (size_t)(t + 1) * CT * D);
             mv.load(V + base + (size_t)(t + 1) * CT * D);
+            if constexpr (TOKEN) lgreg = TokenDecay<T, CT>::fetch(lg + (size_t)(t + 1) * CT);
         }
         // masked scores P (all waves share the lower-triangular blocks)
-        masked_scores<T, CT, D, LDD, LDP>(ln, sP, sK, sQ, pw, w);
+        masked_scores<T, CT, D, LDD, LDP>(ln, sP, sK, sQ, dec, w);
 
         __syncthreads();  // P visible
         ln = fresh_lane();
@@ -688,7 +863,7 @@ __global__ __launch_bounds__(D * 2, (CT <= 64 && sizeof(T) == 2) ? 2 : 1) void k
             }
         // Lambda: token r (1-based) carries lambda^r; the token is this lane's column
 #pragma unroll
-        for (int ib = 0; ib < NB; ++ib) acc[ib] *= pw[32 * ib + ln.r + 1];
+        for (int ib = 0; ib < NB; ++ib) acc[ib] *= dec.upto(32 * ib + ln.r);
         // intra: OT[c][i] += sum_{j<=i} V[j][c] P[i][j]
 #pragma unroll
         for (int ks = 0; ks < NKS; ++ks) {
@@ -703,12 +878,12 @@ __global__ __launch_bounds__(D * 2, (CT <= 64 && sizeof(T) == 2) ? 2 : 1) void k
 
         ln = fresh_lane();
         // state update: KV <- lambda^CT KV + (diag{lambda^(CT-1-j)} K)^T V, weight applied to the V fragments
-        const float lamC = pw[CT];
+        const float lamC = dec.whole();
 #pragma unroll
         for (int ab = 0; ab < DB; ++ab) st[ab] *= lamC;
 #pragma unroll
         for (int ks = 0; ks < NKS; ++ks) {
-            const typename E::frag vd = weigh_after<T, CT>(ln, E::ld_ks(ln, sV, LDD, ks * E::KSTEP, 32 * w), ks, pw, geo);
+            const typename E::frag vd = dec.weigh_after(ln, E::ld_ks(ln, sV, LDD, ks * E::KSTEP, 32 * w), ks);
 #pragma unroll
             for (int ab = 0; ab < DB; ++ab) st[ab] = E::mfma(E::ld_ks(ln, sK, LDD, ks * E::KSTEP, 32 * ab), vd, st[ab]);
             SCHED_FENCE();
@@ -738,15 +913,16 @@ struct BwdSmem {
     static constexpr bool OVERLAY = X_BYTES <= IN_BYTES;                    // exchange reuses the input tiles
     static constexpr size_t P_OFF = IN_BYTES + (OVERLAY ? 0 : X_BYTES);
     static constexpr size_t PW_OFF = P_OFF + 2 * (size_t)CT * LDP * sizeof(T);
-    static constexpr size_t TOTAL = PW_OFF + (CT + 1) * sizeof(float);
+    static constexpr size_t TOTAL = PW_OFF + table_floats<CT>() * sizeof(float);
 };
 
-template <typename T, int CT, int D>
+template <typename T, int CT, int D, bool TOKEN>
 __global__ __launch_bounds__(D * 2, (CT <= 64 && sizeof(T) == 2) ? 2 : 1) void k_bwd(const T *__restrict__ Q, const T *__restrict__ K,
                                                 const T *__restrict__ V, const T *__restrict__ dO,
                                                 const float *__restrict__ decay, const T *__restrict__ cache,
                                                 T *__restrict__ dQ, T *__restrict__ dK, T *__restrict__ dV,
                                                 float *__restrict__ dkv_in, const float *__restrict__ scratch,
+                                                float *__restrict__ rtok,
                                                 int H, int ntiles, int nseg, int tiles_per_seg) {
     using E = Elem<T>;
     using SM = BwdSmem<T, CT, D>;
@@ -765,9 +941,20 @@ __global__ __launch_bounds__(D * 2, (CT <= 64 && sizeof(T) == 2) ? 2 : 1) void k
     const int t1 = min(t0 + tiles_per_seg, ntiles);
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);  // wave index, scalar
     Lane ln = fresh_lane();
-    const float lam = decay[chain % H];
-    fill_pow_table<CT>(pw, lam);
-    const GeoWeights<T> geo(lam);
+    const auto dec = DecaySel<TOKEN, T, CT>::make(pw, decay, chain, H);
+    const float *lg = decay + (size_t)chain * ntiles * CT;  // per-token decay: `decay` is log g, [chain][token]
+    float lgreg = 0.0f;
+    if constexpr (TOKEN) lgreg = TokenDecay<T, CT>::fetch(lg + (size_t)(t1 - 1) * CT);
+    // per-token decay: r_t = q_t.dq_t - k_t.dk_t, one partial row per wave, summed and written per tile
+    float *rs = pw + 3 * CT + 4;
+    auto flush_r = [&](int tile) {
+        if (threadIdx.x < CT) {
+            float r = 0.0f;
+#pragma unroll
+            for (int wv = 0; wv < D / 32; ++wv) r += rs[wv * CT + threadIdx.x];
+            rtok[((size_t)chain * ntiles + tile) * CT + threadIdx.x] = r;
+        }
+    };
 
     const size_t base = (size_t)chain * ntiles * CT * D;
     f32x16 dkv[DB];
@@ -782,6 +969,9 @@ __global__ __launch_bounds__(D * 2, (CT <= 64 && sizeof(T) == 2) ? 2 : 1) void k
         // ---- exchange: dKV^T fragments for dK_inter (B[k = c][n = a in w]) ----
         __syncthreads();
         ln = fresh_lane();
+        if constexpr (TOKEN) {
+            if (t < t1 - 1) flush_r(t + 1);
+        }
 #pragma unroll
         for (int ab = 0; ab < DB; ++ab)
 #pragma unroll
@@ -797,11 +987,15 @@ __global__ __launch_bounds__(D * 2, (CT <= 64 && sizeof(T) == 2) ? 2 : 1) void k
         // ---- step 1: V (bufA), dO (bufB) ----
         ma.store(bufA, LDD);
         mb.store(bufB, LDD);
+        if constexpr (TOKEN) dec.fill(lgreg);
         __syncthreads();
         ma.load(K + off);
         mb.load(Q + off);
+        if constexpr (TOKEN) {
+            if (t > t0) lgreg = TokenDecay<T, CT>::fetch(lg + (size_t)(t - 1) * CT);
+        }
 
-        masked_scores<T, CT, D, LDD, LDP>(ln, sDS, bufA, bufB, pw, w);  // dS^T = V dO^T
+        masked_scores<T, CT, D, LDD, LDP>(ln, sDS, bufA, bufB, dec, w);  // dS^T = V dO^T
 
         // All output tiles are accumulated transposed (feature x token), this wave's feature block.
         f32x16 accQ[NB], accK[NB];
@@ -817,7 +1011,7 @@ __global__ __launch_bounds__(D * 2, (CT <= 64 && sizeof(T) == 2) ? 2 : 1) void k
                 for (int ib = 0; ib < NB; ++ib) accQ[ib] = E::mfma(kvf, E::ld_kc(ln, bufB, LDD, 32 * ib, ks * E::KSTEP), accQ[ib]);
             }
 #pragma unroll
-            for (int ib = 0; ib < NB; ++ib) accQ[ib] *= pw[32 * ib + ln.r + 1];
+            for (int ib = 0; ib < NB; ++ib) accQ[ib] *= dec.upto(32 * ib + ln.r);
         }
         // dK_inter^T[a][j] = lambda^(CT-j) sum_c dKV[a][c] V[j][c]
 #pragma unroll
@@ -825,7 +1019,7 @@ __global__ __launch_bounds__(D * 2, (CT <= 64 && sizeof(T) == 2) ? 2 : 1) void k
 #pragma unroll
             for (int jb = 0; jb < NB; ++jb) accK[jb] = E::mfma(xf[ks], E::ld_kc(ln, bufA, LDD, 32 * jb, ks * E::KSTEP), accK[jb]);
 #pragma unroll
-        for (int jb = 0; jb < NB; ++jb) accK[jb] *= pw[CT - 1 - (32 * jb + ln.r)];
+        for (int jb = 0; jb < NB; ++jb) accK[jb] *= dec.after(32 * jb + ln.r);
         // dO fragments of this wave's column block: [k = i][n = c in w]
         typename E::frag dof[NKS];
 #pragma unroll
@@ -841,7 +1035,7 @@ __global__ __launch_bounds__(D * 2, (CT <= 64 && sizeof(T) == 2) ? 2 : 1) void k
             ma.load(V + off - (size_t)CT * D);
             mb.load(dO + off - (size_t)CT * D);
         }
-        masked_scores<T, CT, D, LDD, LDP>(ln, sS, bufA, bufB, pw, w);  // S^T = K Q^T
+        masked_scores<T, CT, D, LDD, LDP>(ln, sS, bufA, bufB, dec, w);  // S^T = K Q^T
         __syncthreads();
 
         // dQ^T[a][i] += sum_{j<=i} K[j][a] dSm[i][j]
@@ -853,6 +1047,11 @@ __global__ __launch_bounds__(D * 2, (CT <= 64 && sizeof(T) == 2) ? 2 : 1) void k
         }
 #pragma unroll
         for (int ib = 0; ib < NB; ++ib) store_out_tile_t<T, D>(ln, dQ + off, accQ[ib], 32 * ib, w);
+        float rpart[NB];
+        if constexpr (TOKEN) {
+#pragma unroll
+            for (int ib = 0; ib < NB; ++ib) rpart[ib] = rowdot<T>(ln, accQ[ib], bufB, LDD, 32 * ib, w);
+        }
         // dK^T[a][j] += sum_{i>=j} Q[i][a] dSm[i][j]
 #pragma unroll
         for (int ks = 0; ks < NKS; ++ks) {
@@ -862,6 +1061,13 @@ __global__ __launch_bounds__(D * 2, (CT <= 64 && sizeof(T) == 2) ? 2 : 1) void k
         }
 #pragma unroll
         for (int jb = 0; jb < NB; ++jb) store_out_tile_t<T, D>(ln, dK + off, accK[jb], 32 * jb, w);
+        if constexpr (TOKEN) {
+#pragma unroll
+            for (int jb = 0; jb < NB; ++jb) {
+                rpart[jb] -= rowdot<T>(ln, accK[jb], bufA, LDD, 32 * jb, w);
+                if (ln.h == 0) rs[w * CT + 32 * jb + ln.r] = rpart[jb];
+            }
+        }
         // dV^T[c][j] = lambda^(CT-j) sum_a dKV[a][c] K[j][a] + sum_{i>=j} dO[i][c] Sm[i][j]
         {
             f32x16 accV[NB];
@@ -876,7 +1082,7 @@ __global__ __launch_bounds__(D * 2, (CT <= 64 && sizeof(T) == 2) ? 2 : 1) void k
                     for (int jb = 0; jb < NB; ++jb) accV[jb] = E::mfma(df, E::ld_kp(ln, bufA, LDD, 32 * jb, 32 * ab, m), accV[jb]);
                 }
 #pragma unroll
-            for (int jb = 0; jb < NB; ++jb) accV[jb] *= pw[CT - 1 - (32 * jb + ln.r)];
+            for (int jb = 0; jb < NB; ++jb) accV[jb] *= dec.after(32 * jb + ln.r);
 #pragma unroll
             for (int ks = 0; ks < NKS; ++ks)
 #pragma unroll
@@ -886,15 +1092,19 @@ __global__ __launch_bounds__(D * 2, (CT <= 64 && sizeof(T) == 2) ? 2 : 1) void k
             for (int jb = 0; jb < NB; ++jb) store_out_tile_t<T, D>(ln, dV + off, accV[jb], 32 * jb, w);
         }
         // dKV <- lambda^CT dKV + (Lambda Q)^T dO  (row weight lambda^(i+1) applied to the dO fragments)
-        const float lamC = pw[CT];
+        const float lamC = dec.whole();
 #pragma unroll
         for (int ab = 0; ab < DB; ++ab) dkv[ab] *= lamC;
 #pragma unroll
         for (int ks = 0; ks < NKS; ++ks) {
-            const typename E::frag dos = weigh_upto<T, CT>(ln, dof[ks], ks, pw, geo);
+            const typename E::frag dos = dec.weigh_upto(ln, dof[ks], ks);
 #pragma unroll
             for (int ab = 0; ab < DB; ++ab) dkv[ab] = E::mfma(E::ld_ks(ln, bufB, LDD, ks * E::KSTEP, 32 * ab), dos, dkv[ab]);
         }
+    }
+    if constexpr (TOKEN) {
+        __syncthreads();
+        flush_r(t0);
     }
     if (seg == 0) state_store<D>(ln, dkv, dkv_in + (size_t)chain * D * D, w);
 }
@@ -920,15 +1130,16 @@ struct Bwd8Smem {
     static constexpr size_t P_OFF = 4 * TILE;
     static constexpr size_t C_OFF = P_OFF + 2 * (size_t)CT * LDP * sizeof(T);   // cached KV_{t-1} tile
     static constexpr size_t PW_OFF = C_OFF + (size_t)D * LDD * sizeof(T);
-    static constexpr size_t TOTAL = PW_OFF + (CT + 1) * sizeof(float);
+    static constexpr size_t TOTAL = PW_OFF + table_floats<CT>() * sizeof(float);
 };
 
-template <typename T, int CT, int D>
+template <typename T, int CT, int D, bool TOKEN>
 __global__ __launch_bounds__(D * 4) void k_bwd8(const T *__restrict__ Q, const T *__restrict__ K,
                                                  const T *__restrict__ V, const T *__restrict__ dO,
                                                  const float *__restrict__ decay, const T *__restrict__ cache,
                                                  T *__restrict__ dQ, T *__restrict__ dK, T *__restrict__ dV,
                                                  float *__restrict__ dkv_in, const float *__restrict__ scratch,
+                                                 float *__restrict__ rtok,
                                                  int H, int ntiles, int nseg, int tiles_per_seg) {
     using E = Elem<T>;
     using F = typename E::frag;
@@ -968,9 +1179,20 @@ __global__ __launch_bounds__(D * 4) void k_bwd8(const T *__restrict__ Q, const T
         mq.load(Q + off);
         mc.load(ctile + (size_t)(t1 - 1) * D * D);
     }
-    const float lam = decay[chain % H];
-    fill_pow_table<CT>(pw, lam);
-    const GeoWeights<T> geo(lam);
+    const auto dec = DecaySel<TOKEN, T, CT>::make(pw, decay, chain, H);
+    const float *lg = decay + (size_t)chain * ntiles * CT;  // per-token decay: `decay` is log g, [chain][token]
+    float lgreg = 0.0f;
+    if constexpr (TOKEN) lgreg = TokenDecay<T, CT>::fetch(lg + (size_t)(t1 - 1) * CT);
+    // per-token decay: r_t = q_t.dq_t - k_t.dk_t, one partial row per wave, summed and written per tile
+    float *rs = pw + 3 * CT + 4;
+    auto flush_r = [&](int tile) {
+        if (threadIdx.x < CT) {
+            float r = 0.0f;
+#pragma unroll
+            for (int wv = 0; wv < 2 * NW; ++wv) r += rs[wv * CT + threadIdx.x];
+            rtok[((size_t)chain * ntiles + tile) * CT + threadIdx.x] = r;
+        }
+    };
 
     // Group-dependent operands (wave-uniform selects).
     const T *sX1 = rg ? sV : sK;     // inter operand: token rows, features contracted with the state
@@ -1003,6 +1225,10 @@ __global__ __launch_bounds__(D * 4) void k_bwd8(const T *__restrict__ Q, const T
         __syncthreads();  // previous tile fully consumed
         ln = fresh_lane();
         PHASE(0);
+        if constexpr (TOKEN) {
+            if (t < t1 - 1) flush_r(t + 1);
+            dec.fill(lgreg);
+        }
         mv.store(sV, LDD);
         mo.store(sdO, LDD);
         mk.store(sK, LDD);
@@ -1017,6 +1243,7 @@ __global__ __launch_bounds__(D * 4) void k_bwd8(const T *__restrict__ Q, const T
             mk.load(K + off - (size_t)CT * D);
             mq.load(Q + off - (size_t)CT * D);
             mc.load(ctile + (size_t)(t - 1) * D * D);
+            if constexpr (TOKEN) lgreg = TokenDecay<T, CT>::fetch(lg + (size_t)(t - 1) * CT);
         }
         // masked score tiles: dS^T = V dO^T (tiles 0..2) and S^T = K Q^T (tiles 3..5), one per wave
         {
@@ -1041,13 +1268,14 @@ __global__ __launch_bounds__(D * 4) void k_bwd8(const T *__restrict__ Q, const T
                         acc2 = E::mfma(f.b.a, f.b.b, acc2);
                     });
                 acc += acc2;
-                store_masked_scores<T, LDP>(ln, idx < NTRI ? sDS : sS, acc, jb, ib, pw);
+                store_masked_scores<T, LDP>(ln, idx < NTRI ? sDS : sS, acc, jb, ib, dec);
             }
         }
         __syncthreads();
         ln = fresh_lane();
         PHASE(2);
 
+        float rq = 0.0f;  // per-token decay: q_i . dq_i over this wave's features, tokens i of block rg
         // ---- dQ^T[a in w][i], tokens i of block rg:
         //      lambda^i sum_c KV_{t-1}[a][c] dO[i][c] + sum_{j<=i} K[j][a] dSm[i][j] ----
         {
@@ -1056,12 +1284,13 @@ __global__ __launch_bounds__(D * 4) void k_bwd8(const T *__restrict__ Q, const T
             pipelined<NKD>(
                 [&](int ks) { return FragPair<F>{E::ld_kc(ln, sC, LDD, 32 * w, ks * E::KSTEP), E::ld_kc(ln, sdO, LDD, r0, ks * E::KSTEP)}; },
                 [&](int, const FragPair<F> &f) { acc = E::mfma(f.a, f.b, acc); });
-            acc *= pw[r0 + ln.r + 1];
+            acc *= dec.upto(r0 + ln.r);
             auto intra = [&](int ks) { return FragPair<F>{E::ld_ks(ln, sK, LDD, ks * E::KSTEP, 32 * w), E::ld_kc(ln, sDS, LDP, r0, ks * E::KSTEP)}; };
             auto fma = [&](int, const FragPair<F> &f) { acc = E::mfma(f.a, f.b, acc); };
             if (rg == 0) pipelined<SPB>(intra, fma);        // keys of block 0
             else pipelined<2 * SPB>(intra, fma);            // keys of blocks 0 and 1
             store_out_tile_t<T, D>(ln, dQ + off, acc, r0, w);
+            if constexpr (TOKEN) rq = rowdot<T>(ln, acc, sQ, LDD, r0, w);
         }
         PHASE(3);
         ln = fresh_lane();
@@ -1085,7 +1314,7 @@ __global__ __launch_bounds__(D * 4) void k_bwd8(const T *__restrict__ Q, const T
                     for (int jb = 0; jb < NB; ++jb) acc[jb] = E::mfma(sf, f.b[jb], acc[jb]);
                 });
 #pragma unroll
-            for (int jb = 0; jb < NB; ++jb) acc[jb] *= pw[CT - 1 - (32 * jb + ln.r)];
+            for (int jb = 0; jb < NB; ++jb) acc[jb] *= dec.after(32 * jb + ln.r);
             struct Three { F a; F b[NB]; };
             pipelined<NKS>(
                 [&](int ks) {
@@ -1103,12 +1332,20 @@ __global__ __launch_bounds__(D * 4) void k_bwd8(const T *__restrict__ Q, const T
                 });
 #pragma unroll
             for (int jb = 0; jb < NB; ++jb) store_out_tile_t<T, D>(ln, gOut + off, acc[jb], 32 * jb, w);
+            if constexpr (TOKEN) {
+#pragma unroll
+                for (int jb = 0; jb < NB; ++jb) {
+                    float r = jb == rg ? rq : 0.0f;
+                    if (rg == 1) r -= rowdot<T>(ln, acc[jb], sK, LDD, 32 * jb, w);  // group 1 holds dK
+                    if (ln.h == 0) rs[w8 * CT + 32 * jb + ln.r] = r;
+                }
+            }
         }
         PHASE(4);
         ln = fresh_lane();
         // ---- state update in this group's orientation (group 0: dKV <- lambda^CT dKV + (Lambda Q)^T dO) ----
         {
-            const float lamC = pw[CT];
+            const float lamC = dec.whole();
 #pragma unroll
             for (int blk = 0; blk < DB; ++blk) st[blk] *= lamC;
             struct Step {
@@ -1124,12 +1361,16 @@ __global__ __launch_bounds__(D * 4) void k_bwd8(const T *__restrict__ Q, const T
                     return f;
                 },
                 [&](int ks, const Step &f) {
-                    const F bs = weigh_upto<T, CT>(ln, f.b, ks, pw, geo);
+                    const F bs = dec.weigh_upto(ln, f.b, ks);
 #pragma unroll
                     for (int blk = 0; blk < DB; ++blk) st[blk] = E::mfma(f.a[blk], bs, st[blk]);
                 });
         }
         PHASE(5);
+    }
+    if constexpr (TOKEN) {
+        __syncthreads();
+        flush_r(t0);
     }
     if (seg == 0 && rg == 0) state_store<D>(ln, st, dkv_in + (size_t)chain * D * D, w);
     PHASE_FLUSH();
@@ -1206,9 +1447,8 @@ __global__ __launch_bounds__(D * 4) void k_bwd8p(const T *__restrict__ Q, const 
         mc.load(ctile + (size_t)(tE / 2) * D * D);
     };
     load_pair(t1 - 2);
-    const float lam = decay[chain % H];
-    fill_pow_table<CT>(pw, lam);
-    const GeoWeights<T> geo(lam);
+    const FixedDecay<T, CT> dec(pw, decay[chain % H]);
+    const GeoWeights<T> &geo = dec.geo;
 
     const T *sX2 = rg ? sQ : sdO;    // intra operand and state-update B operand: [token][feature in w]
     const T *sUA = rg ? sdO : sQ;    // state-update A operand: [token][feature of the state rows]
@@ -1257,7 +1497,7 @@ __global__ __launch_bounds__(D * 4) void k_bwd8p(const T *__restrict__ Q, const 
                     acc2 = E::mfma(f.b.a, f.b.b, acc2);
                 });
             acc += acc2;
-            store_masked_scores<T, LDP>(ln, idx < NTRI ? sDS : sS, acc, jb, ib, pw);
+            store_masked_scores<T, LDP>(ln, idx < NTRI ? sDS : sS, acc, jb, ib, dec);
         }
     };
 
@@ -1414,13 +1654,55 @@ __global__ __launch_bounds__(D * 4) void k_bwd8p(const T *__restrict__ Q, const 
 }
 
 // ---------------------------------------------------------------------------
+// k_dlg: gradient of the per-token log decay from r_t = q_t.dq_t - k_t.dk_t
+// (written per tile by the backward walk):
+//     dlog g_s = <dkv_out, kv_out> + sum_{t >= s} r_t.
+// It follows from expanding <D_s, kv_s> with either recurrence, kv_s = g_s kv_{s-1}
+// + k_s v_s^T or D_s = q_s do_s^T + g_{s+1} D_{s+1} (D_s: gradient w.r.t. kv_s):
+// dlog g_s + k_s.dk_s = q_s.dq_s + dlog g_{s+1}. One workgroup per head; thread i
+// owns a contiguous run of tokens; sums are carried in double.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_dlg(const float *__restrict__ rtok, const float *__restrict__ kv_out,
+                                             const float *__restrict__ dkv_out, float *__restrict__ dlg, int N, int DD) {
+    __shared__ double part[256];
+    const int chain = blockIdx.x, tid = threadIdx.x;
+    double tail = 0.0;
+    if (dkv_out) {
+        const float *a = kv_out + (size_t)chain * DD, *b = dkv_out + (size_t)chain * DD;
+        for (int e = tid; e < DD; e += 256) tail += (double)a[e] * (double)b[e];
+    }
+    part[tid] = tail;
+    __syncthreads();
+    for (int d = 128; d >= 1; d >>= 1) {
+        if (tid < d) part[tid] += part[tid + d];
+        __syncthreads();
+    }
+    const double boundary = part[0];
+    __syncthreads();
+    const int L = (N + 255) / 256;
+    const int lo = min(tid * L, N), hi = min(lo + L, N);
+    const float *r = rtok + (size_t)chain * N;
+    double own = 0.0;
+    for (int s = lo; s < hi; ++s) own += (double)r[s];
+    part[tid] = own;
+    __syncthreads();
+    double after = boundary;
+    for (int j = tid + 1; j < 256; ++j) after += part[j];
+    float *o = dlg + (size_t)chain * N;
+    for (int s = hi - 1; s >= lo; --s) {
+        after += (double)r[s];
+        o[s] = (float)after;
+    }
+}
+
+// ---------------------------------------------------------------------------
 // Host-side launchers
 // ---------------------------------------------------------------------------
 template <typename T, int CT, int D>
 struct Smem {
     using E = Elem<T>;
-    static constexpr size_t local = 2 * (size_t)CT * tile_ld<T, D>() * sizeof(T) + (CT + 1) * sizeof(float);
-    static constexpr size_t fwd = (3 * (size_t)CT * tile_ld<T, D>() + (size_t)CT * (CT + E::PAD)) * sizeof(T) + (CT + 1) * sizeof(float);
+    static constexpr size_t local = 2 * (size_t)CT * tile_ld<T, D>() * sizeof(T) + table_floats<CT>() * sizeof(float);
+    static constexpr size_t fwd = (3 * (size_t)CT * tile_ld<T, D>() + (size_t)CT * (CT + E::PAD)) * sizeof(T) + table_floats<CT>() * sizeof(float);
     static constexpr size_t bwd = BwdSmem<T, CT, D>::TOTAL;
     static_assert(fwd <= 163840 && bwd <= 163840, "LDS budget of one gfx950 CU exceeded");
 };
@@ -1441,46 +1723,66 @@ static hipError_t allow_lds(F kernel, size_t bytes) {
 
 // The local pass only sums over its segment, so its tile need not be the walk's:
 // bfloat16 segments made of an even number of 64-token tiles are read 128 tokens
-// at a time (half the barriers, twice the bytes in flight per workgroup).
+// at a time (half the barriers, twice the bytes in flight per workgroup). With
+// per-token decay (`decay` = log g) the walk's tile is used.
 template <typename T, int CT, int D, bool BWD>
-static hipError_t run_local(const Plan &p, const T *x, const T *y, const float *decay, float *scratch, hipStream_t s) {
+static hipError_t run_local(const Plan &p, const T *x, const T *y, const float *decay, float *scratch, float *seglog,
+                            hipStream_t s) {
     const int chains = p.B * p.H;
     hipError_t e;
+    if (p.token) {
+        constexpr size_t lds = Smem<T, CT, D>::local;
+        auto kl = k_local<T, CT, D, BWD, true>;
+        if ((e = allow_lds(kl, lds)) != hipSuccess) return e;
+        kl<<<dim3(p.nseg - 1, chains), dim3(D * 2), lds, s>>>(x, y, decay, scratch, seglog, p.H, p.ntiles, p.nseg,
+                                                            p.tiles_per_seg);
+        return hipSuccess;
+    }
     if constexpr (sizeof(T) == 2 && CT == 64) {
         if (p.tiles_per_seg % 2 == 0 && p.ntiles % 2 == 0) {
             constexpr size_t lds = Smem<T, 128, D>::local;
-            auto kl = k_local<T, 128, D, BWD>;
+            auto kl = k_local<T, 128, D, BWD, false>;
             if ((e = allow_lds(kl, lds)) != hipSuccess) return e;
-            kl<<<dim3(p.nseg - 1, chains), dim3(D * 2), lds, s>>>(x, y, decay, scratch, p.H, p.ntiles / 2, p.nseg,
+            kl<<<dim3(p.nseg - 1, chains), dim3(D * 2), lds, s>>>(x, y, decay, scratch, nullptr, p.H, p.ntiles / 2, p.nseg,
                                                                 p.tiles_per_seg / 2);
             return hipSuccess;
         }
     }
     constexpr size_t lds = Smem<T, CT, D>::local;
-    auto kl = k_local<T, CT, D, BWD>;
+    auto kl = k_local<T, CT, D, BWD, false>;
     if ((e = allow_lds(kl, lds)) != hipSuccess) return e;
-    kl<<<dim3(p.nseg - 1, chains), dim3(D * 2), lds, s>>>(x, y, decay, scratch, p.H, p.ntiles, p.nseg, p.tiles_per_seg);
+    kl<<<dim3(p.nseg - 1, chains), dim3(D * 2), lds, s>>>(x, y, decay, scratch, nullptr, p.H, p.ntiles, p.nseg,
+                                                        p.tiles_per_seg);
     return hipSuccess;
 }
 
 template <typename T, int CT, int D>
 static hipError_t run_fwd(const Plan &p, const FwdArgs &a, hipStream_t s, const KernelEvents *ke) {
     const int chains = p.B * p.H, DD = D * D;
-    constexpr size_t lds_local = Smem<T, CT, D>::local, lds_fwd = Smem<T, CT, D>::fwd;
+    constexpr size_t lds_fwd = Smem<T, CT, D>::fwd;
+    const dim3 scan_grid((DD / 4 + 255) / 256, chains);
     hipError_t e;
     if (ke) (void)hipEventRecord(ke->ev[0], s);
     if (p.nseg > 1) {
-        if (e = run_local<T, CT, D, false>(p, (const T *)a.k, (const T *)a.v, a.decay, a.scratch, s); e != hipSuccess) return e;
+        if (e = run_local<T, CT, D, false>(p, (const T *)a.k, (const T *)a.v, a.decay, a.scratch, a.seglog, s); e != hipSuccess)
+            return e;
     }
     if (ke) (void)hipEventRecord(ke->ev[1], s);
-    k_scan<false><<<dim3((DD / 4 + 255) / 256, chains), dim3(256), 0, s>>>(a.scratch, a.kv_in, a.decay, p.H, DD, p.nseg,
-                                                                       p.tiles_per_seg, p.ntiles, p.tile);
+    if (p.token)
+        k_scan<false, true><<<scan_grid, dim3(256), 0, s>>>(a.scratch, a.kv_in, nullptr, a.seglog, p.H, DD, p.nseg,
+                                                           p.tiles_per_seg, p.ntiles, p.tile);
+    else
+        k_scan<false, false><<<scan_grid, dim3(256), 0, s>>>(a.scratch, a.kv_in, a.decay, nullptr, p.H, DD, p.nseg,
+                                                            p.tiles_per_seg, p.ntiles, p.tile);
     if (ke) (void)hipEventRecord(ke->ev[2], s);
-    auto kf = k_fwd<T, CT, D>;
-    if ((e = allow_lds(kf, lds_fwd)) != hipSuccess) return e;
-    kf<<<dim3(p.nseg, chains), dim3(D * 2), lds_fwd, s>>>((const T *)a.q, (const T *)a.k, (const T *)a.v, a.decay,
-                                                         (T *)a.out, a.kv_out, (T *)a.cache, (const float *)a.scratch,
-                                                         p.H, p.ntiles, p.nseg, p.tiles_per_seg, p.cache_stride);
+    auto launch = [&](auto kf) -> hipError_t {
+        if (hipError_t e2 = allow_lds(kf, lds_fwd); e2 != hipSuccess) return e2;
+        kf<<<dim3(p.nseg, chains), dim3(D * 2), lds_fwd, s>>>((const T *)a.q, (const T *)a.k, (const T *)a.v, a.decay,
+                                                             (T *)a.out, a.kv_out, (T *)a.cache, (const float *)a.scratch,
+                                                             p.H, p.ntiles, p.nseg, p.tiles_per_seg, p.cache_stride);
+        return hipSuccess;
+    };
+    if (e = p.token ? launch(k_fwd<T, CT, D, true>) : launch(k_fwd<T, CT, D, false>); e != hipSuccess) return e;
     if (ke) (void)hipEventRecord(ke->ev[3], s);
     return hipGetLastError();
 }
@@ -1488,15 +1790,21 @@ static hipError_t run_fwd(const Plan &p, const FwdArgs &a, hipStream_t s, const 
 template <typename T, int CT, int D>
 static hipError_t run_bwd(const Plan &p, const BwdArgs &a, hipStream_t s, const KernelEvents *ke) {
     const int chains = p.B * p.H, DD = D * D;
-    constexpr size_t lds_local = Smem<T, CT, D>::local, lds_bwd = Smem<T, CT, D>::bwd;
+    constexpr size_t lds_bwd = Smem<T, CT, D>::bwd;
+    const dim3 scan_grid((DD / 4 + 255) / 256, chains);
     hipError_t e;
     if (ke) (void)hipEventRecord(ke->ev[0], s);
     if (p.nseg > 1) {
-        if (e = run_local<T, CT, D, true>(p, (const T *)a.q, (const T *)a.dout, a.decay, a.scratch, s); e != hipSuccess) return e;
+        if (e = run_local<T, CT, D, true>(p, (const T *)a.q, (const T *)a.dout, a.decay, a.scratch, a.seglog, s); e != hipSuccess)
+            return e;
     }
     if (ke) (void)hipEventRecord(ke->ev[1], s);
-    k_scan<true><<<dim3((DD / 4 + 255) / 256, chains), dim3(256), 0, s>>>(a.scratch, a.dkv_out, a.decay, p.H, DD, p.nseg,
-                                                                      p.tiles_per_seg, p.ntiles, p.tile);
+    if (p.token)
+        k_scan<true, true><<<scan_grid, dim3(256), 0, s>>>(a.scratch, a.dkv_out, nullptr, a.seglog, p.H, DD, p.nseg,
+                                                          p.tiles_per_seg, p.ntiles, p.tile);
+    else
+        k_scan<true, false><<<scan_grid, dim3(256), 0, s>>>(a.scratch, a.dkv_out, a.decay, nullptr, p.H, DD, p.nseg,
+                                                           p.tiles_per_seg, p.ntiles, p.tile);
     if (ke) (void)hipEventRecord(ke->ev[2], s);
     if constexpr (sizeof(T) == 2 && CT == 64) {
       if (p.cache_stride == 2) {
@@ -1511,22 +1819,30 @@ static hipError_t run_bwd(const Plan &p, const BwdArgs &a, hipStream_t s, const 
       } else {
         constexpr size_t lds_bwd8 = Bwd8Smem<T, CT, D>::TOTAL;
         static_assert(lds_bwd8 <= 163840, "LDS budget of one gfx950 CU exceeded");
-        auto kb = k_bwd8<T, CT, D>;
-        if ((e = allow_lds(kb, lds_bwd8)) != hipSuccess) return e;
-        kb<<<dim3(p.nseg, chains), dim3(D * 4), lds_bwd8, s>>>((const T *)a.q, (const T *)a.k, (const T *)a.v,
-                                                               (const T *)a.dout, a.decay, (const T *)a.cache, (T *)a.dq,
-                                                               (T *)a.dk, (T *)a.dv, a.dkv_in, (const float *)a.scratch,
-                                                               p.H, p.ntiles, p.nseg, p.tiles_per_seg);
+        auto launch = [&](auto kb) -> hipError_t {
+            if (hipError_t e2 = allow_lds(kb, lds_bwd8); e2 != hipSuccess) return e2;
+            kb<<<dim3(p.nseg, chains), dim3(D * 4), lds_bwd8, s>>>((const T *)a.q, (const T *)a.k, (const T *)a.v,
+                                                                   (const T *)a.dout, a.decay, (const T *)a.cache, (T *)a.dq,
+                                                                   (T *)a.dk, (T *)a.dv, a.dkv_in, (const float *)a.scratch,
+                                                                   a.rtok, p.H, p.ntiles, p.nseg, p.tiles_per_seg);
+            return hipSuccess;
+        };
+        if (e = p.token ? launch(k_bwd8<T, CT, D, true>) : launch(k_bwd8<T, CT, D, false>); e != hipSuccess) return e;
       }
     } else {
-        auto kb = k_bwd<T, CT, D>;
-        if ((e = allow_lds(kb, lds_bwd)) != hipSuccess) return e;
-        kb<<<dim3(p.nseg, chains), dim3(D * 2), lds_bwd, s>>>((const T *)a.q, (const T *)a.k, (const T *)a.v,
-                                                             (const T *)a.dout, a.decay, (const T *)a.cache, (T *)a.dq,
-                                                             (T *)a.dk, (T *)a.dv, a.dkv_in, (const float *)a.scratch, p.H,
-                                                             p.ntiles, p.nseg, p.tiles_per_seg);
+        auto launch = [&](auto kb) -> hipError_t {
+            if (hipError_t e2 = allow_lds(kb, lds_bwd); e2 != hipSuccess) return e2;
+            kb<<<dim3(p.nseg, chains), dim3(D * 2), lds_bwd, s>>>((const T *)a.q, (const T *)a.k, (const T *)a.v,
+                                                                 (const T *)a.dout, a.decay, (const T *)a.cache, (T *)a.dq,
+                                                                 (T *)a.dk, (T *)a.dv, a.dkv_in, (const float *)a.scratch,
+                                                                 a.rtok, p.H, p.ntiles, p.nseg, p.tiles_per_seg);
+            return hipSuccess;
+        };
+        if (e = p.token ? launch(k_bwd<T, CT, D, true>) : launch(k_bwd<T, CT, D, false>); e != hipSuccess) return e;
     }
     if (ke) (void)hipEventRecord(ke->ev[3], s);
+    if (p.token)
+        k_dlg<<<dim3(chains), dim3(256), 0, s>>>(a.rtok, a.kv_out, a.dkv_out, a.dlog_g, p.N, DD);
     return hipGetLastError();
 }
 
@@ -1541,8 +1857,8 @@ extern "C" int lasp_debug_phases(unsigned long long *out32, int reset) {
 }
 #endif
 
-int cache_stride_for(int dtype, int tile, int ntiles) {
-    return (dtype == 1 && tile == 64 && ntiles % 2 == 0) ? 2 : 1;
+int cache_stride_for(int dtype, int tile, int ntiles, bool token) {
+    return (!token && dtype == 1 && tile == 64 && ntiles % 2 == 0) ? 2 : 1;
 }
 
 // Tokens per kernel tile: 32 for float data, 64 for bfloat16 data, whatever the

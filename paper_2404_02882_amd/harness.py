@@ -47,10 +47,15 @@ def run_gpu(inp: Inputs, T: int = 1, segments: int = 0, backward: bool = True, c
     cfg = inp.cfg
     B, H, N, D = inp.q.shape
     dt = TORCH_DTYPE[cfg.dtype]
+    token = inp.log_g is not None
     seq = LaspSequence(B, H, N, D, chunk or cfg.chunk, dt, T=T, segments=segments, device=device,
-                       need_backward=backward)
+                       need_backward=backward, token_decay=token)
     q, k, v = (shards(x, T, cfg.dtype, device) for x in (inp.q, inp.k, inp.v))
-    decay = torch.from_numpy(inp.decay).to(device)
+    if token:
+        n = N // T
+        decay = [torch.from_numpy(np.ascontiguousarray(inp.log_g[:, :, t * n:(t + 1) * n])).to(device) for t in range(T)]
+    else:
+        decay = torch.from_numpy(inp.decay).to(device)
     kv_in = torch.from_numpy(inp.kv_in).to(device) if inp.kv_in is not None else None
     out = [torch.full_like(x, float("nan")) for x in q]
     kv_out = seq.forward(q, k, v, decay, out, kv_in)
@@ -59,7 +64,10 @@ def run_gpu(inp: Inputs, T: int = 1, segments: int = 0, backward: bool = True, c
         do = shards(inp.dout, T, cfg.dtype, device)
         g = torch.from_numpy(inp.dkv_out).to(device) if inp.dkv_out is not None else None
         dq, dk, dv = ([torch.full_like(x, float("nan")) for x in q] for _ in range(3))
-        dkv_in = seq.backward(q, k, v, do, decay, dq, dk, dv, g)
+        dlg = [torch.full_like(x, float("nan")) for x in decay] if token else None
+        dkv_in = seq.backward(q, k, v, do, decay, dq, dk, dv, g, dlog_g=dlg)
         res.update(dq=to_host(dq), dk=to_host(dk), dv=to_host(dv), dkv_in=dkv_in.cpu().numpy().astype(np.float64))
+        if token:
+            res["dlog_g"] = to_host(dlg)
     torch.cuda.synchronize()
     return res

@@ -58,6 +58,15 @@ def _bind(handle):
     handle.lasp_fwd.restype = ctypes.c_int
     handle.lasp_bwd.argtypes = [_sp] + [_vp] * 12 + [_sz, _vp]
     handle.lasp_bwd.restype = ctypes.c_int
+    handle.lasp_check_log_decay.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_int64]
+    handle.lasp_gated_state_cache_bytes.argtypes = [_sp]
+    handle.lasp_gated_state_cache_bytes.restype = _sz
+    handle.lasp_gated_scratch_bytes.argtypes = [_sp]
+    handle.lasp_gated_scratch_bytes.restype = _sz
+    handle.lasp_gated_fwd.argtypes = [_sp] + [_vp] * 9 + [_sz, _vp]
+    handle.lasp_gated_fwd.restype = ctypes.c_int
+    handle.lasp_gated_bwd.argtypes = [_sp] + [_vp] * 14 + [_sz, _vp]
+    handle.lasp_gated_bwd.restype = ctypes.c_int
     handle.lasp_profile_begin.argtypes = [ctypes.c_int32]
     handle.lasp_profile_end.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int32),
                                         ctypes.POINTER(ctypes.c_int32)]
@@ -156,6 +165,40 @@ def lasp_bwd(shape: Shape, q, k, v, dout, dkv_out, decay, state_cache, dq, dk, d
                       _stream(stream))
     if rc != 0:
         raise LaspError(rc, "lasp_bwd")
+
+
+def check_log_decay(log_g_host) -> int:
+    import numpy as np
+    a = np.ascontiguousarray(log_g_host, dtype=np.float32).ravel()
+    return int(lib.lasp_check_log_decay(a.ctypes.data_as(ctypes.POINTER(ctypes.c_float)), a.size))
+
+
+def gated_state_cache_bytes(shape: Shape) -> int:
+    return int(lib.lasp_gated_state_cache_bytes(ctypes.byref(shape)))
+
+
+def gated_scratch_bytes(shape: Shape) -> int:
+    return int(lib.lasp_gated_scratch_bytes(ctypes.byref(shape)))
+
+
+def lasp_gated_fwd(shape: Shape, q, k, v, log_g, kv_in, out, kv_out, state_cache, scratch, stream=None) -> None:
+    """Forward with a decay per token (log_g: float32 [B,H,N]); raises LaspError on a non-zero status."""
+    nbytes = scratch.numel() * scratch.element_size() if scratch is not None else 0
+    rc = lib.lasp_gated_fwd(ctypes.byref(shape), _ptr(q), _ptr(k), _ptr(v), _ptr(log_g), _ptr(kv_in), _ptr(out),
+                            _ptr(kv_out), _ptr(state_cache), _ptr(scratch), nbytes, _stream(stream))
+    if rc != 0:
+        raise LaspError(rc, "lasp_gated_fwd")
+
+
+def lasp_gated_bwd(shape: Shape, q, k, v, dout, log_g, kv_out, dkv_out, state_cache, dq, dk, dv, dlog_g, dkv_in,
+                   scratch, stream=None) -> None:
+    """Backward with a decay per token; raises LaspError on a non-zero status."""
+    nbytes = scratch.numel() * scratch.element_size() if scratch is not None else 0
+    rc = lib.lasp_gated_bwd(ctypes.byref(shape), _ptr(q), _ptr(k), _ptr(v), _ptr(dout), _ptr(log_g), _ptr(kv_out),
+                            _ptr(dkv_out), _ptr(state_cache), _ptr(dq), _ptr(dk), _ptr(dv), _ptr(dlog_g),
+                            _ptr(dkv_in), _ptr(scratch), nbytes, _stream(stream))
+    if rc != 0:
+        raise LaspError(rc, "lasp_gated_bwd")
 
 
 class Workspace:

@@ -18,7 +18,8 @@ from . import lasp
 
 
 class LaspSequence:
-    def __init__(self, B, H, N, D, chunk, dtype: torch.dtype, T=1, segments=0, device="cuda", need_backward=True):
+    def __init__(self, B, H, N, D, chunk, dtype: torch.dtype, T=1, segments=0, device="cuda", need_backward=True,
+                 token_decay=False):
         if N % T != 0:
             raise ValueError("N must be a multiple of T")
         self.B, self.H, self.N, self.D, self.T = B, H, N, D, T
@@ -28,8 +29,13 @@ class LaspSequence:
         rc = lasp.check_shape(self.shape)
         if rc != 0:
             raise lasp.LaspError(rc, "LaspSequence")
-        self.scratch = torch.empty(lasp.scratch_bytes(self.shape), dtype=torch.uint8, device=device)
-        self.caches = [torch.empty(lasp.state_cache_bytes(self.shape), dtype=torch.uint8, device=device)
+        # token_decay: `decay` of forward / backward is a list of T log-decay shards [B,H,N/T] (float32)
+        # instead of the [H] vector of lambdas, and backward also fills dlog_g shards.
+        self.token_decay = token_decay
+        scratch_bytes = lasp.gated_scratch_bytes if token_decay else lasp.scratch_bytes
+        cache_bytes = lasp.gated_state_cache_bytes if token_decay else lasp.state_cache_bytes
+        self.scratch = torch.empty(scratch_bytes(self.shape), dtype=torch.uint8, device=device)
+        self.caches = [torch.empty(cache_bytes(self.shape), dtype=torch.uint8, device=device)
                        for _ in range(T)] if need_backward else [None] * T
         st = dict(dtype=torch.float32, device=device)
         # kv[t] = state entering shard t (kv[T] = final); dkv[t] = gradient w.r.t. kv[t]
@@ -48,16 +54,25 @@ class LaspSequence:
             self.kv[0].copy_(kv_in)
         for t in range(self.T):
             first = None if (t == 0 and not self.has_kv_in) else self.kv[t]
-            lasp.lasp_fwd(self.shape, q[t], k[t], v[t], first, decay, out[t], self.kv[t + 1], self.caches[t],
-                          self.scratch)
+            if self.token_decay:
+                lasp.lasp_gated_fwd(self.shape, q[t], k[t], v[t], decay[t], first, out[t], self.kv[t + 1],
+                                    self.caches[t], self.scratch)
+            else:
+                lasp.lasp_fwd(self.shape, q[t], k[t], v[t], first, decay, out[t], self.kv[t + 1], self.caches[t],
+                              self.scratch)
         return self.kv[self.T]
 
-    def backward(self, q, k, v, dout, decay, dq, dk, dv, dkv_out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    def backward(self, q, k, v, dout, decay, dq, dk, dv, dkv_out: Optional[torch.Tensor] = None,
+                 dlog_g: Optional[List[torch.Tensor]] = None) -> torch.Tensor:
         self.has_dkv_out = dkv_out is not None
         if dkv_out is not None:
             self.dkv[self.T].copy_(dkv_out)
         for t in reversed(range(self.T)):
             last = None if (t == self.T - 1 and not self.has_dkv_out) else self.dkv[t + 1]
-            lasp.lasp_bwd(self.shape, q[t], k[t], v[t], dout[t], last, decay, self.caches[t], dq[t], dk[t], dv[t],
-                          self.dkv[t], self.scratch)
+            if self.token_decay:
+                lasp.lasp_gated_bwd(self.shape, q[t], k[t], v[t], dout[t], decay[t], self.kv[t + 1], last,
+                                    self.caches[t], dq[t], dk[t], dv[t], dlog_g[t], self.dkv[t], self.scratch)
+            else:
+                lasp.lasp_bwd(self.shape, q[t], k[t], v[t], dout[t], last, decay, self.caches[t], dq[t], dk[t], dv[t],
+                              self.dkv[t], self.scratch)
         return self.dkv[0]

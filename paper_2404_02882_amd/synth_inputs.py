@@ -33,6 +33,7 @@ class Config:
     fwd_only: bool = False
     k_outlier_frac: float = 0.0
     k_outlier_scale: float = 1.0
+    token_decay: bool = False   # a decay g_s per token (log_g) instead of one lambda per head
 
 
 # The five workloads (shapes, decay and value recipe as stated for the build).
@@ -43,6 +44,9 @@ CONFIGS = {
     "c4": Config("c4", B=1, H=16, N=262144, D=128, chunk=128, dtype="bf16", T=8, seed=1004),
     "c5": Config("c5", B=4, H=32, N=16384, D=128, chunk=256, dtype="bf16", seed=1005,
                  k_outlier_frac=0.01, k_outlier_scale=8.0),
+    # the same shapes as c2 / c3 with a decay per token
+    "g2": Config("g2", B=2, H=8, N=4096, D=64, chunk=64, dtype="bf16", T=4, seed=1012, token_decay=True),
+    "g3": Config("g3", B=1, H=16, N=32768, D=128, chunk=128, dtype="bf16", seed=1013, token_decay=True),
 }
 
 
@@ -83,6 +87,20 @@ class Inputs:
     decay: np.ndarray   # fp32 [H]
     kv_in: Optional[np.ndarray] = None     # fp32 [B,H,D,D] or None (zeros)
     dkv_out: Optional[np.ndarray] = None
+    log_g: Optional[np.ndarray] = None     # fp32 [B,H,N], natural log of the per-token decay (token_decay configs)
+
+
+def token_log_decay(cfg: Config, N: int, seed: int, reset_frac: float = 0.001) -> np.ndarray:
+    """log g for every head and token: log(lambda_h) * 2u, u ~ U(0,1), so that the mean decay of a head
+    is that of the fixed schedule and single tokens range from no decay to twice the head's rate; a
+    fraction `reset_frac` of the tokens gets log g = -8 (the gate almost closes, as data-dependent
+    gates do at boundaries in the input). Own random stream: q, k, v do not depend on it."""
+    rng = np.random.default_rng(seed + 7919)
+    lam = decay_schedule(cfg.H).astype(np.float64)
+    u = rng.random((cfg.B, cfg.H, N))
+    lg = np.log(lam)[None, :, None] * 2.0 * u
+    lg[rng.random((cfg.B, cfg.H, N)) < reset_frac] = -8.0
+    return lg.astype(np.float32)
 
 
 def make_inputs(cfg: Config, n_tokens: Optional[int] = None, with_states: bool = False,
@@ -107,8 +125,9 @@ def make_inputs(cfg: Config, n_tokens: Optional[int] = None, with_states: bool =
     if with_states:
         kv_in = rng.standard_normal((cfg.B, cfg.H, cfg.D, cfg.D), dtype=np.float32)
         dkv_out = rng.standard_normal((cfg.B, cfg.H, cfg.D, cfg.D), dtype=np.float32)
+    log_g = token_log_decay(cfg, N, cfg.seed if seed is None else seed) if cfg.token_decay else None
     return Inputs(cfg, quantize(q, cfg.dtype), quantize(k, cfg.dtype), quantize(v, cfg.dtype),
-                  quantize(dout, cfg.dtype), decay, kv_in, dkv_out)
+                  quantize(dout, cfg.dtype), decay, kv_in, dkv_out, log_g)
 
 
 def sample_rows(cfg: Config, N: int, n: int, seed: int) -> np.ndarray:

@@ -124,3 +124,64 @@ def test_bwd_rejects_before_launch(L):
     assert call(*a) == 6
     a = list(ok_args); a[11] = g
     assert call(*a) == 6
+
+
+# ---------------------------------------------------------------- per-token decay entry points
+def test_gated_sizes(L):
+    s = L.make_shape(1, 16, 32768, 128, 128, "bf16")
+    tile = L.tile_tokens(s)
+    per_tile = 16 * (32768 // tile) * 128 * 128 * 2
+    assert L.gated_state_cache_bytes(s) in (per_tile, per_tile // 2)
+    # segment states + one log-decay per segment + one float per token and head
+    assert L.gated_scratch_bytes(s) >= L.scratch_bytes(s) + 16 * 32768 * 4
+    bad = L.make_shape(1, 1, 100, 64, 64, "bf16")
+    assert L.gated_scratch_bytes(bad) == 0 and L.gated_state_cache_bytes(bad) == 0
+
+
+def test_check_log_decay(L):
+    assert L.check_log_decay([0.0, -0.5, -30.0]) == 0
+    assert L.check_log_decay([1e-3]) == 4
+    assert L.check_log_decay([float("nan")]) == 4
+    assert L.check_log_decay([float("-inf")]) == 4
+
+
+def test_gated_fwd_rejects_before_launch(L):
+    s = L.make_shape(1, 1, 64, 64, 64, "bf16")
+    sb = L.gated_scratch_bytes(s)
+    q, k, v, lg, kvin, out, kvout, cache, scr = [_fake(i) for i in range(1, 10)]
+    call = lambda *a: L.lib.lasp_gated_fwd(*a)
+    ok_args = [ctypes.byref(s), q, k, v, lg, kvin, out, kvout, cache, scr, sb, None]
+    for idx in (1, 2, 3, 4, 6, 7):
+        a = list(ok_args)
+        a[idx] = None
+        assert call(*a) == 1, idx
+    a = list(ok_args); a[9] = None
+    assert call(*a) == 5
+    a = list(ok_args); a[10] = L.scratch_bytes(s)    # the fixed-decay size is too small
+    assert call(*a) == 5
+    a = list(ok_args); a[6] = lg                     # out aliases log_g
+    assert call(*a) == 6
+    a = list(ok_args); a[0] = ctypes.byref(L.make_shape(1, 1, 65, 64, 64, "bf16"))
+    assert call(*a) == 2
+
+
+def test_gated_bwd_rejects_before_launch(L):
+    s = L.make_shape(1, 1, 64, 64, 64, "f32")
+    sb = L.gated_scratch_bytes(s)
+    q, k, v, do, lg, kvout, g, cache, dq, dk, dv, dlg, gin, scr = [_fake(i) for i in range(1, 15)]
+    call = lambda *a: L.lib.lasp_gated_bwd(*a)
+    ok_args = [ctypes.byref(s), q, k, v, do, lg, kvout, g, cache, dq, dk, dv, dlg, gin, scr, sb, None]
+    for idx in (1, 2, 3, 4, 5, 8, 9, 10, 11, 12, 13):   # every required pointer
+        a = list(ok_args)
+        a[idx] = None
+        assert call(*a) == 1, idx
+    a = list(ok_args); a[6] = None                   # dkv_out given but kv_out missing
+    assert call(*a) == 1
+    a = list(ok_args); a[14] = None
+    assert call(*a) == 5
+    a = list(ok_args); a[15] = sb - 1
+    assert call(*a) == 5
+    a = list(ok_args); a[12] = lg                    # dlog_g aliases log_g
+    assert call(*a) == 6
+    a = list(ok_args); a[13] = kvout                 # dkv_in aliases kv_out
+    assert call(*a) == 6
