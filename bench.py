@@ -33,7 +33,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--config", default="c3", help="named workload (c3 is the headline)")
+    ap.add_argument("--config", default="c3", help="named workload (c3 is the headline; g3 = c3 with a decay per token)")
     ap.add_argument("--segments", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-tokens", type=int, default=32768)
@@ -57,16 +57,23 @@ def main():
     inp = si.make_inputs(cfg)
     B, H, N, D, T = cfg.B, cfg.H, cfg.N, cfg.D, cfg.T
     dt = harness.TORCH_DTYPE[cfg.dtype]
-    seq = LaspSequence(B, H, N, D, cfg.chunk, dt, T=T, segments=args.segments, device=dev)
+    token = cfg.token_decay
+    seq = LaspSequence(B, H, N, D, cfg.chunk, dt, T=T, segments=args.segments, device=dev, token_decay=token)
     q, k, v, do = (harness.shards(x, T, cfg.dtype, dev) for x in (inp.q, inp.k, inp.v, inp.dout))
-    decay = torch.from_numpy(inp.decay).to(dev)
+    if token:   # a decay per token: log g shards [B,H,N/T] in, dlog_g shards out
+        n = N // T
+        decay = [torch.from_numpy(np.ascontiguousarray(inp.log_g[:, :, t * n:(t + 1) * n])).to(dev) for t in range(T)]
+        dlg = [torch.empty_like(x) for x in decay]
+    else:
+        decay = torch.from_numpy(inp.decay).to(dev)
+        dlg = None
     out, dq, dk, dv = ([torch.empty_like(x) for x in q] for _ in range(4))
     tile = lasp.tile_tokens(seq.shape)
     nseg = lasp.num_segments(seq.shape)
 
     def step():
         seq.forward(q, k, v, decay, out)
-        seq.backward(q, k, v, do, decay, dq, dk, dv)
+        seq.backward(q, k, v, do, decay, dq, dk, dv, dlog_g=dlg)
 
     for _ in range(args.warmup):
         step()
@@ -90,7 +97,11 @@ def main():
                      "bwd_scan": kernel_ms["bwd"][1] / nb, "bwd_walk": kernel_ms["bwd"][2] / nb}
     # algorithmic (compulsory) HBM bytes per token-head: forward walk reads q,k,v and
     # writes o; backward walk reads q,k,v,do and writes dq,dk,dv; local passes read two tensors.
-    alg_bytes = {"fwd_walk": 4 * D * esz, "bwd_walk": 7 * D * esz, "fwd_local": 2 * D * esz, "bwd_local": 2 * D * esz}
+    # With a decay per token every kernel also reads log g (4 B per token-head); dlog_g is written by a
+    # separate small kernel.
+    gb = 4 if token else 0
+    alg_bytes = {"fwd_walk": 4 * D * esz + gb, "bwd_walk": 7 * D * esz + gb, "fwd_local": 2 * D * esz + gb,
+                 "bwd_local": 2 * D * esz + gb}
     dominant = max(("fwd_walk", "bwd_walk", "fwd_local", "bwd_local"), key=lambda n: per_launch_ms[n])
     dom_bytes = alg_bytes[dominant] * tok_heads_per_launch
     achieved = dom_bytes / (per_launch_ms[dominant] * 1e-3) / 1e9
@@ -105,7 +116,7 @@ def main():
     # configured chunk length C (intra-chunk 14*C*d, inter-chunk and state updates 12*d*d), not issued
     # flops (the kernels run shorter tiles than C and rebuild half of the cached states)
     flops_step = (14 * cfg.chunk * D + 12 * D * D) * B * H * N
-    min_bytes_step = 11 * D * esz * B * H * N
+    min_bytes_step = (11 * D * esz + 3 * gb) * B * H * N
     step_s = ms_per_step * 1e-3
     extra = {"algorithmic_tflops": round(flops_step / step_s / 1e12, 2),
              "mfma_bf16_peak_frac": round(flops_step / step_s / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
@@ -141,20 +152,26 @@ def main():
         sl = slice(0, n_s)
         a = [np.ascontiguousarray(x[:, :, sl], dtype=np.float64) for x in (inp.q, inp.k, inp.v, inp.dout)]
         c0 = time.perf_counter()
-        lasp_oracle.fwd_chunked(a[0], a[1], a[2], inp.decay, cfg.chunk)
-        lasp_oracle.bwd_chunked(a[0], a[1], a[2], a[3], inp.decay, cfg.chunk)
+        if token:
+            lg = np.ascontiguousarray(inp.log_g[:, :, sl], dtype=np.float64)
+            lasp_oracle.gated_fwd_chunked(a[0], a[1], a[2], lg, cfg.chunk)
+            lasp_oracle.gated_bwd_chunked(a[0], a[1], a[2], a[3], lg, cfg.chunk)
+        else:
+            lasp_oracle.fwd_chunked(a[0], a[1], a[2], inp.decay, cfg.chunk)
+            lasp_oracle.bwd_chunked(a[0], a[1], a[2], a[3], inp.decay, cfg.chunk)
         c1 = time.perf_counter()
         cpu = {"value": round(B * n_s / (c1 - c0), 1), "unit": "tokens/s", "cores": lasp_oracle.num_threads(),
                "kind": "oracle",
                "sample": f"chunked fp64 oracle (Alg. 2 + Alg. 3), fwd+bwd, first {n_s} of {N} tokens of all "
                          f"{B * H} heads, {c1 - c0:.1f} s"}
 
-    line = {"metric": "fwd+bwd tokens/sec, chunked causal linear attention with decay (LASP per-device hot path)",
+    line = {"metric": "fwd+bwd tokens/sec, chunked causal linear attention with decay (LASP per-device hot path)"
+                      + (", decay per token" if token else ""),
             "value": round(tokens_per_s, 1), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
             "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
             "scaling": "weak", "vs_baseline": None, "dtype": cfg.dtype, "data": "synthetic",
             "config": {"workload": f"{cfg.name}: B={B} H={H} N={N} d={D} chunk={cfg.chunk} {cfg.dtype}, "
-                                   f"T={T} sub-sequence(s), fwd+bwd",
+                                   f"T={T} sub-sequence(s), fwd+bwd" + (", decay per token (log_g in, dlog_g out)" if token else ""),
                        "tile_tokens": tile, "segments_per_head": nseg,
                        "state_cache_bytes": seq.cache_bytes()},
             "roofline": roofline, "whole_step": extra, "copy_reference": copy, "cpu_baseline": cpu}

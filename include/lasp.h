@@ -23,6 +23,7 @@
  *     learnable, so no gradient is produced for it.
  *   - Every function returns a lasp_status; nothing throws or aborts. All
  *     argument checks run on the host before anything is launched.
+ *   - Every buffer is 16-byte aligned (the kernels move 16-byte pieces).
  *   - Outputs must not alias inputs or each other. Calls that share a scratch
  *     or state_cache buffer must be ordered on one stream.
  */
@@ -44,7 +45,8 @@ typedef enum {
     LASP_ERR_DECAY = 4,     /* lasp_check_decay: a value outside (0, 1] or not finite */
     LASP_ERR_WORKSPACE = 5, /* scratch missing or smaller than lasp_scratch_bytes() */
     LASP_ERR_ALIAS = 6,     /* an output buffer overlaps an input or another output */
-    LASP_ERR_HIP = 7        /* the HIP runtime refused a launch */
+    LASP_ERR_HIP = 7,       /* the HIP runtime refused a launch */
+    LASP_ERR_ALIGN = 8      /* a buffer is not 16-byte aligned */
 } lasp_status;
 
 typedef enum { LASP_F32 = 0, LASP_BF16 = 1 } lasp_dtype;

@@ -103,6 +103,16 @@ struct Span {
 };
 bool overlap(Span a, Span b) { return a.p && b.p && a.p < b.p + b.n && b.p < a.p + a.n; }
 
+// The kernels move data in 16-byte pieces. NULL (an absent optional buffer) passes.
+template <size_t NI, size_t NO>
+bool aligned16(const Span (&ins)[NI], const Span (&outs)[NO]) {
+    for (const Span &x : ins)
+        if ((uintptr_t)x.p % 16 != 0) return false;
+    for (const Span &x : outs)
+        if ((uintptr_t)x.p % 16 != 0) return false;
+    return true;
+}
+
 }  // namespace
 
 extern "C" {
@@ -119,6 +129,7 @@ const char *lasp_status_str(int status) {
         case LASP_ERR_WORKSPACE: return "scratch buffer missing or too small (see lasp_scratch_bytes)";
         case LASP_ERR_ALIAS: return "an output buffer overlaps an input or another output";
         case LASP_ERR_HIP: return "HIP runtime error at launch";
+        case LASP_ERR_ALIGN: return "a buffer is not 16-byte aligned";
         default: return "unknown status";
     }
 }
@@ -188,6 +199,7 @@ int lasp_fwd(const lasp_shape *shape, const void *q, const void *k, const void *
     const Span outs[] = {{(const char *)out, tb}, {(const char *)kv_out, sb},
                          {(const char *)state_cache, lasp_state_cache_bytes(shape)},
                          {(const char *)scratch, lasp_scratch_bytes(shape)}};
+    if (!aligned16(ins, outs)) return LASP_ERR_ALIGN;
     for (const Span &o : outs) {
         for (const Span &i : ins)
             if (overlap(o, i)) return LASP_ERR_ALIAS;
@@ -215,6 +227,7 @@ int lasp_bwd(const lasp_shape *shape, const void *q, const void *k, const void *
                         {(const char *)state_cache, lasp_state_cache_bytes(shape)}};
     const Span outs[] = {{(const char *)dq, tb}, {(const char *)dk, tb}, {(const char *)dv, tb},
                          {(const char *)dkv_in, sb}, {(const char *)scratch, lasp_scratch_bytes(shape)}};
+    if (!aligned16(ins, outs)) return LASP_ERR_ALIGN;
     for (const Span &o : outs) {
         for (const Span &i : ins)
             if (overlap(o, i)) return LASP_ERR_ALIAS;
@@ -244,6 +257,7 @@ int lasp_gated_fwd(const lasp_shape *shape, const void *q, const void *k, const 
                         {(const char *)kv_in, sb}, {(const char *)log_g, gb}};
     const Span outs[] = {{(const char *)out, tb}, {(const char *)kv_out, sb},
                          {(const char *)state_cache, cache_bytes(shape, true)}, {(const char *)scratch, l.total}};
+    if (!aligned16(ins, outs)) return LASP_ERR_ALIGN;
     for (const Span &o : outs) {
         for (const Span &i : ins)
             if (overlap(o, i)) return LASP_ERR_ALIAS;
@@ -276,6 +290,7 @@ int lasp_gated_bwd(const lasp_shape *shape, const void *q, const void *k, const 
                         {(const char *)log_g, gb}, {(const char *)state_cache, cache_bytes(shape, true)}};
     const Span outs[] = {{(const char *)dq, tb}, {(const char *)dk, tb}, {(const char *)dv, tb},
                          {(const char *)dlog_g, gb}, {(const char *)dkv_in, sb}, {(const char *)scratch, l.total}};
+    if (!aligned16(ins, outs)) return LASP_ERR_ALIGN;
     for (const Span &o : outs) {
         for (const Span &i : ins)
             if (overlap(o, i)) return LASP_ERR_ALIAS;

@@ -1659,40 +1659,60 @@ __global__ __launch_bounds__(D * 4) void k_bwd8p(const T *__restrict__ Q, const 
 //     dlog g_s = <dkv_out, kv_out> + sum_{t >= s} r_t.
 // It follows from expanding <D_s, kv_s> with either recurrence, kv_s = g_s kv_{s-1}
 // + k_s v_s^T or D_s = q_s do_s^T + g_{s+1} D_{s+1} (D_s: gradient w.r.t. kv_s):
-// dlog g_s + k_s.dk_s = q_s.dq_s + dlog g_{s+1}. One workgroup per head; thread i
-// owns a contiguous run of tokens; sums are carried in double.
+// dlog g_s + k_s.dk_s = q_s.dq_s + dlog g_{s+1}. One workgroup per block of
+// kDlgBlock tokens of a head: it sums everything behind its block (r of the later
+// tokens and the boundary term), then scans its own tokens from the right. Sums
+// are carried in double; the order of additions is fixed, so reruns are identical.
 // ---------------------------------------------------------------------------
+constexpr int kDlgBlock = 1024;  // tokens per workgroup: 256 threads x 4
+
+DEVI double block_sum(double x, double *sh) {  // sum over the 256 threads, returned to all
+    const int tid = threadIdx.x;
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) x += __shfl_xor(x, d, 64);
+    __syncthreads();
+    if ((tid & 63) == 0) sh[tid >> 6] = x;
+    __syncthreads();
+    return sh[0] + sh[1] + sh[2] + sh[3];
+}
+
 __global__ __launch_bounds__(256) void k_dlg(const float *__restrict__ rtok, const float *__restrict__ kv_out,
                                              const float *__restrict__ dkv_out, float *__restrict__ dlg, int N, int DD) {
-    __shared__ double part[256];
-    const int chain = blockIdx.x, tid = threadIdx.x;
-    double tail = 0.0;
-    if (dkv_out) {
-        const float *a = kv_out + (size_t)chain * DD, *b = dkv_out + (size_t)chain * DD;
-        for (int e = tid; e < DD; e += 256) tail += (double)a[e] * (double)b[e];
-    }
-    part[tid] = tail;
-    __syncthreads();
-    for (int d = 128; d >= 1; d >>= 1) {
-        if (tid < d) part[tid] += part[tid + d];
-        __syncthreads();
-    }
-    const double boundary = part[0];
-    __syncthreads();
-    const int L = (N + 255) / 256;
-    const int lo = min(tid * L, N), hi = min(lo + L, N);
+    __shared__ double sh[4];
+    const int chain = blockIdx.y, tid = threadIdx.x;
+    const int s0 = blockIdx.x * kDlgBlock;  // first token of this block
     const float *r = rtok + (size_t)chain * N;
-    double own = 0.0;
-    for (int s = lo; s < hi; ++s) own += (double)r[s];
-    part[tid] = own;
-    __syncthreads();
-    double after = boundary;
-    for (int j = tid + 1; j < 256; ++j) after += part[j];
-    float *o = dlg + (size_t)chain * N;
-    for (int s = hi - 1; s >= lo; --s) {
-        after += (double)r[s];
-        o[s] = (float)after;
+    double behind = 0.0;
+    if (dkv_out) {
+        const f32x4 *a = (const f32x4 *)(kv_out + (size_t)chain * DD), *b = (const f32x4 *)(dkv_out + (size_t)chain * DD);
+        for (int e = tid; e < DD / 4; e += 256) {
+            const f32x4 x = a[e], y = b[e];
+            behind += (double)x[0] * y[0] + (double)x[1] * y[1] + (double)x[2] * y[2] + (double)x[3] * y[3];
+        }
     }
+    for (int s = s0 + kDlgBlock + 4 * tid; s < N; s += kDlgBlock) {  // N % 4 == 0
+        const f32x4 x = *(const f32x4 *)(r + s);
+        behind += ((double)x[0] + x[1]) + ((double)x[2] + x[3]);
+    }
+    behind = block_sum(behind, sh);
+    // this thread's four tokens, suffix sums inside the group
+    const int s = s0 + 4 * tid;
+    f32x4 x = {0, 0, 0, 0};
+    if (s < N) x = *(const f32x4 *)(r + s);
+    double v3 = x[3], v2 = v3 + x[2], v1 = v2 + x[1], v0 = v1 + x[0];
+    // exclusive suffix sum of the group totals over the threads behind this one
+    double incl = v0;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const double y = __shfl_down(incl, d, 64);
+        if ((tid & 63) + d < 64) incl += y;
+    }
+    __syncthreads();
+    if ((tid & 63) == 0) sh[tid >> 6] = incl;  // total of this wave
+    __syncthreads();
+    double after = behind + (incl - v0);
+    for (int wv = (tid >> 6) + 1; wv < 4; ++wv) after += sh[wv];
+    if (s < N) *(f32x4 *)(dlg + (size_t)chain * N + s) = f32x4{(float)(after + v0), (float)(after + v1), (float)(after + v2), (float)(after + v3)};
 }
 
 // ---------------------------------------------------------------------------
@@ -1842,7 +1862,8 @@ static hipError_t run_bwd(const Plan &p, const BwdArgs &a, hipStream_t s, const 
     }
     if (ke) (void)hipEventRecord(ke->ev[3], s);
     if (p.token)
-        k_dlg<<<dim3(chains), dim3(256), 0, s>>>(a.rtok, a.kv_out, a.dkv_out, a.dlog_g, p.N, DD);
+        k_dlg<<<dim3((p.N + kDlgBlock - 1) / kDlgBlock, chains), dim3(256), 0, s>>>(a.rtok, a.kv_out, a.dkv_out, a.dlog_g,
+                                                                                      p.N, DD);
     return hipGetLastError();
 }
 

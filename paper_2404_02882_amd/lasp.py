@@ -17,7 +17,7 @@ LIB_PATH = os.path.join(_HERE, "liblasp.so")
 
 LASP_F32, LASP_BF16 = 0, 1
 STATUS_NAMES = {0: "LASP_OK", 1: "LASP_ERR_NULL", 2: "LASP_ERR_SHAPE", 3: "LASP_ERR_DTYPE", 4: "LASP_ERR_DECAY",
-                5: "LASP_ERR_WORKSPACE", 6: "LASP_ERR_ALIAS", 7: "LASP_ERR_HIP"}
+                5: "LASP_ERR_WORKSPACE", 6: "LASP_ERR_ALIAS", 7: "LASP_ERR_HIP", 8: "LASP_ERR_ALIGN"}
 
 
 class Shape(ctypes.Structure):

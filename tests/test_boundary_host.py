@@ -27,7 +27,7 @@ def test_exports_every_declared_symbol(L):
 
 
 def test_status_strings(L):
-    for s in range(8):
+    for s in range(9):
         assert L.status_str(s) and "unknown" not in L.status_str(s)
     assert "unknown" in L.status_str(99)
 
@@ -97,6 +97,9 @@ def test_fwd_rejects_before_launch(L):
     assert call(ctypes.byref(s), q, k, v, kvin, dec, q, kvout, cache, scr, sb, None) == 6      # out aliases q
     assert call(ctypes.byref(s), q, k, v, kvin, dec, out, kvin, cache, scr, sb, None) == 6     # kv_out aliases kv_in
     assert call(ctypes.byref(s), q, k, v, kvin, dec, out, kvout, out, scr, sb, None) == 6      # cache aliases out
+    odd = ctypes.c_void_p(q.value + 8)
+    assert call(ctypes.byref(s), odd, k, v, kvin, dec, out, kvout, cache, scr, sb, None) == 8   # q not 16-byte aligned
+    assert call(ctypes.byref(s), q, k, v, kvin, dec, out, kvout, cache, ctypes.c_void_p(scr.value + 4), sb, None) == 8
     bad = L.make_shape(1, 1, 65, 64, 64, "bf16")
     assert call(ctypes.byref(bad), q, k, v, kvin, dec, out, kvout, cache, scr, sb, None) == 2
     bad = L.make_shape(1, 1, 64, 64, 64, 7)
@@ -185,3 +188,5 @@ def test_gated_bwd_rejects_before_launch(L):
     assert call(*a) == 6
     a = list(ok_args); a[13] = kvout                 # dkv_in aliases kv_out
     assert call(*a) == 6
+    a = list(ok_args); a[12] = ctypes.c_void_p(dlg.value + 4)   # dlog_g not 16-byte aligned
+    assert call(*a) == 8
