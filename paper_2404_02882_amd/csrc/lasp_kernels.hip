@@ -398,27 +398,55 @@ constexpr float kLog2e = 1.44269504088896340736f;
 template <typename T, int CT>
 struct TokenDecay {
     static constexpr bool kToken = true;
-    static_assert(CT <= 64, "one wave scans a tile");
+    static constexpr int PER = (CT + 63) / 64;  // tokens per lane of the wave that scans the tile
+    static_assert(CT <= 128 && CT % PER == 0, "one wave scans a tile");
+    struct LogG {
+        float x[PER];
+        DEVI float sum() const {
+            float s = 0.0f;
+#pragma unroll
+            for (int e = 0; e < PER; ++e) s += x[e];
+            return s;
+        }
+    };
     float *cum, *wu, *wa;  // LDS: cumulative log2 decay up to and including token i; 2^cum[i]; 2^(cum[CT-1]-cum[j])
     DEVI explicit TokenDecay(float *tab) : cum(tab), wu(tab + CT), wa(tab + 2 * CT) {}
-    // log2 g of token threadIdx.x of the tile starting at `lg` (threads >= CT: unused)
-    static DEVI float fetch(const float *lg) { return threadIdx.x < CT ? lg[threadIdx.x] * kLog2e : 0.0f; }
+    // log2 g of the tokens PER*l .. PER*l+PER-1 of the tile starting at `lg`, in lane l of wave 0 (zero elsewhere)
+    static DEVI LogG fetch(const float *lg) {
+        LogG v;
+#pragma unroll
+        for (int e = 0; e < PER; ++e) {
+            const int i = PER * threadIdx.x + e;
+            v.x[e] = (threadIdx.x < 64 && i < CT) ? lg[i] * kLog2e : 0.0f;
+        }
+        return v;
+    }
     // Rebuilds the tables from the values fetch() returned. Every thread calls it between
     // the barrier that retires the previous tile and the one that publishes the next.
-    DEVI void fill(float x) const {
+    DEVI void fill(const LogG &v) const {
         if (threadIdx.x < 64) {
             const int l = threadIdx.x;
-            float c = l < CT ? x : 0.0f;
+            float c[PER];
+            c[0] = v.x[0];
+#pragma unroll
+            for (int e = 1; e < PER; ++e) c[e] = c[e - 1] + v.x[e];
+            float incl = c[PER - 1];  // inclusive scan of the lane totals
 #pragma unroll
             for (int d = 1; d < 64; d <<= 1) {
-                const float y = __shfl_up(c, d, 64);
-                if (l >= d) c += y;
+                const float y = __shfl_up(incl, d, 64);
+                if (l >= d) incl += y;
             }
-            const float total = __shfl(c, CT - 1, 64);
-            if (l < CT) {
-                cum[l] = c;
-                wu[l] = exp2f(c);
-                wa[l] = exp2f(total - c);
+            const float total = __shfl(incl, 63, 64);  // lanes past the tile hold zeros
+            const float before = incl - c[PER - 1];
+#pragma unroll
+            for (int e = 0; e < PER; ++e) {
+                const int i = PER * l + e;
+                if (i < CT) {
+                    const float ci = before + c[e];
+                    cum[i] = ci;
+                    wu[i] = exp2f(ci);
+                    wa[i] = exp2f(total - ci);
+                }
             }
         }
     }
@@ -591,7 +619,7 @@ DEVI void cache_store(const Lane &ln, T *g, const f32x16 (&st)[D / 32], T *idle_
 // The row weight is applied to the Y fragments (shared by all row blocks).
 // ---------------------------------------------------------------------------
 template <typename T, int CT, int D, bool BWD, bool TOKEN>
-__global__ __launch_bounds__(D * 2) void k_local(const T *__restrict__ X, const T *__restrict__ Y,
+__global__ __launch_bounds__(D * 2, 2) void k_local(const T *__restrict__ X, const T *__restrict__ Y,
                                                   const float *__restrict__ decay, float *__restrict__ scratch,
                                                   float *__restrict__ seglog, int H, int ntiles, int nseg,
                                                   int tiles_per_seg) {
@@ -626,14 +654,15 @@ __global__ __launch_bounds__(D * 2) void k_local(const T *__restrict__ X, const 
         // with the tile's own weights): S <- whole S + (after (.) X)^T Y forward, (upto (.) X)^T Y backward.
         const TokenDecay<T, CT> dec(pw);
         const float *lg = decay + (size_t)chain * ntiles * CT;
-        float lgreg = TokenDecay<T, CT>::fetch(lg + (size_t)tile_of(0) * CT), lgsum = 0.0f;
+        typename TokenDecay<T, CT>::LogG lgreg = TokenDecay<T, CT>::fetch(lg + (size_t)tile_of(0) * CT);
+        float lgsum = 0.0f;
         for (int n = 0; n < ntl; ++n) {
             __syncthreads();
             ln = fresh_lane();
             mx.store(sX, LDD);
             my.store(sY, LDD);
             dec.fill(lgreg);
-            lgsum += lgreg;
+            lgsum += lgreg.sum();
             __syncthreads();
             if (n + 1 < ntl) {
                 mx.load(X + base + (size_t)tile_of(n + 1) * CT * D);
@@ -821,7 +850,7 @@ __global__ __launch_bounds__(D * 2, (CT <= 64 && sizeof(T) == 2) ? 2 : 1) void k
     state_load<D>(ln, st, scratch + ((size_t)chain * nseg + seg) * D * D, w);
     const auto dec = DecaySel<TOKEN, T, CT>::make(pw, decay, chain, H);
     const float *lg = decay + (size_t)chain * ntiles * CT;  // per-token decay: `decay` is log g, [chain][token]
-    float lgreg = 0.0f;
+    typename TokenDecay<T, CT>::LogG lgreg = {};
     if constexpr (TOKEN) lgreg = TokenDecay<T, CT>::fetch(lg + (size_t)t0 * CT);
 
     for (int t = t0; t < t1; ++t) {
@@ -943,7 +972,7 @@ __global__ __launch_bounds__(D * 2, (CT <= 64 && sizeof(T) == 2) ? 2 : 1) void k
     Lane ln = fresh_lane();
     const auto dec = DecaySel<TOKEN, T, CT>::make(pw, decay, chain, H);
     const float *lg = decay + (size_t)chain * ntiles * CT;  // per-token decay: `decay` is log g, [chain][token]
-    float lgreg = 0.0f;
+    typename TokenDecay<T, CT>::LogG lgreg = {};
     if constexpr (TOKEN) lgreg = TokenDecay<T, CT>::fetch(lg + (size_t)(t1 - 1) * CT);
     // per-token decay: r_t = q_t.dq_t - k_t.dk_t, one partial row per wave, summed and written per tile
     float *rs = pw + 3 * CT + 4;
@@ -1181,7 +1210,7 @@ __global__ __launch_bounds__(D * 4) void k_bwd8(const T *__restrict__ Q, const T
     }
     const auto dec = DecaySel<TOKEN, T, CT>::make(pw, decay, chain, H);
     const float *lg = decay + (size_t)chain * ntiles * CT;  // per-token decay: `decay` is log g, [chain][token]
-    float lgreg = 0.0f;
+    typename TokenDecay<T, CT>::LogG lgreg = {};
     if constexpr (TOKEN) lgreg = TokenDecay<T, CT>::fetch(lg + (size_t)(t1 - 1) * CT);
     // per-token decay: r_t = q_t.dq_t - k_t.dk_t, one partial row per wave, summed and written per tile
     float *rs = pw + 3 * CT + 4;
@@ -1394,15 +1423,17 @@ struct Bwd8pSmem {
     static constexpr size_t P_OFF = 6 * TILE;
     static constexpr size_t C_OFF = P_OFF + 2 * (size_t)CT * LDP * sizeof(T);
     static constexpr size_t PW_OFF = C_OFF + (size_t)D * LDD * sizeof(T);
-    static constexpr size_t TOTAL = PW_OFF + (CT + 1) * sizeof(float);
+    // decay tables of the O tile and of the E tile, then one row of per-token partial sums per wave
+    static constexpr size_t TOTAL = PW_OFF + (6 * CT + 4 + 8 * CT) * sizeof(float);
 };
 
-template <typename T, int CT, int D>
+template <typename T, int CT, int D, bool TOKEN>
 __global__ __launch_bounds__(D * 4) void k_bwd8p(const T *__restrict__ Q, const T *__restrict__ K,
                                                   const T *__restrict__ V, const T *__restrict__ dO,
                                                   const float *__restrict__ decay, const T *__restrict__ cache,
                                                   T *__restrict__ dQ, T *__restrict__ dK, T *__restrict__ dV,
                                                   float *__restrict__ dkv_in, const float *__restrict__ scratch,
+                                                  float *__restrict__ rtok,
                                                   int H, int ntiles, int nseg, int tiles_per_seg) {
     using E = Elem<T>;
     using F = typename E::frag;
@@ -1436,8 +1467,31 @@ __global__ __launch_bounds__(D * 4) void k_bwd8p(const T *__restrict__ Q, const 
     TileMover<T, CT, D, NT> mvO, moX, mkO, mqX, mvE, mkE;   // moX / mqX carry dO, Q of the O tile, then of the E tile
     TileMover<T, D, D, NT> mc;                               // cached state at the start of the E tile
     const T *ctile = cache + (size_t)chain * (ntiles / 2) * D * D;
+    // With a decay per token (`decay` = log g, [chain][token]) the O and the E tile have their own
+    // tables; with one lambda per head both names refer to the same table.
+    const auto decO = DecaySel<TOKEN, T, CT>::make(pw, decay, chain, H);
+    const auto decE = [&] {
+        if constexpr (TOKEN) return TokenDecay<T, CT>(pw + 3 * CT);
+        else return decO;
+    }();
+    const float *lg = decay + (size_t)chain * ntiles * CT;
+    typename TokenDecay<T, CT>::LogG lgO = {}, lgE = {};
+    // per-token decay: r_t = q_t.dq_t - k_t.dk_t, one partial row per wave, summed and written per tile
+    float *rs = pw + 6 * CT + 4;
+    auto flush_r = [&](int tile) {
+        if (threadIdx.x < CT) {
+            float r = 0.0f;
+#pragma unroll
+            for (int wv = 0; wv < 2 * NW; ++wv) r += rs[wv * CT + threadIdx.x];
+            rtok[((size_t)chain * ntiles + tile) * CT + threadIdx.x] = r;
+        }
+    };
     auto load_pair = [&](int tE) {
         const size_t oE = base + (size_t)tE * TS, oO = oE + TS;
+        if constexpr (TOKEN) {
+            lgO = TokenDecay<T, CT>::fetch(lg + (size_t)(tE + 1) * CT);
+            lgE = TokenDecay<T, CT>::fetch(lg + (size_t)tE * CT);
+        }
         mvO.load(V + oO);
         moX.load(dO + oO);
         mkO.load(K + oO);
@@ -1447,8 +1501,6 @@ __global__ __launch_bounds__(D * 4) void k_bwd8p(const T *__restrict__ Q, const 
         mc.load(ctile + (size_t)(tE / 2) * D * D);
     };
     load_pair(t1 - 2);
-    const FixedDecay<T, CT> dec(pw, decay[chain % H]);
-    const GeoWeights<T> &geo = dec.geo;
 
     const T *sX2 = rg ? sQ : sdO;    // intra operand and state-update B operand: [token][feature in w]
     const T *sUA = rg ? sdO : sQ;    // state-update A operand: [token][feature of the state rows]
@@ -1475,7 +1527,7 @@ __global__ __launch_bounds__(D * 4) void k_bwd8p(const T *__restrict__ Q, const 
     }
 
     // masked score tiles of the tile whose V, K are at pV, pK (dO, Q in sdO, sQ): one 32x32 block per wave
-    auto scores = [&](const T *pV, const T *pK) {
+    auto scores = [&](const auto &dec, const T *pV, const T *pK) {
         constexpr int NTRI = 3;
 #pragma unroll
         for (int idx = 0; idx < 2 * NTRI; ++idx) {
@@ -1502,20 +1554,22 @@ __global__ __launch_bounds__(D * 4) void k_bwd8p(const T *__restrict__ Q, const 
     };
 
     // dQ, this group's dV or dK, and the dKV update for the tile at element offset `off`
-    auto products = [&](const T *pV, const T *pK, size_t off) {
+    auto products = [&](const auto &dec, const T *pV, const T *pK, size_t off) {
         const T *sX1 = rg ? pV : pK;  // inter operand: token rows, features contracted with the state
+        float rq = 0.0f;  // per-token decay: q_i . dq_i over this wave's features, tokens i of block rg
         {   // dQ^T[a in w][i], tokens i of block rg
             const int r0 = 32 * rg;
             f32x16 acc = {0};
             pipelined<NKD>(
                 [&](int ks) { return FragPair<F>{E::ld_kc(ln, sC, LDD, 32 * w, ks * E::KSTEP), E::ld_kc(ln, sdO, LDD, r0, ks * E::KSTEP)}; },
                 [&](int, const FragPair<F> &f) { acc = E::mfma(f.a, f.b, acc); });
-            acc *= pw[r0 + ln.r + 1];
+            acc *= dec.upto(r0 + ln.r);
             auto intra = [&](int ks) { return FragPair<F>{E::ld_ks(ln, pK, LDD, ks * E::KSTEP, 32 * w), E::ld_kc(ln, sDS, LDP, r0, ks * E::KSTEP)}; };
             auto fma = [&](int, const FragPair<F> &f) { acc = E::mfma(f.a, f.b, acc); };
             if (rg == 0) pipelined<SPB>(intra, fma);
             else pipelined<2 * SPB>(intra, fma);
             store_out_tile_t<T, D>(ln, dQ + off, acc, r0, w);
+            if constexpr (TOKEN) rq = rowdot<T>(ln, acc, sQ, LDD, r0, w);
         }
         ln = fresh_lane();
         {   // dV^T[c in w][j] (group 0) or dK^T[a in w][j] (group 1), both token blocks
@@ -1536,7 +1590,7 @@ __global__ __launch_bounds__(D * 4) void k_bwd8p(const T *__restrict__ Q, const 
                     for (int jb = 0; jb < NB; ++jb) acc[jb] = E::mfma(sf, f.b[jb], acc[jb]);
                 });
 #pragma unroll
-            for (int jb = 0; jb < NB; ++jb) acc[jb] *= pw[CT - 1 - (32 * jb + ln.r)];
+            for (int jb = 0; jb < NB; ++jb) acc[jb] *= dec.after(32 * jb + ln.r);
             struct Three { F a; F b[NB]; };
             pipelined<NKS>(
                 [&](int ks) {
@@ -1554,10 +1608,18 @@ __global__ __launch_bounds__(D * 4) void k_bwd8p(const T *__restrict__ Q, const 
                 });
 #pragma unroll
             for (int jb = 0; jb < NB; ++jb) store_out_tile_t<T, D>(ln, gOut + off, acc[jb], 32 * jb, w);
+            if constexpr (TOKEN) {
+#pragma unroll
+                for (int jb = 0; jb < NB; ++jb) {
+                    float r = jb == rg ? rq : 0.0f;
+                    if (rg == 1) r -= rowdot<T>(ln, acc[jb], pK, LDD, 32 * jb, w);  // group 1 holds dK
+                    if (ln.h == 0) rs[w8 * CT + 32 * jb + ln.r] = r;
+                }
+            }
         }
         ln = fresh_lane();
         {   // state update in this group's orientation
-            const float lamC = pw[CT];
+            const float lamC = dec.whole();
 #pragma unroll
             for (int blk = 0; blk < DB; ++blk) st[blk] *= lamC;
             struct Step { F b; F a[DB]; };
@@ -1570,7 +1632,7 @@ __global__ __launch_bounds__(D * 4) void k_bwd8p(const T *__restrict__ Q, const 
                     return f;
                 },
                 [&](int ks, const Step &f) {
-                    const F bs = weigh_upto<T, CT>(ln, f.b, ks, pw, geo);
+                    const F bs = dec.weigh_upto(ln, f.b, ks);
 #pragma unroll
                     for (int blk = 0; blk < DB; ++blk) st[blk] = E::mfma(f.a[blk], bs, st[blk]);
                 });
@@ -1582,6 +1644,11 @@ __global__ __launch_bounds__(D * 4) void k_bwd8p(const T *__restrict__ Q, const 
         __syncthreads();  // previous pair fully consumed
         ln = fresh_lane();
         PHASE(0);
+        if constexpr (TOKEN) {
+            if (tE + 2 < t1) flush_r(tE + 2);  // E tile of the previous pair
+            decO.fill(lgO);
+            decE.fill(lgE);
+        }
         mvO.store(sVO, LDD);
         moX.store(sdO, LDD);
         mkO.store(sKO, LDD);
@@ -1596,11 +1663,11 @@ __global__ __launch_bounds__(D * 4) void k_bwd8p(const T *__restrict__ Q, const 
         mqX.load(Q + offE);
         PHASE(2);
         // ---- O tile ----
-        scores(sVO, sKO);
+        scores(decO, sVO, sKO);
         PHASE(3);
         {   // sC <- KV_mid, in place: block (cb, ab) of KV_mid^T[c][a] = lambda^CT KV^T + sum_j V_E[j][c] (w_j K_E[j][a])
             constexpr int NBLK = DB * DB, PER = (NBLK + 2 * NW - 1) / (2 * NW);
-            const float lamC = pw[CT];
+            const float lamC = decE.whole();
 #pragma unroll
             for (int u = 0; u < PER; ++u) {
                 const int blk = w8 * PER + u;
@@ -1610,7 +1677,7 @@ __global__ __launch_bounds__(D * 4) void k_bwd8p(const T *__restrict__ Q, const 
                 pipelined<NKS>(
                     [&](int ks) { return FragPair<F>{E::ld_ks(ln, sVE, LDD, ks * E::KSTEP, 32 * cb), E::ld_ks(ln, sKE, LDD, ks * E::KSTEP, 32 * ab)}; },
                     [&](int ks, const FragPair<F> &f) {
-                        acc = E::mfma(f.a, weigh_after<T, CT>(ln, f.b, ks, pw, geo), acc);
+                        acc = E::mfma(f.a, decE.weigh_after(ln, f.b, ks), acc);
                     });
                 // lane r holds a = 32 ab + r and, per register group q, c = 32 cb + 8 q + 4 h + (0..3)
 #pragma unroll
@@ -1627,11 +1694,12 @@ __global__ __launch_bounds__(D * 4) void k_bwd8p(const T *__restrict__ Q, const 
         __syncthreads();
         ln = fresh_lane();
         PHASE(5);
-        products(sVO, sKO, offO);
+        products(decO, sVO, sKO, offO);
         PHASE(6);
         __syncthreads();  // O tile consumed: sdO, sQ, sC are free
         ln = fresh_lane();
         PHASE(7);
+        if constexpr (TOKEN) flush_r(tE + 1);
         moX.store(sdO, LDD);
         mqX.store(sQ, LDD);
         mc.store(sC, LDD);
@@ -1641,15 +1709,19 @@ __global__ __launch_bounds__(D * 4) void k_bwd8p(const T *__restrict__ Q, const 
         if (tE > t0) load_pair(tE - 2);
         PHASE(9);
         // ---- E tile ----
-        scores(sVE, sKE);
+        scores(decE, sVE, sKE);
         PHASE(10);
         __syncthreads();
         ln = fresh_lane();
         PHASE(11);
-        products(sVE, sKE, offE);
+        products(decE, sVE, sKE, offE);
         PHASE(12);
     }
     PHASE_FLUSH();
+    if constexpr (TOKEN) {
+        __syncthreads();
+        flush_r(t0);
+    }
     if (seg == 0 && rg == 0) state_store<D>(ln, st, dkv_in + (size_t)chain * D * D, w);
 }
 
@@ -1750,30 +1822,27 @@ static hipError_t run_local(const Plan &p, const T *x, const T *y, const float *
                             hipStream_t s) {
     const int chains = p.B * p.H;
     hipError_t e;
-    if (p.token) {
-        constexpr size_t lds = Smem<T, CT, D>::local;
-        auto kl = k_local<T, CT, D, BWD, true>;
-        if ((e = allow_lds(kl, lds)) != hipSuccess) return e;
-        kl<<<dim3(p.nseg - 1, chains), dim3(D * 2), lds, s>>>(x, y, decay, scratch, seglog, p.H, p.ntiles, p.nseg,
-                                                            p.tiles_per_seg);
-        return hipSuccess;
-    }
     if constexpr (sizeof(T) == 2 && CT == 64) {
         if (p.tiles_per_seg % 2 == 0 && p.ntiles % 2 == 0) {
             constexpr size_t lds = Smem<T, 128, D>::local;
-            auto kl = k_local<T, 128, D, BWD, false>;
-            if ((e = allow_lds(kl, lds)) != hipSuccess) return e;
-            kl<<<dim3(p.nseg - 1, chains), dim3(D * 2), lds, s>>>(x, y, decay, scratch, nullptr, p.H, p.ntiles / 2, p.nseg,
-                                                                p.tiles_per_seg / 2);
-            return hipSuccess;
+            auto launch = [&](auto kl) -> hipError_t {
+                if (hipError_t e2 = allow_lds(kl, lds); e2 != hipSuccess) return e2;
+                kl<<<dim3(p.nseg - 1, chains), dim3(D * 2), lds, s>>>(x, y, decay, scratch, seglog, p.H, p.ntiles / 2, p.nseg,
+                                                                    p.tiles_per_seg / 2);
+                return hipSuccess;
+            };
+            return p.token ? launch(k_local<T, 128, D, BWD, true>) : launch(k_local<T, 128, D, BWD, false>);
         }
     }
     constexpr size_t lds = Smem<T, CT, D>::local;
-    auto kl = k_local<T, CT, D, BWD, false>;
-    if ((e = allow_lds(kl, lds)) != hipSuccess) return e;
-    kl<<<dim3(p.nseg - 1, chains), dim3(D * 2), lds, s>>>(x, y, decay, scratch, nullptr, p.H, p.ntiles, p.nseg,
-                                                        p.tiles_per_seg);
-    return hipSuccess;
+    auto launch = [&](auto kl) -> hipError_t {
+        if (hipError_t e2 = allow_lds(kl, lds); e2 != hipSuccess) return e2;
+        kl<<<dim3(p.nseg - 1, chains), dim3(D * 2), lds, s>>>(x, y, decay, scratch, seglog, p.H, p.ntiles, p.nseg,
+                                                            p.tiles_per_seg);
+        return hipSuccess;
+    };
+    (void)e;
+    return p.token ? launch(k_local<T, CT, D, BWD, true>) : launch(k_local<T, CT, D, BWD, false>);
 }
 
 template <typename T, int CT, int D>
@@ -1830,12 +1899,15 @@ static hipError_t run_bwd(const Plan &p, const BwdArgs &a, hipStream_t s, const 
       if (p.cache_stride == 2) {
         constexpr size_t lds_bwd8p = Bwd8pSmem<T, CT, D>::TOTAL;
         static_assert(lds_bwd8p <= 163840, "LDS budget of one gfx950 CU exceeded");
-        auto kb = k_bwd8p<T, CT, D>;
-        if ((e = allow_lds(kb, lds_bwd8p)) != hipSuccess) return e;
-        kb<<<dim3(p.nseg, chains), dim3(D * 4), lds_bwd8p, s>>>((const T *)a.q, (const T *)a.k, (const T *)a.v,
-                                                                (const T *)a.dout, a.decay, (const T *)a.cache, (T *)a.dq,
-                                                                (T *)a.dk, (T *)a.dv, a.dkv_in, (const float *)a.scratch,
-                                                                p.H, p.ntiles, p.nseg, p.tiles_per_seg);
+        auto launch = [&](auto kb) -> hipError_t {
+            if (hipError_t e2 = allow_lds(kb, lds_bwd8p); e2 != hipSuccess) return e2;
+            kb<<<dim3(p.nseg, chains), dim3(D * 4), lds_bwd8p, s>>>((const T *)a.q, (const T *)a.k, (const T *)a.v,
+                                                                    (const T *)a.dout, a.decay, (const T *)a.cache, (T *)a.dq,
+                                                                    (T *)a.dk, (T *)a.dv, a.dkv_in, (const float *)a.scratch,
+                                                                    a.rtok, p.H, p.ntiles, p.nseg, p.tiles_per_seg);
+            return hipSuccess;
+        };
+        if (e = p.token ? launch(k_bwd8p<T, CT, D, true>) : launch(k_bwd8p<T, CT, D, false>); e != hipSuccess) return e;
       } else {
         constexpr size_t lds_bwd8 = Bwd8Smem<T, CT, D>::TOTAL;
         static_assert(lds_bwd8 <= 163840, "LDS budget of one gfx950 CU exceeded");
@@ -1879,7 +1951,8 @@ extern "C" int lasp_debug_phases(unsigned long long *out32, int reset) {
 #endif
 
 int cache_stride_for(int dtype, int tile, int ntiles, bool token) {
-    return (!token && dtype == 1 && tile == 64 && ntiles % 2 == 0) ? 2 : 1;
+    (void)token;  // both decay models have the pair kernel
+    return (dtype == 1 && tile == 64 && ntiles % 2 == 0) ? 2 : 1;
 }
 
 // Tokens per kernel tile: 32 for float data, 64 for bfloat16 data, whatever the

@@ -114,6 +114,22 @@ def test_ragged_segments_and_determinism(gpu, oracle):
                 assert np.array_equal(got[name], again[name]), name
 
 
+def test_even_tile_counts_pair_cache(gpu, oracle):
+    """Even tile counts use the paired state cache and the 128-token local pass; segment requests
+    that are odd or do not divide the tiles are rounded to whole pairs."""
+    harness, lasp, si = gpu
+    for D in (64, 128):
+        cfg = si.Config("gpairs", B=1, H=2, N=64 * 12, D=D, chunk=64, dtype="bf16", seed=46 + D, token_decay=True)
+        inp = si.make_inputs(cfg, with_states=True)
+        rng = np.random.default_rng(cfg.seed)
+        inp.log_g = np.log(rng.uniform(0.85, 1.0, (1, 2, cfg.N))).astype(np.float32)
+        ref = oracle_all(oracle, inp)
+        for segments in (1, 2, 3, 5, 6, 12):
+            say(f"case gated pairs D={D} segments={segments}")
+            got = harness.run_gpu(inp, segments=segments)
+            compare(harness, got, ref, TOL["bf16"], f"gD{D}/seg{segments}")
+
+
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_extreme_gates(gpu, oracle, dtype):
     """No decay at all, gates that almost close (the state is cut there), and a head whose every
