@@ -21,11 +21,16 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X published dense bf16 MFMA rate
 
-# HBM bytes per launch on config c3 from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
-# runs summarised in profiles/c3_fwd_bwd_kernels.md (read + written, scaled by the
-# plain-copy calibration: FETCH_SIZE x 2.000, WRITE_SIZE x 1.000). Other configs: None.
-MEASURED_TRAFFIC_BYTES_C3 = {"fwd_walk": int((416.2 + 258.7) * 2**20), "bwd_walk": int((660.4 + 385.0) * 2**20),
-                             "fwd_local": int((248.1 + 31.0) * 2**20), "bwd_local": int((240.1 + 15.0) * 2**20)}
+# HBM bytes per launch from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs summarised in
+# profiles/<config>_fwd_bwd_kernels.md (read + written MiB, scaled by the plain-copy calibration:
+# FETCH_SIZE x 2.000, WRITE_SIZE x 1.000), for the default launch configuration. Other configs: None.
+_MIB = 2**20
+MEASURED_TRAFFIC_BYTES = {
+    "c3": {"fwd_walk": int((416.2 + 258.3) * _MIB), "bwd_walk": int((660.1 + 385.0) * _MIB),
+           "fwd_local": int((248.1 + 31.0) * _MIB), "bwd_local": int((240.1 + 15.0) * _MIB)},
+    "g3": {"fwd_walk": int((418.2 + 257.5) * _MIB), "bwd_walk": int((660.1 + 387.0) * _MIB),
+           "fwd_local": int((250.0 + 31.0) * _MIB), "bwd_local": int((242.0 + 15.0) * _MIB)},
+}
 
 
 def main():
@@ -107,7 +112,7 @@ def main():
     achieved = dom_bytes / (per_launch_ms[dominant] * 1e-3) / 1e9
     roofline = {"kernel": dominant, "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
                 "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-                "traffic": MEASURED_TRAFFIC_BYTES_C3.get(dominant) if (args.config == "c3" and args.segments == 0) else None,
+                "traffic": MEASURED_TRAFFIC_BYTES.get(args.config, {}).get(dominant) if args.segments == 0 else None,
                 "algorithmic_bytes_per_launch": dom_bytes,
                 "avg_launch_ms": round(per_launch_ms[dominant], 4),
                 "kernel_ms_per_launch": {n: round(x, 4) for n, x in per_launch_ms.items()}}
