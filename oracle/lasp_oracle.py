@@ -351,3 +351,26 @@ def gated_bwd_split(bwd_fn, q, k, v, dout, log_g, T, kv_ins, dkv_out=None, **kw)
                                                    log_g[:, :, sl], kv_in=kv_ins[t], dkv_out=g, **kw)
     cat = lambda xs: np.concatenate(xs, axis=2)
     return cat(dqs), cat(dks), cat(dvs), cat(dls), g
+
+
+# ---------------------------------------------------------------------------
+# Norm(.) of the normalised linear attention O = Norm((Q K^T (.) M) V) (Sec. 2,
+# linear-attention paragraph): read as the parameter-free root-mean-square
+# normalisation of every output row over the head dimension,
+#     y_s = o_s / sqrt(mean_c o_s[c]^2 + eps).
+# It acts on one token at a time, so it composes with any form of the oracle
+# above: forward = norm_fwd(fwd_*(...)), backward = bwd_*(..., dout = norm_bwd(...)).
+# ---------------------------------------------------------------------------
+def norm_fwd(o, eps):
+    """Returns (y, rstd): y = o * rstd, rstd = (mean(o^2, last axis) + eps)^(-1/2), rstd shaped like o[..., 0]."""
+    o = _d(o)
+    rstd = 1.0 / np.sqrt(np.mean(o * o, axis=-1) + float(eps))
+    return o * rstd[..., None], rstd
+
+
+def norm_bwd(dy, y, rstd):
+    """Gradient w.r.t. o of sum(y * dy), from the normalised output and rstd:
+    do_s = rstd_s (dy_s - y_s mean_c(dy_s[c] y_s[c]))."""
+    dy, y, rstd = _d(dy), _d(y), _d(rstd)
+    m = np.mean(dy * y, axis=-1)
+    return rstd[..., None] * (dy - y * m[..., None])
