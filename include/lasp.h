@@ -176,6 +176,32 @@ int lasp_gated_bwd(const lasp_shape *shape, const void *q, const void *k, const 
                    void *hip_stream);
 
 /*
+ * ---- Normalised output ------------------------------------------------------
+ * O = Norm((Q K^T (.) M) V) (Sec. 2, linear-attention paragraph; Sec. 3.2 drops
+ * the Norm only to shorten its derivation). The paper does not spell Norm out;
+ * here it is the parameter-free root-mean-square normalisation of every output
+ * row over the head dimension,
+ *     y_s = o_s * rstd_s,   rstd_s = (mean_c o_s[c]^2 + eps)^(-1/2),
+ * fused into the forward kernel's epilogue (o never goes to memory) and into
+ * the backward kernels' prologue:  do_s = rstd_s (dy_s - y_s mean_c(dy_s[c] y_s[c])).
+ * One lambda per head (lasp_fwd / lasp_bwd semantics otherwise).
+ *
+ *   eps     >= 0, finite (LASP_ERR_SHAPE otherwise).
+ *   out     forward: the NORMALISED output y, [B][H][N][D] in `dtype`; backward:
+ *           the same buffer, as input.
+ *   rstd    DEVICE float [B][H][N]: written by lasp_fwd_norm, read by lasp_bwd_norm.
+ *   dout    backward: gradient w.r.t. the normalised output y.
+ */
+int lasp_fwd_norm(const lasp_shape *shape, const void *q, const void *k, const void *v,
+                  const float *kv_in, const float *decay, float eps, void *out, float *rstd,
+                  float *kv_out, void *state_cache, void *scratch, size_t scratch_bytes,
+                  void *hip_stream);
+int lasp_bwd_norm(const lasp_shape *shape, const void *q, const void *k, const void *v,
+                  const void *out, const float *rstd, const void *dout, const float *dkv_out,
+                  const float *decay, const void *state_cache, void *dq, void *dk, void *dv,
+                  float *dkv_in, void *scratch, size_t scratch_bytes, void *hip_stream);
+
+/*
  * Per-kernel timing, for benchmarks (diagnostic; not on the hot path, not
  * thread-safe). Between lasp_profile_begin and lasp_profile_end every
  * lasp_fwd / lasp_bwd call records HIP events around its three kernels on the

@@ -28,7 +28,7 @@ bool valid_dims(const lasp_shape *s) {
     return true;
 }
 
-int make_plan(const lasp_shape *s, Pass pass, lasp::Plan *p, bool token = false) {
+int make_plan(const lasp_shape *s, Pass pass, lasp::Plan *p, bool token = false, bool norm = false) {
     if (!s) return LASP_ERR_NULL;
     if (s->dtype != LASP_F32 && s->dtype != LASP_BF16) return LASP_ERR_DTYPE;
     if (!valid_dims(s)) return LASP_ERR_SHAPE;
@@ -49,6 +49,7 @@ int make_plan(const lasp_shape *s, Pass pass, lasp::Plan *p, bool token = false)
         if (want < 1) want = 1;
     }
     p->token = token;
+    p->norm = norm;
     p->cache_stride = lasp::cache_stride_for(p->dtype, p->tile, p->ntiles, token);
     p->tiles_per_seg = (p->ntiles + want - 1) / want;
     if (p->cache_stride == 2) p->tiles_per_seg += p->tiles_per_seg & 1;   // segments start on cached tiles
@@ -206,7 +207,7 @@ int lasp_fwd(const lasp_shape *shape, const void *q, const void *k, const void *
         for (const Span &o2 : outs)
             if (&o != &o2 && overlap(o, o2)) return LASP_ERR_ALIAS;
     }
-    lasp::FwdArgs a{q, k, v, kv_in, decay, out, kv_out, state_cache, (float *)scratch, nullptr};
+    lasp::FwdArgs a{q, k, v, kv_in, decay, out, kv_out, state_cache, (float *)scratch, nullptr, nullptr, 0.0f};
     return lasp::launch_fwd(p, a, (hipStream_t)hip_stream, next_slot(0)) == hipSuccess ? LASP_OK : LASP_ERR_HIP;
 }
 
@@ -235,7 +236,7 @@ int lasp_bwd(const lasp_shape *shape, const void *q, const void *k, const void *
             if (&o != &o2 && overlap(o, o2)) return LASP_ERR_ALIAS;
     }
     lasp::BwdArgs a{q, k, v, dout, dkv_out, decay, state_cache, dq, dk, dv, dkv_in, (float *)scratch,
-                    nullptr, nullptr, nullptr, nullptr};
+                    nullptr, nullptr, nullptr, nullptr, nullptr, nullptr};
     return lasp::launch_bwd(p, a, (hipStream_t)hip_stream, next_slot(1)) == hipSuccess ? LASP_OK : LASP_ERR_HIP;
 }
 
@@ -265,7 +266,7 @@ int lasp_gated_fwd(const lasp_shape *shape, const void *q, const void *k, const 
             if (&o != &o2 && overlap(o, o2)) return LASP_ERR_ALIAS;
     }
     lasp::FwdArgs a{q, k, v, kv_in, log_g, out, kv_out, state_cache, (float *)scratch,
-                    (float *)((char *)scratch + l.seglog)};
+                    (float *)((char *)scratch + l.seglog), nullptr, 0.0f};
     return lasp::launch_fwd(p, a, (hipStream_t)hip_stream, next_slot(0)) == hipSuccess ? LASP_OK : LASP_ERR_HIP;
 }
 
@@ -298,7 +299,69 @@ int lasp_gated_bwd(const lasp_shape *shape, const void *q, const void *k, const 
             if (&o != &o2 && overlap(o, o2)) return LASP_ERR_ALIAS;
     }
     lasp::BwdArgs a{q, k, v, dout, dkv_out, log_g, state_cache, dq, dk, dv, dkv_in, (float *)scratch,
-                    kv_out, dlog_g, (float *)((char *)scratch + l.seglog), (float *)((char *)scratch + l.rtok)};
+                    kv_out, dlog_g, (float *)((char *)scratch + l.seglog), (float *)((char *)scratch + l.rtok),
+                    nullptr, nullptr};
+    return lasp::launch_bwd(p, a, (hipStream_t)hip_stream, next_slot(1)) == hipSuccess ? LASP_OK : LASP_ERR_HIP;
+}
+
+int lasp_fwd_norm(const lasp_shape *shape, const void *q, const void *k, const void *v, const float *kv_in,
+                  const float *decay, float eps, void *out, float *rstd, float *kv_out, void *state_cache,
+                  void *scratch, size_t scratch_bytes, void *hip_stream) {
+    lasp::Plan p;
+    int rc = make_plan(shape, kForward, &p, false, true);
+    if (rc != LASP_OK) return rc;
+    if (!q || !k || !v || !decay || !out || !rstd || !kv_out) return LASP_ERR_NULL;
+    if (!std::isfinite(eps) || eps < 0.0f) return LASP_ERR_SHAPE;
+    if (!scratch || scratch_bytes < lasp_scratch_bytes(shape)) return LASP_ERR_WORKSPACE;
+
+    const size_t tb = (size_t)p.B * p.H * p.N * p.D * elem_bytes(p.dtype);
+    const size_t sb = (size_t)p.B * p.H * p.D * p.D * sizeof(float);
+    const size_t gb = (size_t)p.B * p.H * p.N * sizeof(float);
+    const Span ins[] = {{(const char *)q, tb}, {(const char *)k, tb}, {(const char *)v, tb},
+                        {(const char *)kv_in, sb}, {(const char *)decay, p.H * sizeof(float)}};
+    const Span outs[] = {{(const char *)out, tb}, {(const char *)rstd, gb}, {(const char *)kv_out, sb},
+                         {(const char *)state_cache, lasp_state_cache_bytes(shape)},
+                         {(const char *)scratch, lasp_scratch_bytes(shape)}};
+    if (!aligned16(ins, outs)) return LASP_ERR_ALIGN;
+    for (const Span &o : outs) {
+        for (const Span &i : ins)
+            if (overlap(o, i)) return LASP_ERR_ALIAS;
+        for (const Span &o2 : outs)
+            if (&o != &o2 && overlap(o, o2)) return LASP_ERR_ALIAS;
+    }
+    lasp::FwdArgs a{q, k, v, kv_in, decay, out, kv_out, state_cache, (float *)scratch, nullptr, rstd, eps};
+    return lasp::launch_fwd(p, a, (hipStream_t)hip_stream, next_slot(0)) == hipSuccess ? LASP_OK : LASP_ERR_HIP;
+}
+
+int lasp_bwd_norm(const lasp_shape *shape, const void *q, const void *k, const void *v, const void *out,
+                  const float *rstd, const void *dout, const float *dkv_out, const float *decay,
+                  const void *state_cache, void *dq, void *dk, void *dv, float *dkv_in, void *scratch,
+                  size_t scratch_bytes, void *hip_stream) {
+    lasp::Plan p;
+    int rc = make_plan(shape, kBackward, &p, false, true);
+    if (rc != LASP_OK) return rc;
+    if (!q || !k || !v || !out || !rstd || !dout || !decay || !state_cache || !dq || !dk || !dv || !dkv_in)
+        return LASP_ERR_NULL;
+    if (!scratch || scratch_bytes < lasp_scratch_bytes(shape)) return LASP_ERR_WORKSPACE;
+
+    const size_t tb = (size_t)p.B * p.H * p.N * p.D * elem_bytes(p.dtype);
+    const size_t sb = (size_t)p.B * p.H * p.D * p.D * sizeof(float);
+    const size_t gb = (size_t)p.B * p.H * p.N * sizeof(float);
+    const Span ins[] = {{(const char *)q, tb}, {(const char *)k, tb}, {(const char *)v, tb},
+                        {(const char *)out, tb}, {(const char *)rstd, gb}, {(const char *)dout, tb},
+                        {(const char *)dkv_out, sb}, {(const char *)decay, p.H * sizeof(float)},
+                        {(const char *)state_cache, lasp_state_cache_bytes(shape)}};
+    const Span outs[] = {{(const char *)dq, tb}, {(const char *)dk, tb}, {(const char *)dv, tb},
+                         {(const char *)dkv_in, sb}, {(const char *)scratch, lasp_scratch_bytes(shape)}};
+    if (!aligned16(ins, outs)) return LASP_ERR_ALIGN;
+    for (const Span &o : outs) {
+        for (const Span &i : ins)
+            if (overlap(o, i)) return LASP_ERR_ALIAS;
+        for (const Span &o2 : outs)
+            if (&o != &o2 && overlap(o, o2)) return LASP_ERR_ALIAS;
+    }
+    lasp::BwdArgs a{q, k, v, dout, dkv_out, decay, state_cache, dq, dk, dv, dkv_in, (float *)scratch,
+                    nullptr, nullptr, nullptr, nullptr, out, rstd};
     return lasp::launch_bwd(p, a, (hipStream_t)hip_stream, next_slot(1)) == hipSuccess ? LASP_OK : LASP_ERR_HIP;
 }
 

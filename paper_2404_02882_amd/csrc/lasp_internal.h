@@ -19,6 +19,7 @@ struct Plan {
     int tiles_per_seg;  // ceil(ntiles / nseg); the last segment may be shorter
     int cache_stride;   // the state cache holds the start state of every cache_stride-th tile (1 or 2)
     bool token;         // per-token decay: `decay` of the argument structs is log g, [B][H][N]
+    bool norm;          // output rows are normalised (forward epilogue, backward prologue); token == false
 };
 
 struct FwdArgs {
@@ -30,6 +31,8 @@ struct FwdArgs {
     void *cache;          // may be null
     float *scratch;       // [B*H][nseg][D][D]
     float *seglog;        // per-token decay only: [B*H][nseg], log2 of the decay over each segment
+    float *rstd_out;      // norm only: [B][H][N]
+    float eps;            // norm only
 };
 
 struct BwdArgs {
@@ -45,6 +48,9 @@ struct BwdArgs {
     float *dlog_g;        // [B][H][N]
     float *seglog;        // [B*H][nseg]
     float *rtok;          // [B*H][N] scratch: q_t.dq_t - k_t.dk_t
+    // norm only: `dout` is the gradient w.r.t. the normalised output
+    const void *yn;       // the normalised output the forward pass wrote
+    const float *rstd;    // [B][H][N], from the forward pass
 };
 
 // Optional event recorder: when non-null, launch_* records ev[0] before the

@@ -325,6 +325,74 @@ struct TileMover {
     }
 };
 
+// ---------------------------------------------------------------------------
+// Norm(.) of the normalised linear attention O = Norm((Q K^T (.) M) V) (Sec. 2),
+// taken as the parameter-free root-mean-square normalisation of an output row:
+//     y = o * rstd,  rstd = (mean_c o[c]^2 + eps)^(-1/2).
+// Backward, applied to a tile of dY while it is still in registers on its way to
+// LDS (the kernels then see dO as if it had been an input):
+//     dO = rstd (dY - Y mean_c(dY[c] Y[c])).
+// A row's pieces sit in COLS / EPV consecutive lanes of one wave, so the row mean
+// is a butterfly over those lanes. NormTile holds what the prologue needs beside
+// dY: the same pieces of Y and one rstd per piece row.
+// ---------------------------------------------------------------------------
+template <typename T, int ROWS, int COLS, int NT>
+struct NormTile {
+    typedef TileMover<T, ROWS, COLS, NT> TM;
+    TM y;
+    float rstd[TM::NV];
+    DEVI void load(const T *y_tile, const float *rstd_tile) {  // both uniform: first element / first row of the tile
+        y.load(y_tile);
+        const unsigned lo = (threadIdx.x / TM::VPR) * sizeof(float);
+#pragma unroll
+        for (int i = 0; i < TM::NV; ++i) rstd[i] = gload<float>(rstd_tile + i * (NT / TM::VPR), lo);
+    }
+    DEVI void apply(TM &dy) const {
+        static_assert(TM::VPR <= 32, "a row lies inside one half-wave");
+#pragma unroll
+        for (int i = 0; i < TM::NV; ++i) {
+            constexpr int E = TM::EPV;
+            float a[E], b[E];
+            if constexpr (sizeof(T) == 2) {
+                union { u32x4 u; bf16x8 v; } ua, ub;
+                ua.u = dy.r[i];
+                ub.u = y.r[i];
+                const f32x8 fa = __builtin_convertvector(ua.v, f32x8), fb = __builtin_convertvector(ub.v, f32x8);
+#pragma unroll
+                for (int e = 0; e < E; ++e) {
+                    a[e] = fa[e];
+                    b[e] = fb[e];
+                }
+            } else {
+#pragma unroll
+                for (int e = 0; e < E; ++e) {
+                    a[e] = __uint_as_float(dy.r[i][e]);
+                    b[e] = __uint_as_float(y.r[i][e]);
+                }
+            }
+            float p = 0.0f;
+#pragma unroll
+            for (int e = 0; e < E; ++e) p += a[e] * b[e];
+#pragma unroll
+            for (int m = 1; m < TM::VPR; m <<= 1) p += __shfl_xor(p, m, 64);
+            const float mean = p * (1.0f / COLS), rs = rstd[i];
+#pragma unroll
+            for (int e = 0; e < E; ++e) a[e] = rs * (a[e] - b[e] * mean);
+            if constexpr (sizeof(T) == 2) {
+                f32x8 f;
+#pragma unroll
+                for (int e = 0; e < E; ++e) f[e] = a[e];
+                union { u32x4 u; bf16x8 v; } uo;
+                uo.v = __builtin_convertvector(f, bf16x8);
+                dy.r[i] = uo.u;
+            } else {
+#pragma unroll
+                for (int e = 0; e < E; ++e) dy.r[i][e] = __float_as_uint(a[e]);
+            }
+        }
+    }
+};
+
 // Row weights lambda^(CT-1-k) ("after": tokens after k in the tile) and lambda^(k+1)
 // ("upto": 1-based position) for the KH consecutive tokens k_first .. k_first+KH-1 a
 // lane holds in one fragment, as one table entry times a wave-uniform factor per element:
@@ -618,11 +686,15 @@ DEVI void cache_store(const Lane &ln, T *g, const f32x16 (&st)[D / 32], T *idle_
 //   backward: S <- lambda^CT S + (diag{lambda^1..lambda^CT} X)^T Y, tiles descending
 // The row weight is applied to the Y fragments (shared by all row blocks).
 // ---------------------------------------------------------------------------
-template <typename T, int CT, int D, bool BWD, bool TOKEN>
+// NORM (backward only): Y is dY, the gradient w.r.t. the normalised output; the tile is turned into dO
+// on its way to LDS from the normalised output `yn` and `rstd` ([chain][token]).
+template <typename T, int CT, int D, bool BWD, bool TOKEN, bool NORM = false>
 __global__ __launch_bounds__(D * 2, 2) void k_local(const T *__restrict__ X, const T *__restrict__ Y,
                                                   const float *__restrict__ decay, float *__restrict__ scratch,
                                                   float *__restrict__ seglog, int H, int ntiles, int nseg,
-                                                  int tiles_per_seg) {
+                                                  int tiles_per_seg, const T *__restrict__ yn = nullptr,
+                                                  const float *__restrict__ rstd = nullptr) {
+    static_assert(!NORM || (BWD && !TOKEN), "the Norm prologue belongs to the backward pass with one lambda per head");
     using E = Elem<T>;
     constexpr int NT = D * 2, LDD = tile_ld<T, D>(), DB = D / 32, NKS = CT / E::KSTEP;
     extern __shared__ __attribute__((aligned(16))) char smem[];
@@ -644,6 +716,9 @@ __global__ __launch_bounds__(D * 2, 2) void k_local(const T *__restrict__ X, con
     TileMover<T, CT, D, NT> mx, my;
     mx.load(X + base + (size_t)tile_of(0) * CT * D);
     my.load(Y + base + (size_t)tile_of(0) * CT * D);
+    NormTile<T, CT, D, NT> mn;
+    const float *rstd_c = rstd + (size_t)chain * ntiles * CT;
+    if constexpr (NORM) mn.load(yn + base + (size_t)tile_of(0) * CT * D, rstd_c + (size_t)tile_of(0) * CT);
     PHASE(22);
     f32x16 st[DB];
 #pragma unroll
@@ -706,6 +781,7 @@ __global__ __launch_bounds__(D * 2, 2) void k_local(const T *__restrict__ X, con
         __syncthreads();  // previous tile fully consumed (and pw visible on the first pass)
         ln = fresh_lane();
         PHASE(24);
+        if constexpr (NORM) mn.apply(my);
         mx.store(sX, LDD);
         my.store(sY, LDD);
         PHASE(25);
@@ -714,6 +790,7 @@ __global__ __launch_bounds__(D * 2, 2) void k_local(const T *__restrict__ X, con
         if (n + 1 < ntl) {
             mx.load(X + base + (size_t)tile_of(n + 1) * CT * D);
             my.load(Y + base + (size_t)tile_of(n + 1) * CT * D);
+            if constexpr (NORM) mn.load(yn + base + (size_t)tile_of(n + 1) * CT * D, rstd_c + (size_t)tile_of(n + 1) * CT);
         }
         PHASE(27);
         // Token weight relative to the whole segment, so the accumulators are never rescaled:
@@ -819,12 +896,15 @@ __global__ __launch_bounds__(256) void k_scan(float *__restrict__ scratch, const
 //   KV_t   = lambda^CT KV_{t-1} + (lambda^CT Lambda^-1 K)^T V
 // The state KV_{t-1} each tile starts from is optionally written to the cache.
 // ---------------------------------------------------------------------------
-template <typename T, int CT, int D, bool TOKEN>
+// NORM: every output row is divided by its root mean square (plus eps under the root) before it is
+// stored, and the factor is written to rstd_out ([chain][token]) for the backward pass.
+template <typename T, int CT, int D, bool TOKEN, bool NORM = false>
 __global__ __launch_bounds__(D * 2, (CT <= 64 && sizeof(T) == 2) ? 2 : 1) void k_fwd(const T *__restrict__ Q, const T *__restrict__ K,
                                                 const T *__restrict__ V, const float *__restrict__ decay,
                                                 T *__restrict__ O, float *__restrict__ kv_out,
                                                 T *__restrict__ cache, const float *__restrict__ scratch,
-                                                int H, int ntiles, int nseg, int tiles_per_seg, int cache_stride) {
+                                                int H, int ntiles, int nseg, int tiles_per_seg, int cache_stride,
+                                                float *__restrict__ rstd_out = nullptr, float eps = 0.0f) {
     using E = Elem<T>;
     constexpr int NT = D * 2, LDD = tile_ld<T, D>(), LDP = CT + E::PAD, DB = D / 32, NB = CT / 32, NKS = CT / E::KSTEP,
                   SPB = 32 / E::KSTEP;
@@ -901,6 +981,28 @@ __global__ __launch_bounds__(D * 2, (CT <= 64 && sizeof(T) == 2) ? 2 : 1) void k
             for (int ib = ks / SPB; ib < NB; ++ib) acc[ib] = E::mfma(vf, E::ld_kc(ln, sP, LDP, 32 * ib, ks * E::KSTEP), acc[ib]);
             SCHED_FENCE();
         }
+        if constexpr (NORM) {
+            // sum of squares of a token's row: this wave's 32 features, then the other waves' through LDS
+            float *red = pw + 3 * CT + 4;
+#pragma unroll
+            for (int ib = 0; ib < NB; ++ib) {
+                float ss = 0.0f;
+#pragma unroll
+                for (int i = 0; i < 16; ++i) ss += acc[ib][i] * acc[ib][i];
+                ss += __shfl_xor(ss, 32, 64);
+                if (ln.h == 0) red[w * CT + 32 * ib + ln.r] = ss;
+            }
+            __syncthreads();
+#pragma unroll
+            for (int ib = 0; ib < NB; ++ib) {
+                float tot = 0.0f;
+#pragma unroll
+                for (int wv = 0; wv < D / 32; ++wv) tot += red[wv * CT + 32 * ib + ln.r];
+                const float rs = rsqrtf(tot * (1.0f / D) + eps);
+                acc[ib] *= rs;
+                if (w == 0 && ln.h == 0) rstd_out[((size_t)chain * ntiles + t) * CT + 32 * ib + ln.r] = rs;
+            }
+        }
         T *o = O + base + (size_t)t * CT * D;
 #pragma unroll
         for (int ib = 0; ib < NB; ++ib) store_out_tile_t<T, D>(ln, o, acc[ib], 32 * ib, w);
@@ -945,14 +1047,17 @@ struct BwdSmem {
     static constexpr size_t TOTAL = PW_OFF + table_floats<CT>() * sizeof(float);
 };
 
-template <typename T, int CT, int D, bool TOKEN>
+// NORM: dO is dY, the gradient w.r.t. the normalised output `yn`; every dY tile is turned into dO on its
+// way to LDS (NormTile) from `yn` and `rstd` ([chain][token]).
+template <typename T, int CT, int D, bool TOKEN, bool NORM = false>
 __global__ __launch_bounds__(D * 2, (CT <= 64 && sizeof(T) == 2) ? 2 : 1) void k_bwd(const T *__restrict__ Q, const T *__restrict__ K,
                                                 const T *__restrict__ V, const T *__restrict__ dO,
                                                 const float *__restrict__ decay, const T *__restrict__ cache,
                                                 T *__restrict__ dQ, T *__restrict__ dK, T *__restrict__ dV,
                                                 float *__restrict__ dkv_in, const float *__restrict__ scratch,
                                                 float *__restrict__ rtok,
-                                                int H, int ntiles, int nseg, int tiles_per_seg) {
+                                                int H, int ntiles, int nseg, int tiles_per_seg,
+                                                const T *__restrict__ yn = nullptr, const float *__restrict__ rstd = nullptr) {
     using E = Elem<T>;
     using SM = BwdSmem<T, CT, D>;
     constexpr int NT = D * 2, LDD = SM::LDD, LDP = SM::LDP, DB = D / 32, NB = CT / 32, NKS = CT / E::KSTEP,
@@ -992,6 +1097,9 @@ __global__ __launch_bounds__(D * 2, (CT <= 64 && sizeof(T) == 2) ? 2 : 1) void k
     TileMover<T, CT, D, NT> ma, mb;
     ma.load(V + base + (size_t)(t1 - 1) * CT * D);
     mb.load(dO + base + (size_t)(t1 - 1) * CT * D);
+    NormTile<T, CT, D, NT> mn;
+    const float *rstd_c = rstd + (size_t)chain * ntiles * CT;
+    if constexpr (NORM) mn.load(yn + base + (size_t)(t1 - 1) * CT * D, rstd_c + (size_t)(t1 - 1) * CT);
 
     for (int t = t1 - 1; t >= t0; --t) {
         const size_t off = base + (size_t)t * CT * D;
@@ -1014,6 +1122,7 @@ __global__ __launch_bounds__(D * 2, (CT <= 64 && sizeof(T) == 2) ? 2 : 1) void k
         __syncthreads();
 
         // ---- step 1: V (bufA), dO (bufB) ----
+        if constexpr (NORM) mn.apply(mb);
         ma.store(bufA, LDD);
         mb.store(bufB, LDD);
         if constexpr (TOKEN) dec.fill(lgreg);
@@ -1063,6 +1172,7 @@ __global__ __launch_bounds__(D * 2, (CT <= 64 && sizeof(T) == 2) ? 2 : 1) void k
         if (t > t0) {
             ma.load(V + off - (size_t)CT * D);
             mb.load(dO + off - (size_t)CT * D);
+            if constexpr (NORM) mn.load(yn + off - (size_t)CT * D, rstd_c + (size_t)(t - 1) * CT);
         }
         masked_scores<T, CT, D, LDD, LDP>(ln, sS, bufA, bufB, dec, w);  // S^T = K Q^T
         __syncthreads();
@@ -1162,14 +1272,15 @@ struct Bwd8Smem {
     static constexpr size_t TOTAL = PW_OFF + table_floats<CT>() * sizeof(float);
 };
 
-template <typename T, int CT, int D, bool TOKEN>
+template <typename T, int CT, int D, bool TOKEN, bool NORM = false>
 __global__ __launch_bounds__(D * 4) void k_bwd8(const T *__restrict__ Q, const T *__restrict__ K,
                                                  const T *__restrict__ V, const T *__restrict__ dO,
                                                  const float *__restrict__ decay, const T *__restrict__ cache,
                                                  T *__restrict__ dQ, T *__restrict__ dK, T *__restrict__ dV,
                                                  float *__restrict__ dkv_in, const float *__restrict__ scratch,
                                                  float *__restrict__ rtok,
-                                                 int H, int ntiles, int nseg, int tiles_per_seg) {
+                                                 int H, int ntiles, int nseg, int tiles_per_seg,
+                                                 const T *__restrict__ yn = nullptr, const float *__restrict__ rstd = nullptr) {
     using E = Elem<T>;
     using F = typename E::frag;
     using SM = Bwd8Smem<T, CT, D>;
@@ -1208,6 +1319,9 @@ __global__ __launch_bounds__(D * 4) void k_bwd8(const T *__restrict__ Q, const T
         mq.load(Q + off);
         mc.load(ctile + (size_t)(t1 - 1) * D * D);
     }
+    NormTile<T, CT, D, NT> mn;  // NORM: dO is dY; turned into dO from the normalised output and rstd on its way to LDS
+    const float *rstd_c = rstd + (size_t)chain * ntiles * CT;
+    if constexpr (NORM) mn.load(yn + base + (size_t)(t1 - 1) * CT * D, rstd_c + (size_t)(t1 - 1) * CT);
     const auto dec = DecaySel<TOKEN, T, CT>::make(pw, decay, chain, H);
     const float *lg = decay + (size_t)chain * ntiles * CT;  // per-token decay: `decay` is log g, [chain][token]
     typename TokenDecay<T, CT>::LogG lgreg = {};
@@ -1258,6 +1372,7 @@ __global__ __launch_bounds__(D * 4) void k_bwd8(const T *__restrict__ Q, const T
             if (t < t1 - 1) flush_r(t + 1);
             dec.fill(lgreg);
         }
+        if constexpr (NORM) mn.apply(mo);
         mv.store(sV, LDD);
         mo.store(sdO, LDD);
         mk.store(sK, LDD);
@@ -1272,6 +1387,7 @@ __global__ __launch_bounds__(D * 4) void k_bwd8(const T *__restrict__ Q, const T
             mk.load(K + off - (size_t)CT * D);
             mq.load(Q + off - (size_t)CT * D);
             mc.load(ctile + (size_t)(t - 1) * D * D);
+            if constexpr (NORM) mn.load(yn + off - (size_t)CT * D, rstd_c + (size_t)(t - 1) * CT);
             if constexpr (TOKEN) lgreg = TokenDecay<T, CT>::fetch(lg + (size_t)(t - 1) * CT);
         }
         // masked score tiles: dS^T = V dO^T (tiles 0..2) and S^T = K Q^T (tiles 3..5), one per wave
@@ -1427,14 +1543,15 @@ struct Bwd8pSmem {
     static constexpr size_t TOTAL = PW_OFF + (6 * CT + 4 + 8 * CT) * sizeof(float);
 };
 
-template <typename T, int CT, int D, bool TOKEN>
+template <typename T, int CT, int D, bool TOKEN, bool NORM = false>
 __global__ __launch_bounds__(D * 4) void k_bwd8p(const T *__restrict__ Q, const T *__restrict__ K,
                                                   const T *__restrict__ V, const T *__restrict__ dO,
                                                   const float *__restrict__ decay, const T *__restrict__ cache,
                                                   T *__restrict__ dQ, T *__restrict__ dK, T *__restrict__ dV,
                                                   float *__restrict__ dkv_in, const float *__restrict__ scratch,
                                                   float *__restrict__ rtok,
-                                                  int H, int ntiles, int nseg, int tiles_per_seg) {
+                                                  int H, int ntiles, int nseg, int tiles_per_seg,
+                                                  const T *__restrict__ yn = nullptr, const float *__restrict__ rstd = nullptr) {
     using E = Elem<T>;
     using F = typename E::frag;
     using SM = Bwd8pSmem<T, CT, D>;
@@ -1486,8 +1603,11 @@ __global__ __launch_bounds__(D * 4) void k_bwd8p(const T *__restrict__ Q, const 
             rtok[((size_t)chain * ntiles + tile) * CT + threadIdx.x] = r;
         }
     };
+    NormTile<T, CT, D, NT> mnX;  // NORM: partner of moX (dO is dY; see NormTile)
+    const float *rstd_c = rstd + (size_t)chain * ntiles * CT;
     auto load_pair = [&](int tE) {
         const size_t oE = base + (size_t)tE * TS, oO = oE + TS;
+        if constexpr (NORM) mnX.load(yn + oO, rstd_c + (size_t)(tE + 1) * CT);
         if constexpr (TOKEN) {
             lgO = TokenDecay<T, CT>::fetch(lg + (size_t)(tE + 1) * CT);
             lgE = TokenDecay<T, CT>::fetch(lg + (size_t)tE * CT);
@@ -1649,6 +1769,7 @@ __global__ __launch_bounds__(D * 4) void k_bwd8p(const T *__restrict__ Q, const 
             decO.fill(lgO);
             decE.fill(lgE);
         }
+        if constexpr (NORM) mnX.apply(moX);
         mvO.store(sVO, LDD);
         moX.store(sdO, LDD);
         mkO.store(sKO, LDD);
@@ -1661,6 +1782,7 @@ __global__ __launch_bounds__(D * 4) void k_bwd8p(const T *__restrict__ Q, const 
         PHASE(1);
         moX.load(dO + offE);
         mqX.load(Q + offE);
+        if constexpr (NORM) mnX.load(yn + offE, rstd_c + (size_t)tE * CT);
         PHASE(2);
         // ---- O tile ----
         scores(decO, sVO, sKO);
@@ -1700,6 +1822,7 @@ __global__ __launch_bounds__(D * 4) void k_bwd8p(const T *__restrict__ Q, const 
         ln = fresh_lane();
         PHASE(7);
         if constexpr (TOKEN) flush_r(tE + 1);
+        if constexpr (NORM) mnX.apply(moX);
         moX.store(sdO, LDD);
         mqX.store(sQ, LDD);
         mc.store(sC, LDD);
@@ -1819,16 +1942,25 @@ static hipError_t allow_lds(F kernel, size_t bytes) {
 // per-token decay (`decay` = log g) the walk's tile is used.
 template <typename T, int CT, int D, bool BWD>
 static hipError_t run_local(const Plan &p, const T *x, const T *y, const float *decay, float *scratch, float *seglog,
-                            hipStream_t s) {
+                            const T *yn, const float *rstd, hipStream_t s) {
     const int chains = p.B * p.H;
-    hipError_t e;
+    if constexpr (BWD) {
+        if (p.norm) {  // the Norm prologue needs a third tile in registers: the walk's tile length
+            constexpr size_t lds = Smem<T, CT, D>::local;
+            auto kl = k_local<T, CT, D, true, false, true>;
+            if (hipError_t e2 = allow_lds(kl, lds); e2 != hipSuccess) return e2;
+            kl<<<dim3(p.nseg - 1, chains), dim3(D * 2), lds, s>>>(x, y, decay, scratch, seglog, p.H, p.ntiles, p.nseg,
+                                                                p.tiles_per_seg, yn, rstd);
+            return hipSuccess;
+        }
+    }
     if constexpr (sizeof(T) == 2 && CT == 64) {
         if (p.tiles_per_seg % 2 == 0 && p.ntiles % 2 == 0) {
             constexpr size_t lds = Smem<T, 128, D>::local;
             auto launch = [&](auto kl) -> hipError_t {
                 if (hipError_t e2 = allow_lds(kl, lds); e2 != hipSuccess) return e2;
                 kl<<<dim3(p.nseg - 1, chains), dim3(D * 2), lds, s>>>(x, y, decay, scratch, seglog, p.H, p.ntiles / 2, p.nseg,
-                                                                    p.tiles_per_seg / 2);
+                                                                    p.tiles_per_seg / 2, nullptr, nullptr);
                 return hipSuccess;
             };
             return p.token ? launch(k_local<T, 128, D, BWD, true>) : launch(k_local<T, 128, D, BWD, false>);
@@ -1838,10 +1970,9 @@ static hipError_t run_local(const Plan &p, const T *x, const T *y, const float *
     auto launch = [&](auto kl) -> hipError_t {
         if (hipError_t e2 = allow_lds(kl, lds); e2 != hipSuccess) return e2;
         kl<<<dim3(p.nseg - 1, chains), dim3(D * 2), lds, s>>>(x, y, decay, scratch, seglog, p.H, p.ntiles, p.nseg,
-                                                            p.tiles_per_seg);
+                                                            p.tiles_per_seg, nullptr, nullptr);
         return hipSuccess;
     };
-    (void)e;
     return p.token ? launch(k_local<T, CT, D, BWD, true>) : launch(k_local<T, CT, D, BWD, false>);
 }
 
@@ -1853,7 +1984,8 @@ static hipError_t run_fwd(const Plan &p, const FwdArgs &a, hipStream_t s, const 
     hipError_t e;
     if (ke) (void)hipEventRecord(ke->ev[0], s);
     if (p.nseg > 1) {
-        if (e = run_local<T, CT, D, false>(p, (const T *)a.k, (const T *)a.v, a.decay, a.scratch, a.seglog, s); e != hipSuccess)
+        if (e = run_local<T, CT, D, false>(p, (const T *)a.k, (const T *)a.v, a.decay, a.scratch, a.seglog, nullptr, nullptr, s);
+            e != hipSuccess)
             return e;
     }
     if (ke) (void)hipEventRecord(ke->ev[1], s);
@@ -1868,10 +2000,13 @@ static hipError_t run_fwd(const Plan &p, const FwdArgs &a, hipStream_t s, const 
         if (hipError_t e2 = allow_lds(kf, lds_fwd); e2 != hipSuccess) return e2;
         kf<<<dim3(p.nseg, chains), dim3(D * 2), lds_fwd, s>>>((const T *)a.q, (const T *)a.k, (const T *)a.v, a.decay,
                                                              (T *)a.out, a.kv_out, (T *)a.cache, (const float *)a.scratch,
-                                                             p.H, p.ntiles, p.nseg, p.tiles_per_seg, p.cache_stride);
+                                                             p.H, p.ntiles, p.nseg, p.tiles_per_seg, p.cache_stride,
+                                                             a.rstd_out, a.eps);
         return hipSuccess;
     };
-    if (e = p.token ? launch(k_fwd<T, CT, D, true>) : launch(k_fwd<T, CT, D, false>); e != hipSuccess) return e;
+    if (e = p.token ? launch(k_fwd<T, CT, D, true>) : p.norm ? launch(k_fwd<T, CT, D, false, true>) : launch(k_fwd<T, CT, D, false>);
+        e != hipSuccess)
+        return e;
     if (ke) (void)hipEventRecord(ke->ev[3], s);
     return hipGetLastError();
 }
@@ -1884,7 +2019,9 @@ static hipError_t run_bwd(const Plan &p, const BwdArgs &a, hipStream_t s, const 
     hipError_t e;
     if (ke) (void)hipEventRecord(ke->ev[0], s);
     if (p.nseg > 1) {
-        if (e = run_local<T, CT, D, true>(p, (const T *)a.q, (const T *)a.dout, a.decay, a.scratch, a.seglog, s); e != hipSuccess)
+        if (e = run_local<T, CT, D, true>(p, (const T *)a.q, (const T *)a.dout, a.decay, a.scratch, a.seglog, (const T *)a.yn,
+                                          a.rstd, s);
+            e != hipSuccess)
             return e;
     }
     if (ke) (void)hipEventRecord(ke->ev[1], s);
@@ -1904,10 +2041,15 @@ static hipError_t run_bwd(const Plan &p, const BwdArgs &a, hipStream_t s, const 
             kb<<<dim3(p.nseg, chains), dim3(D * 4), lds_bwd8p, s>>>((const T *)a.q, (const T *)a.k, (const T *)a.v,
                                                                     (const T *)a.dout, a.decay, (const T *)a.cache, (T *)a.dq,
                                                                     (T *)a.dk, (T *)a.dv, a.dkv_in, (const float *)a.scratch,
-                                                                    a.rtok, p.H, p.ntiles, p.nseg, p.tiles_per_seg);
+                                                                    a.rtok, p.H, p.ntiles, p.nseg, p.tiles_per_seg,
+                                                                    (const T *)a.yn, a.rstd);
             return hipSuccess;
         };
-        if (e = p.token ? launch(k_bwd8p<T, CT, D, true>) : launch(k_bwd8p<T, CT, D, false>); e != hipSuccess) return e;
+        if (e = p.token  ? launch(k_bwd8p<T, CT, D, true>)
+                : p.norm ? launch(k_bwd8p<T, CT, D, false, true>)
+                         : launch(k_bwd8p<T, CT, D, false>);
+            e != hipSuccess)
+            return e;
       } else {
         constexpr size_t lds_bwd8 = Bwd8Smem<T, CT, D>::TOTAL;
         static_assert(lds_bwd8 <= 163840, "LDS budget of one gfx950 CU exceeded");
@@ -1916,10 +2058,15 @@ static hipError_t run_bwd(const Plan &p, const BwdArgs &a, hipStream_t s, const 
             kb<<<dim3(p.nseg, chains), dim3(D * 4), lds_bwd8, s>>>((const T *)a.q, (const T *)a.k, (const T *)a.v,
                                                                    (const T *)a.dout, a.decay, (const T *)a.cache, (T *)a.dq,
                                                                    (T *)a.dk, (T *)a.dv, a.dkv_in, (const float *)a.scratch,
-                                                                   a.rtok, p.H, p.ntiles, p.nseg, p.tiles_per_seg);
+                                                                   a.rtok, p.H, p.ntiles, p.nseg, p.tiles_per_seg,
+                                                                   (const T *)a.yn, a.rstd);
             return hipSuccess;
         };
-        if (e = p.token ? launch(k_bwd8<T, CT, D, true>) : launch(k_bwd8<T, CT, D, false>); e != hipSuccess) return e;
+        if (e = p.token  ? launch(k_bwd8<T, CT, D, true>)
+                : p.norm ? launch(k_bwd8<T, CT, D, false, true>)
+                         : launch(k_bwd8<T, CT, D, false>);
+            e != hipSuccess)
+            return e;
       }
     } else {
         auto launch = [&](auto kb) -> hipError_t {
@@ -1927,10 +2074,15 @@ static hipError_t run_bwd(const Plan &p, const BwdArgs &a, hipStream_t s, const 
             kb<<<dim3(p.nseg, chains), dim3(D * 2), lds_bwd, s>>>((const T *)a.q, (const T *)a.k, (const T *)a.v,
                                                                  (const T *)a.dout, a.decay, (const T *)a.cache, (T *)a.dq,
                                                                  (T *)a.dk, (T *)a.dv, a.dkv_in, (const float *)a.scratch,
-                                                                 a.rtok, p.H, p.ntiles, p.nseg, p.tiles_per_seg);
+                                                                 a.rtok, p.H, p.ntiles, p.nseg, p.tiles_per_seg,
+                                                                 (const T *)a.yn, a.rstd);
             return hipSuccess;
         };
-        if (e = p.token ? launch(k_bwd<T, CT, D, true>) : launch(k_bwd<T, CT, D, false>); e != hipSuccess) return e;
+        if (e = p.token  ? launch(k_bwd<T, CT, D, true>)
+                : p.norm ? launch(k_bwd<T, CT, D, false, true>)
+                         : launch(k_bwd<T, CT, D, false>);
+            e != hipSuccess)
+            return e;
     }
     if (ke) (void)hipEventRecord(ke->ev[3], s);
     if (p.token)

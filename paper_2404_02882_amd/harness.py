@@ -42,14 +42,16 @@ def rel_errors(x: np.ndarray, ref: np.ndarray):
 
 
 def run_gpu(inp: Inputs, T: int = 1, segments: int = 0, backward: bool = True, chunk: Optional[int] = None,
-            device="cuda") -> Dict[str, np.ndarray]:
-    """Forward (and backward) of the whole sequence as T sub-sequences; returns float64 host arrays."""
+            device="cuda", norm_eps: Optional[float] = None) -> Dict[str, np.ndarray]:
+    """Forward (and backward) of the whole sequence as T sub-sequences; returns float64 host arrays.
+    With norm_eps the output is the normalised one, `rstd` is returned too and inp.dout is the gradient
+    w.r.t. the normalised output."""
     cfg = inp.cfg
     B, H, N, D = inp.q.shape
     dt = TORCH_DTYPE[cfg.dtype]
     token = inp.log_g is not None
     seq = LaspSequence(B, H, N, D, chunk or cfg.chunk, dt, T=T, segments=segments, device=device,
-                       need_backward=backward, token_decay=token)
+                       need_backward=backward, token_decay=token, norm_eps=norm_eps)
     q, k, v = (shards(x, T, cfg.dtype, device) for x in (inp.q, inp.k, inp.v))
     if token:
         n = N // T
@@ -58,14 +60,19 @@ def run_gpu(inp: Inputs, T: int = 1, segments: int = 0, backward: bool = True, c
         decay = torch.from_numpy(inp.decay).to(device)
     kv_in = torch.from_numpy(inp.kv_in).to(device) if inp.kv_in is not None else None
     out = [torch.full_like(x, float("nan")) for x in q]
-    kv_out = seq.forward(q, k, v, decay, out, kv_in)
+    rstd = None
+    if norm_eps is not None:
+        rstd = [torch.full((B, H, N // T), float("nan"), dtype=torch.float32, device=device) for _ in range(T)]
+    kv_out = seq.forward(q, k, v, decay, out, kv_in, rstd=rstd)
     res = {"out": to_host(out), "kv_out": kv_out.cpu().numpy().astype(np.float64)}
+    if rstd is not None:
+        res["rstd"] = to_host(rstd)
     if backward:
         do = shards(inp.dout, T, cfg.dtype, device)
         g = torch.from_numpy(inp.dkv_out).to(device) if inp.dkv_out is not None else None
         dq, dk, dv = ([torch.full_like(x, float("nan")) for x in q] for _ in range(3))
         dlg = [torch.full_like(x, float("nan")) for x in decay] if token else None
-        dkv_in = seq.backward(q, k, v, do, decay, dq, dk, dv, g, dlog_g=dlg)
+        dkv_in = seq.backward(q, k, v, do, decay, dq, dk, dv, g, dlog_g=dlg, out=out, rstd=rstd)
         res.update(dq=to_host(dq), dk=to_host(dk), dv=to_host(dv), dkv_in=dkv_in.cpu().numpy().astype(np.float64))
         if token:
             res["dlog_g"] = to_host(dlg)

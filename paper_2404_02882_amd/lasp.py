@@ -67,6 +67,10 @@ def _bind(handle):
     handle.lasp_gated_fwd.restype = ctypes.c_int
     handle.lasp_gated_bwd.argtypes = [_sp] + [_vp] * 14 + [_sz, _vp]
     handle.lasp_gated_bwd.restype = ctypes.c_int
+    handle.lasp_fwd_norm.argtypes = [_sp] + [_vp] * 5 + [ctypes.c_float] + [_vp] * 5 + [_sz, _vp]
+    handle.lasp_fwd_norm.restype = ctypes.c_int
+    handle.lasp_bwd_norm.argtypes = [_sp] + [_vp] * 14 + [_sz, _vp]
+    handle.lasp_bwd_norm.restype = ctypes.c_int
     handle.lasp_profile_begin.argtypes = [ctypes.c_int32]
     handle.lasp_profile_end.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int32),
                                         ctypes.POINTER(ctypes.c_int32)]
@@ -199,6 +203,28 @@ def lasp_gated_bwd(shape: Shape, q, k, v, dout, log_g, kv_out, dkv_out, state_ca
                             _ptr(dkv_in), _ptr(scratch), nbytes, _stream(stream))
     if rc != 0:
         raise LaspError(rc, "lasp_gated_bwd")
+
+
+def lasp_fwd_norm(shape: Shape, q, k, v, kv_in, decay, eps, out, rstd, kv_out, state_cache, scratch,
+                  stream=None) -> None:
+    """Forward with the normalised output (out = Norm(o), rstd: float32 [B,H,N]); raises LaspError."""
+    nbytes = scratch.numel() * scratch.element_size() if scratch is not None else 0
+    rc = lib.lasp_fwd_norm(ctypes.byref(shape), _ptr(q), _ptr(k), _ptr(v), _ptr(kv_in), _ptr(decay), float(eps),
+                           _ptr(out), _ptr(rstd), _ptr(kv_out), _ptr(state_cache), _ptr(scratch), nbytes,
+                           _stream(stream))
+    if rc != 0:
+        raise LaspError(rc, "lasp_fwd_norm")
+
+
+def lasp_bwd_norm(shape: Shape, q, k, v, out, rstd, dout, dkv_out, decay, state_cache, dq, dk, dv, dkv_in,
+                  scratch, stream=None) -> None:
+    """Backward of lasp_fwd_norm (dout: gradient w.r.t. the normalised output); raises LaspError."""
+    nbytes = scratch.numel() * scratch.element_size() if scratch is not None else 0
+    rc = lib.lasp_bwd_norm(ctypes.byref(shape), _ptr(q), _ptr(k), _ptr(v), _ptr(out), _ptr(rstd), _ptr(dout),
+                           _ptr(dkv_out), _ptr(decay), _ptr(state_cache), _ptr(dq), _ptr(dk), _ptr(dv),
+                           _ptr(dkv_in), _ptr(scratch), nbytes, _stream(stream))
+    if rc != 0:
+        raise LaspError(rc, "lasp_bwd_norm")
 
 
 class Workspace:

@@ -19,7 +19,7 @@ from . import lasp
 
 class LaspSequence:
     def __init__(self, B, H, N, D, chunk, dtype: torch.dtype, T=1, segments=0, device="cuda", need_backward=True,
-                 token_decay=False):
+                 token_decay=False, norm_eps: Optional[float] = None):
         if N % T != 0:
             raise ValueError("N must be a multiple of T")
         self.B, self.H, self.N, self.D, self.T = B, H, N, D, T
@@ -31,6 +31,11 @@ class LaspSequence:
             raise lasp.LaspError(rc, "LaspSequence")
         # token_decay: `decay` of forward / backward is a list of T log-decay shards [B,H,N/T] (float32)
         # instead of the [H] vector of lambdas, and backward also fills dlog_g shards.
+        # norm_eps: outputs are normalised (lasp_fwd_norm / lasp_bwd_norm); forward fills `rstd` shards
+        # [B,H,N/T], backward takes them and the forward outputs. Not combined with token_decay.
+        if token_decay and norm_eps is not None:
+            raise ValueError("the normalised output is implemented for one lambda per head only")
+        self.norm_eps = norm_eps
         self.token_decay = token_decay
         scratch_bytes = lasp.gated_scratch_bytes if token_decay else lasp.scratch_bytes
         cache_bytes = lasp.gated_state_cache_bytes if token_decay else lasp.state_cache_bytes
@@ -48,13 +53,16 @@ class LaspSequence:
         return sum(c.numel() for c in self.caches if c is not None)
 
     def forward(self, q: List[torch.Tensor], k, v, decay, out: List[torch.Tensor],
-                kv_in: Optional[torch.Tensor] = None) -> torch.Tensor:
+                kv_in: Optional[torch.Tensor] = None, rstd: Optional[List[torch.Tensor]] = None) -> torch.Tensor:
         self.has_kv_in = kv_in is not None
         if kv_in is not None:
             self.kv[0].copy_(kv_in)
         for t in range(self.T):
             first = None if (t == 0 and not self.has_kv_in) else self.kv[t]
-            if self.token_decay:
+            if self.norm_eps is not None:
+                lasp.lasp_fwd_norm(self.shape, q[t], k[t], v[t], first, decay, self.norm_eps, out[t], rstd[t],
+                                   self.kv[t + 1], self.caches[t], self.scratch)
+            elif self.token_decay:
                 lasp.lasp_gated_fwd(self.shape, q[t], k[t], v[t], decay[t], first, out[t], self.kv[t + 1],
                                     self.caches[t], self.scratch)
             else:
@@ -63,13 +71,17 @@ class LaspSequence:
         return self.kv[self.T]
 
     def backward(self, q, k, v, dout, decay, dq, dk, dv, dkv_out: Optional[torch.Tensor] = None,
-                 dlog_g: Optional[List[torch.Tensor]] = None) -> torch.Tensor:
+                 dlog_g: Optional[List[torch.Tensor]] = None, out: Optional[List[torch.Tensor]] = None,
+                 rstd: Optional[List[torch.Tensor]] = None) -> torch.Tensor:
         self.has_dkv_out = dkv_out is not None
         if dkv_out is not None:
             self.dkv[self.T].copy_(dkv_out)
         for t in reversed(range(self.T)):
             last = None if (t == self.T - 1 and not self.has_dkv_out) else self.dkv[t + 1]
-            if self.token_decay:
+            if self.norm_eps is not None:
+                lasp.lasp_bwd_norm(self.shape, q[t], k[t], v[t], out[t], rstd[t], dout[t], last, decay, self.caches[t],
+                                   dq[t], dk[t], dv[t], self.dkv[t], self.scratch)
+            elif self.token_decay:
                 lasp.lasp_gated_bwd(self.shape, q[t], k[t], v[t], dout[t], decay[t], self.kv[t + 1], last,
                                     self.caches[t], dq[t], dk[t], dv[t], dlog_g[t], self.dkv[t], self.scratch)
             else:

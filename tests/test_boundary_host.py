@@ -190,3 +190,36 @@ def test_gated_bwd_rejects_before_launch(L):
     assert call(*a) == 6
     a = list(ok_args); a[12] = ctypes.c_void_p(dlg.value + 4)   # dlog_g not 16-byte aligned
     assert call(*a) == 8
+
+
+# ---------------------------------------------------------------- normalised output entry points
+def test_norm_rejects_before_launch(L):
+    s = L.make_shape(1, 1, 64, 64, 64, "bf16")
+    sb = L.scratch_bytes(s)
+    q, k, v, kvin, dec, out, rstd, kvout, cache, scr = [_fake(i) for i in range(1, 11)]
+    call = lambda *a: L.lib.lasp_fwd_norm(*a)
+    ok_args = [ctypes.byref(s), q, k, v, kvin, dec, 1e-6, out, rstd, kvout, cache, scr, sb, None]
+    for idx in (1, 2, 3, 5, 7, 8, 9):
+        a = list(ok_args)
+        a[idx] = None
+        assert call(*a) == 1, idx
+    a = list(ok_args); a[6] = -1.0
+    assert call(*a) == 2
+    a = list(ok_args); a[6] = float("nan")
+    assert call(*a) == 2
+    a = list(ok_args); a[12] = sb - 1
+    assert call(*a) == 5
+    a = list(ok_args); a[8] = out                    # rstd aliases out
+    assert call(*a) == 6
+
+    do, g, dq, dk, dv, gin = [_fake(i) for i in range(11, 17)]
+    call = lambda *a: L.lib.lasp_bwd_norm(*a)
+    ok_args = [ctypes.byref(s), q, k, v, out, rstd, do, g, dec, cache, dq, dk, dv, gin, scr, sb, None]
+    for idx in (1, 2, 3, 4, 5, 6, 8, 9, 10, 11, 12, 13):
+        a = list(ok_args)
+        a[idx] = None
+        assert call(*a) == 1, idx
+    a = list(ok_args); a[14] = None
+    assert call(*a) == 5
+    a = list(ok_args); a[10] = out                   # dq aliases the forward output
+    assert call(*a) == 6
