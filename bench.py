@@ -26,10 +26,12 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X published dense bf16 MFMA rate
 # FETCH_SIZE x 2.000, WRITE_SIZE x 1.000), for the default launch configuration. Other configs: None.
 _MIB = 2**20
 MEASURED_TRAFFIC_BYTES = {
-    "c3": {"fwd_walk": int((416.2 + 258.3) * _MIB), "bwd_walk": int((660.1 + 385.0) * _MIB),
+    "c3": {"fwd_walk": int((416.2 + 258.1) * _MIB), "bwd_walk": int((660.0 + 385.0) * _MIB),
            "fwd_local": int((248.1 + 31.0) * _MIB), "bwd_local": int((240.1 + 15.0) * _MIB)},
-    "g3": {"fwd_walk": int((418.2 + 257.5) * _MIB), "bwd_walk": int((660.1 + 387.0) * _MIB),
-           "fwd_local": int((250.0 + 31.0) * _MIB), "bwd_local": int((242.0 + 15.0) * _MIB)},
+    "g3": {"fwd_walk": int((418.2 + 257.5) * _MIB), "bwd_walk": int((659.6 + 387.0) * _MIB),
+           "fwd_local": int((250.1 + 31.0) * _MIB), "bwd_local": int((242.0 + 15.0) * _MIB)},
+    "n3": {"fwd_walk": int((416.2 + 260.6) * _MIB), "bwd_walk": int((806.6 + 386.0) * _MIB),
+           "fwd_local": int((248.1 + 31.0) * _MIB), "bwd_local": int((362.0 + 15.0) * _MIB)},
 }
 
 
@@ -38,7 +40,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--config", default="c3", help="named workload (c3 is the headline; g3 = c3 with a decay per token)")
+    ap.add_argument("--config", default="c3", help="named workload (c3 is the headline; g3 = c3 with a decay per token, n3 = c3 with the fused Norm)")
     ap.add_argument("--segments", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-tokens", type=int, default=32768)
@@ -63,7 +65,9 @@ def main():
     B, H, N, D, T = cfg.B, cfg.H, cfg.N, cfg.D, cfg.T
     dt = harness.TORCH_DTYPE[cfg.dtype]
     token = cfg.token_decay
-    seq = LaspSequence(B, H, N, D, cfg.chunk, dt, T=T, segments=args.segments, device=dev, token_decay=token)
+    norm = cfg.norm_eps is not None
+    seq = LaspSequence(B, H, N, D, cfg.chunk, dt, T=T, segments=args.segments, device=dev, token_decay=token,
+                       norm_eps=cfg.norm_eps)
     q, k, v, do = (harness.shards(x, T, cfg.dtype, dev) for x in (inp.q, inp.k, inp.v, inp.dout))
     if token:   # a decay per token: log g shards [B,H,N/T] in, dlog_g shards out
         n = N // T
@@ -73,12 +77,13 @@ def main():
         decay = torch.from_numpy(inp.decay).to(dev)
         dlg = None
     out, dq, dk, dv = ([torch.empty_like(x) for x in q] for _ in range(4))
+    rstd = [torch.empty(B, H, N // T, dtype=torch.float32, device=dev) for _ in range(T)] if norm else None
     tile = lasp.tile_tokens(seq.shape)
     nseg = lasp.num_segments(seq.shape)
 
     def step():
-        seq.forward(q, k, v, decay, out)
-        seq.backward(q, k, v, do, decay, dq, dk, dv, dlog_g=dlg)
+        seq.forward(q, k, v, decay, out, rstd=rstd)
+        seq.backward(q, k, v, do, decay, dq, dk, dv, dlog_g=dlg, out=out, rstd=rstd)
 
     for _ in range(args.warmup):
         step()
@@ -104,9 +109,12 @@ def main():
     # writes o; backward walk reads q,k,v,do and writes dq,dk,dv; local passes read two tensors.
     # With a decay per token every kernel also reads log g (4 B per token-head); dlog_g is written by a
     # separate small kernel.
+    # With the fused Norm the forward walk also writes rstd (4 B) and both backward kernels also read the
+    # normalised output and rstd (dO is rebuilt from dY on the fly).
     gb = 4 if token else 0
-    alg_bytes = {"fwd_walk": 4 * D * esz + gb, "bwd_walk": 7 * D * esz + gb, "fwd_local": 2 * D * esz + gb,
-                 "bwd_local": 2 * D * esz + gb}
+    nb = D * esz + 4 if norm else 0
+    alg_bytes = {"fwd_walk": 4 * D * esz + gb + (4 if norm else 0), "bwd_walk": 7 * D * esz + gb + nb,
+                 "fwd_local": 2 * D * esz + gb, "bwd_local": 2 * D * esz + gb + nb}
     dominant = max(("fwd_walk", "bwd_walk", "fwd_local", "bwd_local"), key=lambda n: per_launch_ms[n])
     dom_bytes = alg_bytes[dominant] * tok_heads_per_launch
     achieved = dom_bytes / (per_launch_ms[dominant] * 1e-3) / 1e9
@@ -121,7 +129,7 @@ def main():
     # configured chunk length C (intra-chunk 14*C*d, inter-chunk and state updates 12*d*d), not issued
     # flops (the kernels run shorter tiles than C and rebuild half of the cached states)
     flops_step = (14 * cfg.chunk * D + 12 * D * D) * B * H * N
-    min_bytes_step = (11 * D * esz + 3 * gb) * B * H * N
+    min_bytes_step = (11 * D * esz + 3 * gb + (D * esz + 8 if norm else 0)) * B * H * N
     step_s = ms_per_step * 1e-3
     extra = {"algorithmic_tflops": round(flops_step / step_s / 1e12, 2),
              "mfma_bf16_peak_frac": round(flops_step / step_s / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
@@ -157,7 +165,11 @@ def main():
         sl = slice(0, n_s)
         a = [np.ascontiguousarray(x[:, :, sl], dtype=np.float64) for x in (inp.q, inp.k, inp.v, inp.dout)]
         c0 = time.perf_counter()
-        if token:
+        if norm:
+            o, _ = lasp_oracle.fwd_chunked(a[0], a[1], a[2], inp.decay, cfg.chunk)
+            y, rs = lasp_oracle.norm_fwd(o, cfg.norm_eps)
+            lasp_oracle.bwd_chunked(a[0], a[1], a[2], lasp_oracle.norm_bwd(a[3], y, rs), inp.decay, cfg.chunk)
+        elif token:
             lg = np.ascontiguousarray(inp.log_g[:, :, sl], dtype=np.float64)
             lasp_oracle.gated_fwd_chunked(a[0], a[1], a[2], lg, cfg.chunk)
             lasp_oracle.gated_bwd_chunked(a[0], a[1], a[2], a[3], lg, cfg.chunk)
@@ -171,12 +183,13 @@ def main():
                          f"{B * H} heads, {c1 - c0:.1f} s"}
 
     line = {"metric": "fwd+bwd tokens/sec, chunked causal linear attention with decay (LASP per-device hot path)"
-                      + (", decay per token" if token else ""),
+                      + (", decay per token" if token else "") + (", normalised output" if norm else ""),
             "value": round(tokens_per_s, 1), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
             "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
             "scaling": "weak", "vs_baseline": None, "dtype": cfg.dtype, "data": "synthetic",
             "config": {"workload": f"{cfg.name}: B={B} H={H} N={N} d={D} chunk={cfg.chunk} {cfg.dtype}, "
-                                   f"T={T} sub-sequence(s), fwd+bwd" + (", decay per token (log_g in, dlog_g out)" if token else ""),
+                                   f"T={T} sub-sequence(s), fwd+bwd" + (", decay per token (log_g in, dlog_g out)" if token else "")
+                                   + (f", output RMS-normalised per row (eps {cfg.norm_eps})" if norm else ""),
                        "tile_tokens": tile, "segments_per_head": nseg,
                        "state_cache_bytes": seq.cache_bytes()},
             "roofline": roofline, "whole_step": extra, "copy_reference": copy, "cpu_baseline": cpu}
