@@ -42,6 +42,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--config", default="c3", help="named workload (c3 is the headline; g3 = c3 with a decay per token, n3 = c3 with the fused Norm)")
     ap.add_argument("--segments", type=int, default=0)
+    ap.add_argument("--graph", action="store_true",
+                    help="time the step as replays of one HIP graph (pays off when the T-loop is launch-bound); "
+                         "per-kernel times then come from a short eager pass before the timed region")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-tokens", type=int, default=32768)
     ap.add_argument("--copy-mib", type=int, default=1024,
@@ -88,14 +91,32 @@ def main():
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
-    lasp.profile_begin(args.steps * T)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step()
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    kernel_ms, nf, nb = lasp.profile_end()
+    if args.graph:
+        from paper_2404_02882_amd.sequence import GraphedStep
+        lasp.profile_begin(5 * T)          # per-kernel times from an eager pass: events are not captured
+        for _ in range(5):
+            step()
+        torch.cuda.synchronize()
+        kernel_ms, nf, nb = lasp.profile_end()
+        graphed = GraphedStep(seq, dict(q=q, k=k, v=v, decay=decay, out=out, rstd=rstd),
+                              dict(q=q, k=k, v=v, dout=do, decay=decay, dq=dq, dk=dk, dv=dv, dlog_g=dlg, out=out, rstd=rstd))
+        for _ in range(args.warmup):
+            graphed.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            graphed.replay()
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+    else:
+        lasp.profile_begin(args.steps * T)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            step()
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        kernel_ms, nf, nb = lasp.profile_end()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     tokens_per_s = B * N / (ms_per_step * 1e-3)
 
@@ -190,7 +211,7 @@ def main():
             "config": {"workload": f"{cfg.name}: B={B} H={H} N={N} d={D} chunk={cfg.chunk} {cfg.dtype}, "
                                    f"T={T} sub-sequence(s), fwd+bwd" + (", decay per token (log_g in, dlog_g out)" if token else "")
                                    + (f", output RMS-normalised per row (eps {cfg.norm_eps})" if norm else ""),
-                       "tile_tokens": tile, "segments_per_head": nseg,
+                       "tile_tokens": tile, "segments_per_head": nseg, "hip_graph": bool(args.graph),
                        "state_cache_bytes": seq.cache_bytes()},
             "roofline": roofline, "whole_step": extra, "copy_reference": copy, "cpu_baseline": cpu}
     print(json.dumps(line), flush=True)

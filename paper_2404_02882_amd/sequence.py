@@ -88,3 +88,38 @@ class LaspSequence:
                 lasp.lasp_bwd(self.shape, q[t], k[t], v[t], dout[t], last, decay, self.caches[t], dq[t], dk[t], dv[t],
                               self.dkv[t], self.scratch)
         return self.dkv[0]
+
+
+class GraphedStep:
+    """One forward + backward pass of a LaspSequence captured in a HIP graph and replayed.
+
+    With short sub-sequences the T-loop is launch-bound (six small kernels per call, 2T calls per
+    step); a graph replays them with one submission. The library allocates nothing and never
+    synchronises, so its calls can be captured as they are. The graph reads and writes the very
+    tensors given here: refresh their contents in place between replays. Per-kernel timing
+    (lasp_profile_begin) must be off while capturing.
+    """
+
+    def __init__(self, seq: LaspSequence, fwd_kwargs: dict, bwd_kwargs: Optional[dict] = None, warmup: int = 2):
+        self.seq = seq
+
+        def run():
+            seq.forward(**fwd_kwargs)
+            if bwd_kwargs is not None:
+                seq.backward(**bwd_kwargs)
+
+        # eager passes first, on a side stream as graph capture requires: they set the kernels'
+        # LDS attributes (a host-side call that must not fall inside the capture)
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            for _ in range(max(1, warmup)):
+                run()
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        self.graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(self.graph):
+            run()
+
+    def replay(self) -> None:
+        self.graph.replay()
