@@ -40,7 +40,7 @@ extern "C" {
 typedef enum {
     LASP_OK = 0,
     LASP_ERR_NULL = 1,      /* a required pointer is NULL */
-    LASP_ERR_SHAPE = 2,     /* B,H,N <= 0; D not 64/128; chunk not 64/128/256; N % chunk != 0; bad segments */
+    LASP_ERR_SHAPE = 2,     /* B,H,N <= 0; D not 64/128; chunk not 64/128/256; bad segments; Norm with N % tile != 0 */
     LASP_ERR_DTYPE = 3,     /* dtype is neither LASP_F32 nor LASP_BF16 */
     LASP_ERR_DECAY = 4,     /* lasp_check_decay: a value outside (0, 1] or not finite */
     LASP_ERR_WORKSPACE = 5, /* scratch missing or smaller than lasp_scratch_bytes() */
@@ -53,14 +53,19 @@ typedef enum { LASP_F32 = 0, LASP_BF16 = 1 } lasp_dtype;
 
 /*
  * Problem shape of one call.
- *   N        tokens in this sub-sequence (the paper's per-rank length N/T).
+ *   N        tokens in this sub-sequence (the paper's per-rank length N/T), any
+ *            positive number. When N is not a multiple of lasp_tile_tokens() the
+ *            last tile is short; the per-token-decay kernels handle that, so
+ *            lasp_fwd / lasp_bwd then run those with log g = log(lambda) filled in
+ *            by the library (about 10 % slower, more scratch); the fused Norm
+ *            entry points reject such N.
  *   chunk    the chunk length C of Alg. 2 / Alg. 3. The kernels walk the
  *            sub-sequence in tiles of lasp_tile_tokens() tokens; the tile
  *            divides the chunk, which is exact because the state update of
  *            Sec. 3.2 composes over consecutive tiles.
  *   segments 0 = chosen by the library. Otherwise the number of independent
  *            segments each head's sub-sequence is cut into so that B*H*segments
- *            workgroups fill the chip (1 <= segments <= N / tile).
+ *            workgroups fill the chip (1 <= segments <= ceil(N / tile)).
  */
 typedef struct {
     int32_t B, H, N, D, chunk;

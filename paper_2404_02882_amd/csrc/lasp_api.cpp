@@ -23,7 +23,6 @@ bool valid_dims(const lasp_shape *s) {
     if (s->B <= 0 || s->H <= 0 || s->N <= 0) return false;
     if (s->D != 64 && s->D != 128) return false;
     if (s->chunk != 64 && s->chunk != 128 && s->chunk != 256) return false;
-    if (s->N % s->chunk != 0) return false;
     if ((int64_t)s->B * s->H > 65535) return false;  // grid.y limit
     return true;
 }
@@ -38,7 +37,13 @@ int make_plan(const lasp_shape *s, Pass pass, lasp::Plan *p, bool token = false,
     p->D = s->D;
     p->dtype = s->dtype;
     p->tile = lasp::tile_tokens(s->dtype, s->chunk, s->D);
-    p->ntiles = s->N / p->tile;
+    p->ntiles = (s->N + p->tile - 1) / p->tile;
+    // A short last tile is handled by the per-token-decay kernels only: with one lambda per head the
+    // library synthesises log g = log(lambda) and runs those; the fused Norm has no such path.
+    const bool ragged = s->N % p->tile != 0;
+    if (ragged && norm) return LASP_ERR_SHAPE;
+    p->synth = ragged && !token;
+    if (p->synth) token = true;
     int want = s->segments;
     if (want < 0 || want > p->ntiles) return LASP_ERR_SHAPE;
     if (want == 0) {
@@ -62,12 +67,14 @@ size_t elem_bytes(int dtype) { return dtype == LASP_F32 ? 4 : 2; }
 size_t cache_bytes(const lasp_shape *shape, bool token) {
     lasp::Plan p;
     if (make_plan(shape, kForward, &p, token) != LASP_OK) return 0;
+    // (a synthesised plan has token == true and the same cache stride rule)
     return (size_t)p.B * p.H * (p.ntiles / p.cache_stride) * p.D * p.D * elem_bytes(p.dtype);
 }
 
-// Scratch layout: [segment states][per-token decay only: segment log-decays][.. : per-token r_t].
+// Scratch layout: [segment states][per-token decay only: segment log-decays][.. : per-token r_t]
+// [synthesised log g only: log g per token].
 struct ScratchLayout {
-    size_t states, seglog, rtok, total;  // byte offsets of the three regions (states = 0) and the total size
+    size_t states, seglog, rtok, logg, total;  // byte offsets of the regions (states = 0) and the total size
 };
 bool scratch_layout(const lasp_shape *shape, bool token, ScratchLayout *l) {
     lasp::Plan f, b;
@@ -76,11 +83,13 @@ bool scratch_layout(const lasp_shape *shape, bool token, ScratchLayout *l) {
     const size_t chains = (size_t)f.B * f.H;
     l->states = 0;
     l->seglog = chains * nseg * f.D * f.D * sizeof(float);
-    l->rtok = l->seglog;
+    l->rtok = l->logg = l->seglog;
     l->total = l->seglog;
-    if (token) {
+    if (f.token) {   // requested, or synthesised for a short last tile
+        const size_t per_token = ((chains * (size_t)f.N * sizeof(float) + 255) / 256) * 256;
         l->rtok = l->seglog + ((chains * nseg * sizeof(float) + 255) / 256) * 256;
-        l->total = l->rtok + chains * (size_t)f.N * sizeof(float);
+        l->logg = l->rtok + per_token;
+        l->total = l->logg + (f.synth ? per_token : 0);
     }
     return true;
 }
@@ -124,7 +133,7 @@ const char *lasp_status_str(int status) {
     switch (status) {
         case LASP_OK: return "ok";
         case LASP_ERR_NULL: return "a required pointer is NULL";
-        case LASP_ERR_SHAPE: return "unsupported shape (need B,H,N > 0, D in {64,128}, chunk in {64,128,256}, N % chunk == 0, 0 <= segments <= N/tile)";
+        case LASP_ERR_SHAPE: return "unsupported shape (need B,H,N > 0, D in {64,128}, chunk in {64,128,256}, 0 <= segments <= ceil(N/tile); with the fused Norm N % tile == 0)";
         case LASP_ERR_DTYPE: return "unsupported dtype (LASP_F32 or LASP_BF16)";
         case LASP_ERR_DECAY: return "decay must be finite and in (0, 1] (log decay: finite and <= 0)";
         case LASP_ERR_WORKSPACE: return "scratch buffer missing or too small (see lasp_scratch_bytes)";
@@ -208,6 +217,14 @@ int lasp_fwd(const lasp_shape *shape, const void *q, const void *k, const void *
             if (&o != &o2 && overlap(o, o2)) return LASP_ERR_ALIAS;
     }
     lasp::FwdArgs a{q, k, v, kv_in, decay, out, kv_out, state_cache, (float *)scratch, nullptr, nullptr, 0.0f};
+    if (p.synth) {
+        ScratchLayout l;
+        scratch_layout(shape, false, &l);
+        float *lg = (float *)((char *)scratch + l.logg);
+        if (lasp::launch_fill_logg(p, decay, lg, (hipStream_t)hip_stream) != hipSuccess) return LASP_ERR_HIP;
+        a.decay = lg;
+        a.seglog = (float *)((char *)scratch + l.seglog);
+    }
     return lasp::launch_fwd(p, a, (hipStream_t)hip_stream, next_slot(0)) == hipSuccess ? LASP_OK : LASP_ERR_HIP;
 }
 
@@ -237,6 +254,15 @@ int lasp_bwd(const lasp_shape *shape, const void *q, const void *k, const void *
     }
     lasp::BwdArgs a{q, k, v, dout, dkv_out, decay, state_cache, dq, dk, dv, dkv_in, (float *)scratch,
                     nullptr, nullptr, nullptr, nullptr, nullptr, nullptr};
+    if (p.synth) {
+        ScratchLayout l;
+        scratch_layout(shape, false, &l);
+        float *lg = (float *)((char *)scratch + l.logg);
+        if (lasp::launch_fill_logg(p, decay, lg, (hipStream_t)hip_stream) != hipSuccess) return LASP_ERR_HIP;
+        a.decay = lg;
+        a.seglog = (float *)((char *)scratch + l.seglog);
+        a.rtok = (float *)((char *)scratch + l.rtok);   // written by the kernels, not used further
+    }
     return lasp::launch_bwd(p, a, (hipStream_t)hip_stream, next_slot(1)) == hipSuccess ? LASP_OK : LASP_ERR_HIP;
 }
 

@@ -14,12 +14,13 @@ struct Plan {
     int B, H, N, D;
     int dtype;          // 0 = float, 1 = bfloat16
     int tile;           // tokens per kernel tile (CT)
-    int ntiles;         // N / tile
+    int ntiles;         // ceil(N / tile); only the last tile may be short, and only with token == true
     int nseg;           // segments per head (S)
     int tiles_per_seg;  // ceil(ntiles / nseg); the last segment may be shorter
     int cache_stride;   // the state cache holds the start state of every cache_stride-th tile (1 or 2)
     bool token;         // per-token decay: `decay` of the argument structs is log g, [B][H][N]
     bool norm;          // output rows are normalised (forward epilogue, backward prologue); token == false
+    bool synth;         // one lambda per head but N % tile != 0: log g is synthesised and the token kernels run
 };
 
 struct FwdArgs {
@@ -65,6 +66,8 @@ int tile_tokens(int dtype, int chunk, int D);
 // walk rebuilds the other) when the kernels support it, else 1.
 int cache_stride_for(int dtype, int tile, int ntiles, bool token);
 
+// log_g[b][h][s] = log(decay[h]) for all N tokens (device buffers).
+hipError_t launch_fill_logg(const Plan &p, const float *decay, float *log_g, hipStream_t stream);
 hipError_t launch_fwd(const Plan &p, const FwdArgs &a, hipStream_t stream, const KernelEvents *ke);
 hipError_t launch_bwd(const Plan &p, const BwdArgs &a, hipStream_t stream, const KernelEvents *ke);
 

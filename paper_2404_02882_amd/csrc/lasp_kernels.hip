@@ -310,6 +310,16 @@ struct TileMover {
 #pragma unroll
         for (int i = 0; i < NV; ++i) r[i] = gload<u32x4>(g + i * (NT / VPR) * COLS, lo);
     }
+    // rows >= nrows are not touched in memory and read as zero (the last tile of a sub-sequence whose
+    // length is not a multiple of the tile)
+    DEVI void load(const T *g, int nrows) {
+        if (nrows >= ROWS) return load(g);
+        const unsigned lo = lane_off(COLS) * sizeof(T);
+        const int row0 = threadIdx.x / VPR;
+#pragma unroll
+        for (int i = 0; i < NV; ++i)
+            r[i] = row0 + i * (NT / VPR) < nrows ? gload<u32x4>(g + i * (NT / VPR) * COLS, lo) : u32x4{0, 0, 0, 0};
+    }
     DEVI void store(T *s, int ld) const {
         if (sizeof(T) == 2 && ld == kSwzLd) {
             static_assert(sizeof(T) != 2 || COLS != 128 || (NT / VPR) % 16 == 0, "row step must keep row % 16");
@@ -480,12 +490,13 @@ struct TokenDecay {
     float *cum, *wu, *wa;  // LDS: cumulative log2 decay up to and including token i; 2^cum[i]; 2^(cum[CT-1]-cum[j])
     DEVI explicit TokenDecay(float *tab) : cum(tab), wu(tab + CT), wa(tab + 2 * CT) {}
     // log2 g of the tokens PER*l .. PER*l+PER-1 of the tile starting at `lg`, in lane l of wave 0 (zero elsewhere)
-    static DEVI LogG fetch(const float *lg) {
+    // tokens >= nvalid (past the end of the sub-sequence) are not read and do not decay: log g = 0
+    static DEVI LogG fetch(const float *lg, int nvalid = CT) {
         LogG v;
 #pragma unroll
         for (int e = 0; e < PER; ++e) {
             const int i = PER * threadIdx.x + e;
-            v.x[e] = (threadIdx.x < 64 && i < CT) ? lg[i] * kLog2e : 0.0f;
+            v.x[e] = (threadIdx.x < 64 && i < CT && i < nvalid) ? lg[i] * kLog2e : 0.0f;
         }
         return v;
     }
@@ -624,8 +635,9 @@ DEVI void masked_scores(const Lane &ln, T *sP, const T *sA, const T *sB, const D
 // (lane_r) = token row0 + lane_r. Each lane owns four consecutive features of
 // its token per register group, so it stores them as one 8- or 16-byte piece.
 template <typename T, int D>
-DEVI void store_out_tile_t(const Lane &ln, T *g, const f32x16 &acc, int row0, int w) {
+DEVI void store_out_tile_t(const Lane &ln, T *g, const f32x16 &acc, int row0, int w, int nrows = 1 << 30) {
     const unsigned lo = (ln.r * D + 32 * w + 4 * ln.h) * sizeof(T);
+    if (row0 + ln.r >= nrows) return;  // token past the end of the sub-sequence
 #pragma unroll
     for (int q = 0; q < 4; ++q)
         Elem<T>::gst4(g + row0 * D + 8 * q, lo, acc[4 * q], acc[4 * q + 1], acc[4 * q + 2], acc[4 * q + 3]);
@@ -692,7 +704,7 @@ template <typename T, int CT, int D, bool BWD, bool TOKEN, bool NORM = false>
 __global__ __launch_bounds__(D * 2, 2) void k_local(const T *__restrict__ X, const T *__restrict__ Y,
                                                   const float *__restrict__ decay, float *__restrict__ scratch,
                                                   float *__restrict__ seglog, int H, int ntiles, int nseg,
-                                                  int tiles_per_seg, const T *__restrict__ yn = nullptr,
+                                                  int tiles_per_seg, int ntok, const T *__restrict__ yn = nullptr,
                                                   const float *__restrict__ rstd = nullptr) {
     static_assert(!NORM || (BWD && !TOKEN), "the Norm prologue belongs to the backward pass with one lambda per head");
     using E = Elem<T>;
@@ -709,15 +721,17 @@ __global__ __launch_bounds__(D * 2, 2) void k_local(const T *__restrict__ X, con
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);  // wave index, scalar
     Lane ln = fresh_lane();
     PHASE_DECL();
-    const size_t base = (size_t)chain * ntiles * CT * D;
+    const size_t base = (size_t)chain * ntok * D;
     const int ntl = t1 - t0;
     auto tile_of = [&](int n) { return BWD ? t1 - 1 - n : t0 + n; };
     // the first tile is requested before anything else so that its latency covers the set-up
+    // rows of tile `t` that exist: the last tile of a sub-sequence may be short (per-token decay only)
+    auto nvalid = [&](int t) { return TOKEN ? min(CT, ntok - t * CT) : CT; };
     TileMover<T, CT, D, NT> mx, my;
-    mx.load(X + base + (size_t)tile_of(0) * CT * D);
-    my.load(Y + base + (size_t)tile_of(0) * CT * D);
+    mx.load(X + base + (size_t)tile_of(0) * CT * D, nvalid(tile_of(0)));
+    my.load(Y + base + (size_t)tile_of(0) * CT * D, nvalid(tile_of(0)));
     NormTile<T, CT, D, NT> mn;
-    const float *rstd_c = rstd + (size_t)chain * ntiles * CT;
+    const float *rstd_c = rstd + (size_t)chain * ntok;
     if constexpr (NORM) mn.load(yn + base + (size_t)tile_of(0) * CT * D, rstd_c + (size_t)tile_of(0) * CT);
     PHASE(22);
     f32x16 st[DB];
@@ -728,8 +742,8 @@ __global__ __launch_bounds__(D * 2, 2) void k_local(const T *__restrict__ X, con
         // `decay` is log g, [chain][token]. Per tile (state update of Alg. 2 / dKV update of Alg. 3
         // with the tile's own weights): S <- whole S + (after (.) X)^T Y forward, (upto (.) X)^T Y backward.
         const TokenDecay<T, CT> dec(pw);
-        const float *lg = decay + (size_t)chain * ntiles * CT;
-        typename TokenDecay<T, CT>::LogG lgreg = TokenDecay<T, CT>::fetch(lg + (size_t)tile_of(0) * CT);
+        const float *lg = decay + (size_t)chain * ntok;
+        typename TokenDecay<T, CT>::LogG lgreg = TokenDecay<T, CT>::fetch(lg + (size_t)tile_of(0) * CT, nvalid(tile_of(0)));
         float lgsum = 0.0f;
         for (int n = 0; n < ntl; ++n) {
             __syncthreads();
@@ -740,9 +754,10 @@ __global__ __launch_bounds__(D * 2, 2) void k_local(const T *__restrict__ X, con
             lgsum += lgreg.sum();
             __syncthreads();
             if (n + 1 < ntl) {
-                mx.load(X + base + (size_t)tile_of(n + 1) * CT * D);
-                my.load(Y + base + (size_t)tile_of(n + 1) * CT * D);
-                lgreg = TokenDecay<T, CT>::fetch(lg + (size_t)tile_of(n + 1) * CT);
+                const int tn = tile_of(n + 1);
+                mx.load(X + base + (size_t)tn * CT * D, nvalid(tn));
+                my.load(Y + base + (size_t)tn * CT * D, nvalid(tn));
+                lgreg = TokenDecay<T, CT>::fetch(lg + (size_t)tn * CT, nvalid(tn));
             }
             const float whole = dec.whole();
 #pragma unroll
@@ -903,7 +918,7 @@ __global__ __launch_bounds__(D * 2, (CT <= 64 && sizeof(T) == 2) ? 2 : 1) void k
                                                 const T *__restrict__ V, const float *__restrict__ decay,
                                                 T *__restrict__ O, float *__restrict__ kv_out,
                                                 T *__restrict__ cache, const float *__restrict__ scratch,
-                                                int H, int ntiles, int nseg, int tiles_per_seg, int cache_stride,
+                                                int H, int ntiles, int nseg, int tiles_per_seg, int cache_stride, int ntok,
                                                 float *__restrict__ rstd_out = nullptr, float eps = 0.0f) {
     using E = Elem<T>;
     constexpr int NT = D * 2, LDD = tile_ld<T, D>(), LDP = CT + E::PAD, DB = D / 32, NB = CT / 32, NKS = CT / E::KSTEP,
@@ -921,17 +936,19 @@ __global__ __launch_bounds__(D * 2, (CT <= 64 && sizeof(T) == 2) ? 2 : 1) void k
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);  // wave index, scalar
     Lane ln = fresh_lane();
     // requests first (tile, then start state), table arithmetic while they fly
-    const size_t base = (size_t)chain * ntiles * CT * D;
+    const size_t base = (size_t)chain * ntok * D;
+    // rows of tile `t` that exist: the last tile of a sub-sequence may be short (per-token decay only)
+    auto nvalid = [&](int t) { return TOKEN ? min(CT, ntok - t * CT) : CT; };
     TileMover<T, CT, D, NT> mq, mk, mv;
-    mq.load(Q + base + (size_t)t0 * CT * D);
-    mk.load(K + base + (size_t)t0 * CT * D);
-    mv.load(V + base + (size_t)t0 * CT * D);
+    mq.load(Q + base + (size_t)t0 * CT * D, nvalid(t0));
+    mk.load(K + base + (size_t)t0 * CT * D, nvalid(t0));
+    mv.load(V + base + (size_t)t0 * CT * D, nvalid(t0));
     f32x16 st[DB];
     state_load<D>(ln, st, scratch + ((size_t)chain * nseg + seg) * D * D, w);
     const auto dec = DecaySel<TOKEN, T, CT>::make(pw, decay, chain, H);
-    const float *lg = decay + (size_t)chain * ntiles * CT;  // per-token decay: `decay` is log g, [chain][token]
+    const float *lg = decay + (size_t)chain * ntok;  // per-token decay: `decay` is log g, [chain][token]
     typename TokenDecay<T, CT>::LogG lgreg = {};
-    if constexpr (TOKEN) lgreg = TokenDecay<T, CT>::fetch(lg + (size_t)t0 * CT);
+    if constexpr (TOKEN) lgreg = TokenDecay<T, CT>::fetch(lg + (size_t)t0 * CT, nvalid(t0));
 
     for (int t = t0; t < t1; ++t) {
         __syncthreads();
@@ -945,10 +962,10 @@ __global__ __launch_bounds__(D * 2, (CT <= 64 && sizeof(T) == 2) ? 2 : 1) void k
         if constexpr (TOKEN) dec.fill(lgreg);
         __syncthreads();
         if (t + 1 < t1) {
-            mq.load(Q + base + (size_t)(t + 1) * CT * D);
-            mk.load(K + base + (size_t)(t + 1) * CT * D);
-            mv.load(V + base + (size_t)(t + 1) * CT * D);
-            if constexpr (TOKEN) lgreg = TokenDecay<T, CT>::fetch(lg + (size_t)(t + 1) * CT);
+            mq.load(Q + base + (size_t)(t + 1) * CT * D, nvalid(t + 1));
+            mk.load(K + base + (size_t)(t + 1) * CT * D, nvalid(t + 1));
+            mv.load(V + base + (size_t)(t + 1) * CT * D, nvalid(t + 1));
+            if constexpr (TOKEN) lgreg = TokenDecay<T, CT>::fetch(lg + (size_t)(t + 1) * CT, nvalid(t + 1));
         }
         // masked scores P (all waves share the lower-triangular blocks)
         masked_scores<T, CT, D, LDD, LDP>(ln, sP, sK, sQ, dec, w);
@@ -1000,12 +1017,12 @@ __global__ __launch_bounds__(D * 2, (CT <= 64 && sizeof(T) == 2) ? 2 : 1) void k
                 for (int wv = 0; wv < D / 32; ++wv) tot += red[wv * CT + 32 * ib + ln.r];
                 const float rs = rsqrtf(tot * (1.0f / D) + eps);
                 acc[ib] *= rs;
-                if (w == 0 && ln.h == 0) rstd_out[((size_t)chain * ntiles + t) * CT + 32 * ib + ln.r] = rs;
+                if (w == 0 && ln.h == 0) rstd_out[(size_t)chain * ntok + (size_t)t * CT + 32 * ib + ln.r] = rs;
             }
         }
         T *o = O + base + (size_t)t * CT * D;
 #pragma unroll
-        for (int ib = 0; ib < NB; ++ib) store_out_tile_t<T, D>(ln, o, acc[ib], 32 * ib, w);
+        for (int ib = 0; ib < NB; ++ib) store_out_tile_t<T, D>(ln, o, acc[ib], 32 * ib, w, nvalid(t));
 
         ln = fresh_lane();
         // state update: KV <- lambda^CT KV + (diag{lambda^(CT-1-j)} K)^T V, weight applied to the V fragments
@@ -1056,7 +1073,7 @@ __global__ __launch_bounds__(D * 2, (CT <= 64 && sizeof(T) == 2) ? 2 : 1) void k
                                                 T *__restrict__ dQ, T *__restrict__ dK, T *__restrict__ dV,
                                                 float *__restrict__ dkv_in, const float *__restrict__ scratch,
                                                 float *__restrict__ rtok,
-                                                int H, int ntiles, int nseg, int tiles_per_seg,
+                                                int H, int ntiles, int nseg, int tiles_per_seg, int ntok,
                                                 const T *__restrict__ yn = nullptr, const float *__restrict__ rstd = nullptr) {
     using E = Elem<T>;
     using SM = BwdSmem<T, CT, D>;
@@ -1076,9 +1093,11 @@ __global__ __launch_bounds__(D * 2, (CT <= 64 && sizeof(T) == 2) ? 2 : 1) void k
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);  // wave index, scalar
     Lane ln = fresh_lane();
     const auto dec = DecaySel<TOKEN, T, CT>::make(pw, decay, chain, H);
-    const float *lg = decay + (size_t)chain * ntiles * CT;  // per-token decay: `decay` is log g, [chain][token]
+    const float *lg = decay + (size_t)chain * ntok;  // per-token decay: `decay` is log g, [chain][token]
     typename TokenDecay<T, CT>::LogG lgreg = {};
-    if constexpr (TOKEN) lgreg = TokenDecay<T, CT>::fetch(lg + (size_t)(t1 - 1) * CT);
+    // rows of tile `t` that exist: the last tile of a sub-sequence may be short (per-token decay only)
+    auto nvalid = [&](int t) { return TOKEN ? min(CT, ntok - t * CT) : CT; };
+    if constexpr (TOKEN) lgreg = TokenDecay<T, CT>::fetch(lg + (size_t)(t1 - 1) * CT, nvalid(t1 - 1));
     // per-token decay: r_t = q_t.dq_t - k_t.dk_t, one partial row per wave, summed and written per tile
     float *rs = pw + 3 * CT + 4;
     auto flush_r = [&](int tile) {
@@ -1086,19 +1105,19 @@ __global__ __launch_bounds__(D * 2, (CT <= 64 && sizeof(T) == 2) ? 2 : 1) void k
             float r = 0.0f;
 #pragma unroll
             for (int wv = 0; wv < D / 32; ++wv) r += rs[wv * CT + threadIdx.x];
-            rtok[((size_t)chain * ntiles + tile) * CT + threadIdx.x] = r;
+            if (tile * CT + (int)threadIdx.x < ntok) rtok[(size_t)chain * ntok + (size_t)tile * CT + threadIdx.x] = r;
         }
     };
 
-    const size_t base = (size_t)chain * ntiles * CT * D;
+    const size_t base = (size_t)chain * ntok * D;
     f32x16 dkv[DB];
     state_load<D>(ln, dkv, scratch + ((size_t)chain * nseg + seg) * D * D, w);
 
     TileMover<T, CT, D, NT> ma, mb;
-    ma.load(V + base + (size_t)(t1 - 1) * CT * D);
-    mb.load(dO + base + (size_t)(t1 - 1) * CT * D);
+    ma.load(V + base + (size_t)(t1 - 1) * CT * D, nvalid(t1 - 1));
+    mb.load(dO + base + (size_t)(t1 - 1) * CT * D, nvalid(t1 - 1));
     NormTile<T, CT, D, NT> mn;
-    const float *rstd_c = rstd + (size_t)chain * ntiles * CT;
+    const float *rstd_c = rstd + (size_t)chain * ntok;
     if constexpr (NORM) mn.load(yn + base + (size_t)(t1 - 1) * CT * D, rstd_c + (size_t)(t1 - 1) * CT);
 
     for (int t = t1 - 1; t >= t0; --t) {
@@ -1127,10 +1146,10 @@ __global__ __launch_bounds__(D * 2, (CT <= 64 && sizeof(T) == 2) ? 2 : 1) void k
         mb.store(bufB, LDD);
         if constexpr (TOKEN) dec.fill(lgreg);
         __syncthreads();
-        ma.load(K + off);
-        mb.load(Q + off);
+        ma.load(K + off, nvalid(t));
+        mb.load(Q + off, nvalid(t));
         if constexpr (TOKEN) {
-            if (t > t0) lgreg = TokenDecay<T, CT>::fetch(lg + (size_t)(t - 1) * CT);
+            if (t > t0) lgreg = TokenDecay<T, CT>::fetch(lg + (size_t)(t - 1) * CT);   // only the last tile can be short
         }
 
         masked_scores<T, CT, D, LDD, LDP>(ln, sDS, bufA, bufB, dec, w);  // dS^T = V dO^T
@@ -1185,7 +1204,7 @@ __global__ __launch_bounds__(D * 2, (CT <= 64 && sizeof(T) == 2) ? 2 : 1) void k
             for (int ib = ks / SPB; ib < NB; ++ib) accQ[ib] = E::mfma(kf, E::ld_kc(ln, sDS, LDP, 32 * ib, ks * E::KSTEP), accQ[ib]);
         }
 #pragma unroll
-        for (int ib = 0; ib < NB; ++ib) store_out_tile_t<T, D>(ln, dQ + off, accQ[ib], 32 * ib, w);
+        for (int ib = 0; ib < NB; ++ib) store_out_tile_t<T, D>(ln, dQ + off, accQ[ib], 32 * ib, w, nvalid(t));
         float rpart[NB];
         if constexpr (TOKEN) {
 #pragma unroll
@@ -1199,7 +1218,7 @@ __global__ __launch_bounds__(D * 2, (CT <= 64 && sizeof(T) == 2) ? 2 : 1) void k
             for (int jb = 0; jb <= ks / SPB; ++jb) accK[jb] = E::mfma(qf, E::ld_ks(ln, sDS, LDP, ks * E::KSTEP, 32 * jb), accK[jb]);
         }
 #pragma unroll
-        for (int jb = 0; jb < NB; ++jb) store_out_tile_t<T, D>(ln, dK + off, accK[jb], 32 * jb, w);
+        for (int jb = 0; jb < NB; ++jb) store_out_tile_t<T, D>(ln, dK + off, accK[jb], 32 * jb, w, nvalid(t));
         if constexpr (TOKEN) {
 #pragma unroll
             for (int jb = 0; jb < NB; ++jb) {
@@ -1228,7 +1247,7 @@ __global__ __launch_bounds__(D * 2, (CT <= 64 && sizeof(T) == 2) ? 2 : 1) void k
                 for (int jb = 0; jb <= ks / SPB; ++jb)
                     accV[jb] = E::mfma(dof[ks], E::ld_ks(ln, sS, LDP, ks * E::KSTEP, 32 * jb), accV[jb]);
 #pragma unroll
-            for (int jb = 0; jb < NB; ++jb) store_out_tile_t<T, D>(ln, dV + off, accV[jb], 32 * jb, w);
+            for (int jb = 0; jb < NB; ++jb) store_out_tile_t<T, D>(ln, dV + off, accV[jb], 32 * jb, w, nvalid(t));
         }
         // dKV <- lambda^CT dKV + (Lambda Q)^T dO  (row weight lambda^(i+1) applied to the dO fragments)
         const float lamC = dec.whole();
@@ -1279,7 +1298,7 @@ __global__ __launch_bounds__(D * 4) void k_bwd8(const T *__restrict__ Q, const T
                                                  T *__restrict__ dQ, T *__restrict__ dK, T *__restrict__ dV,
                                                  float *__restrict__ dkv_in, const float *__restrict__ scratch,
                                                  float *__restrict__ rtok,
-                                                 int H, int ntiles, int nseg, int tiles_per_seg,
+                                                 int H, int ntiles, int nseg, int tiles_per_seg, int ntok,
                                                  const T *__restrict__ yn = nullptr, const float *__restrict__ rstd = nullptr) {
     using E = Elem<T>;
     using F = typename E::frag;
@@ -1307,25 +1326,26 @@ __global__ __launch_bounds__(D * 4) void k_bwd8(const T *__restrict__ Q, const T
     PHASE_DECL();
 
     // requests first (last tile of the segment, its cached state), set-up arithmetic while they fly
-    const size_t base = (size_t)chain * ntiles * CT * D;
+    const size_t base = (size_t)chain * ntok * D;
     TileMover<T, CT, D, NT> mv, mo, mk, mq;
     TileMover<T, D, D, NT> mc;  // cached state tile KV_{t-1}, [a][c]
     const T *ctile = cache + (size_t)chain * ntiles * D * D;
     {
         const size_t off = base + (size_t)(t1 - 1) * CT * D;
-        mv.load(V + off);
-        mo.load(dO + off);
-        mk.load(K + off);
-        mq.load(Q + off);
+        const int nv = TOKEN ? min(CT, ntok - (t1 - 1) * CT) : CT;  // the last tile of a sub-sequence may be short
+        mv.load(V + off, nv);
+        mo.load(dO + off, nv);
+        mk.load(K + off, nv);
+        mq.load(Q + off, nv);
         mc.load(ctile + (size_t)(t1 - 1) * D * D);
     }
     NormTile<T, CT, D, NT> mn;  // NORM: dO is dY; turned into dO from the normalised output and rstd on its way to LDS
-    const float *rstd_c = rstd + (size_t)chain * ntiles * CT;
+    const float *rstd_c = rstd + (size_t)chain * ntok;
     if constexpr (NORM) mn.load(yn + base + (size_t)(t1 - 1) * CT * D, rstd_c + (size_t)(t1 - 1) * CT);
     const auto dec = DecaySel<TOKEN, T, CT>::make(pw, decay, chain, H);
-    const float *lg = decay + (size_t)chain * ntiles * CT;  // per-token decay: `decay` is log g, [chain][token]
+    const float *lg = decay + (size_t)chain * ntok;  // per-token decay: `decay` is log g, [chain][token]
     typename TokenDecay<T, CT>::LogG lgreg = {};
-    if constexpr (TOKEN) lgreg = TokenDecay<T, CT>::fetch(lg + (size_t)(t1 - 1) * CT);
+    if constexpr (TOKEN) lgreg = TokenDecay<T, CT>::fetch(lg + (size_t)(t1 - 1) * CT, min(CT, ntok - (t1 - 1) * CT));
     // per-token decay: r_t = q_t.dq_t - k_t.dk_t, one partial row per wave, summed and written per tile
     float *rs = pw + 3 * CT + 4;
     auto flush_r = [&](int tile) {
@@ -1333,7 +1353,7 @@ __global__ __launch_bounds__(D * 4) void k_bwd8(const T *__restrict__ Q, const T
             float r = 0.0f;
 #pragma unroll
             for (int wv = 0; wv < 2 * NW; ++wv) r += rs[wv * CT + threadIdx.x];
-            rtok[((size_t)chain * ntiles + tile) * CT + threadIdx.x] = r;
+            if (tile * CT + (int)threadIdx.x < ntok) rtok[(size_t)chain * ntok + (size_t)tile * CT + threadIdx.x] = r;
         }
     };
 
@@ -1365,6 +1385,7 @@ __global__ __launch_bounds__(D * 4) void k_bwd8(const T *__restrict__ Q, const T
 
     for (int t = t1 - 1; t >= t0; --t) {
         const size_t off = base + (size_t)t * CT * D;
+        const int nrows = TOKEN ? min(CT, ntok - t * CT) : CT;  // rows of this tile that exist
         __syncthreads();  // previous tile fully consumed
         ln = fresh_lane();
         PHASE(0);
@@ -1434,7 +1455,7 @@ __global__ __launch_bounds__(D * 4) void k_bwd8(const T *__restrict__ Q, const T
             auto fma = [&](int, const FragPair<F> &f) { acc = E::mfma(f.a, f.b, acc); };
             if (rg == 0) pipelined<SPB>(intra, fma);        // keys of block 0
             else pipelined<2 * SPB>(intra, fma);            // keys of blocks 0 and 1
-            store_out_tile_t<T, D>(ln, dQ + off, acc, r0, w);
+            store_out_tile_t<T, D>(ln, dQ + off, acc, r0, w, nrows);
             if constexpr (TOKEN) rq = rowdot<T>(ln, acc, sQ, LDD, r0, w);
         }
         PHASE(3);
@@ -1476,7 +1497,7 @@ __global__ __launch_bounds__(D * 4) void k_bwd8(const T *__restrict__ Q, const T
                         if (jb <= ks / SPB) acc[jb] = E::mfma(f.a, f.b[jb], acc[jb]);
                 });
 #pragma unroll
-            for (int jb = 0; jb < NB; ++jb) store_out_tile_t<T, D>(ln, gOut + off, acc[jb], 32 * jb, w);
+            for (int jb = 0; jb < NB; ++jb) store_out_tile_t<T, D>(ln, gOut + off, acc[jb], 32 * jb, w, nrows);
             if constexpr (TOKEN) {
 #pragma unroll
                 for (int jb = 0; jb < NB; ++jb) {
@@ -1550,7 +1571,7 @@ __global__ __launch_bounds__(D * 4) void k_bwd8p(const T *__restrict__ Q, const 
                                                   T *__restrict__ dQ, T *__restrict__ dK, T *__restrict__ dV,
                                                   float *__restrict__ dkv_in, const float *__restrict__ scratch,
                                                   float *__restrict__ rtok,
-                                                  int H, int ntiles, int nseg, int tiles_per_seg,
+                                                  int H, int ntiles, int nseg, int tiles_per_seg, int ntok,
                                                   const T *__restrict__ yn = nullptr, const float *__restrict__ rstd = nullptr) {
     using E = Elem<T>;
     using F = typename E::frag;
@@ -1579,7 +1600,7 @@ __global__ __launch_bounds__(D * 4) void k_bwd8p(const T *__restrict__ Q, const 
     Lane ln = fresh_lane();
     PHASE_DECL();
 
-    const size_t base = (size_t)chain * ntiles * CT * D;
+    const size_t base = (size_t)chain * ntok * D;
     const size_t TS = (size_t)CT * D;  // elements per tile
     TileMover<T, CT, D, NT> mvO, moX, mkO, mqX, mvE, mkE;   // moX / mqX carry dO, Q of the O tile, then of the E tile
     TileMover<T, D, D, NT> mc;                               // cached state at the start of the E tile
@@ -1591,7 +1612,7 @@ __global__ __launch_bounds__(D * 4) void k_bwd8p(const T *__restrict__ Q, const 
         if constexpr (TOKEN) return TokenDecay<T, CT>(pw + 3 * CT);
         else return decO;
     }();
-    const float *lg = decay + (size_t)chain * ntiles * CT;
+    const float *lg = decay + (size_t)chain * ntok;
     typename TokenDecay<T, CT>::LogG lgO = {}, lgE = {};
     // per-token decay: r_t = q_t.dq_t - k_t.dk_t, one partial row per wave, summed and written per tile
     float *rs = pw + 6 * CT + 4;
@@ -1600,22 +1621,24 @@ __global__ __launch_bounds__(D * 4) void k_bwd8p(const T *__restrict__ Q, const 
             float r = 0.0f;
 #pragma unroll
             for (int wv = 0; wv < 2 * NW; ++wv) r += rs[wv * CT + threadIdx.x];
-            rtok[((size_t)chain * ntiles + tile) * CT + threadIdx.x] = r;
+            if (tile * CT + (int)threadIdx.x < ntok) rtok[(size_t)chain * ntok + (size_t)tile * CT + threadIdx.x] = r;
         }
     };
     NormTile<T, CT, D, NT> mnX;  // NORM: partner of moX (dO is dY; see NormTile)
-    const float *rstd_c = rstd + (size_t)chain * ntiles * CT;
+    const float *rstd_c = rstd + (size_t)chain * ntok;
     auto load_pair = [&](int tE) {
         const size_t oE = base + (size_t)tE * TS, oO = oE + TS;
         if constexpr (NORM) mnX.load(yn + oO, rstd_c + (size_t)(tE + 1) * CT);
+        // only the O tile of the last pair can be short (per-token decay only)
+        const int nvO = TOKEN ? min(CT, ntok - (tE + 1) * CT) : CT;
         if constexpr (TOKEN) {
-            lgO = TokenDecay<T, CT>::fetch(lg + (size_t)(tE + 1) * CT);
+            lgO = TokenDecay<T, CT>::fetch(lg + (size_t)(tE + 1) * CT, nvO);
             lgE = TokenDecay<T, CT>::fetch(lg + (size_t)tE * CT);
         }
-        mvO.load(V + oO);
-        moX.load(dO + oO);
-        mkO.load(K + oO);
-        mqX.load(Q + oO);
+        mvO.load(V + oO, nvO);
+        moX.load(dO + oO, nvO);
+        mkO.load(K + oO, nvO);
+        mqX.load(Q + oO, nvO);
         mvE.load(V + oE);
         mkE.load(K + oE);
         mc.load(ctile + (size_t)(tE / 2) * D * D);
@@ -1674,7 +1697,7 @@ __global__ __launch_bounds__(D * 4) void k_bwd8p(const T *__restrict__ Q, const 
     };
 
     // dQ, this group's dV or dK, and the dKV update for the tile at element offset `off`
-    auto products = [&](const auto &dec, const T *pV, const T *pK, size_t off) {
+    auto products = [&](const auto &dec, const T *pV, const T *pK, size_t off, int nrows) {
         const T *sX1 = rg ? pV : pK;  // inter operand: token rows, features contracted with the state
         float rq = 0.0f;  // per-token decay: q_i . dq_i over this wave's features, tokens i of block rg
         {   // dQ^T[a in w][i], tokens i of block rg
@@ -1688,7 +1711,7 @@ __global__ __launch_bounds__(D * 4) void k_bwd8p(const T *__restrict__ Q, const 
             auto fma = [&](int, const FragPair<F> &f) { acc = E::mfma(f.a, f.b, acc); };
             if (rg == 0) pipelined<SPB>(intra, fma);
             else pipelined<2 * SPB>(intra, fma);
-            store_out_tile_t<T, D>(ln, dQ + off, acc, r0, w);
+            store_out_tile_t<T, D>(ln, dQ + off, acc, r0, w, nrows);
             if constexpr (TOKEN) rq = rowdot<T>(ln, acc, sQ, LDD, r0, w);
         }
         ln = fresh_lane();
@@ -1727,7 +1750,7 @@ __global__ __launch_bounds__(D * 4) void k_bwd8p(const T *__restrict__ Q, const 
                         if (jb <= ks / SPB) acc[jb] = E::mfma(f.a, f.b[jb], acc[jb]);
                 });
 #pragma unroll
-            for (int jb = 0; jb < NB; ++jb) store_out_tile_t<T, D>(ln, gOut + off, acc[jb], 32 * jb, w);
+            for (int jb = 0; jb < NB; ++jb) store_out_tile_t<T, D>(ln, gOut + off, acc[jb], 32 * jb, w, nrows);
             if constexpr (TOKEN) {
 #pragma unroll
                 for (int jb = 0; jb < NB; ++jb) {
@@ -1816,7 +1839,7 @@ __global__ __launch_bounds__(D * 4) void k_bwd8p(const T *__restrict__ Q, const 
         __syncthreads();
         ln = fresh_lane();
         PHASE(5);
-        products(decO, sVO, sKO, offO);
+        products(decO, sVO, sKO, offO, TOKEN ? min(CT, ntok - (tE + 1) * CT) : CT);
         PHASE(6);
         __syncthreads();  // O tile consumed: sdO, sQ, sC are free
         ln = fresh_lane();
@@ -1837,7 +1860,7 @@ __global__ __launch_bounds__(D * 4) void k_bwd8p(const T *__restrict__ Q, const 
         __syncthreads();
         ln = fresh_lane();
         PHASE(11);
-        products(decE, sVE, sKE, offE);
+        products(decE, sVE, sKE, offE, CT);
         PHASE(12);
     }
     PHASE_FLUSH();
@@ -1885,15 +1908,13 @@ __global__ __launch_bounds__(256) void k_dlg(const float *__restrict__ rtok, con
             behind += (double)x[0] * y[0] + (double)x[1] * y[1] + (double)x[2] * y[2] + (double)x[3] * y[3];
         }
     }
-    for (int s = s0 + kDlgBlock + 4 * tid; s < N; s += kDlgBlock) {  // N % 4 == 0
-        const f32x4 x = *(const f32x4 *)(r + s);
-        behind += ((double)x[0] + x[1]) + ((double)x[2] + x[3]);
-    }
+    for (int s = s0 + kDlgBlock + tid; s < N; s += 256) behind += (double)r[s];
     behind = block_sum(behind, sh);
     // this thread's four tokens, suffix sums inside the group
     const int s = s0 + 4 * tid;
-    f32x4 x = {0, 0, 0, 0};
-    if (s < N) x = *(const f32x4 *)(r + s);
+    float x[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) x[e] = s + e < N ? r[s + e] : 0.0f;
     double v3 = x[3], v2 = v3 + x[2], v1 = v2 + x[1], v0 = v1 + x[0];
     // exclusive suffix sum of the group totals over the threads behind this one
     double incl = v0;
@@ -1907,7 +1928,11 @@ __global__ __launch_bounds__(256) void k_dlg(const float *__restrict__ rtok, con
     __syncthreads();
     double after = behind + (incl - v0);
     for (int wv = (tid >> 6) + 1; wv < 4; ++wv) after += sh[wv];
-    if (s < N) *(f32x4 *)(dlg + (size_t)chain * N + s) = f32x4{(float)(after + v0), (float)(after + v1), (float)(after + v2), (float)(after + v3)};
+    const double v[4] = {v0, v1, v2, v3};
+    float *o = dlg + (size_t)chain * N;
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+        if (s + e < N) o[s + e] = (float)(after + v[e]);
 }
 
 // ---------------------------------------------------------------------------
@@ -1950,7 +1975,7 @@ static hipError_t run_local(const Plan &p, const T *x, const T *y, const float *
             auto kl = k_local<T, CT, D, true, false, true>;
             if (hipError_t e2 = allow_lds(kl, lds); e2 != hipSuccess) return e2;
             kl<<<dim3(p.nseg - 1, chains), dim3(D * 2), lds, s>>>(x, y, decay, scratch, seglog, p.H, p.ntiles, p.nseg,
-                                                                p.tiles_per_seg, yn, rstd);
+                                                                p.tiles_per_seg, p.N, yn, rstd);
             return hipSuccess;
         }
     }
@@ -1960,7 +1985,7 @@ static hipError_t run_local(const Plan &p, const T *x, const T *y, const float *
             auto launch = [&](auto kl) -> hipError_t {
                 if (hipError_t e2 = allow_lds(kl, lds); e2 != hipSuccess) return e2;
                 kl<<<dim3(p.nseg - 1, chains), dim3(D * 2), lds, s>>>(x, y, decay, scratch, seglog, p.H, p.ntiles / 2, p.nseg,
-                                                                    p.tiles_per_seg / 2, nullptr, nullptr);
+                                                                    p.tiles_per_seg / 2, p.N, nullptr, nullptr);
                 return hipSuccess;
             };
             return p.token ? launch(k_local<T, 128, D, BWD, true>) : launch(k_local<T, 128, D, BWD, false>);
@@ -1970,7 +1995,7 @@ static hipError_t run_local(const Plan &p, const T *x, const T *y, const float *
     auto launch = [&](auto kl) -> hipError_t {
         if (hipError_t e2 = allow_lds(kl, lds); e2 != hipSuccess) return e2;
         kl<<<dim3(p.nseg - 1, chains), dim3(D * 2), lds, s>>>(x, y, decay, scratch, seglog, p.H, p.ntiles, p.nseg,
-                                                            p.tiles_per_seg, nullptr, nullptr);
+                                                            p.tiles_per_seg, p.N, nullptr, nullptr);
         return hipSuccess;
     };
     return p.token ? launch(k_local<T, CT, D, BWD, true>) : launch(k_local<T, CT, D, BWD, false>);
@@ -2000,7 +2025,7 @@ static hipError_t run_fwd(const Plan &p, const FwdArgs &a, hipStream_t s, const 
         if (hipError_t e2 = allow_lds(kf, lds_fwd); e2 != hipSuccess) return e2;
         kf<<<dim3(p.nseg, chains), dim3(D * 2), lds_fwd, s>>>((const T *)a.q, (const T *)a.k, (const T *)a.v, a.decay,
                                                              (T *)a.out, a.kv_out, (T *)a.cache, (const float *)a.scratch,
-                                                             p.H, p.ntiles, p.nseg, p.tiles_per_seg, p.cache_stride,
+                                                             p.H, p.ntiles, p.nseg, p.tiles_per_seg, p.cache_stride, p.N,
                                                              a.rstd_out, a.eps);
         return hipSuccess;
     };
@@ -2041,7 +2066,7 @@ static hipError_t run_bwd(const Plan &p, const BwdArgs &a, hipStream_t s, const 
             kb<<<dim3(p.nseg, chains), dim3(D * 4), lds_bwd8p, s>>>((const T *)a.q, (const T *)a.k, (const T *)a.v,
                                                                     (const T *)a.dout, a.decay, (const T *)a.cache, (T *)a.dq,
                                                                     (T *)a.dk, (T *)a.dv, a.dkv_in, (const float *)a.scratch,
-                                                                    a.rtok, p.H, p.ntiles, p.nseg, p.tiles_per_seg,
+                                                                    a.rtok, p.H, p.ntiles, p.nseg, p.tiles_per_seg, p.N,
                                                                     (const T *)a.yn, a.rstd);
             return hipSuccess;
         };
@@ -2058,7 +2083,7 @@ static hipError_t run_bwd(const Plan &p, const BwdArgs &a, hipStream_t s, const 
             kb<<<dim3(p.nseg, chains), dim3(D * 4), lds_bwd8, s>>>((const T *)a.q, (const T *)a.k, (const T *)a.v,
                                                                    (const T *)a.dout, a.decay, (const T *)a.cache, (T *)a.dq,
                                                                    (T *)a.dk, (T *)a.dv, a.dkv_in, (const float *)a.scratch,
-                                                                   a.rtok, p.H, p.ntiles, p.nseg, p.tiles_per_seg,
+                                                                   a.rtok, p.H, p.ntiles, p.nseg, p.tiles_per_seg, p.N,
                                                                    (const T *)a.yn, a.rstd);
             return hipSuccess;
         };
@@ -2074,7 +2099,7 @@ static hipError_t run_bwd(const Plan &p, const BwdArgs &a, hipStream_t s, const 
             kb<<<dim3(p.nseg, chains), dim3(D * 2), lds_bwd, s>>>((const T *)a.q, (const T *)a.k, (const T *)a.v,
                                                                  (const T *)a.dout, a.decay, (const T *)a.cache, (T *)a.dq,
                                                                  (T *)a.dk, (T *)a.dv, a.dkv_in, (const float *)a.scratch,
-                                                                 a.rtok, p.H, p.ntiles, p.nseg, p.tiles_per_seg,
+                                                                 a.rtok, p.H, p.ntiles, p.nseg, p.tiles_per_seg, p.N,
                                                                  (const T *)a.yn, a.rstd);
             return hipSuccess;
         };
@@ -2085,9 +2110,21 @@ static hipError_t run_bwd(const Plan &p, const BwdArgs &a, hipStream_t s, const 
             return e;
     }
     if (ke) (void)hipEventRecord(ke->ev[3], s);
-    if (p.token)
+    if (p.token && a.dlog_g)
         k_dlg<<<dim3((p.N + kDlgBlock - 1) / kDlgBlock, chains), dim3(256), 0, s>>>(a.rtok, a.kv_out, a.dkv_out, a.dlog_g,
                                                                                       p.N, DD);
+    return hipGetLastError();
+}
+
+// log g = log(lambda_h) for every token of head h: lets a sub-sequence whose length is not a multiple of
+// the tile run through the per-token-decay kernels (which handle a short last tile) with one lambda per head.
+__global__ __launch_bounds__(256) void k_fill_logg(const float *__restrict__ decay, float *__restrict__ log_g, int H, int N) {
+    const int chain = blockIdx.y;
+    const float x = (float)log((double)decay[chain % H]);
+    for (int s = blockIdx.x * 256 + threadIdx.x; s < N; s += gridDim.x * 256) log_g[(size_t)chain * N + s] = x;
+}
+hipError_t launch_fill_logg(const Plan &p, const float *decay, float *log_g, hipStream_t stream) {
+    k_fill_logg<<<dim3((p.N + 255) / 256 < 64 ? (p.N + 255) / 256 : 64, p.B * p.H), dim3(256), 0, stream>>>(decay, log_g, p.H, p.N);
     return hipGetLastError();
 }
 

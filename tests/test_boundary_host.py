@@ -35,7 +35,7 @@ def test_status_strings(L):
 @pytest.mark.parametrize("kw,expect", [
     (dict(), 0),
     (dict(D=96), 2), (dict(D=256), 2), (dict(chunk=32), 2), (dict(chunk=512), 2),
-    (dict(N=1000), 2), (dict(N=0), 2), (dict(B=0), 2), (dict(H=-1), 2),
+    (dict(N=1000), 0), (dict(N=1), 0), (dict(N=0), 2), (dict(B=0), 2), (dict(H=-1), 2),
     (dict(dtype=2), 3), (dict(dtype=-1), 3),
     (dict(segments=-1), 2), (dict(segments="tiles+1"), 2), (dict(segments="tiles"), 0),
 ])
@@ -64,8 +64,14 @@ def test_sizes_and_plan(L):
     # a segment count that does not divide the tiles still covers them all
     r = L.make_shape(1, 1, 64 * 7, 64, 64, "bf16", segments=3)
     assert 1 <= L.num_segments(r) <= 3
-    bad = L.make_shape(1, 1, 100, 64, 64, "bf16")
+    bad = L.make_shape(1, 1, 128, 96, 64, "bf16")
     assert L.tile_tokens(bad) == 0 and L.scratch_bytes(bad) == 0 and L.state_cache_bytes(bad) == 0
+    # a length that is not a multiple of the tile: one more (short) tile, and scratch for the synthesised log g
+    rag = L.make_shape(1, 2, 64 * 3 + 5, 64, 64, "bf16")
+    full = L.make_shape(1, 2, 64 * 4, 64, 64, "bf16")
+    assert L.state_cache_bytes(rag) == L.state_cache_bytes(full)
+    assert L.scratch_bytes(rag) > L.scratch_bytes(full)
+    assert L.gated_scratch_bytes(rag) < L.scratch_bytes(rag)
 
 
 def test_check_decay(L):
@@ -100,7 +106,7 @@ def test_fwd_rejects_before_launch(L):
     odd = ctypes.c_void_p(q.value + 8)
     assert call(ctypes.byref(s), odd, k, v, kvin, dec, out, kvout, cache, scr, sb, None) == 8   # q not 16-byte aligned
     assert call(ctypes.byref(s), q, k, v, kvin, dec, out, kvout, cache, ctypes.c_void_p(scr.value + 4), sb, None) == 8
-    bad = L.make_shape(1, 1, 65, 64, 64, "bf16")
+    bad = L.make_shape(1, 1, 64, 96, 64, "bf16")
     assert call(ctypes.byref(bad), q, k, v, kvin, dec, out, kvout, cache, scr, sb, None) == 2
     bad = L.make_shape(1, 1, 64, 64, 64, 7)
     assert call(ctypes.byref(bad), q, k, v, kvin, dec, out, kvout, cache, scr, sb, None) == 3
@@ -137,7 +143,7 @@ def test_gated_sizes(L):
     assert L.gated_state_cache_bytes(s) in (per_tile, per_tile // 2)
     # segment states + one log-decay per segment + one float per token and head
     assert L.gated_scratch_bytes(s) >= L.scratch_bytes(s) + 16 * 32768 * 4
-    bad = L.make_shape(1, 1, 100, 64, 64, "bf16")
+    bad = L.make_shape(1, 1, 100, 64, 32, "bf16")
     assert L.gated_scratch_bytes(bad) == 0 and L.gated_state_cache_bytes(bad) == 0
 
 
@@ -164,7 +170,7 @@ def test_gated_fwd_rejects_before_launch(L):
     assert call(*a) == 5
     a = list(ok_args); a[6] = lg                     # out aliases log_g
     assert call(*a) == 6
-    a = list(ok_args); a[0] = ctypes.byref(L.make_shape(1, 1, 65, 64, 64, "bf16"))
+    a = list(ok_args); a[0] = ctypes.byref(L.make_shape(1, 1, 64, 64, 96, "bf16"))
     assert call(*a) == 2
 
 
@@ -211,6 +217,8 @@ def test_norm_rejects_before_launch(L):
     assert call(*a) == 5
     a = list(ok_args); a[8] = out                    # rstd aliases out
     assert call(*a) == 6
+    a = list(ok_args); a[0] = ctypes.byref(L.make_shape(1, 1, 100, 64, 64, "bf16"))   # Norm needs whole tiles
+    assert call(*a) == 2
 
     do, g, dq, dk, dv, gin = [_fake(i) for i in range(11, 17)]
     call = lambda *a: L.lib.lasp_bwd_norm(*a)
