@@ -12,9 +12,16 @@
 //                local states into the state each segment starts from
 //                (KV_t = lambda^len KV_{t-1} + local, the state update of
 //                Sec. 3.2 taken over a whole segment).
-//   3. k_fwd / k_bwd : each segment walks its tiles with the d x d state held
-//                in registers: intra-chunk left product, inter-chunk right
-//                product, state update (Alg. 2 / Alg. 3 per tile).
+//   3. k_fwd / k_bwd8p, k_bwd8, k_bwd : each segment walks its tiles with the
+//                d x d state held in registers: intra-chunk left product,
+//                inter-chunk right product, state update (Alg. 2 / Alg. 3 per
+//                tile). Backward: k_bwd8p for bfloat16 with an even tile count
+//                (one cached state per pair of tiles), k_bwd8 for an odd one,
+//                k_bwd for float.
+// Every kernel is instantiated for a decay model (lasp_device.h): one lambda
+// per head, or a decay per token (general recurrent form of App. A.4), which
+// adds k_dlg for the gradient of the log decay; and optionally with the output
+// normalisation fused (forward epilogue, backward prologue).
 // This is the paper's "intra parts in parallel, inter parts in sequence"
 // (Alg. 2) folded onto one GPU; there are no atomics, so results are
 // bit-reproducible.
@@ -29,665 +36,9 @@
 #include <hip/hip_runtime.h>
 
 #include "lasp_internal.h"
+#include "lasp_device.h"
 
 namespace lasp {
-
-typedef unsigned short bf16_t;  // storage type of bfloat16 data
-typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
-typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
-typedef __attribute__((ext_vector_type(8))) float f32x8;
-typedef __attribute__((ext_vector_type(4))) float f32x4;
-typedef __attribute__((ext_vector_type(16))) float f32x16;
-typedef __attribute__((ext_vector_type(4))) short s16x4;
-typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
-
-#define DEVI __device__ __forceinline__
-// Compiler scheduling fence: keeps the loads of one product step from being
-// hoisted across earlier steps (which would blow up register live ranges).
-#define SCHED_FENCE() ((void)0)
-
-// Optional per-phase cycle accounting (diagnostic builds only, -DLASP_PHASE_TIMING):
-// thread 0 of every workgroup accumulates shader-clock cycles between PHASE marks
-// and adds them to a device-global table that lasp_debug_phases() reads back.
-#ifdef LASP_PHASE_TIMING
-__device__ unsigned long long g_phase_cycles[32];
-#define PHASE_DECL()                                   \
-    __shared__ unsigned long long ph_acc[32];          \
-    if (threadIdx.x < 32) ph_acc[threadIdx.x] = 0;     \
-    unsigned long long ph_last = clock64()
-#define PHASE(n)                                               \
-    do {                                                       \
-        unsigned long long now_ = clock64();                   \
-        if (threadIdx.x == 0) ph_acc[n] += now_ - ph_last;     \
-        ph_last = now_;                                        \
-    } while (0)
-#define PHASE_FLUSH()                                                                            \
-    do {                                                                                         \
-        __syncthreads();                                                                         \
-        if (threadIdx.x < 32) atomicAdd(&g_phase_cycles[threadIdx.x], ph_acc[threadIdx.x]);      \
-    } while (0)
-#else
-#define PHASE_DECL() ((void)0)
-#define PHASE(n) ((void)0)
-#define PHASE_FLUSH() ((void)0)
-#endif
-
-// Software pipelining of a product loop: the operand fragments of step s+1 are
-// requested before the MFMAs of step s are issued, so that LDS latency is
-// covered by matrix work of the same wave. `load(s)` returns the fragments of
-// step s, `use(s, frags)` consumes them.
-template <int N, typename Load, typename Use>
-DEVI void pipelined(Load load, Use use) {
-    // two steps ahead: with one or two waves per SIMD the LDS round trip is longer
-    // than the matrix work of a single step
-    auto cur = load(0);
-    decltype(cur) nxt;
-    if (N > 1) nxt = load(1);
-#pragma unroll
-    for (int s = 0; s < N; ++s) {
-        decltype(cur) nn;
-        if (s + 2 < N) nn = load(s + 2);
-        use(s, cur);
-        if (s + 1 < N) cur = nxt;
-        if (s + 2 < N) nxt = nn;
-    }
-}
-template <typename F>
-struct FragPair {
-    F a, b;
-};
-
-// Global access as (uniform base + compile-time bytes) + 32-bit per-lane byte
-// offset: the form the hardware addresses with a scalar base register pair and
-// one vector offset register, instead of a 64-bit address pair per access.
-template <typename V>
-DEVI V gload(const void *base, unsigned lane_bytes) { return *(const V *)((const char *)base + lane_bytes); }
-template <typename V>
-DEVI void gstore(void *base, unsigned lane_bytes, V v) { *(V *)((char *)base + lane_bytes) = v; }
-
-// Lane coordinates inside a wave: id 0..63, r = row / column inside a 32-wide
-// tile, h = which half of an MFMA's contraction step. A Lane is rebuilt from an
-// opaque copy of the thread index at every phase of a kernel (fresh_lane), so
-// the compiler derives the LDS/global lane offsets again where they are used
-// instead of keeping dozens of loop-invariant address registers alive, which
-// would spill; a spill reload queues behind the outstanding HBM prefetch.
-struct Lane {
-    int id, r, h;
-    DEVI explicit Lane(int tid) : id(tid & 63), r(tid & 31), h((tid >> 5) & 1) {}
-    // Row of accumulator register i (0..15) inside a 32x32 MFMA tile; the column is r.
-    DEVI int acc_row(int i) const { return 8 * (i >> 2) + 4 * h + (i & 3); }
-};
-DEVI Lane fresh_lane() {
-    int t = threadIdx.x;
-    asm volatile("" : "+v"(t));
-    return Lane(t);
-}
-
-// LDS layout of bfloat16 tiles with 128-element rows (256 bytes = all 64 banks):
-// no padding; the 16-byte chunk c of row `row` is stored at chunk c ^ swz16(row).
-// A row stride of exactly 128 elements selects this layout in the loaders below.
-// It is conflict-free for 16 lanes reading one chunk of 16 consecutive rows, for
-// the four-row by two-chunk blocks of a transposing read, and for whole-row stores.
-constexpr int kSwzLd = 128;
-DEVI int swz16(int row) { return ((row & 7) << 1) | ((row >> 3) & 1); }
-// element offset of (row, col) in a tile with row stride ld
-DEVI int lds_off(int ld, int row, int col) {
-    return ld == kSwzLd ? row * kSwzLd + ((((col >> 3) ^ swz16(row))) << 3) + (col & 7) : row * ld + col;
-}
-template <typename T, int D>
-constexpr int tile_ld() { return (sizeof(T) == 2 && D == 128) ? kSwzLd : D + (sizeof(T) == 2 ? 24 : 4); }
-
-// ---------------------------------------------------------------------------
-// Element traits: how MFMA operand fragments are fetched for each data type.
-// A fragment is what one lane feeds to one MFMA: for a 32-row (or 32-column)
-// operand block, lane (r, h) supplies row/column r and the h-th half of the
-// KSTEP contraction indices of that MFMA.
-//   ld_kc : contraction index contiguous in memory  X[(row0 + r) * ld + k]
-//   ld_ks : contraction index strided in memory     X[k * ld + col0 + r]
-//   ld_kp : contraction index contiguous, but taken in the permuted order in
-//           which an accumulator tile enumerates its rows (sub-step m of the
-//           32-wide block starting at kb), so that accumulator registers can be
-//           the other operand.
-// ---------------------------------------------------------------------------
-template <typename T>
-struct Elem;
-
-template <>
-struct Elem<float> {
-    typedef float frag;
-    static constexpr int KSTEP = 2;   // contraction extent of one MFMA
-    static constexpr int NSUB = 16;   // MFMAs per 32-wide contraction block
-    static constexpr int PAD = 4;     // elements of row padding in LDS tiles
-    static DEVI f32x16 mfma(frag a, frag b, f32x16 c) { return __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, c, 0, 0, 0); }
-    static DEVI frag ld_kc(const Lane &ln, const float *X, int ld, int row0, int k0) { return X[(row0 + ln.r) * ld + k0 + ln.h]; }
-    static DEVI frag ld_ks(const Lane &ln, const float *X, int ld, int k0, int col0) { return X[(k0 + ln.h) * ld + col0 + ln.r]; }
-    // ld_kc from global memory: uniform tile pointer, row block row0, contraction step k0
-    static DEVI frag ld_kc_g(const Lane &ln, const float *X, int ld, int row0, int k0) {
-        return gload<float>(X + k0, ((row0 + ln.r) * ld + ln.h) * sizeof(float));
-    }
-    static DEVI frag ld_kp(const Lane &ln, const float *X, int ld, int row0, int kb, int m) {
-        return X[(row0 + ln.r) * ld + kb + ln.acc_row(m)];
-    }
-    // accumulator tile -> fragment for sub-step m
-    static DEVI frag from_acc(const f32x16 &t, int m) { return t[m]; }
-    // multiply each contraction element k of the fragment by w[k]
-    template <typename W>
-    static DEVI frag scale(const Lane &ln, frag f, int k0, W w) { return f * w(k0 + ln.h); }
-    // Elements per lane of one fragment, and the geometric form of a row weight:
-    // every contraction element e of the fragment is multiplied by a * g[e].
-    static constexpr int KH = 1;
-    static DEVI frag scale_geo(frag f, float a, const float (&g)[8]) { return f * (a * g[0]); }
-    // multiply contraction element k of the fragment of step k0 by tab[k] (tab in LDS)
-    static DEVI frag scale_tab(const Lane &ln, frag f, const float *tab, int k0) { return f * tab[k0 + ln.h]; }
-    // store 4 values of consecutive columns
-    static DEVI void st4(float *p, float a, float b, float c, float d) { *(f32x4 *)p = f32x4{a, b, c, d}; }
-    static DEVI void st1(float *p, float a) { *p = a; }
-    static DEVI void gst4(float *base, unsigned lane_bytes, float a, float b, float c, float d) {
-        gstore<f32x4>(base, lane_bytes, f32x4{a, b, c, d});
-    }
-    static DEVI void gst1(float *base, unsigned lane_bytes, float a) { gstore<float>(base, lane_bytes, a); }
-    static DEVI float ld1(const float *p) { return *p; }
-};
-
-template <>
-struct Elem<bf16_t> {
-    typedef bf16x8 frag;
-    static constexpr int KSTEP = 16;
-    static constexpr int NSUB = 2;
-    static constexpr int PAD = 24;  // row stride = 12 banks mod 64: conflict-free 16-byte row reads, disjoint 4-row transposing reads
-    static DEVI f32x16 mfma(frag a, frag b, f32x16 c) { return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0); }
-    // row0 is a multiple of 16 and k0 a multiple of 16 wherever these are called.
-    static DEVI frag ld_kc(const Lane &ln, const bf16_t *X, int ld, int row0, int k0) {
-        if (ld == kSwzLd) {
-            const int t = ln.h ^ swz16(ln.r);  // lane constant; chunk (k0/8 + h) ^ swz = (k0/8) ^ t since k0/8 is even
-            return *(const bf16x8 *)(X + (row0 + ln.r) * kSwzLd + (((k0 >> 3) ^ t) << 3));
-        }
-        return *(const bf16x8 *)(X + (row0 + ln.r) * ld + k0 + 8 * ln.h);
-    }
-    static DEVI frag ld_kc_g(const Lane &ln, const bf16_t *X, int ld, int row0, int k0) {
-        return gload<bf16x8>(X + k0, ((row0 + ln.r) * ld + 8 * ln.h) * sizeof(bf16_t));
-    }
-    // LDS only: two transposing reads (ds_read_b64_tr_b16). Within each group of
-    // 16 lanes, lane i ends up with element (row e, column i) of the 4 x 16 block
-    // whose rows the lanes addressed in 4-element pieces.
-    static DEVI frag ld_ks(const Lane &ln, const bf16_t *X, int ld, int k0, int col0) {
-        const int l = ln.id;
-        const int l16 = l & 15;
-        typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
-        const bf16_t *plo, *phi;
-        if (ld == kSwzLd) {
-            const int rowl = 8 * ln.h + (l16 >> 2);                    // row inside the 16-row group (k0 % 16 == 0)
-            const int c = (col0 >> 3) + 2 * ((l >> 4) & 1) + ((l16 & 3) >> 1);  // chunk of this lane's 8-byte piece
-            const int e = 4 * (l16 & 1);                                // element inside the chunk
-            plo = X + (k0 + rowl) * kSwzLd + ((c ^ swz16(rowl)) << 3) + e;
-            phi = X + (k0 + rowl + 4) * kSwzLd + ((c ^ swz16(rowl + 4)) << 3) + e;
-        } else {
-            plo = X + (k0 + 8 * ln.h + (l16 >> 2)) * ld + col0 + 16 * ((l >> 4) & 1) + 4 * (l16 & 3);
-            phi = plo + 4 * ld;
-        }
-        s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)plo);
-        s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)phi);
-        union { struct { s16x4 a, b; } s; bf16x8 v; } u;
-        u.s.a = lo;
-        u.s.b = hi;
-        return u.v;
-    }
-    static DEVI frag ld_kp(const Lane &ln, const bf16_t *X, int ld, int row0, int kb, int m) {
-        union { struct { bf16x4 a, b; } s; bf16x8 v; } u;
-        if (ld == kSwzLd) {
-            const int sw = swz16(ln.r), c = (kb >> 3) + 2 * m;
-            const bf16_t *p = X + (row0 + ln.r) * kSwzLd + 4 * ln.h;
-            u.s.a = *(const bf16x4 *)(p + ((c ^ sw) << 3));
-            u.s.b = *(const bf16x4 *)(p + (((c + 1) ^ sw) << 3));
-        } else {
-            const bf16_t *p = X + (row0 + ln.r) * ld + kb + 16 * m + 4 * ln.h;
-            u.s.a = *(const bf16x4 *)p;
-            u.s.b = *(const bf16x4 *)(p + 8);
-        }
-        return u.v;
-    }
-    static DEVI frag from_acc(const f32x16 &t, int m) {
-        f32x8 x;
-#pragma unroll
-        for (int e = 0; e < 8; ++e) x[e] = t[8 * m + e];
-        return __builtin_convertvector(x, bf16x8);
-    }
-    template <typename W>
-    static DEVI frag scale(const Lane &ln, frag f, int k0, W w) {
-        f32x8 x = __builtin_convertvector(f, f32x8);
-#pragma unroll
-        for (int e = 0; e < 8; ++e) x[e] *= w(k0 + 8 * ln.h + e);
-        return __builtin_convertvector(x, bf16x8);
-    }
-    static constexpr int KH = 8;
-    static DEVI frag scale_geo(frag f, float a, const float (&g)[8]) {
-        f32x8 x = __builtin_convertvector(f, f32x8);
-#pragma unroll
-        for (int e = 0; e < 8; ++e) x[e] *= a * g[e];
-        return __builtin_convertvector(x, bf16x8);
-    }
-    static DEVI frag scale_tab(const Lane &ln, frag f, const float *tab, int k0) {
-        const f32x4 *t = (const f32x4 *)(tab + k0 + 8 * ln.h);  // 16-byte aligned: tab is, k0 % 16 == 0
-        const f32x4 lo = t[0], hi = t[1];
-        f32x8 x = __builtin_convertvector(f, f32x8);
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            x[e] *= lo[e];
-            x[4 + e] *= hi[e];
-        }
-        return __builtin_convertvector(x, bf16x8);
-    }
-    static DEVI void st4(bf16_t *p, float a, float b, float c, float d) {
-        *(bf16x4 *)p = __builtin_convertvector(f32x4{a, b, c, d}, bf16x4);
-    }
-    static DEVI void st1(bf16_t *p, float a) {
-        union { __bf16 b; bf16_t u; } c;
-        c.b = (__bf16)a;
-        *p = c.u;
-    }
-    static DEVI float ld1(const bf16_t *p) { return __uint_as_float(((unsigned)*p) << 16); }
-    static DEVI void gst4(bf16_t *base, unsigned lane_bytes, float a, float b, float c, float d) {
-        gstore<bf16x4>(base, lane_bytes, __builtin_convertvector(f32x4{a, b, c, d}, bf16x4));
-    }
-    static DEVI void gst1(bf16_t *base, unsigned lane_bytes, float a) { gstore<__bf16>(base, lane_bytes, (__bf16)a); }
-};
-
-// ---------------------------------------------------------------------------
-// Tile movement: global -> registers -> LDS in 16-byte pieces. Splitting the
-// two halves lets the next tile's loads fly while the current one is computed.
-// ---------------------------------------------------------------------------
-template <typename T, int ROWS, int COLS, int NT>
-struct TileMover {
-    static constexpr int EPV = 16 / sizeof(T);          // elements per 16-byte piece
-    static constexpr int VPR = COLS / EPV;              // pieces per row
-    static constexpr int NV = ROWS * VPR / NT;          // pieces per thread
-    static_assert(ROWS * VPR % NT == 0 && NT % VPR == 0, "tile must divide evenly over the workgroup");
-    u32x4 r[NV];
-    // Per-lane element offset of piece 0; piece i lies NT/VPR rows further down.
-    static DEVI unsigned lane_off(int ld) { return (threadIdx.x / VPR) * ld + (threadIdx.x % VPR) * EPV; }
-    DEVI void load(const T *g) {  // g: first element of the tile (uniform), row stride COLS
-        const unsigned lo = lane_off(COLS) * sizeof(T);
-#pragma unroll
-        for (int i = 0; i < NV; ++i) r[i] = gload<u32x4>(g + i * (NT / VPR) * COLS, lo);
-    }
-    // rows >= nrows are not touched in memory and read as zero (the last tile of a sub-sequence whose
-    // length is not a multiple of the tile)
-    DEVI void load(const T *g, int nrows) {
-        if (nrows >= ROWS) return load(g);
-        const unsigned lo = lane_off(COLS) * sizeof(T);
-        const int row0 = threadIdx.x / VPR;
-#pragma unroll
-        for (int i = 0; i < NV; ++i)
-            r[i] = row0 + i * (NT / VPR) < nrows ? gload<u32x4>(g + i * (NT / VPR) * COLS, lo) : u32x4{0, 0, 0, 0};
-    }
-    DEVI void store(T *s, int ld) const {
-        if (sizeof(T) == 2 && ld == kSwzLd) {
-            static_assert(sizeof(T) != 2 || COLS != 128 || (NT / VPR) % 16 == 0, "row step must keep row % 16");
-            const int row = threadIdx.x / VPR, chunk = threadIdx.x % VPR;
-            const unsigned lo = row * kSwzLd + ((chunk ^ swz16(row)) << 3);
-#pragma unroll
-            for (int i = 0; i < NV; ++i) *(u32x4 *)(s + i * (NT / VPR) * kSwzLd + lo) = r[i];
-            return;
-        }
-        const unsigned lo = lane_off(ld);
-#pragma unroll
-        for (int i = 0; i < NV; ++i) *(u32x4 *)(s + i * (NT / VPR) * ld + lo) = r[i];
-    }
-};
-
-// ---------------------------------------------------------------------------
-// Norm(.) of the normalised linear attention O = Norm((Q K^T (.) M) V) (Sec. 2),
-// taken as the parameter-free root-mean-square normalisation of an output row:
-//     y = o * rstd,  rstd = (mean_c o[c]^2 + eps)^(-1/2).
-// Backward, applied to a tile of dY while it is still in registers on its way to
-// LDS (the kernels then see dO as if it had been an input):
-//     dO = rstd (dY - Y mean_c(dY[c] Y[c])).
-// A row's pieces sit in COLS / EPV consecutive lanes of one wave, so the row mean
-// is a butterfly over those lanes. NormTile holds what the prologue needs beside
-// dY: the same pieces of Y and one rstd per piece row.
-// ---------------------------------------------------------------------------
-template <typename T, int ROWS, int COLS, int NT>
-struct NormTile {
-    typedef TileMover<T, ROWS, COLS, NT> TM;
-    TM y;
-    float rstd[TM::NV];
-    DEVI void load(const T *y_tile, const float *rstd_tile) {  // both uniform: first element / first row of the tile
-        y.load(y_tile);
-        const unsigned lo = (threadIdx.x / TM::VPR) * sizeof(float);
-#pragma unroll
-        for (int i = 0; i < TM::NV; ++i) rstd[i] = gload<float>(rstd_tile + i * (NT / TM::VPR), lo);
-    }
-    DEVI void apply(TM &dy) const {
-        static_assert(TM::VPR <= 32, "a row lies inside one half-wave");
-#pragma unroll
-        for (int i = 0; i < TM::NV; ++i) {
-            constexpr int E = TM::EPV;
-            float a[E], b[E];
-            if constexpr (sizeof(T) == 2) {
-                union { u32x4 u; bf16x8 v; } ua, ub;
-                ua.u = dy.r[i];
-                ub.u = y.r[i];
-                const f32x8 fa = __builtin_convertvector(ua.v, f32x8), fb = __builtin_convertvector(ub.v, f32x8);
-#pragma unroll
-                for (int e = 0; e < E; ++e) {
-                    a[e] = fa[e];
-                    b[e] = fb[e];
-                }
-            } else {
-#pragma unroll
-                for (int e = 0; e < E; ++e) {
-                    a[e] = __uint_as_float(dy.r[i][e]);
-                    b[e] = __uint_as_float(y.r[i][e]);
-                }
-            }
-            float p = 0.0f;
-#pragma unroll
-            for (int e = 0; e < E; ++e) p += a[e] * b[e];
-#pragma unroll
-            for (int m = 1; m < TM::VPR; m <<= 1) p += __shfl_xor(p, m, 64);
-            const float mean = p * (1.0f / COLS), rs = rstd[i];
-#pragma unroll
-            for (int e = 0; e < E; ++e) a[e] = rs * (a[e] - b[e] * mean);
-            if constexpr (sizeof(T) == 2) {
-                f32x8 f;
-#pragma unroll
-                for (int e = 0; e < E; ++e) f[e] = a[e];
-                union { u32x4 u; bf16x8 v; } uo;
-                uo.v = __builtin_convertvector(f, bf16x8);
-                dy.r[i] = uo.u;
-            } else {
-#pragma unroll
-                for (int e = 0; e < E; ++e) dy.r[i][e] = __float_as_uint(a[e]);
-            }
-        }
-    }
-};
-
-// Row weights lambda^(CT-1-k) ("after": tokens after k in the tile) and lambda^(k+1)
-// ("upto": 1-based position) for the KH consecutive tokens k_first .. k_first+KH-1 a
-// lane holds in one fragment, as one table entry times a wave-uniform factor per element:
-//   after: pw[CT-KH-k_first] * lambda^(KH-1-e)      upto: pw[k_first+1] * lambda^e
-template <typename T>
-struct GeoWeights {
-    float after[8], upto[8];
-    DEVI explicit GeoWeights(float lam) {
-        const float l2f = (float)log2((double)lam);
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            after[e] = e < Elem<T>::KH ? exp2f((float)(Elem<T>::KH - 1 - e) * l2f) : 1.0f;
-            upto[e] = e < Elem<T>::KH ? exp2f((float)e * l2f) : 1.0f;
-        }
-    }
-};
-template <typename T, int CT>
-DEVI typename Elem<T>::frag weigh_after(const Lane &ln, typename Elem<T>::frag f, int ks, const float *pw, const GeoWeights<T> &g) {
-    const int k_first = ks * Elem<T>::KSTEP + Elem<T>::KH * ln.h;
-    return Elem<T>::scale_geo(f, pw[CT - Elem<T>::KH - k_first], g.after);
-}
-template <typename T, int CT>
-DEVI typename Elem<T>::frag weigh_upto(const Lane &ln, typename Elem<T>::frag f, int ks, const float *pw, const GeoWeights<T> &g) {
-    const int k_first = ks * Elem<T>::KSTEP + Elem<T>::KH * ln.h;
-    return Elem<T>::scale_geo(f, pw[k_first + 1], g.upto);
-}
-
-// lambda^n for n = 0..CT into LDS, evaluated in double so that the table adds
-// no error of its own.
-template <int CT>
-DEVI void fill_pow_table(float *pw, float lam) {
-    for (int i = threadIdx.x; i <= CT; i += blockDim.x) pw[i] = (float)exp2((double)i * log2((double)lam));
-}
-
-// ---------------------------------------------------------------------------
-// Decay model of a tile of CT tokens (token indices 0-based inside the tile):
-//   upto(i)      weight the state entering the tile carries at token i   (Lambda of Alg. 2)
-//   after(j)     weight token j carries at the end of the tile           (lambda^C Lambda^-1)
-//   whole()      weight the entering state carries at the end of the tile (lambda^C)
-//   masked(x,i,j) x times the weight key j carries at query i, zero for j > i (mask M)
-// FixedDecay: one lambda per head (Alg. 2 / Alg. 3 as printed); every weight is a
-// power of lambda read from one table that serves all tiles.
-// TokenDecay: a decay g_s per token (general recurrent form of App. A.4 with a
-// scalar oscillation state); the weights are products of the g inside the tile,
-// held as cumulative base-2 logarithms and rebuilt for every tile by fill().
-// ---------------------------------------------------------------------------
-template <typename T, int CT>
-struct FixedDecay {
-    static constexpr bool kToken = false;
-    const float *pw;
-    GeoWeights<T> geo;
-    DEVI FixedDecay(float *tab, float lam) : pw(tab), geo(lam) { fill_pow_table<CT>(tab, lam); }
-    DEVI float upto(int i) const { return pw[i + 1]; }
-    DEVI float after(int j) const { return pw[CT - 1 - j]; }
-    DEVI float whole() const { return pw[CT]; }
-    DEVI float masked(float x, int i, int j) const {
-        const int d = i - j;
-        const float m = pw[d >= 0 ? d : 0];
-        return d >= 0 ? x * m : 0.0f;
-    }
-    DEVI typename Elem<T>::frag weigh_after(const Lane &ln, typename Elem<T>::frag f, int ks) const {
-        return lasp::weigh_after<T, CT>(ln, f, ks, pw, geo);
-    }
-    DEVI typename Elem<T>::frag weigh_upto(const Lane &ln, typename Elem<T>::frag f, int ks) const {
-        return lasp::weigh_upto<T, CT>(ln, f, ks, pw, geo);
-    }
-};
-
-constexpr float kLog2e = 1.44269504088896340736f;
-
-template <typename T, int CT>
-struct TokenDecay {
-    static constexpr bool kToken = true;
-    static constexpr int PER = (CT + 63) / 64;  // tokens per lane of the wave that scans the tile
-    static_assert(CT <= 128 && CT % PER == 0, "one wave scans a tile");
-    struct LogG {
-        float x[PER];
-        DEVI float sum() const {
-            float s = 0.0f;
-#pragma unroll
-            for (int e = 0; e < PER; ++e) s += x[e];
-            return s;
-        }
-    };
-    float *cum, *wu, *wa;  // LDS: cumulative log2 decay up to and including token i; 2^cum[i]; 2^(cum[CT-1]-cum[j])
-    DEVI explicit TokenDecay(float *tab) : cum(tab), wu(tab + CT), wa(tab + 2 * CT) {}
-    // log2 g of the tokens PER*l .. PER*l+PER-1 of the tile starting at `lg`, in lane l of wave 0 (zero elsewhere)
-    // tokens >= nvalid (past the end of the sub-sequence) are not read and do not decay: log g = 0
-    static DEVI LogG fetch(const float *lg, int nvalid = CT) {
-        LogG v;
-#pragma unroll
-        for (int e = 0; e < PER; ++e) {
-            const int i = PER * threadIdx.x + e;
-            v.x[e] = (threadIdx.x < 64 && i < CT && i < nvalid) ? lg[i] * kLog2e : 0.0f;
-        }
-        return v;
-    }
-    // Rebuilds the tables from the values fetch() returned. Every thread calls it between
-    // the barrier that retires the previous tile and the one that publishes the next.
-    DEVI void fill(const LogG &v) const {
-        if (threadIdx.x < 64) {
-            const int l = threadIdx.x;
-            float c[PER];
-            c[0] = v.x[0];
-#pragma unroll
-            for (int e = 1; e < PER; ++e) c[e] = c[e - 1] + v.x[e];
-            float incl = c[PER - 1];  // inclusive scan of the lane totals
-#pragma unroll
-            for (int d = 1; d < 64; d <<= 1) {
-                const float y = __shfl_up(incl, d, 64);
-                if (l >= d) incl += y;
-            }
-            const float total = __shfl(incl, 63, 64);  // lanes past the tile hold zeros
-            const float before = incl - c[PER - 1];
-#pragma unroll
-            for (int e = 0; e < PER; ++e) {
-                const int i = PER * l + e;
-                if (i < CT) {
-                    const float ci = before + c[e];
-                    cum[i] = ci;
-                    wu[i] = exp2f(ci);
-                    wa[i] = exp2f(total - ci);
-                }
-            }
-        }
-    }
-    DEVI float upto(int i) const { return wu[i]; }
-    DEVI float after(int j) const { return wa[j]; }
-    DEVI float whole() const { return wu[CT - 1]; }
-    DEVI float masked(float x, int i, int j) const { return i >= j ? x * exp2f(cum[i] - cum[j]) : 0.0f; }
-    DEVI typename Elem<T>::frag weigh_after(const Lane &ln, typename Elem<T>::frag f, int ks) const {
-        return Elem<T>::scale_tab(ln, f, wa, ks * Elem<T>::KSTEP);
-    }
-    DEVI typename Elem<T>::frag weigh_upto(const Lane &ln, typename Elem<T>::frag f, int ks) const {
-        return Elem<T>::scale_tab(ln, f, wu, ks * Elem<T>::KSTEP);
-    }
-};
-template <bool TOKEN, typename T, int CT>
-struct DecaySel {
-    typedef FixedDecay<T, CT> type;
-    // `decay` is lambda per head
-    static DEVI type make(float *tab, const float *decay, int chain, int H) { return type(tab, decay[chain % H]); }
-};
-template <typename T, int CT>
-struct DecaySel<true, T, CT> {
-    typedef TokenDecay<T, CT> type;
-    static DEVI type make(float *tab, const float *, int, int) { return type(tab); }
-};
-
-// floats of LDS behind the tiles of every kernel: decay tables, and one row of
-// per-token partial sums per wave (backward walk with per-token decay)
-template <int CT>
-constexpr int table_floats() { return 3 * CT + 4 + 8 * CT; }
-
-// Sum over this wave's 32 features of accT[feature][token] * X[token][feature] for the
-// lane's token (accT: a transposed output tile in accumulator layout, X: the LDS tile
-// with token rows starting at row0). Both half-waves end up with the full sum.
-template <typename T>
-DEVI float rowdot(const Lane &ln, const f32x16 &acc, const T *sX, int ld, int row0, int w) {
-    float s = 0.0f;
-#pragma unroll
-    for (int q = 0; q < 4; ++q) {
-        const T *p = sX + lds_off(ld, row0 + ln.r, 32 * w + 8 * q + 4 * ln.h);
-#pragma unroll
-        for (int e = 0; e < 4; ++e) s += acc[4 * q + e] * Elem<T>::ld1(p + e);
-    }
-    return s + __shfl_xor(s, 32, 64);
-}
-
-// Load / store a wave's column block of a [D][D] float state (row-major [a][c])
-// into accumulator layout: st[ab][i] = S[32 ab + ln.acc_row(i)][32 w + ln.r].
-template <int D>
-DEVI void state_load(const Lane &ln, f32x16 (&st)[D / 32], const float *g, int w) {
-    const unsigned lo = (4 * ln.h * D + 32 * w + ln.r) * sizeof(float);
-#pragma unroll
-    for (int ab = 0; ab < D / 32; ++ab)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) st[ab][i] = gload<float>(g + (32 * ab + 8 * (i >> 2) + (i & 3)) * D, lo);
-}
-template <int D>
-DEVI void state_store(const Lane &ln, const f32x16 (&st)[D / 32], float *g, int w) {
-    const unsigned lo = (4 * ln.h * D + 32 * w + ln.r) * sizeof(float);
-#pragma unroll
-    for (int ab = 0; ab < D / 32; ++ab)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) gstore<float>(g + (32 * ab + 8 * (i >> 2) + (i & 3)) * D, lo, st[ab][i]);
-}
-
-// Masked score tile (Alg. 2 / Alg. 3 mask M): the wave holds the transposed
-// 32x32 block ST[j][i] = sum_d A[j][d] B[i][d] in accumulator layout (row = key j,
-// column = query i), multiplies by lambda^(i-j) for i >= j (zero above the
-// diagonal) and writes it as P[i][j] so that four consecutive keys land in one
-// store.
-template <typename T, int LDP, typename DK>
-DEVI void store_masked_scores(const Lane &ln, T *sP, const f32x16 &acc, int jb, int ib, const DK &dec) {
-    const int iq = 32 * ib + ln.r;
-#pragma unroll
-    for (int g = 0; g < 4; ++g) {
-        const int j0 = 32 * jb + 8 * g + 4 * ln.h;
-        float x[4];
-#pragma unroll
-        for (int e = 0; e < 4; ++e) x[e] = dec.masked(acc[4 * g + e], iq, j0 + e);
-        Elem<T>::st4(sP + iq * LDP + j0, x[0], x[1], x[2], x[3]);
-    }
-}
-
-// ST[jb][ib] = A[jb] B[ib]^T over the feature dimension (both operands have the
-// contraction index contiguous), for every lower-triangular block assigned to
-// this wave; result masked and stored to sP.
-template <typename T, int CT, int D, int LDD, int LDP, typename DK>
-DEVI void masked_scores(const Lane &ln, T *sP, const T *sA, const T *sB, const DK &dec, int w) {
-    using E = Elem<T>;
-    constexpr int NB = CT / 32, NW = D / 32;
-    int idx = 0;
-#pragma unroll
-    for (int ib = 0; ib < NB; ++ib)
-#pragma unroll
-        for (int jb = 0; jb <= ib; ++jb, ++idx) {
-            if (idx % NW != w) continue;
-            f32x16 acc = {0};
-#pragma unroll
-            for (int k0 = 0; k0 < D; k0 += E::KSTEP)
-                acc = E::mfma(E::ld_kc(ln, sA, LDD, 32 * jb, k0), E::ld_kc(ln, sB, LDD, 32 * ib, k0), acc);
-            store_masked_scores<T, LDP>(ln, sP, acc, jb, ib, dec);
-        }
-}
-
-// Write one 32x32 accumulator tile holding the TRANSPOSE of an output block:
-// accumulator row = feature column 32 w + ln.acc_row(i), accumulator column
-// (lane_r) = token row0 + lane_r. Each lane owns four consecutive features of
-// its token per register group, so it stores them as one 8- or 16-byte piece.
-template <typename T, int D>
-DEVI void store_out_tile_t(const Lane &ln, T *g, const f32x16 &acc, int row0, int w, int nrows = 1 << 30) {
-    const unsigned lo = (ln.r * D + 32 * w + 4 * ln.h) * sizeof(T);
-    if (row0 + ln.r >= nrows) return;  // token past the end of the sub-sequence
-#pragma unroll
-    for (int q = 0; q < 4; ++q)
-        Elem<T>::gst4(g + row0 * D + 8 * q, lo, acc[4 * q], acc[4 * q + 1], acc[4 * q + 2], acc[4 * q + 3]);
-}
-
-// Store a wave's column block of the state into the cache tile g ([a][c], row
-// stride D). Accumulator layout gives each lane four consecutive a for one c,
-// the wrong way round for wide stores, so for bfloat16 the wave transposes one
-// 32x32 block at a time through a private slice of an idle LDS buffer (written
-// [c][a], read back with transposing reads) and stores 16 bytes per lane:
-// 64-byte row segments instead of single elements. Other types store element
-// by element. The LDS slice is only touched by this wave (LDS operations of one
-// wave execute in order); the caller's next barrier orders it against later use.
-template <typename T, int CT, int D>
-DEVI void cache_store(const Lane &ln, T *g, const f32x16 (&st)[D / 32], T *idle_lds, int w) {
-    using E = Elem<T>;
-    constexpr int LDS_ROW = 36;  // 32 a + 4 pad elements: 8-byte aligned rows, staggered banks
-    constexpr bool STAGED = sizeof(T) == 2 && (D / 32) * 32 * LDS_ROW <= CT * (CT + E::PAD);
-    if constexpr (STAGED) {
-        T *R = idle_lds + w * 32 * LDS_ROW;
-        const int l = ln.id, bl = l >> 4, i = l & 15;
-        const unsigned glo = (i * D + 32 * w + 8 * bl) * sizeof(T);
-        typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
-#pragma unroll
-        for (int ab = 0; ab < D / 32; ++ab) {
-#pragma unroll
-            for (int q = 0; q < 4; ++q)
-                E::st4(R + ln.r * LDS_ROW + 8 * q + 4 * ln.h, st[ab][4 * q], st[ab][4 * q + 1], st[ab][4 * q + 2],
-                       st[ab][4 * q + 3]);
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-            __builtin_amdgcn_wave_barrier();
-#pragma unroll
-            for (int it = 0; it < 2; ++it) {
-                const T *p = R + (8 * bl + (i >> 2)) * LDS_ROW + 16 * it + 4 * (i & 3);
-                union { struct { s16x4 a, b; } s; u32x4 v; } u;
-                u.s.a = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)p);
-                u.s.b = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(p + 4 * LDS_ROW));
-                gstore<u32x4>(g + (32 * ab + 16 * it) * D, glo, u.v);
-            }
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-            __builtin_amdgcn_wave_barrier();
-        }
-    } else {
-        const unsigned slo = (4 * ln.h * D + 32 * w + ln.r) * sizeof(T);
-#pragma unroll
-        for (int ab = 0; ab < D / 32; ++ab)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) E::gst1(g + (32 * ab + 8 * (i >> 2) + (i & 3)) * D, slo, st[ab][i]);
-    }
-}
 
 // ---------------------------------------------------------------------------
 // k_local: local state of a segment, from zero.
@@ -985,7 +336,6 @@ __global__ __launch_bounds__(D * 2, (CT <= 64 && sizeof(T) == 2) ? 2 : 1) void k
                 const typename E::frag sf = E::from_acc(st[ab], m);
 #pragma unroll
                 for (int ib = 0; ib < NB; ++ib) acc[ib] = E::mfma(sf, E::ld_kp(ln, sQ, LDD, 32 * ib, 32 * ab, m), acc[ib]);
-                SCHED_FENCE();
             }
         // Lambda: token r (1-based) carries lambda^r; the token is this lane's column
 #pragma unroll
@@ -996,7 +346,6 @@ __global__ __launch_bounds__(D * 2, (CT <= 64 && sizeof(T) == 2) ? 2 : 1) void k
             const typename E::frag vf = E::ld_ks(ln, sV, LDD, ks * E::KSTEP, 32 * w);
 #pragma unroll
             for (int ib = ks / SPB; ib < NB; ++ib) acc[ib] = E::mfma(vf, E::ld_kc(ln, sP, LDP, 32 * ib, ks * E::KSTEP), acc[ib]);
-            SCHED_FENCE();
         }
         if constexpr (NORM) {
             // sum of squares of a token's row: this wave's 32 features, then the other waves' through LDS
@@ -1034,7 +383,6 @@ __global__ __launch_bounds__(D * 2, (CT <= 64 && sizeof(T) == 2) ? 2 : 1) void k
             const typename E::frag vd = dec.weigh_after(ln, E::ld_ks(ln, sV, LDD, ks * E::KSTEP, 32 * w), ks);
 #pragma unroll
             for (int ab = 0; ab < DB; ++ab) st[ab] = E::mfma(E::ld_ks(ln, sK, LDD, ks * E::KSTEP, 32 * ab), vd, st[ab]);
-            SCHED_FENCE();
         }
     }
     if (seg == nseg - 1) state_store<D>(ln, st, kv_out + (size_t)chain * D * D, w);
