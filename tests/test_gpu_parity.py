@@ -194,29 +194,32 @@ def test_c2_split_and_unsplit(gpu, oracle):
         assert emax <= TOL["bf16"] and efro <= TOL["bf16"], name
 
 
-def _big_config(gpu, oracle, name, heads, nrows=256):
+def _big_config(gpu, oracle, name, heads, nrows=256, also_unsplit=False):
     """Full-size run in the launch configuration bench.py uses (segments = auto);
     full-tensor comparison against the chunked oracle on a subset of heads, and
-    brute-force rows sampled over all heads."""
+    brute-force rows sampled over all heads. `also_unsplit`: the whole sequence
+    once more as a single call (the largest N one call sees)."""
     harness, lasp, si = gpu
     cfg = si.CONFIGS[name]
     say(f"case {name}: generating inputs")
     inp = si.make_inputs(cfg)
-    say(f"case {name}: gpu run T={cfg.T}")
-    got = harness.run_gpu(inp, T=cfg.T)
     say(f"case {name}: chunked oracle on heads {heads}")
     ref = oracle_all(oracle, inp, form="chunked", chunk=cfg.chunk, heads=heads)
-    compare(harness, got, ref, TOL[cfg.dtype], name, heads=heads)
     say(f"case {name}: brute-force rows")
     rows = si.sample_rows(cfg, cfg.N, nrows, seed=cfg.seed + 1)
     o = oracle.fwd_brute_rows(inp.q, inp.k, inp.v, inp.decay, rows)
     dq, dk, dv = oracle.bwd_brute_rows(inp.q, inp.k, inp.v, inp.dout, inp.decay, rows)
     b, h, s = rows[:, 0], rows[:, 1], rows[:, 2]
-    for nm, r in (("out", o), ("dq", dq), ("dk", dk), ("dv", dv)):
-        x = got[nm][b, h, s]
-        emax, efro = harness.rel_errors(x, r)
-        say(f"  {name} rows {nm:4s} max-rel {emax:.3e} fro-rel {efro:.3e}")
-        assert emax <= TOL[cfg.dtype] and efro <= TOL[cfg.dtype], (name, nm)
+    for T in ((cfg.T, 1) if also_unsplit and cfg.T != 1 else (cfg.T,)):
+        say(f"case {name}: gpu run T={T}")
+        got = harness.run_gpu(inp, T=T)
+        compare(harness, got, ref, TOL[cfg.dtype], f"{name}/T{T}", heads=heads)
+        for nm, r in (("out", o), ("dq", dq), ("dk", dk), ("dv", dv)):
+            x = got[nm][b, h, s]
+            emax, efro = harness.rel_errors(x, r)
+            say(f"  {name}/T{T} rows {nm:4s} max-rel {emax:.3e} fro-rel {efro:.3e}")
+            assert emax <= TOL[cfg.dtype] and efro <= TOL[cfg.dtype], (name, nm)
+        del got
 
 
 def test_c3_full_size(gpu, oracle):
@@ -231,5 +234,5 @@ def test_c4_long_sequence(gpu, oracle):
     import torch
     harness, lasp, si = gpu
     torch.cuda.reset_peak_memory_stats()
-    _big_config(gpu, oracle, "c4", heads=[3, 12], nrows=64)
+    _big_config(gpu, oracle, "c4", heads=[3, 12], nrows=64, also_unsplit=True)
     say(f"  c4 peak device memory {torch.cuda.max_memory_allocated() / 2**30:.2f} GiB")
