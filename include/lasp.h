@@ -189,7 +189,8 @@ int lasp_gated_bwd(const lasp_shape *shape, const void *q, const void *k, const 
  *     y_s = o_s * rstd_s,   rstd_s = (mean_c o_s[c]^2 + eps)^(-1/2),
  * fused into the forward kernel's epilogue (o never goes to memory) and into
  * the backward kernels' prologue:  do_s = rstd_s (dy_s - y_s mean_c(dy_s[c] y_s[c])).
- * One lambda per head (lasp_fwd / lasp_bwd semantics otherwise).
+ * lasp_fwd / lasp_bwd semantics otherwise (one lambda per head; the per-token
+ * decay has its own pair below).
  *
  *   eps     >= 0, finite (LASP_ERR_SHAPE otherwise).
  *   out     forward: the NORMALISED output y, [B][H][N][D] in `dtype`; backward:
@@ -205,6 +206,22 @@ int lasp_bwd_norm(const lasp_shape *shape, const void *q, const void *k, const v
                   const void *out, const float *rstd, const void *dout, const float *dkv_out,
                   const float *decay, const void *state_cache, void *dq, void *dk, void *dv,
                   float *dkv_in, void *scratch, size_t scratch_bytes, void *hip_stream);
+
+/*
+ * Per-token decay and normalised output together: arguments as in
+ * lasp_gated_fwd / lasp_gated_bwd plus eps, rstd and (backward) the normalised
+ * output, with the meaning they have in lasp_fwd_norm / lasp_bwd_norm; dout is
+ * the gradient w.r.t. the normalised output; N must be a multiple of the tile.
+ */
+int lasp_gated_fwd_norm(const lasp_shape *shape, const void *q, const void *k, const void *v,
+                        const float *log_g, const float *kv_in, float eps, void *out, float *rstd,
+                        float *kv_out, void *state_cache, void *scratch, size_t scratch_bytes,
+                        void *hip_stream);
+int lasp_gated_bwd_norm(const lasp_shape *shape, const void *q, const void *k, const void *v,
+                        const void *out, const float *rstd, const void *dout, const float *log_g,
+                        const float *kv_out, const float *dkv_out, const void *state_cache,
+                        void *dq, void *dk, void *dv, float *dlog_g, float *dkv_in, void *scratch,
+                        size_t scratch_bytes, void *hip_stream);
 
 /*
  * Per-kernel timing, for benchmarks (diagnostic; not on the hot path, not

@@ -391,6 +391,73 @@ int lasp_bwd_norm(const lasp_shape *shape, const void *q, const void *k, const v
     return lasp::launch_bwd(p, a, (hipStream_t)hip_stream, next_slot(1)) == hipSuccess ? LASP_OK : LASP_ERR_HIP;
 }
 
+int lasp_gated_fwd_norm(const lasp_shape *shape, const void *q, const void *k, const void *v, const float *log_g,
+                        const float *kv_in, float eps, void *out, float *rstd, float *kv_out, void *state_cache,
+                        void *scratch, size_t scratch_bytes, void *hip_stream) {
+    lasp::Plan p;
+    int rc = make_plan(shape, kForward, &p, true, true);
+    if (rc != LASP_OK) return rc;
+    if (!q || !k || !v || !log_g || !out || !rstd || !kv_out) return LASP_ERR_NULL;
+    if (!std::isfinite(eps) || eps < 0.0f) return LASP_ERR_SHAPE;
+    ScratchLayout l;
+    scratch_layout(shape, true, &l);
+    if (!scratch || scratch_bytes < l.total) return LASP_ERR_WORKSPACE;
+
+    const size_t tb = (size_t)p.B * p.H * p.N * p.D * elem_bytes(p.dtype);
+    const size_t sb = (size_t)p.B * p.H * p.D * p.D * sizeof(float);
+    const size_t gb = (size_t)p.B * p.H * p.N * sizeof(float);
+    const Span ins[] = {{(const char *)q, tb}, {(const char *)k, tb}, {(const char *)v, tb},
+                        {(const char *)kv_in, sb}, {(const char *)log_g, gb}};
+    const Span outs[] = {{(const char *)out, tb}, {(const char *)rstd, gb}, {(const char *)kv_out, sb},
+                         {(const char *)state_cache, cache_bytes(shape, true)}, {(const char *)scratch, l.total}};
+    if (!aligned16(ins, outs)) return LASP_ERR_ALIGN;
+    for (const Span &o : outs) {
+        for (const Span &i : ins)
+            if (overlap(o, i)) return LASP_ERR_ALIAS;
+        for (const Span &o2 : outs)
+            if (&o != &o2 && overlap(o, o2)) return LASP_ERR_ALIAS;
+    }
+    lasp::FwdArgs a{q, k, v, kv_in, log_g, out, kv_out, state_cache, (float *)scratch,
+                    (float *)((char *)scratch + l.seglog), rstd, eps};
+    return lasp::launch_fwd(p, a, (hipStream_t)hip_stream, next_slot(0)) == hipSuccess ? LASP_OK : LASP_ERR_HIP;
+}
+
+int lasp_gated_bwd_norm(const lasp_shape *shape, const void *q, const void *k, const void *v, const void *out,
+                        const float *rstd, const void *dout, const float *log_g, const float *kv_out,
+                        const float *dkv_out, const void *state_cache, void *dq, void *dk, void *dv,
+                        float *dlog_g, float *dkv_in, void *scratch, size_t scratch_bytes, void *hip_stream) {
+    lasp::Plan p;
+    int rc = make_plan(shape, kBackward, &p, true, true);
+    if (rc != LASP_OK) return rc;
+    if (!q || !k || !v || !out || !rstd || !dout || !log_g || !state_cache || !dq || !dk || !dv || !dlog_g || !dkv_in)
+        return LASP_ERR_NULL;
+    if (dkv_out && !kv_out) return LASP_ERR_NULL;
+    ScratchLayout l;
+    scratch_layout(shape, true, &l);
+    if (!scratch || scratch_bytes < l.total) return LASP_ERR_WORKSPACE;
+
+    const size_t tb = (size_t)p.B * p.H * p.N * p.D * elem_bytes(p.dtype);
+    const size_t sb = (size_t)p.B * p.H * p.D * p.D * sizeof(float);
+    const size_t gb = (size_t)p.B * p.H * p.N * sizeof(float);
+    const Span ins[] = {{(const char *)q, tb}, {(const char *)k, tb}, {(const char *)v, tb},
+                        {(const char *)out, tb}, {(const char *)rstd, gb}, {(const char *)dout, tb},
+                        {(const char *)dkv_out, sb}, {(const char *)kv_out, sb}, {(const char *)log_g, gb},
+                        {(const char *)state_cache, cache_bytes(shape, true)}};
+    const Span outs[] = {{(const char *)dq, tb}, {(const char *)dk, tb}, {(const char *)dv, tb},
+                         {(const char *)dlog_g, gb}, {(const char *)dkv_in, sb}, {(const char *)scratch, l.total}};
+    if (!aligned16(ins, outs)) return LASP_ERR_ALIGN;
+    for (const Span &o : outs) {
+        for (const Span &i : ins)
+            if (overlap(o, i)) return LASP_ERR_ALIAS;
+        for (const Span &o2 : outs)
+            if (&o != &o2 && overlap(o, o2)) return LASP_ERR_ALIAS;
+    }
+    lasp::BwdArgs a{q, k, v, dout, dkv_out, log_g, state_cache, dq, dk, dv, dkv_in, (float *)scratch,
+                    kv_out, dlog_g, (float *)((char *)scratch + l.seglog), (float *)((char *)scratch + l.rtok),
+                    out, rstd};
+    return lasp::launch_bwd(p, a, (hipStream_t)hip_stream, next_slot(1)) == hipSuccess ? LASP_OK : LASP_ERR_HIP;
+}
+
 int lasp_profile_begin(int32_t max_calls) {
     if (max_calls <= 0 || g_prof.on) return LASP_ERR_SHAPE;
     for (int kind = 0; kind < 2; ++kind) {

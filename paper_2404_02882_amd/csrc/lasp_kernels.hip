@@ -57,7 +57,7 @@ __global__ __launch_bounds__(D * 2, 2) void k_local(const T *__restrict__ X, con
                                                   float *__restrict__ seglog, int H, int ntiles, int nseg,
                                                   int tiles_per_seg, int ntok, const T *__restrict__ yn = nullptr,
                                                   const float *__restrict__ rstd = nullptr) {
-    static_assert(!NORM || (BWD && !TOKEN), "the Norm prologue belongs to the backward pass with one lambda per head");
+    static_assert(!NORM || BWD, "the Norm prologue belongs to the backward pass");
     using E = Elem<T>;
     constexpr int NT = D * 2, LDD = tile_ld<T, D>(), DB = D / 32, NKS = CT / E::KSTEP;
     extern __shared__ __attribute__((aligned(16))) char smem[];
@@ -99,6 +99,7 @@ __global__ __launch_bounds__(D * 2, 2) void k_local(const T *__restrict__ X, con
         for (int n = 0; n < ntl; ++n) {
             __syncthreads();
             ln = fresh_lane();
+            if constexpr (NORM) mn.apply(my);
             mx.store(sX, LDD);
             my.store(sY, LDD);
             dec.fill(lgreg);
@@ -108,6 +109,7 @@ __global__ __launch_bounds__(D * 2, 2) void k_local(const T *__restrict__ X, con
                 const int tn = tile_of(n + 1);
                 mx.load(X + base + (size_t)tn * CT * D, nvalid(tn));
                 my.load(Y + base + (size_t)tn * CT * D, nvalid(tn));
+                if constexpr (NORM) mn.load(yn + base + (size_t)tn * CT * D, rstd_c + (size_t)tn * CT);
                 lgreg = TokenDecay<T, CT>::fetch(lg + (size_t)tn * CT, nvalid(tn));
             }
             const float whole = dec.whole();
@@ -1320,11 +1322,13 @@ static hipError_t run_local(const Plan &p, const T *x, const T *y, const float *
     if constexpr (BWD) {
         if (p.norm) {  // the Norm prologue needs a third tile in registers: the walk's tile length
             constexpr size_t lds = Smem<T, CT, D>::local;
-            auto kl = k_local<T, CT, D, true, false, true>;
-            if (hipError_t e2 = allow_lds(kl, lds); e2 != hipSuccess) return e2;
-            kl<<<dim3(p.nseg - 1, chains), dim3(D * 2), lds, s>>>(x, y, decay, scratch, seglog, p.H, p.ntiles, p.nseg,
-                                                                p.tiles_per_seg, p.N, yn, rstd);
-            return hipSuccess;
+            auto launch = [&](auto kl) -> hipError_t {
+                if (hipError_t e2 = allow_lds(kl, lds); e2 != hipSuccess) return e2;
+                kl<<<dim3(p.nseg - 1, chains), dim3(D * 2), lds, s>>>(x, y, decay, scratch, seglog, p.H, p.ntiles, p.nseg,
+                                                                    p.tiles_per_seg, p.N, yn, rstd);
+                return hipSuccess;
+            };
+            return p.token ? launch(k_local<T, CT, D, true, true, true>) : launch(k_local<T, CT, D, true, false, true>);
         }
     }
     if constexpr (sizeof(T) == 2 && CT == 64) {
@@ -1377,7 +1381,8 @@ static hipError_t run_fwd(const Plan &p, const FwdArgs &a, hipStream_t s, const 
                                                              a.rstd_out, a.eps);
         return hipSuccess;
     };
-    if (e = p.token ? launch(k_fwd<T, CT, D, true>) : p.norm ? launch(k_fwd<T, CT, D, false, true>) : launch(k_fwd<T, CT, D, false>);
+    if (e = p.token ? (p.norm ? launch(k_fwd<T, CT, D, true, true>) : launch(k_fwd<T, CT, D, true>))
+                    : (p.norm ? launch(k_fwd<T, CT, D, false, true>) : launch(k_fwd<T, CT, D, false>));
         e != hipSuccess)
         return e;
     if (ke) (void)hipEventRecord(ke->ev[3], s);
@@ -1418,9 +1423,8 @@ static hipError_t run_bwd(const Plan &p, const BwdArgs &a, hipStream_t s, const 
                                                                     (const T *)a.yn, a.rstd);
             return hipSuccess;
         };
-        if (e = p.token  ? launch(k_bwd8p<T, CT, D, true>)
-                : p.norm ? launch(k_bwd8p<T, CT, D, false, true>)
-                         : launch(k_bwd8p<T, CT, D, false>);
+        if (e = p.token ? (p.norm ? launch(k_bwd8p<T, CT, D, true, true>) : launch(k_bwd8p<T, CT, D, true>))
+                        : (p.norm ? launch(k_bwd8p<T, CT, D, false, true>) : launch(k_bwd8p<T, CT, D, false>));
             e != hipSuccess)
             return e;
       } else {
@@ -1435,9 +1439,8 @@ static hipError_t run_bwd(const Plan &p, const BwdArgs &a, hipStream_t s, const 
                                                                    (const T *)a.yn, a.rstd);
             return hipSuccess;
         };
-        if (e = p.token  ? launch(k_bwd8<T, CT, D, true>)
-                : p.norm ? launch(k_bwd8<T, CT, D, false, true>)
-                         : launch(k_bwd8<T, CT, D, false>);
+        if (e = p.token ? (p.norm ? launch(k_bwd8<T, CT, D, true, true>) : launch(k_bwd8<T, CT, D, true>))
+                        : (p.norm ? launch(k_bwd8<T, CT, D, false, true>) : launch(k_bwd8<T, CT, D, false>));
             e != hipSuccess)
             return e;
       }
@@ -1451,9 +1454,8 @@ static hipError_t run_bwd(const Plan &p, const BwdArgs &a, hipStream_t s, const 
                                                                  (const T *)a.yn, a.rstd);
             return hipSuccess;
         };
-        if (e = p.token  ? launch(k_bwd<T, CT, D, true>)
-                : p.norm ? launch(k_bwd<T, CT, D, false, true>)
-                         : launch(k_bwd<T, CT, D, false>);
+        if (e = p.token ? (p.norm ? launch(k_bwd<T, CT, D, true, true>) : launch(k_bwd<T, CT, D, true>))
+                        : (p.norm ? launch(k_bwd<T, CT, D, false, true>) : launch(k_bwd<T, CT, D, false>));
             e != hipSuccess)
             return e;
     }

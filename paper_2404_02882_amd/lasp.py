@@ -71,6 +71,10 @@ def _bind(handle):
     handle.lasp_fwd_norm.restype = ctypes.c_int
     handle.lasp_bwd_norm.argtypes = [_sp] + [_vp] * 14 + [_sz, _vp]
     handle.lasp_bwd_norm.restype = ctypes.c_int
+    handle.lasp_gated_fwd_norm.argtypes = [_sp] + [_vp] * 5 + [ctypes.c_float] + [_vp] * 5 + [_sz, _vp]
+    handle.lasp_gated_fwd_norm.restype = ctypes.c_int
+    handle.lasp_gated_bwd_norm.argtypes = [_sp] + [_vp] * 16 + [_sz, _vp]
+    handle.lasp_gated_bwd_norm.restype = ctypes.c_int
     handle.lasp_profile_begin.argtypes = [ctypes.c_int32]
     handle.lasp_profile_end.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int32),
                                         ctypes.POINTER(ctypes.c_int32)]
@@ -225,6 +229,28 @@ def lasp_bwd_norm(shape: Shape, q, k, v, out, rstd, dout, dkv_out, decay, state_
                            _ptr(dkv_in), _ptr(scratch), nbytes, _stream(stream))
     if rc != 0:
         raise LaspError(rc, "lasp_bwd_norm")
+
+
+def lasp_gated_fwd_norm(shape: Shape, q, k, v, log_g, kv_in, eps, out, rstd, kv_out, state_cache, scratch,
+                        stream=None) -> None:
+    """Per-token decay and normalised output together; raises LaspError on a non-zero status."""
+    nbytes = scratch.numel() * scratch.element_size() if scratch is not None else 0
+    rc = lib.lasp_gated_fwd_norm(ctypes.byref(shape), _ptr(q), _ptr(k), _ptr(v), _ptr(log_g), _ptr(kv_in), float(eps),
+                                 _ptr(out), _ptr(rstd), _ptr(kv_out), _ptr(state_cache), _ptr(scratch), nbytes,
+                                 _stream(stream))
+    if rc != 0:
+        raise LaspError(rc, "lasp_gated_fwd_norm")
+
+
+def lasp_gated_bwd_norm(shape: Shape, q, k, v, out, rstd, dout, log_g, kv_out, dkv_out, state_cache, dq, dk, dv,
+                        dlog_g, dkv_in, scratch, stream=None) -> None:
+    """Backward of lasp_gated_fwd_norm; raises LaspError on a non-zero status."""
+    nbytes = scratch.numel() * scratch.element_size() if scratch is not None else 0
+    rc = lib.lasp_gated_bwd_norm(ctypes.byref(shape), _ptr(q), _ptr(k), _ptr(v), _ptr(out), _ptr(rstd), _ptr(dout),
+                                 _ptr(log_g), _ptr(kv_out), _ptr(dkv_out), _ptr(state_cache), _ptr(dq), _ptr(dk),
+                                 _ptr(dv), _ptr(dlog_g), _ptr(dkv_in), _ptr(scratch), nbytes, _stream(stream))
+    if rc != 0:
+        raise LaspError(rc, "lasp_gated_bwd_norm")
 
 
 class Workspace:

@@ -32,9 +32,7 @@ class LaspSequence:
         # token_decay: `decay` of forward / backward is a list of T log-decay shards [B,H,N/T] (float32)
         # instead of the [H] vector of lambdas, and backward also fills dlog_g shards.
         # norm_eps: outputs are normalised (lasp_fwd_norm / lasp_bwd_norm); forward fills `rstd` shards
-        # [B,H,N/T], backward takes them and the forward outputs. Not combined with token_decay.
-        if token_decay and norm_eps is not None:
-            raise ValueError("the normalised output is implemented for one lambda per head only")
+        # [B,H,N/T], backward takes them and the forward outputs. Both may be set together.
         self.norm_eps = norm_eps
         self.token_decay = token_decay
         scratch_bytes = lasp.gated_scratch_bytes if token_decay else lasp.scratch_bytes
@@ -59,7 +57,10 @@ class LaspSequence:
             self.kv[0].copy_(kv_in)
         for t in range(self.T):
             first = None if (t == 0 and not self.has_kv_in) else self.kv[t]
-            if self.norm_eps is not None:
+            if self.norm_eps is not None and self.token_decay:
+                lasp.lasp_gated_fwd_norm(self.shape, q[t], k[t], v[t], decay[t], first, self.norm_eps, out[t], rstd[t],
+                                         self.kv[t + 1], self.caches[t], self.scratch)
+            elif self.norm_eps is not None:
                 lasp.lasp_fwd_norm(self.shape, q[t], k[t], v[t], first, decay, self.norm_eps, out[t], rstd[t],
                                    self.kv[t + 1], self.caches[t], self.scratch)
             elif self.token_decay:
@@ -78,7 +79,11 @@ class LaspSequence:
             self.dkv[self.T].copy_(dkv_out)
         for t in reversed(range(self.T)):
             last = None if (t == self.T - 1 and not self.has_dkv_out) else self.dkv[t + 1]
-            if self.norm_eps is not None:
+            if self.norm_eps is not None and self.token_decay:
+                lasp.lasp_gated_bwd_norm(self.shape, q[t], k[t], v[t], out[t], rstd[t], dout[t], decay[t],
+                                         self.kv[t + 1], last, self.caches[t], dq[t], dk[t], dv[t], dlog_g[t],
+                                         self.dkv[t], self.scratch)
+            elif self.norm_eps is not None:
                 lasp.lasp_bwd_norm(self.shape, q[t], k[t], v[t], out[t], rstd[t], dout[t], last, decay, self.caches[t],
                                    dq[t], dk[t], dv[t], self.dkv[t], self.scratch)
             elif self.token_decay:

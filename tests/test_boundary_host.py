@@ -231,3 +231,30 @@ def test_norm_rejects_before_launch(L):
     assert call(*a) == 5
     a = list(ok_args); a[10] = out                   # dq aliases the forward output
     assert call(*a) == 6
+
+
+def test_gated_norm_rejects_before_launch(L):
+    s = L.make_shape(1, 1, 64, 64, 64, "bf16")
+    sb = L.gated_scratch_bytes(s)
+    q, k, v, lg, kvin, out, rstd, kvout, cache, scr = [_fake(i) for i in range(1, 11)]
+    call = lambda *a: L.lib.lasp_gated_fwd_norm(*a)
+    ok_args = [ctypes.byref(s), q, k, v, lg, kvin, 1e-6, out, rstd, kvout, cache, scr, sb, None]
+    for idx in (1, 2, 3, 4, 7, 8, 9):
+        a = list(ok_args)
+        a[idx] = None
+        assert call(*a) == 1, idx
+    a = list(ok_args); a[12] = L.scratch_bytes(s)
+    assert call(*a) == 5
+    a = list(ok_args); a[0] = ctypes.byref(L.make_shape(1, 1, 70, 64, 64, "bf16"))   # Norm needs whole tiles
+    assert call(*a) == 2
+    do, g, dq, dk, dv, dlg, gin = [_fake(i) for i in range(11, 18)]
+    call = lambda *a: L.lib.lasp_gated_bwd_norm(*a)
+    ok_args = [ctypes.byref(s), q, k, v, out, rstd, do, lg, kvout, g, cache, dq, dk, dv, dlg, gin, scr, sb, None]
+    for idx in (1, 2, 3, 4, 5, 6, 7, 10, 11, 12, 13, 14, 15):
+        a = list(ok_args)
+        a[idx] = None
+        assert call(*a) == 1, idx
+    a = list(ok_args); a[8] = None      # dkv_out without kv_out
+    assert call(*a) == 1
+    a = list(ok_args); a[14] = out      # dlog_g aliases the forward output
+    assert call(*a) == 6

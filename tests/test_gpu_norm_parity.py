@@ -100,3 +100,23 @@ def test_c3_shape_full_size(gpu, oracle):
     say(f"case norm c3: chunked oracle on heads {heads}")
     ref = oracle_all(oracle, inp, EPS, heads=heads, chunk=cfg.chunk)
     compare(harness, got, ref, TOL["bf16"], "nc3", heads=heads)
+
+
+@pytest.mark.parametrize("dtype,D,N,segments", [("f32", 64, 32 * 6, 2), ("bf16", 128, 64 * 8, 0), ("bf16", 64, 64 * 5, 3)])
+def test_token_decay_with_norm(gpu, oracle, dtype, D, N, segments):
+    """Per-token decay and the fused Norm together (lasp_gated_fwd_norm / lasp_gated_bwd_norm), T = 2 where
+    the length allows: all gradients including dlog_g against the composed oracle."""
+    harness, lasp, si = gpu
+    cfg = si.Config("gnorm", B=2, H=3, N=N, D=D, chunk=64, dtype=dtype, seed=900 + N, token_decay=True)
+    say(f"case gated+norm dtype={dtype} D={D} N={N} segments={segments}")
+    inp = si.make_inputs(cfg, with_states=True)
+    rng = np.random.default_rng(cfg.seed)
+    inp.log_g = np.log(rng.uniform(0.8, 1.0, (2, 3, N))).astype(np.float32)
+    T = 2 if (N // 2) % 64 == 0 else 1
+    got = harness.run_gpu(inp, T=T, segments=segments, norm_eps=EPS)
+    o, kvo = oracle.gated_fwd_brute(inp.q, inp.k, inp.v, inp.log_g, inp.kv_in)
+    y, rstd = oracle.norm_fwd(o, EPS)
+    do = oracle.norm_bwd(inp.dout, y, rstd)
+    dq, dk, dv, dlg, gin = oracle.gated_bwd_brute(inp.q, inp.k, inp.v, do, inp.log_g, inp.kv_in, inp.dkv_out)
+    ref = dict(out=y, rstd=rstd, kv_out=kvo, dq=dq, dk=dk, dv=dv, dlog_g=dlg, dkv_in=gin)
+    compare(harness, got, ref, TOL[dtype], f"gnorm/{dtype}")
