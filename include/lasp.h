@@ -40,7 +40,7 @@ extern "C" {
 typedef enum {
     LASP_OK = 0,
     LASP_ERR_NULL = 1,      /* a required pointer is NULL */
-    LASP_ERR_SHAPE = 2,     /* B,H,N <= 0; D not 64/128; chunk not 64/128/256; bad segments; Norm with N % tile != 0 */
+    LASP_ERR_SHAPE = 2,     /* B,H,N <= 0; D not 64/128; chunk not 64/128/256; bad segments or kv_heads; Norm with N % tile != 0 */
     LASP_ERR_DTYPE = 3,     /* dtype is neither LASP_F32 nor LASP_BF16 */
     LASP_ERR_DECAY = 4,     /* lasp_check_decay: a value outside (0, 1] or not finite */
     LASP_ERR_WORKSPACE = 5, /* scratch missing or smaller than lasp_scratch_bytes() */
@@ -63,6 +63,13 @@ typedef enum { LASP_F32 = 0, LASP_BF16 = 1 } lasp_dtype;
  *            sub-sequence in tiles of lasp_tile_tokens() tokens; the tile
  *            divides the chunk, which is exact because the state update of
  *            Sec. 3.2 composes over consecutive tiles.
+ *   kv_heads 0 or H: every query head has its own key/value head. Otherwise a
+ *            divisor of H: k, v (and dk, dv) are [B][kv_heads][N][D] and the
+ *            H / kv_heads consecutive query heads of a group share one of them
+ *            (multi-query / grouped-query heads, which the method is indifferent
+ *            to: Sec. 1). States, decays and everything indexed by head stay per
+ *            QUERY head. The backward pass then needs scratch for dK, dV per query
+ *            head (two token tensors), summed over each group at the end.
  *   segments 0 = chosen by the library. Otherwise the number of independent
  *            segments each head's sub-sequence is cut into so that B*H*segments
  *            workgroups fill the chip (1 <= segments <= ceil(N / tile)).
@@ -71,6 +78,7 @@ typedef struct {
     int32_t B, H, N, D, chunk;
     int32_t dtype;    /* lasp_dtype */
     int32_t segments; /* 0 = auto */
+    int32_t kv_heads; /* 0 = H */
 } lasp_shape;
 
 int lasp_version(void);

@@ -374,3 +374,22 @@ def norm_bwd(dy, y, rstd):
     dy, y, rstd = _d(dy), _d(y), _d(rstd)
     m = np.mean(dy * y, axis=-1)
     return rstd[..., None] * (dy - y * m[..., None])
+
+
+# ---------------------------------------------------------------------------
+# Grouped key/value heads (multi-query / grouped-query attention, which the
+# method is indifferent to, Sec. 1): kv_heads K/V heads serve H query heads,
+# query heads h*G .. h*G+G-1 share K/V head h (G = H / kv_heads). By definition
+# this is ordinary multi-head attention on K, V repeated G times along the head
+# axis; the gradient of a shared head is the sum over the heads it serves.
+# ---------------------------------------------------------------------------
+def group_expand(x, G):
+    """[B, kv_heads, N, D] -> [B, kv_heads * G, N, D], each K/V head repeated for its G query heads."""
+    return np.repeat(_d(x), int(G), axis=1)
+
+
+def group_reduce(dx, G):
+    """Gradient of group_expand: [B, H, N, D] -> [B, H / G, N, D], summed over each group."""
+    dx = _d(dx)
+    B, H, N, D = dx.shape
+    return dx.reshape(B, H // int(G), int(G), N, D).sum(axis=2)

@@ -24,6 +24,7 @@ bool valid_dims(const lasp_shape *s) {
     if (s->D != 64 && s->D != 128) return false;
     if (s->chunk != 64 && s->chunk != 128 && s->chunk != 256) return false;
     if ((int64_t)s->B * s->H > 65535) return false;  // grid.y limit
+    if (s->kv_heads < 0 || (s->kv_heads > 0 && (s->kv_heads > s->H || s->H % s->kv_heads != 0))) return false;
     return true;
 }
 
@@ -36,6 +37,7 @@ int make_plan(const lasp_shape *s, Pass pass, lasp::Plan *p, bool token = false,
     p->N = s->N;
     p->D = s->D;
     p->dtype = s->dtype;
+    p->kvdiv = s->kv_heads > 0 ? s->H / s->kv_heads : 1;
     p->tile = lasp::tile_tokens(s->dtype, s->chunk, s->D);
     p->ntiles = (s->N + p->tile - 1) / p->tile;
     // A short last tile is handled by the per-token-decay kernels only: with one lambda per head the
@@ -72,10 +74,11 @@ size_t cache_bytes(const lasp_shape *shape, bool token) {
 }
 
 // Scratch layout: [segment states][per-token decay only: segment log-decays][.. : per-token r_t]
-// [synthesised log g only: log g per token].
+// [synthesised log g only: log g per token][grouped K/V heads only: dK, dV per query head].
 struct ScratchLayout {
-    size_t states, seglog, rtok, logg, total;  // byte offsets of the regions (states = 0) and the total size
+    size_t states, seglog, rtok, logg, dk_part, dv_part, total;  // byte offsets of the regions (states = 0), total size
 };
+size_t round256(size_t x) { return (x + 255) / 256 * 256; }
 bool scratch_layout(const lasp_shape *shape, bool token, ScratchLayout *l) {
     lasp::Plan f, b;
     if (make_plan(shape, kForward, &f, token) != LASP_OK || make_plan(shape, kBackward, &b, token) != LASP_OK) return false;
@@ -84,13 +87,20 @@ bool scratch_layout(const lasp_shape *shape, bool token, ScratchLayout *l) {
     l->states = 0;
     l->seglog = chains * nseg * f.D * f.D * sizeof(float);
     l->rtok = l->logg = l->seglog;
-    l->total = l->seglog;
+    size_t end = l->seglog;
     if (f.token) {   // requested, or synthesised for a short last tile
-        const size_t per_token = ((chains * (size_t)f.N * sizeof(float) + 255) / 256) * 256;
-        l->rtok = l->seglog + ((chains * nseg * sizeof(float) + 255) / 256) * 256;
+        const size_t per_token = round256(chains * (size_t)f.N * sizeof(float));
+        l->rtok = l->seglog + round256(chains * nseg * sizeof(float));
         l->logg = l->rtok + per_token;
-        l->total = l->logg + (f.synth ? per_token : 0);
+        end = l->logg + (f.synth ? per_token : 0);
     }
+    l->dk_part = l->dv_part = end;
+    if (f.kvdiv > 1) {
+        const size_t per_tensor = round256(chains * (size_t)f.N * f.D * elem_bytes(f.dtype));
+        l->dv_part = l->dk_part + per_tensor;
+        end = l->dv_part + per_tensor;
+    }
+    l->total = end;
     return true;
 }
 
@@ -108,26 +118,138 @@ const lasp::KernelEvents *next_slot(int kind) {
 }
 
 struct Span {
-    const char *p;
+    const void *p;
     size_t n;
 };
-bool overlap(Span a, Span b) { return a.p && b.p && a.p < b.p + b.n && b.p < a.p + a.n; }
+bool overlap(Span a, Span b) {
+    const char *x = (const char *)a.p, *y = (const char *)b.p;
+    return x && y && x < y + b.n && y < x + a.n;
+}
 
-// The kernels move data in 16-byte pieces. NULL (an absent optional buffer) passes.
-template <size_t NI, size_t NO>
-bool aligned16(const Span (&ins)[NI], const Span (&outs)[NO]) {
+// Outputs must not overlap inputs or each other, and the kernels move data in 16-byte pieces.
+// NULL (an absent optional buffer) passes both checks.
+int check_buffers(const std::vector<Span> &ins, const std::vector<Span> &outs) {
     for (const Span &x : ins)
-        if ((uintptr_t)x.p % 16 != 0) return false;
+        if ((uintptr_t)x.p % 16 != 0) return LASP_ERR_ALIGN;
     for (const Span &x : outs)
-        if ((uintptr_t)x.p % 16 != 0) return false;
-    return true;
+        if ((uintptr_t)x.p % 16 != 0) return LASP_ERR_ALIGN;
+    for (const Span &o : outs) {
+        for (const Span &i : ins)
+            if (overlap(o, i)) return LASP_ERR_ALIAS;
+        for (const Span &o2 : outs)
+            if (&o != &o2 && overlap(o, o2)) return LASP_ERR_ALIAS;
+    }
+    return LASP_OK;
+}
+
+// One forward call of any flavour: `token` selects the decay model (decay = lambda [H] or log g
+// [B][H][N]), `norm` the fused output normalisation (eps, rstd).
+struct FwdCall {
+    const lasp_shape *shape;
+    const void *q, *k, *v;
+    const float *kv_in, *decay;
+    bool token, norm;
+    float eps;
+    void *out;
+    float *rstd, *kv_out;
+    void *cache, *scratch;
+    size_t scratch_bytes;
+    void *stream;
+};
+
+int run_fwd_call(const FwdCall &c) {
+    lasp::Plan p;
+    int rc = make_plan(c.shape, kForward, &p, c.token, c.norm);
+    if (rc != LASP_OK) return rc;
+    if (!c.q || !c.k || !c.v || !c.decay || !c.out || !c.kv_out || (c.norm && !c.rstd)) return LASP_ERR_NULL;
+    if (c.norm && (!std::isfinite(c.eps) || c.eps < 0.0f)) return LASP_ERR_SHAPE;
+    ScratchLayout l;
+    scratch_layout(c.shape, c.token, &l);
+    if (!c.scratch || c.scratch_bytes < l.total) return LASP_ERR_WORKSPACE;
+
+    const size_t esz = elem_bytes(p.dtype);
+    const size_t tb = (size_t)p.B * p.H * p.N * p.D * esz, kvb = tb / p.kvdiv;
+    const size_t sb = (size_t)p.B * p.H * p.D * p.D * sizeof(float);
+    const size_t gb = (size_t)p.B * p.H * p.N * sizeof(float);
+    rc = check_buffers({{c.q, tb}, {c.k, kvb}, {c.v, kvb}, {c.kv_in, sb}, {c.decay, c.token ? gb : p.H * sizeof(float)}},
+                       {{c.out, tb}, {c.rstd, gb}, {c.kv_out, sb}, {c.cache, cache_bytes(c.shape, c.token)},
+                        {c.scratch, l.total}});
+    if (rc != LASP_OK) return rc;
+
+    hipStream_t stream = (hipStream_t)c.stream;
+    char *scr = (char *)c.scratch;
+    lasp::FwdArgs a{c.q, c.k, c.v, c.kv_in, c.decay, c.out, c.kv_out, c.cache, (float *)scr,
+                    p.token ? (float *)(scr + l.seglog) : nullptr, c.rstd, c.eps};
+    if (p.synth) {
+        float *lg = (float *)(scr + l.logg);
+        if (lasp::launch_fill_logg(p, c.decay, lg, stream) != hipSuccess) return LASP_ERR_HIP;
+        a.decay = lg;
+    }
+    return lasp::launch_fwd(p, a, stream, next_slot(0)) == hipSuccess ? LASP_OK : LASP_ERR_HIP;
+}
+
+// One backward call of any flavour. `yn`, `rstd`: norm only; `kv_out`, `dlog_g`: per-token decay only.
+struct BwdCall {
+    const lasp_shape *shape;
+    const void *q, *k, *v, *dout;
+    const float *dkv_out, *decay;
+    bool token, norm;
+    const void *yn;
+    const float *rstd, *kv_out;
+    const void *cache;
+    void *dq, *dk, *dv;
+    float *dlog_g, *dkv_in;
+    void *scratch;
+    size_t scratch_bytes;
+    void *stream;
+};
+
+int run_bwd_call(const BwdCall &c) {
+    lasp::Plan p;
+    int rc = make_plan(c.shape, kBackward, &p, c.token, c.norm);
+    if (rc != LASP_OK) return rc;
+    if (!c.q || !c.k || !c.v || !c.dout || !c.decay || !c.cache || !c.dq || !c.dk || !c.dv || !c.dkv_in)
+        return LASP_ERR_NULL;
+    if (c.norm && (!c.yn || !c.rstd)) return LASP_ERR_NULL;
+    if (c.token && (!c.dlog_g || (c.dkv_out && !c.kv_out))) return LASP_ERR_NULL;
+    ScratchLayout l;
+    scratch_layout(c.shape, c.token, &l);
+    if (!c.scratch || c.scratch_bytes < l.total) return LASP_ERR_WORKSPACE;
+
+    const size_t esz = elem_bytes(p.dtype);
+    const size_t tb = (size_t)p.B * p.H * p.N * p.D * esz, kvb = tb / p.kvdiv;
+    const size_t sb = (size_t)p.B * p.H * p.D * p.D * sizeof(float);
+    const size_t gb = (size_t)p.B * p.H * p.N * sizeof(float);
+    rc = check_buffers({{c.q, tb}, {c.k, kvb}, {c.v, kvb}, {c.dout, tb}, {c.dkv_out, sb}, {c.kv_out, sb}, {c.yn, tb},
+                        {c.rstd, gb}, {c.decay, c.token ? gb : p.H * sizeof(float)},
+                        {c.cache, cache_bytes(c.shape, c.token)}},
+                       {{c.dq, tb}, {c.dk, kvb}, {c.dv, kvb}, {c.dlog_g, gb}, {c.dkv_in, sb}, {c.scratch, l.total}});
+    if (rc != LASP_OK) return rc;
+
+    hipStream_t stream = (hipStream_t)c.stream;
+    char *scr = (char *)c.scratch;
+    lasp::BwdArgs a{c.q, c.k, c.v, c.dout, c.dkv_out, c.decay, c.cache, c.dq, c.dk, c.dv, c.dkv_in, (float *)scr,
+                    c.kv_out, c.dlog_g, p.token ? (float *)(scr + l.seglog) : nullptr,
+                    p.token ? (float *)(scr + l.rtok) : nullptr, c.yn, c.rstd, nullptr, nullptr};
+    if (p.synth) {
+        float *lg = (float *)(scr + l.logg);
+        if (lasp::launch_fill_logg(p, c.decay, lg, stream) != hipSuccess) return LASP_ERR_HIP;
+        a.decay = lg;
+    }
+    if (p.kvdiv > 1) {   // the kernels write dK, dV per query head; launch_bwd sums each group into the outputs
+        a.dk_out = c.dk;
+        a.dv_out = c.dv;
+        a.dk = scr + l.dk_part;
+        a.dv = scr + l.dv_part;
+    }
+    return lasp::launch_bwd(p, a, stream, next_slot(1)) == hipSuccess ? LASP_OK : LASP_ERR_HIP;
 }
 
 }  // namespace
 
 extern "C" {
 
-int lasp_version(void) { return 1; }
+int lasp_version(void) { return 2; }
 
 const char *lasp_status_str(int status) {
     switch (status) {
@@ -196,266 +318,68 @@ int lasp_check_log_decay(const float *log_g_host, int64_t n) {
 int lasp_fwd(const lasp_shape *shape, const void *q, const void *k, const void *v, const float *kv_in,
              const float *decay, void *out, float *kv_out, void *state_cache, void *scratch,
              size_t scratch_bytes, void *hip_stream) {
-    lasp::Plan p;
-    int rc = make_plan(shape, kForward, &p);
-    if (rc != LASP_OK) return rc;
-    if (!q || !k || !v || !decay || !out || !kv_out) return LASP_ERR_NULL;
-    if (!scratch || scratch_bytes < lasp_scratch_bytes(shape)) return LASP_ERR_WORKSPACE;
-
-    const size_t tb = (size_t)p.B * p.H * p.N * p.D * elem_bytes(p.dtype);
-    const size_t sb = (size_t)p.B * p.H * p.D * p.D * sizeof(float);
-    const Span ins[] = {{(const char *)q, tb}, {(const char *)k, tb}, {(const char *)v, tb},
-                        {(const char *)kv_in, sb}, {(const char *)decay, p.H * sizeof(float)}};
-    const Span outs[] = {{(const char *)out, tb}, {(const char *)kv_out, sb},
-                         {(const char *)state_cache, lasp_state_cache_bytes(shape)},
-                         {(const char *)scratch, lasp_scratch_bytes(shape)}};
-    if (!aligned16(ins, outs)) return LASP_ERR_ALIGN;
-    for (const Span &o : outs) {
-        for (const Span &i : ins)
-            if (overlap(o, i)) return LASP_ERR_ALIAS;
-        for (const Span &o2 : outs)
-            if (&o != &o2 && overlap(o, o2)) return LASP_ERR_ALIAS;
-    }
-    lasp::FwdArgs a{q, k, v, kv_in, decay, out, kv_out, state_cache, (float *)scratch, nullptr, nullptr, 0.0f};
-    if (p.synth) {
-        ScratchLayout l;
-        scratch_layout(shape, false, &l);
-        float *lg = (float *)((char *)scratch + l.logg);
-        if (lasp::launch_fill_logg(p, decay, lg, (hipStream_t)hip_stream) != hipSuccess) return LASP_ERR_HIP;
-        a.decay = lg;
-        a.seglog = (float *)((char *)scratch + l.seglog);
-    }
-    return lasp::launch_fwd(p, a, (hipStream_t)hip_stream, next_slot(0)) == hipSuccess ? LASP_OK : LASP_ERR_HIP;
+    FwdCall c{shape, q, k, v, kv_in, decay, false, false, 0.0f, out, nullptr, kv_out, state_cache, scratch, scratch_bytes,
+              hip_stream};
+    return run_fwd_call(c);
 }
 
 int lasp_bwd(const lasp_shape *shape, const void *q, const void *k, const void *v, const void *dout,
              const float *dkv_out, const float *decay, const void *state_cache, void *dq, void *dk,
              void *dv, float *dkv_in, void *scratch, size_t scratch_bytes, void *hip_stream) {
-    lasp::Plan p;
-    int rc = make_plan(shape, kBackward, &p);
-    if (rc != LASP_OK) return rc;
-    if (!q || !k || !v || !dout || !decay || !state_cache || !dq || !dk || !dv || !dkv_in) return LASP_ERR_NULL;
-    if (!scratch || scratch_bytes < lasp_scratch_bytes(shape)) return LASP_ERR_WORKSPACE;
-
-    const size_t tb = (size_t)p.B * p.H * p.N * p.D * elem_bytes(p.dtype);
-    const size_t sb = (size_t)p.B * p.H * p.D * p.D * sizeof(float);
-    const Span ins[] = {{(const char *)q, tb}, {(const char *)k, tb}, {(const char *)v, tb},
-                        {(const char *)dout, tb}, {(const char *)dkv_out, sb},
-                        {(const char *)decay, p.H * sizeof(float)},
-                        {(const char *)state_cache, lasp_state_cache_bytes(shape)}};
-    const Span outs[] = {{(const char *)dq, tb}, {(const char *)dk, tb}, {(const char *)dv, tb},
-                         {(const char *)dkv_in, sb}, {(const char *)scratch, lasp_scratch_bytes(shape)}};
-    if (!aligned16(ins, outs)) return LASP_ERR_ALIGN;
-    for (const Span &o : outs) {
-        for (const Span &i : ins)
-            if (overlap(o, i)) return LASP_ERR_ALIAS;
-        for (const Span &o2 : outs)
-            if (&o != &o2 && overlap(o, o2)) return LASP_ERR_ALIAS;
-    }
-    lasp::BwdArgs a{q, k, v, dout, dkv_out, decay, state_cache, dq, dk, dv, dkv_in, (float *)scratch,
-                    nullptr, nullptr, nullptr, nullptr, nullptr, nullptr};
-    if (p.synth) {
-        ScratchLayout l;
-        scratch_layout(shape, false, &l);
-        float *lg = (float *)((char *)scratch + l.logg);
-        if (lasp::launch_fill_logg(p, decay, lg, (hipStream_t)hip_stream) != hipSuccess) return LASP_ERR_HIP;
-        a.decay = lg;
-        a.seglog = (float *)((char *)scratch + l.seglog);
-        a.rtok = (float *)((char *)scratch + l.rtok);   // written by the kernels, not used further
-    }
-    return lasp::launch_bwd(p, a, (hipStream_t)hip_stream, next_slot(1)) == hipSuccess ? LASP_OK : LASP_ERR_HIP;
+    BwdCall c{shape, q, k, v, dout, dkv_out, decay, false, false, nullptr, nullptr, nullptr, state_cache, dq, dk, dv,
+              nullptr, dkv_in, scratch, scratch_bytes, hip_stream};
+    return run_bwd_call(c);
 }
 
 int lasp_gated_fwd(const lasp_shape *shape, const void *q, const void *k, const void *v, const float *log_g,
                    const float *kv_in, void *out, float *kv_out, void *state_cache, void *scratch,
                    size_t scratch_bytes, void *hip_stream) {
-    lasp::Plan p;
-    int rc = make_plan(shape, kForward, &p, true);
-    if (rc != LASP_OK) return rc;
-    if (!q || !k || !v || !log_g || !out || !kv_out) return LASP_ERR_NULL;
-    ScratchLayout l;
-    scratch_layout(shape, true, &l);
-    if (!scratch || scratch_bytes < l.total) return LASP_ERR_WORKSPACE;
-
-    const size_t tb = (size_t)p.B * p.H * p.N * p.D * elem_bytes(p.dtype);
-    const size_t sb = (size_t)p.B * p.H * p.D * p.D * sizeof(float);
-    const size_t gb = (size_t)p.B * p.H * p.N * sizeof(float);
-    const Span ins[] = {{(const char *)q, tb}, {(const char *)k, tb}, {(const char *)v, tb},
-                        {(const char *)kv_in, sb}, {(const char *)log_g, gb}};
-    const Span outs[] = {{(const char *)out, tb}, {(const char *)kv_out, sb},
-                         {(const char *)state_cache, cache_bytes(shape, true)}, {(const char *)scratch, l.total}};
-    if (!aligned16(ins, outs)) return LASP_ERR_ALIGN;
-    for (const Span &o : outs) {
-        for (const Span &i : ins)
-            if (overlap(o, i)) return LASP_ERR_ALIAS;
-        for (const Span &o2 : outs)
-            if (&o != &o2 && overlap(o, o2)) return LASP_ERR_ALIAS;
-    }
-    lasp::FwdArgs a{q, k, v, kv_in, log_g, out, kv_out, state_cache, (float *)scratch,
-                    (float *)((char *)scratch + l.seglog), nullptr, 0.0f};
-    return lasp::launch_fwd(p, a, (hipStream_t)hip_stream, next_slot(0)) == hipSuccess ? LASP_OK : LASP_ERR_HIP;
+    FwdCall c{shape, q, k, v, kv_in, log_g, true, false, 0.0f, out, nullptr, kv_out, state_cache, scratch, scratch_bytes,
+              hip_stream};
+    return run_fwd_call(c);
 }
 
 int lasp_gated_bwd(const lasp_shape *shape, const void *q, const void *k, const void *v, const void *dout,
                    const float *log_g, const float *kv_out, const float *dkv_out, const void *state_cache,
                    void *dq, void *dk, void *dv, float *dlog_g, float *dkv_in, void *scratch,
                    size_t scratch_bytes, void *hip_stream) {
-    lasp::Plan p;
-    int rc = make_plan(shape, kBackward, &p, true);
-    if (rc != LASP_OK) return rc;
-    if (!q || !k || !v || !dout || !log_g || !state_cache || !dq || !dk || !dv || !dlog_g || !dkv_in) return LASP_ERR_NULL;
-    if (dkv_out && !kv_out) return LASP_ERR_NULL;
-    ScratchLayout l;
-    scratch_layout(shape, true, &l);
-    if (!scratch || scratch_bytes < l.total) return LASP_ERR_WORKSPACE;
-
-    const size_t tb = (size_t)p.B * p.H * p.N * p.D * elem_bytes(p.dtype);
-    const size_t sb = (size_t)p.B * p.H * p.D * p.D * sizeof(float);
-    const size_t gb = (size_t)p.B * p.H * p.N * sizeof(float);
-    const Span ins[] = {{(const char *)q, tb}, {(const char *)k, tb}, {(const char *)v, tb},
-                        {(const char *)dout, tb}, {(const char *)dkv_out, sb}, {(const char *)kv_out, sb},
-                        {(const char *)log_g, gb}, {(const char *)state_cache, cache_bytes(shape, true)}};
-    const Span outs[] = {{(const char *)dq, tb}, {(const char *)dk, tb}, {(const char *)dv, tb},
-                         {(const char *)dlog_g, gb}, {(const char *)dkv_in, sb}, {(const char *)scratch, l.total}};
-    if (!aligned16(ins, outs)) return LASP_ERR_ALIGN;
-    for (const Span &o : outs) {
-        for (const Span &i : ins)
-            if (overlap(o, i)) return LASP_ERR_ALIAS;
-        for (const Span &o2 : outs)
-            if (&o != &o2 && overlap(o, o2)) return LASP_ERR_ALIAS;
-    }
-    lasp::BwdArgs a{q, k, v, dout, dkv_out, log_g, state_cache, dq, dk, dv, dkv_in, (float *)scratch,
-                    kv_out, dlog_g, (float *)((char *)scratch + l.seglog), (float *)((char *)scratch + l.rtok),
-                    nullptr, nullptr};
-    return lasp::launch_bwd(p, a, (hipStream_t)hip_stream, next_slot(1)) == hipSuccess ? LASP_OK : LASP_ERR_HIP;
+    BwdCall c{shape, q, k, v, dout, dkv_out, log_g, true, false, nullptr, nullptr, kv_out, state_cache, dq, dk, dv,
+              dlog_g, dkv_in, scratch, scratch_bytes, hip_stream};
+    return run_bwd_call(c);
 }
 
 int lasp_fwd_norm(const lasp_shape *shape, const void *q, const void *k, const void *v, const float *kv_in,
                   const float *decay, float eps, void *out, float *rstd, float *kv_out, void *state_cache,
                   void *scratch, size_t scratch_bytes, void *hip_stream) {
-    lasp::Plan p;
-    int rc = make_plan(shape, kForward, &p, false, true);
-    if (rc != LASP_OK) return rc;
-    if (!q || !k || !v || !decay || !out || !rstd || !kv_out) return LASP_ERR_NULL;
-    if (!std::isfinite(eps) || eps < 0.0f) return LASP_ERR_SHAPE;
-    if (!scratch || scratch_bytes < lasp_scratch_bytes(shape)) return LASP_ERR_WORKSPACE;
-
-    const size_t tb = (size_t)p.B * p.H * p.N * p.D * elem_bytes(p.dtype);
-    const size_t sb = (size_t)p.B * p.H * p.D * p.D * sizeof(float);
-    const size_t gb = (size_t)p.B * p.H * p.N * sizeof(float);
-    const Span ins[] = {{(const char *)q, tb}, {(const char *)k, tb}, {(const char *)v, tb},
-                        {(const char *)kv_in, sb}, {(const char *)decay, p.H * sizeof(float)}};
-    const Span outs[] = {{(const char *)out, tb}, {(const char *)rstd, gb}, {(const char *)kv_out, sb},
-                         {(const char *)state_cache, lasp_state_cache_bytes(shape)},
-                         {(const char *)scratch, lasp_scratch_bytes(shape)}};
-    if (!aligned16(ins, outs)) return LASP_ERR_ALIGN;
-    for (const Span &o : outs) {
-        for (const Span &i : ins)
-            if (overlap(o, i)) return LASP_ERR_ALIAS;
-        for (const Span &o2 : outs)
-            if (&o != &o2 && overlap(o, o2)) return LASP_ERR_ALIAS;
-    }
-    lasp::FwdArgs a{q, k, v, kv_in, decay, out, kv_out, state_cache, (float *)scratch, nullptr, rstd, eps};
-    return lasp::launch_fwd(p, a, (hipStream_t)hip_stream, next_slot(0)) == hipSuccess ? LASP_OK : LASP_ERR_HIP;
+    FwdCall c{shape, q, k, v, kv_in, decay, false, true, eps, out, rstd, kv_out, state_cache, scratch, scratch_bytes,
+              hip_stream};
+    return run_fwd_call(c);
 }
 
 int lasp_bwd_norm(const lasp_shape *shape, const void *q, const void *k, const void *v, const void *out,
                   const float *rstd, const void *dout, const float *dkv_out, const float *decay,
                   const void *state_cache, void *dq, void *dk, void *dv, float *dkv_in, void *scratch,
                   size_t scratch_bytes, void *hip_stream) {
-    lasp::Plan p;
-    int rc = make_plan(shape, kBackward, &p, false, true);
-    if (rc != LASP_OK) return rc;
-    if (!q || !k || !v || !out || !rstd || !dout || !decay || !state_cache || !dq || !dk || !dv || !dkv_in)
-        return LASP_ERR_NULL;
-    if (!scratch || scratch_bytes < lasp_scratch_bytes(shape)) return LASP_ERR_WORKSPACE;
-
-    const size_t tb = (size_t)p.B * p.H * p.N * p.D * elem_bytes(p.dtype);
-    const size_t sb = (size_t)p.B * p.H * p.D * p.D * sizeof(float);
-    const size_t gb = (size_t)p.B * p.H * p.N * sizeof(float);
-    const Span ins[] = {{(const char *)q, tb}, {(const char *)k, tb}, {(const char *)v, tb},
-                        {(const char *)out, tb}, {(const char *)rstd, gb}, {(const char *)dout, tb},
-                        {(const char *)dkv_out, sb}, {(const char *)decay, p.H * sizeof(float)},
-                        {(const char *)state_cache, lasp_state_cache_bytes(shape)}};
-    const Span outs[] = {{(const char *)dq, tb}, {(const char *)dk, tb}, {(const char *)dv, tb},
-                         {(const char *)dkv_in, sb}, {(const char *)scratch, lasp_scratch_bytes(shape)}};
-    if (!aligned16(ins, outs)) return LASP_ERR_ALIGN;
-    for (const Span &o : outs) {
-        for (const Span &i : ins)
-            if (overlap(o, i)) return LASP_ERR_ALIAS;
-        for (const Span &o2 : outs)
-            if (&o != &o2 && overlap(o, o2)) return LASP_ERR_ALIAS;
-    }
-    lasp::BwdArgs a{q, k, v, dout, dkv_out, decay, state_cache, dq, dk, dv, dkv_in, (float *)scratch,
-                    nullptr, nullptr, nullptr, nullptr, out, rstd};
-    return lasp::launch_bwd(p, a, (hipStream_t)hip_stream, next_slot(1)) == hipSuccess ? LASP_OK : LASP_ERR_HIP;
+    BwdCall c{shape, q, k, v, dout, dkv_out, decay, false, true, out, rstd, nullptr, state_cache, dq, dk, dv,
+              nullptr, dkv_in, scratch, scratch_bytes, hip_stream};
+    return run_bwd_call(c);
 }
 
 int lasp_gated_fwd_norm(const lasp_shape *shape, const void *q, const void *k, const void *v, const float *log_g,
                         const float *kv_in, float eps, void *out, float *rstd, float *kv_out, void *state_cache,
                         void *scratch, size_t scratch_bytes, void *hip_stream) {
-    lasp::Plan p;
-    int rc = make_plan(shape, kForward, &p, true, true);
-    if (rc != LASP_OK) return rc;
-    if (!q || !k || !v || !log_g || !out || !rstd || !kv_out) return LASP_ERR_NULL;
-    if (!std::isfinite(eps) || eps < 0.0f) return LASP_ERR_SHAPE;
-    ScratchLayout l;
-    scratch_layout(shape, true, &l);
-    if (!scratch || scratch_bytes < l.total) return LASP_ERR_WORKSPACE;
-
-    const size_t tb = (size_t)p.B * p.H * p.N * p.D * elem_bytes(p.dtype);
-    const size_t sb = (size_t)p.B * p.H * p.D * p.D * sizeof(float);
-    const size_t gb = (size_t)p.B * p.H * p.N * sizeof(float);
-    const Span ins[] = {{(const char *)q, tb}, {(const char *)k, tb}, {(const char *)v, tb},
-                        {(const char *)kv_in, sb}, {(const char *)log_g, gb}};
-    const Span outs[] = {{(const char *)out, tb}, {(const char *)rstd, gb}, {(const char *)kv_out, sb},
-                         {(const char *)state_cache, cache_bytes(shape, true)}, {(const char *)scratch, l.total}};
-    if (!aligned16(ins, outs)) return LASP_ERR_ALIGN;
-    for (const Span &o : outs) {
-        for (const Span &i : ins)
-            if (overlap(o, i)) return LASP_ERR_ALIAS;
-        for (const Span &o2 : outs)
-            if (&o != &o2 && overlap(o, o2)) return LASP_ERR_ALIAS;
-    }
-    lasp::FwdArgs a{q, k, v, kv_in, log_g, out, kv_out, state_cache, (float *)scratch,
-                    (float *)((char *)scratch + l.seglog), rstd, eps};
-    return lasp::launch_fwd(p, a, (hipStream_t)hip_stream, next_slot(0)) == hipSuccess ? LASP_OK : LASP_ERR_HIP;
+    FwdCall c{shape, q, k, v, kv_in, log_g, true, true, eps, out, rstd, kv_out, state_cache, scratch, scratch_bytes,
+              hip_stream};
+    return run_fwd_call(c);
 }
 
 int lasp_gated_bwd_norm(const lasp_shape *shape, const void *q, const void *k, const void *v, const void *out,
                         const float *rstd, const void *dout, const float *log_g, const float *kv_out,
                         const float *dkv_out, const void *state_cache, void *dq, void *dk, void *dv,
                         float *dlog_g, float *dkv_in, void *scratch, size_t scratch_bytes, void *hip_stream) {
-    lasp::Plan p;
-    int rc = make_plan(shape, kBackward, &p, true, true);
-    if (rc != LASP_OK) return rc;
-    if (!q || !k || !v || !out || !rstd || !dout || !log_g || !state_cache || !dq || !dk || !dv || !dlog_g || !dkv_in)
-        return LASP_ERR_NULL;
-    if (dkv_out && !kv_out) return LASP_ERR_NULL;
-    ScratchLayout l;
-    scratch_layout(shape, true, &l);
-    if (!scratch || scratch_bytes < l.total) return LASP_ERR_WORKSPACE;
-
-    const size_t tb = (size_t)p.B * p.H * p.N * p.D * elem_bytes(p.dtype);
-    const size_t sb = (size_t)p.B * p.H * p.D * p.D * sizeof(float);
-    const size_t gb = (size_t)p.B * p.H * p.N * sizeof(float);
-    const Span ins[] = {{(const char *)q, tb}, {(const char *)k, tb}, {(const char *)v, tb},
-                        {(const char *)out, tb}, {(const char *)rstd, gb}, {(const char *)dout, tb},
-                        {(const char *)dkv_out, sb}, {(const char *)kv_out, sb}, {(const char *)log_g, gb},
-                        {(const char *)state_cache, cache_bytes(shape, true)}};
-    const Span outs[] = {{(const char *)dq, tb}, {(const char *)dk, tb}, {(const char *)dv, tb},
-                         {(const char *)dlog_g, gb}, {(const char *)dkv_in, sb}, {(const char *)scratch, l.total}};
-    if (!aligned16(ins, outs)) return LASP_ERR_ALIGN;
-    for (const Span &o : outs) {
-        for (const Span &i : ins)
-            if (overlap(o, i)) return LASP_ERR_ALIAS;
-        for (const Span &o2 : outs)
-            if (&o != &o2 && overlap(o, o2)) return LASP_ERR_ALIAS;
-    }
-    lasp::BwdArgs a{q, k, v, dout, dkv_out, log_g, state_cache, dq, dk, dv, dkv_in, (float *)scratch,
-                    kv_out, dlog_g, (float *)((char *)scratch + l.seglog), (float *)((char *)scratch + l.rtok),
-                    out, rstd};
-    return lasp::launch_bwd(p, a, (hipStream_t)hip_stream, next_slot(1)) == hipSuccess ? LASP_OK : LASP_ERR_HIP;
+    BwdCall c{shape, q, k, v, dout, dkv_out, log_g, true, true, out, rstd, kv_out, state_cache, dq, dk, dv,
+              dlog_g, dkv_in, scratch, scratch_bytes, hip_stream};
+    return run_bwd_call(c);
 }
 
 int lasp_profile_begin(int32_t max_calls) {

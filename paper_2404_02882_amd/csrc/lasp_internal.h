@@ -20,6 +20,7 @@ struct Plan {
     int cache_stride;   // the state cache holds the start state of every cache_stride-th tile (1 or 2)
     bool token;         // per-token decay: `decay` of the argument structs is log g, [B][H][N]
     bool norm;          // output rows are normalised (forward epilogue, backward prologue); token == false
+    int kvdiv;          // query heads per K/V head (1 = every query head has its own)
     bool synth;         // one lambda per head but N % tile != 0: log g is synthesised and the token kernels run
 };
 
@@ -52,6 +53,9 @@ struct BwdArgs {
     // norm only: `dout` is the gradient w.r.t. the normalised output
     const void *yn;       // the normalised output the forward pass wrote
     const float *rstd;    // [B][H][N], from the forward pass
+    // grouped K/V heads only (kvdiv > 1): dk, dv above are per-query-head buffers in scratch,
+    // summed over each group into these [B][kv_heads][N][D] outputs
+    void *dk_out, *dv_out;
 };
 
 // Optional event recorder: when non-null, launch_* records ev[0] before the

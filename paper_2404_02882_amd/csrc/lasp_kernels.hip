@@ -40,6 +40,14 @@
 
 namespace lasp {
 
+// Grouped K/V heads: query heads h*kvdiv .. h*kvdiv+kvdiv-1 of a batch entry share K/V head h. The
+// kernels index every token tensor by the query-head chain (b*H + h); K and V pointers are moved once,
+// at kernel entry, by the distance between the chain's own slot and its K/V head's slot.
+DEVI ptrdiff_t kv_shift(int chain, int H, int kvdiv, int ntok, int D) {
+    const int kvchain = (chain / H) * (H / kvdiv) + (chain % H) / kvdiv;
+    return (ptrdiff_t)(kvchain - chain) * ntok * D;
+}
+
 // ---------------------------------------------------------------------------
 // k_local: local state of a segment, from zero.
 //   forward : local = sum_s lambda^(len - s) k_s v_s^T            (X = K, Y = V)
@@ -55,7 +63,7 @@ template <typename T, int CT, int D, bool BWD, bool TOKEN, bool NORM = false>
 __global__ __launch_bounds__(D * 2, 2) void k_local(const T *__restrict__ X, const T *__restrict__ Y,
                                                   const float *__restrict__ decay, float *__restrict__ scratch,
                                                   float *__restrict__ seglog, int H, int ntiles, int nseg,
-                                                  int tiles_per_seg, int ntok, const T *__restrict__ yn = nullptr,
+                                                  int tiles_per_seg, int ntok, int kvdiv, const T *__restrict__ yn = nullptr,
                                                   const float *__restrict__ rstd = nullptr) {
     static_assert(!NORM || BWD, "the Norm prologue belongs to the backward pass");
     using E = Elem<T>;
@@ -73,6 +81,11 @@ __global__ __launch_bounds__(D * 2, 2) void k_local(const T *__restrict__ X, con
     Lane ln = fresh_lane();
     PHASE_DECL();
     const size_t base = (size_t)chain * ntok * D;
+    if (!BWD) {  // forward: X, Y are K, V
+        const ptrdiff_t sh = kv_shift(chain, H, kvdiv, ntok, D);
+        X += sh;
+        Y += sh;
+    }
     const int ntl = t1 - t0;
     auto tile_of = [&](int n) { return BWD ? t1 - 1 - n : t0 + n; };
     // the first tile is requested before anything else so that its latency covers the set-up
@@ -271,7 +284,7 @@ __global__ __launch_bounds__(D * 2, (CT <= 64 && sizeof(T) == 2) ? 2 : 1) void k
                                                 const T *__restrict__ V, const float *__restrict__ decay,
                                                 T *__restrict__ O, float *__restrict__ kv_out,
                                                 T *__restrict__ cache, const float *__restrict__ scratch,
-                                                int H, int ntiles, int nseg, int tiles_per_seg, int cache_stride, int ntok,
+                                                int H, int ntiles, int nseg, int tiles_per_seg, int cache_stride, int ntok, int kvdiv,
                                                 float *__restrict__ rstd_out = nullptr, float eps = 0.0f) {
     using E = Elem<T>;
     constexpr int NT = D * 2, LDD = tile_ld<T, D>(), LDP = CT + E::PAD, DB = D / 32, NB = CT / 32, NKS = CT / E::KSTEP,
@@ -290,6 +303,11 @@ __global__ __launch_bounds__(D * 2, (CT <= 64 && sizeof(T) == 2) ? 2 : 1) void k
     Lane ln = fresh_lane();
     // requests first (tile, then start state), table arithmetic while they fly
     const size_t base = (size_t)chain * ntok * D;
+    {   // K, V of this chain's K/V head
+        const ptrdiff_t sh = kv_shift(chain, H, kvdiv, ntok, D);
+        K += sh;
+        V += sh;
+    }
     // rows of tile `t` that exist: the last tile of a sub-sequence may be short (per-token decay only)
     auto nvalid = [&](int t) { return TOKEN ? min(CT, ntok - t * CT) : CT; };
     TileMover<T, CT, D, NT> mq, mk, mv;
@@ -423,7 +441,7 @@ __global__ __launch_bounds__(D * 2, (CT <= 64 && sizeof(T) == 2) ? 2 : 1) void k
                                                 T *__restrict__ dQ, T *__restrict__ dK, T *__restrict__ dV,
                                                 float *__restrict__ dkv_in, const float *__restrict__ scratch,
                                                 float *__restrict__ rtok,
-                                                int H, int ntiles, int nseg, int tiles_per_seg, int ntok,
+                                                int H, int ntiles, int nseg, int tiles_per_seg, int ntok, int kvdiv,
                                                 const T *__restrict__ yn = nullptr, const float *__restrict__ rstd = nullptr) {
     using E = Elem<T>;
     using SM = BwdSmem<T, CT, D>;
@@ -460,6 +478,11 @@ __global__ __launch_bounds__(D * 2, (CT <= 64 && sizeof(T) == 2) ? 2 : 1) void k
     };
 
     const size_t base = (size_t)chain * ntok * D;
+    {   // K, V of this chain's K/V head
+        const ptrdiff_t sh = kv_shift(chain, H, kvdiv, ntok, D);
+        K += sh;
+        V += sh;
+    }
     f32x16 dkv[DB];
     state_load<D>(ln, dkv, scratch + ((size_t)chain * nseg + seg) * D * D, w);
 
@@ -648,7 +671,7 @@ __global__ __launch_bounds__(D * 4) void k_bwd8(const T *__restrict__ Q, const T
                                                  T *__restrict__ dQ, T *__restrict__ dK, T *__restrict__ dV,
                                                  float *__restrict__ dkv_in, const float *__restrict__ scratch,
                                                  float *__restrict__ rtok,
-                                                 int H, int ntiles, int nseg, int tiles_per_seg, int ntok,
+                                                 int H, int ntiles, int nseg, int tiles_per_seg, int ntok, int kvdiv,
                                                  const T *__restrict__ yn = nullptr, const float *__restrict__ rstd = nullptr) {
     using E = Elem<T>;
     using F = typename E::frag;
@@ -677,6 +700,11 @@ __global__ __launch_bounds__(D * 4) void k_bwd8(const T *__restrict__ Q, const T
 
     // requests first (last tile of the segment, its cached state), set-up arithmetic while they fly
     const size_t base = (size_t)chain * ntok * D;
+    {   // K, V of this chain's K/V head
+        const ptrdiff_t sh = kv_shift(chain, H, kvdiv, ntok, D);
+        K += sh;
+        V += sh;
+    }
     TileMover<T, CT, D, NT> mv, mo, mk, mq;
     TileMover<T, D, D, NT> mc;  // cached state tile KV_{t-1}, [a][c]
     const T *ctile = cache + (size_t)chain * ntiles * D * D;
@@ -921,7 +949,7 @@ __global__ __launch_bounds__(D * 4) void k_bwd8p(const T *__restrict__ Q, const 
                                                   T *__restrict__ dQ, T *__restrict__ dK, T *__restrict__ dV,
                                                   float *__restrict__ dkv_in, const float *__restrict__ scratch,
                                                   float *__restrict__ rtok,
-                                                  int H, int ntiles, int nseg, int tiles_per_seg, int ntok,
+                                                  int H, int ntiles, int nseg, int tiles_per_seg, int ntok, int kvdiv,
                                                   const T *__restrict__ yn = nullptr, const float *__restrict__ rstd = nullptr) {
     using E = Elem<T>;
     using F = typename E::frag;
@@ -951,6 +979,11 @@ __global__ __launch_bounds__(D * 4) void k_bwd8p(const T *__restrict__ Q, const 
     PHASE_DECL();
 
     const size_t base = (size_t)chain * ntok * D;
+    {   // K, V of this chain's K/V head
+        const ptrdiff_t sh = kv_shift(chain, H, kvdiv, ntok, D);
+        K += sh;
+        V += sh;
+    }
     const size_t TS = (size_t)CT * D;  // elements per tile
     TileMover<T, CT, D, NT> mvO, moX, mkO, mqX, mvE, mkE;   // moX / mqX carry dO, Q of the O tile, then of the E tile
     TileMover<T, D, D, NT> mc;                               // cached state at the start of the E tile
@@ -1311,6 +1344,32 @@ static hipError_t allow_lds(F kernel, size_t bytes) {
     return e;
 }
 
+// Grouped K/V heads, backward: the walking kernel wrote dK, dV per QUERY head into `part`
+// ([chains][ntok][D]); dK, dV of a K/V head are the sums over its kvdiv query heads, added in fp32
+// in a fixed order and rounded once.
+template <typename T>
+__global__ __launch_bounds__(256) void k_group_sum(const T *__restrict__ part, T *__restrict__ out, int kvdiv, size_t per_head) {
+    const size_t kvchain = blockIdx.y;
+    const T *src = part + kvchain * kvdiv * per_head;
+    T *dst = out + kvchain * per_head;
+    for (size_t e = ((size_t)blockIdx.x * 256 + threadIdx.x) * 4; e < per_head; e += (size_t)gridDim.x * 256 * 4) {
+        float acc[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+        for (int g = 0; g < kvdiv; ++g)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) acc[i] += Elem<T>::ld1(src + (size_t)g * per_head + e + i);
+        Elem<T>::st4(dst + e, acc[0], acc[1], acc[2], acc[3]);   // per_head = ntok * D is a multiple of 4
+    }
+}
+template <typename T>
+static hipError_t run_group_sum(const Plan &p, const void *part, void *out, hipStream_t s) {
+    const size_t per_head = (size_t)p.N * p.D;
+    const int kvchains = p.B * (p.H / p.kvdiv);
+    size_t blocks = (per_head / 4 + 255) / 256;
+    if (blocks > 1024) blocks = 1024;
+    k_group_sum<T><<<dim3((unsigned)blocks, kvchains), dim3(256), 0, s>>>((const T *)part, (T *)out, p.kvdiv, per_head);
+    return hipGetLastError();
+}
+
 // The local pass only sums over its segment, so its tile need not be the walk's:
 // bfloat16 segments made of an even number of 64-token tiles are read 128 tokens
 // at a time (half the barriers, twice the bytes in flight per workgroup). With
@@ -1325,7 +1384,7 @@ static hipError_t run_local(const Plan &p, const T *x, const T *y, const float *
             auto launch = [&](auto kl) -> hipError_t {
                 if (hipError_t e2 = allow_lds(kl, lds); e2 != hipSuccess) return e2;
                 kl<<<dim3(p.nseg - 1, chains), dim3(D * 2), lds, s>>>(x, y, decay, scratch, seglog, p.H, p.ntiles, p.nseg,
-                                                                    p.tiles_per_seg, p.N, yn, rstd);
+                                                                    p.tiles_per_seg, p.N, p.kvdiv, yn, rstd);
                 return hipSuccess;
             };
             return p.token ? launch(k_local<T, CT, D, true, true, true>) : launch(k_local<T, CT, D, true, false, true>);
@@ -1337,7 +1396,7 @@ static hipError_t run_local(const Plan &p, const T *x, const T *y, const float *
             auto launch = [&](auto kl) -> hipError_t {
                 if (hipError_t e2 = allow_lds(kl, lds); e2 != hipSuccess) return e2;
                 kl<<<dim3(p.nseg - 1, chains), dim3(D * 2), lds, s>>>(x, y, decay, scratch, seglog, p.H, p.ntiles / 2, p.nseg,
-                                                                    p.tiles_per_seg / 2, p.N, nullptr, nullptr);
+                                                                    p.tiles_per_seg / 2, p.N, p.kvdiv, nullptr, nullptr);
                 return hipSuccess;
             };
             return p.token ? launch(k_local<T, 128, D, BWD, true>) : launch(k_local<T, 128, D, BWD, false>);
@@ -1347,7 +1406,7 @@ static hipError_t run_local(const Plan &p, const T *x, const T *y, const float *
     auto launch = [&](auto kl) -> hipError_t {
         if (hipError_t e2 = allow_lds(kl, lds); e2 != hipSuccess) return e2;
         kl<<<dim3(p.nseg - 1, chains), dim3(D * 2), lds, s>>>(x, y, decay, scratch, seglog, p.H, p.ntiles, p.nseg,
-                                                            p.tiles_per_seg, p.N, nullptr, nullptr);
+                                                            p.tiles_per_seg, p.N, p.kvdiv, nullptr, nullptr);
         return hipSuccess;
     };
     return p.token ? launch(k_local<T, CT, D, BWD, true>) : launch(k_local<T, CT, D, BWD, false>);
@@ -1377,7 +1436,7 @@ static hipError_t run_fwd(const Plan &p, const FwdArgs &a, hipStream_t s, const 
         if (hipError_t e2 = allow_lds(kf, lds_fwd); e2 != hipSuccess) return e2;
         kf<<<dim3(p.nseg, chains), dim3(D * 2), lds_fwd, s>>>((const T *)a.q, (const T *)a.k, (const T *)a.v, a.decay,
                                                              (T *)a.out, a.kv_out, (T *)a.cache, (const float *)a.scratch,
-                                                             p.H, p.ntiles, p.nseg, p.tiles_per_seg, p.cache_stride, p.N,
+                                                             p.H, p.ntiles, p.nseg, p.tiles_per_seg, p.cache_stride, p.N, p.kvdiv,
                                                              a.rstd_out, a.eps);
         return hipSuccess;
     };
@@ -1419,7 +1478,7 @@ static hipError_t run_bwd(const Plan &p, const BwdArgs &a, hipStream_t s, const 
             kb<<<dim3(p.nseg, chains), dim3(D * 4), lds_bwd8p, s>>>((const T *)a.q, (const T *)a.k, (const T *)a.v,
                                                                     (const T *)a.dout, a.decay, (const T *)a.cache, (T *)a.dq,
                                                                     (T *)a.dk, (T *)a.dv, a.dkv_in, (const float *)a.scratch,
-                                                                    a.rtok, p.H, p.ntiles, p.nseg, p.tiles_per_seg, p.N,
+                                                                    a.rtok, p.H, p.ntiles, p.nseg, p.tiles_per_seg, p.N, p.kvdiv,
                                                                     (const T *)a.yn, a.rstd);
             return hipSuccess;
         };
@@ -1435,7 +1494,7 @@ static hipError_t run_bwd(const Plan &p, const BwdArgs &a, hipStream_t s, const 
             kb<<<dim3(p.nseg, chains), dim3(D * 4), lds_bwd8, s>>>((const T *)a.q, (const T *)a.k, (const T *)a.v,
                                                                    (const T *)a.dout, a.decay, (const T *)a.cache, (T *)a.dq,
                                                                    (T *)a.dk, (T *)a.dv, a.dkv_in, (const float *)a.scratch,
-                                                                   a.rtok, p.H, p.ntiles, p.nseg, p.tiles_per_seg, p.N,
+                                                                   a.rtok, p.H, p.ntiles, p.nseg, p.tiles_per_seg, p.N, p.kvdiv,
                                                                    (const T *)a.yn, a.rstd);
             return hipSuccess;
         };
@@ -1450,7 +1509,7 @@ static hipError_t run_bwd(const Plan &p, const BwdArgs &a, hipStream_t s, const 
             kb<<<dim3(p.nseg, chains), dim3(D * 2), lds_bwd, s>>>((const T *)a.q, (const T *)a.k, (const T *)a.v,
                                                                  (const T *)a.dout, a.decay, (const T *)a.cache, (T *)a.dq,
                                                                  (T *)a.dk, (T *)a.dv, a.dkv_in, (const float *)a.scratch,
-                                                                 a.rtok, p.H, p.ntiles, p.nseg, p.tiles_per_seg, p.N,
+                                                                 a.rtok, p.H, p.ntiles, p.nseg, p.tiles_per_seg, p.N, p.kvdiv,
                                                                  (const T *)a.yn, a.rstd);
             return hipSuccess;
         };
@@ -1458,6 +1517,10 @@ static hipError_t run_bwd(const Plan &p, const BwdArgs &a, hipStream_t s, const 
                         : (p.norm ? launch(k_bwd<T, CT, D, false, true>) : launch(k_bwd<T, CT, D, false>));
             e != hipSuccess)
             return e;
+    }
+    if (p.kvdiv > 1) {
+        if (e = run_group_sum<T>(p, a.dk, a.dk_out, s); e != hipSuccess) return e;
+        if (e = run_group_sum<T>(p, a.dv, a.dv_out, s); e != hipSuccess) return e;
     }
     if (ke) (void)hipEventRecord(ke->ev[3], s);
     if (p.token && a.dlog_g)

@@ -48,10 +48,11 @@ def run_gpu(inp: Inputs, T: int = 1, segments: int = 0, backward: bool = True, c
     w.r.t. the normalised output."""
     cfg = inp.cfg
     B, H, N, D = inp.q.shape
+    kv_heads = inp.k.shape[1] if inp.k.shape[1] != H else 0   # grouped K/V heads: k, v are [B,kv_heads,N,D]
     dt = TORCH_DTYPE[cfg.dtype]
     token = inp.log_g is not None
     seq = LaspSequence(B, H, N, D, chunk or cfg.chunk, dt, T=T, segments=segments, device=device,
-                       need_backward=backward, token_decay=token, norm_eps=norm_eps)
+                       need_backward=backward, token_decay=token, norm_eps=norm_eps, kv_heads=kv_heads)
     q, k, v = (shards(x, T, cfg.dtype, device) for x in (inp.q, inp.k, inp.v))
     if token:
         n = N // T
@@ -70,7 +71,8 @@ def run_gpu(inp: Inputs, T: int = 1, segments: int = 0, backward: bool = True, c
     if backward:
         do = shards(inp.dout, T, cfg.dtype, device)
         g = torch.from_numpy(inp.dkv_out).to(device) if inp.dkv_out is not None else None
-        dq, dk, dv = ([torch.full_like(x, float("nan")) for x in q] for _ in range(3))
+        dq = [torch.full_like(x, float("nan")) for x in q]
+        dk, dv = ([torch.full_like(x, float("nan")) for x in k] for _ in range(2))
         dlg = [torch.full_like(x, float("nan")) for x in decay] if token else None
         dkv_in = seq.backward(q, k, v, do, decay, dq, dk, dv, g, dlog_g=dlg, out=out, rstd=rstd)
         res.update(dq=to_host(dq), dk=to_host(dk), dv=to_host(dv), dkv_in=dkv_in.cpu().numpy().astype(np.float64))

@@ -19,13 +19,14 @@ from . import lasp
 
 class LaspSequence:
     def __init__(self, B, H, N, D, chunk, dtype: torch.dtype, T=1, segments=0, device="cuda", need_backward=True,
-                 token_decay=False, norm_eps: Optional[float] = None):
+                 token_decay=False, norm_eps: Optional[float] = None, kv_heads=0):
         if N % T != 0:
             raise ValueError("N must be a multiple of T")
         self.B, self.H, self.N, self.D, self.T = B, H, N, D, T
         self.n_sub = N // T
         self.dtype = dtype
-        self.shape = lasp.make_shape(B, H, self.n_sub, D, chunk, dtype, segments)
+        # kv_heads: k, v, dk, dv shards are [B,kv_heads,N/T,D]; groups of H/kv_heads query heads share them
+        self.shape = lasp.make_shape(B, H, self.n_sub, D, chunk, dtype, segments, kv_heads)
         rc = lasp.check_shape(self.shape)
         if rc != 0:
             raise lasp.LaspError(rc, "LaspSequence")

@@ -258,3 +258,27 @@ def test_gated_norm_rejects_before_launch(L):
     assert call(*a) == 1
     a = list(ok_args); a[14] = out      # dlog_g aliases the forward output
     assert call(*a) == 6
+
+
+# ---------------------------------------------------------------- grouped K/V heads
+def test_kv_heads_shape_and_sizes(L):
+    base = dict(B=2, H=8, N=1024, D=128, chunk=128, dtype=1, segments=0)
+    for kvh, expect in ((0, 0), (8, 0), (4, 0), (1, 0), (3, 2), (16, 2), (-1, 2)):
+        assert L.check_shape(L.make_shape(**base, kv_heads=kvh)) == expect, kvh
+    mha, gqa = L.make_shape(**base), L.make_shape(**base, kv_heads=2)
+    assert L.state_cache_bytes(gqa) == L.state_cache_bytes(mha)                 # states stay per query head
+    tensor = 2 * 8 * 1024 * 128 * 2
+    assert L.scratch_bytes(gqa) == L.scratch_bytes(mha) + 2 * tensor            # dK, dV per query head
+    assert L.gated_scratch_bytes(gqa) == L.gated_scratch_bytes(mha) + 2 * tensor
+
+
+def test_kv_heads_alias_check_uses_group_sizes(L):
+    """k of a grouped call is [B, kv_heads, N, D]: an output overlapping its last bytes is an alias.
+    (Every call here stops at validation; nothing is launched.)"""
+    s = L.make_shape(1, 4, 64, 64, 64, "bf16", kv_heads=1)
+    sb = L.scratch_bytes(s)
+    one_head = 64 * 64 * 2
+    q, kvin, dec, kvout, cache, scr = [_fake(i) for i in range(1, 7)]
+    k, v = _fake(8), _fake(9)
+    out_inside_k = ctypes.c_void_p(k.value + one_head - 16)
+    assert L.lib.lasp_fwd(ctypes.byref(s), q, k, v, kvin, dec, out_inside_k, kvout, cache, scr, sb, None) == 6

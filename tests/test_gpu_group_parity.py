@@ -1,0 +1,77 @@
+"""Grouped key/value heads (kv_heads < H) through the C-ABI against the oracle: multi-head attention on
+K, V repeated per group, dK / dV summed over each group. Tolerances 1e-4 float, 2e-2 bfloat16."""
+import sys
+
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"f32": 1e-4, "bf16": 2e-2}
+
+
+def say(*a):
+    print(*a, flush=True)
+    sys.stdout.flush()
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    import torch
+    assert torch.cuda.is_available(), "needs a GPU"
+    from paper_2404_02882_amd import harness, lasp, synth_inputs
+    return harness, lasp, synth_inputs
+
+
+def check(harness, got, ref, tol, label):
+    for name, r in ref.items():
+        emax, efro = harness.rel_errors(got[name], r)
+        say(f"  {label} {name:7s} max-rel {emax:.3e} fro-rel {efro:.3e}")
+        assert np.isfinite(emax) and emax <= tol and efro <= tol, (label, name, emax, efro)
+
+
+CASES = [
+    # dtype, D, N, H, kv_heads, segments, T
+    ("f32", 64, 32 * 6, 4, 2, 2, 1),
+    ("bf16", 128, 64 * 8, 4, 1, 0, 2),      # multi-query, pair cache, two chained calls
+    ("bf16", 64, 64 * 5, 6, 2, 3, 1),       # odd tile count
+    ("bf16", 128, 64 * 3 + 9, 4, 2, 0, 1),  # short last tile
+]
+
+
+@pytest.mark.parametrize("dtype,D,N,H,kvh,segments,T", CASES)
+def test_fixed_decay(gpu, oracle, dtype, D, N, H, kvh, segments, T):
+    harness, lasp, si = gpu
+    G = H // kvh
+    cfg = si.Config("group", B=2, H=H, N=N, D=D, chunk=64, dtype=dtype, seed=1100 + N + H)
+    say(f"case grouped dtype={dtype} D={D} N={N} H={H} kv_heads={kvh} segments={segments} T={T}")
+    inp = si.make_inputs(cfg, with_states=True)
+    inp.k, inp.v = np.ascontiguousarray(inp.k[:, :kvh]), np.ascontiguousarray(inp.v[:, :kvh])
+    inp.decay = np.linspace(0.9, 1.0, H).astype(np.float32)
+    got = harness.run_gpu(inp, T=T, segments=segments)
+    ke, ve = oracle.group_expand(inp.k, G), oracle.group_expand(inp.v, G)
+    o, kvo = oracle.fwd_brute(inp.q, ke, ve, inp.decay, inp.kv_in)
+    dq, dk, dv, gin = oracle.bwd_brute(inp.q, ke, ve, inp.dout, inp.decay, inp.kv_in, inp.dkv_out)
+    ref = dict(out=o, kv_out=kvo, dq=dq, dk=oracle.group_reduce(dk, G), dv=oracle.group_reduce(dv, G), dkv_in=gin)
+    check(harness, got, ref, TOL[dtype], f"group/{dtype}")
+
+
+def test_token_decay_and_norm(gpu, oracle):
+    """Grouped heads with a decay per token and the fused Norm (every option at once)."""
+    harness, lasp, si = gpu
+    H, kvh, N, D, eps = 4, 2, 64 * 6, 128, 1e-5
+    G = H // kvh
+    cfg = si.Config("groupg", B=1, H=H, N=N, D=D, chunk=64, dtype="bf16", seed=1201, token_decay=True)
+    inp = si.make_inputs(cfg, with_states=True)
+    inp.k, inp.v = np.ascontiguousarray(inp.k[:, :kvh]), np.ascontiguousarray(inp.v[:, :kvh])
+    rng = np.random.default_rng(cfg.seed)
+    inp.log_g = np.log(rng.uniform(0.85, 1.0, (1, H, N))).astype(np.float32)
+    got = harness.run_gpu(inp, T=1, norm_eps=eps)
+    ke, ve = oracle.group_expand(inp.k, G), oracle.group_expand(inp.v, G)
+    o, kvo = oracle.gated_fwd_brute(inp.q, ke, ve, inp.log_g, inp.kv_in)
+    y, rstd = oracle.norm_fwd(o, eps)
+    dq, dk, dv, dlg, gin = oracle.gated_bwd_brute(inp.q, ke, ve, oracle.norm_bwd(inp.dout, y, rstd), inp.log_g,
+                                                  inp.kv_in, inp.dkv_out)
+    ref = dict(out=y, rstd=rstd, kv_out=kvo, dq=dq, dk=oracle.group_reduce(dk, G), dv=oracle.group_reduce(dv, G),
+               dlog_g=dlg, dkv_in=gin)
+    check(harness, got, ref, TOL["bf16"], "group/gated+norm")
