@@ -118,6 +118,19 @@ def main():
         t1 = time.perf_counter()
         kernel_ms, nf, nb = lasp.profile_end()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
+    graph_ms = None
+    if not args.graph:   # for information: the same steps as replays of one HIP graph (not `value`)
+        from paper_2404_02882_amd.sequence import GraphedStep
+        graphed = GraphedStep(seq, dict(q=q, k=k, v=v, decay=decay, out=out, rstd=rstd),
+                              dict(q=q, k=k, v=v, dout=do, decay=decay, dq=dq, dk=dk, dv=dv, dlog_g=dlg, out=out, rstd=rstd))
+        for _ in range(args.warmup):
+            graphed.replay()
+        torch.cuda.synchronize()
+        g0 = time.perf_counter()
+        for _ in range(args.steps):
+            graphed.replay()
+        torch.cuda.synchronize()
+        graph_ms = (time.perf_counter() - g0) * 1e3 / args.steps
     tokens_per_s = B * N / (ms_per_step * 1e-3)
 
     # ---- roofline of the dominant kernel (largest share of the step) ----
@@ -152,7 +165,8 @@ def main():
     flops_step = (14 * cfg.chunk * D + 12 * D * D) * B * H * N
     min_bytes_step = (11 * D * esz + 3 * gb + (D * esz + 8 if norm else 0)) * B * H * N
     step_s = ms_per_step * 1e-3
-    extra = {"algorithmic_tflops": round(flops_step / step_s / 1e12, 2),
+    extra = {"hip_graph_replay_ms_per_step": round(graph_ms, 4) if graph_ms is not None else None,
+             "algorithmic_tflops": round(flops_step / step_s / 1e12, 2),
              "mfma_bf16_peak_frac": round(flops_step / step_s / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
              "min_hbm_bytes_per_step": min_bytes_step,
              "step_hbm_frac_at_min_bytes": round(min_bytes_step / step_s / 1e9 / HBM_PEAK_GBS, 4)}
