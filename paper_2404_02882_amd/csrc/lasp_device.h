@@ -168,7 +168,7 @@ struct Elem<bf16_t> {
     typedef bf16x8 frag;
     static constexpr int KSTEP = 16;
     static constexpr int NSUB = 2;
-    static constexpr int PAD = 24;  // row stride = 12 banks mod 64: conflict-free 16-byte row reads, disjoint 4-row transposing reads
+    static constexpr int PAD = 8;   // 64-wide rows: stride 72 elements = 36 banks, an odd multiple of 4: the 16-byte reads of 16 consecutive rows and the 8-byte pieces of a transposing read over 4 rows fall on disjoint banks
     static DEVI f32x16 mfma(frag a, frag b, f32x16 c) { return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0); }
     // row0 is a multiple of 16 and k0 a multiple of 16 wherever these are called.
     static DEVI frag ld_kc(const Lane &ln, const bf16_t *X, int ld, int row0, int k0) {

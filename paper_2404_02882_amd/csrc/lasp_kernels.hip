@@ -1009,22 +1009,34 @@ __global__ __launch_bounds__(D * 4) void k_bwd8p(const T *__restrict__ Q, const 
     };
     NormTile<T, CT, D, NT> mnX;  // NORM: partner of moX (dO is dY; see NormTile)
     const float *rstd_c = rstd + (size_t)chain * ntok;
-    auto load_pair = [&](int tE) {
+    // The requests for a pair come in two parts. K and V of both tiles go into registers that are idle
+    // from the top of an iteration on, so inside the loop they are issued a whole tile early (during
+    // the O tile of the pair before); dO, Q of the O tile and the cached state follow once the E tile
+    // of the pair before has taken their registers' contents. Fewer requests are then issued in one
+    // burst, which is where the waves stall at the memory pipeline's entry.
+    auto load_pair_kv = [&](int tE) {
         const size_t oE = base + (size_t)tE * TS, oO = oE + TS;
-        if constexpr (NORM) mnX.load(yn + oO, rstd_c + (size_t)(tE + 1) * CT);
-        // only the O tile of the last pair can be short (per-token decay only)
+        const int nvO = TOKEN ? min(CT, ntok - (tE + 1) * CT) : CT;   // only the O tile of the last pair can be short
+        mvO.load(V + oO, nvO);
+        mkO.load(K + oO, nvO);
+        mvE.load(V + oE);
+        mkE.load(K + oE);
+    };
+    auto load_pair_rest = [&](int tE) {
+        const size_t oE = base + (size_t)tE * TS, oO = oE + TS;
         const int nvO = TOKEN ? min(CT, ntok - (tE + 1) * CT) : CT;
+        if constexpr (NORM) mnX.load(yn + oO, rstd_c + (size_t)(tE + 1) * CT);
         if constexpr (TOKEN) {
             lgO = TokenDecay<T, CT>::fetch(lg + (size_t)(tE + 1) * CT, nvO);
             lgE = TokenDecay<T, CT>::fetch(lg + (size_t)tE * CT);
         }
-        mvO.load(V + oO, nvO);
         moX.load(dO + oO, nvO);
-        mkO.load(K + oO, nvO);
         mqX.load(Q + oO, nvO);
-        mvE.load(V + oE);
-        mkE.load(K + oE);
         mc.load(ctile + (size_t)(tE / 2) * D * D);
+    };
+    auto load_pair = [&](int tE) {
+        load_pair_kv(tE);
+        load_pair_rest(tE);
     };
     load_pair(t1 - 2);
 
@@ -1183,6 +1195,7 @@ __global__ __launch_bounds__(D * 4) void k_bwd8p(const T *__restrict__ Q, const 
         mvE.store(sVE, LDD);
         mkE.store(sKE, LDD);
         mc.store(sC, LDD);   // mc keeps the cached state in registers for the E tile
+        if (tE > t0) load_pair_kv(tE - 2);
         __syncthreads();
         ln = fresh_lane();
         PHASE(1);
@@ -1235,7 +1248,7 @@ __global__ __launch_bounds__(D * 4) void k_bwd8p(const T *__restrict__ Q, const 
         __syncthreads();
         ln = fresh_lane();
         PHASE(8);
-        if (tE > t0) load_pair(tE - 2);
+        if (tE > t0) load_pair_rest(tE - 2);
         PHASE(9);
         // ---- E tile ----
         scores(decE, sVE, sKE);
