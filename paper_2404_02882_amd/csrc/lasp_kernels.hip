@@ -924,19 +924,22 @@ __global__ __launch_bounds__(D * 4) void k_bwd8(const T *__restrict__ Q, const T
 // k_bwd8p: k_bwd8 for a state cache that holds one state per PAIR of tiles
 // (half the cache traffic of both passes). Tiles are walked in reverse as pairs
 // (E = even tile, O = the odd tile after it). The cache gives KV at the start
-// of E. The O tile needs the state one tile later,
-//     KV_mid = lambda^CT KV + (diag{lambda^(CT-1-j)} K_E)^T V_E   (state update of Sec. 3.2),
-// which the workgroup rebuilds in place in LDS from K_E, V_E; these are needed for
-// the E tile anyway and are simply fetched one tile early. After the O tile the
-// cached state is written to LDS again (it is still in registers) for the E tile.
-// Per pair: six barriers, 9 tile loads, one cache-tile load.
+// of E. The O tile's dQ needs the state one tile later,
+//     KV_mid = lambda^CT KV + (diag{lambda^(CT-1-j)} K_E)^T V_E   (state update of Sec. 3.2);
+// instead of rebuilding it, dQ of the O tile treats the pair as one chunk of 2 CT
+// tokens (Alg. 3 with C = 2 CT, restricted to the rows of the O tile):
+//     dQ_O = Lambda' dO_O KV^T + [(dO_O V_E^T) (.) M'] K_E + [(dO_O V_O^T) (.) M] K_O,
+// Lambda'_i = lambda^(CT+i), M'_ij = lambda^(CT+i-j): one more masked score tile
+// (sDX) and four more contraction steps, and the cached tile stays in LDS for
+// both tiles. K_E, V_E are needed for the E tile anyway and are simply fetched
+// one tile early. Per pair: six barriers, 9 tile loads, one cache-tile load.
 // ---------------------------------------------------------------------------
 template <typename T, int CT, int D>
 struct Bwd8pSmem {
     static constexpr int LDD = tile_ld<T, D>(), LDP = CT + Elem<T>::PAD;
     static constexpr size_t TILE = (size_t)CT * LDD * sizeof(T);
     static constexpr size_t P_OFF = 6 * TILE;
-    static constexpr size_t C_OFF = P_OFF + 2 * (size_t)CT * LDP * sizeof(T);
+    static constexpr size_t C_OFF = P_OFF + 3 * (size_t)CT * LDP * sizeof(T);   // S, dS and the cross tile dS(O x E)
     static constexpr size_t PW_OFF = C_OFF + (size_t)D * LDD * sizeof(T);
     // decay tables of the O tile and of the E tile, then one row of per-token partial sums per wave
     static constexpr size_t TOTAL = PW_OFF + (6 * CT + 4 + 8 * CT) * sizeof(float);
@@ -966,6 +969,7 @@ __global__ __launch_bounds__(D * 4) void k_bwd8p(const T *__restrict__ Q, const 
     T *sKE = sVE + CT * LDD;       // K of the E tile
     T *sS = (T *)(smem + SM::P_OFF);
     T *sDS = sS + CT * LDP;
+    T *sDX = sDS + CT * LDP;       // masked dS between the O tile's queries and the E tile's keys
     T *sC = (T *)(smem + SM::C_OFF);
     float *pw = (float *)(smem + SM::PW_OFF);
 
@@ -995,6 +999,19 @@ __global__ __launch_bounds__(D * 4) void k_bwd8p(const T *__restrict__ Q, const 
         if constexpr (TOKEN) return TokenDecay<T, CT>(pw + 3 * CT);
         else return decO;
     }();
+    if constexpr (!TOKEN) {   // lambda^(CT+1) .. lambda^(2 CT): weights between the two tiles of a pair
+        const float lam = decay[chain % H];
+        for (int i = CT + 1 + threadIdx.x; i <= 2 * CT; i += blockDim.x) pw[i] = (float)exp2((double)i * log2((double)lam));
+    }
+    // weight key j of the E tile carries at query i of the O tile, and the E tile's entering state at query i
+    auto cross_weight = [&](int i, int j) {
+        if constexpr (TOKEN) return decO.upto(i) * decE.after(j);
+        else return pw[CT + i - j];
+    };
+    auto far_upto = [&](int i) {
+        if constexpr (TOKEN) return decO.upto(i) * decE.whole();
+        else return pw[CT + i + 1];
+    };
     const float *lg = decay + (size_t)chain * ntok;
     typename TokenDecay<T, CT>::LogG lgO = {}, lgE = {};
     // per-token decay: r_t = q_t.dq_t - k_t.dk_t, one partial row per wave, summed and written per tile
@@ -1021,6 +1038,7 @@ __global__ __launch_bounds__(D * 4) void k_bwd8p(const T *__restrict__ Q, const 
         mkO.load(K + oO, nvO);
         mvE.load(V + oE);
         mkE.load(K + oE);
+        mc.load(ctile + (size_t)(tE / 2) * D * D);
     };
     auto load_pair_rest = [&](int tE) {
         const size_t oE = base + (size_t)tE * TS, oO = oE + TS;
@@ -1032,7 +1050,6 @@ __global__ __launch_bounds__(D * 4) void k_bwd8p(const T *__restrict__ Q, const 
         }
         moX.load(dO + oO, nvO);
         mqX.load(Q + oO, nvO);
-        mc.load(ctile + (size_t)(tE / 2) * D * D);
     };
     auto load_pair = [&](int tE) {
         load_pair_kv(tE);
@@ -1065,6 +1082,41 @@ __global__ __launch_bounds__(D * 4) void k_bwd8p(const T *__restrict__ Q, const 
     }
 
     // masked score tiles of the tile whose V, K are at pV, pK (dO, Q in sdO, sQ): one 32x32 block per wave
+    // The O tile's queries against the E tile's keys: dSX^T[j][i] = sum_c V_E[j][c] dO_O[i][c], all four
+    // 32x32 blocks, weighted and stored as sDX[i][j]. Two blocks go to the two waves that have no
+    // triangular block, one each to two waves of group 0.
+    auto cross_scores = [&]() {
+#pragma unroll
+        for (int blk = 0; blk < 4; ++blk) {
+            const int owner = blk < 2 ? 6 + blk : blk;   // waves 6, 7, 2, 3
+            if (owner % (2 * NW) != w8) continue;
+            const int ib = blk >> 1, jb = blk & 1;
+            f32x16 acc = {0}, acc2 = {0};
+            pipelined<NKD / 2>(
+                [&](int s2) {
+                    FragPair<FragPair<F>> f;
+                    f.a.a = E::ld_kc(ln, sVE, LDD, 32 * jb, 2 * s2 * E::KSTEP);
+                    f.a.b = E::ld_kc(ln, sdO, LDD, 32 * ib, 2 * s2 * E::KSTEP);
+                    f.b.a = E::ld_kc(ln, sVE, LDD, 32 * jb, (2 * s2 + 1) * E::KSTEP);
+                    f.b.b = E::ld_kc(ln, sdO, LDD, 32 * ib, (2 * s2 + 1) * E::KSTEP);
+                    return f;
+                },
+                [&](int, const FragPair<FragPair<F>> &f) {
+                    acc = E::mfma(f.a.a, f.a.b, acc);
+                    acc2 = E::mfma(f.b.a, f.b.b, acc2);
+                });
+            acc += acc2;
+            const int iq = 32 * ib + ln.r;
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const int j0 = 32 * jb + 8 * g + 4 * ln.h;
+                float x[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) x[e] = acc[4 * g + e] * cross_weight(iq, j0 + e);
+                E::st4(sDX + iq * LDP + j0, x[0], x[1], x[2], x[3]);
+            }
+        }
+    };
     auto scores = [&](const auto &dec, const T *pV, const T *pK) {
         constexpr int NTRI = 3;
 #pragma unroll
@@ -1092,7 +1144,9 @@ __global__ __launch_bounds__(D * 4) void k_bwd8p(const T *__restrict__ Q, const 
     };
 
     // dQ, this group's dV or dK, and the dKV update for the tile at element offset `off`
-    auto products = [&](const auto &dec, const T *pV, const T *pK, size_t off, int nrows) {
+    // `cross` (the O tile): the cached state is the one the E tile starts from, so dQ takes the E tile
+    // as the first half of its own chunk: far weights on the state term, plus the E tile's keys through sDX.
+    auto products = [&](const auto &dec, const T *pV, const T *pK, size_t off, int nrows, bool cross) {
         const T *sX1 = rg ? pV : pK;  // inter operand: token rows, features contracted with the state
         float rq = 0.0f;  // per-token decay: q_i . dq_i over this wave's features, tokens i of block rg
         {   // dQ^T[a in w][i], tokens i of block rg
@@ -1101,9 +1155,13 @@ __global__ __launch_bounds__(D * 4) void k_bwd8p(const T *__restrict__ Q, const 
             pipelined<NKD>(
                 [&](int ks) { return FragPair<F>{E::ld_kc(ln, sC, LDD, 32 * w, ks * E::KSTEP), E::ld_kc(ln, sdO, LDD, r0, ks * E::KSTEP)}; },
                 [&](int, const FragPair<F> &f) { acc = E::mfma(f.a, f.b, acc); });
-            acc *= dec.upto(r0 + ln.r);
-            auto intra = [&](int ks) { return FragPair<F>{E::ld_ks(ln, pK, LDD, ks * E::KSTEP, 32 * w), E::ld_kc(ln, sDS, LDP, r0, ks * E::KSTEP)}; };
+            acc *= cross ? far_upto(r0 + ln.r) : dec.upto(r0 + ln.r);
             auto fma = [&](int, const FragPair<F> &f) { acc = E::mfma(f.a, f.b, acc); };
+            if (cross)
+                pipelined<NKS>(
+                    [&](int ks) { return FragPair<F>{E::ld_ks(ln, sKE, LDD, ks * E::KSTEP, 32 * w), E::ld_kc(ln, sDX, LDP, r0, ks * E::KSTEP)}; },
+                    fma);
+            auto intra = [&](int ks) { return FragPair<F>{E::ld_ks(ln, pK, LDD, ks * E::KSTEP, 32 * w), E::ld_kc(ln, sDS, LDP, r0, ks * E::KSTEP)}; };
             if (rg == 0) pipelined<SPB>(intra, fma);
             else pipelined<2 * SPB>(intra, fma);
             store_out_tile_t<T, D>(ln, dQ + off, acc, r0, w, nrows);
@@ -1194,7 +1252,7 @@ __global__ __launch_bounds__(D * 4) void k_bwd8p(const T *__restrict__ Q, const 
         mqX.store(sQ, LDD);
         mvE.store(sVE, LDD);
         mkE.store(sKE, LDD);
-        mc.store(sC, LDD);   // mc keeps the cached state in registers for the E tile
+        mc.store(sC, LDD);   // the state the E tile starts from serves both tiles of the pair
         if (tE > t0) load_pair_kv(tE - 2);
         __syncthreads();
         ln = fresh_lane();
@@ -1206,45 +1264,20 @@ __global__ __launch_bounds__(D * 4) void k_bwd8p(const T *__restrict__ Q, const 
         // ---- O tile ----
         scores(decO, sVO, sKO);
         PHASE(3);
-        {   // sC <- KV_mid, in place: block (cb, ab) of KV_mid^T[c][a] = lambda^CT KV^T + sum_j V_E[j][c] (w_j K_E[j][a])
-            constexpr int NBLK = DB * DB, PER = (NBLK + 2 * NW - 1) / (2 * NW);
-            const float lamC = decE.whole();
-#pragma unroll
-            for (int u = 0; u < PER; ++u) {
-                const int blk = w8 * PER + u;
-                if (blk >= NBLK) continue;
-                const int cb = blk / DB, ab = blk % DB;
-                f32x16 acc = {0};
-                pipelined<NKS>(
-                    [&](int ks) { return FragPair<F>{E::ld_ks(ln, sVE, LDD, ks * E::KSTEP, 32 * cb), E::ld_ks(ln, sKE, LDD, ks * E::KSTEP, 32 * ab)}; },
-                    [&](int ks, const FragPair<F> &f) {
-                        acc = E::mfma(f.a, decE.weigh_after(ln, f.b, ks), acc);
-                    });
-                // lane r holds a = 32 ab + r and, per register group q, c = 32 cb + 8 q + 4 h + (0..3)
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    T *pc = sC + lds_off(LDD, 32 * ab + ln.r, 32 * cb + 8 * q + 4 * ln.h);
-                    float o[4];
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) o[e] = lamC * E::ld1(pc + e) + acc[4 * q + e];
-                    E::st4(pc, o[0], o[1], o[2], o[3]);
-                }
-            }
-        }
+        cross_scores();
         PHASE(4);
         __syncthreads();
         ln = fresh_lane();
         PHASE(5);
-        products(decO, sVO, sKO, offO, TOKEN ? min(CT, ntok - (tE + 1) * CT) : CT);
+        products(decO, sVO, sKO, offO, TOKEN ? min(CT, ntok - (tE + 1) * CT) : CT, true);
         PHASE(6);
-        __syncthreads();  // O tile consumed: sdO, sQ, sC are free
+        __syncthreads();  // O tile consumed: sdO, sQ are free
         ln = fresh_lane();
         PHASE(7);
         if constexpr (TOKEN) flush_r(tE + 1);
         if constexpr (NORM) mnX.apply(moX);
         moX.store(sdO, LDD);
         mqX.store(sQ, LDD);
-        mc.store(sC, LDD);
         __syncthreads();
         ln = fresh_lane();
         PHASE(8);
@@ -1256,7 +1289,7 @@ __global__ __launch_bounds__(D * 4) void k_bwd8p(const T *__restrict__ Q, const 
         __syncthreads();
         ln = fresh_lane();
         PHASE(11);
-        products(decE, sVE, sKE, offE, CT);
+        products(decE, sVE, sKE, offE, CT, false);
         PHASE(12);
     }
     PHASE_FLUSH();
