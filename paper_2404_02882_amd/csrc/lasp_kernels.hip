@@ -1588,10 +1588,10 @@ hipError_t launch_fill_logg(const Plan &p, const float *decay, float *log_g, hip
 }
 
 #ifdef LASP_PHASE_TIMING
-extern "C" int lasp_debug_phases(unsigned long long *out32, int reset) {
-    if (out32 && hipMemcpyFromSymbol(out32, HIP_SYMBOL(g_phase_cycles), sizeof(g_phase_cycles)) != hipSuccess) return 1;
+extern "C" int lasp_debug_phases(unsigned long long *out256, int reset) {
+    if (out256 && hipMemcpyFromSymbol(out256, HIP_SYMBOL(g_phase_cycles), sizeof(g_phase_cycles)) != hipSuccess) return 1;
     if (reset) {
-        unsigned long long z[32] = {};
+        unsigned long long z[8 * 32] = {};
         if (hipMemcpyToSymbol(HIP_SYMBOL(g_phase_cycles), z, sizeof(z)) != hipSuccess) return 1;
     }
     return 0;
