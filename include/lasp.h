@@ -101,8 +101,9 @@ int32_t lasp_num_segments(const lasp_shape *shape);
  * Bytes of the state cache: the states KV_{t-1} that tiles start from, written
  * by lasp_fwd and read by lasp_bwd for dQ_inter (the paper caches the state a
  * rank receives, Alg. 2 "save KV_{t-1}", Sec. 3.4; this build caches one state
- * per tile, or one per two tiles where the backward kernel rebuilds the other
- * on chip, so that the backward pass never reruns the forward recurrence).
+ * per tile, or one per two tiles where the backward kernel reaches the other
+ * tile from its neighbour's state, so that the backward pass never reruns the
+ * forward recurrence).
  * The layout is private to the library; slot 0 is kv_in. Stored in `dtype`.
  * 0 on an invalid shape.
  */

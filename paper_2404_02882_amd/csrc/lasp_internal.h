@@ -67,7 +67,7 @@ struct KernelEvents {
 // Tile length used for a (dtype, chunk, D) combination.
 int tile_tokens(int dtype, int chunk, int D);
 // Cache stride for a shape: 2 (one cached state per pair of tiles, the backward
-// walk rebuilds the other) when the kernels support it, else 1.
+// walk reaches the other tile from its neighbour's state) when the kernels support it, else 1.
 int cache_stride_for(int dtype, int tile, int ntiles, bool token);
 
 // log_g[b][h][s] = log(decay[h]) for all N tokens (device buffers).
