@@ -26,11 +26,11 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X published dense bf16 MFMA rate
 # FETCH_SIZE x 2.000, WRITE_SIZE x 1.000), for the default launch configuration. Other configs: None.
 _MIB = 2**20
 MEASURED_TRAFFIC_BYTES = {
-    "c3": {"fwd_walk": int((416.2 + 258.3) * _MIB), "bwd_walk": int((660.9 + 385.0) * _MIB),
+    "c3": {"fwd_walk": int((416.2 + 258.1) * _MIB), "bwd_walk": int((659.1 + 385.0) * _MIB),
            "fwd_local": int((248.1 + 31.0) * _MIB), "bwd_local": int((240.1 + 15.0) * _MIB)},
-    "g3": {"fwd_walk": int((418.2 + 257.5) * _MIB), "bwd_walk": int((659.8 + 387.0) * _MIB),
+    "g3": {"fwd_walk": int((418.2 + 257.4) * _MIB), "bwd_walk": int((659.4 + 387.0) * _MIB),
            "fwd_local": int((250.1 + 31.0) * _MIB), "bwd_local": int((242.0 + 15.0) * _MIB)},
-    "n3": {"fwd_walk": int((416.2 + 260.6) * _MIB), "bwd_walk": int((821.8 + 387.0) * _MIB),
+    "n3": {"fwd_walk": int((416.2 + 260.6) * _MIB), "bwd_walk": int((789.1 + 385.0) * _MIB),
            "fwd_local": int((248.1 + 31.0) * _MIB), "bwd_local": int((362.0 + 15.0) * _MIB)},
 }
 
