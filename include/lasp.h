@@ -191,7 +191,7 @@ int lasp_gated_bwd(const lasp_shape *shape, const void *q, const void *k, const 
 
 /*
  * ---- Normalised output ------------------------------------------------------
- * O = Norm((Q K^T (.) M) V) (Sec. 2, linear-attention paragraph; Sec. 3.2 drops
+ * O = Norm((Q K^T (.) M) V) (Sec. 3.1, Eq. (2); Sec. 3.2 drops
  * the Norm only to shorten its derivation). The paper does not spell Norm out;
  * here it is the parameter-free root-mean-square normalisation of every output
  * row over the head dimension,

@@ -354,7 +354,7 @@ def gated_bwd_split(bwd_fn, q, k, v, dout, log_g, T, kv_ins, dkv_out=None, **kw)
 
 
 # ---------------------------------------------------------------------------
-# Norm(.) of the normalised linear attention O = Norm((Q K^T (.) M) V) (Sec. 2,
+# Norm(.) of the normalised linear attention O = Norm((Q K^T (.) M) V) (Sec. 3.1, Eq. (2),
 # linear-attention paragraph): read as the parameter-free root-mean-square
 # normalisation of every output row over the head dimension,
 #     y_s = o_s / sqrt(mean_c o_s[c]^2 + eps).
@@ -393,3 +393,62 @@ def group_reduce(dx, G):
     dx = _d(dx)
     B, H, N, D = dx.shape
     return dx.reshape(B, H // int(G), int(G), N, D).sum(axis=2)
+
+
+# ---------------------------------------------------------------------------
+# Bidirectional (unmasked) linear attention, Sec. 3.1: without the causal mask
+# the attention is O = (Q K^T) V, which associativity turns into the
+# right-product form O = Q (K^T V) of Eq. (3) (both without the Norm, which
+# composes as above). No decay, no order among the tokens: the d x d state
+# K^T V is a plain sum over every token of the sequence.
+# `*_left` is the definition (N x N scores); `*_right` is Eq. (3).
+# ---------------------------------------------------------------------------
+def _t(x):
+    return np.swapaxes(x, -1, -2)
+
+
+def bidir_fwd_left(q, k, v):
+    """O = (Q K^T) V per (batch, head): the definition, with the N x N score matrix."""
+    q, k, v = _d(q), _d(k), _d(v)
+    return np.matmul(np.matmul(q, _t(k)), v)
+
+
+def bidir_state(x, y):
+    """[B,H,N,D] x [B,H,N,D] -> [B,H,D,D]: sum over tokens of x_s y_s^T (K^T V of Eq. (3))."""
+    return np.matmul(_t(_d(x)), _d(y))
+
+
+def bidir_fwd_right(q, kv):
+    """O = Q KV, Eq. (3), for a given state KV [B,H,D,D]."""
+    return np.matmul(_d(q), _d(kv))
+
+
+def bidir_bwd_left(q, k, v, dout):
+    """Gradients of sum(O * dout) for O = (Q K^T) V, from the N x N matrices S = Q K^T and dS = dout V^T:
+    dQ = dS K, dK = dS^T Q, dV = S^T dout."""
+    q, k, v, dout = _d(q), _d(k), _d(v), _d(dout)
+    s = np.matmul(q, _t(k))
+    ds = np.matmul(dout, _t(v))
+    return np.matmul(ds, k), np.matmul(_t(ds), q), np.matmul(_t(s), dout)
+
+
+def bidir_fwd_rows(q, k, v, rows):
+    """Sampled output rows from the definition: o_s = sum_i (q_s . k_i) v_i. rows: [n,3] of (b,h,s)."""
+    q, k, v = _d(q), _d(k), _d(v)
+    out = np.empty((len(rows), q.shape[-1]))
+    for n, (b, h, s) in enumerate(np.asarray(rows, dtype=np.int64)):
+        out[n] = (k[b, h] @ q[b, h, s]) @ v[b, h]
+    return out
+
+
+def bidir_bwd_rows(q, k, v, dout, rows):
+    """Sampled gradient rows from the definition:
+    dq_s = sum_i (do_s . v_i) k_i, dk_s = sum_i (do_i . v_s) q_i, dv_s = sum_i (q_i . k_s) do_i."""
+    q, k, v, dout = _d(q), _d(k), _d(v), _d(dout)
+    D = q.shape[-1]
+    dq, dk, dv = (np.empty((len(rows), D)) for _ in range(3))
+    for n, (b, h, s) in enumerate(np.asarray(rows, dtype=np.int64)):
+        dq[n] = (v[b, h] @ dout[b, h, s]) @ k[b, h]
+        dk[n] = (dout[b, h] @ v[b, h, s]) @ q[b, h]
+        dv[n] = (q[b, h] @ k[b, h, s]) @ dout[b, h]
+    return dq, dk, dv

@@ -311,7 +311,7 @@ struct TileMover {
 };
 
 // ---------------------------------------------------------------------------
-// Norm(.) of the normalised linear attention O = Norm((Q K^T (.) M) V) (Sec. 2),
+// Norm(.) of the normalised linear attention O = Norm((Q K^T (.) M) V) (Sec. 3.1, Eq. (2)),
 // taken as the parameter-free root-mean-square normalisation of an output row:
 //     y = o * rstd,  rstd = (mean_c o[c]^2 + eps)^(-1/2).
 // Backward, applied to a tile of dY while it is still in registers on its way to

@@ -1,5 +1,5 @@
 """Pins of the oracle's Norm(.) (root-mean-square normalisation of every output row, the reading of the
-Norm in O = Norm((Q K^T (.) M) V) of Sec. 2) to things other than itself (CPU only)."""
+Norm in O = Norm((Q K^T (.) M) V) of Sec. 3.1, Eq. (2)) to things other than itself (CPU only)."""
 import numpy as np
 import pytest
 
