@@ -233,6 +233,51 @@ int lasp_gated_bwd_norm(const lasp_shape *shape, const void *q, const void *k, c
                         size_t scratch_bytes, void *hip_stream);
 
 /*
+ * ---- Bidirectional (unmasked) attention ---------------------------------------
+ * Without the causal mask the attention of Sec. 3.1 is O = (Q K^T) V, which
+ * associativity turns into the right-product form O = Q (K^T V) of Eq. (3)
+ * (here without the Norm). There is no decay and no order among the tokens:
+ * the d x d state is the plain sum KV = sum_s k_s v_s^T over EVERY token of the
+ * sequence, so sub-sequences do not form a chain. Each adds its tokens to the
+ * state (on several devices: one sum of a [B][H][D][D] float tensor across
+ * them), and only then does any of them compute its outputs:
+ *     forward : KV  = sum_s k_s v_s^T     (lasp_bidir_state on K, V, once per sub-sequence)
+ *               O   = Q KV                (lasp_bidir_fwd)
+ *     backward: dKV = sum_s q_s do_s^T    (lasp_bidir_state on Q, dO, once per sub-sequence)
+ *               dQ  = dO KV^T,  dK = V dKV^T,  dV = K dKV    (lasp_bidir_bwd)
+ * The paper states the formula only; the split into these calls, and summing
+ * the state across sub-sequences instead of handing it round a ring, are this
+ * library's reading of it.
+ *
+ * Shapes as in lasp_shape with kv_heads 0 or H (LASP_ERR_SHAPE otherwise);
+ * `chunk` must be a valid chunk length but has no effect; any N >= 1;
+ * `segments`: 0 = automatic, else the number of partial sums per head of the
+ * state reduction (1 <= segments <= ceil(N / tile)). Token tensors
+ * [B][H][N][D] in `dtype`, states [B][H][D][D] float with rows indexed by the
+ * FIRST factor's feature (k, resp. q), all in DEVICE memory, 16-byte aligned,
+ * outputs not overlapping inputs or each other. Statuses and asynchrony as for
+ * lasp_fwd. Products run on MFMA in `dtype` with fp32 accumulation; a state is
+ * rounded to `dtype` where it enters a product.
+ */
+/* Bytes of scratch lasp_bidir_state needs (partial sums); 0 on an invalid shape. */
+size_t lasp_bidir_scratch_bytes(const lasp_shape *shape);
+/*
+ * state (+)= sum over this sub-sequence's tokens s of x_s y_s^T, per head.
+ *   accumulate  0: state is overwritten; otherwise the sum is added to it (the
+ *               second and later sub-sequences, or a state received from elsewhere).
+ * Partial sums are added in a fixed order: bit-reproducible.
+ */
+int lasp_bidir_state(const lasp_shape *shape, const void *x, const void *y, float *state,
+                     int32_t accumulate, void *scratch, size_t scratch_bytes, void *hip_stream);
+/* out = q kv for every head: [N][D] x [D][D]. */
+int lasp_bidir_fwd(const lasp_shape *shape, const void *q, const float *kv, void *out,
+                   void *hip_stream);
+/* dq = dout kv^T, dk = v dkv^T, dv = k dkv (kv, dkv: the complete states of the whole sequence). */
+int lasp_bidir_bwd(const lasp_shape *shape, const void *k, const void *v, const void *dout,
+                   const float *kv, const float *dkv, void *dq, void *dk, void *dv,
+                   void *hip_stream);
+
+/*
  * Per-kernel timing, for benchmarks (diagnostic; not on the hot path, not
  * thread-safe). Between lasp_profile_begin and lasp_profile_end every
  * lasp_fwd / lasp_bwd call records HIP events around its three kernels on the
@@ -241,7 +286,10 @@ int lasp_gated_bwd_norm(const lasp_shape *shape, const void *q, const void *k, c
  * the summed milliseconds per kernel
  *     ms_sum[0..2] = forward  {local pass, scan, tile walk}
  *     ms_sum[3..5] = backward {local pass, scan, tile walk}
- * and the number of recorded calls, and releases the events.
+ * and the number of recorded calls, and releases the events. The bidirectional
+ * calls record too: lasp_bidir_state as a forward call (reduction under "local
+ * pass", sum of the partials under "scan"), lasp_bidir_fwd as a forward call and
+ * lasp_bidir_bwd as a backward call (their one kernel under "tile walk").
  * begin: LASP_ERR_SHAPE if max_calls <= 0 or profiling is already on,
  * LASP_ERR_HIP if events cannot be created. end: LASP_ERR_NULL on NULL
  * arguments, LASP_ERR_SHAPE if profiling is off.

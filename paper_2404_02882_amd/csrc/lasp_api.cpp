@@ -245,11 +245,38 @@ int run_bwd_call(const BwdCall &c) {
     return lasp::launch_bwd(p, a, stream, next_slot(1)) == hipSuccess ? LASP_OK : LASP_ERR_HIP;
 }
 
+// Bidirectional path: shape rules of the causal path, own K/V head per query head only.
+int make_bidir_plan(const lasp_shape *s, lasp::BidirPlan *p) {
+    if (!s) return LASP_ERR_NULL;
+    if (s->dtype != LASP_F32 && s->dtype != LASP_BF16) return LASP_ERR_DTYPE;
+    if (!valid_dims(s)) return LASP_ERR_SHAPE;
+    if (s->kv_heads != 0 && s->kv_heads != s->H) return LASP_ERR_SHAPE;
+    p->B = s->B;
+    p->H = s->H;
+    p->N = s->N;
+    p->D = s->D;
+    p->dtype = s->dtype;
+    const int tile = lasp::bidir_reduce_tile(s->dtype);
+    p->ntiles_r = (s->N + tile - 1) / tile;
+    int want = s->segments;
+    if (want < 0 || want > p->ntiles_r) return LASP_ERR_SHAPE;
+    if (want == 0) {
+        const int64_t chains = (int64_t)s->B * s->H;
+        want = (int)((lasp::kBidirTargetWorkgroups + chains - 1) / chains);
+        if (want > p->ntiles_r) want = p->ntiles_r;
+    }
+    p->tiles_per_seg = (p->ntiles_r + want - 1) / want;
+    p->nseg = (p->ntiles_r + p->tiles_per_seg - 1) / p->tiles_per_seg;
+    return LASP_OK;
+}
+
+size_t bidir_scratch(const lasp::BidirPlan &p) { return (size_t)p.B * p.H * p.nseg * p.D * p.D * sizeof(float); }
+
 }  // namespace
 
 extern "C" {
 
-int lasp_version(void) { return 2; }
+int lasp_version(void) { return 3; }
 
 const char *lasp_status_str(int status) {
     switch (status) {
@@ -380,6 +407,54 @@ int lasp_gated_bwd_norm(const lasp_shape *shape, const void *q, const void *k, c
     BwdCall c{shape, q, k, v, dout, dkv_out, log_g, true, true, out, rstd, kv_out, state_cache, dq, dk, dv,
               dlog_g, dkv_in, scratch, scratch_bytes, hip_stream};
     return run_bwd_call(c);
+}
+
+size_t lasp_bidir_scratch_bytes(const lasp_shape *shape) {
+    lasp::BidirPlan p;
+    return make_bidir_plan(shape, &p) == LASP_OK ? bidir_scratch(p) : 0;
+}
+
+int lasp_bidir_state(const lasp_shape *shape, const void *x, const void *y, float *state, int32_t accumulate,
+                     void *scratch, size_t scratch_bytes, void *hip_stream) {
+    lasp::BidirPlan p;
+    int rc = make_bidir_plan(shape, &p);
+    if (rc != LASP_OK) return rc;
+    if (!x || !y || !state) return LASP_ERR_NULL;
+    if (!scratch || scratch_bytes < bidir_scratch(p)) return LASP_ERR_WORKSPACE;
+    const size_t tb = (size_t)p.B * p.H * p.N * p.D * elem_bytes(p.dtype);
+    const size_t sb = (size_t)p.B * p.H * p.D * p.D * sizeof(float);
+    rc = check_buffers({{x, tb}, {y, tb}}, {{state, sb}, {scratch, bidir_scratch(p)}});
+    if (rc != LASP_OK) return rc;
+    return lasp::launch_bidir_state(p, x, y, state, accumulate != 0, (float *)scratch, (hipStream_t)hip_stream,
+                                    next_slot(0)) == hipSuccess ? LASP_OK : LASP_ERR_HIP;
+}
+
+int lasp_bidir_fwd(const lasp_shape *shape, const void *q, const float *kv, void *out, void *hip_stream) {
+    lasp::BidirPlan p;
+    int rc = make_bidir_plan(shape, &p);
+    if (rc != LASP_OK) return rc;
+    if (!q || !kv || !out) return LASP_ERR_NULL;
+    const size_t tb = (size_t)p.B * p.H * p.N * p.D * elem_bytes(p.dtype);
+    const size_t sb = (size_t)p.B * p.H * p.D * p.D * sizeof(float);
+    rc = check_buffers({{q, tb}, {kv, sb}}, {{out, tb}});
+    if (rc != LASP_OK) return rc;
+    const lasp::BidirOps ops{{q, nullptr, nullptr}, {kv, nullptr, nullptr}, {out, nullptr, nullptr}, {0, 0, 0}};
+    return lasp::launch_bidir_apply(p, ops, 1, (hipStream_t)hip_stream, next_slot(0)) == hipSuccess ? LASP_OK : LASP_ERR_HIP;
+}
+
+int lasp_bidir_bwd(const lasp_shape *shape, const void *k, const void *v, const void *dout, const float *kv,
+                   const float *dkv, void *dq, void *dk, void *dv, void *hip_stream) {
+    lasp::BidirPlan p;
+    int rc = make_bidir_plan(shape, &p);
+    if (rc != LASP_OK) return rc;
+    if (!k || !v || !dout || !kv || !dkv || !dq || !dk || !dv) return LASP_ERR_NULL;
+    const size_t tb = (size_t)p.B * p.H * p.N * p.D * elem_bytes(p.dtype);
+    const size_t sb = (size_t)p.B * p.H * p.D * p.D * sizeof(float);
+    rc = check_buffers({{k, tb}, {v, tb}, {dout, tb}, {kv, sb}, {dkv, sb}}, {{dq, tb}, {dk, tb}, {dv, tb}});
+    if (rc != LASP_OK) return rc;
+    // dQ = dO KV^T, dK = V dKV^T, dV = K dKV
+    const lasp::BidirOps ops{{dout, v, k}, {kv, dkv, dkv}, {dq, dk, dv}, {1, 1, 0}};
+    return lasp::launch_bidir_apply(p, ops, 3, (hipStream_t)hip_stream, next_slot(1)) == hipSuccess ? LASP_OK : LASP_ERR_HIP;
 }
 
 int lasp_profile_begin(int32_t max_calls) {

@@ -75,5 +75,28 @@ hipError_t launch_fill_logg(const Plan &p, const float *decay, float *log_g, hip
 hipError_t launch_fwd(const Plan &p, const FwdArgs &a, hipStream_t stream, const KernelEvents *ke);
 hipError_t launch_bwd(const Plan &p, const BwdArgs &a, hipStream_t stream, const KernelEvents *ke);
 
+
+// Bidirectional (unmasked) path: O = Q (K^T V).
+struct BidirPlan {
+    int B, H, N, D, dtype;
+    int ntiles_r;        // ceil(N / reduce tile)
+    int nseg;            // segments per head of the state reduction (partial sums in scratch)
+    int tiles_per_seg;   // ceil(ntiles_r / nseg); every segment non-empty
+};
+// Up to three products Out = X S (trans == 0) or X S^T (trans != 0), S [B*H][D][D] float.
+struct BidirOps {
+    const void *x[3];
+    const float *s[3];
+    void *out[3];
+    int trans[3];
+};
+constexpr int kBidirTargetWorkgroups = 512;   // two 4-wave workgroups per CU
+int bidir_reduce_tile(int dtype);
+// events: ev[0]..ev[1] the reduction, ev[1]..ev[2] the sum of the partials
+hipError_t launch_bidir_state(const BidirPlan &p, const void *x, const void *y, float *state, int accumulate, float *part,
+                              hipStream_t stream, const KernelEvents *ke);
+// events: ev[2]..ev[3] the product kernel
+hipError_t launch_bidir_apply(const BidirPlan &p, const BidirOps &ops, int nops, hipStream_t stream, const KernelEvents *ke);
+
 }  // namespace lasp
 #endif

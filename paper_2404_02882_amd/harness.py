@@ -9,7 +9,7 @@ import numpy as np
 import torch
 
 from . import lasp
-from .sequence import LaspSequence
+from .sequence import BidirSequence, LaspSequence
 from .synth_inputs import Inputs, bf16_bits
 
 TORCH_DTYPE = {"f32": torch.float32, "bf16": torch.bfloat16}
@@ -78,5 +78,30 @@ def run_gpu(inp: Inputs, T: int = 1, segments: int = 0, backward: bool = True, c
         res.update(dq=to_host(dq), dk=to_host(dk), dv=to_host(dv), dkv_in=dkv_in.cpu().numpy().astype(np.float64))
         if token:
             res["dlog_g"] = to_host(dlg)
+    torch.cuda.synchronize()
+    return res
+
+
+def run_gpu_bidir(inp: Inputs, lengths=None, segments: int = 0, backward: bool = True, device="cuda") -> Dict[str, np.ndarray]:
+    """Bidirectional attention of the whole sequence cut into sub-sequences of the given lengths
+    (default: one); uses q, k, v, dout of `inp` only. Returns float64 host arrays."""
+    cfg = inp.cfg
+    B, H, N, D = inp.q.shape
+    lengths = [N] if lengths is None else list(lengths)
+    assert sum(lengths) == N
+    edges = np.concatenate([[0], np.cumsum(lengths)])
+    cut = lambda x: [to_device(x[:, :, a:b], cfg.dtype, device) for a, b in zip(edges[:-1], edges[1:])]
+    seq = BidirSequence(B, H, lengths, D, cfg.chunk, TORCH_DTYPE[cfg.dtype], segments=segments, device=device)
+    q, k, v = cut(inp.q), cut(inp.k), cut(inp.v)
+    out = [torch.full_like(x, float("nan")) for x in q]
+    seq.kv.fill_(float("nan"))
+    kv = seq.forward(q, k, v, out)
+    res = {"out": to_host(out), "kv": kv.cpu().numpy().astype(np.float64)}
+    if backward:
+        do = cut(inp.dout)
+        dq, dk, dv = ([torch.full_like(x, float("nan")) for x in q] for _ in range(3))
+        seq.dkv.fill_(float("nan"))
+        dkv = seq.backward(q, k, v, do, dq, dk, dv)
+        res.update(dq=to_host(dq), dk=to_host(dk), dv=to_host(dv), dkv=dkv.cpu().numpy().astype(np.float64))
     torch.cuda.synchronize()
     return res

@@ -76,6 +76,14 @@ def _bind(handle):
     handle.lasp_gated_fwd_norm.restype = ctypes.c_int
     handle.lasp_gated_bwd_norm.argtypes = [_sp] + [_vp] * 16 + [_sz, _vp]
     handle.lasp_gated_bwd_norm.restype = ctypes.c_int
+    handle.lasp_bidir_scratch_bytes.argtypes = [_sp]
+    handle.lasp_bidir_scratch_bytes.restype = _sz
+    handle.lasp_bidir_state.argtypes = [_sp, _vp, _vp, _vp, ctypes.c_int32, _vp, _sz, _vp]
+    handle.lasp_bidir_state.restype = ctypes.c_int
+    handle.lasp_bidir_fwd.argtypes = [_sp] + [_vp] * 4
+    handle.lasp_bidir_fwd.restype = ctypes.c_int
+    handle.lasp_bidir_bwd.argtypes = [_sp] + [_vp] * 9
+    handle.lasp_bidir_bwd.restype = ctypes.c_int
     handle.lasp_profile_begin.argtypes = [ctypes.c_int32]
     handle.lasp_profile_end.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int32),
                                         ctypes.POINTER(ctypes.c_int32)]
@@ -252,6 +260,34 @@ def lasp_gated_bwd_norm(shape: Shape, q, k, v, out, rstd, dout, log_g, kv_out, d
                                  _ptr(dv), _ptr(dlog_g), _ptr(dkv_in), _ptr(scratch), nbytes, _stream(stream))
     if rc != 0:
         raise LaspError(rc, "lasp_gated_bwd_norm")
+
+
+def bidir_scratch_bytes(shape: Shape) -> int:
+    return int(lib.lasp_bidir_scratch_bytes(ctypes.byref(shape)))
+
+
+def lasp_bidir_state(shape: Shape, x, y, state, accumulate, scratch, stream=None) -> None:
+    """state (+)= sum over tokens of x_s y_s^T (bidirectional attention); raises LaspError on a non-zero status."""
+    nbytes = scratch.numel() * scratch.element_size() if scratch is not None else 0
+    rc = lib.lasp_bidir_state(ctypes.byref(shape), _ptr(x), _ptr(y), _ptr(state), int(bool(accumulate)), _ptr(scratch),
+                              nbytes, _stream(stream))
+    if rc != 0:
+        raise LaspError(rc, "lasp_bidir_state")
+
+
+def lasp_bidir_fwd(shape: Shape, q, kv, out, stream=None) -> None:
+    """out = q kv; raises LaspError on a non-zero status."""
+    rc = lib.lasp_bidir_fwd(ctypes.byref(shape), _ptr(q), _ptr(kv), _ptr(out), _stream(stream))
+    if rc != 0:
+        raise LaspError(rc, "lasp_bidir_fwd")
+
+
+def lasp_bidir_bwd(shape: Shape, k, v, dout, kv, dkv, dq, dk, dv, stream=None) -> None:
+    """dq = dout kv^T, dk = v dkv^T, dv = k dkv; raises LaspError on a non-zero status."""
+    rc = lib.lasp_bidir_bwd(ctypes.byref(shape), _ptr(k), _ptr(v), _ptr(dout), _ptr(kv), _ptr(dkv), _ptr(dq), _ptr(dk),
+                            _ptr(dv), _stream(stream))
+    if rc != 0:
+        raise LaspError(rc, "lasp_bidir_bwd")
 
 
 class Workspace:

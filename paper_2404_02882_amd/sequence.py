@@ -129,3 +129,42 @@ class GraphedStep:
 
     def replay(self) -> None:
         self.graph.replay()
+
+
+class BidirSequence:
+    """Bidirectional (unmasked) attention O = Q (K^T V) over sub-sequences of any lengths.
+
+    The state is a sum over every token, so nothing is handed from shard to shard: a first loop adds
+    each shard's K^T V into `kv` (on several devices: their partial states summed across them), a
+    second loop computes each shard's output from the complete state. Backward likewise with
+    dKV = Q^T dO. All buffers are allocated up front; the calls only enqueue kernels.
+    """
+
+    def __init__(self, B, H, lengths, D, chunk, dtype: torch.dtype, segments=0, device="cuda"):
+        self.lengths = [int(n) for n in lengths]
+        self.shapes = [lasp.make_shape(B, H, n, D, chunk, dtype, segments) for n in self.lengths]
+        need = 0
+        for shp in self.shapes:
+            nbytes = lasp.bidir_scratch_bytes(shp)
+            if nbytes == 0:
+                raise lasp.LaspError(lasp.check_shape(shp) or 2, "BidirSequence")
+            need = max(need, nbytes)
+        self.scratch = torch.empty(need, dtype=torch.uint8, device=device)
+        st = dict(dtype=torch.float32, device=device)
+        self.kv = torch.empty(B, H, D, D, **st)
+        self.dkv = torch.empty(B, H, D, D, **st)
+
+    def forward(self, q: List[torch.Tensor], k, v, out: List[torch.Tensor]) -> torch.Tensor:
+        for t, shp in enumerate(self.shapes):
+            lasp.lasp_bidir_state(shp, k[t], v[t], self.kv, t > 0, self.scratch)
+        for t, shp in enumerate(self.shapes):
+            lasp.lasp_bidir_fwd(shp, q[t], self.kv, out[t])
+        return self.kv
+
+    def backward(self, q, k, v, dout, dq, dk, dv) -> torch.Tensor:
+        """Needs the state `kv` of the forward pass."""
+        for t, shp in enumerate(self.shapes):
+            lasp.lasp_bidir_state(shp, q[t], dout[t], self.dkv, t > 0, self.scratch)
+        for t, shp in enumerate(self.shapes):
+            lasp.lasp_bidir_bwd(shp, k[t], v[t], dout[t], self.kv, self.dkv, dq[t], dk[t], dv[t])
+        return self.dkv

@@ -35,6 +35,7 @@ class Config:
     k_outlier_scale: float = 1.0
     token_decay: bool = False   # a decay g_s per token (log_g) instead of one lambda per head
     norm_eps: Optional[float] = None   # outputs are RMS-normalised per row (fused Norm); dout is then the gradient w.r.t. them
+    bidirectional: bool = False   # unmasked attention O = Q (K^T V): no decay, no states handed over
 
 
 # The five workloads (shapes, decay and value recipe as stated for the build).
@@ -50,6 +51,9 @@ CONFIGS = {
     "g3": Config("g3", B=1, H=16, N=32768, D=128, chunk=128, dtype="bf16", seed=1013, token_decay=True),
     # c3's shape with the normalised output
     "n3": Config("n3", B=1, H=16, N=32768, D=128, chunk=128, dtype="bf16", seed=1023, norm_eps=1e-5),
+    # c2's / c3's shapes without the causal mask (bidirectional attention)
+    "b2": Config("b2", B=2, H=8, N=4096, D=64, chunk=64, dtype="bf16", T=4, seed=1032, decay="one", bidirectional=True),
+    "b3": Config("b3", B=1, H=16, N=32768, D=128, chunk=128, dtype="bf16", seed=1033, decay="one", bidirectional=True),
 }
 
 

@@ -282,3 +282,64 @@ def test_kv_heads_alias_check_uses_group_sizes(L):
     k, v = _fake(8), _fake(9)
     out_inside_k = ctypes.c_void_p(k.value + one_head - 16)
     assert L.lib.lasp_fwd(ctypes.byref(s), q, k, v, kvin, dec, out_inside_k, kvout, cache, scr, sb, None) == 6
+
+
+# ---------------------------------------------------------------- bidirectional entry points
+def test_bidir_sizes(L):
+    s = L.make_shape(1, 16, 32768, 128, 128, "bf16")
+    sb = L.bidir_scratch_bytes(s)
+    assert sb > 0 and sb % (16 * 128 * 128 * 4) == 0            # whole partial states per head
+    assert 16 * (sb // (16 * 128 * 128 * 4)) >= 256              # enough workgroups to fill 256 CUs
+    one = L.make_shape(1, 16, 32768, 128, 128, "bf16", segments=1)
+    assert L.bidir_scratch_bytes(one) == 16 * 128 * 128 * 4
+    assert L.bidir_scratch_bytes(L.make_shape(2, 3, 1, 64, 64, "f32")) == 2 * 3 * 64 * 64 * 4   # N = 1: one partial
+    assert L.bidir_scratch_bytes(L.make_shape(1, 4, 100, 64, 64, "bf16", kv_heads=2)) == 0      # no grouped heads here
+    assert L.bidir_scratch_bytes(L.make_shape(1, 4, 100, 64, 64, "bf16", kv_heads=4)) > 0
+    assert L.bidir_scratch_bytes(L.make_shape(1, 4, 100, 96, 64, "bf16")) == 0
+    assert L.bidir_scratch_bytes(L.make_shape(1, 4, 100, 64, 64, "bf16", segments=3)) == 0      # > ceil(100 / 64) tiles
+
+
+def test_bidir_rejects_before_launch(L):
+    s = L.make_shape(1, 2, 100, 64, 64, "bf16")
+    sb = L.bidir_scratch_bytes(s)
+    x, y, st, scr, q, kv, out, k, v, do, dkv, dq, dk, dv = [_fake(i) for i in range(1, 15)]
+    state = lambda *a: L.lib.lasp_bidir_state(*a)
+    ok = [ctypes.byref(s), x, y, st, 0, scr, sb, None]
+    for idx in (0, 1, 2, 3):
+        a = list(ok); a[idx] = None
+        assert state(*a) == 1, idx
+    a = list(ok); a[5] = None
+    assert state(*a) == 5
+    a = list(ok); a[6] = sb - 1
+    assert state(*a) == 5
+    a = list(ok); a[3] = scr
+    assert state(*a) == 6                                          # state aliases the scratch
+    a = list(ok); a[1] = ctypes.c_void_p(x.value + 2)
+    assert state(*a) == 8
+    grouped = L.make_shape(1, 2, 100, 64, 64, "bf16", kv_heads=1)
+    a = list(ok); a[0] = ctypes.byref(grouped)
+    assert state(*a) == 2
+    a = list(ok); a[0] = ctypes.byref(L.make_shape(1, 2, 100, 64, 64, 5))
+    assert state(*a) == 3
+
+    fwd = lambda *a: L.lib.lasp_bidir_fwd(*a)
+    ok = [ctypes.byref(s), q, kv, out, None]
+    for idx in (0, 1, 2, 3):
+        a = list(ok); a[idx] = None
+        assert fwd(*a) == 1, idx
+    a = list(ok); a[3] = q
+    assert fwd(*a) == 6
+    a = list(ok); a[2] = ctypes.c_void_p(kv.value + 4)
+    assert fwd(*a) == 8
+
+    bwd = lambda *a: L.lib.lasp_bidir_bwd(*a)
+    ok = [ctypes.byref(s), k, v, do, kv, dkv, dq, dk, dv, None]
+    for idx in range(9):
+        a = list(ok); a[idx] = None
+        assert bwd(*a) == 1, idx
+    a = list(ok); a[6] = do
+    assert bwd(*a) == 6                                            # dq aliases dout
+    a = list(ok); a[8] = dk
+    assert bwd(*a) == 6                                            # dv aliases dk
+    a = list(ok); a[0] = ctypes.byref(L.make_shape(1, 2, 0, 64, 64, "bf16"))
+    assert bwd(*a) == 2
