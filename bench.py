@@ -40,7 +40,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--config", default="c3", help="named workload (c3 is the headline; g3 = c3 with a decay per token, n3 = c3 with the fused Norm)")
+    ap.add_argument("--config", default="c3", help="named workload (c3 is the headline; g3 = c3 with a decay per token, n3 = c3 with the fused Norm, b3 = c3 without mask and decay)")
     ap.add_argument("--segments", type=int, default=0)
     ap.add_argument("--graph", action="store_true",
                     help="time the step as replays of one HIP graph (pays off when the T-loop is launch-bound); "
@@ -64,6 +64,8 @@ def main():
     cfg = si.CONFIGS[args.config]
     dev = "cuda:0"
     torch.cuda.set_device(0)
+    if cfg.bidirectional:
+        return bench_bidirectional(args, cfg, dev)
     inp = si.make_inputs(cfg)
     B, H, N, D, T = cfg.B, cfg.H, cfg.N, cfg.D, cfg.T
     dt = harness.TORCH_DTYPE[cfg.dtype]
@@ -171,25 +173,7 @@ def main():
              "min_hbm_bytes_per_step": min_bytes_step,
              "step_hbm_frac_at_min_bytes": round(min_bytes_step / step_s / 1e9 / HBM_PEAK_GBS, 4)}
 
-    # ---- plain copy of known size: measured HBM copy bandwidth (and counter calibration) ----
-    copy = None
-    if args.copy_mib > 0:
-        n = args.copy_mib * (1 << 20)
-        src = torch.empty(n, dtype=torch.uint8, device=dev).fill_(1)
-        dst = torch.empty_like(src)
-        for _ in range(3):
-            dst.copy_(src)
-        torch.cuda.synchronize()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        for _ in range(10):
-            dst.copy_(src)
-        e1.record()
-        torch.cuda.synchronize()
-        copy_ms = e0.elapsed_time(e1) / 10
-        copy = {"bytes_read": n, "bytes_written": n, "ms": round(copy_ms, 4),
-                "gbs_read_plus_write": round(2 * n / (copy_ms * 1e-3) / 1e9, 1)}
-        del src, dst
+    copy = copy_reference(args, dev)
 
     # ---- CPU oracle on a bounded sample of the same workload ----
     cpu = None
@@ -227,6 +211,129 @@ def main():
                                    + (f", output RMS-normalised per row (eps {cfg.norm_eps})" if norm else ""),
                        "tile_tokens": tile, "segments_per_head": nseg, "hip_graph": bool(args.graph),
                        "state_cache_bytes": seq.cache_bytes()},
+            "roofline": roofline, "whole_step": extra, "copy_reference": copy, "cpu_baseline": cpu}
+    print(json.dumps(line), flush=True)
+
+
+def copy_reference(args, dev):
+    """Plain device-to-device copy of known size: measured HBM copy bandwidth (and counter calibration)."""
+    import torch
+    if args.copy_mib <= 0:
+        return None
+    n = args.copy_mib * (1 << 20)
+    src = torch.empty(n, dtype=torch.uint8, device=dev).fill_(1)
+    dst = torch.empty_like(src)
+    for _ in range(3):
+        dst.copy_(src)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(10):
+        dst.copy_(src)
+    e1.record()
+    torch.cuda.synchronize()
+    copy_ms = e0.elapsed_time(e1) / 10
+    return {"bytes_read": n, "bytes_written": n, "ms": round(copy_ms, 4),
+            "gbs_read_plus_write": round(2 * n / (copy_ms * 1e-3) / 1e9, 1)}
+
+
+def bench_bidirectional(args, cfg, dev):
+    """One step = forward + backward of the unmasked attention O = Q (K^T V): per sub-sequence the state
+    reduction on (K, V), then the output product; backward the reduction on (Q, dO), then the three
+    gradient products in one launch."""
+    import numpy as np
+    import torch
+    from paper_2404_02882_amd import harness, lasp, synth_inputs as si
+    from paper_2404_02882_amd.sequence import BidirSequence
+
+    inp = si.make_inputs(cfg)
+    B, H, N, D, T = cfg.B, cfg.H, cfg.N, cfg.D, cfg.T
+    dt = harness.TORCH_DTYPE[cfg.dtype]
+    lengths = [N // T] * T
+    seq = BidirSequence(B, H, lengths, D, cfg.chunk, dt, segments=args.segments, device=dev)
+    q, k, v, do = (harness.shards(x, T, cfg.dtype, dev) for x in (inp.q, inp.k, inp.v, inp.dout))
+    out, dq, dk, dv = ([torch.empty_like(x) for x in q] for _ in range(4))
+
+    def step():
+        seq.forward(q, k, v, out)
+        seq.backward(q, k, v, do, dq, dk, dv)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    lasp.profile_begin(args.steps * 3 * T)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    kernel_ms, nf, nb = lasp.profile_end()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    tokens_per_s = B * N / (ms_per_step * 1e-3)
+    # for information: the same steps as replays of one HIP graph (not `value`)
+    from paper_2404_02882_amd.sequence import GraphedStep
+    graphed = GraphedStep(seq, dict(q=q, k=k, v=v, out=out), dict(q=q, k=k, v=v, dout=do, dq=dq, dk=dk, dv=dv))
+    for _ in range(args.warmup):
+        graphed.replay()
+    torch.cuda.synchronize()
+    g0 = time.perf_counter()
+    for _ in range(args.steps):
+        graphed.replay()
+    torch.cuda.synchronize()
+    graph_ms = (time.perf_counter() - g0) * 1e3 / args.steps
+
+    # forward-kind records: 2T state calls and T output calls per step; backward-kind: T calls per step
+    launches = args.steps * T
+    per_launch_ms = {"state_reduce": kernel_ms["fwd"][0] / (2 * launches), "state_sum": kernel_ms["fwd"][1] / (2 * launches),
+                     "fwd_apply": kernel_ms["fwd"][2] / launches, "bwd_apply": kernel_ms["bwd"][2] / launches}
+    assert nf == 3 * launches and nb == launches, (nf, nb)
+    esz = 2 if cfg.dtype == "bf16" else 4
+    tok_heads_per_launch = B * H * (N // T)
+    # compulsory HBM bytes per token-head: the reduction reads two tensors; the output product reads q and
+    # writes o; the gradient products read dO, V, K and write dQ, dK, dV
+    alg_bytes = {"state_reduce": 2 * D * esz, "fwd_apply": 2 * D * esz, "bwd_apply": 6 * D * esz}
+    dominant = max(alg_bytes, key=lambda n: per_launch_ms[n])
+    dom_bytes = alg_bytes[dominant] * tok_heads_per_launch
+    achieved = dom_bytes / (per_launch_ms[dominant] * 1e-3) / 1e9
+    roofline = {"kernel": dominant, "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
+                "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
+                "traffic": MEASURED_TRAFFIC_BYTES.get(args.config, {}).get(dominant) if args.segments == 0 else None,
+                "algorithmic_bytes_per_launch": dom_bytes,
+                "avg_launch_ms": round(per_launch_ms[dominant], 4),
+                "kernel_ms_per_launch": {n: round(x, 4) for n, x in per_launch_ms.items()}}
+    flops_step = 12 * D * D * B * H * N      # two reductions and four products of 2 d^2 each per token-head
+    min_bytes_step = 11 * D * esz * B * H * N
+    step_s = ms_per_step * 1e-3
+    extra = {"hip_graph_replay_ms_per_step": round(graph_ms, 4),
+             "algorithmic_tflops": round(flops_step / step_s / 1e12, 2),
+             "mfma_bf16_peak_frac": round(flops_step / step_s / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
+             "min_hbm_bytes_per_step": min_bytes_step,
+             "step_hbm_frac_at_min_bytes": round(min_bytes_step / step_s / 1e9 / HBM_PEAK_GBS, 4)}
+    copy = copy_reference(args, dev)
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import lasp_oracle
+        n_s = min(args.cpu_sample_tokens, N, 8192)   # the definition is quadratic in the tokens
+        a = [np.ascontiguousarray(x[:, :, :n_s], dtype=np.float64) for x in (inp.q, inp.k, inp.v, inp.dout)]
+        c0 = time.perf_counter()
+        lasp_oracle.bidir_fwd_left(a[0], a[1], a[2])
+        lasp_oracle.bidir_bwd_left(a[0], a[1], a[2], a[3])
+        c1 = time.perf_counter()
+        cpu = {"value": round(B * n_s / (c1 - c0), 1), "unit": "tokens/s", "cores": os.cpu_count(), "kind": "oracle",
+               "sample": f"fp64 oracle, the definition O = (Q K^T) V with its N x N scores (quadratic: the rate falls "
+                         f"with N), fwd+bwd, a {n_s}-token sequence of all {B * H} heads, {c1 - c0:.1f} s; numpy "
+                         f"matmul on the host's BLAS threads"}
+
+    line = {"metric": "fwd+bwd tokens/sec, bidirectional (unmasked) linear attention O = Q (K^T V)",
+            "value": round(tokens_per_s, 1), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
+            "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
+            "scaling": "weak", "vs_baseline": None, "dtype": cfg.dtype, "data": "synthetic",
+            "config": {"workload": f"{cfg.name}: B={B} H={H} N={N} d={D} {cfg.dtype}, T={T} sub-sequence(s), fwd+bwd, "
+                                   f"no mask, no decay",
+                       "partial_states_per_head": lasp.bidir_scratch_bytes(seq.shapes[0]) // (B * H * D * D * 4),
+                       "hip_graph": False},
             "roofline": roofline, "whole_step": extra, "copy_reference": copy, "cpu_baseline": cpu}
     print(json.dumps(line), flush=True)
 

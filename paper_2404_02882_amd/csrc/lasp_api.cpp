@@ -262,7 +262,7 @@ int make_bidir_plan(const lasp_shape *s, lasp::BidirPlan *p) {
     if (want < 0 || want > p->ntiles_r) return LASP_ERR_SHAPE;
     if (want == 0) {
         const int64_t chains = (int64_t)s->B * s->H;
-        want = (int)((lasp::kBidirTargetWorkgroups + chains - 1) / chains);
+        want = (int)((lasp::kBidirTargetSegments + chains - 1) / chains);
         if (want > p->ntiles_r) want = p->ntiles_r;
     }
     p->tiles_per_seg = (p->ntiles_r + want - 1) / want;

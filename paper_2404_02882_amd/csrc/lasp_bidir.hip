@@ -40,23 +40,27 @@ __global__ __launch_bounds__(D * 2, 2) void k_bidir_reduce(const T *__restrict__
     Lane ln = fresh_lane();
     const size_t base = (size_t)chain * ntok * D;
     auto nvalid = [&](int t) { return min(CT, ntok - t * CT); };
-    TileMover<T, CT, D, NT> mx, my;
-    mx.load(X + base + (size_t)t0 * CT * D, nvalid(t0));
-    my.load(Y + base + (size_t)t0 * CT * D, nvalid(t0));
+    // Two tiles are in flight at any time: a streaming sum has nothing else to hide the memory latency with.
+    TileMover<T, CT, D, NT> mx[2], my[2];
+    auto request = [&](int b, int t) {
+        if (t < t1) {
+            mx[b].load(X + base + (size_t)t * CT * D, nvalid(t));
+            my[b].load(Y + base + (size_t)t * CT * D, nvalid(t));
+        }
+    };
+    request(0, t0);
+    request(1, t0 + 1);
     f32x16 st[DB];
 #pragma unroll
     for (int ab = 0; ab < DB; ++ab) st[ab] = f32x16{0};
 
-    for (int t = t0; t < t1; ++t) {
+    auto consume = [&](int b, int t) {
         __syncthreads();  // previous tile fully consumed
         ln = fresh_lane();
-        mx.store(sX, LDD);
-        my.store(sY, LDD);
+        mx[b].store(sX, LDD);
+        my[b].store(sY, LDD);
         __syncthreads();
-        if (t + 1 < t1) {
-            mx.load(X + base + (size_t)(t + 1) * CT * D, nvalid(t + 1));
-            my.load(Y + base + (size_t)(t + 1) * CT * D, nvalid(t + 1));
-        }
+        request(b, t + 2);
         struct Step {
             typename E::frag y;
             typename E::frag x[DB];
@@ -73,6 +77,10 @@ __global__ __launch_bounds__(D * 2, 2) void k_bidir_reduce(const T *__restrict__
 #pragma unroll
                 for (int ab = 0; ab < DB; ++ab) st[ab] = E::mfma(f.x[ab], f.y, st[ab]);
             });
+    };
+    for (int t = t0; t < t1; t += 2) {
+        consume(0, t);
+        if (t + 1 < t1) consume(1, t + 1);
     }
     state_store<D>(ln, st, part + ((size_t)chain * nseg + seg) * D * D, w);
 }
@@ -107,9 +115,10 @@ __global__ __launch_bounds__(256) void k_bidir_sum(const float *__restrict__ par
 template <typename T, int CT, int D>
 __global__ __launch_bounds__(D * 2, 2) void k_bidir_apply(BidirOps ops, int ntiles, int tiles_per_blk, int ntok) {
     using E = Elem<T>;
-    constexpr int NT = D * 2, LDD = tile_ld<T, D>(), DB = D / 32, NB = CT / 32;
+    constexpr int NT = D * 2, LDD = tile_ld<T, D>(), DB = D / 32, NB = CT / 32, LDO = D + 16 / (int)sizeof(T);
     extern __shared__ __attribute__((aligned(16))) char smem[];
     T *sX = (T *)smem;
+    T *sO = sX + CT * LDD;   // output tile [token][feature], rows padded by 16 bytes
 
     const int chain = blockIdx.y, op = blockIdx.z;
     const int t0 = blockIdx.x * tiles_per_blk;
@@ -125,8 +134,13 @@ __global__ __launch_bounds__(D * 2, 2) void k_bidir_apply(BidirOps ops, int ntil
     const float *S = pick(ops.s[0], ops.s[1], ops.s[2]) + (size_t)chain * D * D;
     const int trans = pick(ops.trans[0], ops.trans[1], ops.trans[2]);
     auto nvalid = [&](int t) { return min(CT, ntok - t * CT); };
-    TileMover<T, CT, D, NT> mx;
-    mx.load(X + (size_t)t0 * CT * D, nvalid(t0));
+    // Two tiles are in flight at any time (nothing else hides the memory latency of a streaming product).
+    TileMover<T, CT, D, NT> mx[2];
+    auto request = [&](int b, int t) {
+        if (t < t1) mx[b].load(X + (size_t)t * CT * D, nvalid(t));
+    };
+    request(0, t0);
+    request(1, t0 + 1);
 
     typename E::frag sf[DB][E::NSUB];
     {
@@ -151,12 +165,12 @@ __global__ __launch_bounds__(D * 2, 2) void k_bidir_apply(BidirOps ops, int ntil
             for (int m = 0; m < E::NSUB; ++m) sf[ab][m] = E::from_acc(st[ab], m);
     }
 
-    for (int t = t0; t < t1; ++t) {
-        __syncthreads();  // previous tile fully consumed
+    auto consume = [&](int b, int t) {
+        __syncthreads();  // previous tile fully consumed: sX and sO are free
         ln = fresh_lane();
-        mx.store(sX, LDD);
+        mx[b].store(sX, LDD);
         __syncthreads();
-        if (t + 1 < t1) mx.load(X + (size_t)(t + 1) * CT * D, nvalid(t + 1));
+        request(b, t + 2);
         f32x16 acc[NB];
 #pragma unroll
         for (int ib = 0; ib < NB; ++ib) acc[ib] = f32x16{0};
@@ -166,15 +180,50 @@ __global__ __launch_bounds__(D * 2, 2) void k_bidir_apply(BidirOps ops, int ntil
             for (int m = 0; m < E::NSUB; ++m)
 #pragma unroll
                 for (int ib = 0; ib < NB; ++ib) acc[ib] = E::mfma(sf[ab][m], E::ld_kp(ln, sX, LDD, 32 * ib, 32 * ab, m), acc[ib]);
-        T *o = O + (size_t)t * CT * D;
+        // The accumulators hold the transposed tile (lane = token, four consecutive features per register
+        // group). Written to memory as they are, a store instruction would touch 32 rows with 8 or 16 bytes
+        // each; through LDS every row leaves as whole 16-byte pieces of consecutive lanes.
 #pragma unroll
-        for (int ib = 0; ib < NB; ++ib) store_out_tile_t<T, D>(ln, o, acc[ib], 32 * ib, w, nvalid(t));
+        for (int ib = 0; ib < NB; ++ib)
+#pragma unroll
+            for (int g = 0; g < 4; ++g)
+                E::st4(sO + (32 * ib + ln.r) * LDO + 32 * w + 8 * g + 4 * ln.h, acc[ib][4 * g], acc[ib][4 * g + 1],
+                       acc[ib][4 * g + 2], acc[ib][4 * g + 3]);
+        __syncthreads();
+        {
+            using M = TileMover<T, CT, D, NT>;
+            const int row0 = threadIdx.x / M::VPR, nrows = nvalid(t);
+            const unsigned glo = M::lane_off(D) * sizeof(T);
+            const T *src = sO + M::lane_off(LDO);
+            T *o = O + (size_t)t * CT * D;
+#pragma unroll
+            for (int i = 0; i < M::NV; ++i)
+                if (row0 + i * (NT / M::VPR) < nrows)
+                    gstore<u32x4>(o + i * (NT / M::VPR) * D, glo, *(const u32x4 *)(src + i * (NT / M::VPR) * LDO));
+        }
+    };
+    for (int t = t0; t < t1; t += 2) {
+        consume(0, t);
+        if (t + 1 < t1) consume(1, t + 1);
     }
 }
 
 // ---------------------------------------------------------------------------
 // Host-side launchers
 // ---------------------------------------------------------------------------
+// Raise the dynamic LDS limit of a kernel above the 64 KB default, once per kernel and device.
+template <typename F>
+static hipError_t allow_lds_bidir(F kernel, size_t bytes) {
+    static bool done[64] = {};
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (bytes <= 65536 || (dev >= 0 && dev < 64 && done[dev])) return hipSuccess;
+    e = hipFuncSetAttribute((const void *)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+    if (e == hipSuccess && dev >= 0 && dev < 64) done[dev] = true;
+    return e;
+}
+
 template <typename T, int CT, int D>
 static hipError_t run_bidir_state(const BidirPlan &p, const void *x, const void *y, float *state, int accumulate,
                                   float *part, hipStream_t s, const KernelEvents *ke) {
@@ -196,8 +245,9 @@ static hipError_t run_bidir_state(const BidirPlan &p, const void *x, const void 
 template <typename T, int CT, int D>
 static hipError_t run_bidir_apply(const BidirPlan &p, const BidirOps &ops, int nops, hipStream_t s, const KernelEvents *ke) {
     const int chains = p.B * p.H;
-    constexpr size_t lds = (size_t)CT * tile_ld<T, D>() * sizeof(T);
-    static_assert(lds <= 65536, "fits the default dynamic LDS limit");
+    constexpr size_t lds = (size_t)CT * (tile_ld<T, D>() + D + 16 / sizeof(T)) * sizeof(T);
+    static_assert(2 * lds <= 163840, "two workgroups per CU");
+    if (hipError_t e = allow_lds_bidir(k_bidir_apply<T, CT, D>, lds); e != hipSuccess) return e;
     const int ntiles = (p.N + CT - 1) / CT;
     int nblk = (kBidirTargetWorkgroups + chains * nops - 1) / (chains * nops);
     if (nblk > ntiles) nblk = ntiles;

@@ -90,7 +90,8 @@ struct BidirOps {
     void *out[3];
     int trans[3];
 };
-constexpr int kBidirTargetWorkgroups = 512;   // two 4-wave workgroups per CU
+constexpr int kBidirTargetWorkgroups = 512;   // products: two 4-wave workgroups per CU
+constexpr int kBidirTargetSegments = 256;     // reduction: one partial sum per CU (fewer partials to write and add)
 int bidir_reduce_tile(int dtype);
 // events: ev[0]..ev[1] the reduction, ev[1]..ev[2] the sum of the partials
 hipError_t launch_bidir_state(const BidirPlan &p, const void *x, const void *y, float *state, int accumulate, float *part,
