@@ -452,3 +452,71 @@ def bidir_bwd_rows(q, k, v, dout, rows):
         dk[n] = (dout[b, h] @ v[b, h, s]) @ q[b, h]
         dv[n] = (q[b, h] @ k[b, h, s]) @ dout[b, h]
     return dq, dk, dv
+
+
+# ---------------------------------------------------------------------------
+# Key and value dimensions that differ (d_k for q, k; d_v for v, out): the
+# state is [d_k][d_v] and nothing else changes in Alg. 2 / Alg. 3 or in the
+# general recurrent form of App. A.4. Written out from the definition with the
+# N x N weight matrix, per (batch, head), for small N:
+#     W[s][i] = weight of token i in the state seen by token s (i <= s):
+#               lambda^(s-i), or g_{i+1} ... g_s with a decay per token,
+#     up[s]   = weight of kv_in at token s, after[i] = weight of token i in kv_out,
+#     out     = (Q K^T (.) W) V + diag(up) Q kv_in
+#     kv_out  = whole * kv_in + (diag(after) K)^T V
+# and the gradients of L = sum(out * dout) + <kv_out, dkv_out>.
+# ---------------------------------------------------------------------------
+def _weights(N, lam=None, log_g=None):
+    if log_g is None:
+        cum = np.arange(1, N + 1, dtype=np.float64) * np.log(float(lam)) if lam > 0 else None
+    else:
+        cum = np.cumsum(np.asarray(log_g, dtype=np.float64))
+    W = np.tril(np.exp(cum[:, None] - cum[None, :]))
+    return W, np.exp(cum), np.exp(cum[-1] - cum), float(np.exp(cum[-1]))
+
+
+def dims_fwd_brute(q, k, v, decay=None, kv_in=None, log_g=None):
+    """q, k [B,H,N,dk]; v [B,H,N,dv]; decay [H] or log_g [B,H,N]; kv_in [B,H,dk,dv] or None -> (out, kv_out)."""
+    q, k, v = _d(q), _d(k), _d(v)
+    B, H, N, dk = q.shape
+    dv = v.shape[-1]
+    out, kv_out = np.empty((B, H, N, dv)), np.empty((B, H, dk, dv))
+    for b in range(B):
+        for h in range(H):
+            W, up, after, whole = _weights(N, None if decay is None else float(decay[h]), None if log_g is None else log_g[b, h])
+            s0 = np.zeros((dk, dv)) if kv_in is None else _d(kv_in)[b, h]
+            out[b, h] = ((q[b, h] @ k[b, h].T) * W) @ v[b, h] + up[:, None] * (q[b, h] @ s0)
+            kv_out[b, h] = whole * s0 + (after[:, None] * k[b, h]).T @ v[b, h]
+    return out, kv_out
+
+
+def dims_bwd_brute(q, k, v, dout, decay=None, kv_in=None, dkv_out=None, log_g=None):
+    """-> (dq, dk, dv, dkv_in) for one lambda per head, (dq, dk, dv, dlog_g, dkv_in) with log_g."""
+    q, k, v, dout = _d(q), _d(k), _d(v), _d(dout)
+    B, H, N, dk = q.shape
+    dv = v.shape[-1]
+    dq, dkk, dvv = np.empty_like(q), np.empty_like(k), np.empty_like(v)
+    dkv_in, dlg = np.empty((B, H, dk, dv)), np.empty((B, H, N))
+    for b in range(B):
+        for h in range(H):
+            W, up, after, whole = _weights(N, None if decay is None else float(decay[h]), None if log_g is None else log_g[b, h])
+            s0 = np.zeros((dk, dv)) if kv_in is None else _d(kv_in)[b, h]
+            G = np.zeros((dk, dv)) if dkv_out is None else _d(dkv_out)[b, h]
+            S = (q[b, h] @ k[b, h].T) * W
+            dS = (dout[b, h] @ v[b, h].T) * W
+            dq[b, h] = dS @ k[b, h] + up[:, None] * (dout[b, h] @ s0.T)
+            dkk[b, h] = dS.T @ q[b, h] + after[:, None] * (v[b, h] @ G.T)
+            dvv[b, h] = S.T @ dout[b, h] + after[:, None] * (k[b, h] @ G)
+            dkv_in[b, h] = (up[:, None] * q[b, h]).T @ dout[b, h] + whole * G
+            if log_g is not None:
+                # d L / d log g_s: every weight whose product contains g_s, i.e. pairs (i < s <= t), the
+                # kv_in term of tokens t >= s and the kv_out terms of tokens i < s and of kv_in
+                P = (dout[b, h] @ v[b, h].T) * (q[b, h] @ k[b, h].T) * W          # contribution of pair (t, i)
+                a = up * np.sum((q[b, h] @ s0) * dout[b, h], axis=1)              # kv_in seen by token t
+                c = after * np.sum((k[b, h] @ G) * v[b, h], axis=1)               # token i seen by kv_out
+                z = whole * float(np.sum(s0 * G))
+                for s in range(N):
+                    dlg[b, h, s] = P[s:, :s].sum() + a[s:].sum() + c[:s].sum() + z
+    if log_g is None:
+        return dq, dkk, dvv, dkv_in
+    return dq, dkk, dvv, dlg, dkv_in
