@@ -42,7 +42,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--config", default="c3", help="named workload (c3 is the headline; g3 = c3 with a decay per token, n3 = c3 with the fused Norm, b3 = c3 without mask and decay)")
+    ap.add_argument("--config", default="c3", help="named workload (c3 is the headline; g3 = c3 with a decay per token, n3 = c3 with the fused Norm, b3 = c3 without mask and decay, m3 = c3 with d_k = 64, d_v = 128)")
     ap.add_argument("--segments", type=int, default=0)
     ap.add_argument("--graph", action="store_true",
                     help="time the step as replays of one HIP graph (pays off when the T-loop is launch-bound); "
@@ -73,8 +73,9 @@ def main():
     dt = harness.TORCH_DTYPE[cfg.dtype]
     token = cfg.token_decay
     norm = cfg.norm_eps is not None
+    dk_, dv_ = D, cfg.Dv or D   # key and value dimensions
     seq = LaspSequence(B, H, N, D, cfg.chunk, dt, T=T, segments=args.segments, device=dev, token_decay=token,
-                       norm_eps=cfg.norm_eps)
+                       norm_eps=cfg.norm_eps, Dv=cfg.Dv)
     q, k, v, do = (harness.shards(x, T, cfg.dtype, dev) for x in (inp.q, inp.k, inp.v, inp.dout))
     if token:   # a decay per token: log g shards [B,H,N/T] in, dlog_g shards out
         n = N // T
@@ -83,7 +84,7 @@ def main():
     else:
         decay = torch.from_numpy(inp.decay).to(dev)
         dlg = None
-    out, dq, dk, dv = ([torch.empty_like(x) for x in q] for _ in range(4))
+    out, dq, dk, dv = ([torch.empty_like(x) for x in y] for y in (v, q, k, v))
     rstd = [torch.empty(B, H, N // T, dtype=torch.float32, device=dev) for _ in range(T)] if norm else None
     tile = lasp.tile_tokens(seq.shape)
     nseg = lasp.num_segments(seq.shape)
@@ -151,8 +152,9 @@ def main():
     # normalised output and rstd (dO is rebuilt from dY on the fly).
     gb = 4 if token else 0
     nb = D * esz + 4 if norm else 0
-    alg_bytes = {"fwd_walk": 4 * D * esz + gb + (4 if norm else 0), "bwd_walk": 7 * D * esz + gb + nb,
-                 "fwd_local": 2 * D * esz + gb, "bwd_local": 2 * D * esz + gb + nb}
+    alg_bytes = {"fwd_walk": (2 * dk_ + 2 * dv_) * esz + gb + (4 if norm else 0),
+                 "bwd_walk": (4 * dk_ + 3 * dv_) * esz + gb + nb,
+                 "fwd_local": (dk_ + dv_) * esz + gb, "bwd_local": (dk_ + dv_) * esz + gb + nb}
     dominant = max(("fwd_walk", "bwd_walk", "fwd_local", "bwd_local"), key=lambda n: per_launch_ms[n])
     dom_bytes = alg_bytes[dominant] * tok_heads_per_launch
     achieved = dom_bytes / (per_launch_ms[dominant] * 1e-3) / 1e9
@@ -166,8 +168,8 @@ def main():
     # whole-step figures against both roofs: the chunked algorithm's flops per token-head at the
     # configured chunk length C (intra-chunk 14*C*d, inter-chunk and state updates 12*d*d), not issued
     # flops (the kernels run shorter tiles than C and rebuild half of the cached states)
-    flops_step = (14 * cfg.chunk * D + 12 * D * D) * B * H * N
-    min_bytes_step = (11 * D * esz + 3 * gb + (D * esz + 8 if norm else 0)) * B * H * N
+    flops_step = (cfg.chunk * (8 * dk_ + 6 * dv_) + 12 * dk_ * dv_) * B * H * N   # = 14 C d + 12 d^2 at d_k = d_v = d
+    min_bytes_step = ((6 * dk_ + 5 * dv_) * esz + 3 * gb + (D * esz + 8 if norm else 0)) * B * H * N
     step_s = ms_per_step * 1e-3
     extra = {"hip_graph_replay_ms_per_step": round(graph_ms, 4) if graph_ms is not None else None,
              "algorithmic_tflops": round(flops_step / step_s / 1e12, 2),
@@ -185,6 +187,9 @@ def main():
         n_s -= n_s % cfg.chunk
         sl = slice(0, n_s)
         a = [np.ascontiguousarray(x[:, :, sl], dtype=np.float64) for x in (inp.q, inp.k, inp.v, inp.dout)]
+        if dk_ != dv_:   # the C oracle has one head dimension: the narrower side gets zero columns (changes no value)
+            dmax = max(dk_, dv_)
+            a = [np.pad(x, ((0, 0), (0, 0), (0, 0), (0, dmax - x.shape[3]))) for x in a]
         c0 = time.perf_counter()
         if norm:
             o, _ = lasp_oracle.fwd_chunked(a[0], a[1], a[2], inp.decay, cfg.chunk)
@@ -201,14 +206,16 @@ def main():
         cpu = {"value": round(B * n_s / (c1 - c0), 1), "unit": "tokens/s", "cores": lasp_oracle.num_threads(),
                "kind": "oracle",
                "sample": f"chunked fp64 oracle (Alg. 2 + Alg. 3), fwd+bwd, first {n_s} of {N} tokens of all "
-                         f"{B * H} heads, {c1 - c0:.1f} s"}
+                         f"{B * H} heads, {c1 - c0:.1f} s"
+                         + (f"; run at d = {max(dk_, dv_)} with zero columns on the narrower side" if dk_ != dv_ else "")}
 
     line = {"metric": "fwd+bwd tokens/sec, chunked causal linear attention with decay (LASP per-device hot path)"
                       + (", decay per token" if token else "") + (", normalised output" if norm else ""),
             "value": round(tokens_per_s, 1), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
             "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
             "scaling": "weak", "vs_baseline": None, "dtype": cfg.dtype, "data": "synthetic",
-            "config": {"workload": f"{cfg.name}: B={B} H={H} N={N} d={D} chunk={cfg.chunk} {cfg.dtype}, "
+            "config": {"workload": f"{cfg.name}: B={B} H={H} N={N} " + (f"d_k={dk_} d_v={dv_}" if dk_ != dv_ else f"d={D}")
+                                   + f" chunk={cfg.chunk} {cfg.dtype}, "
                                    f"T={T} sub-sequence(s), fwd+bwd" + (", decay per token (log_g in, dlog_g out)" if token else "")
                                    + (f", output RMS-normalised per row (eps {cfg.norm_eps})" if norm else ""),
                        "tile_tokens": tile, "segments_per_head": nseg, "hip_graph": bool(args.graph),

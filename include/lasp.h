@@ -70,6 +70,14 @@ typedef enum { LASP_F32 = 0, LASP_BF16 = 1 } lasp_dtype;
  *            to: Sec. 1). States, decays and everything indexed by head stay per
  *            QUERY head. The backward pass then needs scratch for dK, dV per query
  *            head (two token tensors), summed over each group at the end.
+ *   Dv       0 or D: queries, keys and values share the head dimension D. Otherwise
+ *            the value dimension d_v (64 or 128) while D is the key dimension d_k:
+ *            q, k, dq, dk are [..][N][D], v, out, dout, dv are [..][N][Dv], and
+ *            every state (kv_in, kv_out, dkv_out, dkv_in) is [B][H][D][Dv], rows
+ *            indexed by the key feature. The kernels run at max(D, Dv) with the
+ *            narrower of the two zero-padded on chip (memory traffic follows the
+ *            real sizes, scratch and the state cache the padded ones). Not
+ *            offered with the fused Norm or the bidirectional calls.
  *   segments 0 = chosen by the library. Otherwise the number of independent
  *            segments each head's sub-sequence is cut into so that B*H*segments
  *            workgroups fill the chip (1 <= segments <= ceil(N / tile)).
@@ -79,6 +87,7 @@ typedef struct {
     int32_t dtype;    /* lasp_dtype */
     int32_t segments; /* 0 = auto */
     int32_t kv_heads; /* 0 = H */
+    int32_t Dv;       /* 0 = D */
 } lasp_shape;
 
 int lasp_version(void);

@@ -25,6 +25,7 @@ bool valid_dims(const lasp_shape *s) {
     if (s->chunk != 64 && s->chunk != 128 && s->chunk != 256) return false;
     if ((int64_t)s->B * s->H > 65535) return false;  // grid.y limit
     if (s->kv_heads < 0 || (s->kv_heads > 0 && (s->kv_heads > s->H || s->H % s->kv_heads != 0))) return false;
+    if (s->Dv != 0 && s->Dv != 64 && s->Dv != 128) return false;
     return true;
 }
 
@@ -35,10 +36,13 @@ int make_plan(const lasp_shape *s, Pass pass, lasp::Plan *p, bool token = false,
     p->B = s->B;
     p->H = s->H;
     p->N = s->N;
-    p->D = s->D;
+    p->dk = s->D;
+    p->dv = s->Dv != 0 ? s->Dv : s->D;
+    p->D = p->dk > p->dv ? p->dk : p->dv;   // the kernels' dimension; the narrower of the two is zero-padded on chip
+    if (norm && p->dk != p->dv) return LASP_ERR_SHAPE;
     p->dtype = s->dtype;
     p->kvdiv = s->kv_heads > 0 ? s->H / s->kv_heads : 1;
-    p->tile = lasp::tile_tokens(s->dtype, s->chunk, s->D);
+    p->tile = lasp::tile_tokens(s->dtype, s->chunk, p->D);
     p->ntiles = (s->N + p->tile - 1) / p->tile;
     // A short last tile is handled by the per-token-decay kernels only: with one lambda per head the
     // library synthesises log g = log(lambda) and runs those; the fused Norm has no such path.
@@ -57,7 +61,7 @@ int make_plan(const lasp_shape *s, Pass pass, lasp::Plan *p, bool token = false,
     }
     p->token = token;
     p->norm = norm;
-    p->cache_stride = lasp::cache_stride_for(p->dtype, p->tile, p->ntiles, token);
+    p->cache_stride = lasp::cache_stride_for(p->dtype, p->tile, p->ntiles, token, p->dk != p->dv);
     p->tiles_per_seg = (p->ntiles + want - 1) / want;
     if (p->cache_stride == 2) p->tiles_per_seg += p->tiles_per_seg & 1;   // segments start on cached tiles
     p->nseg = (p->ntiles + p->tiles_per_seg - 1) / p->tiles_per_seg;  // every segment non-empty
@@ -96,9 +100,8 @@ bool scratch_layout(const lasp_shape *shape, bool token, ScratchLayout *l) {
     }
     l->dk_part = l->dv_part = end;
     if (f.kvdiv > 1) {
-        const size_t per_tensor = round256(chains * (size_t)f.N * f.D * elem_bytes(f.dtype));
-        l->dv_part = l->dk_part + per_tensor;
-        end = l->dv_part + per_tensor;
+        l->dv_part = l->dk_part + round256(chains * (size_t)f.N * f.dk * elem_bytes(f.dtype));
+        end = l->dv_part + round256(chains * (size_t)f.N * f.dv * elem_bytes(f.dtype));
     }
     l->total = end;
     return true;
@@ -168,11 +171,12 @@ int run_fwd_call(const FwdCall &c) {
     if (!c.scratch || c.scratch_bytes < l.total) return LASP_ERR_WORKSPACE;
 
     const size_t esz = elem_bytes(p.dtype);
-    const size_t tb = (size_t)p.B * p.H * p.N * p.D * esz, kvb = tb / p.kvdiv;
-    const size_t sb = (size_t)p.B * p.H * p.D * p.D * sizeof(float);
+    const size_t qb = (size_t)p.B * p.H * p.N * p.dk * esz, ob = (size_t)p.B * p.H * p.N * p.dv * esz;   // q / out
+    const size_t sb = (size_t)p.B * p.H * p.dk * p.dv * sizeof(float);
     const size_t gb = (size_t)p.B * p.H * p.N * sizeof(float);
-    rc = check_buffers({{c.q, tb}, {c.k, kvb}, {c.v, kvb}, {c.kv_in, sb}, {c.decay, c.token ? gb : p.H * sizeof(float)}},
-                       {{c.out, tb}, {c.rstd, gb}, {c.kv_out, sb}, {c.cache, cache_bytes(c.shape, c.token)},
+    rc = check_buffers({{c.q, qb}, {c.k, qb / p.kvdiv}, {c.v, ob / p.kvdiv}, {c.kv_in, sb},
+                        {c.decay, c.token ? gb : p.H * sizeof(float)}},
+                       {{c.out, ob}, {c.rstd, gb}, {c.kv_out, sb}, {c.cache, cache_bytes(c.shape, c.token)},
                         {c.scratch, l.total}});
     if (rc != LASP_OK) return rc;
 
@@ -217,13 +221,14 @@ int run_bwd_call(const BwdCall &c) {
     if (!c.scratch || c.scratch_bytes < l.total) return LASP_ERR_WORKSPACE;
 
     const size_t esz = elem_bytes(p.dtype);
-    const size_t tb = (size_t)p.B * p.H * p.N * p.D * esz, kvb = tb / p.kvdiv;
-    const size_t sb = (size_t)p.B * p.H * p.D * p.D * sizeof(float);
+    const size_t qb = (size_t)p.B * p.H * p.N * p.dk * esz, ob = (size_t)p.B * p.H * p.N * p.dv * esz;   // q / out
+    const size_t sb = (size_t)p.B * p.H * p.dk * p.dv * sizeof(float);
     const size_t gb = (size_t)p.B * p.H * p.N * sizeof(float);
-    rc = check_buffers({{c.q, tb}, {c.k, kvb}, {c.v, kvb}, {c.dout, tb}, {c.dkv_out, sb}, {c.kv_out, sb}, {c.yn, tb},
-                        {c.rstd, gb}, {c.decay, c.token ? gb : p.H * sizeof(float)},
+    rc = check_buffers({{c.q, qb}, {c.k, qb / p.kvdiv}, {c.v, ob / p.kvdiv}, {c.dout, ob}, {c.dkv_out, sb}, {c.kv_out, sb},
+                        {c.yn, ob}, {c.rstd, gb}, {c.decay, c.token ? gb : p.H * sizeof(float)},
                         {c.cache, cache_bytes(c.shape, c.token)}},
-                       {{c.dq, tb}, {c.dk, kvb}, {c.dv, kvb}, {c.dlog_g, gb}, {c.dkv_in, sb}, {c.scratch, l.total}});
+                       {{c.dq, qb}, {c.dk, qb / p.kvdiv}, {c.dv, ob / p.kvdiv}, {c.dlog_g, gb}, {c.dkv_in, sb},
+                        {c.scratch, l.total}});
     if (rc != LASP_OK) return rc;
 
     hipStream_t stream = (hipStream_t)c.stream;
@@ -251,6 +256,7 @@ int make_bidir_plan(const lasp_shape *s, lasp::BidirPlan *p) {
     if (s->dtype != LASP_F32 && s->dtype != LASP_BF16) return LASP_ERR_DTYPE;
     if (!valid_dims(s)) return LASP_ERR_SHAPE;
     if (s->kv_heads != 0 && s->kv_heads != s->H) return LASP_ERR_SHAPE;
+    if (s->Dv != 0 && s->Dv != s->D) return LASP_ERR_SHAPE;
     p->B = s->B;
     p->H = s->H;
     p->N = s->N;
@@ -276,13 +282,13 @@ size_t bidir_scratch(const lasp::BidirPlan &p) { return (size_t)p.B * p.H * p.ns
 
 extern "C" {
 
-int lasp_version(void) { return 3; }
+int lasp_version(void) { return 4; }
 
 const char *lasp_status_str(int status) {
     switch (status) {
         case LASP_OK: return "ok";
         case LASP_ERR_NULL: return "a required pointer is NULL";
-        case LASP_ERR_SHAPE: return "unsupported shape (need B,H,N > 0, D in {64,128}, chunk in {64,128,256}, 0 <= segments <= ceil(N/tile); with the fused Norm N % tile == 0)";
+        case LASP_ERR_SHAPE: return "unsupported shape (need B,H,N > 0, D and Dv in {64,128} (Dv 0 = D), chunk in {64,128,256}, 0 <= segments <= ceil(N/tile); with the fused Norm N % tile == 0 and Dv = D)";
         case LASP_ERR_DTYPE: return "unsupported dtype (LASP_F32 or LASP_BF16)";
         case LASP_ERR_DECAY: return "decay must be finite and in (0, 1] (log decay: finite and <= 0)";
         case LASP_ERR_WORKSPACE: return "scratch buffer missing or too small (see lasp_scratch_bytes)";

@@ -295,6 +295,22 @@ struct TileMover {
         for (int i = 0; i < NV; ++i)
             r[i] = row0 + i * (NT / VPR) < nrows ? gload<u32x4>(g + i * (NT / VPR) * COLS, lo) : u32x4{0, 0, 0, 0};
     }
+    // Tile of a tensor whose rows hold only W <= COLS elements (row stride W): columns >= W read as zero,
+    // so a narrower key or value dimension rides through the COLS-wide kernels as zero padding.
+    template <int W>
+    DEVI void load_w(const T *g, int nrows) {
+        if constexpr (W == COLS) {
+            load(g, nrows);
+        } else {
+            static_assert(W < COLS && W % EPV == 0, "narrow rows are whole 16-byte pieces");
+            const int row0 = threadIdx.x / VPR, chunk = threadIdx.x % VPR;
+            const unsigned lo = (row0 * W + chunk * EPV) * sizeof(T);
+            const bool col_ok = chunk * EPV < W;
+#pragma unroll
+            for (int i = 0; i < NV; ++i)
+                r[i] = col_ok && row0 + i * (NT / VPR) < nrows ? gload<u32x4>(g + i * (NT / VPR) * W, lo) : u32x4{0, 0, 0, 0};
+        }
+    }
     DEVI void store(T *s, int ld) const {
         if (sizeof(T) == 2 && ld == kSwzLd) {
             static_assert(sizeof(T) != 2 || COLS != 128 || (NT / VPR) % 16 == 0, "row step must keep row % 16");
@@ -557,6 +573,19 @@ DEVI void state_load(const Lane &ln, f32x16 (&st)[D / 32], const float *g, int w
 #pragma unroll
         for (int i = 0; i < 16; ++i) st[ab][i] = gload<float>(g + (32 * ab + 8 * (i >> 2) + (i & 3)) * D, lo);
 }
+// The same for a state handed to the caller, [WK][WV] float (row stride WV), of which the kernels hold
+// the zero-padded [D][D] version: only the real rows and columns are written.
+template <int D, int WK, int WV>
+DEVI void state_store_w(const Lane &ln, const f32x16 (&st)[D / 32], float *g, int w) {
+    if constexpr (WV < D) {
+        if (32 * w >= WV) return;
+    }
+    const unsigned lo = (4 * ln.h * WV + 32 * w + ln.r) * sizeof(float);
+#pragma unroll
+    for (int ab = 0; ab < WK / 32; ++ab)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) gstore<float>(g + (32 * ab + 8 * (i >> 2) + (i & 3)) * WV, lo, st[ab][i]);
+}
 template <int D>
 DEVI void state_store(const Lane &ln, const f32x16 (&st)[D / 32], float *g, int w) {
     const unsigned lo = (4 * ln.h * D + 32 * w + ln.r) * sizeof(float);
@@ -609,13 +638,18 @@ DEVI void masked_scores(const Lane &ln, T *sP, const T *sA, const T *sB, const D
 // accumulator row = feature column 32 w + ln.acc_row(i), accumulator column
 // (lane_r) = token row0 + lane_r. Each lane owns four consecutive features of
 // its token per register group, so it stores them as one 8- or 16-byte piece.
-template <typename T, int D>
+// W <= D: the tensor's rows hold only W features (row stride W); waves whose column block lies
+// beyond them hold padding and store nothing.
+template <typename T, int D, int W = D>
 DEVI void store_out_tile_t(const Lane &ln, T *g, const f32x16 &acc, int row0, int w, int nrows = 1 << 30) {
-    const unsigned lo = (ln.r * D + 32 * w + 4 * ln.h) * sizeof(T);
+    if constexpr (W < D) {
+        if (32 * w >= W) return;
+    }
+    const unsigned lo = (ln.r * W + 32 * w + 4 * ln.h) * sizeof(T);
     if (row0 + ln.r >= nrows) return;  // token past the end of the sub-sequence
 #pragma unroll
     for (int q = 0; q < 4; ++q)
-        Elem<T>::gst4(g + row0 * D + 8 * q, lo, acc[4 * q], acc[4 * q + 1], acc[4 * q + 2], acc[4 * q + 3]);
+        Elem<T>::gst4(g + row0 * W + 8 * q, lo, acc[4 * q], acc[4 * q + 1], acc[4 * q + 2], acc[4 * q + 3]);
 }
 
 // Store a wave's column block of the state into the cache tile g ([a][c], row

@@ -11,7 +11,8 @@ namespace lasp {
 
 // Everything a launch needs, already validated by the host layer.
 struct Plan {
-    int B, H, N, D;
+    int B, H, N, D;     // D: the kernels' head dimension, max(dk, dv)
+    int dk, dv;         // key (q, k) and value (v, out) dimensions as stored; the narrower one is zero-padded to D on chip
     int dtype;          // 0 = float, 1 = bfloat16
     int tile;           // tokens per kernel tile (CT)
     int ntiles;         // ceil(N / tile); only the last tile may be short, and only with token == true
@@ -68,7 +69,7 @@ struct KernelEvents {
 int tile_tokens(int dtype, int chunk, int D);
 // Cache stride for a shape: 2 (one cached state per pair of tiles, the backward
 // walk reaches the other tile from its neighbour's state) when the kernels support it, else 1.
-int cache_stride_for(int dtype, int tile, int ntiles, bool token);
+int cache_stride_for(int dtype, int tile, int ntiles, bool token, bool mixed_dims);
 
 // log_g[b][h][s] = log(decay[h]) for all N tokens (device buffers).
 hipError_t launch_fill_logg(const Plan &p, const float *decay, float *log_g, hipStream_t stream);

@@ -43,9 +43,13 @@ namespace lasp {
 // Grouped K/V heads: query heads h*kvdiv .. h*kvdiv+kvdiv-1 of a batch entry share K/V head h. The
 // kernels index every token tensor by the query-head chain (b*H + h); K and V pointers are moved once,
 // at kernel entry, by the distance between the chain's own slot and its K/V head's slot.
-DEVI ptrdiff_t kv_shift(int chain, int H, int kvdiv, int ntok, int D) {
+DEVI ptrdiff_t kv_shift(int chain, int H, int kvdiv, int ntok, int width) {
     const int kvchain = (chain / H) * (H / kvdiv) + (chain % H) / kvdiv;
-    return (ptrdiff_t)(kvchain - chain) * ntok * D;
+    return (ptrdiff_t)(kvchain - chain) * ntok * width;
+}
+// First element of tile `t` (CT tokens) of a chain in a token tensor whose rows hold `width` elements.
+DEVI size_t tile_off(int chain, int ntok, int t, int CT, int width) {
+    return ((size_t)chain * ntok + (size_t)t * CT) * width;
 }
 
 // ---------------------------------------------------------------------------
@@ -59,13 +63,16 @@ DEVI ptrdiff_t kv_shift(int chain, int H, int kvdiv, int ntok, int D) {
 // ---------------------------------------------------------------------------
 // NORM (backward only): Y is dY, the gradient w.r.t. the normalised output; the tile is turned into dO
 // on its way to LDS from the normalised output `yn` and `rstd` ([chain][token]).
-template <typename T, int CT, int D, bool BWD, bool TOKEN, bool NORM = false>
+// WX, WY: elements per row of X and Y in memory (<= D; narrower rows are zero-padded on their way to LDS,
+// which serves key and value dimensions that differ).
+template <typename T, int CT, int D, bool BWD, bool TOKEN, bool NORM = false, int WX = D, int WY = D>
 __global__ __launch_bounds__(D * 2, 2) void k_local(const T *__restrict__ X, const T *__restrict__ Y,
                                                   const float *__restrict__ decay, float *__restrict__ scratch,
                                                   float *__restrict__ seglog, int H, int ntiles, int nseg,
                                                   int tiles_per_seg, int ntok, int kvdiv, const T *__restrict__ yn = nullptr,
                                                   const float *__restrict__ rstd = nullptr) {
     static_assert(!NORM || BWD, "the Norm prologue belongs to the backward pass");
+    static_assert(!NORM || (WX == D && WY == D), "the Norm prologue takes full-width rows");
     using E = Elem<T>;
     constexpr int NT = D * 2, LDD = tile_ld<T, D>(), DB = D / 32, NKS = CT / E::KSTEP;
     extern __shared__ __attribute__((aligned(16))) char smem[];
@@ -80,20 +87,21 @@ __global__ __launch_bounds__(D * 2, 2) void k_local(const T *__restrict__ X, con
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);  // wave index, scalar
     Lane ln = fresh_lane();
     PHASE_DECL();
-    const size_t base = (size_t)chain * ntok * D;
+    const size_t base = (size_t)chain * ntok * D;   // (full-width tensors: the Norm prologue)
     if (!BWD) {  // forward: X, Y are K, V
-        const ptrdiff_t sh = kv_shift(chain, H, kvdiv, ntok, D);
-        X += sh;
-        Y += sh;
+        X += kv_shift(chain, H, kvdiv, ntok, WX);
+        Y += kv_shift(chain, H, kvdiv, ntok, WY);
     }
+    auto xoff = [&](int t) { return tile_off(chain, ntok, t, CT, WX); };
+    auto yoff = [&](int t) { return tile_off(chain, ntok, t, CT, WY); };
     const int ntl = t1 - t0;
     auto tile_of = [&](int n) { return BWD ? t1 - 1 - n : t0 + n; };
     // the first tile is requested before anything else so that its latency covers the set-up
     // rows of tile `t` that exist: the last tile of a sub-sequence may be short (per-token decay only)
     auto nvalid = [&](int t) { return TOKEN ? min(CT, ntok - t * CT) : CT; };
     TileMover<T, CT, D, NT> mx, my;
-    mx.load(X + base + (size_t)tile_of(0) * CT * D, nvalid(tile_of(0)));
-    my.load(Y + base + (size_t)tile_of(0) * CT * D, nvalid(tile_of(0)));
+    mx.template load_w<WX>(X + xoff(tile_of(0)), nvalid(tile_of(0)));
+    my.template load_w<WY>(Y + yoff(tile_of(0)), nvalid(tile_of(0)));
     NormTile<T, CT, D, NT> mn;
     const float *rstd_c = rstd + (size_t)chain * ntok;
     if constexpr (NORM) mn.load(yn + base + (size_t)tile_of(0) * CT * D, rstd_c + (size_t)tile_of(0) * CT);
@@ -120,8 +128,8 @@ __global__ __launch_bounds__(D * 2, 2) void k_local(const T *__restrict__ X, con
             __syncthreads();
             if (n + 1 < ntl) {
                 const int tn = tile_of(n + 1);
-                mx.load(X + base + (size_t)tn * CT * D, nvalid(tn));
-                my.load(Y + base + (size_t)tn * CT * D, nvalid(tn));
+                mx.template load_w<WX>(X + xoff(tn), nvalid(tn));
+                my.template load_w<WY>(Y + yoff(tn), nvalid(tn));
                 if constexpr (NORM) mn.load(yn + base + (size_t)tn * CT * D, rstd_c + (size_t)tn * CT);
                 lgreg = TokenDecay<T, CT>::fetch(lg + (size_t)tn * CT, nvalid(tn));
             }
@@ -169,8 +177,8 @@ __global__ __launch_bounds__(D * 2, 2) void k_local(const T *__restrict__ X, con
         __syncthreads();
         PHASE(26);
         if (n + 1 < ntl) {
-            mx.load(X + base + (size_t)tile_of(n + 1) * CT * D);
-            my.load(Y + base + (size_t)tile_of(n + 1) * CT * D);
+            mx.template load_w<WX>(X + xoff(tile_of(n + 1)), CT);
+            my.template load_w<WY>(Y + yoff(tile_of(n + 1)), CT);
             if constexpr (NORM) mn.load(yn + base + (size_t)tile_of(n + 1) * CT * D, rstd_c + (size_t)tile_of(n + 1) * CT);
         }
         PHASE(27);
@@ -235,7 +243,8 @@ __global__ __launch_bounds__(D * 2, 2) void k_local(const T *__restrict__ X, con
 template <bool BWD, bool TOKEN>
 __global__ __launch_bounds__(256) void k_scan(float *__restrict__ scratch, const float *__restrict__ boundary,
                                               const float *__restrict__ decay, const float *__restrict__ seglog,
-                                              int H, int DD, int nseg, int tiles_per_seg, int ntiles, int tile) {
+                                              int H, int DD, int nseg, int tiles_per_seg, int ntiles, int tile,
+                                              int D, int wk, int wv) {
     const int chain = blockIdx.y;
     const int e = (blockIdx.x * blockDim.x + threadIdx.x) * 4;  // four consecutive state elements per thread
     if (e >= DD) return;
@@ -245,7 +254,12 @@ __global__ __launch_bounds__(256) void k_scan(float *__restrict__ scratch, const
         p_full = (float)exp2((double)(tiles_per_seg * tile) * l2);
         p_last = (float)exp2((double)((ntiles - (nseg - 1) * tiles_per_seg) * tile) * l2);
     }
-    f32x4 carry = boundary ? *(const f32x4 *)(boundary + (size_t)chain * DD + e) : f32x4{0, 0, 0, 0};
+    // The caller's state is [wk][wv]; the kernels work on its zero-padded [D][D] version (DD = D * D).
+    f32x4 carry = {0, 0, 0, 0};
+    if (boundary) {
+        const int row = e / D, col = e % D;
+        if (row < wk && col < wv) carry = *(const f32x4 *)(boundary + ((size_t)chain * wk + row) * wv + col);
+    }
     float *s = scratch + (size_t)chain * nseg * DD + e;
     constexpr int U = 8;  // segments whose local states are fetched together (independent loads)
     for (int n0 = 0; n0 < nseg; n0 += U) {
@@ -279,7 +293,8 @@ __global__ __launch_bounds__(256) void k_scan(float *__restrict__ scratch, const
 // ---------------------------------------------------------------------------
 // NORM: every output row is divided by its root mean square (plus eps under the root) before it is
 // stored, and the factor is written to rstd_out ([chain][token]) for the backward pass.
-template <typename T, int CT, int D, bool TOKEN, bool NORM = false>
+// WK, WV: elements per row of Q, K and of V, O in memory (<= D; see k_local).
+template <typename T, int CT, int D, bool TOKEN, bool NORM = false, int WK = D, int WV = D>
 __global__ __launch_bounds__(D * 2, (CT <= 64 && sizeof(T) == 2) ? 2 : 1) void k_fwd(const T *__restrict__ Q, const T *__restrict__ K,
                                                 const T *__restrict__ V, const float *__restrict__ decay,
                                                 T *__restrict__ O, float *__restrict__ kv_out,
@@ -301,19 +316,18 @@ __global__ __launch_bounds__(D * 2, (CT <= 64 && sizeof(T) == 2) ? 2 : 1) void k
     const int t1 = min(t0 + tiles_per_seg, ntiles);
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);  // wave index, scalar
     Lane ln = fresh_lane();
+    static_assert(!NORM || (WK == D && WV == D), "the Norm epilogue takes full-width rows");
     // requests first (tile, then start state), table arithmetic while they fly
-    const size_t base = (size_t)chain * ntok * D;
-    {   // K, V of this chain's K/V head
-        const ptrdiff_t sh = kv_shift(chain, H, kvdiv, ntok, D);
-        K += sh;
-        V += sh;
-    }
+    K += kv_shift(chain, H, kvdiv, ntok, WK);   // K, V of this chain's K/V head
+    V += kv_shift(chain, H, kvdiv, ntok, WV);
+    auto koff = [&](int t) { return tile_off(chain, ntok, t, CT, WK); };
+    auto voff = [&](int t) { return tile_off(chain, ntok, t, CT, WV); };
     // rows of tile `t` that exist: the last tile of a sub-sequence may be short (per-token decay only)
     auto nvalid = [&](int t) { return TOKEN ? min(CT, ntok - t * CT) : CT; };
     TileMover<T, CT, D, NT> mq, mk, mv;
-    mq.load(Q + base + (size_t)t0 * CT * D, nvalid(t0));
-    mk.load(K + base + (size_t)t0 * CT * D, nvalid(t0));
-    mv.load(V + base + (size_t)t0 * CT * D, nvalid(t0));
+    mq.template load_w<WK>(Q + koff(t0), nvalid(t0));
+    mk.template load_w<WK>(K + koff(t0), nvalid(t0));
+    mv.template load_w<WV>(V + voff(t0), nvalid(t0));
     f32x16 st[DB];
     state_load<D>(ln, st, scratch + ((size_t)chain * nseg + seg) * D * D, w);
     const auto dec = DecaySel<TOKEN, T, CT>::make(pw, decay, chain, H);
@@ -333,9 +347,9 @@ __global__ __launch_bounds__(D * 2, (CT <= 64 && sizeof(T) == 2) ? 2 : 1) void k
         if constexpr (TOKEN) dec.fill(lgreg);
         __syncthreads();
         if (t + 1 < t1) {
-            mq.load(Q + base + (size_t)(t + 1) * CT * D, nvalid(t + 1));
-            mk.load(K + base + (size_t)(t + 1) * CT * D, nvalid(t + 1));
-            mv.load(V + base + (size_t)(t + 1) * CT * D, nvalid(t + 1));
+            mq.template load_w<WK>(Q + koff(t + 1), nvalid(t + 1));
+            mk.template load_w<WK>(K + koff(t + 1), nvalid(t + 1));
+            mv.template load_w<WV>(V + voff(t + 1), nvalid(t + 1));
             if constexpr (TOKEN) lgreg = TokenDecay<T, CT>::fetch(lg + (size_t)(t + 1) * CT, nvalid(t + 1));
         }
         // masked scores P (all waves share the lower-triangular blocks)
@@ -389,9 +403,9 @@ __global__ __launch_bounds__(D * 2, (CT <= 64 && sizeof(T) == 2) ? 2 : 1) void k
                 if (w == 0 && ln.h == 0) rstd_out[(size_t)chain * ntok + (size_t)t * CT + 32 * ib + ln.r] = rs;
             }
         }
-        T *o = O + base + (size_t)t * CT * D;
+        T *o = O + voff(t);
 #pragma unroll
-        for (int ib = 0; ib < NB; ++ib) store_out_tile_t<T, D>(ln, o, acc[ib], 32 * ib, w, nvalid(t));
+        for (int ib = 0; ib < NB; ++ib) store_out_tile_t<T, D, WV>(ln, o, acc[ib], 32 * ib, w, nvalid(t));
 
         ln = fresh_lane();
         // state update: KV <- lambda^CT KV + (diag{lambda^(CT-1-j)} K)^T V, weight applied to the V fragments
@@ -405,7 +419,7 @@ __global__ __launch_bounds__(D * 2, (CT <= 64 && sizeof(T) == 2) ? 2 : 1) void k
             for (int ab = 0; ab < DB; ++ab) st[ab] = E::mfma(E::ld_ks(ln, sK, LDD, ks * E::KSTEP, 32 * ab), vd, st[ab]);
         }
     }
-    if (seg == nseg - 1) state_store<D>(ln, st, kv_out + (size_t)chain * D * D, w);
+    if (seg == nseg - 1) state_store_w<D, WK, WV>(ln, st, kv_out + (size_t)chain * WK * WV, w);
 }
 
 // ---------------------------------------------------------------------------
@@ -434,8 +448,9 @@ struct BwdSmem {
 
 // NORM: dO is dY, the gradient w.r.t. the normalised output `yn`; every dY tile is turned into dO on its
 // way to LDS (NormTile) from `yn` and `rstd` ([chain][token]).
-template <typename T, int CT, int D, bool TOKEN, bool NORM = false>
-__global__ __launch_bounds__(D * 2, (CT <= 64 && sizeof(T) == 2) ? 2 : 1) void k_bwd(const T *__restrict__ Q, const T *__restrict__ K,
+// WK, WV: elements per row of Q, K, dQ, dK and of V, dO, dV in memory (<= D; see k_local).
+template <typename T, int CT, int D, bool TOKEN, bool NORM = false, int WK = D, int WV = D>
+__global__ __launch_bounds__(D * 2, (CT <= 64 && sizeof(T) == 2 && WK == D && WV == D) ? 2 : 1) void k_bwd(const T *__restrict__ Q, const T *__restrict__ K,
                                                 const T *__restrict__ V, const T *__restrict__ dO,
                                                 const float *__restrict__ decay, const T *__restrict__ cache,
                                                 T *__restrict__ dQ, T *__restrict__ dK, T *__restrict__ dV,
@@ -477,18 +492,18 @@ __global__ __launch_bounds__(D * 2, (CT <= 64 && sizeof(T) == 2) ? 2 : 1) void k
         }
     };
 
-    const size_t base = (size_t)chain * ntok * D;
-    {   // K, V of this chain's K/V head
-        const ptrdiff_t sh = kv_shift(chain, H, kvdiv, ntok, D);
-        K += sh;
-        V += sh;
-    }
+    static_assert(!NORM || (WK == D && WV == D), "the Norm prologue takes full-width rows");
+    const size_t base = (size_t)chain * ntok * D;   // (full-width tensors: the Norm prologue)
+    K += kv_shift(chain, H, kvdiv, ntok, WK);   // K, V of this chain's K/V head
+    V += kv_shift(chain, H, kvdiv, ntok, WV);
+    auto koff = [&](int t) { return tile_off(chain, ntok, t, CT, WK); };
+    auto voff = [&](int t) { return tile_off(chain, ntok, t, CT, WV); };
     f32x16 dkv[DB];
     state_load<D>(ln, dkv, scratch + ((size_t)chain * nseg + seg) * D * D, w);
 
     TileMover<T, CT, D, NT> ma, mb;
-    ma.load(V + base + (size_t)(t1 - 1) * CT * D, nvalid(t1 - 1));
-    mb.load(dO + base + (size_t)(t1 - 1) * CT * D, nvalid(t1 - 1));
+    ma.template load_w<WV>(V + voff(t1 - 1), nvalid(t1 - 1));
+    mb.template load_w<WV>(dO + voff(t1 - 1), nvalid(t1 - 1));
     NormTile<T, CT, D, NT> mn;
     const float *rstd_c = rstd + (size_t)chain * ntok;
     if constexpr (NORM) mn.load(yn + base + (size_t)(t1 - 1) * CT * D, rstd_c + (size_t)(t1 - 1) * CT);
@@ -519,8 +534,8 @@ __global__ __launch_bounds__(D * 2, (CT <= 64 && sizeof(T) == 2) ? 2 : 1) void k
         mb.store(bufB, LDD);
         if constexpr (TOKEN) dec.fill(lgreg);
         __syncthreads();
-        ma.load(K + off, nvalid(t));
-        mb.load(Q + off, nvalid(t));
+        ma.template load_w<WK>(K + koff(t), nvalid(t));
+        mb.template load_w<WK>(Q + koff(t), nvalid(t));
         if constexpr (TOKEN) {
             if (t > t0) lgreg = TokenDecay<T, CT>::fetch(lg + (size_t)(t - 1) * CT);   // only the last tile can be short
         }
@@ -562,8 +577,8 @@ __global__ __launch_bounds__(D * 2, (CT <= 64 && sizeof(T) == 2) ? 2 : 1) void k
         mb.store(bufB, LDD);
         __syncthreads();
         if (t > t0) {
-            ma.load(V + off - (size_t)CT * D);
-            mb.load(dO + off - (size_t)CT * D);
+            ma.template load_w<WV>(V + voff(t - 1), CT);
+            mb.template load_w<WV>(dO + voff(t - 1), CT);
             if constexpr (NORM) mn.load(yn + off - (size_t)CT * D, rstd_c + (size_t)(t - 1) * CT);
         }
         masked_scores<T, CT, D, LDD, LDP>(ln, sS, bufA, bufB, dec, w);  // S^T = K Q^T
@@ -577,7 +592,7 @@ __global__ __launch_bounds__(D * 2, (CT <= 64 && sizeof(T) == 2) ? 2 : 1) void k
             for (int ib = ks / SPB; ib < NB; ++ib) accQ[ib] = E::mfma(kf, E::ld_kc(ln, sDS, LDP, 32 * ib, ks * E::KSTEP), accQ[ib]);
         }
 #pragma unroll
-        for (int ib = 0; ib < NB; ++ib) store_out_tile_t<T, D>(ln, dQ + off, accQ[ib], 32 * ib, w, nvalid(t));
+        for (int ib = 0; ib < NB; ++ib) store_out_tile_t<T, D, WK>(ln, dQ + koff(t), accQ[ib], 32 * ib, w, nvalid(t));
         float rpart[NB];
         if constexpr (TOKEN) {
 #pragma unroll
@@ -591,7 +606,7 @@ __global__ __launch_bounds__(D * 2, (CT <= 64 && sizeof(T) == 2) ? 2 : 1) void k
             for (int jb = 0; jb <= ks / SPB; ++jb) accK[jb] = E::mfma(qf, E::ld_ks(ln, sDS, LDP, ks * E::KSTEP, 32 * jb), accK[jb]);
         }
 #pragma unroll
-        for (int jb = 0; jb < NB; ++jb) store_out_tile_t<T, D>(ln, dK + off, accK[jb], 32 * jb, w, nvalid(t));
+        for (int jb = 0; jb < NB; ++jb) store_out_tile_t<T, D, WK>(ln, dK + koff(t), accK[jb], 32 * jb, w, nvalid(t));
         if constexpr (TOKEN) {
 #pragma unroll
             for (int jb = 0; jb < NB; ++jb) {
@@ -620,7 +635,7 @@ __global__ __launch_bounds__(D * 2, (CT <= 64 && sizeof(T) == 2) ? 2 : 1) void k
                 for (int jb = 0; jb <= ks / SPB; ++jb)
                     accV[jb] = E::mfma(dof[ks], E::ld_ks(ln, sS, LDP, ks * E::KSTEP, 32 * jb), accV[jb]);
 #pragma unroll
-            for (int jb = 0; jb < NB; ++jb) store_out_tile_t<T, D>(ln, dV + off, accV[jb], 32 * jb, w, nvalid(t));
+            for (int jb = 0; jb < NB; ++jb) store_out_tile_t<T, D, WV>(ln, dV + voff(t), accV[jb], 32 * jb, w, nvalid(t));
         }
         // dKV <- lambda^CT dKV + (Lambda Q)^T dO  (row weight lambda^(i+1) applied to the dO fragments)
         const float lamC = dec.whole();
@@ -637,7 +652,7 @@ __global__ __launch_bounds__(D * 2, (CT <= 64 && sizeof(T) == 2) ? 2 : 1) void k
         __syncthreads();
         flush_r(t0);
     }
-    if (seg == 0) state_store<D>(ln, dkv, dkv_in + (size_t)chain * D * D, w);
+    if (seg == 0) state_store_w<D, WK, WV>(ln, dkv, dkv_in + (size_t)chain * WK * WV, w);
 }
 
 // ---------------------------------------------------------------------------
@@ -1407,8 +1422,8 @@ __global__ __launch_bounds__(256) void k_group_sum(const T *__restrict__ part, T
     }
 }
 template <typename T>
-static hipError_t run_group_sum(const Plan &p, const void *part, void *out, hipStream_t s) {
-    const size_t per_head = (size_t)p.N * p.D;
+static hipError_t run_group_sum(const Plan &p, const void *part, void *out, int width, hipStream_t s) {
+    const size_t per_head = (size_t)p.N * width;
     const int kvchains = p.B * (p.H / p.kvdiv);
     size_t blocks = (per_head / 4 + 255) / 256;
     if (blocks > 1024) blocks = 1024;
@@ -1420,10 +1435,20 @@ static hipError_t run_group_sum(const Plan &p, const void *part, void *out, hipS
 // bfloat16 segments made of an even number of 64-token tiles are read 128 tokens
 // at a time (half the barriers, twice the bytes in flight per workgroup). With
 // per-token decay (`decay` = log g) the walk's tile is used.
-template <typename T, int CT, int D, bool BWD>
+template <typename T, int CT, int D, bool BWD, int WK = D, int WV = D>
 static hipError_t run_local(const Plan &p, const T *x, const T *y, const float *decay, float *scratch, float *seglog,
                             const T *yn, const float *rstd, hipStream_t s) {
     const int chains = p.B * p.H;
+    if constexpr (WK != D || WV != D) {   // key and value dimensions differ: the walk's tile, narrow rows zero-padded
+        constexpr size_t lds = Smem<T, CT, D>::local;
+        auto launch = [&](auto kl) -> hipError_t {
+            if (hipError_t e2 = allow_lds(kl, lds); e2 != hipSuccess) return e2;
+            kl<<<dim3(p.nseg - 1, chains), dim3(D * 2), lds, s>>>(x, y, decay, scratch, seglog, p.H, p.ntiles, p.nseg,
+                                                                p.tiles_per_seg, p.N, p.kvdiv, nullptr, nullptr);
+            return hipSuccess;
+        };
+        return p.token ? launch(k_local<T, CT, D, BWD, true, false, WK, WV>) : launch(k_local<T, CT, D, BWD, false, false, WK, WV>);
+    } else {
     if constexpr (BWD) {
         if (p.norm) {  // the Norm prologue needs a third tile in registers: the walk's tile length
             constexpr size_t lds = Smem<T, CT, D>::local;
@@ -1456,9 +1481,10 @@ static hipError_t run_local(const Plan &p, const T *x, const T *y, const float *
         return hipSuccess;
     };
     return p.token ? launch(k_local<T, CT, D, BWD, true>) : launch(k_local<T, CT, D, BWD, false>);
+    }
 }
 
-template <typename T, int CT, int D>
+template <typename T, int CT, int D, int WK = D, int WV = D>
 static hipError_t run_fwd(const Plan &p, const FwdArgs &a, hipStream_t s, const KernelEvents *ke) {
     const int chains = p.B * p.H, DD = D * D;
     constexpr size_t lds_fwd = Smem<T, CT, D>::fwd;
@@ -1466,17 +1492,17 @@ static hipError_t run_fwd(const Plan &p, const FwdArgs &a, hipStream_t s, const 
     hipError_t e;
     if (ke) (void)hipEventRecord(ke->ev[0], s);
     if (p.nseg > 1) {
-        if (e = run_local<T, CT, D, false>(p, (const T *)a.k, (const T *)a.v, a.decay, a.scratch, a.seglog, nullptr, nullptr, s);
+        if (e = run_local<T, CT, D, false, WK, WV>(p, (const T *)a.k, (const T *)a.v, a.decay, a.scratch, a.seglog, nullptr, nullptr, s);
             e != hipSuccess)
             return e;
     }
     if (ke) (void)hipEventRecord(ke->ev[1], s);
     if (p.token)
         k_scan<false, true><<<scan_grid, dim3(256), 0, s>>>(a.scratch, a.kv_in, nullptr, a.seglog, p.H, DD, p.nseg,
-                                                           p.tiles_per_seg, p.ntiles, p.tile);
+                                                           p.tiles_per_seg, p.ntiles, p.tile, D, p.dk, p.dv);
     else
         k_scan<false, false><<<scan_grid, dim3(256), 0, s>>>(a.scratch, a.kv_in, a.decay, nullptr, p.H, DD, p.nseg,
-                                                            p.tiles_per_seg, p.ntiles, p.tile);
+                                                            p.tiles_per_seg, p.ntiles, p.tile, D, p.dk, p.dv);
     if (ke) (void)hipEventRecord(ke->ev[2], s);
     auto launch = [&](auto kf) -> hipError_t {
         if (hipError_t e2 = allow_lds(kf, lds_fwd); e2 != hipSuccess) return e2;
@@ -1486,15 +1512,18 @@ static hipError_t run_fwd(const Plan &p, const FwdArgs &a, hipStream_t s, const 
                                                              a.rstd_out, a.eps);
         return hipSuccess;
     };
-    if (e = p.token ? (p.norm ? launch(k_fwd<T, CT, D, true, true>) : launch(k_fwd<T, CT, D, true>))
+    if constexpr (WK != D || WV != D) {   // (the host layer rejects the fused Norm for such shapes)
+        e = p.token ? launch(k_fwd<T, CT, D, true, false, WK, WV>) : launch(k_fwd<T, CT, D, false, false, WK, WV>);
+    } else {
+        e = p.token ? (p.norm ? launch(k_fwd<T, CT, D, true, true>) : launch(k_fwd<T, CT, D, true>))
                     : (p.norm ? launch(k_fwd<T, CT, D, false, true>) : launch(k_fwd<T, CT, D, false>));
-        e != hipSuccess)
-        return e;
+    }
+    if (e != hipSuccess) return e;
     if (ke) (void)hipEventRecord(ke->ev[3], s);
     return hipGetLastError();
 }
 
-template <typename T, int CT, int D>
+template <typename T, int CT, int D, int WK = D, int WV = D>
 static hipError_t run_bwd(const Plan &p, const BwdArgs &a, hipStream_t s, const KernelEvents *ke) {
     const int chains = p.B * p.H, DD = D * D;
     constexpr size_t lds_bwd = Smem<T, CT, D>::bwd;
@@ -1502,7 +1531,7 @@ static hipError_t run_bwd(const Plan &p, const BwdArgs &a, hipStream_t s, const 
     hipError_t e;
     if (ke) (void)hipEventRecord(ke->ev[0], s);
     if (p.nseg > 1) {
-        if (e = run_local<T, CT, D, true>(p, (const T *)a.q, (const T *)a.dout, a.decay, a.scratch, a.seglog, (const T *)a.yn,
+        if (e = run_local<T, CT, D, true, WK, WV>(p, (const T *)a.q, (const T *)a.dout, a.decay, a.scratch, a.seglog, (const T *)a.yn,
                                           a.rstd, s);
             e != hipSuccess)
             return e;
@@ -1510,12 +1539,25 @@ static hipError_t run_bwd(const Plan &p, const BwdArgs &a, hipStream_t s, const 
     if (ke) (void)hipEventRecord(ke->ev[1], s);
     if (p.token)
         k_scan<true, true><<<scan_grid, dim3(256), 0, s>>>(a.scratch, a.dkv_out, nullptr, a.seglog, p.H, DD, p.nseg,
-                                                          p.tiles_per_seg, p.ntiles, p.tile);
+                                                          p.tiles_per_seg, p.ntiles, p.tile, D, p.dk, p.dv);
     else
         k_scan<true, false><<<scan_grid, dim3(256), 0, s>>>(a.scratch, a.dkv_out, a.decay, nullptr, p.H, DD, p.nseg,
-                                                           p.tiles_per_seg, p.ntiles, p.tile);
+                                                           p.tiles_per_seg, p.ntiles, p.tile, D, p.dk, p.dv);
     if (ke) (void)hipEventRecord(ke->ev[2], s);
-    if constexpr (sizeof(T) == 2 && CT == 64) {
+    if constexpr (WK != D || WV != D) {   // the four-wave walk serves every data type here; one cached state per tile
+        auto launch = [&](auto kb) -> hipError_t {
+            if (hipError_t e2 = allow_lds(kb, lds_bwd); e2 != hipSuccess) return e2;
+            kb<<<dim3(p.nseg, chains), dim3(D * 2), lds_bwd, s>>>((const T *)a.q, (const T *)a.k, (const T *)a.v,
+                                                                 (const T *)a.dout, a.decay, (const T *)a.cache, (T *)a.dq,
+                                                                 (T *)a.dk, (T *)a.dv, a.dkv_in, (const float *)a.scratch,
+                                                                 a.rtok, p.H, p.ntiles, p.nseg, p.tiles_per_seg, p.N, p.kvdiv,
+                                                                 nullptr, nullptr);
+            return hipSuccess;
+        };
+        if (e = p.token ? launch(k_bwd<T, CT, D, true, false, WK, WV>) : launch(k_bwd<T, CT, D, false, false, WK, WV>);
+            e != hipSuccess)
+            return e;
+    } else if constexpr (sizeof(T) == 2 && CT == 64) {
       if (p.cache_stride == 2) {
         constexpr size_t lds_bwd8p = Bwd8pSmem<T, CT, D>::TOTAL;
         static_assert(lds_bwd8p <= 163840, "LDS budget of one gfx950 CU exceeded");
@@ -1565,13 +1607,13 @@ static hipError_t run_bwd(const Plan &p, const BwdArgs &a, hipStream_t s, const 
             return e;
     }
     if (p.kvdiv > 1) {
-        if (e = run_group_sum<T>(p, a.dk, a.dk_out, s); e != hipSuccess) return e;
-        if (e = run_group_sum<T>(p, a.dv, a.dv_out, s); e != hipSuccess) return e;
+        if (e = run_group_sum<T>(p, a.dk, a.dk_out, p.dk, s); e != hipSuccess) return e;
+        if (e = run_group_sum<T>(p, a.dv, a.dv_out, p.dv, s); e != hipSuccess) return e;
     }
     if (ke) (void)hipEventRecord(ke->ev[3], s);
     if (p.token && a.dlog_g)
         k_dlg<<<dim3((p.N + kDlgBlock - 1) / kDlgBlock, chains), dim3(256), 0, s>>>(a.rtok, a.kv_out, a.dkv_out, a.dlog_g,
-                                                                                      p.N, DD);
+                                                                                      p.N, WK * WV);
     return hipGetLastError();
 }
 
@@ -1598,9 +1640,9 @@ extern "C" int lasp_debug_phases(unsigned long long *out256, int reset) {
 }
 #endif
 
-int cache_stride_for(int dtype, int tile, int ntiles, bool token) {
+int cache_stride_for(int dtype, int tile, int ntiles, bool token, bool mixed_dims) {
     (void)token;  // both decay models have the pair kernel
-    return (dtype == 1 && tile == 64 && ntiles % 2 == 0) ? 2 : 1;
+    return (dtype == 1 && tile == 64 && ntiles % 2 == 0 && !mixed_dims) ? 2 : 1;
 }
 
 // Tokens per kernel tile: 32 for float data, 64 for bfloat16 data, whatever the
@@ -1613,6 +1655,14 @@ int tile_tokens(int dtype, int chunk, int D) {
 }
 
 #define LASP_DISPATCH(FN, ARGS)                                                        \
+    if (p.dk != p.dv) {   /* D = 128 kernels, the narrower of the two zero-padded */     \
+        if (p.dtype == 0) {                                                            \
+            if (p.dk == 64) return FN<float, 32, 128, 64, 128>(p, ARGS, stream, ke);      \
+            return FN<float, 32, 128, 128, 64>(p, ARGS, stream, ke);                      \
+        }                                                                              \
+        if (p.dk == 64) return FN<bf16_t, 64, 128, 64, 128>(p, ARGS, stream, ke);         \
+        return FN<bf16_t, 64, 128, 128, 64>(p, ARGS, stream, ke);                         \
+    }                                                                                  \
     if (p.dtype == 0) {                                                                \
         if (p.D == 64) return FN<float, 32, 64>(p, ARGS, stream, ke);                     \
         return FN<float, 32, 128>(p, ARGS, stream, ke);                                    \

@@ -49,10 +49,11 @@ def run_gpu(inp: Inputs, T: int = 1, segments: int = 0, backward: bool = True, c
     cfg = inp.cfg
     B, H, N, D = inp.q.shape
     kv_heads = inp.k.shape[1] if inp.k.shape[1] != H else 0   # grouped K/V heads: k, v are [B,kv_heads,N,D]
+    Dv = inp.v.shape[3] if inp.v.shape[3] != D else 0         # value dimension that differs from the key dimension
     dt = TORCH_DTYPE[cfg.dtype]
     token = inp.log_g is not None
     seq = LaspSequence(B, H, N, D, chunk or cfg.chunk, dt, T=T, segments=segments, device=device,
-                       need_backward=backward, token_decay=token, norm_eps=norm_eps, kv_heads=kv_heads)
+                       need_backward=backward, token_decay=token, norm_eps=norm_eps, kv_heads=kv_heads, Dv=Dv)
     q, k, v = (shards(x, T, cfg.dtype, device) for x in (inp.q, inp.k, inp.v))
     if token:
         n = N // T
@@ -60,7 +61,7 @@ def run_gpu(inp: Inputs, T: int = 1, segments: int = 0, backward: bool = True, c
     else:
         decay = torch.from_numpy(inp.decay).to(device)
     kv_in = torch.from_numpy(inp.kv_in).to(device) if inp.kv_in is not None else None
-    out = [torch.full_like(x, float("nan")) for x in q]
+    out = [torch.full((B, H, x.shape[2], inp.v.shape[3]), float("nan"), dtype=x.dtype, device=device) for x in q]
     rstd = None
     if norm_eps is not None:
         rstd = [torch.full((B, H, N // T), float("nan"), dtype=torch.float32, device=device) for _ in range(T)]
@@ -72,7 +73,7 @@ def run_gpu(inp: Inputs, T: int = 1, segments: int = 0, backward: bool = True, c
         do = shards(inp.dout, T, cfg.dtype, device)
         g = torch.from_numpy(inp.dkv_out).to(device) if inp.dkv_out is not None else None
         dq = [torch.full_like(x, float("nan")) for x in q]
-        dk, dv = ([torch.full_like(x, float("nan")) for x in k] for _ in range(2))
+        dk, dv = ([torch.full_like(x, float("nan")) for x in y] for y in (k, v))
         dlg = [torch.full_like(x, float("nan")) for x in decay] if token else None
         dkv_in = seq.backward(q, k, v, do, decay, dq, dk, dv, g, dlog_g=dlg, out=out, rstd=rstd)
         res.update(dq=to_host(dq), dk=to_host(dk), dv=to_host(dv), dkv_in=dkv_in.cpu().numpy().astype(np.float64))

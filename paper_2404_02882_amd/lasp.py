@@ -23,7 +23,7 @@ STATUS_NAMES = {0: "LASP_OK", 1: "LASP_ERR_NULL", 2: "LASP_ERR_SHAPE", 3: "LASP_
 class Shape(ctypes.Structure):
     _fields_ = [("B", ctypes.c_int32), ("H", ctypes.c_int32), ("N", ctypes.c_int32), ("D", ctypes.c_int32),
                 ("chunk", ctypes.c_int32), ("dtype", ctypes.c_int32), ("segments", ctypes.c_int32),
-                ("kv_heads", ctypes.c_int32)]
+                ("kv_heads", ctypes.c_int32), ("Dv", ctypes.c_int32)]
 
 
 class LaspError(RuntimeError):
@@ -117,12 +117,12 @@ def version() -> int:
     return int(lib.lasp_version())
 
 
-def make_shape(B, H, N, D, chunk, dtype, segments=0, kv_heads=0) -> Shape:
+def make_shape(B, H, N, D, chunk, dtype, segments=0, kv_heads=0, Dv=0) -> Shape:
     if isinstance(dtype, torch.dtype):
         dtype = {torch.float32: LASP_F32, torch.bfloat16: LASP_BF16}.get(dtype, -1)
     elif isinstance(dtype, str):
         dtype = {"f32": LASP_F32, "bf16": LASP_BF16}.get(dtype, -1)
-    return Shape(int(B), int(H), int(N), int(D), int(chunk), int(dtype), int(segments), int(kv_heads))
+    return Shape(int(B), int(H), int(N), int(D), int(chunk), int(dtype), int(segments), int(kv_heads), int(Dv))
 
 
 def check_shape(shape: Shape) -> int:

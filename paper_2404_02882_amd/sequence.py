@@ -19,14 +19,16 @@ from . import lasp
 
 class LaspSequence:
     def __init__(self, B, H, N, D, chunk, dtype: torch.dtype, T=1, segments=0, device="cuda", need_backward=True,
-                 token_decay=False, norm_eps: Optional[float] = None, kv_heads=0):
+                 token_decay=False, norm_eps: Optional[float] = None, kv_heads=0, Dv=0):
         if N % T != 0:
             raise ValueError("N must be a multiple of T")
         self.B, self.H, self.N, self.D, self.T = B, H, N, D, T
         self.n_sub = N // T
         self.dtype = dtype
         # kv_heads: k, v, dk, dv shards are [B,kv_heads,N/T,D]; groups of H/kv_heads query heads share them
-        self.shape = lasp.make_shape(B, H, self.n_sub, D, chunk, dtype, segments, kv_heads)
+        # Dv: value dimension when it differs from the key dimension D (v, out, dout, dv shards are [..,Dv],
+        # states [B,H,D,Dv])
+        self.shape = lasp.make_shape(B, H, self.n_sub, D, chunk, dtype, segments, kv_heads, Dv)
         rc = lasp.check_shape(self.shape)
         if rc != 0:
             raise lasp.LaspError(rc, "LaspSequence")
@@ -43,8 +45,8 @@ class LaspSequence:
                        for _ in range(T)] if need_backward else [None] * T
         st = dict(dtype=torch.float32, device=device)
         # kv[t] = state entering shard t (kv[T] = final); dkv[t] = gradient w.r.t. kv[t]
-        self.kv = [torch.zeros(B, H, D, D, **st) for _ in range(T + 1)]
-        self.dkv = [torch.zeros(B, H, D, D, **st) for _ in range(T + 1)] if need_backward else None
+        self.kv = [torch.zeros(B, H, D, Dv or D, **st) for _ in range(T + 1)]
+        self.dkv = [torch.zeros(B, H, D, Dv or D, **st) for _ in range(T + 1)] if need_backward else None
         self.has_kv_in = False
         self.has_dkv_out = False
 

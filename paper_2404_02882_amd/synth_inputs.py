@@ -36,6 +36,7 @@ class Config:
     token_decay: bool = False   # a decay g_s per token (log_g) instead of one lambda per head
     norm_eps: Optional[float] = None   # outputs are RMS-normalised per row (fused Norm); dout is then the gradient w.r.t. them
     bidirectional: bool = False   # unmasked attention O = Q (K^T V): no decay, no states handed over
+    Dv: int = 0     # value dimension when it differs from the key dimension D (0 = D)
 
 
 # The five workloads (shapes, decay and value recipe as stated for the build).
@@ -54,6 +55,8 @@ CONFIGS = {
     # c2's / c3's shapes without the causal mask (bidirectional attention)
     "b2": Config("b2", B=2, H=8, N=4096, D=64, chunk=64, dtype="bf16", T=4, seed=1032, decay="one", bidirectional=True),
     "b3": Config("b3", B=1, H=16, N=32768, D=128, chunk=128, dtype="bf16", seed=1033, decay="one", bidirectional=True),
+    # c3's shape with a key dimension of 64 and a value dimension of 128
+    "m3": Config("m3", B=1, H=16, N=32768, D=64, chunk=128, dtype="bf16", seed=1043, Dv=128),
 }
 
 
@@ -119,19 +122,21 @@ def make_inputs(cfg: Config, n_tokens: Optional[int] = None, with_states: bool =
     N = cfg.N if n_tokens is None else int(n_tokens)
     rng = np.random.default_rng(cfg.seed if seed is None else seed)
     shape = (cfg.B, cfg.H, N, cfg.D)
+    dv = cfg.Dv or cfg.D
+    vshape = (cfg.B, cfg.H, N, dv)
     scale = np.float32(cfg.D ** -0.5)
     q = rng.standard_normal(shape, dtype=np.float32) * scale
     k = rng.standard_normal(shape, dtype=np.float32) * scale
-    v = rng.standard_normal(shape, dtype=np.float32) * scale
-    dout = rng.standard_normal(shape, dtype=np.float32)
+    v = rng.standard_normal(vshape, dtype=np.float32) * np.float32(dv ** -0.5)
+    dout = rng.standard_normal(vshape, dtype=np.float32)
     if cfg.k_outlier_frac > 0.0:
         rows = rng.random((cfg.B, cfg.H, N)) < cfg.k_outlier_frac
         k[rows] *= np.float32(cfg.k_outlier_scale)
     decay = np.ones(cfg.H, dtype=np.float32) if cfg.decay == "one" else decay_schedule(cfg.H)
     kv_in = dkv_out = None
     if with_states:
-        kv_in = rng.standard_normal((cfg.B, cfg.H, cfg.D, cfg.D), dtype=np.float32)
-        dkv_out = rng.standard_normal((cfg.B, cfg.H, cfg.D, cfg.D), dtype=np.float32)
+        kv_in = rng.standard_normal((cfg.B, cfg.H, cfg.D, dv), dtype=np.float32)
+        dkv_out = rng.standard_normal((cfg.B, cfg.H, cfg.D, dv), dtype=np.float32)
     log_g = token_log_decay(cfg, N, cfg.seed if seed is None else seed) if cfg.token_decay else None
     return Inputs(cfg, quantize(q, cfg.dtype), quantize(k, cfg.dtype), quantize(v, cfg.dtype),
                   quantize(dout, cfg.dtype), decay, kv_in, dkv_out, log_g)
