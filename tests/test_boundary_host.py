@@ -343,3 +343,32 @@ def test_bidir_rejects_before_launch(L):
     assert bwd(*a) == 6                                            # dv aliases dk
     a = list(ok); a[0] = ctypes.byref(L.make_shape(1, 2, 0, 64, 64, "bf16"))
     assert bwd(*a) == 2
+
+
+# ---------------------------------------------------------------- key and value dimensions that differ
+def test_value_dimension_shapes_and_sizes(L):
+    base = dict(B=1, H=2, N=256, D=64, chunk=64, dtype="bf16")
+    assert L.check_shape(L.make_shape(**base, Dv=0)) == 0
+    assert L.check_shape(L.make_shape(**base, Dv=64)) == 0
+    assert L.check_shape(L.make_shape(**base, Dv=128)) == 0
+    assert L.check_shape(L.make_shape(**base, Dv=96)) == 2
+    assert L.check_shape(L.make_shape(**base, Dv=-64)) == 2
+    mixed, wide = L.make_shape(**base, Dv=128), L.make_shape(**dict(base, D=128))
+    # scratch and the state cache hold padded max(D, Dv)^2 states: at least what the equal-dimension shape needs
+    assert L.scratch_bytes(mixed) >= L.scratch_bytes(wide) > 0
+    assert L.state_cache_bytes(mixed) >= L.state_cache_bytes(wide) > 0
+    assert L.tile_tokens(mixed) == L.tile_tokens(wide)
+
+
+def test_value_dimension_sizes_enter_the_alias_check_and_norm_is_rejected(L):
+    s = L.make_shape(1, 1, 64, 64, 64, "bf16", Dv=128)       # q: 8192 bytes, out: 16384 bytes
+    sb = L.scratch_bytes(s)
+    q, k, v, kvin, dec, out, kvout, cache, scr = [_fake(i) for i in range(1, 10)]
+    inside_out = ctypes.c_void_p(out.value + 16384 - 16)
+    assert L.lib.lasp_fwd(ctypes.byref(s), q, k, v, kvin, dec, out, inside_out, cache, scr, sb, None) == 6
+    s2 = L.make_shape(1, 1, 64, 128, 64, "bf16", Dv=64)      # q: 16384 bytes
+    inside_q = ctypes.c_void_p(q.value + 16384 - 16)
+    assert L.lib.lasp_fwd(ctypes.byref(s2), q, k, v, kvin, dec, inside_q, kvout, cache, scr, L.scratch_bytes(s2), None) == 6
+    rstd = _fake(11)
+    assert L.lib.lasp_fwd_norm(ctypes.byref(s), q, k, v, kvin, dec, ctypes.c_float(1e-5), out, rstd, kvout, cache, scr,
+                               sb, None) == 2
