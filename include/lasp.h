@@ -18,6 +18,8 @@
  *     D contiguous elements of `dtype` (LASP_F32: float, LASP_BF16: bfloat16).
  *   - kv_in, kv_out, dkv_out, dkv_in: [B][H][D][D] float, state[a][c] with a the
  *     key/query feature and c the value feature (KV = sum k[a] v[c]).
+ *     (With lasp_shape.Dv set, value-side tensors have Dv columns and states are
+ *     [D][Dv]; with lasp_shape.kv_heads set, k, v, dk, dv have kv_heads heads.)
  *   - decay: [H] float on the device, lambda_h in (0, 1], shared over the
  *     batch; lambda = 1 is ordinary linear attention (Sec. 3.2). It is not
  *     learnable, so no gradient is produced for it.
@@ -40,7 +42,7 @@ extern "C" {
 typedef enum {
     LASP_OK = 0,
     LASP_ERR_NULL = 1,      /* a required pointer is NULL */
-    LASP_ERR_SHAPE = 2,     /* B,H,N <= 0; D not 64/128; chunk not 64/128/256; bad segments or kv_heads; Norm with N % tile != 0 */
+    LASP_ERR_SHAPE = 2,     /* B,H,N <= 0; D or Dv not 64/128; chunk not 64/128/256; bad segments or kv_heads; Norm with N % tile != 0 or Dv != D */
     LASP_ERR_DTYPE = 3,     /* dtype is neither LASP_F32 nor LASP_BF16 */
     LASP_ERR_DECAY = 4,     /* lasp_check_decay: a value outside (0, 1] or not finite */
     LASP_ERR_WORKSPACE = 5, /* scratch missing or smaller than lasp_scratch_bytes() */
