@@ -960,7 +960,8 @@ struct Bwd8pSmem {
     static constexpr size_t TOTAL = PW_OFF + (6 * CT + 4 + 8 * CT) * sizeof(float);
 };
 
-template <typename T, int CT, int D, bool TOKEN, bool NORM = false>
+// WK, WV: elements per row of Q, K, dQ, dK and of V, dO, dV in memory (<= D; see k_local).
+template <typename T, int CT, int D, bool TOKEN, bool NORM = false, int WK = D, int WV = D>
 __global__ __launch_bounds__(D * 4) void k_bwd8p(const T *__restrict__ Q, const T *__restrict__ K,
                                                   const T *__restrict__ V, const T *__restrict__ dO,
                                                   const float *__restrict__ decay, const T *__restrict__ cache,
@@ -973,6 +974,7 @@ __global__ __launch_bounds__(D * 4) void k_bwd8p(const T *__restrict__ Q, const 
     using F = typename E::frag;
     using SM = Bwd8pSmem<T, CT, D>;
     static_assert(CT == 64, "two 32-token blocks per tile");
+    static_assert(!NORM || (WK == D && WV == D), "the Norm prologue takes full-width rows");
     constexpr int NT = D * 4, NW = D / 32, LDD = SM::LDD, LDP = SM::LDP, DB = D / 32, NB = CT / 32, NKS = CT / E::KSTEP,
                   NKD = D / E::KSTEP, SPB = 32 / E::KSTEP;
     extern __shared__ __attribute__((aligned(16))) char smem[];
@@ -997,13 +999,12 @@ __global__ __launch_bounds__(D * 4) void k_bwd8p(const T *__restrict__ Q, const 
     Lane ln = fresh_lane();
     PHASE_DECL();
 
-    const size_t base = (size_t)chain * ntok * D;
-    {   // K, V of this chain's K/V head
-        const ptrdiff_t sh = kv_shift(chain, H, kvdiv, ntok, D);
-        K += sh;
-        V += sh;
-    }
-    const size_t TS = (size_t)CT * D;  // elements per tile
+    const size_t base = (size_t)chain * ntok * D;   // (full-width tensors: the Norm prologue)
+    K += kv_shift(chain, H, kvdiv, ntok, WK);   // K, V of this chain's K/V head
+    V += kv_shift(chain, H, kvdiv, ntok, WV);
+    auto koff = [&](int t) { return tile_off(chain, ntok, t, CT, WK); };
+    auto voff = [&](int t) { return tile_off(chain, ntok, t, CT, WV); };
+    const size_t TS = (size_t)CT * D;  // elements per full-width tile
     TileMover<T, CT, D, NT> mvO, moX, mkO, mqX, mvE, mkE;   // moX / mqX carry dO, Q of the O tile, then of the E tile
     TileMover<T, D, D, NT> mc;                               // cached state at the start of the E tile
     const T *ctile = cache + (size_t)chain * (ntiles / 2) * D * D;
@@ -1047,12 +1048,11 @@ __global__ __launch_bounds__(D * 4) void k_bwd8p(const T *__restrict__ Q, const 
     // of the pair before has taken their registers' contents. Fewer requests are then issued in one
     // burst, which is where the waves stall at the memory pipeline's entry.
     auto load_pair_kv = [&](int tE) {
-        const size_t oE = base + (size_t)tE * TS, oO = oE + TS;
         const int nvO = TOKEN ? min(CT, ntok - (tE + 1) * CT) : CT;   // only the O tile of the last pair can be short
-        mvO.load(V + oO, nvO);
-        mkO.load(K + oO, nvO);
-        mvE.load(V + oE);
-        mkE.load(K + oE);
+        mvO.template load_w<WV>(V + voff(tE + 1), nvO);
+        mkO.template load_w<WK>(K + koff(tE + 1), nvO);
+        mvE.template load_w<WV>(V + voff(tE), CT);
+        mkE.template load_w<WK>(K + koff(tE), CT);
         mc.load(ctile + (size_t)(tE / 2) * D * D);
     };
     auto load_pair_rest = [&](int tE) {
@@ -1063,8 +1063,8 @@ __global__ __launch_bounds__(D * 4) void k_bwd8p(const T *__restrict__ Q, const 
             lgO = TokenDecay<T, CT>::fetch(lg + (size_t)(tE + 1) * CT, nvO);
             lgE = TokenDecay<T, CT>::fetch(lg + (size_t)tE * CT);
         }
-        moX.load(dO + oO, nvO);
-        mqX.load(Q + oO, nvO);
+        moX.template load_w<WV>(dO + voff(tE + 1), nvO);
+        mqX.template load_w<WK>(Q + koff(tE + 1), nvO);
     };
     auto load_pair = [&](int tE) {
         load_pair_kv(tE);
@@ -1158,10 +1158,10 @@ __global__ __launch_bounds__(D * 4) void k_bwd8p(const T *__restrict__ Q, const 
         }
     };
 
-    // dQ, this group's dV or dK, and the dKV update for the tile at element offset `off`
+    // dQ, this group's dV or dK, and the dKV update for tile `t`
     // `cross` (the O tile): the cached state is the one the E tile starts from, so dQ takes the E tile
     // as the first half of its own chunk: far weights on the state term, plus the E tile's keys through sDX.
-    auto products = [&](const auto &dec, const T *pV, const T *pK, size_t off, int nrows, bool cross) {
+    auto products = [&](const auto &dec, const T *pV, const T *pK, int t, int nrows, bool cross) {
         const T *sX1 = rg ? pV : pK;  // inter operand: token rows, features contracted with the state
         float rq = 0.0f;  // per-token decay: q_i . dq_i over this wave's features, tokens i of block rg
         {   // dQ^T[a in w][i], tokens i of block rg
@@ -1179,7 +1179,7 @@ __global__ __launch_bounds__(D * 4) void k_bwd8p(const T *__restrict__ Q, const 
             auto intra = [&](int ks) { return FragPair<F>{E::ld_ks(ln, pK, LDD, ks * E::KSTEP, 32 * w), E::ld_kc(ln, sDS, LDP, r0, ks * E::KSTEP)}; };
             if (rg == 0) pipelined<SPB>(intra, fma);
             else pipelined<2 * SPB>(intra, fma);
-            store_out_tile_t<T, D>(ln, dQ + off, acc, r0, w, nrows);
+            store_out_tile_t<T, D, WK>(ln, dQ + koff(t), acc, r0, w, nrows);
             if constexpr (TOKEN) rq = rowdot<T>(ln, acc, sQ, LDD, r0, w);
         }
         ln = fresh_lane();
@@ -1218,7 +1218,14 @@ __global__ __launch_bounds__(D * 4) void k_bwd8p(const T *__restrict__ Q, const 
                         if (jb <= ks / SPB) acc[jb] = E::mfma(f.a, f.b[jb], acc[jb]);
                 });
 #pragma unroll
-            for (int jb = 0; jb < NB; ++jb) store_out_tile_t<T, D>(ln, gOut + off, acc[jb], 32 * jb, w, nrows);
+            for (int jb = 0; jb < NB; ++jb) {
+                if constexpr (WK == WV) {
+                    store_out_tile_t<T, D, WK>(ln, gOut + koff(t), acc[jb], 32 * jb, w, nrows);
+                } else {
+                    if (rg) store_out_tile_t<T, D, WK>(ln, dK + koff(t), acc[jb], 32 * jb, w, nrows);
+                    else store_out_tile_t<T, D, WV>(ln, dV + voff(t), acc[jb], 32 * jb, w, nrows);
+                }
+            }
             if constexpr (TOKEN) {
 #pragma unroll
                 for (int jb = 0; jb < NB; ++jb) {
@@ -1251,7 +1258,7 @@ __global__ __launch_bounds__(D * 4) void k_bwd8p(const T *__restrict__ Q, const 
     };
 
     for (int tE = t1 - 2; tE >= t0; tE -= 2) {
-        const size_t offE = base + (size_t)tE * TS, offO = offE + TS;
+        const size_t offE = base + (size_t)tE * TS;   // (the Norm prologue's full-width tensor)
         __syncthreads();  // previous pair fully consumed
         ln = fresh_lane();
         PHASE(0);
@@ -1272,8 +1279,8 @@ __global__ __launch_bounds__(D * 4) void k_bwd8p(const T *__restrict__ Q, const 
         __syncthreads();
         ln = fresh_lane();
         PHASE(1);
-        moX.load(dO + offE);
-        mqX.load(Q + offE);
+        moX.template load_w<WV>(dO + voff(tE), CT);
+        mqX.template load_w<WK>(Q + koff(tE), CT);
         if constexpr (NORM) mnX.load(yn + offE, rstd_c + (size_t)tE * CT);
         PHASE(2);
         // ---- O tile ----
@@ -1284,7 +1291,7 @@ __global__ __launch_bounds__(D * 4) void k_bwd8p(const T *__restrict__ Q, const 
         __syncthreads();
         ln = fresh_lane();
         PHASE(5);
-        products(decO, sVO, sKO, offO, TOKEN ? min(CT, ntok - (tE + 1) * CT) : CT, true);
+        products(decO, sVO, sKO, tE + 1, TOKEN ? min(CT, ntok - (tE + 1) * CT) : CT, true);
         PHASE(6);
         __syncthreads();  // O tile consumed: sdO, sQ are free
         ln = fresh_lane();
@@ -1304,7 +1311,7 @@ __global__ __launch_bounds__(D * 4) void k_bwd8p(const T *__restrict__ Q, const 
         __syncthreads();
         ln = fresh_lane();
         PHASE(11);
-        products(decE, sVE, sKE, offE, CT, false);
+        products(decE, sVE, sKE, tE, CT, false);
         PHASE(12);
     }
     PHASE_FLUSH();
@@ -1312,7 +1319,7 @@ __global__ __launch_bounds__(D * 4) void k_bwd8p(const T *__restrict__ Q, const 
         __syncthreads();
         flush_r(t0);
     }
-    if (seg == 0 && rg == 0) state_store<D>(ln, st, dkv_in + (size_t)chain * D * D, w);
+    if (seg == 0 && rg == 0) state_store_w<D, WK, WV>(ln, st, dkv_in + (size_t)chain * WK * WV, w);
 }
 
 // ---------------------------------------------------------------------------
@@ -1544,7 +1551,25 @@ static hipError_t run_bwd(const Plan &p, const BwdArgs &a, hipStream_t s, const 
         k_scan<true, false><<<scan_grid, dim3(256), 0, s>>>(a.scratch, a.dkv_out, a.decay, nullptr, p.H, DD, p.nseg,
                                                            p.tiles_per_seg, p.ntiles, p.tile, D, p.dk, p.dv);
     if (ke) (void)hipEventRecord(ke->ev[2], s);
-    if constexpr (WK != D || WV != D) {   // the four-wave walk serves every data type here; one cached state per tile
+    if constexpr (sizeof(T) == 2 && CT == 64 && (WK != D || WV != D)) {
+        if (p.cache_stride == 2) {   // even tile count: the pair kernel, as for equal dimensions
+            constexpr size_t lds_bwd8p = Bwd8pSmem<T, CT, D>::TOTAL;
+            auto launch = [&](auto kb) -> hipError_t {
+                if (hipError_t e2 = allow_lds(kb, lds_bwd8p); e2 != hipSuccess) return e2;
+                kb<<<dim3(p.nseg, chains), dim3(D * 4), lds_bwd8p, s>>>((const T *)a.q, (const T *)a.k, (const T *)a.v,
+                                                                        (const T *)a.dout, a.decay, (const T *)a.cache, (T *)a.dq,
+                                                                        (T *)a.dk, (T *)a.dv, a.dkv_in, (const float *)a.scratch,
+                                                                        a.rtok, p.H, p.ntiles, p.nseg, p.tiles_per_seg, p.N, p.kvdiv,
+                                                                        nullptr, nullptr);
+                return hipSuccess;
+            };
+            if (e = p.token ? launch(k_bwd8p<T, CT, D, true, false, WK, WV>) : launch(k_bwd8p<T, CT, D, false, false, WK, WV>);
+                e != hipSuccess)
+                return e;
+        }
+    }
+    if constexpr (WK != D || WV != D) {   // otherwise the four-wave walk, one cached state per tile
+      if (!(sizeof(T) == 2 && CT == 64 && p.cache_stride == 2)) {
         auto launch = [&](auto kb) -> hipError_t {
             if (hipError_t e2 = allow_lds(kb, lds_bwd); e2 != hipSuccess) return e2;
             kb<<<dim3(p.nseg, chains), dim3(D * 2), lds_bwd, s>>>((const T *)a.q, (const T *)a.k, (const T *)a.v,
@@ -1557,6 +1582,7 @@ static hipError_t run_bwd(const Plan &p, const BwdArgs &a, hipStream_t s, const 
         if (e = p.token ? launch(k_bwd<T, CT, D, true, false, WK, WV>) : launch(k_bwd<T, CT, D, false, false, WK, WV>);
             e != hipSuccess)
             return e;
+      }
     } else if constexpr (sizeof(T) == 2 && CT == 64) {
       if (p.cache_stride == 2) {
         constexpr size_t lds_bwd8p = Bwd8pSmem<T, CT, D>::TOTAL;
@@ -1641,8 +1667,9 @@ extern "C" int lasp_debug_phases(unsigned long long *out256, int reset) {
 #endif
 
 int cache_stride_for(int dtype, int tile, int ntiles, bool token, bool mixed_dims) {
-    (void)token;  // both decay models have the pair kernel
-    return (dtype == 1 && tile == 64 && ntiles % 2 == 0 && !mixed_dims) ? 2 : 1;
+    (void)token;       // both decay models have the pair kernel,
+    (void)mixed_dims;  // and so do key and value dimensions that differ
+    return (dtype == 1 && tile == 64 && ntiles % 2 == 0) ? 2 : 1;
 }
 
 // Tokens per kernel tile: 32 for float data, 64 for bfloat16 data, whatever the
