@@ -32,6 +32,8 @@ MEASURED_TRAFFIC_BYTES = {
            "fwd_local": int((250.1 + 31.0) * _MIB), "bwd_local": int((242.0 + 15.0) * _MIB)},
     "n3": {"fwd_walk": int((416.2 + 260.6) * _MIB), "bwd_walk": int((789.1 + 385.0) * _MIB),
            "fwd_local": int((248.1 + 31.0) * _MIB), "bwd_local": int((362.0 + 15.0) * _MIB)},
+    "m3": {"fwd_walk": int((288.2 + 256.7) * _MIB), "bwd_walk": int((529.2 + 256.5) * _MIB),
+           "fwd_local": int((186.1 + 31.0) * _MIB), "bwd_local": int((180.1 + 15.0) * _MIB)},
     "b3": {"bwd_apply": int((401.8 + 384.0) * _MIB), "fwd_apply": int((136.2 + 128.0) * _MIB),
            "state_reduce": int((256.1 + 16.0) * _MIB)},
 }
