@@ -41,7 +41,7 @@ __global__ __launch_bounds__(D * 2, 2) void k_bidir_reduce(const T *__restrict__
     const size_t base = (size_t)chain * ntok * D;
     auto nvalid = [&](int t) { return min(CT, ntok - t * CT); };
     // Two tiles are in flight at any time: a streaming sum has nothing else to hide the memory latency with.
-    TileMover<T, CT, D, NT> mx[2], my[2];
+    TileMover<T, CT, D, NT, true> mx[2], my[2];   // streaming (non-temporal) loads
     auto request = [&](int b, int t) {
         if (t < t1) {
             mx[b].load(X + base + (size_t)t * CT * D, nvalid(t));

@@ -99,7 +99,7 @@ __global__ __launch_bounds__(D * 2, 2) void k_local(const T *__restrict__ X, con
     // the first tile is requested before anything else so that its latency covers the set-up
     // rows of tile `t` that exist: the last tile of a sub-sequence may be short (per-token decay only)
     auto nvalid = [&](int t) { return TOKEN ? min(CT, ntok - t * CT) : CT; };
-    TileMover<T, CT, D, NT> mx, my;
+    TileMover<T, CT, D, NT, true> mx, my;   // streaming (non-temporal) loads
     mx.template load_w<WX>(X + xoff(tile_of(0)), nvalid(tile_of(0)));
     my.template load_w<WY>(Y + yoff(tile_of(0)), nvalid(tile_of(0)));
     NormTile<T, CT, D, NT> mn;
