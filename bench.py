@@ -46,6 +46,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--config", default="c3", help="named workload (c3 is the headline; g3 = c3 with a decay per token, n3 = c3 with the fused Norm, b3 = c3 without mask and decay, m3 = c3 with d_k = 64, d_v = 128)")
     ap.add_argument("--segments", type=int, default=0)
+    ap.add_argument("--sub-sequences", type=int, default=0,
+                    help="process the sequence as this many sub-sequences with the state handed over (0 = the config's T)")
     ap.add_argument("--graph", action="store_true",
                     help="time the step as replays of one HIP graph (pays off when the T-loop is launch-bound); "
                          "per-kernel times then come from a short eager pass before the timed region")
@@ -66,6 +68,9 @@ def main():
     from paper_2404_02882_amd.sequence import LaspSequence
 
     cfg = si.CONFIGS[args.config]
+    if args.sub_sequences > 0:
+        import dataclasses
+        cfg = dataclasses.replace(cfg, T=args.sub_sequences)
     dev = "cuda:0"
     torch.cuda.set_device(0)
     if cfg.bidirectional:
