@@ -42,7 +42,7 @@ extern "C" {
 typedef enum {
     LASP_OK = 0,
     LASP_ERR_NULL = 1,      /* a required pointer is NULL */
-    LASP_ERR_SHAPE = 2,     /* B,H,N <= 0; D or Dv not 64/128; chunk not 64/128/256; bad segments or kv_heads; Norm with N % tile != 0 or Dv != D */
+    LASP_ERR_SHAPE = 2,     /* B,H,N <= 0; D or Dv not 64/128; chunk not 64/128/256; bad segments or kv_heads; Norm with Dv != D */
     LASP_ERR_DTYPE = 3,     /* dtype is neither LASP_F32 nor LASP_BF16 */
     LASP_ERR_DECAY = 4,     /* lasp_check_decay: a value outside (0, 1] or not finite */
     LASP_ERR_WORKSPACE = 5, /* scratch missing or smaller than lasp_scratch_bytes() */
@@ -59,8 +59,7 @@ typedef enum { LASP_F32 = 0, LASP_BF16 = 1 } lasp_dtype;
  *            positive number. When N is not a multiple of lasp_tile_tokens() the
  *            last tile is short; the per-token-decay kernels handle that, so
  *            lasp_fwd / lasp_bwd then run those with log g = log(lambda) filled in
- *            by the library (about 10 % slower, more scratch); the fused Norm
- *            entry points reject such N.
+ *            by the library (about 10 % slower, more scratch).
  *   chunk    the chunk length C of Alg. 2 / Alg. 3. The kernels walk the
  *            sub-sequence in tiles of lasp_tile_tokens() tokens; the tile
  *            divides the chunk, which is exact because the state update of
@@ -231,7 +230,7 @@ int lasp_bwd_norm(const lasp_shape *shape, const void *q, const void *k, const v
  * Per-token decay and normalised output together: arguments as in
  * lasp_gated_fwd / lasp_gated_bwd plus eps, rstd and (backward) the normalised
  * output, with the meaning they have in lasp_fwd_norm / lasp_bwd_norm; dout is
- * the gradient w.r.t. the normalised output; N must be a multiple of the tile.
+ * the gradient w.r.t. the normalised output.
  */
 int lasp_gated_fwd_norm(const lasp_shape *shape, const void *q, const void *k, const void *v,
                         const float *log_g, const float *kv_in, float eps, void *out, float *rstd,

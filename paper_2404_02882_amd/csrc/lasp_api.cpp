@@ -45,9 +45,8 @@ int make_plan(const lasp_shape *s, Pass pass, lasp::Plan *p, bool token = false,
     p->tile = lasp::tile_tokens(s->dtype, s->chunk, p->D);
     p->ntiles = (s->N + p->tile - 1) / p->tile;
     // A short last tile is handled by the per-token-decay kernels only: with one lambda per head the
-    // library synthesises log g = log(lambda) and runs those; the fused Norm has no such path.
+    // library synthesises log g = log(lambda) and runs those (with or without the fused Norm).
     const bool ragged = s->N % p->tile != 0;
-    if (ragged && norm) return LASP_ERR_SHAPE;
     p->synth = ragged && !token;
     if (p->synth) token = true;
     int want = s->segments;
@@ -288,7 +287,7 @@ const char *lasp_status_str(int status) {
     switch (status) {
         case LASP_OK: return "ok";
         case LASP_ERR_NULL: return "a required pointer is NULL";
-        case LASP_ERR_SHAPE: return "unsupported shape (need B,H,N > 0, D and Dv in {64,128} (Dv 0 = D), chunk in {64,128,256}, 0 <= segments <= ceil(N/tile); with the fused Norm N % tile == 0 and Dv = D)";
+        case LASP_ERR_SHAPE: return "unsupported shape (need B,H,N > 0, D and Dv in {64,128} (Dv 0 = D), chunk in {64,128,256}, 0 <= segments <= ceil(N/tile); with the fused Norm Dv = D)";
         case LASP_ERR_DTYPE: return "unsupported dtype (LASP_F32 or LASP_BF16)";
         case LASP_ERR_DECAY: return "decay must be finite and in (0, 1] (log decay: finite and <= 0)";
         case LASP_ERR_WORKSPACE: return "scratch buffer missing or too small (see lasp_scratch_bytes)";

@@ -348,11 +348,15 @@ struct NormTile {
     typedef TileMover<T, ROWS, COLS, NT> TM;
     TM y;
     float rstd[TM::NV];
-    DEVI void load(const T *y_tile, const float *rstd_tile) {  // both uniform: first element / first row of the tile
-        y.load(y_tile);
-        const unsigned lo = (threadIdx.x / TM::VPR) * sizeof(float);
+    // both pointers uniform: first element / first row of the tile; rows >= nrows (a short last tile) are
+    // not touched in memory and count as y = 0, rstd = 0
+    DEVI void load(const T *y_tile, const float *rstd_tile, int nrows = ROWS) {
+        y.load(y_tile, nrows);
+        const int row0 = threadIdx.x / TM::VPR;
+        const unsigned lo = row0 * sizeof(float);
 #pragma unroll
-        for (int i = 0; i < TM::NV; ++i) rstd[i] = gload<float>(rstd_tile + i * (NT / TM::VPR), lo);
+        for (int i = 0; i < TM::NV; ++i)
+            rstd[i] = row0 + i * (NT / TM::VPR) < nrows ? gload<float>(rstd_tile + i * (NT / TM::VPR), lo) : 0.0f;
     }
     template <typename Mover>   // a TileMover of the same geometry (streaming or not)
     DEVI void apply(Mover &dy) const {

@@ -104,7 +104,7 @@ __global__ __launch_bounds__(D * 2, 2) void k_local(const T *__restrict__ X, con
     my.template load_w<WY>(Y + yoff(tile_of(0)), nvalid(tile_of(0)));
     NormTile<T, CT, D, NT> mn;
     const float *rstd_c = rstd + (size_t)chain * ntok;
-    if constexpr (NORM) mn.load(yn + base + (size_t)tile_of(0) * CT * D, rstd_c + (size_t)tile_of(0) * CT);
+    if constexpr (NORM) mn.load(yn + base + (size_t)tile_of(0) * CT * D, rstd_c + (size_t)tile_of(0) * CT, nvalid(tile_of(0)));
     PHASE(22);
     f32x16 st[DB];
 #pragma unroll
@@ -130,7 +130,7 @@ __global__ __launch_bounds__(D * 2, 2) void k_local(const T *__restrict__ X, con
                 const int tn = tile_of(n + 1);
                 mx.template load_w<WX>(X + xoff(tn), nvalid(tn));
                 my.template load_w<WY>(Y + yoff(tn), nvalid(tn));
-                if constexpr (NORM) mn.load(yn + base + (size_t)tn * CT * D, rstd_c + (size_t)tn * CT);
+                if constexpr (NORM) mn.load(yn + base + (size_t)tn * CT * D, rstd_c + (size_t)tn * CT, nvalid(tn));
                 lgreg = TokenDecay<T, CT>::fetch(lg + (size_t)tn * CT, nvalid(tn));
             }
             const float whole = dec.whole();
@@ -400,7 +400,8 @@ __global__ __launch_bounds__(D * 2, (CT <= 64 && sizeof(T) == 2) ? 2 : 1) void k
                 for (int wv = 0; wv < D / 32; ++wv) tot += red[wv * CT + 32 * ib + ln.r];
                 const float rs = rsqrtf(tot * (1.0f / D) + eps);
                 acc[ib] *= rs;
-                if (w == 0 && ln.h == 0) rstd_out[(size_t)chain * ntok + (size_t)t * CT + 32 * ib + ln.r] = rs;
+                if (w == 0 && ln.h == 0 && 32 * ib + ln.r < nvalid(t))
+                    rstd_out[(size_t)chain * ntok + (size_t)t * CT + 32 * ib + ln.r] = rs;
             }
         }
         T *o = O + voff(t);
@@ -506,7 +507,7 @@ __global__ __launch_bounds__(D * 2, (CT <= 64 && sizeof(T) == 2 && WK == D && WV
     mb.template load_w<WV>(dO + voff(t1 - 1), nvalid(t1 - 1));
     NormTile<T, CT, D, NT> mn;
     const float *rstd_c = rstd + (size_t)chain * ntok;
-    if constexpr (NORM) mn.load(yn + base + (size_t)(t1 - 1) * CT * D, rstd_c + (size_t)(t1 - 1) * CT);
+    if constexpr (NORM) mn.load(yn + base + (size_t)(t1 - 1) * CT * D, rstd_c + (size_t)(t1 - 1) * CT, nvalid(t1 - 1));
 
     for (int t = t1 - 1; t >= t0; --t) {
         const size_t off = base + (size_t)t * CT * D;
@@ -734,7 +735,8 @@ __global__ __launch_bounds__(D * 4) void k_bwd8(const T *__restrict__ Q, const T
     }
     NormTile<T, CT, D, NT> mn;  // NORM: dO is dY; turned into dO from the normalised output and rstd on its way to LDS
     const float *rstd_c = rstd + (size_t)chain * ntok;
-    if constexpr (NORM) mn.load(yn + base + (size_t)(t1 - 1) * CT * D, rstd_c + (size_t)(t1 - 1) * CT);
+    if constexpr (NORM)
+        mn.load(yn + base + (size_t)(t1 - 1) * CT * D, rstd_c + (size_t)(t1 - 1) * CT, TOKEN ? min(CT, ntok - (t1 - 1) * CT) : CT);
     const auto dec = DecaySel<TOKEN, T, CT>::make(pw, decay, chain, H);
     const float *lg = decay + (size_t)chain * ntok;  // per-token decay: `decay` is log g, [chain][token]
     typename TokenDecay<T, CT>::LogG lgreg = {};
@@ -1058,7 +1060,7 @@ __global__ __launch_bounds__(D * 4) void k_bwd8p(const T *__restrict__ Q, const 
     auto load_pair_rest = [&](int tE) {
         const size_t oE = base + (size_t)tE * TS, oO = oE + TS;
         const int nvO = TOKEN ? min(CT, ntok - (tE + 1) * CT) : CT;
-        if constexpr (NORM) mnX.load(yn + oO, rstd_c + (size_t)(tE + 1) * CT);
+        if constexpr (NORM) mnX.load(yn + oO, rstd_c + (size_t)(tE + 1) * CT, nvO);
         if constexpr (TOKEN) {
             lgO = TokenDecay<T, CT>::fetch(lg + (size_t)(tE + 1) * CT, nvO);
             lgE = TokenDecay<T, CT>::fetch(lg + (size_t)tE * CT);

@@ -120,3 +120,32 @@ def test_token_decay_with_norm(gpu, oracle, dtype, D, N, segments):
     dq, dk, dv, dlg, gin = oracle.gated_bwd_brute(inp.q, inp.k, inp.v, do, inp.log_g, inp.kv_in, inp.dkv_out)
     ref = dict(out=y, rstd=rstd, kv_out=kvo, dq=dq, dk=dk, dv=dv, dlog_g=dlg, dkv_in=gin)
     compare(harness, got, ref, TOL[dtype], f"gnorm/{dtype}")
+
+
+@pytest.mark.parametrize("dtype,D,N,T,segments,token", [
+    ("f32", 64, 200, 1, 0, False), ("f32", 128, 97, 1, 2, True),
+    ("bf16", 128, 1000, 1, 0, False),      # 16 tiles (pair kernel), the last one short
+    ("bf16", 64, 450, 1, 3, False),        # 8 tiles
+    ("bf16", 128, 421, 1, 0, False),       # 7 tiles (odd count)
+    ("bf16", 128, 700, 1, 4, True), ("bf16", 64, 1, 1, 0, False),
+])
+def test_norm_with_a_short_last_tile(gpu, oracle, dtype, D, N, T, segments, token):
+    """Sub-sequence lengths that are not a multiple of the tile, with the fused Norm (one lambda per head is
+    routed through the per-token-decay kernels; rows past the end are neither read nor written)."""
+    harness, lasp, si = gpu
+    cfg = si.Config("nragged", B=2, H=3, N=N, D=D, chunk=64, dtype=dtype, seed=950 + N, token_decay=token)
+    say(f"case norm ragged dtype={dtype} D={D} N={N} segments={segments} token={token}")
+    inp = si.make_inputs(cfg, with_states=True)
+    if token:
+        inp.log_g = np.log(np.random.default_rng(cfg.seed).uniform(0.8, 1.0, (2, 3, N))).astype(np.float32)
+        got = harness.run_gpu(inp, T=T, segments=segments, norm_eps=EPS)
+        o, kvo = oracle.gated_fwd_brute(inp.q, inp.k, inp.v, inp.log_g, inp.kv_in)
+        y, rstd = oracle.norm_fwd(o, EPS)
+        do = oracle.norm_bwd(inp.dout, y, rstd)
+        dq, dk, dv, dlg, gin = oracle.gated_bwd_brute(inp.q, inp.k, inp.v, do, inp.log_g, inp.kv_in, inp.dkv_out)
+        ref = dict(out=y, rstd=rstd, kv_out=kvo, dq=dq, dk=dk, dv=dv, dlog_g=dlg, dkv_in=gin)
+    else:
+        inp.decay = np.array([0.9, 0.97, 1.0], dtype=np.float32)
+        got = harness.run_gpu(inp, T=T, segments=segments, norm_eps=EPS)
+        ref = oracle_all(oracle, inp, EPS)
+    compare(harness, got, ref, TOL[dtype], f"nragged/{dtype}")
