@@ -42,7 +42,7 @@ extern "C" {
 typedef enum {
     LASP_OK = 0,
     LASP_ERR_NULL = 1,      /* a required pointer is NULL */
-    LASP_ERR_SHAPE = 2,     /* B,H,N <= 0; D or Dv not 64/128; chunk not 64/128/256; bad segments or kv_heads; Norm with Dv != D */
+    LASP_ERR_SHAPE = 2,     /* B,H,N <= 0; D or Dv not 64/128; chunk not 64/128/256; bad segments or kv_heads */
     LASP_ERR_DTYPE = 3,     /* dtype is neither LASP_F32 nor LASP_BF16 */
     LASP_ERR_DECAY = 4,     /* lasp_check_decay: a value outside (0, 1] or not finite */
     LASP_ERR_WORKSPACE = 5, /* scratch missing or smaller than lasp_scratch_bytes() */
@@ -77,8 +77,9 @@ typedef enum { LASP_F32 = 0, LASP_BF16 = 1 } lasp_dtype;
  *            every state (kv_in, kv_out, dkv_out, dkv_in) is [B][H][D][Dv], rows
  *            indexed by the key feature. The kernels run at max(D, Dv) with the
  *            narrower of the two zero-padded on chip (memory traffic follows the
- *            real sizes, scratch and the state cache the padded ones). Not
- *            offered with the fused Norm or the bidirectional calls.
+ *            real sizes, scratch and the state cache the padded ones). The fused
+ *            Norm then runs over the Dv value features. Not offered for the
+ *            bidirectional calls.
  *   segments 0 = chosen by the library. Otherwise the number of independent
  *            segments each head's sub-sequence is cut into so that B*H*segments
  *            workgroups fill the chip (1 <= segments <= ceil(N / tile)).

@@ -39,7 +39,6 @@ int make_plan(const lasp_shape *s, Pass pass, lasp::Plan *p, bool token = false,
     p->dk = s->D;
     p->dv = s->Dv != 0 ? s->Dv : s->D;
     p->D = p->dk > p->dv ? p->dk : p->dv;   // the kernels' dimension; the narrower of the two is zero-padded on chip
-    if (norm && p->dk != p->dv) return LASP_ERR_SHAPE;
     p->dtype = s->dtype;
     p->kvdiv = s->kv_heads > 0 ? s->H / s->kv_heads : 1;
     p->tile = lasp::tile_tokens(s->dtype, s->chunk, p->D);
@@ -287,7 +286,7 @@ const char *lasp_status_str(int status) {
     switch (status) {
         case LASP_OK: return "ok";
         case LASP_ERR_NULL: return "a required pointer is NULL";
-        case LASP_ERR_SHAPE: return "unsupported shape (need B,H,N > 0, D and Dv in {64,128} (Dv 0 = D), chunk in {64,128,256}, 0 <= segments <= ceil(N/tile); with the fused Norm Dv = D)";
+        case LASP_ERR_SHAPE: return "unsupported shape (need B,H,N > 0, D and Dv in {64,128} (Dv 0 = D), chunk in {64,128,256}, 0 <= segments <= ceil(N/tile))";
         case LASP_ERR_DTYPE: return "unsupported dtype (LASP_F32 or LASP_BF16)";
         case LASP_ERR_DECAY: return "decay must be finite and in (0, 1] (log decay: finite and <= 0)";
         case LASP_ERR_WORKSPACE: return "scratch buffer missing or too small (see lasp_scratch_bytes)";

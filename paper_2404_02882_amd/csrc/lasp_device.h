@@ -343,7 +343,9 @@ struct TileMover {
 // is a butterfly over those lanes. NormTile holds what the prologue needs beside
 // dY: the same pieces of Y and one rstd per piece row.
 // ---------------------------------------------------------------------------
-template <typename T, int ROWS, int COLS, int NT>
+// W <= COLS: the rows in memory hold only W features (a value dimension narrower than the kernels');
+// the mean runs over those W, the padding being zero.
+template <typename T, int ROWS, int COLS, int NT, int W = COLS>
 struct NormTile {
     typedef TileMover<T, ROWS, COLS, NT> TM;
     TM y;
@@ -351,7 +353,7 @@ struct NormTile {
     // both pointers uniform: first element / first row of the tile; rows >= nrows (a short last tile) are
     // not touched in memory and count as y = 0, rstd = 0
     DEVI void load(const T *y_tile, const float *rstd_tile, int nrows = ROWS) {
-        y.load(y_tile, nrows);
+        y.template load_w<W>(y_tile, nrows);
         const int row0 = threadIdx.x / TM::VPR;
         const unsigned lo = row0 * sizeof(float);
 #pragma unroll
@@ -388,7 +390,7 @@ struct NormTile {
             for (int e = 0; e < E; ++e) p += a[e] * b[e];
 #pragma unroll
             for (int m = 1; m < TM::VPR; m <<= 1) p += __shfl_xor(p, m, 64);
-            const float mean = p * (1.0f / COLS), rs = rstd[i];
+            const float mean = p * (1.0f / W), rs = rstd[i];
 #pragma unroll
             for (int e = 0; e < E; ++e) a[e] = rs * (a[e] - b[e] * mean);
             if constexpr (sizeof(T) == 2) {

@@ -72,7 +72,6 @@ __global__ __launch_bounds__(D * 2, 2) void k_local(const T *__restrict__ X, con
                                                   int tiles_per_seg, int ntok, int kvdiv, const T *__restrict__ yn = nullptr,
                                                   const float *__restrict__ rstd = nullptr) {
     static_assert(!NORM || BWD, "the Norm prologue belongs to the backward pass");
-    static_assert(!NORM || (WX == D && WY == D), "the Norm prologue takes full-width rows");
     using E = Elem<T>;
     constexpr int NT = D * 2, LDD = tile_ld<T, D>(), DB = D / 32, NKS = CT / E::KSTEP;
     extern __shared__ __attribute__((aligned(16))) char smem[];
@@ -87,7 +86,6 @@ __global__ __launch_bounds__(D * 2, 2) void k_local(const T *__restrict__ X, con
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);  // wave index, scalar
     Lane ln = fresh_lane();
     PHASE_DECL();
-    const size_t base = (size_t)chain * ntok * D;   // (full-width tensors: the Norm prologue)
     if (!BWD) {  // forward: X, Y are K, V
         X += kv_shift(chain, H, kvdiv, ntok, WX);
         Y += kv_shift(chain, H, kvdiv, ntok, WY);
@@ -102,9 +100,9 @@ __global__ __launch_bounds__(D * 2, 2) void k_local(const T *__restrict__ X, con
     TileMover<T, CT, D, NT, true> mx, my;   // streaming (non-temporal) loads
     mx.template load_w<WX>(X + xoff(tile_of(0)), nvalid(tile_of(0)));
     my.template load_w<WY>(Y + yoff(tile_of(0)), nvalid(tile_of(0)));
-    NormTile<T, CT, D, NT> mn;
+    NormTile<T, CT, D, NT, WY> mn;   // the normalised output has the rows of Y (= dY)
     const float *rstd_c = rstd + (size_t)chain * ntok;
-    if constexpr (NORM) mn.load(yn + base + (size_t)tile_of(0) * CT * D, rstd_c + (size_t)tile_of(0) * CT, nvalid(tile_of(0)));
+    if constexpr (NORM) mn.load(yn + yoff(tile_of(0)), rstd_c + (size_t)tile_of(0) * CT, nvalid(tile_of(0)));
     PHASE(22);
     f32x16 st[DB];
 #pragma unroll
@@ -130,7 +128,7 @@ __global__ __launch_bounds__(D * 2, 2) void k_local(const T *__restrict__ X, con
                 const int tn = tile_of(n + 1);
                 mx.template load_w<WX>(X + xoff(tn), nvalid(tn));
                 my.template load_w<WY>(Y + yoff(tn), nvalid(tn));
-                if constexpr (NORM) mn.load(yn + base + (size_t)tn * CT * D, rstd_c + (size_t)tn * CT, nvalid(tn));
+                if constexpr (NORM) mn.load(yn + yoff(tn), rstd_c + (size_t)tn * CT, nvalid(tn));
                 lgreg = TokenDecay<T, CT>::fetch(lg + (size_t)tn * CT, nvalid(tn));
             }
             const float whole = dec.whole();
@@ -179,7 +177,7 @@ __global__ __launch_bounds__(D * 2, 2) void k_local(const T *__restrict__ X, con
         if (n + 1 < ntl) {
             mx.template load_w<WX>(X + xoff(tile_of(n + 1)), CT);
             my.template load_w<WY>(Y + yoff(tile_of(n + 1)), CT);
-            if constexpr (NORM) mn.load(yn + base + (size_t)tile_of(n + 1) * CT * D, rstd_c + (size_t)tile_of(n + 1) * CT);
+            if constexpr (NORM) mn.load(yn + yoff(tile_of(n + 1)), rstd_c + (size_t)tile_of(n + 1) * CT);
         }
         PHASE(27);
         // Token weight relative to the whole segment, so the accumulators are never rescaled:
@@ -316,7 +314,6 @@ __global__ __launch_bounds__(D * 2, (CT <= 64 && sizeof(T) == 2) ? 2 : 1) void k
     const int t1 = min(t0 + tiles_per_seg, ntiles);
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);  // wave index, scalar
     Lane ln = fresh_lane();
-    static_assert(!NORM || (WK == D && WV == D), "the Norm epilogue takes full-width rows");
     // requests first (tile, then start state), table arithmetic while they fly
     K += kv_shift(chain, H, kvdiv, ntok, WK);   // K, V of this chain's K/V head
     V += kv_shift(chain, H, kvdiv, ntok, WV);
@@ -398,7 +395,7 @@ __global__ __launch_bounds__(D * 2, (CT <= 64 && sizeof(T) == 2) ? 2 : 1) void k
                 float tot = 0.0f;
 #pragma unroll
                 for (int wv = 0; wv < D / 32; ++wv) tot += red[wv * CT + 32 * ib + ln.r];
-                const float rs = rsqrtf(tot * (1.0f / D) + eps);
+                const float rs = rsqrtf(tot * (1.0f / WV) + eps);   // mean over the real value features (padding is zero)
                 acc[ib] *= rs;
                 if (w == 0 && ln.h == 0 && 32 * ib + ln.r < nvalid(t))
                     rstd_out[(size_t)chain * ntok + (size_t)t * CT + 32 * ib + ln.r] = rs;
@@ -493,8 +490,6 @@ __global__ __launch_bounds__(D * 2, (CT <= 64 && sizeof(T) == 2 && WK == D && WV
         }
     };
 
-    static_assert(!NORM || (WK == D && WV == D), "the Norm prologue takes full-width rows");
-    const size_t base = (size_t)chain * ntok * D;   // (full-width tensors: the Norm prologue)
     K += kv_shift(chain, H, kvdiv, ntok, WK);   // K, V of this chain's K/V head
     V += kv_shift(chain, H, kvdiv, ntok, WV);
     auto koff = [&](int t) { return tile_off(chain, ntok, t, CT, WK); };
@@ -505,12 +500,11 @@ __global__ __launch_bounds__(D * 2, (CT <= 64 && sizeof(T) == 2 && WK == D && WV
     TileMover<T, CT, D, NT> ma, mb;
     ma.template load_w<WV>(V + voff(t1 - 1), nvalid(t1 - 1));
     mb.template load_w<WV>(dO + voff(t1 - 1), nvalid(t1 - 1));
-    NormTile<T, CT, D, NT> mn;
+    NormTile<T, CT, D, NT, WV> mn;
     const float *rstd_c = rstd + (size_t)chain * ntok;
-    if constexpr (NORM) mn.load(yn + base + (size_t)(t1 - 1) * CT * D, rstd_c + (size_t)(t1 - 1) * CT, nvalid(t1 - 1));
+    if constexpr (NORM) mn.load(yn + voff(t1 - 1), rstd_c + (size_t)(t1 - 1) * CT, nvalid(t1 - 1));
 
     for (int t = t1 - 1; t >= t0; --t) {
-        const size_t off = base + (size_t)t * CT * D;
         // ---- exchange: dKV^T fragments for dK_inter (B[k = c][n = a in w]) ----
         __syncthreads();
         ln = fresh_lane();
@@ -580,7 +574,7 @@ __global__ __launch_bounds__(D * 2, (CT <= 64 && sizeof(T) == 2 && WK == D && WV
         if (t > t0) {
             ma.template load_w<WV>(V + voff(t - 1), CT);
             mb.template load_w<WV>(dO + voff(t - 1), CT);
-            if constexpr (NORM) mn.load(yn + off - (size_t)CT * D, rstd_c + (size_t)(t - 1) * CT);
+            if constexpr (NORM) mn.load(yn + voff(t - 1), rstd_c + (size_t)(t - 1) * CT);
         }
         masked_scores<T, CT, D, LDD, LDP>(ln, sS, bufA, bufB, dec, w);  // S^T = K Q^T
         __syncthreads();
@@ -976,7 +970,6 @@ __global__ __launch_bounds__(D * 4) void k_bwd8p(const T *__restrict__ Q, const 
     using F = typename E::frag;
     using SM = Bwd8pSmem<T, CT, D>;
     static_assert(CT == 64, "two 32-token blocks per tile");
-    static_assert(!NORM || (WK == D && WV == D), "the Norm prologue takes full-width rows");
     constexpr int NT = D * 4, NW = D / 32, LDD = SM::LDD, LDP = SM::LDP, DB = D / 32, NB = CT / 32, NKS = CT / E::KSTEP,
                   NKD = D / E::KSTEP, SPB = 32 / E::KSTEP;
     extern __shared__ __attribute__((aligned(16))) char smem[];
@@ -1001,12 +994,10 @@ __global__ __launch_bounds__(D * 4) void k_bwd8p(const T *__restrict__ Q, const 
     Lane ln = fresh_lane();
     PHASE_DECL();
 
-    const size_t base = (size_t)chain * ntok * D;   // (full-width tensors: the Norm prologue)
     K += kv_shift(chain, H, kvdiv, ntok, WK);   // K, V of this chain's K/V head
     V += kv_shift(chain, H, kvdiv, ntok, WV);
     auto koff = [&](int t) { return tile_off(chain, ntok, t, CT, WK); };
     auto voff = [&](int t) { return tile_off(chain, ntok, t, CT, WV); };
-    const size_t TS = (size_t)CT * D;  // elements per full-width tile
     TileMover<T, CT, D, NT> mvO, moX, mkO, mqX, mvE, mkE;   // moX / mqX carry dO, Q of the O tile, then of the E tile
     TileMover<T, D, D, NT> mc;                               // cached state at the start of the E tile
     const T *ctile = cache + (size_t)chain * (ntiles / 2) * D * D;
@@ -1042,7 +1033,7 @@ __global__ __launch_bounds__(D * 4) void k_bwd8p(const T *__restrict__ Q, const 
             if (tile * CT + (int)threadIdx.x < ntok) rtok[(size_t)chain * ntok + (size_t)tile * CT + threadIdx.x] = r;
         }
     };
-    NormTile<T, CT, D, NT> mnX;  // NORM: partner of moX (dO is dY; see NormTile)
+    NormTile<T, CT, D, NT, WV> mnX;  // NORM: partner of moX (dO is dY; see NormTile)
     const float *rstd_c = rstd + (size_t)chain * ntok;
     // The requests for a pair come in two parts. K and V of both tiles go into registers that are idle
     // from the top of an iteration on, so inside the loop they are issued a whole tile early (during
@@ -1058,9 +1049,8 @@ __global__ __launch_bounds__(D * 4) void k_bwd8p(const T *__restrict__ Q, const 
         mc.load(ctile + (size_t)(tE / 2) * D * D);
     };
     auto load_pair_rest = [&](int tE) {
-        const size_t oE = base + (size_t)tE * TS, oO = oE + TS;
         const int nvO = TOKEN ? min(CT, ntok - (tE + 1) * CT) : CT;
-        if constexpr (NORM) mnX.load(yn + oO, rstd_c + (size_t)(tE + 1) * CT, nvO);
+        if constexpr (NORM) mnX.load(yn + voff(tE + 1), rstd_c + (size_t)(tE + 1) * CT, nvO);
         if constexpr (TOKEN) {
             lgO = TokenDecay<T, CT>::fetch(lg + (size_t)(tE + 1) * CT, nvO);
             lgE = TokenDecay<T, CT>::fetch(lg + (size_t)tE * CT);
@@ -1260,7 +1250,6 @@ __global__ __launch_bounds__(D * 4) void k_bwd8p(const T *__restrict__ Q, const 
     };
 
     for (int tE = t1 - 2; tE >= t0; tE -= 2) {
-        const size_t offE = base + (size_t)tE * TS;   // (the Norm prologue's full-width tensor)
         __syncthreads();  // previous pair fully consumed
         ln = fresh_lane();
         PHASE(0);
@@ -1283,7 +1272,7 @@ __global__ __launch_bounds__(D * 4) void k_bwd8p(const T *__restrict__ Q, const 
         PHASE(1);
         moX.template load_w<WV>(dO + voff(tE), CT);
         mqX.template load_w<WK>(Q + koff(tE), CT);
-        if constexpr (NORM) mnX.load(yn + offE, rstd_c + (size_t)tE * CT);
+        if constexpr (NORM) mnX.load(yn + voff(tE), rstd_c + (size_t)tE * CT);
         PHASE(2);
         // ---- O tile ----
         scores(decO, sVO, sKO);
@@ -1453,9 +1442,13 @@ static hipError_t run_local(const Plan &p, const T *x, const T *y, const float *
         auto launch = [&](auto kl) -> hipError_t {
             if (hipError_t e2 = allow_lds(kl, lds); e2 != hipSuccess) return e2;
             kl<<<dim3(p.nseg - 1, chains), dim3(D * 2), lds, s>>>(x, y, decay, scratch, seglog, p.H, p.ntiles, p.nseg,
-                                                                p.tiles_per_seg, p.N, p.kvdiv, nullptr, nullptr);
+                                                                p.tiles_per_seg, p.N, p.kvdiv, yn, rstd);
             return hipSuccess;
         };
+        if constexpr (BWD) {
+            if (p.norm)
+                return p.token ? launch(k_local<T, CT, D, true, true, true, WK, WV>) : launch(k_local<T, CT, D, true, false, true, WK, WV>);
+        }
         return p.token ? launch(k_local<T, CT, D, BWD, true, false, WK, WV>) : launch(k_local<T, CT, D, BWD, false, false, WK, WV>);
     } else {
     if constexpr (BWD) {
@@ -1521,8 +1514,9 @@ static hipError_t run_fwd(const Plan &p, const FwdArgs &a, hipStream_t s, const 
                                                              a.rstd_out, a.eps);
         return hipSuccess;
     };
-    if constexpr (WK != D || WV != D) {   // (the host layer rejects the fused Norm for such shapes)
-        e = p.token ? launch(k_fwd<T, CT, D, true, false, WK, WV>) : launch(k_fwd<T, CT, D, false, false, WK, WV>);
+    if constexpr (WK != D || WV != D) {
+        e = p.token ? (p.norm ? launch(k_fwd<T, CT, D, true, true, WK, WV>) : launch(k_fwd<T, CT, D, true, false, WK, WV>))
+                    : (p.norm ? launch(k_fwd<T, CT, D, false, true, WK, WV>) : launch(k_fwd<T, CT, D, false, false, WK, WV>));
     } else {
         e = p.token ? (p.norm ? launch(k_fwd<T, CT, D, true, true>) : launch(k_fwd<T, CT, D, true>))
                     : (p.norm ? launch(k_fwd<T, CT, D, false, true>) : launch(k_fwd<T, CT, D, false>));
@@ -1562,10 +1556,11 @@ static hipError_t run_bwd(const Plan &p, const BwdArgs &a, hipStream_t s, const 
                                                                         (const T *)a.dout, a.decay, (const T *)a.cache, (T *)a.dq,
                                                                         (T *)a.dk, (T *)a.dv, a.dkv_in, (const float *)a.scratch,
                                                                         a.rtok, p.H, p.ntiles, p.nseg, p.tiles_per_seg, p.N, p.kvdiv,
-                                                                        nullptr, nullptr);
+                                                                        (const T *)a.yn, a.rstd);
                 return hipSuccess;
             };
-            if (e = p.token ? launch(k_bwd8p<T, CT, D, true, false, WK, WV>) : launch(k_bwd8p<T, CT, D, false, false, WK, WV>);
+            if (e = p.token ? (p.norm ? launch(k_bwd8p<T, CT, D, true, true, WK, WV>) : launch(k_bwd8p<T, CT, D, true, false, WK, WV>))
+                            : (p.norm ? launch(k_bwd8p<T, CT, D, false, true, WK, WV>) : launch(k_bwd8p<T, CT, D, false, false, WK, WV>));
                 e != hipSuccess)
                 return e;
         }
@@ -1578,10 +1573,11 @@ static hipError_t run_bwd(const Plan &p, const BwdArgs &a, hipStream_t s, const 
                                                                  (const T *)a.dout, a.decay, (const T *)a.cache, (T *)a.dq,
                                                                  (T *)a.dk, (T *)a.dv, a.dkv_in, (const float *)a.scratch,
                                                                  a.rtok, p.H, p.ntiles, p.nseg, p.tiles_per_seg, p.N, p.kvdiv,
-                                                                 nullptr, nullptr);
+                                                                 (const T *)a.yn, a.rstd);
             return hipSuccess;
         };
-        if (e = p.token ? launch(k_bwd<T, CT, D, true, false, WK, WV>) : launch(k_bwd<T, CT, D, false, false, WK, WV>);
+        if (e = p.token ? (p.norm ? launch(k_bwd<T, CT, D, true, true, WK, WV>) : launch(k_bwd<T, CT, D, true, false, WK, WV>))
+                        : (p.norm ? launch(k_bwd<T, CT, D, false, true, WK, WV>) : launch(k_bwd<T, CT, D, false, false, WK, WV>));
             e != hipSuccess)
             return e;
       }

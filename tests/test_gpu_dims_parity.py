@@ -131,3 +131,33 @@ def test_m3_full_size(gpu, oracle):
         emax, efro = harness.rel_errors(got[nm][b, h, s], r)
         say(f"  m3 rows {nm:4s} max-rel {emax:.3e} fro-rel {efro:.3e}")
         assert emax <= TOL["bf16"] and efro <= TOL["bf16"], nm
+
+
+@pytest.mark.parametrize("dtype,D,Dv,N,T,segments,token", [
+    ("f32", 64, 128, 192, 1, 0, False), ("f32", 128, 64, 100, 1, 2, True),
+    ("bf16", 64, 128, 512, 2, 0, False), ("bf16", 128, 64, 512, 1, 0, False),
+    ("bf16", 128, 64, 448, 1, 3, False),          # odd tile count: the four-wave walk
+    ("bf16", 64, 128, 640, 1, 0, True), ("bf16", 128, 64, 333, 1, 0, False),
+])
+def test_fused_norm_with_unequal_dims(gpu, oracle, dtype, D, Dv, N, T, segments, token):
+    """The fused Norm runs over the d_v value features: y = Norm(o), gradients through it."""
+    harness, lasp, si = gpu
+    eps = 1e-5
+    cfg = si.Config("dimsn", B=2, H=3, N=N, D=D, chunk=64, dtype=dtype, seed=760 + D + N, Dv=Dv, token_decay=token)
+    say(f"case dims+norm dtype={dtype} D={D} Dv={Dv} N={N} T={T} segments={segments} token={token}")
+    inp = si.make_inputs(cfg, with_states=True)
+    if token:
+        inp.log_g = np.log(np.random.default_rng(cfg.seed).uniform(0.8, 1.0, (2, 3, N))).astype(np.float32)
+    else:
+        inp.decay = np.array([0.9, 0.98, 1.0], dtype=np.float32)
+    got = harness.run_gpu(inp, T=T, segments=segments, norm_eps=eps)
+    lg = inp.log_g if token else None
+    dec = None if token else inp.decay
+    o, kvo = oracle.dims_fwd_brute(inp.q, inp.k, inp.v, dec, inp.kv_in, log_g=lg)
+    y, rstd = oracle.norm_fwd(o, eps)
+    do = oracle.norm_bwd(inp.dout, y, rstd)
+    res = oracle.dims_bwd_brute(inp.q, inp.k, inp.v, do, dec, inp.kv_in, inp.dkv_out, log_g=lg)
+    ref = dict(out=y, rstd=rstd, kv_out=kvo, dq=res[0], dk=res[1], dv=res[2], dkv_in=res[-1])
+    if token:
+        ref["dlog_g"] = res[3]
+    compare(harness, got, ref, TOL[dtype], "dimsn")
