@@ -537,7 +537,9 @@ struct TokenDecay {
     DEVI float upto(int i) const { return wu[i]; }
     DEVI float after(int j) const { return wa[j]; }
     DEVI float whole() const { return wu[CT - 1]; }
-    DEVI float masked(float x, int i, int j) const { return i >= j ? x * exp2f(cum[i] - cum[j]) : 0.0f; }
+    // (the bare hardware exp2: a weight below 2^-126 becomes 0 instead of a denormal, and the library
+    // routine's range handling would cost four more instructions for every score element)
+    DEVI float masked(float x, int i, int j) const { return i >= j ? x * __builtin_amdgcn_exp2f(cum[i] - cum[j]) : 0.0f; }
     DEVI typename Elem<T>::frag weigh_after(const Lane &ln, typename Elem<T>::frag f, int ks) const {
         return Elem<T>::scale_tab(ln, f, wa, ks * Elem<T>::KSTEP);
     }
