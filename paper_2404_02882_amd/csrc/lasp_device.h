@@ -17,6 +17,7 @@ typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(4))) short s16x4;
 typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
+typedef __attribute__((ext_vector_type(2))) unsigned u32x2;
 
 #define DEVI __device__ __forceinline__
 
@@ -661,11 +662,34 @@ DEVI void store_out_tile_t(const Lane &ln, T *g, const f32x16 &acc, int row0, in
     if constexpr (W < D) {
         if (32 * w >= W) return;
     }
-    const unsigned lo = (ln.r * W + 32 * w + 4 * ln.h) * sizeof(T);
-    if (row0 + ln.r >= nrows) return;  // token past the end of the sub-sequence
+    if constexpr (sizeof(T) == 2) {
+        // Two-byte elements: the lane's four features are 8 bytes, and a store instruction of 8-byte pieces
+        // leaves 16 bytes in each of 32 rows. The two half-waves hold neighbouring features of the same
+        // token, so they trade register groups (one v_permlane32_swap per dword: lanes 32..63 of the first
+        // operand against lanes 0..31 of the second) and every lane stores 16 bytes: half the requests.
+        u32x2 d[4];
 #pragma unroll
-    for (int q = 0; q < 4; ++q)
-        Elem<T>::gst4(g + row0 * W + 8 * q, lo, acc[4 * q], acc[4 * q + 1], acc[4 * q + 2], acc[4 * q + 3]);
+        for (int q = 0; q < 4; ++q) {
+            union { bf16x4 v; u32x2 u; } pk;
+            pk.v = __builtin_convertvector(f32x4{acc[4 * q], acc[4 * q + 1], acc[4 * q + 2], acc[4 * q + 3]}, bf16x4);
+            d[q] = pk.u;
+        }
+        const unsigned lo = (ln.r * W + 32 * w + 8 * ln.h) * sizeof(T);
+        const bool live = row0 + ln.r < nrows;  // (a token and its partner lane share the row: both live or both not)
+#pragma unroll
+        for (int p = 0; p < 2; ++p) {
+            // half-wave 0 ends up with features 16p .. 16p+7 of its token, half-wave 1 with 16p+8 .. 16p+15
+            const u32x2 s0 = __builtin_amdgcn_permlane32_swap(d[2 * p][0], d[2 * p + 1][0], false, false);
+            const u32x2 s1 = __builtin_amdgcn_permlane32_swap(d[2 * p][1], d[2 * p + 1][1], false, false);
+            if (live) gstore<u32x4>(g + row0 * W + 16 * p, lo, u32x4{s0[0], s1[0], s0[1], s1[1]});
+        }
+    } else {
+        const unsigned lo = (ln.r * W + 32 * w + 4 * ln.h) * sizeof(T);
+        if (row0 + ln.r >= nrows) return;  // token past the end of the sub-sequence
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+            Elem<T>::gst4(g + row0 * W + 8 * q, lo, acc[4 * q], acc[4 * q + 1], acc[4 * q + 2], acc[4 * q + 3]);
+    }
 }
 
 // Store a wave's column block of the state into the cache tile g ([a][c], row
