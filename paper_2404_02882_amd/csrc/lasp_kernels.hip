@@ -20,8 +20,10 @@
 //                k_bwd for float.
 // Every kernel is instantiated for a decay model (lasp_device.h): one lambda
 // per head, or a decay per token (general recurrent form of App. A.4), which
-// adds k_dlg for the gradient of the log decay; and optionally with the output
-// normalisation fused (forward epilogue, backward prologue).
+// adds k_dlg for the gradient of the log decay; optionally with the output
+// normalisation fused (forward epilogue, backward prologue); and, where the key
+// and value dimensions differ, for the row widths of the key-side and value-side
+// tensors (the narrower rows are zero-padded on their way to LDS).
 // This is the paper's "intra parts in parallel, inter parts in sequence"
 // (Alg. 2) folded onto one GPU; there are no atomics, so results are
 // bit-reproducible.
