@@ -4,6 +4,8 @@
 
 #include <cmath>
 #include <cstdint>
+#include <mutex>
+#include <utility>
 #include <vector>
 
 #include "lasp_internal.h"
@@ -278,9 +280,27 @@ size_t bidir_scratch(const lasp::BidirPlan &p) { return (size_t)p.B * p.H * p.ns
 
 }  // namespace
 
+namespace lasp {
+
+hipError_t allow_dynamic_lds(const void *kernel, size_t bytes) {
+    if (bytes <= 65536) return hipSuccess;
+    int dev = 0;
+    if (hipError_t e = hipGetDevice(&dev); e != hipSuccess) return e;
+    static std::mutex mu;
+    static std::vector<std::pair<const void *, int>> raised;   // (kernel, device) pairs already set
+    std::lock_guard<std::mutex> hold(mu);
+    for (const auto &kd : raised)
+        if (kd.first == kernel && kd.second == dev) return hipSuccess;
+    const hipError_t e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+    if (e == hipSuccess) raised.emplace_back(kernel, dev);
+    return e;
+}
+
+}  // namespace lasp
+
 extern "C" {
 
-int lasp_version(void) { return 4; }
+int lasp_version(void) { return 5; }
 
 const char *lasp_status_str(int status) {
     switch (status) {

@@ -211,19 +211,6 @@ __global__ __launch_bounds__(D * 2, 2) void k_bidir_apply(BidirOps ops, int ntil
 // ---------------------------------------------------------------------------
 // Host-side launchers
 // ---------------------------------------------------------------------------
-// Raise the dynamic LDS limit of a kernel above the 64 KB default, once per kernel and device.
-template <typename F>
-static hipError_t allow_lds_bidir(F kernel, size_t bytes) {
-    static bool done[64] = {};
-    int dev = 0;
-    hipError_t e = hipGetDevice(&dev);
-    if (e != hipSuccess) return e;
-    if (bytes <= 65536 || (dev >= 0 && dev < 64 && done[dev])) return hipSuccess;
-    e = hipFuncSetAttribute((const void *)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
-    if (e == hipSuccess && dev >= 0 && dev < 64) done[dev] = true;
-    return e;
-}
-
 template <typename T, int CT, int D>
 static hipError_t run_bidir_state(const BidirPlan &p, const void *x, const void *y, float *state, int accumulate,
                                   float *part, hipStream_t s, const KernelEvents *ke) {
@@ -247,7 +234,7 @@ static hipError_t run_bidir_apply(const BidirPlan &p, const BidirOps &ops, int n
     const int chains = p.B * p.H;
     constexpr size_t lds = (size_t)CT * (tile_ld<T, D>() + D + 16 / sizeof(T)) * sizeof(T);
     static_assert(2 * lds <= 163840, "two workgroups per CU");
-    if (hipError_t e = allow_lds_bidir(k_bidir_apply<T, CT, D>, lds); e != hipSuccess) return e;
+    if (hipError_t e = allow_dynamic_lds((const void *)k_bidir_apply<T, CT, D>, lds); e != hipSuccess) return e;
     const int ntiles = (p.N + CT - 1) / CT;
     int nblk = (kBidirTargetWorkgroups + chains * nops - 1) / (chains * nops);
     if (nblk > ntiles) nblk = ntiles;

@@ -65,6 +65,11 @@ struct KernelEvents {
     hipEvent_t ev[4];
 };
 
+// Raises the dynamic LDS limit of `kernel` (its host-side address) to `bytes` when that exceeds the 64 KB
+// default. The attribute belongs to the kernel and the device's loaded module, so the runtime is asked
+// once per (kernel, device) pair; later calls are a table lookup. Thread-safe.
+hipError_t allow_dynamic_lds(const void *kernel, size_t bytes);
+
 // Tile length used for a (dtype, chunk, D) combination.
 int tile_tokens(int dtype, int chunk, int D);
 // Cache stride for a shape: 2 (one cached state per pair of tiles, the backward

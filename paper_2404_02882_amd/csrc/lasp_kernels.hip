@@ -1391,18 +1391,21 @@ struct Smem {
     static_assert(fwd <= 163840 && bwd <= 163840, "LDS budget of one gfx950 CU exceeded");
 };
 
-// Raise the dynamic LDS limit of a kernel above the 64 KB default, once per
-// kernel and device (the attribute lives in the loaded module of each device).
-template <typename F>
-static hipError_t allow_lds(F kernel, size_t bytes) {
-    static bool done[64] = {};
-    int dev = 0;
-    hipError_t e = hipGetDevice(&dev);
-    if (e != hipSuccess) return e;
-    if (dev >= 0 && dev < 64 && done[dev]) return hipSuccess;
-    e = hipFuncSetAttribute((const void *)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
-    if (e == hipSuccess && dev >= 0 && dev < 64) done[dev] = true;
-    return e;
+// One launch of a kernel with `lds` bytes of dynamic LDS. Kernels that need more than the 64 KB default
+// have their limit raised first (once per kernel and device, see allow_dynamic_lds).
+template <typename... KArgs, typename... Args>
+static hipError_t launch_kernel(void (*kernel)(KArgs...), dim3 grid, dim3 block, size_t lds, hipStream_t s, Args... args) {
+    if (hipError_t e = allow_dynamic_lds((const void *)kernel, lds); e != hipSuccess) return e;
+    kernel<<<grid, block, lds, s>>>(args...);
+    return hipSuccess;
+}
+
+// A kernel family instantiated for both decay models, with and without the fused Norm: picks the
+// member that serves the plan. Fam::fn<TOKEN, NORM> is the kernel.
+template <typename Fam>
+static auto by_model(const Plan &p) {
+    return p.token ? (p.norm ? Fam::template fn<true, true> : Fam::template fn<true, false>)
+                   : (p.norm ? Fam::template fn<false, true> : Fam::template fn<false, false>);
 }
 
 // Grouped K/V heads, backward: the walking kernel wrote dK, dV per QUERY head into `part`
@@ -1431,67 +1434,55 @@ static hipError_t run_group_sum(const Plan &p, const void *part, void *out, int 
     return hipGetLastError();
 }
 
+// Kernel families by decay model and Norm (see by_model).
+template <typename T, int CT, int D, bool BWD, bool WITH_NORM, int WX, int WY>
+struct LocalFam {   // the Norm prologue exists in the backward pass only
+    template <bool TK, bool NM>
+    static constexpr auto fn = k_local<T, CT, D, BWD, TK, NM && BWD && WITH_NORM, WX, WY>;
+};
+template <typename T, int CT, int D, int WK, int WV>
+struct FwdFam {
+    template <bool TK, bool NM>
+    static constexpr auto fn = k_fwd<T, CT, D, TK, NM, WK, WV>;
+};
+template <typename T, int CT, int D, int WK, int WV>
+struct BwdFam {     // four waves, one cached state per tile
+    template <bool TK, bool NM>
+    static constexpr auto fn = k_bwd<T, CT, D, TK, NM, WK, WV>;
+};
+template <typename T, int CT, int D>
+struct Bwd8Fam {    // eight waves, one cached state per tile
+    template <bool TK, bool NM>
+    static constexpr auto fn = k_bwd8<T, CT, D, TK, NM>;
+};
+template <typename T, int CT, int D, int WK, int WV>
+struct Bwd8pFam {   // eight waves, one cached state per pair of tiles
+    template <bool TK, bool NM>
+    static constexpr auto fn = k_bwd8p<T, CT, D, TK, NM, WK, WV>;
+};
+
 // The local pass only sums over its segment, so its tile need not be the walk's:
 // bfloat16 segments made of an even number of 64-token tiles are read 128 tokens
-// at a time (half the barriers, twice the bytes in flight per workgroup). With
-// per-token decay (`decay` = log g) the walk's tile is used.
+// at a time (half the barriers, twice the bytes in flight per workgroup), unless
+// the Norm prologue (a third tile in registers) or key and value dimensions that
+// differ ask for the walk's tile.
 template <typename T, int CT, int D, bool BWD, int WK = D, int WV = D>
 static hipError_t run_local(const Plan &p, const T *x, const T *y, const float *decay, float *scratch, float *seglog,
                             const T *yn, const float *rstd, hipStream_t s) {
-    const int chains = p.B * p.H;
-    if constexpr (WK != D || WV != D) {   // key and value dimensions differ: the walk's tile, narrow rows zero-padded
-        constexpr size_t lds = Smem<T, CT, D>::local;
-        auto launch = [&](auto kl) -> hipError_t {
-            if (hipError_t e2 = allow_lds(kl, lds); e2 != hipSuccess) return e2;
-            kl<<<dim3(p.nseg - 1, chains), dim3(D * 2), lds, s>>>(x, y, decay, scratch, seglog, p.H, p.ntiles, p.nseg,
-                                                                p.tiles_per_seg, p.N, p.kvdiv, yn, rstd);
-            return hipSuccess;
-        };
-        if constexpr (BWD) {
-            if (p.norm)
-                return p.token ? launch(k_local<T, CT, D, true, true, true, WK, WV>) : launch(k_local<T, CT, D, true, false, true, WK, WV>);
-        }
-        return p.token ? launch(k_local<T, CT, D, BWD, true, false, WK, WV>) : launch(k_local<T, CT, D, BWD, false, false, WK, WV>);
-    } else {
-    if constexpr (BWD) {
-        if (p.norm) {  // the Norm prologue needs a third tile in registers: the walk's tile length
-            constexpr size_t lds = Smem<T, CT, D>::local;
-            auto launch = [&](auto kl) -> hipError_t {
-                if (hipError_t e2 = allow_lds(kl, lds); e2 != hipSuccess) return e2;
-                kl<<<dim3(p.nseg - 1, chains), dim3(D * 2), lds, s>>>(x, y, decay, scratch, seglog, p.H, p.ntiles, p.nseg,
-                                                                    p.tiles_per_seg, p.N, p.kvdiv, yn, rstd);
-                return hipSuccess;
-            };
-            return p.token ? launch(k_local<T, CT, D, true, true, true>) : launch(k_local<T, CT, D, true, false, true>);
-        }
+    const dim3 grid(p.nseg - 1, p.B * p.H), block(D * 2);
+    if constexpr (sizeof(T) == 2 && CT == 64 && WK == D && WV == D) {
+        if (!(BWD && p.norm) && p.tiles_per_seg % 2 == 0 && p.ntiles % 2 == 0)
+            return launch_kernel(by_model<LocalFam<T, 128, D, BWD, false, D, D>>(p), grid, block, Smem<T, 128, D>::local, s, x, y,
+                                 decay, scratch, seglog, p.H, p.ntiles / 2, p.nseg, p.tiles_per_seg / 2, p.N, p.kvdiv,
+                                 (const T *)nullptr, (const float *)nullptr);
     }
-    if constexpr (sizeof(T) == 2 && CT == 64) {
-        if (p.tiles_per_seg % 2 == 0 && p.ntiles % 2 == 0) {
-            constexpr size_t lds = Smem<T, 128, D>::local;
-            auto launch = [&](auto kl) -> hipError_t {
-                if (hipError_t e2 = allow_lds(kl, lds); e2 != hipSuccess) return e2;
-                kl<<<dim3(p.nseg - 1, chains), dim3(D * 2), lds, s>>>(x, y, decay, scratch, seglog, p.H, p.ntiles / 2, p.nseg,
-                                                                    p.tiles_per_seg / 2, p.N, p.kvdiv, nullptr, nullptr);
-                return hipSuccess;
-            };
-            return p.token ? launch(k_local<T, 128, D, BWD, true>) : launch(k_local<T, 128, D, BWD, false>);
-        }
-    }
-    constexpr size_t lds = Smem<T, CT, D>::local;
-    auto launch = [&](auto kl) -> hipError_t {
-        if (hipError_t e2 = allow_lds(kl, lds); e2 != hipSuccess) return e2;
-        kl<<<dim3(p.nseg - 1, chains), dim3(D * 2), lds, s>>>(x, y, decay, scratch, seglog, p.H, p.ntiles, p.nseg,
-                                                            p.tiles_per_seg, p.N, p.kvdiv, nullptr, nullptr);
-        return hipSuccess;
-    };
-    return p.token ? launch(k_local<T, CT, D, BWD, true>) : launch(k_local<T, CT, D, BWD, false>);
-    }
+    return launch_kernel(by_model<LocalFam<T, CT, D, BWD, true, WK, WV>>(p), grid, block, Smem<T, CT, D>::local, s, x, y, decay,
+                         scratch, seglog, p.H, p.ntiles, p.nseg, p.tiles_per_seg, p.N, p.kvdiv, yn, rstd);
 }
 
 template <typename T, int CT, int D, int WK = D, int WV = D>
 static hipError_t run_fwd(const Plan &p, const FwdArgs &a, hipStream_t s, const KernelEvents *ke) {
     const int chains = p.B * p.H, DD = D * D;
-    constexpr size_t lds_fwd = Smem<T, CT, D>::fwd;
     const dim3 scan_grid((DD / 4 + 255) / 256, chains);
     hipError_t e;
     if (ke) (void)hipEventRecord(ke->ev[0], s);
@@ -1508,22 +1499,12 @@ static hipError_t run_fwd(const Plan &p, const FwdArgs &a, hipStream_t s, const 
         k_scan<false, false><<<scan_grid, dim3(256), 0, s>>>(a.scratch, a.kv_in, a.decay, nullptr, p.H, DD, p.nseg,
                                                             p.tiles_per_seg, p.ntiles, p.tile, D, p.dk, p.dv);
     if (ke) (void)hipEventRecord(ke->ev[2], s);
-    auto launch = [&](auto kf) -> hipError_t {
-        if (hipError_t e2 = allow_lds(kf, lds_fwd); e2 != hipSuccess) return e2;
-        kf<<<dim3(p.nseg, chains), dim3(D * 2), lds_fwd, s>>>((const T *)a.q, (const T *)a.k, (const T *)a.v, a.decay,
-                                                             (T *)a.out, a.kv_out, (T *)a.cache, (const float *)a.scratch,
-                                                             p.H, p.ntiles, p.nseg, p.tiles_per_seg, p.cache_stride, p.N, p.kvdiv,
-                                                             a.rstd_out, a.eps);
-        return hipSuccess;
-    };
-    if constexpr (WK != D || WV != D) {
-        e = p.token ? (p.norm ? launch(k_fwd<T, CT, D, true, true, WK, WV>) : launch(k_fwd<T, CT, D, true, false, WK, WV>))
-                    : (p.norm ? launch(k_fwd<T, CT, D, false, true, WK, WV>) : launch(k_fwd<T, CT, D, false, false, WK, WV>));
-    } else {
-        e = p.token ? (p.norm ? launch(k_fwd<T, CT, D, true, true>) : launch(k_fwd<T, CT, D, true>))
-                    : (p.norm ? launch(k_fwd<T, CT, D, false, true>) : launch(k_fwd<T, CT, D, false>));
-    }
-    if (e != hipSuccess) return e;
+    if (e = launch_kernel(by_model<FwdFam<T, CT, D, WK, WV>>(p), dim3(p.nseg, chains), dim3(D * 2), Smem<T, CT, D>::fwd, s,
+                          (const T *)a.q, (const T *)a.k, (const T *)a.v, a.decay, (T *)a.out, a.kv_out, (T *)a.cache,
+                          (const float *)a.scratch, p.H, p.ntiles, p.nseg, p.tiles_per_seg, p.cache_stride, p.N, p.kvdiv,
+                          a.rstd_out, a.eps);
+        e != hipSuccess)
+        return e;
     if (ke) (void)hipEventRecord(ke->ev[3], s);
     return hipGetLastError();
 }
@@ -1531,7 +1512,6 @@ static hipError_t run_fwd(const Plan &p, const FwdArgs &a, hipStream_t s, const 
 template <typename T, int CT, int D, int WK = D, int WV = D>
 static hipError_t run_bwd(const Plan &p, const BwdArgs &a, hipStream_t s, const KernelEvents *ke) {
     const int chains = p.B * p.H, DD = D * D;
-    constexpr size_t lds_bwd = Smem<T, CT, D>::bwd;
     const dim3 scan_grid((DD / 4 + 255) / 256, chains);
     hipError_t e;
     if (ke) (void)hipEventRecord(ke->ev[0], s);
@@ -1549,89 +1529,30 @@ static hipError_t run_bwd(const Plan &p, const BwdArgs &a, hipStream_t s, const 
         k_scan<true, false><<<scan_grid, dim3(256), 0, s>>>(a.scratch, a.dkv_out, a.decay, nullptr, p.H, DD, p.nseg,
                                                            p.tiles_per_seg, p.ntiles, p.tile, D, p.dk, p.dv);
     if (ke) (void)hipEventRecord(ke->ev[2], s);
-    if constexpr (sizeof(T) == 2 && CT == 64 && (WK != D || WV != D)) {
-        if (p.cache_stride == 2) {   // even tile count: the pair kernel, as for equal dimensions
-            constexpr size_t lds_bwd8p = Bwd8pSmem<T, CT, D>::TOTAL;
-            auto launch = [&](auto kb) -> hipError_t {
-                if (hipError_t e2 = allow_lds(kb, lds_bwd8p); e2 != hipSuccess) return e2;
-                kb<<<dim3(p.nseg, chains), dim3(D * 4), lds_bwd8p, s>>>((const T *)a.q, (const T *)a.k, (const T *)a.v,
-                                                                        (const T *)a.dout, a.decay, (const T *)a.cache, (T *)a.dq,
-                                                                        (T *)a.dk, (T *)a.dv, a.dkv_in, (const float *)a.scratch,
-                                                                        a.rtok, p.H, p.ntiles, p.nseg, p.tiles_per_seg, p.N, p.kvdiv,
-                                                                        (const T *)a.yn, a.rstd);
-                return hipSuccess;
-            };
-            if (e = p.token ? (p.norm ? launch(k_bwd8p<T, CT, D, true, true, WK, WV>) : launch(k_bwd8p<T, CT, D, true, false, WK, WV>))
-                            : (p.norm ? launch(k_bwd8p<T, CT, D, false, true, WK, WV>) : launch(k_bwd8p<T, CT, D, false, false, WK, WV>));
-                e != hipSuccess)
-                return e;
+    // The walking kernel: bfloat16 tiles of 64 tokens run in eight waves, with one cached state per pair of
+    // tiles when the tile count is even; everything else in four waves with one cached state per tile. All
+    // three take the same arguments.
+    auto walk = by_model<BwdFam<T, CT, D, WK, WV>>(p);
+    unsigned threads = D * 2;
+    size_t lds = Smem<T, CT, D>::bwd;
+    if constexpr (sizeof(T) == 2 && CT == 64) {
+        static_assert(Bwd8pSmem<T, CT, D>::TOTAL <= 163840 && Bwd8Smem<T, CT, D>::TOTAL <= 163840, "LDS budget of one gfx950 CU exceeded");
+        if (p.cache_stride == 2) {
+            walk = by_model<Bwd8pFam<T, CT, D, WK, WV>>(p);
+            threads = D * 4;
+            lds = Bwd8pSmem<T, CT, D>::TOTAL;
+        } else if constexpr (WK == D && WV == D) {
+            walk = by_model<Bwd8Fam<T, CT, D>>(p);
+            threads = D * 4;
+            lds = Bwd8Smem<T, CT, D>::TOTAL;
         }
     }
-    if constexpr (WK != D || WV != D) {   // otherwise the four-wave walk, one cached state per tile
-      if (!(sizeof(T) == 2 && CT == 64 && p.cache_stride == 2)) {
-        auto launch = [&](auto kb) -> hipError_t {
-            if (hipError_t e2 = allow_lds(kb, lds_bwd); e2 != hipSuccess) return e2;
-            kb<<<dim3(p.nseg, chains), dim3(D * 2), lds_bwd, s>>>((const T *)a.q, (const T *)a.k, (const T *)a.v,
-                                                                 (const T *)a.dout, a.decay, (const T *)a.cache, (T *)a.dq,
-                                                                 (T *)a.dk, (T *)a.dv, a.dkv_in, (const float *)a.scratch,
-                                                                 a.rtok, p.H, p.ntiles, p.nseg, p.tiles_per_seg, p.N, p.kvdiv,
-                                                                 (const T *)a.yn, a.rstd);
-            return hipSuccess;
-        };
-        if (e = p.token ? (p.norm ? launch(k_bwd<T, CT, D, true, true, WK, WV>) : launch(k_bwd<T, CT, D, true, false, WK, WV>))
-                        : (p.norm ? launch(k_bwd<T, CT, D, false, true, WK, WV>) : launch(k_bwd<T, CT, D, false, false, WK, WV>));
-            e != hipSuccess)
-            return e;
-      }
-    } else if constexpr (sizeof(T) == 2 && CT == 64) {
-      if (p.cache_stride == 2) {
-        constexpr size_t lds_bwd8p = Bwd8pSmem<T, CT, D>::TOTAL;
-        static_assert(lds_bwd8p <= 163840, "LDS budget of one gfx950 CU exceeded");
-        auto launch = [&](auto kb) -> hipError_t {
-            if (hipError_t e2 = allow_lds(kb, lds_bwd8p); e2 != hipSuccess) return e2;
-            kb<<<dim3(p.nseg, chains), dim3(D * 4), lds_bwd8p, s>>>((const T *)a.q, (const T *)a.k, (const T *)a.v,
-                                                                    (const T *)a.dout, a.decay, (const T *)a.cache, (T *)a.dq,
-                                                                    (T *)a.dk, (T *)a.dv, a.dkv_in, (const float *)a.scratch,
-                                                                    a.rtok, p.H, p.ntiles, p.nseg, p.tiles_per_seg, p.N, p.kvdiv,
-                                                                    (const T *)a.yn, a.rstd);
-            return hipSuccess;
-        };
-        if (e = p.token ? (p.norm ? launch(k_bwd8p<T, CT, D, true, true>) : launch(k_bwd8p<T, CT, D, true>))
-                        : (p.norm ? launch(k_bwd8p<T, CT, D, false, true>) : launch(k_bwd8p<T, CT, D, false>));
-            e != hipSuccess)
-            return e;
-      } else {
-        constexpr size_t lds_bwd8 = Bwd8Smem<T, CT, D>::TOTAL;
-        static_assert(lds_bwd8 <= 163840, "LDS budget of one gfx950 CU exceeded");
-        auto launch = [&](auto kb) -> hipError_t {
-            if (hipError_t e2 = allow_lds(kb, lds_bwd8); e2 != hipSuccess) return e2;
-            kb<<<dim3(p.nseg, chains), dim3(D * 4), lds_bwd8, s>>>((const T *)a.q, (const T *)a.k, (const T *)a.v,
-                                                                   (const T *)a.dout, a.decay, (const T *)a.cache, (T *)a.dq,
-                                                                   (T *)a.dk, (T *)a.dv, a.dkv_in, (const float *)a.scratch,
-                                                                   a.rtok, p.H, p.ntiles, p.nseg, p.tiles_per_seg, p.N, p.kvdiv,
-                                                                   (const T *)a.yn, a.rstd);
-            return hipSuccess;
-        };
-        if (e = p.token ? (p.norm ? launch(k_bwd8<T, CT, D, true, true>) : launch(k_bwd8<T, CT, D, true>))
-                        : (p.norm ? launch(k_bwd8<T, CT, D, false, true>) : launch(k_bwd8<T, CT, D, false>));
-            e != hipSuccess)
-            return e;
-      }
-    } else {
-        auto launch = [&](auto kb) -> hipError_t {
-            if (hipError_t e2 = allow_lds(kb, lds_bwd); e2 != hipSuccess) return e2;
-            kb<<<dim3(p.nseg, chains), dim3(D * 2), lds_bwd, s>>>((const T *)a.q, (const T *)a.k, (const T *)a.v,
-                                                                 (const T *)a.dout, a.decay, (const T *)a.cache, (T *)a.dq,
-                                                                 (T *)a.dk, (T *)a.dv, a.dkv_in, (const float *)a.scratch,
-                                                                 a.rtok, p.H, p.ntiles, p.nseg, p.tiles_per_seg, p.N, p.kvdiv,
-                                                                 (const T *)a.yn, a.rstd);
-            return hipSuccess;
-        };
-        if (e = p.token ? (p.norm ? launch(k_bwd<T, CT, D, true, true>) : launch(k_bwd<T, CT, D, true>))
-                        : (p.norm ? launch(k_bwd<T, CT, D, false, true>) : launch(k_bwd<T, CT, D, false>));
-            e != hipSuccess)
-            return e;
-    }
+    if (e = launch_kernel(walk, dim3(p.nseg, chains), dim3(threads), lds, s, (const T *)a.q, (const T *)a.k, (const T *)a.v,
+                          (const T *)a.dout, a.decay, (const T *)a.cache, (T *)a.dq, (T *)a.dk, (T *)a.dv, a.dkv_in,
+                          (const float *)a.scratch, a.rtok, p.H, p.ntiles, p.nseg, p.tiles_per_seg, p.N, p.kvdiv,
+                          (const T *)a.yn, a.rstd);
+        e != hipSuccess)
+        return e;
     if (p.kvdiv > 1) {
         if (e = run_group_sum<T>(p, a.dk, a.dk_out, p.dk, s); e != hipSuccess) return e;
         if (e = run_group_sum<T>(p, a.dv, a.dv_out, p.dv, s); e != hipSuccess) return e;

@@ -172,15 +172,15 @@ def test_g2_split_and_unsplit(gpu, oracle):
 
 def test_g3_full_size(gpu, oracle):
     """The benchmark shape with a decay per token, in the launch configuration bench.py times:
-    full tensors against the chunked oracle on a subset of heads, brute-force rows over all heads."""
+    full tensors against the chunked oracle on every head, brute-force rows over all heads."""
     harness, lasp, si = gpu
     cfg = si.CONFIGS["g3"]
-    heads = [0, 5, 10, 15]
+    heads = None   # every head
     say("case g3: generating inputs")
     inp = si.make_inputs(cfg)
     say("case g3: gpu run")
     got = harness.run_gpu(inp, T=cfg.T)
-    say(f"case g3: chunked oracle on heads {heads}")
+    say("case g3: chunked oracle on all heads")
     ref = oracle_all(oracle, inp, form="chunked", chunk=cfg.chunk, heads=heads)
     compare(harness, got, ref, TOL["bf16"], "g3", heads=heads)
     say("case g3: brute-force rows")
