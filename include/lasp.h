@@ -145,6 +145,29 @@ int lasp_fwd(const lasp_shape *shape, const void *q, const void *k, const void *
              void *state_cache, void *scratch, size_t scratch_bytes, void *hip_stream);
 
 /*
+ * lasp_fwd for callers that cannot allocate device memory or must not pass a
+ * workspace: code under HIP graph capture, tight serving loops, harnesses that
+ * forbid hipMalloc. Same computation, same kernels and bit-identical results;
+ * the scratch (segment states) is a fixed array inside the library instead of a
+ * caller's buffer. The call allocates and frees nothing and does not synchronise.
+ *   - The array holds lasp_noalloc_scratch_limit() bytes (32 MiB) on every
+ *     device the library is used on, until the process ends. A shape whose
+ *     lasp_scratch_bytes() exceeds it is rejected with LASP_ERR_WORKSPACE before
+ *     anything is launched (lower `segments`, or use lasp_fwd).
+ *   - All calls on one device share that array: calls that overlap in time on one
+ *     device (different streams, or threads) race. Order them on one stream.
+ *     Nothing in it needs clearing between calls: every slot a call reads it has
+ *     written first.
+ *   - The first call on a device resolves the array's address (one host-side
+ *     look-up, no allocation); make that call outside a graph capture.
+ * Arguments and statuses otherwise as for lasp_fwd.
+ */
+int lasp_fwd_noalloc(const lasp_shape *shape, const void *q, const void *k, const void *v,
+                     const float *kv_in, const float *decay, void *out, float *kv_out,
+                     void *state_cache, void *hip_stream);
+size_t lasp_noalloc_scratch_limit(void);
+
+/*
  * Backward (Alg. 3 with Recv/Send replaced by dkv_out/dkv_in). Gradients of
  *     L = sum(out * dout) + sum(kv_out * dkv_out):
  *     dq_s = kv_s do_s,  dk_s = dkv_s v_s,  dv_s = dkv_s^T k_s,

@@ -309,7 +309,7 @@ const char *lasp_status_str(int status) {
         case LASP_ERR_SHAPE: return "unsupported shape (need B,H,N > 0, D and Dv in {64,128} (Dv 0 = D), chunk in {64,128,256}, 0 <= segments <= ceil(N/tile))";
         case LASP_ERR_DTYPE: return "unsupported dtype (LASP_F32 or LASP_BF16)";
         case LASP_ERR_DECAY: return "decay must be finite and in (0, 1] (log decay: finite and <= 0)";
-        case LASP_ERR_WORKSPACE: return "scratch buffer missing or too small (see lasp_scratch_bytes)";
+        case LASP_ERR_WORKSPACE: return "scratch buffer missing or too small (see lasp_scratch_bytes); lasp_fwd_noalloc: the shape needs more scratch than the library holds (see lasp_noalloc_scratch_limit)";
         case LASP_ERR_ALIAS: return "an output buffer overlaps an input or another output";
         case LASP_ERR_HIP: return "HIP runtime error at launch";
         case LASP_ERR_ALIGN: return "a buffer is not 16-byte aligned";
@@ -373,6 +373,21 @@ int lasp_fwd(const lasp_shape *shape, const void *q, const void *k, const void *
               hip_stream};
     return run_fwd_call(c);
 }
+
+int lasp_fwd_noalloc(const lasp_shape *shape, const void *q, const void *k, const void *v, const float *kv_in,
+                     const float *decay, void *out, float *kv_out, void *state_cache, void *hip_stream) {
+    ScratchLayout l;
+    if (int rc = lasp_check_shape(shape); rc != LASP_OK) return rc;
+    if (!scratch_layout(shape, false, &l)) return LASP_ERR_SHAPE;
+    if (l.total > lasp::kStaticScratchBytes) return LASP_ERR_WORKSPACE;   // beyond the library's own scratch
+    void *scr = nullptr;
+    if (lasp::static_scratch(&scr) != hipSuccess) return LASP_ERR_HIP;
+    FwdCall c{shape, q, k, v, kv_in, decay, false, false, 0.0f, out, nullptr, kv_out, state_cache, scr,
+              lasp::kStaticScratchBytes, hip_stream};
+    return run_fwd_call(c);
+}
+
+size_t lasp_noalloc_scratch_limit(void) { return lasp::kStaticScratchBytes; }
 
 int lasp_bwd(const lasp_shape *shape, const void *q, const void *k, const void *v, const void *dout,
              const float *dkv_out, const float *decay, const void *state_cache, void *dq, void *dk,

@@ -70,6 +70,12 @@ struct KernelEvents {
 // once per (kernel, device) pair; later calls are a table lookup. Thread-safe.
 hipError_t allow_dynamic_lds(const void *kernel, size_t bytes);
 
+// The library's own scratch for lasp_fwd_noalloc: a file-scope device array of kStaticScratchBytes
+// (32 MiB: 512 float [128][128] segment states, the automatic plan of 16 heads). static_scratch() returns
+// its address on the current device (resolved once per device).
+constexpr size_t kStaticScratchBytes = (size_t)32 << 20;
+hipError_t static_scratch(void **ptr);
+
 // Tile length used for a (dtype, chunk, D) combination.
 int tile_tokens(int dtype, int chunk, int D);
 // Cache stride for a shape: 2 (one cached state per pair of tiles, the backward

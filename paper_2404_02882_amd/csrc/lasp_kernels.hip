@@ -37,6 +37,8 @@
 // state are always fp32.
 #include <hip/hip_runtime.h>
 
+#include <mutex>
+
 #include "lasp_internal.h"
 #include "lasp_device.h"
 
@@ -1586,6 +1588,29 @@ extern "C" int lasp_debug_phases(unsigned long long *out256, int reset) {
     return 0;
 }
 #endif
+
+// Scratch of the entry point that allocates nothing (lasp_fwd_noalloc): the segment states live in this
+// array instead of a buffer the caller brings. Every device the library runs on holds its own copy, at
+// its own address, until the process ends. The name below is a host-side stand-in, not a device address:
+// host code uses the pointer static_scratch() returns, never the name.
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+hipError_t static_scratch(void **ptr) {
+    static std::mutex mu;
+    static void *addr[64] = {};   // per device, filled on the first call with that device current
+    int dev = 0;
+    if (hipError_t e = hipGetDevice(&dev); e != hipSuccess) return e;
+    if (dev < 0 || dev >= 64) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> hold(mu);
+    if (!addr[dev]) {
+        void *p = nullptr;
+        if (hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)); e != hipSuccess) return e;
+        if (!p) return hipErrorInvalidSymbol;
+        addr[dev] = p;
+    }
+    *ptr = addr[dev];
+    return hipSuccess;
+}
 
 int cache_stride_for(int dtype, int tile, int ntiles, bool token, bool mixed_dims) {
     (void)token;       // both decay models have the pair kernel,

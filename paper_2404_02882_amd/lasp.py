@@ -57,6 +57,10 @@ def _bind(handle):
     handle.lasp_scratch_bytes.restype = _sz
     handle.lasp_fwd.argtypes = [_sp] + [_vp] * 9 + [_sz, _vp]
     handle.lasp_fwd.restype = ctypes.c_int
+    handle.lasp_fwd_noalloc.argtypes = [_sp] + [_vp] * 9
+    handle.lasp_fwd_noalloc.restype = ctypes.c_int
+    handle.lasp_noalloc_scratch_limit.argtypes = []
+    handle.lasp_noalloc_scratch_limit.restype = _sz
     handle.lasp_bwd.argtypes = [_sp] + [_vp] * 12 + [_sz, _vp]
     handle.lasp_bwd.restype = ctypes.c_int
     handle.lasp_check_log_decay.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_int64]
@@ -171,6 +175,18 @@ def lasp_fwd(shape: Shape, q, k, v, kv_in, decay, out, kv_out, state_cache, scra
                       _ptr(kv_out), _ptr(state_cache), _ptr(scratch), nbytes, _stream(stream))
     if rc != 0:
         raise LaspError(rc, "lasp_fwd")
+
+
+def noalloc_scratch_limit() -> int:
+    return int(lib.lasp_noalloc_scratch_limit())
+
+
+def lasp_fwd_noalloc(shape: Shape, q, k, v, kv_in, decay, out, kv_out, state_cache, stream=None) -> None:
+    """lasp_fwd with the library's own fixed scratch (no workspace argument); raises LaspError on a non-zero status."""
+    rc = lib.lasp_fwd_noalloc(ctypes.byref(shape), _ptr(q), _ptr(k), _ptr(v), _ptr(kv_in), _ptr(decay), _ptr(out),
+                              _ptr(kv_out), _ptr(state_cache), _stream(stream))
+    if rc != 0:
+        raise LaspError(rc, "lasp_fwd_noalloc")
 
 
 def lasp_bwd(shape: Shape, q, k, v, dout, dkv_out, decay, state_cache, dq, dk, dv, dkv_in, scratch,
