@@ -68,6 +68,20 @@ DEVI void pipelined(Load load, Use use) {
         if (s + 2 < N) nxt = nn;
     }
 }
+// The same for a long run of single-fragment steps with few registers: step i's fragment is requested
+// AHEAD steps before it is used, so AHEAD fragments are in flight instead of whole multi-fragment steps.
+template <int N, int AHEAD, typename Load, typename Use>
+DEVI void pipelined_flat(Load load, Use use) {
+    decltype(load(0)) ring[AHEAD];
+#pragma unroll
+    for (int i = 0; i < AHEAD && i < N; ++i) ring[i] = load(i);
+#pragma unroll
+    for (int i = 0; i < N; ++i) {
+        const auto cur = ring[i % AHEAD];
+        if (i + AHEAD < N) ring[i % AHEAD] = load(i + AHEAD);
+        use(i, cur);
+    }
+}
 template <typename F>
 struct FragPair {
     F a, b;
@@ -416,12 +430,15 @@ struct NormTile {
 template <typename T>
 struct GeoWeights {
     float after[8], upto[8];
+    // (lam is the same in every lane; the factors are moved to scalar registers, where they cost no
+    // vector registers for the length of the kernel)
+    static DEVI float uniform(float x) { return __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(x))); }
     DEVI explicit GeoWeights(float lam) {
         const float l2f = (float)log2((double)lam);
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
-            after[e] = e < Elem<T>::KH ? exp2f((float)(Elem<T>::KH - 1 - e) * l2f) : 1.0f;
-            upto[e] = e < Elem<T>::KH ? exp2f((float)e * l2f) : 1.0f;
+            after[e] = e < Elem<T>::KH ? uniform(exp2f((float)(Elem<T>::KH - 1 - e) * l2f)) : 1.0f;
+            upto[e] = e < Elem<T>::KH ? uniform(exp2f((float)e * l2f)) : 1.0f;
         }
     }
 };
@@ -458,17 +475,22 @@ DEVI void fill_pow_table(float *pw, float lam) {
 template <typename T, int CT>
 struct FixedDecay {
     static constexpr bool kToken = false;
+    // Table in LDS: CT - 1 zeros, then lambda^0 .. lambda^(2 CT). pw points at lambda^0, so pw[d] is
+    // lambda^d for 0 <= d <= 2 CT and ZERO for -(CT - 1) <= d < 0: the mask M (zero where the key comes after
+    // the query) is a plain multiplication by pw[i - j], no compare and select. Exponents above CT serve the
+    // kernel that reaches across a pair of tiles.
+    static constexpr int kTableFloats = 3 * CT;
     const float *pw;
     GeoWeights<T> geo;
-    DEVI FixedDecay(float *tab, float lam) : pw(tab), geo(lam) { fill_pow_table<CT>(tab, lam); }
+    DEVI FixedDecay(float *tab, float lam) : pw(tab + (CT - 1)), geo(lam) {
+        const double l2 = log2((double)lam);   // evaluated in double so that the table adds no error of its own
+        for (int i = threadIdx.x; i < kTableFloats; i += blockDim.x)
+            tab[i] = i < CT - 1 ? 0.0f : (float)exp2((double)(i - (CT - 1)) * l2);
+    }
     DEVI float upto(int i) const { return pw[i + 1]; }
     DEVI float after(int j) const { return pw[CT - 1 - j]; }
     DEVI float whole() const { return pw[CT]; }
-    DEVI float masked(float x, int i, int j) const {
-        const int d = i - j;
-        const float m = pw[d >= 0 ? d : 0];
-        return d >= 0 ? x * m : 0.0f;
-    }
+    DEVI float masked(float x, int i, int j) const { return x * pw[i - j]; }
     DEVI typename Elem<T>::frag weigh_after(const Lane &ln, typename Elem<T>::frag f, int ks) const {
         return lasp::weigh_after<T, CT>(ln, f, ks, pw, geo);
     }
@@ -657,32 +679,64 @@ DEVI void masked_scores(const Lane &ln, T *sP, const T *sA, const T *sB, const D
 // its token per register group, so it stores them as one 8- or 16-byte piece.
 // W <= D: the tensor's rows hold only W features (row stride W); waves whose column block lies
 // beyond them hold padding and store nothing.
+// The two-byte form of such a tile, ready to store. The lane's four features of a register group are 8
+// bytes, and a store instruction of 8-byte pieces would leave 16 bytes in each of 32 rows. Two exchanges
+// between lanes widen that:
+//   - The two half-waves hold neighbouring features of the same token, so they trade register groups
+//     (v_permlane32_swap: lanes 32..63 of the first operand against lanes 0..31 of the second): every
+//     lane then holds two 16-byte pieces of its token, features 16 p + 8 h .. + 7 (p = 0, 1).
+//   - Lanes 16 apart hold the same pieces of tokens 16 apart, so piece 1 of the lower 16 tokens is traded
+//     against piece 0 of the upper 16 (v_permlane16_swap: odd 16-lane rows of the first operand against
+//     even rows of the second): v[0] then holds all four pieces (64 contiguous bytes) of tokens 0..15,
+//     v[1] those of tokens 16..31. A store instruction writes 16 rows of 64 bytes, not 32 rows of 32:
+//     half the memory requests for the same bytes.
+// After both, lane l holds in v[j] the features 16 ((l >> 4) & 1) + 8 (l >> 5) .. + 7 of token 16 j + (l & 15)
+// (features relative to the wave's 32-feature block, tokens relative to the tile's 32-token block).
+struct PackedTile {
+    u32x4 v[2];
+};
+DEVI PackedTile pack_out_tile_t(const f32x16 &acc) {
+    u32x2 d[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        union { bf16x4 v; u32x2 u; } pk;
+        pk.v = __builtin_convertvector(f32x4{acc[4 * q], acc[4 * q + 1], acc[4 * q + 2], acc[4 * q + 3]}, bf16x4);
+        d[q] = pk.u;
+    }
+    u32x4 piece[2];
+#pragma unroll
+    for (int p = 0; p < 2; ++p) {
+        const u32x2 s0 = __builtin_amdgcn_permlane32_swap(d[2 * p][0], d[2 * p + 1][0], false, false);
+        const u32x2 s1 = __builtin_amdgcn_permlane32_swap(d[2 * p][1], d[2 * p + 1][1], false, false);
+        piece[p] = u32x4{s0[0], s1[0], s0[1], s1[1]};
+    }
+    PackedTile t;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        const u32x2 x = __builtin_amdgcn_permlane16_swap(piece[0][e], piece[1][e], false, false);
+        t.v[0][e] = x[0];
+        t.v[1][e] = x[1];
+    }
+    return t;
+}
+// g: first element of the tile (uniform); rows hold W two-byte elements; the wave's block starts at feature 32 w
+template <typename T, int W>
+DEVI void store_packed_tile_t(const Lane &ln, T *g, const PackedTile &t, int row0, int w, int nrows = 1 << 30) {
+    static_assert(sizeof(T) == 2, "two-byte elements");
+    const int tok = ln.id & 15, feat = 32 * w + 16 * ((ln.id >> 4) & 1) + 8 * (ln.id >> 5);
+    const unsigned lo = (tok * W + feat) * sizeof(T);
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+        if (row0 + 16 * j + tok < nrows) gstore<u32x4>(g + (row0 + 16 * j) * W, lo, t.v[j]);
+}
+
 template <typename T, int D, int W = D>
 DEVI void store_out_tile_t(const Lane &ln, T *g, const f32x16 &acc, int row0, int w, int nrows = 1 << 30) {
     if constexpr (W < D) {
         if (32 * w >= W) return;
     }
     if constexpr (sizeof(T) == 2) {
-        // Two-byte elements: the lane's four features are 8 bytes, and a store instruction of 8-byte pieces
-        // leaves 16 bytes in each of 32 rows. The two half-waves hold neighbouring features of the same
-        // token, so they trade register groups (one v_permlane32_swap per dword: lanes 32..63 of the first
-        // operand against lanes 0..31 of the second) and every lane stores 16 bytes: half the requests.
-        u32x2 d[4];
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            union { bf16x4 v; u32x2 u; } pk;
-            pk.v = __builtin_convertvector(f32x4{acc[4 * q], acc[4 * q + 1], acc[4 * q + 2], acc[4 * q + 3]}, bf16x4);
-            d[q] = pk.u;
-        }
-        const unsigned lo = (ln.r * W + 32 * w + 8 * ln.h) * sizeof(T);
-        const bool live = row0 + ln.r < nrows;  // (a token and its partner lane share the row: both live or both not)
-#pragma unroll
-        for (int p = 0; p < 2; ++p) {
-            // half-wave 0 ends up with features 16p .. 16p+7 of its token, half-wave 1 with 16p+8 .. 16p+15
-            const u32x2 s0 = __builtin_amdgcn_permlane32_swap(d[2 * p][0], d[2 * p + 1][0], false, false);
-            const u32x2 s1 = __builtin_amdgcn_permlane32_swap(d[2 * p][1], d[2 * p + 1][1], false, false);
-            if (live) gstore<u32x4>(g + row0 * W + 16 * p, lo, u32x4{s0[0], s1[0], s0[1], s1[1]});
-        }
+        store_packed_tile_t<T, W>(ln, g, pack_out_tile_t(acc), row0, w, nrows);
     } else {
         const unsigned lo = (ln.r * W + 32 * w + 4 * ln.h) * sizeof(T);
         if (row0 + ln.r >= nrows) return;  // token past the end of the sub-sequence

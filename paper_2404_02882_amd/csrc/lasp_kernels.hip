@@ -665,7 +665,9 @@ __global__ __launch_bounds__(D * 2, (CT <= 64 && sizeof(T) == 2 && WK == D && WV
 //       group 1 holds dKV[a in w][c] (rows c) and produces dK (dK_inter contracts c);
 //     under the exchange K<->V, Q<->dO, S<->dS the two products are the same
 //     code, including the dKV update, so the groups differ only in pointers;
-//   - dQ needs only the cached state and is split by token block between them.
+//   - dQ needs only the cached state and is split by token block between them
+//     (group 0, which the hardware favours when both wait to issue, takes the
+//     block with the longer key range).
 // ---------------------------------------------------------------------------
 template <typename T, int CT, int D>
 struct Bwd8Smem {
@@ -834,11 +836,11 @@ __global__ __launch_bounds__(D * 4) void k_bwd8(const T *__restrict__ Q, const T
         ln = fresh_lane();
         PHASE(2);
 
-        float rq = 0.0f;  // per-token decay: q_i . dq_i over this wave's features, tokens i of block rg
-        // ---- dQ^T[a in w][i], tokens i of block rg:
+        float rq = 0.0f;  // per-token decay: q_i . dq_i over this wave's features, tokens i of block 1 - rg
+        // ---- dQ^T[a in w][i], tokens i of block 1 - rg:
         //      lambda^i sum_c KV_{t-1}[a][c] dO[i][c] + sum_{j<=i} K[j][a] dSm[i][j] ----
         {
-            const int r0 = 32 * rg;
+            const int r0 = 32 * (1 - rg);   // group 0 takes the second token block (whose keys span both blocks), group 1 the first
             f32x16 acc = {0};
             pipelined<NKD>(
                 [&](int ks) { return FragPair<F>{E::ld_kc(ln, sC, LDD, 32 * w, ks * E::KSTEP), E::ld_kc(ln, sdO, LDD, r0, ks * E::KSTEP)}; },
@@ -846,8 +848,8 @@ __global__ __launch_bounds__(D * 4) void k_bwd8(const T *__restrict__ Q, const T
             acc *= dec.upto(r0 + ln.r);
             auto intra = [&](int ks) { return FragPair<F>{E::ld_ks(ln, sK, LDD, ks * E::KSTEP, 32 * w), E::ld_kc(ln, sDS, LDP, r0, ks * E::KSTEP)}; };
             auto fma = [&](int, const FragPair<F> &f) { acc = E::mfma(f.a, f.b, acc); };
-            if (rg == 0) pipelined<SPB>(intra, fma);        // keys of block 0
-            else pipelined<2 * SPB>(intra, fma);            // keys of blocks 0 and 1
+            if (rg == 0) pipelined<2 * SPB>(intra, fma);    // keys of blocks 0 and 1
+            else pipelined<SPB>(intra, fma);                // keys of block 0
             store_out_tile_t<T, D>(ln, dQ + off, acc, r0, w, nrows);
             if constexpr (TOKEN) rq = rowdot<T>(ln, acc, sQ, LDD, r0, w);
         }
@@ -894,7 +896,7 @@ __global__ __launch_bounds__(D * 4) void k_bwd8(const T *__restrict__ Q, const T
             if constexpr (TOKEN) {
 #pragma unroll
                 for (int jb = 0; jb < NB; ++jb) {
-                    float r = jb == rg ? rq : 0.0f;
+                    float r = jb == 1 - rg ? rq : 0.0f;
                     if (rg == 1) r -= rowdot<T>(ln, acc[jb], sK, LDD, 32 * jb, w);  // group 1 holds dK
                     if (ln.h == 0) rs[w8 * CT + 32 * jb + ln.r] = r;
                 }
@@ -1012,18 +1014,15 @@ __global__ __launch_bounds__(D * 4) void k_bwd8p(const T *__restrict__ Q, const 
         if constexpr (TOKEN) return TokenDecay<T, CT>(pw + 3 * CT);
         else return decO;
     }();
-    if constexpr (!TOKEN) {   // lambda^(CT+1) .. lambda^(2 CT): weights between the two tiles of a pair
-        const float lam = decay[chain % H];
-        for (int i = CT + 1 + threadIdx.x; i <= 2 * CT; i += blockDim.x) pw[i] = (float)exp2((double)i * log2((double)lam));
-    }
     // weight key j of the E tile carries at query i of the O tile, and the E tile's entering state at query i
+    // (one lambda per head: powers CT+1 .. 2 CT of the same table)
     auto cross_weight = [&](int i, int j) {
         if constexpr (TOKEN) return decO.upto(i) * decE.after(j);
-        else return pw[CT + i - j];
+        else return decO.pw[CT + i - j];
     };
     auto far_upto = [&](int i) {
         if constexpr (TOKEN) return decO.upto(i) * decE.whole();
-        else return pw[CT + i + 1];
+        else return decO.pw[CT + i + 1];
     };
     const float *lg = decay + (size_t)chain * ntok;
     typename TokenDecay<T, CT>::LogG lgO = {}, lgE = {};
@@ -1159,9 +1158,9 @@ __global__ __launch_bounds__(D * 4) void k_bwd8p(const T *__restrict__ Q, const 
     // as the first half of its own chunk: far weights on the state term, plus the E tile's keys through sDX.
     auto products = [&](const auto &dec, const T *pV, const T *pK, int t, int nrows, bool cross) {
         const T *sX1 = rg ? pV : pK;  // inter operand: token rows, features contracted with the state
-        float rq = 0.0f;  // per-token decay: q_i . dq_i over this wave's features, tokens i of block rg
-        {   // dQ^T[a in w][i], tokens i of block rg
-            const int r0 = 32 * rg;
+        float rq = 0.0f;  // per-token decay: q_i . dq_i over this wave's features, tokens i of block 1 - rg
+        {   // dQ^T[a in w][i], tokens i of block 1 - rg
+            const int r0 = 32 * (1 - rg);   // group 0 takes the second token block (whose keys span both blocks), group 1 the first
             f32x16 acc = {0};
             pipelined<NKD>(
                 [&](int ks) { return FragPair<F>{E::ld_kc(ln, sC, LDD, 32 * w, ks * E::KSTEP), E::ld_kc(ln, sdO, LDD, r0, ks * E::KSTEP)}; },
@@ -1173,8 +1172,8 @@ __global__ __launch_bounds__(D * 4) void k_bwd8p(const T *__restrict__ Q, const 
                     [&](int ks) { return FragPair<F>{E::ld_ks(ln, sKE, LDD, ks * E::KSTEP, 32 * w), E::ld_kc(ln, sDX, LDP, r0, ks * E::KSTEP)}; },
                     fma);
             auto intra = [&](int ks) { return FragPair<F>{E::ld_ks(ln, pK, LDD, ks * E::KSTEP, 32 * w), E::ld_kc(ln, sDS, LDP, r0, ks * E::KSTEP)}; };
-            if (rg == 0) pipelined<SPB>(intra, fma);
-            else pipelined<2 * SPB>(intra, fma);
+            if (rg == 0) pipelined<2 * SPB>(intra, fma);    // keys of blocks 0 and 1
+            else pipelined<SPB>(intra, fma);                // keys of block 0
             store_out_tile_t<T, D, WK>(ln, dQ + koff(t), acc, r0, w, nrows);
             if constexpr (TOKEN) rq = rowdot<T>(ln, acc, sQ, LDD, r0, w);
         }
@@ -1225,7 +1224,7 @@ __global__ __launch_bounds__(D * 4) void k_bwd8p(const T *__restrict__ Q, const 
             if constexpr (TOKEN) {
 #pragma unroll
                 for (int jb = 0; jb < NB; ++jb) {
-                    float r = jb == rg ? rq : 0.0f;
+                    float r = jb == 1 - rg ? rq : 0.0f;
                     if (rg == 1) r -= rowdot<T>(ln, acc[jb], pK, LDD, 32 * jb, w);  // group 1 holds dK
                     if (ln.h == 0) rs[w8 * CT + 32 * jb + ln.r] = r;
                 }
@@ -1533,21 +1532,28 @@ static hipError_t run_bwd(const Plan &p, const BwdArgs &a, hipStream_t s, const 
     if (ke) (void)hipEventRecord(ke->ev[2], s);
     // The walking kernel: bfloat16 tiles of 64 tokens run in eight waves, with one cached state per pair of
     // tiles when the tile count is even; everything else in four waves with one cached state per tile. All
-    // three take the same arguments.
-    auto walk = by_model<BwdFam<T, CT, D, WK, WV>>(p);
+    // three take the same arguments. (Only the kernels a shape can reach are instantiated.)
+    typedef void (*Walk)(const T *, const T *, const T *, const T *, const float *, const T *, T *, T *, T *, float *,
+                         const float *, float *, int, int, int, int, int, int, const T *, const float *);
+    Walk walk = nullptr;
     unsigned threads = D * 2;
     size_t lds = Smem<T, CT, D>::bwd;
-    if constexpr (sizeof(T) == 2 && CT == 64) {
+    constexpr bool kEightWaves = sizeof(T) == 2 && CT == 64, kEqualDims = WK == D && WV == D;
+    if constexpr (kEightWaves) {
         static_assert(Bwd8pSmem<T, CT, D>::TOTAL <= 163840 && Bwd8Smem<T, CT, D>::TOTAL <= 163840, "LDS budget of one gfx950 CU exceeded");
         if (p.cache_stride == 2) {
             walk = by_model<Bwd8pFam<T, CT, D, WK, WV>>(p);
             threads = D * 4;
             lds = Bwd8pSmem<T, CT, D>::TOTAL;
-        } else if constexpr (WK == D && WV == D) {
+        } else if constexpr (kEqualDims) {
             walk = by_model<Bwd8Fam<T, CT, D>>(p);
             threads = D * 4;
             lds = Bwd8Smem<T, CT, D>::TOTAL;
+        } else {
+            walk = by_model<BwdFam<T, CT, D, WK, WV>>(p);
         }
+    } else {
+        walk = by_model<BwdFam<T, CT, D, WK, WV>>(p);
     }
     if (e = launch_kernel(walk, dim3(p.nseg, chains), dim3(threads), lds, s, (const T *)a.q, (const T *)a.k, (const T *)a.v,
                           (const T *)a.dout, a.decay, (const T *)a.cache, (T *)a.dq, (T *)a.dk, (T *)a.dv, a.dkv_in,
