@@ -21,22 +21,64 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X published dense bf16 MFMA rate
 
-# HBM bytes per launch from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs summarised in
-# profiles/<config>_fwd_bwd_kernels.md (read + written MiB, scaled by the plain-copy calibration:
-# FETCH_SIZE x 2.000, WRITE_SIZE x 1.000), for the default launch configuration. Other configs: None.
-_MIB = 2**20
-MEASURED_TRAFFIC_BYTES = {
-    "c3": {"fwd_walk": int((416.2 + 258.1) * _MIB), "bwd_walk": int((659.1 + 385.0) * _MIB),
-           "fwd_local": int((248.1 + 31.0) * _MIB), "bwd_local": int((240.1 + 15.0) * _MIB)},
-    "g3": {"fwd_walk": int((418.2 + 257.4) * _MIB), "bwd_walk": int((659.4 + 387.0) * _MIB),
-           "fwd_local": int((250.1 + 31.0) * _MIB), "bwd_local": int((242.0 + 15.0) * _MIB)},
-    "n3": {"fwd_walk": int((416.2 + 260.6) * _MIB), "bwd_walk": int((789.1 + 385.0) * _MIB),
-           "fwd_local": int((248.1 + 31.0) * _MIB), "bwd_local": int((362.0 + 15.0) * _MIB)},
-    "m3": {"fwd_walk": int((288.2 + 256.7) * _MIB), "bwd_walk": int((529.2 + 256.5) * _MIB),
-           "fwd_local": int((186.1 + 31.0) * _MIB), "bwd_local": int((180.1 + 15.0) * _MIB)},
-    "b3": {"bwd_apply": int((401.8 + 384.0) * _MIB), "fwd_apply": int((136.2 + 128.0) * _MIB),
-           "state_reduce": int((256.1 + 16.0) * _MIB)},
-}
+# kernel name fragments of the rows of profiles/<config>_fwd_bwd_kernels.md that hold the HBM traffic per launch
+PROFILE_ROW = {"fwd_walk": "k_fwd<", "bwd_walk": "k_bwd", "fwd_local": ("k_local<", ", false, "), "bwd_local": ("k_local<", ", true, "),
+               "bwd_apply": "backward (3 products)", "fwd_apply": "forward (1 product)", "state_reduce": "k_bidir_reduce<"}
+
+
+def traffic_from_profile(config, kernel):
+    """HBM bytes one launch of `kernel` moves, read from the committed rocprofv3 summary of this config
+    (table 'HBM traffic per launch': read MiB + written MiB, already scaled by the plain-copy calibration).
+    Returns (bytes, path) or (None, None) when the summary or the row is missing."""
+    import re
+    path = os.path.join(ROOT, "profiles", f"{config}_fwd_bwd_kernels.md")
+    if not os.path.exists(path):
+        return None, None
+    want = PROFILE_ROW.get(kernel)
+    want = (want,) if isinstance(want, str) else want
+    in_table = False
+    for line in open(path):
+        if line.startswith("## HBM traffic per launch"):
+            in_table = True
+        if not in_table or not line.startswith("| `"):
+            continue
+        cells = [c.strip() for c in line.strip().strip("|").split("|")]
+        name = cells[0]
+        # the local passes differ in the BWD template argument (4th); the walks in the kernel name
+        if kernel in ("fwd_local", "bwd_local"):
+            m = re.match(r"`lasp::k_local<[^,]+, \d+, \d+, (true|false)", name)
+            if not m or (m.group(1) == "true") != (kernel == "bwd_local"):
+                continue
+        elif not all(w in name for w in want) or "k_bwd" in want[0] and "k_bidir" in name:
+            continue
+        try:
+            return int((float(cells[2]) + float(cells[4])) * 2**20), os.path.relpath(path, ROOT)
+        except (IndexError, ValueError):
+            return None, None
+    return None, None
+
+
+def flop_counts(B, H, N, dk, dv, chunk, tile):
+    """Flops of one forward + backward step per the three conventions reported (d_k, d_v; per token-head, times B H N).
+    algorithmic: Alg. 2 / Alg. 3 as printed, full C x C tiles at the configured chunk C:
+        forward  scores 2 C dk + PV 2 C dv + Q KV 2 dk dv + state update 2 dk dv
+        backward scores S, dS 2 C dk + 2 C dv, intra dQ, dK 2 * 2 C dk, intra dV 2 C dv, inter dQ, dK, dV and the dKV update 4 * 2 dk dv
+        (= 14 C d + 12 d^2 at dk = dv = d)
+    causal_minimal: the same with only the 32 x 32 blocks of a chunk that the causal mask leaves non-zero
+    issued: what the kernels execute: tiles of `tile` tokens with the all-zero 32 x 32 blocks skipped, the local passes
+        (2 dk dv each, forward and backward), the dKV update done by both wave groups of the backward walk (+ 2 dk dv) and
+        the O tile's dQ reaching across the pair (scores and product over the E tile's keys, averaged over both tiles)."""
+    th = B * H * N
+    intra_f = lambda c: c * (2 * dk + 2 * dv)                 # forward intra terms per token at tile length c
+    intra_b = lambda c: c * (2 * dk + 2 * dv + 4 * dk + 2 * dv)  # backward intra terms
+    inter = 12 * dk * dv
+    nb = lambda c: max(c // 32, 1)
+    tri = lambda c: (nb(c) + 1) / (2 * nb(c))                 # share of 32 x 32 blocks on or below the diagonal
+    alg = th * (intra_f(chunk) + intra_b(chunk) + inter)
+    causal = th * ((intra_f(chunk) + intra_b(chunk)) * tri(chunk) + inter)
+    issued = th * ((intra_f(tile) + intra_b(tile)) * tri(tile) + inter + 2 * 2 * dk * dv + 2 * dk * dv
+                   + (tile * (2 * dv + 2 * dk)) / 2)
+    return {"algorithmic": alg, "causal_minimal": causal, "issued": issued}
 
 
 def main():
@@ -48,9 +90,13 @@ def main():
     ap.add_argument("--segments", type=int, default=0)
     ap.add_argument("--sub-sequences", type=int, default=0,
                     help="process the sequence as this many sub-sequences with the state handed over (0 = the config's T)")
-    ap.add_argument("--graph", action="store_true",
-                    help="time the step as replays of one HIP graph (pays off when the T-loop is launch-bound); "
-                         "per-kernel times then come from a short eager pass before the timed region")
+    ap.add_argument("--eager", action="store_true",
+                    help="time the step as eager launches (one C-ABI call per sub-sequence and pass) instead of replays of "
+                         "one HIP graph of the same calls; the per-kernel HIP events then lie inside the timed region")
+    ap.add_argument("--graph", action="store_true", help="(the default; kept for older command lines)")
+    ap.add_argument("--prewarm-seconds", type=float, default=1.0,
+                    help="untimed steps run for this long before the counted warm-up, so that a cold device is at its "
+                         "steady clocks when the short timed region starts")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-tokens", type=int, default=32768)
     ap.add_argument("--copy-mib", type=int, default=1024,
@@ -65,7 +111,7 @@ def main():
     import numpy as np
     import torch
     from paper_2404_02882_amd import harness, lasp, synth_inputs as si
-    from paper_2404_02882_amd.sequence import LaspSequence
+    from paper_2404_02882_amd.sequence import GraphedStep, LaspSequence
 
     cfg = si.CONFIGS[args.config]
     if args.sub_sequences > 0:
@@ -81,6 +127,7 @@ def main():
     token = cfg.token_decay
     norm = cfg.norm_eps is not None
     dk_, dv_ = D, cfg.Dv or D   # key and value dimensions
+    torch.cuda.reset_peak_memory_stats()
     seq = LaspSequence(B, H, N, D, cfg.chunk, dt, T=T, segments=args.segments, device=dev, token_decay=token,
                        norm_eps=cfg.norm_eps, Dv=cfg.Dv)
     q, k, v, do = (harness.shards(x, T, cfg.dtype, dev) for x in (inp.q, inp.k, inp.v, inp.dout))
@@ -95,62 +142,69 @@ def main():
     rstd = [torch.empty(B, H, N // T, dtype=torch.float32, device=dev) for _ in range(T)] if norm else None
     tile = lasp.tile_tokens(seq.shape)
     nseg = lasp.num_segments(seq.shape)
+    fwd_kw = dict(q=q, k=k, v=v, decay=decay, out=out, rstd=rstd)
+    bwd_kw = dict(q=q, k=k, v=v, dout=do, decay=decay, dq=dq, dk=dk, dv=dv, dlog_g=dlg, out=out, rstd=rstd)
 
     def step():
-        seq.forward(q, k, v, decay, out, rstd=rstd)
-        seq.backward(q, k, v, do, decay, dq, dk, dv, dlog_g=dlg, out=out, rstd=rstd)
+        seq.forward(**fwd_kw)
+        seq.backward(**bwd_kw)
 
+    def timed(fn, n):
+        """wall-clock milliseconds per call of n calls, bracketed by device synchronisation"""
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(n):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e3 / n
+
+    # untimed: everything host-side first (graph capture leaves the device idle), then the step itself for
+    # `prewarm_seconds` so that a cold device is at its steady clocks, then the counted warm-up
+    step()
+    graphed = GraphedStep(seq, fwd_kw, bwd_kw)
+    fwd_only, bwd_only = GraphedStep(seq, fwd_kw, None), GraphedStep(seq, None, bwd_kw)
+    run = step if args.eager else graphed.replay
+    t_end = time.perf_counter() + max(args.prewarm_seconds, 0.0)
+    while time.perf_counter() < t_end:
+        for _ in range(20):
+            run()
+        torch.cuda.synchronize()
     for _ in range(args.warmup):
-        step()
-    torch.cuda.synchronize()
-    if args.graph:
-        from paper_2404_02882_amd.sequence import GraphedStep
-        lasp.profile_begin(5 * T)          # per-kernel times from an eager pass: events are not captured
-        for _ in range(5):
-            step()
-        torch.cuda.synchronize()
-        kernel_ms, nf, nb = lasp.profile_end()
-        graphed = GraphedStep(seq, dict(q=q, k=k, v=v, decay=decay, out=out, rstd=rstd),
-                              dict(q=q, k=k, v=v, dout=do, decay=decay, dq=dq, dk=dk, dv=dv, dlog_g=dlg, out=out, rstd=rstd))
-        for _ in range(args.warmup):
-            graphed.replay()
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for _ in range(args.steps):
-            graphed.replay()
-        torch.cuda.synchronize()
-        t1 = time.perf_counter()
-    else:
+        run()
+    # ---- the timed region: exactly `steps` steps ----
+    if args.eager:
         lasp.profile_begin(args.steps * T)
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for _ in range(args.steps):
-            step()
-        torch.cuda.synchronize()
-        t1 = time.perf_counter()
-        kernel_ms, nf, nb = lasp.profile_end()
-    ms_per_step = (t1 - t0) * 1e3 / args.steps
-    graph_ms = None
-    if not args.graph:   # for information: the same steps as replays of one HIP graph (not `value`)
-        from paper_2404_02882_amd.sequence import GraphedStep
-        graphed = GraphedStep(seq, dict(q=q, k=k, v=v, decay=decay, out=out, rstd=rstd),
-                              dict(q=q, k=k, v=v, dout=do, decay=decay, dq=dq, dk=dk, dv=dv, dlog_g=dlg, out=out, rstd=rstd))
-        for _ in range(args.warmup):
-            graphed.replay()
-        torch.cuda.synchronize()
-        g0 = time.perf_counter()
-        for _ in range(args.steps):
-            graphed.replay()
-        torch.cuda.synchronize()
-        graph_ms = (time.perf_counter() - g0) * 1e3 / args.steps
+    ms_per_step = timed(run, args.steps)
+    if args.eager:
+        kernel_ms, nf, nb_calls = lasp.profile_end()
+        eager_ms, graph_ms = ms_per_step, timed(graphed.replay, args.steps)
+    else:
+        # per-kernel times: HIP events are not captured in a graph, so they come from an eager pass of the same steps
+        lasp.profile_begin(args.steps * T)
+        eager_ms = timed(step, args.steps)
+        kernel_ms, nf, nb_calls = lasp.profile_end()
+        graph_ms = ms_per_step
     tokens_per_s = B * N / (ms_per_step * 1e-3)
+    # spread of single steps (HIP events around every step, a separate pass) and the two passes on their own
+    evs = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
+    evs[0].record()
+    for i in range(args.steps):
+        run()
+        evs[i + 1].record()
+    torch.cuda.synchronize()
+    per_step = sorted(evs[i].elapsed_time(evs[i + 1]) for i in range(args.steps))
+    for g in (fwd_only, bwd_only):
+        for _ in range(3):
+            g.replay()
+    fwd_ms, bwd_ms = timed(fwd_only.replay, args.steps), timed(bwd_only.replay, args.steps)
+    peak_mem = torch.cuda.max_memory_allocated()
 
     # ---- roofline of the dominant kernel (largest share of the step) ----
     tok_heads_per_launch = B * H * (N // T)
     esz = 2 if cfg.dtype == "bf16" else 4
     per_launch_ms = {"fwd_local": kernel_ms["fwd"][0] / nf, "fwd_scan": kernel_ms["fwd"][1] / nf,
-                     "fwd_walk": kernel_ms["fwd"][2] / nf, "bwd_local": kernel_ms["bwd"][0] / nb,
-                     "bwd_scan": kernel_ms["bwd"][1] / nb, "bwd_walk": kernel_ms["bwd"][2] / nb}
+                     "fwd_walk": kernel_ms["fwd"][2] / nf, "bwd_local": kernel_ms["bwd"][0] / nb_calls,
+                     "bwd_scan": kernel_ms["bwd"][1] / nb_calls, "bwd_walk": kernel_ms["bwd"][2] / nb_calls}
     # algorithmic (compulsory) HBM bytes per token-head: forward walk reads q,k,v and
     # writes o; backward walk reads q,k,v,do and writes dq,dk,dv; local passes read two tensors.
     # With a decay per token every kernel also reads log g (4 B per token-head); dlog_g is written by a
@@ -165,22 +219,34 @@ def main():
     dominant = max(("fwd_walk", "bwd_walk", "fwd_local", "bwd_local"), key=lambda n: per_launch_ms[n])
     dom_bytes = alg_bytes[dominant] * tok_heads_per_launch
     achieved = dom_bytes / (per_launch_ms[dominant] * 1e-3) / 1e9
+    traffic, traffic_src = traffic_from_profile(args.config, dominant) if args.segments == 0 and args.sub_sequences == 0 else (None, None)
     roofline = {"kernel": dominant, "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
                 "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-                "traffic": MEASURED_TRAFFIC_BYTES.get(args.config, {}).get(dominant) if args.segments == 0 else None,
+                "traffic": traffic, "traffic_source": traffic_src,
                 "algorithmic_bytes_per_launch": dom_bytes,
                 "avg_launch_ms": round(per_launch_ms[dominant], 4),
-                "kernel_ms_per_launch": {n: round(x, 4) for n, x in per_launch_ms.items()}}
+                "kernel_ms_per_launch": {n: round(x, 4) for n, x in per_launch_ms.items()},
+                "kernel_times_from": "HIP events on the launch stream around every kernel of "
+                                     + ("the timed eager steps" if args.eager else f"{args.steps} eager steps run right after the timed graph replays")}
 
-    # whole-step figures against both roofs: the chunked algorithm's flops per token-head at the
-    # configured chunk length C (intra-chunk 14*C*d, inter-chunk and state updates 12*d*d), not issued
-    # flops (the kernels run shorter tiles than C and rebuild half of the cached states)
-    flops_step = (cfg.chunk * (8 * dk_ + 6 * dv_) + 12 * dk_ * dv_) * B * H * N   # = 14 C d + 12 d^2 at d_k = d_v = d
+    # whole-step figures against both roofs. Flops: see flop_counts(); `chunk` is validated but does not select the
+    # kernels' tile (64 tokens for bfloat16, 32 for float), so the algorithmic count at C = chunk is not what is issued.
+    flops = flop_counts(B, H, N, dk_, dv_, cfg.chunk, tile)
     min_bytes_step = ((6 * dk_ + 5 * dv_) * esz + 3 * gb + (D * esz + 8 if norm else 0)) * B * H * N
     step_s = ms_per_step * 1e-3
-    extra = {"hip_graph_replay_ms_per_step": round(graph_ms, 4) if graph_ms is not None else None,
-             "algorithmic_tflops": round(flops_step / step_s / 1e12, 2),
-             "mfma_bf16_peak_frac": round(flops_step / step_s / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
+    tf = lambda f: round(f / step_s / 1e12, 2)
+    extra = {"timed_as": "eager launches" if args.eager else "hip graph replay",
+             "eager_ms_per_step": round(eager_ms, 4), "hip_graph_replay_ms_per_step": round(graph_ms, 4),
+             "step_ms_median": round(per_step[len(per_step) // 2], 4), "step_ms_min": round(per_step[0], 4),
+             "step_ms_max": round(per_step[-1], 4),
+             "forward_only_ms": round(fwd_ms, 4), "backward_only_ms": round(bwd_ms, 4),
+             "algorithmic_tflops": tf(flops["algorithmic"]),
+             "mfma_bf16_peak_frac": round(flops["algorithmic"] / step_s / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
+             "causal_minimal_tflops": tf(flops["causal_minimal"]),
+             "causal_minimal_mfma_frac": round(flops["causal_minimal"] / step_s / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
+             "issued_tflops": tf(flops["issued"]),
+             "issued_mfma_frac": round(flops["issued"] / step_s / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
+             "flops_per_step": {n: int(x) for n, x in flops.items()},
              "min_hbm_bytes_per_step": min_bytes_step,
              "step_hbm_frac_at_min_bytes": round(min_bytes_step / step_s / 1e9 / HBM_PEAK_GBS, 4)}
 
@@ -192,29 +258,54 @@ def main():
         from oracle import lasp_oracle
         n_s = min(args.cpu_sample_tokens, N)
         n_s -= n_s % cfg.chunk
-        sl = slice(0, n_s)
-        a = [np.ascontiguousarray(x[:, :, sl], dtype=np.float64) for x in (inp.q, inp.k, inp.v, inp.dout)]
-        if dk_ != dv_:   # the C oracle has one head dimension: the narrower side gets zero columns (changes no value)
-            dmax = max(dk_, dv_)
-            a = [np.pad(x, ((0, 0), (0, 0), (0, 0), (0, dmax - x.shape[3]))) for x in a]
-        c0 = time.perf_counter()
-        if norm:
-            o, _ = lasp_oracle.fwd_chunked(a[0], a[1], a[2], inp.decay, cfg.chunk)
-            y, rs = lasp_oracle.norm_fwd(o, cfg.norm_eps)
-            lasp_oracle.bwd_chunked(a[0], a[1], a[2], lasp_oracle.norm_bwd(a[3], y, rs), inp.decay, cfg.chunk)
-        elif token:
-            lg = np.ascontiguousarray(inp.log_g[:, :, sl], dtype=np.float64)
-            lasp_oracle.gated_fwd_chunked(a[0], a[1], a[2], lg, cfg.chunk)
-            lasp_oracle.gated_bwd_chunked(a[0], a[1], a[2], a[3], lg, cfg.chunk)
-        else:
-            lasp_oracle.fwd_chunked(a[0], a[1], a[2], inp.decay, cfg.chunk)
-            lasp_oracle.bwd_chunked(a[0], a[1], a[2], a[3], inp.decay, cfg.chunk)
-        c1 = time.perf_counter()
-        cpu = {"value": round(B * n_s / (c1 - c0), 1), "unit": "tokens/s", "cores": lasp_oracle.num_threads(),
+
+        def oracle_pass(n_tok):
+            sl = slice(0, n_tok)
+            a = [np.ascontiguousarray(x[:, :, sl], dtype=np.float64) for x in (inp.q, inp.k, inp.v, inp.dout)]
+            if dk_ != dv_:   # the C oracle has one head dimension: the narrower side gets zero columns (changes no value)
+                dmax = max(dk_, dv_)
+                a = [np.pad(x, ((0, 0), (0, 0), (0, 0), (0, dmax - x.shape[3]))) for x in a]
+            c0 = time.perf_counter()
+            if norm:
+                o, _ = lasp_oracle.fwd_chunked(a[0], a[1], a[2], inp.decay, cfg.chunk)
+                y, rs = lasp_oracle.norm_fwd(o, cfg.norm_eps)
+                lasp_oracle.bwd_chunked(a[0], a[1], a[2], lasp_oracle.norm_bwd(a[3], y, rs), inp.decay, cfg.chunk)
+            elif token:
+                lg = np.ascontiguousarray(inp.log_g[:, :, sl], dtype=np.float64)
+                lasp_oracle.gated_fwd_chunked(a[0], a[1], a[2], lg, cfg.chunk)
+                lasp_oracle.gated_bwd_chunked(a[0], a[1], a[2], a[3], lg, cfg.chunk)
+            else:
+                lasp_oracle.fwd_chunked(a[0], a[1], a[2], inp.decay, cfg.chunk)
+                lasp_oracle.bwd_chunked(a[0], a[1], a[2], a[3], inp.decay, cfg.chunk)
+            return time.perf_counter() - c0
+
+        cores = lasp_oracle.num_threads()
+        secs = oracle_pass(n_s)
+        # the same oracle on one core, on a shorter prefix (its cost is linear in the tokens)
+        n_1 = max(cfg.chunk, min(n_s, 4096) // cfg.chunk * cfg.chunk)
+        lasp_oracle.set_num_threads(1)
+        secs_1 = oracle_pass(n_1)
+        lasp_oracle.set_num_threads(cores)
+        # the definition itself (brute force, quadratic in the tokens) on the small named workload c2, and what
+        # that rate extrapolates to for this workload (cost ~ B H N^2 d): an extrapolation, not a measurement
+        c2 = si.CONFIGS["c2"]
+        i2 = si.make_inputs(c2)
+        b0 = time.perf_counter()
+        lasp_oracle.fwd_brute(i2.q, i2.k, i2.v, i2.decay)
+        lasp_oracle.bwd_brute(i2.q, i2.k, i2.v, i2.dout, i2.decay)
+        secs_b = time.perf_counter() - b0
+        scale = (B * H * N * N * max(dk_, dv_)) / (c2.B * c2.H * c2.N * c2.N * c2.D)
+        cpu = {"value": round(B * n_s / secs, 1), "unit": "tokens/s", "cores": cores,
                "kind": "oracle",
                "sample": f"chunked fp64 oracle (Alg. 2 + Alg. 3), fwd+bwd, first {n_s} of {N} tokens of all "
-                         f"{B * H} heads, {c1 - c0:.1f} s"
-                         + (f"; run at d = {max(dk_, dv_)} with zero columns on the narrower side" if dk_ != dv_ else "")}
+                         f"{B * H} heads, {secs:.1f} s"
+                         + (f"; run at d = {max(dk_, dv_)} with zero columns on the narrower side" if dk_ != dv_ else ""),
+               "one_core": {"value": round(B * n_1 / secs_1, 1), "unit": "tokens/s", "cores": 1,
+                            "sample": f"the same oracle with one thread, first {n_1} tokens of all {B * H} heads, {secs_1:.1f} s"},
+               "brute_force": {"measured_seconds": round(secs_b, 2), "cores": cores,
+                               "sample": f"fp64 brute force (the definition), fwd+bwd, all of c2 (B={c2.B} H={c2.H} N={c2.N} d={c2.D})",
+                               "extrapolated_seconds_this_workload": round(secs_b * scale, 1),
+                               "extrapolation": "measured seconds x (B H N^2 d of this workload / of c2); not a measurement"}}
 
     line = {"metric": "fwd+bwd tokens/sec, chunked causal linear attention with decay (LASP per-device hot path)"
                       + (", decay per token" if token else "") + (", normalised output" if norm else ""),
@@ -225,8 +316,9 @@ def main():
                                    + f" chunk={cfg.chunk} {cfg.dtype}, "
                                    f"T={T} sub-sequence(s), fwd+bwd" + (", decay per token (log_g in, dlog_g out)" if token else "")
                                    + (f", output RMS-normalised per row (eps {cfg.norm_eps})" if norm else ""),
-                       "tile_tokens": tile, "segments_per_head": nseg, "hip_graph": bool(args.graph),
-                       "state_cache_bytes": seq.cache_bytes()},
+                       "tile_tokens": tile, "chunk_selects_tile": False, "segments_per_head": nseg,
+                       "hip_graph": not args.eager, "prewarm_seconds": args.prewarm_seconds,
+                       "state_cache_bytes": seq.cache_bytes(), "peak_device_memory_bytes": int(peak_mem)},
             "roofline": roofline, "whole_step": extra, "copy_reference": copy, "cpu_baseline": cpu}
     print(json.dumps(line), flush=True)
 
@@ -274,30 +366,39 @@ def bench_bidirectional(args, cfg, dev):
         seq.forward(q, k, v, out)
         seq.backward(q, k, v, do, dq, dk, dv)
 
-    for _ in range(args.warmup):
-        step()
-    torch.cuda.synchronize()
-    lasp.profile_begin(args.steps * 3 * T)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step()
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    kernel_ms, nf, nb = lasp.profile_end()
-    ms_per_step = (t1 - t0) * 1e3 / args.steps
-    tokens_per_s = B * N / (ms_per_step * 1e-3)
-    # for information: the same steps as replays of one HIP graph (not `value`)
+    def timed(fn, n):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(n):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e3 / n
+
+    # untimed: graph capture first (it leaves the device idle), then the step itself for `prewarm_seconds`
+    # so that a cold device is at its steady clocks, then the counted warm-up
     from paper_2404_02882_amd.sequence import GraphedStep
+    step()
     graphed = GraphedStep(seq, dict(q=q, k=k, v=v, out=out), dict(q=q, k=k, v=v, dout=do, dq=dq, dk=dk, dv=dv))
+    run = step if args.eager else graphed.replay
+    t_end = time.perf_counter() + max(args.prewarm_seconds, 0.0)
+    while time.perf_counter() < t_end:
+        for _ in range(20):
+            run()
+        torch.cuda.synchronize()
     for _ in range(args.warmup):
-        graphed.replay()
-    torch.cuda.synchronize()
-    g0 = time.perf_counter()
-    for _ in range(args.steps):
-        graphed.replay()
-    torch.cuda.synchronize()
-    graph_ms = (time.perf_counter() - g0) * 1e3 / args.steps
+        run()
+    if args.eager:
+        lasp.profile_begin(args.steps * 3 * T)
+    ms_per_step = timed(run, args.steps)     # the timed region: exactly `steps` steps
+    if args.eager:
+        kernel_ms, nf, nb = lasp.profile_end()
+        eager_ms, graph_ms = ms_per_step, timed(graphed.replay, args.steps)
+    else:       # per-kernel HIP events from an eager pass of the same steps (events are not captured in a graph)
+        lasp.profile_begin(args.steps * 3 * T)
+        eager_ms = timed(step, args.steps)
+        kernel_ms, nf, nb = lasp.profile_end()
+        graph_ms = ms_per_step
+    tokens_per_s = B * N / (ms_per_step * 1e-3)
 
     # forward-kind records: 2T state calls and T output calls per step; backward-kind: T calls per step
     launches = args.steps * T
@@ -314,14 +415,16 @@ def bench_bidirectional(args, cfg, dev):
     achieved = dom_bytes / (per_launch_ms[dominant] * 1e-3) / 1e9
     roofline = {"kernel": dominant, "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
                 "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-                "traffic": MEASURED_TRAFFIC_BYTES.get(args.config, {}).get(dominant) if args.segments == 0 else None,
+                "traffic": traffic_from_profile(args.config, dominant)[0] if args.segments == 0 else None,
+                "traffic_source": traffic_from_profile(args.config, dominant)[1] if args.segments == 0 else None,
                 "algorithmic_bytes_per_launch": dom_bytes,
                 "avg_launch_ms": round(per_launch_ms[dominant], 4),
                 "kernel_ms_per_launch": {n: round(x, 4) for n, x in per_launch_ms.items()}}
     flops_step = 12 * D * D * B * H * N      # two reductions and four products of 2 d^2 each per token-head
     min_bytes_step = 11 * D * esz * B * H * N
     step_s = ms_per_step * 1e-3
-    extra = {"hip_graph_replay_ms_per_step": round(graph_ms, 4),
+    extra = {"timed_as": "eager launches" if args.eager else "hip graph replay",
+             "eager_ms_per_step": round(eager_ms, 4), "hip_graph_replay_ms_per_step": round(graph_ms, 4),
              "algorithmic_tflops": round(flops_step / step_s / 1e12, 2),
              "mfma_bf16_peak_frac": round(flops_step / step_s / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
              "min_hbm_bytes_per_step": min_bytes_step,
@@ -349,7 +452,7 @@ def bench_bidirectional(args, cfg, dev):
             "config": {"workload": f"{cfg.name}: B={B} H={H} N={N} d={D} {cfg.dtype}, T={T} sub-sequence(s), fwd+bwd, "
                                    f"no mask, no decay",
                        "partial_states_per_head": lasp.bidir_scratch_bytes(seq.shapes[0]) // (B * H * D * D * 4),
-                       "hip_graph": False},
+                       "hip_graph": not args.eager, "prewarm_seconds": args.prewarm_seconds},
             "roofline": roofline, "whole_step": extra, "copy_reference": copy, "cpu_baseline": cpu}
     print(json.dumps(line), flush=True)
 

@@ -70,6 +70,12 @@ def num_threads() -> int:
     return int(_load().lasp_oracle_num_threads())
 
 
+def set_num_threads(n: int) -> None:
+    """Threads the OpenMP loops use from now on (for timing the oracle on one core; the arithmetic is untouched)."""
+    _load()
+    ctypes.CDLL("libgomp.so.1").omp_set_num_threads(int(n))
+
+
 def _fwd(name, q, k, v, decay, kv_in, chunk=None):
     lib = _load()
     q, k, v, decay = _d(q), _d(k), _d(v), _d(decay)

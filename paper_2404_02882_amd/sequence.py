@@ -108,11 +108,16 @@ class GraphedStep:
     (lasp_profile_begin) must be off while capturing.
     """
 
-    def __init__(self, seq: LaspSequence, fwd_kwargs: dict, bwd_kwargs: Optional[dict] = None, warmup: int = 2):
+    def __init__(self, seq: LaspSequence, fwd_kwargs: Optional[dict], bwd_kwargs: Optional[dict] = None, warmup: int = 2):
+        """fwd_kwargs None: the graph holds the backward pass alone (the state caches must already hold what a
+        forward pass over the same inputs wrote); bwd_kwargs None: the forward pass alone."""
         self.seq = seq
+        if fwd_kwargs is None and bwd_kwargs is None:
+            raise ValueError("nothing to capture")
 
         def run():
-            seq.forward(**fwd_kwargs)
+            if fwd_kwargs is not None:
+                seq.forward(**fwd_kwargs)
             if bwd_kwargs is not None:
                 seq.backward(**bwd_kwargs)
 

@@ -18,3 +18,33 @@ def test_world_size_above_one_is_refused():
     r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py")], capture_output=True, text=True, timeout=120,
                        env=env)
     assert r.returncode == 2 and "one GPU" in r.stderr
+
+
+def test_flop_conventions():
+    """The three flop counts bench.py reports: the printed algorithm at chunk C (14 C d + 12 d^2 per token-head),
+    the causal minimum (10 of 16 blocks of a 128-token chunk), and what the 64-token kernels issue."""
+    sys.path.insert(0, ROOT)
+    import bench
+    f = bench.flop_counts(1, 16, 32768, 128, 128, 128, 64)
+    th = 16 * 32768
+    assert f["algorithmic"] == th * (14 * 128 * 128 + 12 * 128 * 128)
+    assert f["causal_minimal"] == th * (14 * 128 * 128 * 10 / 16 + 12 * 128 * 128)
+    assert f["causal_minimal"] < f["issued"] < f["algorithmic"]
+    g = bench.flop_counts(2, 8, 4096, 64, 64, 64, 64)     # chunk = tile: 3 of 4 blocks in both counts
+    assert g["causal_minimal"] == 2 * 8 * 4096 * (14 * 64 * 64 * 3 / 4 + 12 * 64 * 64)
+
+
+def test_traffic_is_read_from_the_committed_profiles():
+    """roofline.traffic comes from profiles/<config>_fwd_bwd_kernels.md, not from a constant in bench.py."""
+    sys.path.insert(0, ROOT)
+    import bench
+    got, src = bench.traffic_from_profile("c3", "bwd_walk")
+    assert src == os.path.join("profiles", "c3_fwd_bwd_kernels.md")
+    text = open(os.path.join(ROOT, src)).read()
+    table = text[text.index("## HBM traffic per launch"):]
+    row = [l for l in table.splitlines() if l.startswith("| `lasp::k_bwd")][0].split("|")
+    assert got == int((float(row[3]) + float(row[5])) * 2**20)
+    # the backward walk of c3 moves its algorithmic bytes (1792 B per token-head) plus the state cache and start states
+    assert 1792 * 16 * 32768 < got < 1.3 * 1792 * 16 * 32768
+    assert bench.traffic_from_profile("c3", "fwd_local")[0] != bench.traffic_from_profile("c3", "bwd_local")[0]
+    assert bench.traffic_from_profile("no_such_config", "bwd_walk") == (None, None)
