@@ -97,6 +97,9 @@ def main():
     ap.add_argument("--prewarm-seconds", type=float, default=1.0,
                     help="untimed steps run for this long before the counted warm-up, so that a cold device is at its "
                          "steady clocks when the short timed region starts")
+    ap.add_argument("--recompute", action="store_true",
+                    help="keep no state cache between the passes: every backward call rebuilds the states of its "
+                         "sub-sequence (Sec. 3.4: recomputation instead of caching)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-tokens", type=int, default=32768)
     ap.add_argument("--copy-mib", type=int, default=1024,
@@ -129,7 +132,7 @@ def main():
     dk_, dv_ = D, cfg.Dv or D   # key and value dimensions
     torch.cuda.reset_peak_memory_stats()
     seq = LaspSequence(B, H, N, D, cfg.chunk, dt, T=T, segments=args.segments, device=dev, token_decay=token,
-                       norm_eps=cfg.norm_eps, Dv=cfg.Dv)
+                       norm_eps=cfg.norm_eps, Dv=cfg.Dv, recompute=args.recompute)
     q, k, v, do = (harness.shards(x, T, cfg.dtype, dev) for x in (inp.q, inp.k, inp.v, inp.dout))
     if token:   # a decay per token: log g shards [B,H,N/T] in, dlog_g shards out
         n = N // T
@@ -318,7 +321,9 @@ def main():
                                    + (f", output RMS-normalised per row (eps {cfg.norm_eps})" if norm else ""),
                        "tile_tokens": tile, "chunk_selects_tile": False, "segments_per_head": nseg,
                        "hip_graph": not args.eager, "prewarm_seconds": args.prewarm_seconds,
-                       "state_cache_bytes": seq.cache_bytes(), "peak_device_memory_bytes": int(peak_mem)},
+                       "state_cache": "none (states rebuilt in the backward pass)" if args.recompute else "kept between the passes",
+                       "state_cache_bytes": seq.cache_bytes(), "workspace_bytes": int(seq.scratch.numel()),
+                       "peak_device_memory_bytes": int(peak_mem)},
             "roofline": roofline, "whole_step": extra, "copy_reference": copy, "cpu_baseline": cpu}
     print(json.dumps(line), flush=True)
 

@@ -177,14 +177,31 @@ size_t lasp_noalloc_scratch_limit(void);
  * parts from the cached KV_{t-1} and the carried dKV).
  *
  *   dkv_out      NULL = zeros (last sub-sequence, Alg. 3 "dKV = 0").
- *   state_cache  required: the buffer the matching lasp_fwd call filled (same
- *                shape, same inputs, same kv_in).
+ *   state_cache  the buffer the matching lasp_fwd call filled (same shape, same
+ *                inputs, same kv_in), or NULL = recompute: the paper's alternative
+ *                to caching (Sec. 3.4, "KV state caching" on / off). The call then
+ *                rebuilds the states first, from k, v and kv_in, with the forward
+ *                kernels reduced to their states (Alg. 2 without the outputs),
+ *                into the tail of `scratch`, which must then hold at least
+ *                lasp_bwd_recompute_scratch_bytes(). Nothing has to be kept between
+ *                the forward and the backward pass but kv_in; the price is one more
+ *                pass over k, v.
+ *   kv_in        the state the sub-sequence started from (what lasp_fwd was given;
+ *                NULL = zeros). Read only when state_cache is NULL: the cache's first
+ *                slot already holds it.
  *   dq, dk, dv, dkv_in  required.
  */
 int lasp_bwd(const lasp_shape *shape, const void *q, const void *k, const void *v,
-             const void *dout, const float *dkv_out, const float *decay,
+             const void *dout, const float *kv_in, const float *dkv_out, const float *decay,
              const void *state_cache, void *dq, void *dk, void *dv, float *dkv_in,
              void *scratch, size_t scratch_bytes, void *hip_stream);
+
+/*
+ * Bytes of scratch lasp_bwd (and lasp_bwd_norm) needs when it is given no state
+ * cache: lasp_scratch_bytes() rounded up to 256, plus lasp_state_cache_bytes().
+ * 0 on an invalid shape.
+ */
+size_t lasp_bwd_recompute_scratch_bytes(const lasp_shape *shape);
 
 /*
  * ---- Per-token decay -------------------------------------------------------
@@ -207,6 +224,8 @@ int lasp_bwd(const lasp_shape *shape, const void *q, const void *k, const void *
  *               dlog_g_s = <dkv_out, kv_out> + sum_{t>=s} (q_t . dq_t - k_t . dk_t).
  *   kv_out  (backward) the state the matching lasp_gated_fwd returned; required
  *           when dkv_out is given, ignored otherwise.
+ *   kv_in   (backward) as for lasp_bwd: read only when state_cache is NULL
+ *           (recompute; scratch of lasp_gated_bwd_recompute_scratch_bytes()).
  * Everything else (layouts, states, state_cache, scratch, stream, status codes,
  * aliasing rules) is as for lasp_fwd / lasp_bwd, with the sizes from the
  * lasp_gated_* size functions.
@@ -214,11 +233,12 @@ int lasp_bwd(const lasp_shape *shape, const void *q, const void *k, const void *
 int lasp_check_log_decay(const float *log_g_host, int64_t n);
 size_t lasp_gated_state_cache_bytes(const lasp_shape *shape);
 size_t lasp_gated_scratch_bytes(const lasp_shape *shape);
+size_t lasp_gated_bwd_recompute_scratch_bytes(const lasp_shape *shape);
 int lasp_gated_fwd(const lasp_shape *shape, const void *q, const void *k, const void *v,
                    const float *log_g, const float *kv_in, void *out, float *kv_out,
                    void *state_cache, void *scratch, size_t scratch_bytes, void *hip_stream);
 int lasp_gated_bwd(const lasp_shape *shape, const void *q, const void *k, const void *v,
-                   const void *dout, const float *log_g, const float *kv_out,
+                   const void *dout, const float *log_g, const float *kv_in, const float *kv_out,
                    const float *dkv_out, const void *state_cache, void *dq, void *dk, void *dv,
                    float *dlog_g, float *dkv_in, void *scratch, size_t scratch_bytes,
                    void *hip_stream);
@@ -240,15 +260,17 @@ int lasp_gated_bwd(const lasp_shape *shape, const void *q, const void *k, const 
  *           the same buffer, as input.
  *   rstd    DEVICE float [B][H][N]: written by lasp_fwd_norm, read by lasp_bwd_norm.
  *   dout    backward: gradient w.r.t. the normalised output y.
+ *   kv_in, state_cache (backward): as for lasp_bwd, NULL cache = recompute.
  */
 int lasp_fwd_norm(const lasp_shape *shape, const void *q, const void *k, const void *v,
                   const float *kv_in, const float *decay, float eps, void *out, float *rstd,
                   float *kv_out, void *state_cache, void *scratch, size_t scratch_bytes,
                   void *hip_stream);
 int lasp_bwd_norm(const lasp_shape *shape, const void *q, const void *k, const void *v,
-                  const void *out, const float *rstd, const void *dout, const float *dkv_out,
-                  const float *decay, const void *state_cache, void *dq, void *dk, void *dv,
-                  float *dkv_in, void *scratch, size_t scratch_bytes, void *hip_stream);
+                  const void *out, const float *rstd, const void *dout, const float *kv_in,
+                  const float *dkv_out, const float *decay, const void *state_cache, void *dq,
+                  void *dk, void *dv, float *dkv_in, void *scratch, size_t scratch_bytes,
+                  void *hip_stream);
 
 /*
  * Per-token decay and normalised output together: arguments as in
@@ -262,9 +284,9 @@ int lasp_gated_fwd_norm(const lasp_shape *shape, const void *q, const void *k, c
                         void *hip_stream);
 int lasp_gated_bwd_norm(const lasp_shape *shape, const void *q, const void *k, const void *v,
                         const void *out, const float *rstd, const void *dout, const float *log_g,
-                        const float *kv_out, const float *dkv_out, const void *state_cache,
-                        void *dq, void *dk, void *dv, float *dlog_g, float *dkv_in, void *scratch,
-                        size_t scratch_bytes, void *hip_stream);
+                        const float *kv_in, const float *kv_out, const float *dkv_out,
+                        const void *state_cache, void *dq, void *dk, void *dv, float *dlog_g,
+                        float *dkv_in, void *scratch, size_t scratch_bytes, void *hip_stream);
 
 /*
  * ---- Bidirectional (unmasked) attention ---------------------------------------

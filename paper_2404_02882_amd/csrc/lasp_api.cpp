@@ -183,7 +183,7 @@ int run_fwd_call(const FwdCall &c) {
     hipStream_t stream = (hipStream_t)c.stream;
     char *scr = (char *)c.scratch;
     lasp::FwdArgs a{c.q, c.k, c.v, c.kv_in, c.decay, c.out, c.kv_out, c.cache, (float *)scr,
-                    p.token ? (float *)(scr + l.seglog) : nullptr, c.rstd, c.eps};
+                    p.token ? (float *)(scr + l.seglog) : nullptr, c.rstd, c.eps, false};
     if (p.synth) {
         float *lg = (float *)(scr + l.logg);
         if (lasp::launch_fill_logg(p, c.decay, lg, stream) != hipSuccess) return LASP_ERR_HIP;
@@ -196,6 +196,7 @@ int run_fwd_call(const FwdCall &c) {
 struct BwdCall {
     const lasp_shape *shape;
     const void *q, *k, *v, *dout;
+    const float *kv_in;     // used only when cache is NULL (the states are then rebuilt from it); NULL = zeros
     const float *dkv_out, *decay;
     bool token, norm;
     const void *yn;
@@ -208,39 +209,59 @@ struct BwdCall {
     void *stream;
 };
 
+// Without a state cache the backward pass rebuilds the states first (Sec. 3.4: recomputation instead of
+// caching): the forward pass reduced to its states writes them into the tail of the scratch buffer.
+size_t recompute_scratch(const lasp_shape *shape, bool token) {
+    ScratchLayout l;
+    if (!scratch_layout(shape, token, &l)) return 0;
+    return round256(l.total) + cache_bytes(shape, token);
+}
+
 int run_bwd_call(const BwdCall &c) {
     lasp::Plan p;
     int rc = make_plan(c.shape, kBackward, &p, c.token, c.norm);
     if (rc != LASP_OK) return rc;
-    if (!c.q || !c.k || !c.v || !c.dout || !c.decay || !c.cache || !c.dq || !c.dk || !c.dv || !c.dkv_in)
+    if (!c.q || !c.k || !c.v || !c.dout || !c.decay || !c.dq || !c.dk || !c.dv || !c.dkv_in)
         return LASP_ERR_NULL;
     if (c.norm && (!c.yn || !c.rstd)) return LASP_ERR_NULL;
     if (c.token && (!c.dlog_g || (c.dkv_out && !c.kv_out))) return LASP_ERR_NULL;
     ScratchLayout l;
     scratch_layout(c.shape, c.token, &l);
-    if (!c.scratch || c.scratch_bytes < l.total) return LASP_ERR_WORKSPACE;
+    const bool rebuild = c.cache == nullptr;
+    const size_t cb = cache_bytes(c.shape, c.token);
+    const size_t need = rebuild ? round256(l.total) + cb : l.total;
+    if (!c.scratch || c.scratch_bytes < need) return LASP_ERR_WORKSPACE;
+    char *scr = (char *)c.scratch;
+    const void *cache = rebuild ? scr + round256(l.total) : c.cache;
 
     const size_t esz = elem_bytes(p.dtype);
     const size_t qb = (size_t)p.B * p.H * p.N * p.dk * esz, ob = (size_t)p.B * p.H * p.N * p.dv * esz;   // q / out
     const size_t sb = (size_t)p.B * p.H * p.dk * p.dv * sizeof(float);
     const size_t gb = (size_t)p.B * p.H * p.N * sizeof(float);
     rc = check_buffers({{c.q, qb}, {c.k, qb / p.kvdiv}, {c.v, ob / p.kvdiv}, {c.dout, ob}, {c.dkv_out, sb}, {c.kv_out, sb},
-                        {c.yn, ob}, {c.rstd, gb}, {c.decay, c.token ? gb : p.H * sizeof(float)},
-                        {c.cache, cache_bytes(c.shape, c.token)}},
+                        {rebuild ? c.kv_in : nullptr, sb}, {c.yn, ob}, {c.rstd, gb}, {c.decay, c.token ? gb : p.H * sizeof(float)},
+                        {c.cache, cb}},
                        {{c.dq, qb}, {c.dk, qb / p.kvdiv}, {c.dv, ob / p.kvdiv}, {c.dlog_g, gb}, {c.dkv_in, sb},
-                        {c.scratch, l.total}});
+                        {c.scratch, need}});
     if (rc != LASP_OK) return rc;
 
     hipStream_t stream = (hipStream_t)c.stream;
-    char *scr = (char *)c.scratch;
-    lasp::BwdArgs a{c.q, c.k, c.v, c.dout, c.dkv_out, c.decay, c.cache, c.dq, c.dk, c.dv, c.dkv_in, (float *)scr,
-                    c.kv_out, c.dlog_g, p.token ? (float *)(scr + l.seglog) : nullptr,
-                    p.token ? (float *)(scr + l.rtok) : nullptr, c.yn, c.rstd, nullptr, nullptr};
+    const float *decay = c.decay;
     if (p.synth) {
         float *lg = (float *)(scr + l.logg);
         if (lasp::launch_fill_logg(p, c.decay, lg, stream) != hipSuccess) return LASP_ERR_HIP;
-        a.decay = lg;
+        decay = lg;
     }
+    if (rebuild) {   // the forward pass's own plan (its segment count), states only, into the scratch tail
+        lasp::Plan f;
+        if (rc = make_plan(c.shape, kForward, &f, c.token, false); rc != LASP_OK) return rc;
+        const lasp::FwdArgs fa{nullptr, c.k, c.v, c.kv_in, decay, nullptr, nullptr, (void *)cache, (float *)scr,
+                               f.token ? (float *)(scr + l.seglog) : nullptr, nullptr, 0.0f, true};
+        if (lasp::launch_fwd(f, fa, stream, nullptr) != hipSuccess) return LASP_ERR_HIP;
+    }
+    lasp::BwdArgs a{c.q, c.k, c.v, c.dout, c.dkv_out, decay, cache, c.dq, c.dk, c.dv, c.dkv_in, (float *)scr,
+                    c.kv_out, c.dlog_g, p.token ? (float *)(scr + l.seglog) : nullptr,
+                    p.token ? (float *)(scr + l.rtok) : nullptr, c.yn, c.rstd, nullptr, nullptr};
     if (p.kvdiv > 1) {   // the kernels write dK, dV per query head; launch_bwd sums each group into the outputs
         a.dk_out = c.dk;
         a.dv_out = c.dv;
@@ -300,7 +321,7 @@ hipError_t allow_dynamic_lds(const void *kernel, size_t bytes) {
 
 extern "C" {
 
-int lasp_version(void) { return 5; }
+int lasp_version(void) { return 6; }
 
 const char *lasp_status_str(int status) {
     switch (status) {
@@ -389,10 +410,13 @@ int lasp_fwd_noalloc(const lasp_shape *shape, const void *q, const void *k, cons
 
 size_t lasp_noalloc_scratch_limit(void) { return lasp::kStaticScratchBytes; }
 
+size_t lasp_bwd_recompute_scratch_bytes(const lasp_shape *shape) { return recompute_scratch(shape, false); }
+size_t lasp_gated_bwd_recompute_scratch_bytes(const lasp_shape *shape) { return recompute_scratch(shape, true); }
+
 int lasp_bwd(const lasp_shape *shape, const void *q, const void *k, const void *v, const void *dout,
-             const float *dkv_out, const float *decay, const void *state_cache, void *dq, void *dk,
+             const float *kv_in, const float *dkv_out, const float *decay, const void *state_cache, void *dq, void *dk,
              void *dv, float *dkv_in, void *scratch, size_t scratch_bytes, void *hip_stream) {
-    BwdCall c{shape, q, k, v, dout, dkv_out, decay, false, false, nullptr, nullptr, nullptr, state_cache, dq, dk, dv,
+    BwdCall c{shape, q, k, v, dout, kv_in, dkv_out, decay, false, false, nullptr, nullptr, nullptr, state_cache, dq, dk, dv,
               nullptr, dkv_in, scratch, scratch_bytes, hip_stream};
     return run_bwd_call(c);
 }
@@ -406,10 +430,10 @@ int lasp_gated_fwd(const lasp_shape *shape, const void *q, const void *k, const 
 }
 
 int lasp_gated_bwd(const lasp_shape *shape, const void *q, const void *k, const void *v, const void *dout,
-                   const float *log_g, const float *kv_out, const float *dkv_out, const void *state_cache,
-                   void *dq, void *dk, void *dv, float *dlog_g, float *dkv_in, void *scratch,
+                   const float *log_g, const float *kv_in, const float *kv_out, const float *dkv_out,
+                   const void *state_cache, void *dq, void *dk, void *dv, float *dlog_g, float *dkv_in, void *scratch,
                    size_t scratch_bytes, void *hip_stream) {
-    BwdCall c{shape, q, k, v, dout, dkv_out, log_g, true, false, nullptr, nullptr, kv_out, state_cache, dq, dk, dv,
+    BwdCall c{shape, q, k, v, dout, kv_in, dkv_out, log_g, true, false, nullptr, nullptr, kv_out, state_cache, dq, dk, dv,
               dlog_g, dkv_in, scratch, scratch_bytes, hip_stream};
     return run_bwd_call(c);
 }
@@ -423,10 +447,10 @@ int lasp_fwd_norm(const lasp_shape *shape, const void *q, const void *k, const v
 }
 
 int lasp_bwd_norm(const lasp_shape *shape, const void *q, const void *k, const void *v, const void *out,
-                  const float *rstd, const void *dout, const float *dkv_out, const float *decay,
+                  const float *rstd, const void *dout, const float *kv_in, const float *dkv_out, const float *decay,
                   const void *state_cache, void *dq, void *dk, void *dv, float *dkv_in, void *scratch,
                   size_t scratch_bytes, void *hip_stream) {
-    BwdCall c{shape, q, k, v, dout, dkv_out, decay, false, true, out, rstd, nullptr, state_cache, dq, dk, dv,
+    BwdCall c{shape, q, k, v, dout, kv_in, dkv_out, decay, false, true, out, rstd, nullptr, state_cache, dq, dk, dv,
               nullptr, dkv_in, scratch, scratch_bytes, hip_stream};
     return run_bwd_call(c);
 }
@@ -440,10 +464,10 @@ int lasp_gated_fwd_norm(const lasp_shape *shape, const void *q, const void *k, c
 }
 
 int lasp_gated_bwd_norm(const lasp_shape *shape, const void *q, const void *k, const void *v, const void *out,
-                        const float *rstd, const void *dout, const float *log_g, const float *kv_out,
+                        const float *rstd, const void *dout, const float *log_g, const float *kv_in, const float *kv_out,
                         const float *dkv_out, const void *state_cache, void *dq, void *dk, void *dv,
                         float *dlog_g, float *dkv_in, void *scratch, size_t scratch_bytes, void *hip_stream) {
-    BwdCall c{shape, q, k, v, dout, dkv_out, log_g, true, true, out, rstd, kv_out, state_cache, dq, dk, dv,
+    BwdCall c{shape, q, k, v, dout, kv_in, dkv_out, log_g, true, true, out, rstd, kv_out, state_cache, dq, dk, dv,
               dlog_g, dkv_in, scratch, scratch_bytes, hip_stream};
     return run_bwd_call(c);
 }

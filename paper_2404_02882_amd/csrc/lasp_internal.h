@@ -36,6 +36,7 @@ struct FwdArgs {
     float *seglog;        // per-token decay only: [B*H][nseg], log2 of the decay over each segment
     float *rstd_out;      // norm only: [B][H][N]
     float eps;            // norm only
+    bool states_only;     // rebuild the state cache only: q, out, rstd_out are not touched (kv_out still is)
 };
 
 struct BwdArgs {

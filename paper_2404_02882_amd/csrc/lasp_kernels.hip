@@ -296,7 +296,10 @@ __global__ __launch_bounds__(256) void k_scan(float *__restrict__ scratch, const
 // NORM: every output row is divided by its root mean square (plus eps under the root) before it is
 // stored, and the factor is written to rstd_out ([chain][token]) for the backward pass.
 // WK, WV: elements per row of Q, K and of V, O in memory (<= D; see k_local).
-template <typename T, int CT, int D, bool TOKEN, bool NORM = false, int WK = D, int WV = D>
+// STATES: only the states are wanted (a backward pass that was given no state cache rebuilds it, Sec. 3.4's
+// recomputation instead of caching): Q is not read, no scores and no outputs are computed; K, V are
+// walked, every tile's entering state goes to the cache and the state is updated.
+template <typename T, int CT, int D, bool TOKEN, bool NORM = false, int WK = D, int WV = D, bool STATES = false>
 __global__ __launch_bounds__(D * 2, (CT <= 64 && sizeof(T) == 2) ? 2 : 1) void k_fwd(const T *__restrict__ Q, const T *__restrict__ K,
                                                 const T *__restrict__ V, const float *__restrict__ decay,
                                                 T *__restrict__ O, float *__restrict__ kv_out,
@@ -325,8 +328,9 @@ __global__ __launch_bounds__(D * 2, (CT <= 64 && sizeof(T) == 2) ? 2 : 1) void k
     auto voff = [&](int t) { return tile_off(chain, ntok, t, CT, WV); };
     // rows of tile `t` that exist: the last tile of a sub-sequence may be short (per-token decay only)
     auto nvalid = [&](int t) { return TOKEN ? min(CT, ntok - t * CT) : CT; };
+    static_assert(!STATES || !NORM, "the states do not depend on the Norm");
     TileMover<T, CT, D, NT> mq, mk, mv;
-    mq.template load_w<WK>(Q + koff(t0), nvalid(t0));
+    if constexpr (!STATES) mq.template load_w<WK>(Q + koff(t0), nvalid(t0));
     mk.template load_w<WK>(K + koff(t0), nvalid(t0));
     mv.template load_w<WV>(V + voff(t0), nvalid(t0));
     f32x16 st[DB];
@@ -342,17 +346,18 @@ __global__ __launch_bounds__(D * 2, (CT <= 64 && sizeof(T) == 2) ? 2 : 1) void k
         // The state this tile starts from goes to the cache as KV_{t-1}, rows a, columns c.
         if (cache && t % cache_stride == 0)
             cache_store<T, CT, D>(ln, cache + ((size_t)chain * (ntiles / cache_stride) + t / cache_stride) * D * D, st, sP, w);
-        mq.store(sQ, LDD);
+        if constexpr (!STATES) mq.store(sQ, LDD);
         mk.store(sK, LDD);
         mv.store(sV, LDD);
         if constexpr (TOKEN) dec.fill(lgreg);
         __syncthreads();
         if (t + 1 < t1) {
-            mq.template load_w<WK>(Q + koff(t + 1), nvalid(t + 1));
+            if constexpr (!STATES) mq.template load_w<WK>(Q + koff(t + 1), nvalid(t + 1));
             mk.template load_w<WK>(K + koff(t + 1), nvalid(t + 1));
             mv.template load_w<WV>(V + voff(t + 1), nvalid(t + 1));
             if constexpr (TOKEN) lgreg = TokenDecay<T, CT>::fetch(lg + (size_t)(t + 1) * CT, nvalid(t + 1));
         }
+        if constexpr (!STATES) {
         // masked scores P (all waves share the lower-triangular blocks)
         masked_scores<T, CT, D, LDD, LDP>(ln, sP, sK, sQ, dec, w);
 
@@ -408,6 +413,7 @@ __global__ __launch_bounds__(D * 2, (CT <= 64 && sizeof(T) == 2) ? 2 : 1) void k
         T *o = O + voff(t);
 #pragma unroll
         for (int ib = 0; ib < NB; ++ib) store_out_tile_t<T, D, WV>(ln, o, acc[ib], 32 * ib, w, nvalid(t));
+        }   // !STATES
 
         ln = fresh_lane();
         // state update: KV <- lambda^CT KV + (diag{lambda^(CT-1-j)} K)^T V, weight applied to the V fragments
@@ -421,7 +427,7 @@ __global__ __launch_bounds__(D * 2, (CT <= 64 && sizeof(T) == 2) ? 2 : 1) void k
             for (int ab = 0; ab < DB; ++ab) st[ab] = E::mfma(E::ld_ks(ln, sK, LDD, ks * E::KSTEP, 32 * ab), vd, st[ab]);
         }
     }
-    if (seg == nseg - 1) state_store_w<D, WK, WV>(ln, st, kv_out + (size_t)chain * WK * WV, w);
+    if (seg == nseg - 1 && kv_out) state_store_w<D, WK, WV>(ln, st, kv_out + (size_t)chain * WK * WV, w);
 }
 
 // ---------------------------------------------------------------------------
@@ -1447,6 +1453,11 @@ struct FwdFam {
     static constexpr auto fn = k_fwd<T, CT, D, TK, NM, WK, WV>;
 };
 template <typename T, int CT, int D, int WK, int WV>
+struct StatesFam {  // the forward walk reduced to the states (no Norm: the states do not depend on it)
+    template <bool TK, bool NM>
+    static constexpr auto fn = k_fwd<T, CT, D, TK, false, WK, WV, true>;
+};
+template <typename T, int CT, int D, int WK, int WV>
 struct BwdFam {     // four waves, one cached state per tile
     template <bool TK, bool NM>
     static constexpr auto fn = k_bwd<T, CT, D, TK, NM, WK, WV>;
@@ -1500,7 +1511,8 @@ static hipError_t run_fwd(const Plan &p, const FwdArgs &a, hipStream_t s, const 
         k_scan<false, false><<<scan_grid, dim3(256), 0, s>>>(a.scratch, a.kv_in, a.decay, nullptr, p.H, DD, p.nseg,
                                                             p.tiles_per_seg, p.ntiles, p.tile, D, p.dk, p.dv);
     if (ke) (void)hipEventRecord(ke->ev[2], s);
-    if (e = launch_kernel(by_model<FwdFam<T, CT, D, WK, WV>>(p), dim3(p.nseg, chains), dim3(D * 2), Smem<T, CT, D>::fwd, s,
+    const auto walk = a.states_only ? by_model<StatesFam<T, CT, D, WK, WV>>(p) : by_model<FwdFam<T, CT, D, WK, WV>>(p);
+    if (e = launch_kernel(walk, dim3(p.nseg, chains), dim3(D * 2), Smem<T, CT, D>::fwd, s,
                           (const T *)a.q, (const T *)a.k, (const T *)a.v, a.decay, (T *)a.out, a.kv_out, (T *)a.cache,
                           (const float *)a.scratch, p.H, p.ntiles, p.nseg, p.tiles_per_seg, p.cache_stride, p.N, p.kvdiv,
                           a.rstd_out, a.eps);

@@ -42,10 +42,10 @@ def rel_errors(x: np.ndarray, ref: np.ndarray):
 
 
 def run_gpu(inp: Inputs, T: int = 1, segments: int = 0, backward: bool = True, chunk: Optional[int] = None,
-            device="cuda", norm_eps: Optional[float] = None) -> Dict[str, np.ndarray]:
+            device="cuda", norm_eps: Optional[float] = None, recompute: bool = False) -> Dict[str, np.ndarray]:
     """Forward (and backward) of the whole sequence as T sub-sequences; returns float64 host arrays.
     With norm_eps the output is the normalised one, `rstd` is returned too and inp.dout is the gradient
-    w.r.t. the normalised output."""
+    w.r.t. the normalised output. `recompute`: no state cache; the backward calls rebuild the states."""
     cfg = inp.cfg
     B, H, N, D = inp.q.shape
     kv_heads = inp.k.shape[1] if inp.k.shape[1] != H else 0   # grouped K/V heads: k, v are [B,kv_heads,N,D]
@@ -53,7 +53,8 @@ def run_gpu(inp: Inputs, T: int = 1, segments: int = 0, backward: bool = True, c
     dt = TORCH_DTYPE[cfg.dtype]
     token = inp.log_g is not None
     seq = LaspSequence(B, H, N, D, chunk or cfg.chunk, dt, T=T, segments=segments, device=device,
-                       need_backward=backward, token_decay=token, norm_eps=norm_eps, kv_heads=kv_heads, Dv=Dv)
+                       need_backward=backward, token_decay=token, norm_eps=norm_eps, kv_heads=kv_heads, Dv=Dv,
+                       recompute=recompute)
     q, k, v = (shards(x, T, cfg.dtype, device) for x in (inp.q, inp.k, inp.v))
     if token:
         n = N // T

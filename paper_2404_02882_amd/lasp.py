@@ -61,7 +61,11 @@ def _bind(handle):
     handle.lasp_fwd_noalloc.restype = ctypes.c_int
     handle.lasp_noalloc_scratch_limit.argtypes = []
     handle.lasp_noalloc_scratch_limit.restype = _sz
-    handle.lasp_bwd.argtypes = [_sp] + [_vp] * 12 + [_sz, _vp]
+    handle.lasp_bwd.argtypes = [_sp] + [_vp] * 13 + [_sz, _vp]
+    handle.lasp_bwd_recompute_scratch_bytes.argtypes = [_sp]
+    handle.lasp_bwd_recompute_scratch_bytes.restype = _sz
+    handle.lasp_gated_bwd_recompute_scratch_bytes.argtypes = [_sp]
+    handle.lasp_gated_bwd_recompute_scratch_bytes.restype = _sz
     handle.lasp_bwd.restype = ctypes.c_int
     handle.lasp_check_log_decay.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_int64]
     handle.lasp_gated_state_cache_bytes.argtypes = [_sp]
@@ -70,15 +74,15 @@ def _bind(handle):
     handle.lasp_gated_scratch_bytes.restype = _sz
     handle.lasp_gated_fwd.argtypes = [_sp] + [_vp] * 9 + [_sz, _vp]
     handle.lasp_gated_fwd.restype = ctypes.c_int
-    handle.lasp_gated_bwd.argtypes = [_sp] + [_vp] * 14 + [_sz, _vp]
+    handle.lasp_gated_bwd.argtypes = [_sp] + [_vp] * 15 + [_sz, _vp]
     handle.lasp_gated_bwd.restype = ctypes.c_int
     handle.lasp_fwd_norm.argtypes = [_sp] + [_vp] * 5 + [ctypes.c_float] + [_vp] * 5 + [_sz, _vp]
     handle.lasp_fwd_norm.restype = ctypes.c_int
-    handle.lasp_bwd_norm.argtypes = [_sp] + [_vp] * 14 + [_sz, _vp]
+    handle.lasp_bwd_norm.argtypes = [_sp] + [_vp] * 15 + [_sz, _vp]
     handle.lasp_bwd_norm.restype = ctypes.c_int
     handle.lasp_gated_fwd_norm.argtypes = [_sp] + [_vp] * 5 + [ctypes.c_float] + [_vp] * 5 + [_sz, _vp]
     handle.lasp_gated_fwd_norm.restype = ctypes.c_int
-    handle.lasp_gated_bwd_norm.argtypes = [_sp] + [_vp] * 16 + [_sz, _vp]
+    handle.lasp_gated_bwd_norm.argtypes = [_sp] + [_vp] * 17 + [_sz, _vp]
     handle.lasp_gated_bwd_norm.restype = ctypes.c_int
     handle.lasp_bidir_scratch_bytes.argtypes = [_sp]
     handle.lasp_bidir_scratch_bytes.restype = _sz
@@ -189,11 +193,20 @@ def lasp_fwd_noalloc(shape: Shape, q, k, v, kv_in, decay, out, kv_out, state_cac
         raise LaspError(rc, "lasp_fwd_noalloc")
 
 
-def lasp_bwd(shape: Shape, q, k, v, dout, dkv_out, decay, state_cache, dq, dk, dv, dkv_in, scratch,
+def bwd_recompute_scratch_bytes(shape: Shape) -> int:
+    return int(lib.lasp_bwd_recompute_scratch_bytes(ctypes.byref(shape)))
+
+
+def gated_bwd_recompute_scratch_bytes(shape: Shape) -> int:
+    return int(lib.lasp_gated_bwd_recompute_scratch_bytes(ctypes.byref(shape)))
+
+
+def lasp_bwd(shape: Shape, q, k, v, dout, kv_in, dkv_out, decay, state_cache, dq, dk, dv, dkv_in, scratch,
              stream=None) -> None:
-    """Enqueue the backward pass; raises LaspError on a non-zero status."""
+    """Enqueue the backward pass (state_cache None = the states are rebuilt from k, v, kv_in); raises LaspError
+    on a non-zero status."""
     nbytes = scratch.numel() * scratch.element_size() if scratch is not None else 0
-    rc = lib.lasp_bwd(ctypes.byref(shape), _ptr(q), _ptr(k), _ptr(v), _ptr(dout), _ptr(dkv_out), _ptr(decay),
+    rc = lib.lasp_bwd(ctypes.byref(shape), _ptr(q), _ptr(k), _ptr(v), _ptr(dout), _ptr(kv_in), _ptr(dkv_out), _ptr(decay),
                       _ptr(state_cache), _ptr(dq), _ptr(dk), _ptr(dv), _ptr(dkv_in), _ptr(scratch), nbytes,
                       _stream(stream))
     if rc != 0:
@@ -223,11 +236,11 @@ def lasp_gated_fwd(shape: Shape, q, k, v, log_g, kv_in, out, kv_out, state_cache
         raise LaspError(rc, "lasp_gated_fwd")
 
 
-def lasp_gated_bwd(shape: Shape, q, k, v, dout, log_g, kv_out, dkv_out, state_cache, dq, dk, dv, dlog_g, dkv_in,
+def lasp_gated_bwd(shape: Shape, q, k, v, dout, log_g, kv_in, kv_out, dkv_out, state_cache, dq, dk, dv, dlog_g, dkv_in,
                    scratch, stream=None) -> None:
     """Backward with a decay per token; raises LaspError on a non-zero status."""
     nbytes = scratch.numel() * scratch.element_size() if scratch is not None else 0
-    rc = lib.lasp_gated_bwd(ctypes.byref(shape), _ptr(q), _ptr(k), _ptr(v), _ptr(dout), _ptr(log_g), _ptr(kv_out),
+    rc = lib.lasp_gated_bwd(ctypes.byref(shape), _ptr(q), _ptr(k), _ptr(v), _ptr(dout), _ptr(log_g), _ptr(kv_in), _ptr(kv_out),
                             _ptr(dkv_out), _ptr(state_cache), _ptr(dq), _ptr(dk), _ptr(dv), _ptr(dlog_g),
                             _ptr(dkv_in), _ptr(scratch), nbytes, _stream(stream))
     if rc != 0:
@@ -245,12 +258,12 @@ def lasp_fwd_norm(shape: Shape, q, k, v, kv_in, decay, eps, out, rstd, kv_out, s
         raise LaspError(rc, "lasp_fwd_norm")
 
 
-def lasp_bwd_norm(shape: Shape, q, k, v, out, rstd, dout, dkv_out, decay, state_cache, dq, dk, dv, dkv_in,
+def lasp_bwd_norm(shape: Shape, q, k, v, out, rstd, dout, kv_in, dkv_out, decay, state_cache, dq, dk, dv, dkv_in,
                   scratch, stream=None) -> None:
     """Backward of lasp_fwd_norm (dout: gradient w.r.t. the normalised output); raises LaspError."""
     nbytes = scratch.numel() * scratch.element_size() if scratch is not None else 0
     rc = lib.lasp_bwd_norm(ctypes.byref(shape), _ptr(q), _ptr(k), _ptr(v), _ptr(out), _ptr(rstd), _ptr(dout),
-                           _ptr(dkv_out), _ptr(decay), _ptr(state_cache), _ptr(dq), _ptr(dk), _ptr(dv),
+                           _ptr(kv_in), _ptr(dkv_out), _ptr(decay), _ptr(state_cache), _ptr(dq), _ptr(dk), _ptr(dv),
                            _ptr(dkv_in), _ptr(scratch), nbytes, _stream(stream))
     if rc != 0:
         raise LaspError(rc, "lasp_bwd_norm")
@@ -267,12 +280,12 @@ def lasp_gated_fwd_norm(shape: Shape, q, k, v, log_g, kv_in, eps, out, rstd, kv_
         raise LaspError(rc, "lasp_gated_fwd_norm")
 
 
-def lasp_gated_bwd_norm(shape: Shape, q, k, v, out, rstd, dout, log_g, kv_out, dkv_out, state_cache, dq, dk, dv,
+def lasp_gated_bwd_norm(shape: Shape, q, k, v, out, rstd, dout, log_g, kv_in, kv_out, dkv_out, state_cache, dq, dk, dv,
                         dlog_g, dkv_in, scratch, stream=None) -> None:
     """Backward of lasp_gated_fwd_norm; raises LaspError on a non-zero status."""
     nbytes = scratch.numel() * scratch.element_size() if scratch is not None else 0
     rc = lib.lasp_gated_bwd_norm(ctypes.byref(shape), _ptr(q), _ptr(k), _ptr(v), _ptr(out), _ptr(rstd), _ptr(dout),
-                                 _ptr(log_g), _ptr(kv_out), _ptr(dkv_out), _ptr(state_cache), _ptr(dq), _ptr(dk),
+                                 _ptr(log_g), _ptr(kv_in), _ptr(kv_out), _ptr(dkv_out), _ptr(state_cache), _ptr(dq), _ptr(dk),
                                  _ptr(dv), _ptr(dlog_g), _ptr(dkv_in), _ptr(scratch), nbytes, _stream(stream))
     if rc != 0:
         raise LaspError(rc, "lasp_gated_bwd_norm")

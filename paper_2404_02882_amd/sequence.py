@@ -19,7 +19,7 @@ from . import lasp
 
 class LaspSequence:
     def __init__(self, B, H, N, D, chunk, dtype: torch.dtype, T=1, segments=0, device="cuda", need_backward=True,
-                 token_decay=False, norm_eps: Optional[float] = None, kv_heads=0, Dv=0):
+                 token_decay=False, norm_eps: Optional[float] = None, kv_heads=0, Dv=0, recompute=False):
         if N % T != 0:
             raise ValueError("N must be a multiple of T")
         self.B, self.H, self.N, self.D, self.T = B, H, N, D, T
@@ -38,11 +38,18 @@ class LaspSequence:
         # [B,H,N/T], backward takes them and the forward outputs. Both may be set together.
         self.norm_eps = norm_eps
         self.token_decay = token_decay
-        scratch_bytes = lasp.gated_scratch_bytes if token_decay else lasp.scratch_bytes
+        # recompute: no state cache is kept between the passes (Sec. 3.4's alternative to caching); every
+        # backward call rebuilds the states of its shard from k, v and the state the shard started from,
+        # into the tail of the (then larger) scratch buffer, which all shards share
+        self.recompute = bool(recompute)
+        if self.recompute and need_backward:
+            scratch_bytes = lasp.gated_bwd_recompute_scratch_bytes if token_decay else lasp.bwd_recompute_scratch_bytes
+        else:
+            scratch_bytes = lasp.gated_scratch_bytes if token_decay else lasp.scratch_bytes
         cache_bytes = lasp.gated_state_cache_bytes if token_decay else lasp.state_cache_bytes
         self.scratch = torch.empty(scratch_bytes(self.shape), dtype=torch.uint8, device=device)
         self.caches = [torch.empty(cache_bytes(self.shape), dtype=torch.uint8, device=device)
-                       for _ in range(T)] if need_backward else [None] * T
+                       for _ in range(T)] if need_backward and not self.recompute else [None] * T
         st = dict(dtype=torch.float32, device=device)
         # kv[t] = state entering shard t (kv[T] = final); dkv[t] = gradient w.r.t. kv[t]
         self.kv = [torch.zeros(B, H, D, Dv or D, **st) for _ in range(T + 1)]
@@ -82,19 +89,20 @@ class LaspSequence:
             self.dkv[self.T].copy_(dkv_out)
         for t in reversed(range(self.T)):
             last = None if (t == self.T - 1 and not self.has_dkv_out) else self.dkv[t + 1]
+            first = None if (t == 0 and not self.has_kv_in) else self.kv[t]   # read only without a cache
             if self.norm_eps is not None and self.token_decay:
-                lasp.lasp_gated_bwd_norm(self.shape, q[t], k[t], v[t], out[t], rstd[t], dout[t], decay[t],
+                lasp.lasp_gated_bwd_norm(self.shape, q[t], k[t], v[t], out[t], rstd[t], dout[t], decay[t], first,
                                          self.kv[t + 1], last, self.caches[t], dq[t], dk[t], dv[t], dlog_g[t],
                                          self.dkv[t], self.scratch)
             elif self.norm_eps is not None:
-                lasp.lasp_bwd_norm(self.shape, q[t], k[t], v[t], out[t], rstd[t], dout[t], last, decay, self.caches[t],
-                                   dq[t], dk[t], dv[t], self.dkv[t], self.scratch)
+                lasp.lasp_bwd_norm(self.shape, q[t], k[t], v[t], out[t], rstd[t], dout[t], first, last, decay,
+                                   self.caches[t], dq[t], dk[t], dv[t], self.dkv[t], self.scratch)
             elif self.token_decay:
-                lasp.lasp_gated_bwd(self.shape, q[t], k[t], v[t], dout[t], decay[t], self.kv[t + 1], last,
+                lasp.lasp_gated_bwd(self.shape, q[t], k[t], v[t], dout[t], decay[t], first, self.kv[t + 1], last,
                                     self.caches[t], dq[t], dk[t], dv[t], dlog_g[t], self.dkv[t], self.scratch)
             else:
-                lasp.lasp_bwd(self.shape, q[t], k[t], v[t], dout[t], last, decay, self.caches[t], dq[t], dk[t], dv[t],
-                              self.dkv[t], self.scratch)
+                lasp.lasp_bwd(self.shape, q[t], k[t], v[t], dout[t], first, last, decay, self.caches[t], dq[t], dk[t],
+                              dv[t], self.dkv[t], self.scratch)
         return self.dkv[0]
 
 

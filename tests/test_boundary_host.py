@@ -115,24 +115,32 @@ def test_fwd_rejects_before_launch(L):
 def test_bwd_rejects_before_launch(L):
     s = L.make_shape(1, 1, 64, 64, 64, "f32")
     sb = L.scratch_bytes(s)
-    P = [_fake(i) for i in range(1, 14)]
-    q, k, v, do, g, dec, cache, dq, dk, dv, gin, scr, _ = P
+    P = [_fake(i) for i in range(1, 15)]
+    q, k, v, do, g, dec, cache, dq, dk, dv, gin, scr, kvin, _ = P
     call = lambda *a: L.lib.lasp_bwd(*a)
-    ok_args = [ctypes.byref(s), q, k, v, do, g, dec, cache, dq, dk, dv, gin, scr, sb, None]
-    for idx in (1, 2, 3, 4, 6, 7, 8, 9, 10, 11):   # every required pointer
+    ok_args = [ctypes.byref(s), q, k, v, do, kvin, g, dec, cache, dq, dk, dv, gin, scr, sb, None]
+    for idx in (1, 2, 3, 4, 7, 9, 10, 11, 12):   # every required pointer (kv_in, dkv_out and the cache are optional)
         a = list(ok_args)
         a[idx] = None
         assert call(*a) == 1, idx
-    a = list(ok_args); a[12] = None
+    a = list(ok_args); a[13] = None
     assert call(*a) == 5
-    a = list(ok_args); a[13] = 0
+    a = list(ok_args); a[14] = 0
     assert call(*a) == 5
-    a = list(ok_args); a[8] = q
+    a = list(ok_args); a[9] = q
     assert call(*a) == 6
-    a = list(ok_args); a[9] = dq
+    a = list(ok_args); a[10] = dq
     assert call(*a) == 6
-    a = list(ok_args); a[11] = g
+    a = list(ok_args); a[12] = g
     assert call(*a) == 6
+    # no state cache = the states are rebuilt: more scratch, and kv_in becomes an input
+    rb = L.bwd_recompute_scratch_bytes(s)
+    assert rb >= sb + L.state_cache_bytes(s) and rb % 16 == 0
+    a = list(ok_args); a[8] = None                   # scratch of the cached path is too small
+    assert call(*a) == 5
+    a = list(ok_args); a[8] = None; a[14] = rb; a[12] = kvin   # dkv_in aliases kv_in
+    assert call(*a) == 6
+    assert L.bwd_recompute_scratch_bytes(L.make_shape(1, 1, 64, 96, 64, "f32")) == 0
 
 
 # ---------------------------------------------------------------- per-token decay entry points
@@ -177,25 +185,28 @@ def test_gated_fwd_rejects_before_launch(L):
 def test_gated_bwd_rejects_before_launch(L):
     s = L.make_shape(1, 1, 64, 64, 64, "f32")
     sb = L.gated_scratch_bytes(s)
-    q, k, v, do, lg, kvout, g, cache, dq, dk, dv, dlg, gin, scr = [_fake(i) for i in range(1, 15)]
+    q, k, v, do, lg, kvout, g, cache, dq, dk, dv, dlg, gin, scr, kvin = [_fake(i) for i in range(1, 16)]
     call = lambda *a: L.lib.lasp_gated_bwd(*a)
-    ok_args = [ctypes.byref(s), q, k, v, do, lg, kvout, g, cache, dq, dk, dv, dlg, gin, scr, sb, None]
-    for idx in (1, 2, 3, 4, 5, 8, 9, 10, 11, 12, 13):   # every required pointer
+    ok_args = [ctypes.byref(s), q, k, v, do, lg, kvin, kvout, g, cache, dq, dk, dv, dlg, gin, scr, sb, None]
+    for idx in (1, 2, 3, 4, 5, 10, 11, 12, 13, 14):   # every required pointer
         a = list(ok_args)
         a[idx] = None
         assert call(*a) == 1, idx
-    a = list(ok_args); a[6] = None                   # dkv_out given but kv_out missing
+    a = list(ok_args); a[7] = None                   # dkv_out given but kv_out missing
     assert call(*a) == 1
-    a = list(ok_args); a[14] = None
+    a = list(ok_args); a[15] = None
     assert call(*a) == 5
-    a = list(ok_args); a[15] = sb - 1
+    a = list(ok_args); a[16] = sb - 1
     assert call(*a) == 5
-    a = list(ok_args); a[12] = lg                    # dlog_g aliases log_g
+    a = list(ok_args); a[13] = lg                    # dlog_g aliases log_g
     assert call(*a) == 6
-    a = list(ok_args); a[13] = kvout                 # dkv_in aliases kv_out
+    a = list(ok_args); a[14] = kvout                 # dkv_in aliases kv_out
     assert call(*a) == 6
-    a = list(ok_args); a[12] = ctypes.c_void_p(dlg.value + 4)   # dlog_g not 16-byte aligned
+    a = list(ok_args); a[13] = ctypes.c_void_p(dlg.value + 4)   # dlog_g not 16-byte aligned
     assert call(*a) == 8
+    a = list(ok_args); a[9] = None                   # no cache: the cached path's scratch is too small
+    assert call(*a) == 5
+    assert L.gated_bwd_recompute_scratch_bytes(s) >= sb + L.gated_state_cache_bytes(s)
 
 
 # ---------------------------------------------------------------- normalised output entry points
@@ -225,15 +236,17 @@ def test_norm_rejects_before_launch(L):
 
     do, g, dq, dk, dv, gin = [_fake(i) for i in range(11, 17)]
     call = lambda *a: L.lib.lasp_bwd_norm(*a)
-    ok_args = [ctypes.byref(s), q, k, v, out, rstd, do, g, dec, cache, dq, dk, dv, gin, scr, sb, None]
-    for idx in (1, 2, 3, 4, 5, 6, 8, 9, 10, 11, 12, 13):
+    ok_args = [ctypes.byref(s), q, k, v, out, rstd, do, kvin, g, dec, cache, dq, dk, dv, gin, scr, sb, None]
+    for idx in (1, 2, 3, 4, 5, 6, 9, 11, 12, 13, 14):
         a = list(ok_args)
         a[idx] = None
         assert call(*a) == 1, idx
-    a = list(ok_args); a[14] = None
+    a = list(ok_args); a[15] = None
     assert call(*a) == 5
-    a = list(ok_args); a[10] = out                   # dq aliases the forward output
+    a = list(ok_args); a[11] = out                   # dq aliases the forward output
     assert call(*a) == 6
+    a = list(ok_args); a[10] = None                  # no cache: needs the larger scratch
+    assert call(*a) == 5
 
 
 def test_gated_norm_rejects_before_launch(L):
@@ -254,14 +267,14 @@ def test_gated_norm_rejects_before_launch(L):
     assert call(*a) == 5
     do, g, dq, dk, dv, dlg, gin = [_fake(i) for i in range(11, 18)]
     call = lambda *a: L.lib.lasp_gated_bwd_norm(*a)
-    ok_args = [ctypes.byref(s), q, k, v, out, rstd, do, lg, kvout, g, cache, dq, dk, dv, dlg, gin, scr, sb, None]
-    for idx in (1, 2, 3, 4, 5, 6, 7, 10, 11, 12, 13, 14, 15):
+    ok_args = [ctypes.byref(s), q, k, v, out, rstd, do, lg, kvin, kvout, g, cache, dq, dk, dv, dlg, gin, scr, sb, None]
+    for idx in (1, 2, 3, 4, 5, 6, 7, 12, 13, 14, 15, 16):
         a = list(ok_args)
         a[idx] = None
         assert call(*a) == 1, idx
-    a = list(ok_args); a[8] = None      # dkv_out without kv_out
+    a = list(ok_args); a[9] = None      # dkv_out without kv_out
     assert call(*a) == 1
-    a = list(ok_args); a[14] = out      # dlog_g aliases the forward output
+    a = list(ok_args); a[15] = out      # dlog_g aliases the forward output
     assert call(*a) == 6
 
 
