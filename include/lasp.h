@@ -333,26 +333,6 @@ int lasp_bidir_bwd(const lasp_shape *shape, const void *k, const void *v, const 
                    const float *kv, const float *dkv, void *dq, void *dk, void *dv,
                    void *hip_stream);
 
-/*
- * Per-kernel timing, for benchmarks (diagnostic; not on the hot path, not
- * thread-safe). Between lasp_profile_begin and lasp_profile_end every
- * lasp_fwd / lasp_bwd call records HIP events around its three kernels on the
- * stream it launches on (no synchronisation is added), for at most max_calls
- * calls of each kind. lasp_profile_end waits for the recorded events, writes
- * the summed milliseconds per kernel
- *     ms_sum[0..2] = forward  {local pass, scan, tile walk}
- *     ms_sum[3..5] = backward {local pass, scan, tile walk}
- * and the number of recorded calls, and releases the events. The bidirectional
- * calls record too: lasp_bidir_state as a forward call (reduction under "local
- * pass", sum of the partials under "scan"), lasp_bidir_fwd as a forward call and
- * lasp_bidir_bwd as a backward call (their one kernel under "tile walk").
- * begin: LASP_ERR_SHAPE if max_calls <= 0 or profiling is already on,
- * LASP_ERR_HIP if events cannot be created. end: LASP_ERR_NULL on NULL
- * arguments, LASP_ERR_SHAPE if profiling is off.
- */
-int lasp_profile_begin(int32_t max_calls);
-int lasp_profile_end(double ms_sum[6], int32_t *fwd_calls, int32_t *bwd_calls);
-
 #ifdef __cplusplus
 }
 #endif

@@ -1,6 +1,7 @@
 // C-ABI host layer: argument validation, launch planning, dispatch. No device
 // memory is allocated or freed here and nothing synchronises; see include/lasp.h.
 #include "../../include/lasp.h"
+#include "../../include/lasp_profile.h"
 
 #include <cmath>
 #include <cstdint>

@@ -1416,8 +1416,11 @@ static auto by_model(const Plan &p) {
 }
 
 // Grouped K/V heads, backward: the walking kernel wrote dK, dV per QUERY head into `part`
-// ([chains][ntok][D]); dK, dV of a K/V head are the sums over its kvdiv query heads, added in fp32
-// in a fixed order and rounded once.
+// ([chains][ntok][D], in the data type, so each partial gradient is already rounded to it once);
+// dK, dV of a K/V head are the sums over its kvdiv query heads, added in fp32 in a fixed order and
+// rounded to the data type a second time. For bfloat16 the partials' rounding errors (2^-9 relative
+// each, independent) add in quadrature, so the sum stays well inside the 2e-2 bound also for
+// multi-query attention (tested with 16 query heads per K/V head).
 template <typename T>
 __global__ __launch_bounds__(256) void k_group_sum(const T *__restrict__ part, T *__restrict__ out, int kvdiv, size_t per_head) {
     const size_t kvchain = blockIdx.y;

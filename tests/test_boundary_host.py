@@ -17,10 +17,13 @@ def L():
 
 
 def test_exports_every_declared_symbol(L):
-    text = open(os.path.join(ROOT, "include", "lasp.h")).read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    names = set(re.findall(r"\b(lasp_[a-z_]+)\s*\(", text))
-    assert {"lasp_fwd", "lasp_bwd", "lasp_scratch_bytes", "lasp_state_cache_bytes"} <= names
+    names = set()
+    for header in sorted(os.listdir(os.path.join(ROOT, "include"))):   # lasp.h (the method) and lasp_profile.h (timing)
+        text = open(os.path.join(ROOT, "include", header)).read()
+        text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+        names |= set(re.findall(r"\b(lasp_[a-z_]+)\s*\(", text))
+    assert {"lasp_fwd", "lasp_bwd", "lasp_scratch_bytes", "lasp_state_cache_bytes", "lasp_fwd_noalloc",
+            "lasp_bwd_recompute_scratch_bytes", "lasp_profile_begin"} <= names
     for n in names:
         assert hasattr(L.lib, n), n
     assert L.version() >= 1

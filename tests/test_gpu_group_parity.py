@@ -36,6 +36,8 @@ CASES = [
     ("bf16", 128, 64 * 8, 4, 1, 0, 2),      # multi-query, pair cache, two chained calls
     ("bf16", 64, 64 * 5, 6, 2, 3, 1),       # odd tile count
     ("bf16", 128, 64 * 3 + 9, 4, 2, 0, 1),  # short last tile
+    ("bf16", 128, 64 * 6, 16, 1, 0, 1),     # multi-query with 16 query heads on one K/V head: dK, dV are sums of 16 rounded partials
+    ("bf16", 64, 64 * 4, 32, 2, 2, 1),      # 16 query heads per K/V head, two K/V heads
 ]
 
 
