@@ -21,33 +21,6 @@ typedef __attribute__((ext_vector_type(2))) unsigned u32x2;
 
 #define DEVI __device__ __forceinline__
 
-// Optional per-phase cycle accounting (diagnostic builds only, -DLASP_PHASE_TIMING):
-// lane 0 of every wave accumulates shader-clock cycles between PHASE marks and adds
-// them to a device-global [wave][phase] table that lasp_debug_phases() reads back.
-#ifdef LASP_PHASE_TIMING
-__device__ unsigned long long g_phase_cycles[8 * 32];  // [wave][phase]
-#define PHASE_DECL()                                                 \
-    __shared__ unsigned ph_acc[8 * 32];   /* 1 KB: the largest kernel has 1.5 KB of LDS to spare */ \
-    if (threadIdx.x < 256) ph_acc[threadIdx.x] = 0;                  \
-    __syncthreads();                                                 \
-    unsigned long long ph_last = clock64()
-#define PHASE(n)                                                                     \
-    do {                                                                             \
-        unsigned long long now_ = clock64();                                         \
-        if ((threadIdx.x & 63) == 0) ph_acc[(threadIdx.x >> 6) * 32 + (n)] += (unsigned)(now_ - ph_last); \
-        ph_last = now_;                                                              \
-    } while (0)
-#define PHASE_FLUSH()                                                                            \
-    do {                                                                                         \
-        __syncthreads();                                                                         \
-        if (threadIdx.x < 256) atomicAdd(&g_phase_cycles[threadIdx.x], (unsigned long long)ph_acc[threadIdx.x]); \
-    } while (0)
-#else
-#define PHASE_DECL() ((void)0)
-#define PHASE(n) ((void)0)
-#define PHASE_FLUSH() ((void)0)
-#endif
-
 // Software pipelining of a product loop: the operand fragments of step s+1 are
 // requested before the MFMAs of step s are issued, so that LDS latency is
 // covered by matrix work of the same wave. `load(s)` returns the fragments of

@@ -89,7 +89,6 @@ __global__ __launch_bounds__(D * 2, 2) void k_local(const T *__restrict__ X, con
     const int t1 = min(t0 + tiles_per_seg, ntiles);
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);  // wave index, scalar
     Lane ln = fresh_lane();
-    PHASE_DECL();
     if (!BWD) {  // forward: X, Y are K, V
         X += kv_shift(chain, H, kvdiv, ntok, WX);
         Y += kv_shift(chain, H, kvdiv, ntok, WY);
@@ -107,7 +106,6 @@ __global__ __launch_bounds__(D * 2, 2) void k_local(const T *__restrict__ X, con
     NormTile<T, CT, D, NT, WY> mn;   // the normalised output has the rows of Y (= dY)
     const float *rstd_c = rstd + (size_t)chain * ntok;
     if constexpr (NORM) mn.load(yn + yoff(tile_of(0)), rstd_c + (size_t)tile_of(0) * CT, nvalid(tile_of(0)));
-    PHASE(22);
     f32x16 st[DB];
 #pragma unroll
     for (int ab = 0; ab < DB; ++ab) st[ab] = f32x16{0};
@@ -167,23 +165,18 @@ __global__ __launch_bounds__(D * 2, 2) void k_local(const T *__restrict__ X, con
     fill_pow_table<CT>(pw, lam);
     const GeoWeights<T> geo(lam);
     const float l2f = (float)log2((double)lam);
-    PHASE(23);
     for (int n = 0; n < ntl; ++n) {
         __syncthreads();  // previous tile fully consumed (and pw visible on the first pass)
         ln = fresh_lane();
-        PHASE(24);
         if constexpr (NORM) mn.apply(my);
         mx.store(sX, LDD);
         my.store(sY, LDD);
-        PHASE(25);
         __syncthreads();
-        PHASE(26);
         if (n + 1 < ntl) {
             mx.template load_w<WX>(X + xoff(tile_of(n + 1)), CT);
             my.template load_w<WY>(Y + yoff(tile_of(n + 1)), CT);
             if constexpr (NORM) mn.load(yn + yoff(tile_of(n + 1)), rstd_c + (size_t)tile_of(n + 1) * CT);
         }
-        PHASE(27);
         // Token weight relative to the whole segment, so the accumulators are never rescaled:
         // forward lambda^(tokens after it in the segment), backward lambda^(its 1-based position).
         // It factors as (tile factor) * (table entry of the lane's first element) * g[e].
@@ -226,13 +219,9 @@ __global__ __launch_bounds__(D * 2, 2) void k_local(const T *__restrict__ X, con
                     for (int ab = 0; ab < DB; ++ab) st[ab] = E::mfma(f.x[ab], yd, st[ab]);
                 });
         }
-        PHASE(28);
     }
     }
-    PHASE(29);
     state_store<D>(ln, st, scratch + ((size_t)chain * nseg + seg) * D * D, w);
-    PHASE(30);
-    PHASE_FLUSH();
 }
 
 // ---------------------------------------------------------------------------
@@ -718,7 +707,6 @@ __global__ __launch_bounds__(D * 4) void k_bwd8(const T *__restrict__ Q, const T
     const int w = w8 % NW;    // feature block of this wave's outputs
     const int rg = w8 / NW;   // group: 0 produces dV, 1 produces dK
     Lane ln = fresh_lane();
-    PHASE_DECL();
 
     // requests first (last tile of the segment, its cached state), set-up arithmetic while they fly
     const size_t base = (size_t)chain * ntok * D;
@@ -789,7 +777,6 @@ __global__ __launch_bounds__(D * 4) void k_bwd8(const T *__restrict__ Q, const T
         const int nrows = TOKEN ? min(CT, ntok - t * CT) : CT;  // rows of this tile that exist
         __syncthreads();  // previous tile fully consumed
         ln = fresh_lane();
-        PHASE(0);
         if constexpr (TOKEN) {
             if (t < t1 - 1) flush_r(t + 1);
             dec.fill(lgreg);
@@ -802,7 +789,6 @@ __global__ __launch_bounds__(D * 4) void k_bwd8(const T *__restrict__ Q, const T
         mc.store(sC, LDD);
         __syncthreads();
         ln = fresh_lane();
-        PHASE(1);
         if (t > t0) {
             mv.load(V + off - (size_t)CT * D);
             mo.load(dO + off - (size_t)CT * D);
@@ -840,7 +826,6 @@ __global__ __launch_bounds__(D * 4) void k_bwd8(const T *__restrict__ Q, const T
         }
         __syncthreads();
         ln = fresh_lane();
-        PHASE(2);
 
         float rq = 0.0f;  // per-token decay: q_i . dq_i over this wave's features, tokens i of block 1 - rg
         // ---- dQ^T[a in w][i], tokens i of block 1 - rg:
@@ -859,7 +844,6 @@ __global__ __launch_bounds__(D * 4) void k_bwd8(const T *__restrict__ Q, const T
             store_out_tile_t<T, D>(ln, dQ + off, acc, r0, w, nrows);
             if constexpr (TOKEN) rq = rowdot<T>(ln, acc, sQ, LDD, r0, w);
         }
-        PHASE(3);
         ln = fresh_lane();
         // ---- this group's product, both token blocks j (written for dV; dK is the same under K<->V, Q<->dO, S<->dS):
         //      dV^T[c in w][j] = lambda^(CT-j) sum_a dKV[a][c] K[j][a] + sum_{i>=j} dO[i][c] Sm[i][j] ----
@@ -908,7 +892,6 @@ __global__ __launch_bounds__(D * 4) void k_bwd8(const T *__restrict__ Q, const T
                 }
             }
         }
-        PHASE(4);
         ln = fresh_lane();
         // ---- state update in this group's orientation (group 0: dKV <- lambda^CT dKV + (Lambda Q)^T dO) ----
         {
@@ -933,14 +916,12 @@ __global__ __launch_bounds__(D * 4) void k_bwd8(const T *__restrict__ Q, const T
                     for (int blk = 0; blk < DB; ++blk) st[blk] = E::mfma(f.a[blk], bs, st[blk]);
                 });
         }
-        PHASE(5);
     }
     if constexpr (TOKEN) {
         __syncthreads();
         flush_r(t0);
     }
     if (seg == 0 && rg == 0) state_store<D>(ln, st, dkv_in + (size_t)chain * D * D, w);
-    PHASE_FLUSH();
 }
 
 // ---------------------------------------------------------------------------
@@ -1004,7 +985,6 @@ __global__ __launch_bounds__(D * 4) void k_bwd8p(const T *__restrict__ Q, const 
     const int w = w8 % NW;    // feature block of this wave's outputs
     const int rg = w8 / NW;   // group: 0 produces dV, 1 produces dK
     Lane ln = fresh_lane();
-    PHASE_DECL();
 
     K += kv_shift(chain, H, kvdiv, ntok, WK);   // K, V of this chain's K/V head
     V += kv_shift(chain, H, kvdiv, ntok, WV);
@@ -1261,7 +1241,6 @@ __global__ __launch_bounds__(D * 4) void k_bwd8p(const T *__restrict__ Q, const 
     for (int tE = t1 - 2; tE >= t0; tE -= 2) {
         __syncthreads();  // previous pair fully consumed
         ln = fresh_lane();
-        PHASE(0);
         if constexpr (TOKEN) {
             if (tE + 2 < t1) flush_r(tE + 2);  // E tile of the previous pair
             decO.fill(lgO);
@@ -1278,43 +1257,30 @@ __global__ __launch_bounds__(D * 4) void k_bwd8p(const T *__restrict__ Q, const 
         if (tE > t0) load_pair_kv(tE - 2);
         __syncthreads();
         ln = fresh_lane();
-        PHASE(1);
         moX.template load_w<WV>(dO + voff(tE), CT);
         mqX.template load_w<WK>(Q + koff(tE), CT);
         if constexpr (NORM) mnX.load(yn + voff(tE), rstd_c + (size_t)tE * CT);
-        PHASE(2);
         // ---- O tile ----
         scores(decO, sVO, sKO);
-        PHASE(3);
         cross_scores();
-        PHASE(4);
         __syncthreads();
         ln = fresh_lane();
-        PHASE(5);
         products(decO, sVO, sKO, tE + 1, TOKEN ? min(CT, ntok - (tE + 1) * CT) : CT, true);
-        PHASE(6);
         __syncthreads();  // O tile consumed: sdO, sQ are free
         ln = fresh_lane();
-        PHASE(7);
         if constexpr (TOKEN) flush_r(tE + 1);
         if constexpr (NORM) mnX.apply(moX);
         moX.store(sdO, LDD);
         mqX.store(sQ, LDD);
         __syncthreads();
         ln = fresh_lane();
-        PHASE(8);
         if (tE > t0) load_pair_rest(tE - 2);
-        PHASE(9);
         // ---- E tile ----
         scores(decE, sVE, sKE);
-        PHASE(10);
         __syncthreads();
         ln = fresh_lane();
-        PHASE(11);
         products(decE, sVE, sKE, tE, CT, false);
-        PHASE(12);
     }
-    PHASE_FLUSH();
     if constexpr (TOKEN) {
         __syncthreads();
         flush_r(t0);
@@ -1598,17 +1564,6 @@ hipError_t launch_fill_logg(const Plan &p, const float *decay, float *log_g, hip
     k_fill_logg<<<dim3((p.N + 255) / 256 < 64 ? (p.N + 255) / 256 : 64, p.B * p.H), dim3(256), 0, stream>>>(decay, log_g, p.H, p.N);
     return hipGetLastError();
 }
-
-#ifdef LASP_PHASE_TIMING
-extern "C" int lasp_debug_phases(unsigned long long *out256, int reset) {
-    if (out256 && hipMemcpyFromSymbol(out256, HIP_SYMBOL(g_phase_cycles), sizeof(g_phase_cycles)) != hipSuccess) return 1;
-    if (reset) {
-        unsigned long long z[8 * 32] = {};
-        if (hipMemcpyToSymbol(HIP_SYMBOL(g_phase_cycles), z, sizeof(z)) != hipSuccess) return 1;
-    }
-    return 0;
-}
-#endif
 
 // Scratch of the entry point that allocates nothing (lasp_fwd_noalloc): the segment states live in this
 // array instead of a buffer the caller brings. Every device the library runs on holds its own copy, at
