@@ -7,6 +7,8 @@
 
 #include <hip/hip_runtime.h>
 
+#include <type_traits>
+
 namespace lasp {
 
 typedef unsigned short bf16_t;  // storage type of bfloat16 data
@@ -501,8 +503,25 @@ struct TokenDecay {
         }
         return v;
     }
+    // Inclusive prefix sum over the 64 lanes of a wave with data-parallel moves (no LDS round trips): four
+    // shifts inside each row of 16 lanes, then the last lane of row 0 / 2 is added to row 1 / 3, then lane 31
+    // to the upper half. Lanes a shift has no source for receive 0.
+    static DEVI float wave_inclusive_scan(float x) {
+        auto shifted = [](float v, auto ctrl, auto rows) {
+            return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), decltype(ctrl)::value, decltype(rows)::value, 0xf, false));
+        };
+        using std::integral_constant;
+        x += shifted(x, integral_constant<int, 0x111>{}, integral_constant<int, 0xf>{});   // row_shr:1
+        x += shifted(x, integral_constant<int, 0x112>{}, integral_constant<int, 0xf>{});   // row_shr:2
+        x += shifted(x, integral_constant<int, 0x114>{}, integral_constant<int, 0xf>{});   // row_shr:4
+        x += shifted(x, integral_constant<int, 0x118>{}, integral_constant<int, 0xf>{});   // row_shr:8
+        x += shifted(x, integral_constant<int, 0x142>{}, integral_constant<int, 0xa>{});   // row_bcast:15 into rows 1 and 3
+        x += shifted(x, integral_constant<int, 0x143>{}, integral_constant<int, 0xc>{});   // row_bcast:31 into rows 2 and 3
+        return x;
+    }
     // Rebuilds the tables from the values fetch() returned. Every thread calls it between
-    // the barrier that retires the previous tile and the one that publishes the next.
+    // the barrier that retires the previous tile and the one that publishes the next; the other waves
+    // wait for the one that does the work, so it is kept short (register moves, the bare hardware exp2).
     DEVI void fill(const LogG &v) const {
         if (threadIdx.x < 64) {
             const int l = threadIdx.x;
@@ -510,12 +529,7 @@ struct TokenDecay {
             c[0] = v.x[0];
 #pragma unroll
             for (int e = 1; e < PER; ++e) c[e] = c[e - 1] + v.x[e];
-            float incl = c[PER - 1];  // inclusive scan of the lane totals
-#pragma unroll
-            for (int d = 1; d < 64; d <<= 1) {
-                const float y = __shfl_up(incl, d, 64);
-                if (l >= d) incl += y;
-            }
+            const float incl = wave_inclusive_scan(c[PER - 1]);  // inclusive scan of the lane totals
             const float total = __shfl(incl, 63, 64);  // lanes past the tile hold zeros
             const float before = incl - c[PER - 1];
 #pragma unroll
@@ -524,8 +538,8 @@ struct TokenDecay {
                 if (i < CT) {
                     const float ci = before + c[e];
                     cum[i] = ci;
-                    wu[i] = exp2f(ci);
-                    wa[i] = exp2f(total - ci);
+                    wu[i] = __builtin_amdgcn_exp2f(ci);           // (below 2^-126: 0 instead of a denormal)
+                    wa[i] = __builtin_amdgcn_exp2f(total - ci);
                 }
             }
         }
@@ -568,9 +582,17 @@ DEVI float rowdot(const Lane &ln, const f32x16 &acc, const T *sX, int ld, int ro
     float s = 0.0f;
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
+        // the lane's four features of this register group are consecutive in the row (inside one 16-byte chunk)
         const T *p = sX + lds_off(ld, row0 + ln.r, 32 * w + 8 * q + 4 * ln.h);
+        if constexpr (sizeof(T) == 2) {
+            const f32x4 x = __builtin_convertvector(*(const bf16x4 *)p, f32x4);
 #pragma unroll
-        for (int e = 0; e < 4; ++e) s += acc[4 * q + e] * Elem<T>::ld1(p + e);
+            for (int e = 0; e < 4; ++e) s += acc[4 * q + e] * x[e];
+        } else {
+            const f32x4 x = *(const f32x4 *)p;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) s += acc[4 * q + e] * x[e];
+        }
     }
     return s + __shfl_xor(s, 32, 64);
 }
