@@ -1160,8 +1160,8 @@ __global__ __launch_bounds__(D * 4) void k_bwd8p(const T *__restrict__ Q, const 
             auto intra = [&](int ks) { return FragPair<F>{E::ld_ks(ln, pK, LDD, ks * E::KSTEP, 32 * w), E::ld_kc(ln, sDS, LDP, r0, ks * E::KSTEP)}; };
             if (rg == 0) pipelined<2 * SPB>(intra, fma);    // keys of blocks 0 and 1
             else pipelined<SPB>(intra, fma);                // keys of block 0
+            if constexpr (TOKEN) rq = rowdot<T>(ln, acc, sQ, LDD, r0, w);   // (from the fp32 accumulators, before rounding)
             store_out_tile_t<T, D, WK>(ln, dQ + koff(t), acc, r0, w, nrows);
-            if constexpr (TOKEN) rq = rowdot<T>(ln, acc, sQ, LDD, r0, w);
         }
         ln = fresh_lane();
         {   // dV^T[c in w][j] (group 0) or dK^T[a in w][j] (group 1), both token blocks
@@ -1200,19 +1200,16 @@ __global__ __launch_bounds__(D * 4) void k_bwd8p(const T *__restrict__ Q, const 
                 });
 #pragma unroll
             for (int jb = 0; jb < NB; ++jb) {
+                if constexpr (TOKEN) {   // (row dots from the fp32 accumulators, before they are rounded and stored)
+                    float r = jb == 1 - rg ? rq : 0.0f;
+                    if (rg == 1) r -= rowdot<T>(ln, acc[jb], pK, LDD, 32 * jb, w);  // group 1 holds dK
+                    if (ln.h == 0) rs[w8 * CT + 32 * jb + ln.r] = r;
+                }
                 if constexpr (WK == WV) {
                     store_out_tile_t<T, D, WK>(ln, gOut + koff(t), acc[jb], 32 * jb, w, nrows);
                 } else {
                     if (rg) store_out_tile_t<T, D, WK>(ln, dK + koff(t), acc[jb], 32 * jb, w, nrows);
                     else store_out_tile_t<T, D, WV>(ln, dV + voff(t), acc[jb], 32 * jb, w, nrows);
-                }
-            }
-            if constexpr (TOKEN) {
-#pragma unroll
-                for (int jb = 0; jb < NB; ++jb) {
-                    float r = jb == 1 - rg ? rq : 0.0f;
-                    if (rg == 1) r -= rowdot<T>(ln, acc[jb], pK, LDD, 32 * jb, w);  // group 1 holds dK
-                    if (ln.h == 0) rs[w8 * CT + 32 * jb + ln.r] = r;
                 }
             }
         }
