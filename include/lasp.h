@@ -76,8 +76,8 @@ typedef enum { LASP_F32 = 0, LASP_BF16 = 1 } lasp_dtype;
  *            q, k, dq, dk are [..][N][D], v, out, dout, dv are [..][N][Dv], and
  *            every state (kv_in, kv_out, dkv_out, dkv_in) is [B][H][D][Dv], rows
  *            indexed by the key feature. The kernels run at max(D, Dv) with the
- *            narrower of the two zero-padded on chip (memory traffic follows the
- *            real sizes, scratch and the state cache the padded ones). The fused
+ *            narrower of the two zero-padded on chip; memory traffic, scratch and
+ *            the state cache follow the real sizes. The fused
  *            Norm then runs over the Dv value features. Not offered for the
  *            bidirectional calls.
  *   segments 0 = chosen by the library. Otherwise the number of independent
@@ -121,7 +121,7 @@ int32_t lasp_num_segments(const lasp_shape *shape);
 size_t lasp_state_cache_bytes(const lasp_shape *shape);
 
 /*
- * Bytes of scratch both lasp_fwd and lasp_bwd need: one float [D][D] state per
+ * Bytes of scratch both lasp_fwd and lasp_bwd need: one float [D][Dv] state per
  * head per segment. Contents are overwritten by every call. 0 on an invalid shape.
  */
 size_t lasp_scratch_bytes(const lasp_shape *shape);

@@ -75,7 +75,7 @@ size_t cache_bytes(const lasp_shape *shape, bool token) {
     lasp::Plan p;
     if (make_plan(shape, kForward, &p, token) != LASP_OK) return 0;
     // (a synthesised plan has token == true and the same cache stride rule)
-    return (size_t)p.B * p.H * (p.ntiles / p.cache_stride) * p.D * p.D * elem_bytes(p.dtype);
+    return (size_t)p.B * p.H * (p.ntiles / p.cache_stride) * p.dk * p.dv * elem_bytes(p.dtype);   // [d_k][d_v] per slot
 }
 
 // Scratch layout: [segment states][per-token decay only: segment log-decays][.. : per-token r_t]
@@ -90,7 +90,7 @@ bool scratch_layout(const lasp_shape *shape, bool token, ScratchLayout *l) {
     const size_t nseg = f.nseg > b.nseg ? f.nseg : b.nseg;  // one buffer serves both passes
     const size_t chains = (size_t)f.B * f.H;
     l->states = 0;
-    l->seglog = chains * nseg * f.D * f.D * sizeof(float);
+    l->seglog = round256(chains * nseg * f.dk * f.dv * sizeof(float));   // segment states, [d_k][d_v] floats each
     l->rtok = l->logg = l->seglog;
     size_t end = l->seglog;
     if (f.token) {   // requested, or synthesised for a short last tile

@@ -82,7 +82,7 @@ __global__ __launch_bounds__(D * 2, 2) void k_bidir_reduce(const T *__restrict__
         consume(0, t);
         if (t + 1 < t1) consume(1, t + 1);
     }
-    state_store<D>(ln, st, part + ((size_t)chain * nseg + seg) * D * D, w);
+    state_store_w<D>(ln, st, part + ((size_t)chain * nseg + seg) * D * D, w);
 }
 
 // state[chain] = (accumulate ? state[chain] : 0) + part[chain][0] + part[chain][1] + ..., in that order.
@@ -157,7 +157,7 @@ __global__ __launch_bounds__(D * 2, 2) void k_bidir_apply(BidirOps ops, int ntil
                     for (int e = 0; e < 4; ++e) st[ab][4 * g + e] = v[e];
                 }
         } else {
-            state_load<D>(ln, st, S, w);
+            state_load_w<D>(ln, st, S, w);
         }
 #pragma unroll
         for (int ab = 0; ab < DB; ++ab)

@@ -597,19 +597,36 @@ DEVI float rowdot(const Lane &ln, const f32x16 &acc, const T *sX, int ld, int ro
     return s + __shfl_xor(s, 32, 64);
 }
 
-// Load / store a wave's column block of a [D][D] float state (row-major [a][c])
-// into accumulator layout: st[ab][i] = S[32 ab + ln.acc_row(i)][32 w + ln.r].
-template <int D>
-DEVI void state_load(const Lane &ln, f32x16 (&st)[D / 32], const float *g, int w) {
-    const unsigned lo = (4 * ln.h * D + 32 * w + ln.r) * sizeof(float);
+// Load / store a wave's column block of a float state. In memory a state is [WK][WV] (row-major [a][c], row
+// stride WV): the caller's states, the segment states in scratch and (in the data type) the state cache all
+// hold only the real rows and columns; on chip the kernels work on the zero-padded [D][D] state in
+// accumulator layout, st[ab][i] = S[32 ab + ln.acc_row(i)][32 w + ln.r]. Nothing outside [WK][WV] is touched
+// in memory: padding is loaded as zero and never stored.
+template <int D, int WK = D, int WV = D>
+DEVI void state_load_w(const Lane &ln, f32x16 (&st)[D / 32], const float *g, int w) {
+    const bool cols = 32 * w < WV;   // (wave-uniform) this wave's column block holds real columns
+    const unsigned lo = (4 * ln.h * WV + 32 * w + ln.r) * sizeof(float);
 #pragma unroll
     for (int ab = 0; ab < D / 32; ++ab)
 #pragma unroll
-        for (int i = 0; i < 16; ++i) st[ab][i] = gload<float>(g + (32 * ab + 8 * (i >> 2) + (i & 3)) * D, lo);
+        for (int i = 0; i < 16; ++i)
+            st[ab][i] = (ab < WK / 32 && cols) ? gload<float>(g + (32 * ab + 8 * (i >> 2) + (i & 3)) * WV, lo) : 0.0f;
 }
-// The same for a state handed to the caller, [WK][WV] float (row stride WV), of which the kernels hold
-// the zero-padded [D][D] version: only the real rows and columns are written.
-template <int D, int WK, int WV>
+// The same state in the other orientation: st[cb][i] = S[32 w + ln.r][32 cb + ln.acc_row(i)] (the wave owns 32 rows).
+template <int D, int WK = D, int WV = D>
+DEVI void state_load_t_w(const Lane &ln, f32x16 (&st)[D / 32], const float *g, int w) {
+    const bool rows = 32 * w < WK;
+    const unsigned lo = ((32 * w + ln.r) * WV + 4 * ln.h) * sizeof(float);
+#pragma unroll
+    for (int cb = 0; cb < D / 32; ++cb)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const f32x4 x = (cb < WV / 32 && rows) ? gload<f32x4>(g + 32 * cb + 8 * q, lo) : f32x4{0, 0, 0, 0};
+#pragma unroll
+            for (int e = 0; e < 4; ++e) st[cb][4 * q + e] = x[e];
+        }
+}
+template <int D, int WK = D, int WV = D>
 DEVI void state_store_w(const Lane &ln, const f32x16 (&st)[D / 32], float *g, int w) {
     if constexpr (WV < D) {
         if (32 * w >= WV) return;
@@ -619,14 +636,6 @@ DEVI void state_store_w(const Lane &ln, const f32x16 (&st)[D / 32], float *g, in
     for (int ab = 0; ab < WK / 32; ++ab)
 #pragma unroll
         for (int i = 0; i < 16; ++i) gstore<float>(g + (32 * ab + 8 * (i >> 2) + (i & 3)) * WV, lo, st[ab][i]);
-}
-template <int D>
-DEVI void state_store(const Lane &ln, const f32x16 (&st)[D / 32], float *g, int w) {
-    const unsigned lo = (4 * ln.h * D + 32 * w + ln.r) * sizeof(float);
-#pragma unroll
-    for (int ab = 0; ab < D / 32; ++ab)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) gstore<float>(g + (32 * ab + 8 * (i >> 2) + (i & 3)) * D, lo, st[ab][i]);
 }
 
 // Masked score tile (Alg. 2 / Alg. 3 mask M): the wave holds the transposed
@@ -741,26 +750,30 @@ DEVI void store_out_tile_t(const Lane &ln, T *g, const f32x16 &acc, int row0, in
     }
 }
 
-// Store a wave's column block of the state into the cache tile g ([a][c], row
-// stride D). Accumulator layout gives each lane four consecutive a for one c,
+// Store a wave's column block of the state into the cache tile g ([a][c], [WK][WV] real rows and columns,
+// row stride WV). Accumulator layout gives each lane four consecutive a for one c,
 // the wrong way round for wide stores, so for bfloat16 the wave transposes one
 // 32x32 block at a time through a private slice of an idle LDS buffer (written
 // [c][a], read back with transposing reads) and stores 16 bytes per lane:
 // 64-byte row segments instead of single elements. Other types store element
 // by element. The LDS slice is only touched by this wave (LDS operations of one
 // wave execute in order); the caller's next barrier orders it against later use.
-template <typename T, int CT, int D>
+// Waves whose column block is padding (32 w >= WV) and row blocks of padding (ab >= WK / 32) store nothing.
+template <typename T, int CT, int D, int WK = D, int WV = D>
 DEVI void cache_store(const Lane &ln, T *g, const f32x16 (&st)[D / 32], T *idle_lds, int w) {
     using E = Elem<T>;
     constexpr int LDS_ROW = 36;  // 32 a + 4 pad elements: 8-byte aligned rows, staggered banks
     constexpr bool STAGED = sizeof(T) == 2 && (D / 32) * 32 * LDS_ROW <= CT * (CT + E::PAD);
+    if constexpr (WV < D) {
+        if (32 * w >= WV) return;
+    }
     if constexpr (STAGED) {
         T *R = idle_lds + w * 32 * LDS_ROW;
         const int l = ln.id, bl = l >> 4, i = l & 15;
-        const unsigned glo = (i * D + 32 * w + 8 * bl) * sizeof(T);
+        const unsigned glo = (i * WV + 32 * w + 8 * bl) * sizeof(T);
         typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
 #pragma unroll
-        for (int ab = 0; ab < D / 32; ++ab) {
+        for (int ab = 0; ab < WK / 32; ++ab) {
 #pragma unroll
             for (int q = 0; q < 4; ++q)
                 E::st4(R + ln.r * LDS_ROW + 8 * q + 4 * ln.h, st[ab][4 * q], st[ab][4 * q + 1], st[ab][4 * q + 2],
@@ -773,17 +786,17 @@ DEVI void cache_store(const Lane &ln, T *g, const f32x16 (&st)[D / 32], T *idle_
                 union { struct { s16x4 a, b; } s; u32x4 v; } u;
                 u.s.a = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)p);
                 u.s.b = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(p + 4 * LDS_ROW));
-                gstore<u32x4>(g + (32 * ab + 16 * it) * D, glo, u.v);
+                gstore<u32x4>(g + (32 * ab + 16 * it) * WV, glo, u.v);
             }
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
             __builtin_amdgcn_wave_barrier();
         }
     } else {
-        const unsigned slo = (4 * ln.h * D + 32 * w + ln.r) * sizeof(T);
+        const unsigned slo = (4 * ln.h * WV + 32 * w + ln.r) * sizeof(T);
 #pragma unroll
-        for (int ab = 0; ab < D / 32; ++ab)
+        for (int ab = 0; ab < WK / 32; ++ab)
 #pragma unroll
-            for (int i = 0; i < 16; ++i) E::gst1(g + (32 * ab + 8 * (i >> 2) + (i & 3)) * D, slo, st[ab][i]);
+            for (int i = 0; i < 16; ++i) E::gst1(g + (32 * ab + 8 * (i >> 2) + (i & 3)) * WV, slo, st[ab][i]);
     }
 }
 

@@ -221,21 +221,20 @@ __global__ __launch_bounds__(D * 2, 2) void k_local(const T *__restrict__ X, con
         }
     }
     }
-    state_store<D>(ln, st, scratch + ((size_t)chain * nseg + seg) * D * D, w);
+    state_store_w<D, WX, WY>(ln, st, scratch + ((size_t)chain * nseg + seg) * WX * WY, w);
 }
 
 // ---------------------------------------------------------------------------
 // k_scan: per state element, scan over the segments of a head.
 //   forward : start_0 = kv_in (or 0); start_{j+1} = lambda^(len_j) start_j + local_j
 //   backward: recv_{S-1} = dkv_out (or 0); recv_{j-1} = lambda^(len_j) recv_j + local_j
-// scratch[chain][j] holds local_j on entry and start_j / recv_j on exit.
+// scratch[chain][j] ([d_k][d_v] floats each) holds local_j on entry and start_j / recv_j on exit.
 // ---------------------------------------------------------------------------
 // With per-token decay the factor of segment j is 2^seglog[chain][j] (written by k_local).
 template <bool BWD, bool TOKEN>
 __global__ __launch_bounds__(256) void k_scan(float *__restrict__ scratch, const float *__restrict__ boundary,
                                               const float *__restrict__ decay, const float *__restrict__ seglog,
-                                              int H, int DD, int nseg, int tiles_per_seg, int ntiles, int tile,
-                                              int D, int wk, int wv) {
+                                              int H, int DD, int nseg, int tiles_per_seg, int ntiles, int tile) {
     const int chain = blockIdx.y;
     const int e = (blockIdx.x * blockDim.x + threadIdx.x) * 4;  // four consecutive state elements per thread
     if (e >= DD) return;
@@ -245,12 +244,9 @@ __global__ __launch_bounds__(256) void k_scan(float *__restrict__ scratch, const
         p_full = (float)exp2((double)(tiles_per_seg * tile) * l2);
         p_last = (float)exp2((double)((ntiles - (nseg - 1) * tiles_per_seg) * tile) * l2);
     }
-    // The caller's state is [wk][wv]; the kernels work on its zero-padded [D][D] version (DD = D * D).
+    // The caller's state and the segment states share one layout, [d_k][d_v] (DD = d_k * d_v elements).
     f32x4 carry = {0, 0, 0, 0};
-    if (boundary) {
-        const int row = e / D, col = e % D;
-        if (row < wk && col < wv) carry = *(const f32x4 *)(boundary + ((size_t)chain * wk + row) * wv + col);
-    }
+    if (boundary) carry = *(const f32x4 *)(boundary + (size_t)chain * DD + e);
     float *s = scratch + (size_t)chain * nseg * DD + e;
     constexpr int U = 8;  // segments whose local states are fetched together (independent loads)
     for (int n0 = 0; n0 < nseg; n0 += U) {
@@ -323,7 +319,7 @@ __global__ __launch_bounds__(D * 2, (CT <= 64 && sizeof(T) == 2) ? 2 : 1) void k
     mk.template load_w<WK>(K + koff(t0), nvalid(t0));
     mv.template load_w<WV>(V + voff(t0), nvalid(t0));
     f32x16 st[DB];
-    state_load<D>(ln, st, scratch + ((size_t)chain * nseg + seg) * D * D, w);
+    state_load_w<D, WK, WV>(ln, st, scratch + ((size_t)chain * nseg + seg) * WK * WV, w);
     const auto dec = DecaySel<TOKEN, T, CT>::make(pw, decay, chain, H);
     const float *lg = decay + (size_t)chain * ntok;  // per-token decay: `decay` is log g, [chain][token]
     typename TokenDecay<T, CT>::LogG lgreg = {};
@@ -334,7 +330,7 @@ __global__ __launch_bounds__(D * 2, (CT <= 64 && sizeof(T) == 2) ? 2 : 1) void k
         ln = fresh_lane();
         // The state this tile starts from goes to the cache as KV_{t-1}, rows a, columns c.
         if (cache && t % cache_stride == 0)
-            cache_store<T, CT, D>(ln, cache + ((size_t)chain * (ntiles / cache_stride) + t / cache_stride) * D * D, st, sP, w);
+            cache_store<T, CT, D, WK, WV>(ln, cache + ((size_t)chain * (ntiles / cache_stride) + t / cache_stride) * WK * WV, st, sP, w);
         if constexpr (!STATES) mq.store(sQ, LDD);
         mk.store(sK, LDD);
         mv.store(sV, LDD);
@@ -494,7 +490,7 @@ __global__ __launch_bounds__(D * 2, (CT <= 64 && sizeof(T) == 2 && WK == D && WV
     auto koff = [&](int t) { return tile_off(chain, ntok, t, CT, WK); };
     auto voff = [&](int t) { return tile_off(chain, ntok, t, CT, WV); };
     f32x16 dkv[DB];
-    state_load<D>(ln, dkv, scratch + ((size_t)chain * nseg + seg) * D * D, w);
+    state_load_w<D, WK, WV>(ln, dkv, scratch + ((size_t)chain * nseg + seg) * WK * WV, w);
 
     TileMover<T, CT, D, NT> ma, mb;
     ma.template load_w<WV>(V + voff(t1 - 1), nvalid(t1 - 1));
@@ -542,10 +538,11 @@ __global__ __launch_bounds__(D * 2, (CT <= 64 && sizeof(T) == 2 && WK == D && WV
         for (int b = 0; b < NB; ++b) accQ[b] = accK[b] = f32x16{0};
         // dQ_inter^T[a][i] = lambda^i sum_c KV_{t-1}[a][c] dO[i][c]; KV rows are read from the cache in place
         {
-            const T *c = cache + ((size_t)chain * ntiles + t) * D * D;
+            const T *c = cache + ((size_t)chain * ntiles + t) * WK * WV;   // [WK][WV]: rows and columns of padding are not there
 #pragma unroll
             for (int ks = 0; ks < NKD; ++ks) {
-                const typename E::frag kvf = E::ld_kc_g(ln, c, D, 32 * w, ks * E::KSTEP);
+                typename E::frag kvf = {};
+                if (32 * w < WK && ks * E::KSTEP < WV) kvf = E::ld_kc_g(ln, c, WV, 32 * w, ks * E::KSTEP);
 #pragma unroll
                 for (int ib = 0; ib < NB; ++ib) accQ[ib] = E::mfma(kvf, E::ld_kc(ln, bufB, LDD, 32 * ib, ks * E::KSTEP), accQ[ib]);
             }
@@ -757,19 +754,8 @@ __global__ __launch_bounds__(D * 4) void k_bwd8(const T *__restrict__ Q, const T
     f32x16 st[DB];
     {
         const float *g = scratch + ((size_t)chain * nseg + seg) * D * D;
-        if (rg == 0) {
-            state_load<D>(ln, st, g, w);
-        } else {
-            const unsigned lo = ((32 * w + ln.r) * D + 4 * ln.h) * sizeof(float);
-#pragma unroll
-            for (int cb = 0; cb < DB; ++cb)
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    const f32x4 x = gload<f32x4>(g + 32 * cb + 8 * q, lo);
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) st[cb][4 * q + e] = x[e];
-                }
-        }
+        if (rg == 0) state_load_w<D>(ln, st, g, w);
+        else state_load_t_w<D>(ln, st, g, w);
     }
 
     for (int t = t1 - 1; t >= t0; --t) {
@@ -921,7 +907,7 @@ __global__ __launch_bounds__(D * 4) void k_bwd8(const T *__restrict__ Q, const T
         __syncthreads();
         flush_r(t0);
     }
-    if (seg == 0 && rg == 0) state_store<D>(ln, st, dkv_in + (size_t)chain * D * D, w);
+    if (seg == 0 && rg == 0) state_store_w<D>(ln, st, dkv_in + (size_t)chain * D * D, w);
 }
 
 // ---------------------------------------------------------------------------
@@ -992,7 +978,7 @@ __global__ __launch_bounds__(D * 4) void k_bwd8p(const T *__restrict__ Q, const 
     auto voff = [&](int t) { return tile_off(chain, ntok, t, CT, WV); };
     TileMover<T, CT, D, NT> mvO, moX, mkO, mqX, mvE, mkE;   // moX / mqX carry dO, Q of the O tile, then of the E tile
     TileMover<T, D, D, NT> mc;                               // cached state at the start of the E tile
-    const T *ctile = cache + (size_t)chain * (ntiles / 2) * D * D;
+    const T *ctile = cache + (size_t)chain * (ntiles / 2) * WK * WV;   // [WK][WV] per slot
     // With a decay per token (`decay` = log g, [chain][token]) the O and the E tile have their own
     // tables; with one lambda per head both names refer to the same table.
     const auto decO = DecaySel<TOKEN, T, CT>::make(pw, decay, chain, H);
@@ -1035,7 +1021,7 @@ __global__ __launch_bounds__(D * 4) void k_bwd8p(const T *__restrict__ Q, const 
         mkO.template load_w<WK>(K + koff(tE + 1), nvO);
         mvE.template load_w<WV>(V + voff(tE), CT);
         mkE.template load_w<WK>(K + koff(tE), CT);
-        mc.load(ctile + (size_t)(tE / 2) * D * D);
+        mc.template load_w<WV>(ctile + (size_t)(tE / 2) * WK * WV, WK);   // rows and columns of padding read as zero
     };
     auto load_pair_rest = [&](int tE) {
         const int nvO = TOKEN ? min(CT, ntok - (tE + 1) * CT) : CT;
@@ -1061,20 +1047,9 @@ __global__ __launch_bounds__(D * 4) void k_bwd8p(const T *__restrict__ Q, const 
     // st[blk][i]: group 0: dKV[32 blk + acc_row(i)][32 w + r]; group 1: dKV[32 w + r][32 blk + acc_row(i)]
     f32x16 st[DB];
     {
-        const float *g = scratch + ((size_t)chain * nseg + seg) * D * D;
-        if (rg == 0) {
-            state_load<D>(ln, st, g, w);
-        } else {
-            const unsigned lo = ((32 * w + ln.r) * D + 4 * ln.h) * sizeof(float);
-#pragma unroll
-            for (int cb = 0; cb < DB; ++cb)
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    const f32x4 x = gload<f32x4>(g + 32 * cb + 8 * q, lo);
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) st[cb][4 * q + e] = x[e];
-                }
-        }
+        const float *g = scratch + ((size_t)chain * nseg + seg) * WK * WV;
+        if (rg == 0) state_load_w<D, WK, WV>(ln, st, g, w);
+        else state_load_t_w<D, WK, WV>(ln, st, g, w);
     }
 
     // masked score tiles of the tile whose V, K are at pV, pK (dO, Q in sdO, sQ): one 32x32 block per wave
@@ -1460,7 +1435,7 @@ static hipError_t run_local(const Plan &p, const T *x, const T *y, const float *
 
 template <typename T, int CT, int D, int WK = D, int WV = D>
 static hipError_t run_fwd(const Plan &p, const FwdArgs &a, hipStream_t s, const KernelEvents *ke) {
-    const int chains = p.B * p.H, DD = D * D;
+    const int chains = p.B * p.H, DD = WK * WV;   // states hold the real rows and columns only
     const dim3 scan_grid((DD / 4 + 255) / 256, chains);
     hipError_t e;
     if (ke) (void)hipEventRecord(ke->ev[0], s);
@@ -1472,10 +1447,10 @@ static hipError_t run_fwd(const Plan &p, const FwdArgs &a, hipStream_t s, const 
     if (ke) (void)hipEventRecord(ke->ev[1], s);
     if (p.token)
         k_scan<false, true><<<scan_grid, dim3(256), 0, s>>>(a.scratch, a.kv_in, nullptr, a.seglog, p.H, DD, p.nseg,
-                                                           p.tiles_per_seg, p.ntiles, p.tile, D, p.dk, p.dv);
+                                                           p.tiles_per_seg, p.ntiles, p.tile);
     else
         k_scan<false, false><<<scan_grid, dim3(256), 0, s>>>(a.scratch, a.kv_in, a.decay, nullptr, p.H, DD, p.nseg,
-                                                            p.tiles_per_seg, p.ntiles, p.tile, D, p.dk, p.dv);
+                                                            p.tiles_per_seg, p.ntiles, p.tile);
     if (ke) (void)hipEventRecord(ke->ev[2], s);
     const auto walk = a.states_only ? by_model<StatesFam<T, CT, D, WK, WV>>(p) : by_model<FwdFam<T, CT, D, WK, WV>>(p);
     if (e = launch_kernel(walk, dim3(p.nseg, chains), dim3(D * 2), Smem<T, CT, D>::fwd, s,
@@ -1490,7 +1465,7 @@ static hipError_t run_fwd(const Plan &p, const FwdArgs &a, hipStream_t s, const 
 
 template <typename T, int CT, int D, int WK = D, int WV = D>
 static hipError_t run_bwd(const Plan &p, const BwdArgs &a, hipStream_t s, const KernelEvents *ke) {
-    const int chains = p.B * p.H, DD = D * D;
+    const int chains = p.B * p.H, DD = WK * WV;   // states hold the real rows and columns only
     const dim3 scan_grid((DD / 4 + 255) / 256, chains);
     hipError_t e;
     if (ke) (void)hipEventRecord(ke->ev[0], s);
@@ -1503,10 +1478,10 @@ static hipError_t run_bwd(const Plan &p, const BwdArgs &a, hipStream_t s, const 
     if (ke) (void)hipEventRecord(ke->ev[1], s);
     if (p.token)
         k_scan<true, true><<<scan_grid, dim3(256), 0, s>>>(a.scratch, a.dkv_out, nullptr, a.seglog, p.H, DD, p.nseg,
-                                                          p.tiles_per_seg, p.ntiles, p.tile, D, p.dk, p.dv);
+                                                          p.tiles_per_seg, p.ntiles, p.tile);
     else
         k_scan<true, false><<<scan_grid, dim3(256), 0, s>>>(a.scratch, a.dkv_out, a.decay, nullptr, p.H, DD, p.nseg,
-                                                           p.tiles_per_seg, p.ntiles, p.tile, D, p.dk, p.dv);
+                                                           p.tiles_per_seg, p.ntiles, p.tile);
     if (ke) (void)hipEventRecord(ke->ev[2], s);
     // The walking kernel: bfloat16 tiles of 64 tokens run in eight waves, with one cached state per pair of
     // tiles when the tile count is even; everything else in four waves with one cached state per tile. All

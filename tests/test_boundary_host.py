@@ -375,9 +375,10 @@ def test_value_dimension_shapes_and_sizes(L):
     assert L.check_shape(L.make_shape(**base, Dv=96)) == 2
     assert L.check_shape(L.make_shape(**base, Dv=-64)) == 2
     mixed, wide = L.make_shape(**base, Dv=128), L.make_shape(**dict(base, D=128))
-    # scratch and the state cache hold padded max(D, Dv)^2 states: at least what the equal-dimension shape needs
-    assert L.scratch_bytes(mixed) >= L.scratch_bytes(wide) > 0
-    assert L.state_cache_bytes(mixed) >= L.state_cache_bytes(wide) > 0
+    # scratch and the state cache hold [D][Dv] states (the real rows and columns): half of the 128 x 128 shape's
+    narrow = L.make_shape(**base)
+    assert L.scratch_bytes(wide) == 2 * L.scratch_bytes(mixed) == 4 * L.scratch_bytes(narrow) > 0
+    assert L.state_cache_bytes(wide) == 2 * L.state_cache_bytes(mixed) == 4 * L.state_cache_bytes(narrow) > 0
     assert L.tile_tokens(mixed) == L.tile_tokens(wide)
 
 
