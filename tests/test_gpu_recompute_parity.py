@@ -77,6 +77,23 @@ def test_recompute_with_norm_and_grouped_heads(gpu, oracle):
         assert np.array_equal(a[name], b[name]) and np.all(np.isfinite(b[name])), name
 
 
+@pytest.mark.parametrize("D,Dv,N,T", [(64, 128, 64 * 8, 2), (128, 64, 64 * 6, 1), (64, 128, 64 * 5, 1)])
+def test_recompute_with_unequal_dims(gpu, oracle, D, Dv, N, T):
+    """Key and value dimensions that differ: the rebuilt cache has the same [d_k][d_v] slots as the stored one."""
+    harness, lasp, si = gpu
+    cfg = si.Config("recompute_d", B=1, H=3, N=N, D=D, chunk=64, dtype="bf16", seed=7200 + D + N, Dv=Dv)
+    inp = si.make_inputs(cfg, with_states=True)
+    say(f"case recompute dims D={D} Dv={Dv} N={N} T={T}")
+    a = harness.run_gpu(inp, T=T)
+    b = harness.run_gpu(inp, T=T, recompute=True)
+    ref = dict(zip(("dq", "dk", "dv", "dkv_in"), oracle.dims_bwd_brute(inp.q, inp.k, inp.v, inp.dout, inp.decay, inp.kv_in, inp.dkv_out)))
+    for name, r in ref.items():
+        emax, efro = harness.rel_errors(b[name], r)
+        say(f"  recompute dims {name:7s} max-rel {emax:.3e} fro-rel {efro:.3e}")
+        assert emax <= TOL["bf16"] and efro <= TOL["bf16"], name
+        assert np.array_equal(a[name], b[name]), name
+
+
 def test_recompute_full_size_c3(gpu, oracle):
     """c3 in bench.py's launch configuration without a state cache: every gradient tensor of every head."""
     harness, lasp, si = gpu
