@@ -1297,7 +1297,25 @@ __global__ __launch_bounds__(256) void k_dlg(const float *__restrict__ rtok, con
             behind += (double)x[0] * y[0] + (double)x[1] * y[1] + (double)x[2] * y[2] + (double)x[3] * y[3];
         }
     }
-    for (int s = s0 + kDlgBlock + tid; s < N; s += 256) behind += (double)r[s];
+    if (N % 4 == 0) {   // rows of r are 16-byte aligned: four tokens per load, four loads in flight
+        double b1 = 0.0, b2 = 0.0, b3 = 0.0;
+        int s = s0 + kDlgBlock + 4 * tid;
+        for (; s + 3 * kDlgBlock < N; s += 4 * kDlgBlock) {
+            const f32x4 x0 = *(const f32x4 *)(r + s), x1 = *(const f32x4 *)(r + s + kDlgBlock),
+                        x2 = *(const f32x4 *)(r + s + 2 * kDlgBlock), x3 = *(const f32x4 *)(r + s + 3 * kDlgBlock);
+            behind += ((double)x0[0] + x0[1]) + ((double)x0[2] + x0[3]);
+            b1 += ((double)x1[0] + x1[1]) + ((double)x1[2] + x1[3]);
+            b2 += ((double)x2[0] + x2[1]) + ((double)x2[2] + x2[3]);
+            b3 += ((double)x3[0] + x3[1]) + ((double)x3[2] + x3[3]);
+        }
+        for (; s < N; s += kDlgBlock) {
+            const f32x4 x = *(const f32x4 *)(r + s);
+            behind += ((double)x[0] + x[1]) + ((double)x[2] + x[3]);
+        }
+        behind += (b1 + b2) + b3;
+    } else {
+        for (int s = s0 + kDlgBlock + tid; s < N; s += 256) behind += (double)r[s];
+    }
     behind = block_sum(behind, sh);
     // this thread's four tokens, suffix sums inside the group
     const int s = s0 + 4 * tid;
