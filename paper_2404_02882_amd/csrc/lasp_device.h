@@ -522,7 +522,11 @@ struct TokenDecay {
     // Rebuilds the tables from the values fetch() returned. Every thread calls it between
     // the barrier that retires the previous tile and the one that publishes the next; the other waves
     // wait for the one that does the work, so it is kept short (register moves, the bare hardware exp2).
-    DEVI void fill(const LogG &v) const {
+    // `base` (log2) is added to the exponents of both weight tables: a local pass that walks away from
+    // the segment edge its weights refer to passes the decay between that edge and this tile, and never
+    // has to rescale its accumulators. Returns the tile's total log2 decay (in the wave that fills; 0 elsewhere).
+    DEVI float fill(const LogG &v, float base = 0.0f) const {
+        float total = 0.0f;
         if (threadIdx.x < 64) {
             const int l = threadIdx.x;
             float c[PER];
@@ -530,7 +534,7 @@ struct TokenDecay {
 #pragma unroll
             for (int e = 1; e < PER; ++e) c[e] = c[e - 1] + v.x[e];
             const float incl = wave_inclusive_scan(c[PER - 1]);  // inclusive scan of the lane totals
-            const float total = __shfl(incl, 63, 64);  // lanes past the tile hold zeros
+            total = __shfl(incl, 63, 64);  // lanes past the tile hold zeros
             const float before = incl - c[PER - 1];
 #pragma unroll
             for (int e = 0; e < PER; ++e) {
@@ -538,11 +542,12 @@ struct TokenDecay {
                 if (i < CT) {
                     const float ci = before + c[e];
                     cum[i] = ci;
-                    wu[i] = __builtin_amdgcn_exp2f(ci);           // (below 2^-126: 0 instead of a denormal)
-                    wa[i] = __builtin_amdgcn_exp2f(total - ci);
+                    wu[i] = __builtin_amdgcn_exp2f(base + ci);           // (below 2^-126: 0 instead of a denormal)
+                    wa[i] = __builtin_amdgcn_exp2f(base + (total - ci));
                 }
             }
         }
+        return total;
     }
     DEVI float upto(int i) const { return wu[i]; }
     DEVI float after(int j) const { return wa[j]; }

@@ -60,9 +60,10 @@ DEVI size_t tile_off(int chain, int ntok, int t, int CT, int width) {
 // k_local: local state of a segment, from zero.
 //   forward : local = sum_s lambda^(len - s) k_s v_s^T            (X = K, Y = V)
 //   backward: local = sum_s lambda^s q_s do_s^T                    (X = Q, Y = dO)
-// per tile (state update of Alg. 2 / dKV update of Alg. 3):
-//   forward : S <- lambda^CT S + (diag{lambda^(CT-1)..1} X)^T Y, tiles ascending
-//   backward: S <- lambda^CT S + (diag{lambda^1..lambda^CT} X)^T Y, tiles descending
+// This is the state update of Alg. 2 / the dKV update of Alg. 3 unrolled over the segment's tiles: every
+// token's weight is taken relative to the segment's edge (forward: its end, backward: its start) as
+// (decay between the edge and the token's tile) x (the token's weight inside its tile), so the
+// accumulators are plain sums and are never rescaled.
 // The row weight is applied to the Y fragments (shared by all row blocks).
 // ---------------------------------------------------------------------------
 // NORM (backward only): Y is dY, the gradient w.r.t. the normalised output; the tile is turned into dO
@@ -101,41 +102,46 @@ __global__ __launch_bounds__(D * 2, 2) void k_local(const T *__restrict__ X, con
     // rows of tile `t` that exist: the last tile of a sub-sequence may be short (per-token decay only)
     auto nvalid = [&](int t) { return TOKEN ? min(CT, ntok - t * CT) : CT; };
     TileMover<T, CT, D, NT, true> mx, my;   // streaming (non-temporal) loads
-    mx.template load_w<WX>(X + xoff(tile_of(0)), nvalid(tile_of(0)));
-    my.template load_w<WY>(Y + yoff(tile_of(0)), nvalid(tile_of(0)));
     NormTile<T, CT, D, NT, WY> mn;   // the normalised output has the rows of Y (= dY)
     const float *rstd_c = rstd + (size_t)chain * ntok;
-    if constexpr (NORM) mn.load(yn + yoff(tile_of(0)), rstd_c + (size_t)tile_of(0) * CT, nvalid(tile_of(0)));
+    if constexpr (!TOKEN) {   // (the per-token-decay path walks the tiles in the other order)
+        mx.template load_w<WX>(X + xoff(tile_of(0)), nvalid(tile_of(0)));
+        my.template load_w<WY>(Y + yoff(tile_of(0)), nvalid(tile_of(0)));
+        if constexpr (NORM) mn.load(yn + yoff(tile_of(0)), rstd_c + (size_t)tile_of(0) * CT, nvalid(tile_of(0)));
+    }
     f32x16 st[DB];
 #pragma unroll
     for (int ab = 0; ab < DB; ++ab) st[ab] = f32x16{0};
 
     if constexpr (TOKEN) {
-        // `decay` is log g, [chain][token]. Per tile (state update of Alg. 2 / dKV update of Alg. 3
-        // with the tile's own weights): S <- whole S + (after (.) X)^T Y forward, (upto (.) X)^T Y backward.
+        // `decay` is log g, [chain][token]. The sum over the segment's tokens is taken walking AWAY from the
+        // edge the weights refer to (forward: tiles descending from the segment's end, weight = decay over
+        // the tokens after it; backward: tiles ascending from its start, weight = decay up to and including
+        // it), so a token's weight is 2^(decay of the tiles already done + its weight inside its tile) and
+        // the accumulators are never rescaled (same sum as the tile recursion of Alg. 2 / Alg. 3 unrolled).
         const TokenDecay<T, CT> dec(pw);
         const float *lg = decay + (size_t)chain * ntok;
-        typename TokenDecay<T, CT>::LogG lgreg = TokenDecay<T, CT>::fetch(lg + (size_t)tile_of(0) * CT, nvalid(tile_of(0)));
-        float lgsum = 0.0f;
+        auto tile_at = [&](int n) { return BWD ? t0 + n : t1 - 1 - n; };
+        mx.template load_w<WX>(X + xoff(tile_at(0)), nvalid(tile_at(0)));
+        my.template load_w<WY>(Y + yoff(tile_at(0)), nvalid(tile_at(0)));
+        if constexpr (NORM) mn.load(yn + yoff(tile_at(0)), rstd_c + (size_t)tile_at(0) * CT, nvalid(tile_at(0)));
+        typename TokenDecay<T, CT>::LogG lgreg = TokenDecay<T, CT>::fetch(lg + (size_t)tile_at(0) * CT, nvalid(tile_at(0)));
+        float base = 0.0f;   // log2 decay of the tiles already done (kept by the wave that fills the tables)
         for (int n = 0; n < ntl; ++n) {
             __syncthreads();
             ln = fresh_lane();
             if constexpr (NORM) mn.apply(my);
             mx.store(sX, LDD);
             my.store(sY, LDD);
-            dec.fill(lgreg);
-            lgsum += lgreg.sum();
+            base += dec.fill(lgreg, base);
             __syncthreads();
             if (n + 1 < ntl) {
-                const int tn = tile_of(n + 1);
+                const int tn = tile_at(n + 1);
                 mx.template load_w<WX>(X + xoff(tn), nvalid(tn));
                 my.template load_w<WY>(Y + yoff(tn), nvalid(tn));
                 if constexpr (NORM) mn.load(yn + yoff(tn), rstd_c + (size_t)tn * CT, nvalid(tn));
                 lgreg = TokenDecay<T, CT>::fetch(lg + (size_t)tn * CT, nvalid(tn));
             }
-            const float whole = dec.whole();
-#pragma unroll
-            for (int ab = 0; ab < DB; ++ab) st[ab] *= whole;
             struct Step {
                 typename E::frag y;
                 typename E::frag x[DB];
@@ -155,11 +161,7 @@ __global__ __launch_bounds__(D * 2, 2) void k_local(const T *__restrict__ X, con
                 });
         }
         // log2 of the product of g over the segment, for the scan
-        if (threadIdx.x < 64) {
-#pragma unroll
-            for (int d = 32; d >= 1; d >>= 1) lgsum += __shfl_xor(lgsum, d, 64);
-            if (threadIdx.x == 0) seglog[(size_t)chain * nseg + seg] = lgsum;
-        }
+        if (threadIdx.x == 0) seglog[(size_t)chain * nseg + seg] = base;
     } else {
     const float lam = decay[chain % H];
     fill_pow_table<CT>(pw, lam);
