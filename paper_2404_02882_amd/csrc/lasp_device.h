@@ -481,25 +481,28 @@ struct TokenDecay {
     static constexpr bool kToken = true;
     static constexpr int PER = (CT + 63) / 64;  // tokens per lane of the wave that scans the tile
     static_assert(CT <= 128 && CT % PER == 0, "one wave scans a tile");
+    // What fetch() brought for the wave that scans the tile: the raw log g of the lane's tokens and the number
+    // of tokens the tile has. Nothing is computed from the loaded values before fill() needs them: an
+    // instruction that touched them earlier would make the wave wait for the load right where it was issued,
+    // in front of a tile's worth of products.
     struct LogG {
         float x[PER];
-        DEVI float sum() const {
-            float s = 0.0f;
-#pragma unroll
-            for (int e = 0; e < PER; ++e) s += x[e];
-            return s;
-        }
+        int nvalid;
     };
     float *cum, *wu, *wa;  // LDS: cumulative log2 decay up to and including token i; 2^cum[i]; 2^(cum[CT-1]-cum[j])
     DEVI explicit TokenDecay(float *tab) : cum(tab), wu(tab + CT), wa(tab + 2 * CT) {}
-    // log2 g of the tokens PER*l .. PER*l+PER-1 of the tile starting at `lg`, in lane l of wave 0 (zero elsewhere)
-    // tokens >= nvalid (past the end of the sub-sequence) are not read and do not decay: log g = 0
+    // log g of the tokens PER*l .. PER*l+PER-1 of the tile starting at `lg`, in lane l of wave 0 (other waves
+    // load nothing). Tokens >= nvalid (past the end of the sub-sequence) are not read: their lanes fetch the
+    // tile's first token instead and fill() counts them as log g = 0 (they do not decay the state).
     static DEVI LogG fetch(const float *lg, int nvalid = CT) {
-        LogG v;
+        LogG v = {};
+        v.nvalid = nvalid;
+        if (threadIdx.x < 64) {
 #pragma unroll
-        for (int e = 0; e < PER; ++e) {
-            const int i = PER * threadIdx.x + e;
-            v.x[e] = (threadIdx.x < 64 && i < CT && i < nvalid) ? lg[i] * kLog2e : 0.0f;
+            for (int e = 0; e < PER; ++e) {
+                const int i = PER * threadIdx.x + e;
+                v.x[e] = gload<float>(lg, (unsigned)((i < CT && i < nvalid) ? i : 0) * sizeof(float));
+            }
         }
         return v;
     }
@@ -529,12 +532,15 @@ struct TokenDecay {
         float total = 0.0f;
         if (threadIdx.x < 64) {
             const int l = threadIdx.x;
-            float c[PER];
-            c[0] = v.x[0];
+            float c[PER];   // running sums of the lane's own tokens, log2
 #pragma unroll
-            for (int e = 1; e < PER; ++e) c[e] = c[e - 1] + v.x[e];
+            for (int e = 0; e < PER; ++e) {
+                const int i = PER * l + e;
+                const float x = (i < CT && i < v.nvalid) ? v.x[e] * kLog2e : 0.0f;
+                c[e] = e ? c[e - 1] + x : x;
+            }
             const float incl = wave_inclusive_scan(c[PER - 1]);  // inclusive scan of the lane totals
-            total = __shfl(incl, 63, 64);  // lanes past the tile hold zeros
+            total = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(incl), 63));  // lanes past the tile hold zeros
             const float before = incl - c[PER - 1];
 #pragma unroll
             for (int e = 0; e < PER; ++e) {
