@@ -4,9 +4,13 @@
 One step = one forward + one backward pass of chunked causal linear attention
 over one batch of synthetic input already resident in HBM (config c3:
 bf16, B=1, H=16, N=32768, d=128, chunk=128). Prints ONE JSON line:
-tokens/s of the whole step, the roofline of the dominant kernel measured with
-HIP events inside the timed region, and the CPU oracle timed on a bounded
-sample of the same workload.
+tokens/s of the whole step (timed as replays of one HIP graph of the step's
+C-ABI calls, after a pre-warm by wall time; --eager times the eager launches),
+the roofline of the dominant kernel from HIP events recorded on the launch
+stream around every kernel (in an eager pass of the same steps right after the
+timed replays, since events cannot be captured in the graph; with --eager
+inside the timed region itself), and the CPU oracle timed on a bounded sample
+of the same workload.
 """
 import argparse
 import json
@@ -215,7 +219,7 @@ def main():
     # With the fused Norm the forward walk also writes rstd (4 B) and both backward kernels also read the
     # normalised output and rstd (dO is rebuilt from dY on the fly).
     gb = 4 if token else 0
-    nb = D * esz + 4 if norm else 0
+    nb = dv_ * esz + 4 if norm else 0   # the normalised output row and rstd
     alg_bytes = {"fwd_walk": (2 * dk_ + 2 * dv_) * esz + gb + (4 if norm else 0),
                  "bwd_walk": (4 * dk_ + 3 * dv_) * esz + gb + nb,
                  "fwd_local": (dk_ + dv_) * esz + gb, "bwd_local": (dk_ + dv_) * esz + gb + nb}
@@ -235,7 +239,7 @@ def main():
     # whole-step figures against both roofs. Flops: see flop_counts(); `chunk` is validated but does not select the
     # kernels' tile (64 tokens for bfloat16, 32 for float), so the algorithmic count at C = chunk is not what is issued.
     flops = flop_counts(B, H, N, dk_, dv_, cfg.chunk, tile)
-    min_bytes_step = ((6 * dk_ + 5 * dv_) * esz + 3 * gb + (D * esz + 8 if norm else 0)) * B * H * N
+    min_bytes_step = ((6 * dk_ + 5 * dv_) * esz + 3 * gb + (dv_ * esz + 8 if norm else 0)) * B * H * N
     step_s = ms_per_step * 1e-3
     tf = lambda f: round(f / step_s / 1e12, 2)
     extra = {"timed_as": "eager launches" if args.eager else "hip graph replay",

@@ -60,10 +60,11 @@ typedef enum { LASP_F32 = 0, LASP_BF16 = 1 } lasp_dtype;
  *            last tile is short; the per-token-decay kernels handle that, so
  *            lasp_fwd / lasp_bwd then run those with log g = log(lambda) filled in
  *            by the library (about 10 % slower, more scratch).
- *   chunk    the chunk length C of Alg. 2 / Alg. 3. The kernels walk the
- *            sub-sequence in tiles of lasp_tile_tokens() tokens; the tile
- *            divides the chunk, which is exact because the state update of
- *            Sec. 3.2 composes over consecutive tiles.
+ *   chunk    the chunk length C of Alg. 2 / Alg. 3: 64, 128 or 256. It is checked
+ *            and otherwise NOT USED: the kernels always walk the sub-sequence in
+ *            tiles of lasp_tile_tokens() tokens, which divide every allowed chunk.
+ *            The results are those of any chunk length, because the state update
+ *            of Sec. 3.2 composes over consecutive tiles.
  *   kv_heads 0 or H: every query head has its own key/value head. Otherwise a
  *            divisor of H: k, v (and dk, dv) are [B][kv_heads][N][D] and the
  *            H / kv_heads consecutive query heads of a group share one of them
