@@ -322,6 +322,29 @@ struct TileMover {
     }
 };
 
+// Sums across lanes without an LDS round trip.
+// x + (the same value in the lane 32 further up or down): the two half-waves trade with one v_permlane32_swap.
+DEVI float add_other_half(float x) {
+    const auto t = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return __uint_as_float(t[0]) + __uint_as_float(t[1]);   // {lower, lower} + {upper, upper}
+}
+// Sum over groups of N consecutive lanes (N = 2 .. 16, a power of two, groups aligned), returned to all of
+// them: a butterfly of data-parallel moves inside the 16-lane row (quad permutes for distance 1 and 2; once
+// a quad holds one value, mirroring 8 and 16 lanes brings the other half's).
+template <int N>
+DEVI float group_sum(float x) {
+    static_assert(N >= 1 && N <= 16 && (N & (N - 1)) == 0, "inside one row of 16 lanes");
+    auto moved = [](float v, auto ctrl) {
+        return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), decltype(ctrl)::value, 0xf, 0xf, false));
+    };
+    using std::integral_constant;
+    if constexpr (N >= 2) x += moved(x, integral_constant<int, 0xB1>{});    // quad_perm [1,0,3,2]
+    if constexpr (N >= 4) x += moved(x, integral_constant<int, 0x4E>{});    // quad_perm [2,3,0,1]
+    if constexpr (N >= 8) x += moved(x, integral_constant<int, 0x141>{});   // row_half_mirror
+    if constexpr (N >= 16) x += moved(x, integral_constant<int, 0x140>{});  // row_mirror
+    return x;
+}
+
 // ---------------------------------------------------------------------------
 // Norm(.) of the normalised linear attention O = Norm((Q K^T (.) M) V) (Sec. 3.1, Eq. (2)),
 // taken as the parameter-free root-mean-square normalisation of an output row:
@@ -378,8 +401,12 @@ struct NormTile {
             float p = 0.0f;
 #pragma unroll
             for (int e = 0; e < E; ++e) p += a[e] * b[e];
-#pragma unroll
-            for (int m = 1; m < TM::VPR; m <<= 1) p += __shfl_xor(p, m, 64);
+            if constexpr (TM::VPR <= 16) {
+                p = group_sum<TM::VPR>(p);
+            } else {   // 32 lanes per row (float, 128 features): two rows of 16, then the neighbouring row
+                p = group_sum<16>(p);
+                p += __shfl_xor(p, 16, 64);
+            }
             const float mean = p * (1.0f / W), rs = rstd[i];
 #pragma unroll
             for (int e = 0; e < E; ++e) a[e] = rs * (a[e] - b[e] * mean);
@@ -605,7 +632,7 @@ DEVI float rowdot(const Lane &ln, const f32x16 &acc, const T *sX, int ld, int ro
             for (int e = 0; e < 4; ++e) s += acc[4 * q + e] * x[e];
         }
     }
-    return s + __shfl_xor(s, 32, 64);
+    return add_other_half(s);
 }
 
 // Load / store a wave's column block of a float state. In memory a state is [WK][WV] (row-major [a][c], row

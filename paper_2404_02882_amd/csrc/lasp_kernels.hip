@@ -382,7 +382,7 @@ __global__ __launch_bounds__(D * 2, (CT <= 64 && sizeof(T) == 2) ? 2 : 1) void k
                 float ss = 0.0f;
 #pragma unroll
                 for (int i = 0; i < 16; ++i) ss += acc[ib][i] * acc[ib][i];
-                ss += __shfl_xor(ss, 32, 64);
+                ss = add_other_half(ss);
                 if (ln.h == 0) red[w * CT + 32 * ib + ln.r] = ss;
             }
             __syncthreads();
