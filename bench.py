@@ -85,6 +85,42 @@ def flop_counts(B, H, N, dk, dv, chunk, tile):
     return {"algorithmic": alg, "causal_minimal": causal, "issued": issued}
 
 
+class HeadGroups:
+    """The heads of a B = 1 workload cut into G groups that are processed one after the other, each with its own
+    sequence object (own state caches and workspace). A head slice of a [1, H, ...] tensor is contiguous, so the
+    groups run the same library calls on views of the same buffers. forward / backward take the keyword arguments
+    of LaspSequence and slice every tensor that has a head axis."""
+
+    def __init__(self, groups, make_sequence, H):
+        assert H % groups == 0, "the groups must divide the heads"
+        self.hg = H // groups
+        self.seqs = [make_sequence(self.hg) for _ in range(groups)]
+        self.shape = self.seqs[0].shape
+
+    def _slice(self, x, g):
+        import torch
+        lo, hi = g * self.hg, (g + 1) * self.hg
+        if isinstance(x, (list, tuple)):
+            return [self._slice(t, g) for t in x]
+        if isinstance(x, torch.Tensor):
+            return x[lo:hi] if x.dim() == 1 else x[:, lo:hi]
+        return x
+
+    def forward(self, **kw):
+        for g, seq in enumerate(self.seqs):
+            seq.forward(**{n: self._slice(x, g) for n, x in kw.items()})
+
+    def backward(self, **kw):
+        for g, seq in enumerate(self.seqs):
+            seq.backward(**{n: self._slice(x, g) for n, x in kw.items()})
+
+    def cache_bytes(self):
+        return sum(seq.cache_bytes() for seq in self.seqs)
+
+    def workspace_bytes(self):
+        return sum(seq.workspace_bytes() for seq in self.seqs)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -101,6 +137,10 @@ def main():
     ap.add_argument("--prewarm-seconds", type=float, default=1.0,
                     help="untimed steps run for this long before the counted warm-up, so that a cold device is at its "
                          "steady clocks when the short timed region starts")
+    ap.add_argument("--head-groups", type=int, default=1,
+                    help="run the step as this many independent groups of heads, one after the other (local pass, scan "
+                         "and walk of a group back to back, so that the walk re-reads what the local pass of the same "
+                         "few heads just read); needs B = 1. An experiment on the last-level cache, not the default")
     ap.add_argument("--recompute", action="store_true",
                     help="keep no state cache between the passes: every backward call rebuilds the states of its "
                          "sub-sequence (Sec. 3.4: recomputation instead of caching)")
@@ -135,8 +175,14 @@ def main():
     norm = cfg.norm_eps is not None
     dk_, dv_ = D, cfg.Dv or D   # key and value dimensions
     torch.cuda.reset_peak_memory_stats()
-    seq = LaspSequence(B, H, N, D, cfg.chunk, dt, T=T, segments=args.segments, device=dev, token_decay=token,
-                       norm_eps=cfg.norm_eps, Dv=cfg.Dv, recompute=args.recompute)
+    make_sequence = lambda heads: LaspSequence(B, heads, N, D, cfg.chunk, dt, T=T, segments=args.segments, device=dev,
+                                               token_decay=token, norm_eps=cfg.norm_eps, Dv=cfg.Dv, recompute=args.recompute)
+    if args.head_groups > 1:
+        if B != 1:
+            sys.exit("bench.py: --head-groups needs a workload with B = 1 (a head slice must be contiguous)")
+        seq = HeadGroups(args.head_groups, make_sequence, H)
+    else:
+        seq = make_sequence(H)
     q, k, v, do = (harness.shards(x, T, cfg.dtype, dev) for x in (inp.q, inp.k, inp.v, inp.dout))
     if token:   # a decay per token: log g shards [B,H,N/T] in, dlog_g shards out
         n = N // T
@@ -180,14 +226,14 @@ def main():
         run()
     # ---- the timed region: exactly `steps` steps ----
     if args.eager:
-        lasp.profile_begin(args.steps * T)
+        lasp.profile_begin(args.steps * T * args.head_groups)
     ms_per_step = timed(run, args.steps)
     if args.eager:
         kernel_ms, nf, nb_calls = lasp.profile_end()
         eager_ms, graph_ms = ms_per_step, timed(graphed.replay, args.steps)
     else:
         # per-kernel times: HIP events are not captured in a graph, so they come from an eager pass of the same steps
-        lasp.profile_begin(args.steps * T)
+        lasp.profile_begin(args.steps * T * args.head_groups)
         eager_ms = timed(step, args.steps)
         kernel_ms, nf, nb_calls = lasp.profile_end()
         graph_ms = ms_per_step
@@ -207,7 +253,7 @@ def main():
     peak_mem = torch.cuda.max_memory_allocated()
 
     # ---- roofline of the dominant kernel (largest share of the step) ----
-    tok_heads_per_launch = B * H * (N // T)
+    tok_heads_per_launch = B * (H // args.head_groups) * (N // T)
     esz = 2 if cfg.dtype == "bf16" else 4
     per_launch_ms = {"fwd_local": kernel_ms["fwd"][0] / nf, "fwd_scan": kernel_ms["fwd"][1] / nf,
                      "fwd_walk": kernel_ms["fwd"][2] / nf, "bwd_local": kernel_ms["bwd"][0] / nb_calls,
@@ -226,7 +272,8 @@ def main():
     dominant = max(("fwd_walk", "bwd_walk", "fwd_local", "bwd_local"), key=lambda n: per_launch_ms[n])
     dom_bytes = alg_bytes[dominant] * tok_heads_per_launch
     achieved = dom_bytes / (per_launch_ms[dominant] * 1e-3) / 1e9
-    traffic, traffic_src = traffic_from_profile(args.config, dominant) if args.segments == 0 and args.sub_sequences == 0 else (None, None)
+    as_profiled = args.segments == 0 and args.sub_sequences == 0 and args.head_groups == 1   # the committed summaries' launch shape
+    traffic, traffic_src = traffic_from_profile(args.config, dominant) if as_profiled else (None, None)
     roofline = {"kernel": dominant, "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
                 "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
                 "traffic": traffic, "traffic_source": traffic_src,
@@ -326,7 +373,7 @@ def main():
                        "tile_tokens": tile, "chunk_selects_tile": False, "segments_per_head": nseg,
                        "hip_graph": not args.eager, "prewarm_seconds": args.prewarm_seconds,
                        "state_cache": "none (states rebuilt in the backward pass)" if args.recompute else "kept between the passes",
-                       "state_cache_bytes": seq.cache_bytes(), "workspace_bytes": int(seq.scratch.numel()),
+                       "state_cache_bytes": seq.cache_bytes(), "workspace_bytes": seq.workspace_bytes(), "head_groups": args.head_groups,
                        "peak_device_memory_bytes": int(peak_mem)},
             "roofline": roofline, "whole_step": extra, "copy_reference": copy, "cpu_baseline": cpu}
     print(json.dumps(line), flush=True)

@@ -60,6 +60,9 @@ class LaspSequence:
     def cache_bytes(self) -> int:
         return sum(c.numel() for c in self.caches if c is not None)
 
+    def workspace_bytes(self) -> int:
+        return int(self.scratch.numel())
+
     def forward(self, q: List[torch.Tensor], k, v, decay, out: List[torch.Tensor],
                 kv_in: Optional[torch.Tensor] = None, rstd: Optional[List[torch.Tensor]] = None) -> torch.Tensor:
         self.has_kv_in = kv_in is not None
