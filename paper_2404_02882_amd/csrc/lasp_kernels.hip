@@ -1065,7 +1065,7 @@ __global__ __launch_bounds__(D * 4) void k_bwd8p(const T *__restrict__ Q, const 
             if (owner % (2 * NW) != w8) continue;
             const int ib = blk >> 1, jb = blk & 1;
             f32x16 acc = {0}, acc2 = {0};
-            pipelined<NKD / 2>(
+            pipelined<WV / E::KSTEP / 2>(   // (contraction over the real value features)
                 [&](int s2) {
                     FragPair<FragPair<F>> f;
                     f.a.a = E::ld_kc(ln, sVE, LDD, 32 * jb, 2 * s2 * E::KSTEP);
@@ -1098,19 +1098,24 @@ __global__ __launch_bounds__(D * 4) void k_bwd8p(const T *__restrict__ Q, const 
             const int tri = idx % NTRI, ib = tri == 0 ? 0 : 1, jb = tri == 2 ? 1 : 0;
             const T *sA = idx < NTRI ? pV : pK, *sB = idx < NTRI ? sdO : sQ;
             f32x16 acc = {0}, acc2 = {0};
-            pipelined<NKD / 2>(
-                [&](int s2) {
-                    FragPair<FragPair<F>> f;
-                    f.a.a = E::ld_kc(ln, sA, LDD, 32 * jb, 2 * s2 * E::KSTEP);
-                    f.a.b = E::ld_kc(ln, sB, LDD, 32 * ib, 2 * s2 * E::KSTEP);
-                    f.b.a = E::ld_kc(ln, sA, LDD, 32 * jb, (2 * s2 + 1) * E::KSTEP);
-                    f.b.b = E::ld_kc(ln, sB, LDD, 32 * ib, (2 * s2 + 1) * E::KSTEP);
-                    return f;
-                },
-                [&](int, const FragPair<FragPair<F>> &f) {
-                    acc = E::mfma(f.a.a, f.a.b, acc);
-                    acc2 = E::mfma(f.b.a, f.b.b, acc2);
-                });
+            auto contract = [&](auto steps) __attribute__((always_inline)) {
+                pipelined<decltype(steps)::value>(
+                    [&](int s2) {
+                        FragPair<FragPair<F>> f;
+                        f.a.a = E::ld_kc(ln, sA, LDD, 32 * jb, 2 * s2 * E::KSTEP);
+                        f.a.b = E::ld_kc(ln, sB, LDD, 32 * ib, 2 * s2 * E::KSTEP);
+                        f.b.a = E::ld_kc(ln, sA, LDD, 32 * jb, (2 * s2 + 1) * E::KSTEP);
+                        f.b.b = E::ld_kc(ln, sB, LDD, 32 * ib, (2 * s2 + 1) * E::KSTEP);
+                        return f;
+                    },
+                    [&](int, const FragPair<FragPair<F>> &f) {
+                        acc = E::mfma(f.a.a, f.a.b, acc);
+                        acc2 = E::mfma(f.b.a, f.b.b, acc2);
+                    });
+            };
+            // dS = dO V^T contracts over the real value features, S = Q K^T over the real key features
+            if (idx < NTRI) contract(std::integral_constant<int, WV / E::KSTEP / 2>{});
+            else contract(std::integral_constant<int, WK / E::KSTEP / 2>{});
             acc += acc2;
             store_masked_scores<T, LDP>(ln, idx < NTRI ? sDS : sS, acc, jb, ib, dec);
         }
@@ -1119,29 +1124,48 @@ __global__ __launch_bounds__(D * 4) void k_bwd8p(const T *__restrict__ Q, const 
     // dQ, this group's dV or dK, and the dKV update for tile `t`
     // `cross` (the O tile): the cached state is the one the E tile starts from, so dQ takes the E tile
     // as the first half of its own chunk: far weights on the state term, plus the E tile's keys through sDX.
+    // Key and value dimensions that differ: only KB (VB) of the DB 32-wide feature blocks of the key (value)
+    // side are real. A wave whose own output block (dV block w in group 0, dK block w in group 1) is padding
+    // skips that product and its state update. With d_k < d_v the two such waves of group 1 produce ALL of
+    // dQ instead (both token blocks of one key-feature block each), so that no wave carries dQ on top of a
+    // dK or dV block and a state update (the walk's critical path); otherwise every wave with a real
+    // key-feature block produces the dQ tile of that block for one token block (group 0 the second, whose
+    // keys span both blocks, group 1 the first).
+    constexpr int KB = WK / 32, VB = WV / 32;
+    const bool own_block = WK == WV || (rg ? w < KB : w < VB);   // this wave's dK / dV block exists
+    constexpr bool DQ_BY_IDLE = WK < WV && !(TOKEN && NORM);   // (that one combination would run out of registers)
     auto products = [&](const auto &dec, const T *pV, const T *pK, int t, int nrows, bool cross) {
         const T *sX1 = rg ? pV : pK;  // inter operand: token rows, features contracted with the state
-        float rq = 0.0f;  // per-token decay: q_i . dq_i over this wave's features, tokens i of block 1 - rg
-        {   // dQ^T[a in w][i], tokens i of block 1 - rg
-            const int r0 = 32 * (1 - rg);   // group 0 takes the second token block (whose keys span both blocks), group 1 the first
+        float rq[NB] = {};  // per-token decay: q_i . dq_i over the features of the dQ tiles this wave produced, per token block
+        // dQ^T[a in block qa][i], tokens i of the block starting at r0; `both`: the intra part reaches the keys of
+        // both blocks (the second token block) or of block 0 only
+        auto dq_tile = [&](int qa, int r0, auto both) __attribute__((always_inline)) {
             f32x16 acc = {0};
-            pipelined<NKD>(
-                [&](int ks) { return FragPair<F>{E::ld_kc(ln, sC, LDD, 32 * w, ks * E::KSTEP), E::ld_kc(ln, sdO, LDD, r0, ks * E::KSTEP)}; },
+            pipelined<WV / E::KSTEP>(   // (the cached state's real columns)
+                [&](int ks) { return FragPair<F>{E::ld_kc(ln, sC, LDD, 32 * qa, ks * E::KSTEP), E::ld_kc(ln, sdO, LDD, r0, ks * E::KSTEP)}; },
                 [&](int, const FragPair<F> &f) { acc = E::mfma(f.a, f.b, acc); });
             acc *= cross ? far_upto(r0 + ln.r) : dec.upto(r0 + ln.r);
             auto fma = [&](int, const FragPair<F> &f) { acc = E::mfma(f.a, f.b, acc); };
             if (cross)
                 pipelined<NKS>(
-                    [&](int ks) { return FragPair<F>{E::ld_ks(ln, sKE, LDD, ks * E::KSTEP, 32 * w), E::ld_kc(ln, sDX, LDP, r0, ks * E::KSTEP)}; },
+                    [&](int ks) { return FragPair<F>{E::ld_ks(ln, sKE, LDD, ks * E::KSTEP, 32 * qa), E::ld_kc(ln, sDX, LDP, r0, ks * E::KSTEP)}; },
                     fma);
-            auto intra = [&](int ks) { return FragPair<F>{E::ld_ks(ln, pK, LDD, ks * E::KSTEP, 32 * w), E::ld_kc(ln, sDS, LDP, r0, ks * E::KSTEP)}; };
-            if (rg == 0) pipelined<2 * SPB>(intra, fma);    // keys of blocks 0 and 1
-            else pipelined<SPB>(intra, fma);                // keys of block 0
-            if constexpr (TOKEN) rq = rowdot<T>(ln, acc, sQ, LDD, r0, w);   // (from the fp32 accumulators, before rounding)
-            store_out_tile_t<T, D, WK>(ln, dQ + koff(t), acc, r0, w, nrows);
+            auto intra = [&](int ks) { return FragPair<F>{E::ld_ks(ln, pK, LDD, ks * E::KSTEP, 32 * qa), E::ld_kc(ln, sDS, LDP, r0, ks * E::KSTEP)}; };
+            pipelined<decltype(both)::value ? 2 * SPB : SPB>(intra, fma);
+            if constexpr (TOKEN) rq[r0 / 32] = rowdot<T>(ln, acc, sQ, LDD, r0, qa);   // (from the fp32 accumulators, before rounding)
+            store_out_tile_t<T, D, WK>(ln, dQ + koff(t), acc, r0, qa, nrows);
+        };
+        if constexpr (DQ_BY_IDLE) {
+            if (rg == 1 && w >= KB) {
+                dq_tile(w - KB, 32, std::true_type{});
+                dq_tile(w - KB, 0, std::false_type{});
+            }
+        } else if (WK == WV || w < KB) {
+            if (rg == 0) dq_tile(w, 32, std::true_type{});
+            else dq_tile(w, 0, std::false_type{});
         }
         ln = fresh_lane();
-        {   // dV^T[c in w][j] (group 0) or dK^T[a in w][j] (group 1), both token blocks
+        if (own_block) {   // dV^T[c in w][j] (group 0) or dK^T[a in w][j] (group 1), both token blocks
             f32x16 acc[NB];
 #pragma unroll
             for (int jb = 0; jb < NB; ++jb) acc[jb] = f32x16{0};
@@ -1178,7 +1202,7 @@ __global__ __launch_bounds__(D * 4) void k_bwd8p(const T *__restrict__ Q, const 
 #pragma unroll
             for (int jb = 0; jb < NB; ++jb) {
                 if constexpr (TOKEN) {   // (row dots from the fp32 accumulators, before they are rounded and stored)
-                    float r = jb == 1 - rg ? rq : 0.0f;
+                    float r = rq[jb];
                     if (rg == 1) r -= rowdot<T>(ln, acc[jb], pK, LDD, 32 * jb, w);  // group 1 holds dK
                     if (ln.h == 0) rs[w8 * CT + 32 * jb + ln.r] = r;
                 }
@@ -1189,9 +1213,13 @@ __global__ __launch_bounds__(D * 4) void k_bwd8p(const T *__restrict__ Q, const 
                     else store_out_tile_t<T, D, WV>(ln, dV + voff(t), acc[jb], 32 * jb, w, nrows);
                 }
             }
+        } else if constexpr (TOKEN) {   // this wave's row of the per-token sums still has to be defined
+#pragma unroll
+            for (int jb = 0; jb < NB; ++jb)
+                if (ln.h == 0) rs[w8 * CT + 32 * jb + ln.r] = rq[jb];
         }
         ln = fresh_lane();
-        {   // state update in this group's orientation
+        if (own_block) {   // state update in this group's orientation
             const float lamC = dec.whole();
 #pragma unroll
             for (int blk = 0; blk < DB; ++blk) st[blk] *= lamC;
