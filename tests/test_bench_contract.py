@@ -1,4 +1,5 @@
-"""bench.py without a GPU: more than one GPU is refused with a message (this build runs on one device)."""
+"""bench.py without a GPU: more than one GPU is refused with a message (this build runs on one device); the flop
+counts, the traffic parser and the head-groups adapter.
 import os
 import subprocess
 import sys
@@ -48,3 +49,42 @@ def test_traffic_is_read_from_the_committed_profiles():
     assert 1792 * 16 * 32768 < got < 1.3 * 1792 * 16 * 32768
     assert bench.traffic_from_profile("c3", "fwd_local")[0] != bench.traffic_from_profile("c3", "bwd_local")[0]
     assert bench.traffic_from_profile("no_such_config", "bwd_walk") == (None, None)
+
+
+def test_head_groups_slice_every_tensor_with_a_head_axis():
+    """bench.py --head-groups: the adapter hands each group the head slice of every tensor argument (CPU: a recording
+    stand-in for the sequence object, no library call)."""
+    import torch
+    sys.path.insert(0, ROOT)
+    import bench
+
+    class Recorder:
+        shape = "shape of a group"
+
+        def __init__(self):
+            self.calls = []
+
+        def forward(self, **kw):
+            self.calls.append(("fwd", kw))
+
+        def backward(self, **kw):
+            self.calls.append(("bwd", kw))
+
+        def cache_bytes(self):
+            return 3
+
+        def workspace_bytes(self):
+            return 5
+
+    H, made = 6, []
+    groups = bench.HeadGroups(3, lambda heads: made.append(heads) or Recorder(), H)
+    assert made == [2, 2, 2] and groups.cache_bytes() == 9 and groups.workspace_bytes() == 15
+    q = [torch.arange(H * 4.0).reshape(1, H, 4, 1)]
+    decay = torch.arange(float(H))
+    groups.forward(q=q, decay=decay, rstd=None)
+    groups.backward(q=q, decay=decay, dlog_g=None)
+    for g, seq in enumerate(groups.seqs):
+        (kind_f, f), (kind_b, b) = seq.calls
+        assert (kind_f, kind_b) == ("fwd", "bwd")
+        assert torch.equal(f["q"][0], q[0][:, 2 * g:2 * g + 2]) and f["q"][0].is_contiguous()
+        assert torch.equal(f["decay"], decay[2 * g:2 * g + 2]) and f["rstd"] is None and b["dlog_g"] is None
