@@ -1,5 +1,5 @@
 """bench.py without a GPU: more than one GPU is refused with a message (this build runs on one device); the flop
-counts, the traffic parser and the head-groups adapter.
+counts, the traffic parser and the head-groups adapter."""
 import os
 import subprocess
 import sys
